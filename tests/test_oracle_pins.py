@@ -1,0 +1,409 @@
+"""Pins for the CPU checker: every layer definition is tied to something other than itself --
+hand-worked numbers, closed forms, invariants, library routines of another code base (PyTorch's
+CPU operators in fp64, the framework whose layer semantics the paper adopts, Sec. V), and
+central finite differences for every backward function.  CPU only."""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle as orc
+
+R = np.random.default_rng(7)
+T = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))  # noqa: E731
+
+
+# ------------------------------------------------------------------------- conv forward
+def test_conv_hand_worked():
+    # 1 channel 3x3 input, 2x2 kernel, no pad, stride 1: four dot products done by hand.
+    x = np.array([[1, 2, 3], [4, 5, 6], [7, 8, 9]], float).reshape(1, 1, 3, 3)
+    w = np.array([[1, 0], [-1, 2]], float).reshape(1, 1, 2, 2)
+    # y[p,q] = x[p,q] - x[p+1,q] + 2 x[p+1,q+1]   (correlation: no kernel flip)
+    want = np.array([[1 - 4 + 10, 2 - 5 + 12], [4 - 7 + 16, 5 - 8 + 18]], float)
+    got = orc.conv2d(x, w, np.array([0.5]))
+    assert np.array_equal(got[0, 0], want + 0.5)
+    # a flipped-kernel (true convolution) implementation would give x[p+1,q+1] - x[p,q+1] + 2 x[p,q]
+    assert not np.array_equal(got[0, 0], np.array([[5 - 2 + 2, 6 - 3 + 4], [8 - 5 + 8, 9 - 6 + 10]]) + 0.5)
+
+
+def test_conv_hand_worked_pad_stride_channels():
+    # 2 input channels 2x2, one 3x3 kernel per channel, pad 1, stride 2 -> single output (p=q=0)
+    x = np.array([[[1, 2], [3, 4]], [[10, 20], [30, 40]]], float).reshape(1, 2, 2, 2)
+    w = np.arange(18, dtype=float).reshape(1, 2, 3, 3)
+    # output (0,0) sees input rows/cols -1..1: taps (r,s) in {1,2}x{1,2} hit x[r-1,s-1]
+    want = (1 * 4 + 2 * 5 + 3 * 7 + 4 * 8) + (10 * 13 + 20 * 14 + 30 * 16 + 40 * 17)
+    got = orc.conv2d(x, w, None, (2, 2), (1, 1))
+    assert got.shape == (1, 1, 1, 1) and got[0, 0, 0, 0] == want
+
+
+def test_conv_delta_kernel_is_identity():
+    x = R.standard_normal((2, 3, 6, 7))
+    for k in (1, 3, 5):
+        w = np.zeros((3, 3, k, k))
+        for c in range(3):
+            w[c, c, k // 2, k // 2] = 1.0
+        assert np.array_equal(orc.conv2d(x, w, None, (1, 1), (k // 2, k // 2)), x)
+
+
+def test_conv_1x1_is_matrix_product():
+    x = R.standard_normal((2, 5, 4, 3))
+    w = R.standard_normal((7, 5, 1, 1))
+    want = np.einsum("nchw,kc->nkhw", x, w[:, :, 0, 0])
+    assert np.allclose(orc.conv2d(x, w), want, rtol=1e-13, atol=1e-13)
+
+
+def test_conv_ones_counts_taps():
+    H, W, k, p = 5, 6, 3, 1
+    y = orc.conv2d(np.ones((1, 2, H, W)), np.ones((1, 2, k, k)), None, (1, 1), (p, p))
+    cnt_h = np.array([min(i + p, H - 1) - max(i - p, 0) + 1 for i in range(H)])
+    cnt_w = np.array([min(j + p, W - 1) - max(j - p, 0) + 1 for j in range(W)])
+    assert np.array_equal(y[0, 0], 2.0 * np.outer(cnt_h, cnt_w))
+
+
+def test_conv_stride_is_subsampling_and_linear():
+    x, x2 = R.standard_normal((1, 3, 9, 9)), R.standard_normal((1, 3, 9, 9))
+    w = R.standard_normal((4, 3, 3, 3))
+    y1 = orc.conv2d(x, w, None, (1, 1), (1, 1))
+    y2 = orc.conv2d(x, w, None, (2, 2), (1, 1))
+    assert np.array_equal(y2, y1[:, :, ::2, ::2])
+    ysum = orc.conv2d(2.0 * x + x2, w, None, (1, 1), (1, 1))
+    assert np.allclose(ysum, 2.0 * y1 + orc.conv2d(x2, w, None, (1, 1), (1, 1)), rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("shape", [
+    # N, C, H, W, K, R, S, sh, sw, ph, pw   (asymmetric on purpose: catches swapped axes)
+    (2, 3, 8, 11, 4, 3, 3, 1, 1, 1, 1),
+    (1, 4, 9, 7, 5, 3, 2, 2, 1, 1, 0),
+    (2, 3, 15, 14, 6, 7, 7, 2, 2, 3, 3),
+    (1, 8, 6, 6, 3, 1, 1, 2, 2, 0, 0),
+    (1, 2, 7, 10, 3, 2, 5, 1, 3, 0, 2),
+])
+def test_conv_matches_library(shape):
+    N, C, H, W, K, Rr, S, sh, sw, ph, pw = shape
+    x, w, b = R.standard_normal((N, C, H, W)), R.standard_normal((K, C, Rr, S)), R.standard_normal(K)
+    want = F.conv2d(T(x), T(w), T(b), stride=(sh, sw), padding=(ph, pw)).numpy()
+    got = orc.conv2d(x, w, b, (sh, sw), (ph, pw))
+    assert got.shape == want.shape
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+    # sampled evaluation agrees with the full one
+    coords = np.stack([R.integers(0, d, 40) for d in got.shape], 1).astype(np.int32)
+    pts = orc.conv2d_points(x, w, b, coords, (sh, sw), (ph, pw))
+    assert np.array_equal(pts, got[tuple(coords.T)])
+
+
+# ------------------------------------------------------------------------------- BN, ReLU
+def test_bn_identity_and_affine():
+    x = R.standard_normal((2, 3, 4, 4))
+    one, zero = np.ones(3), np.zeros(3)
+    y = orc.bn_infer(x, one, zero, zero, one - 1e-5, 1e-5)
+    assert np.allclose(y, x, rtol=1e-15, atol=1e-15)
+    g, b, m, v = R.uniform(0.5, 1.5, 3), R.uniform(-1, 1, 3), R.standard_normal(3), R.uniform(0.5, 1.5, 3)
+    y = orc.bn_infer(x, g, b, m, v, 1e-5)
+    scale = g / np.sqrt(v + 1e-5)                 # folded form == explicit form
+    want = x * scale[None, :, None, None] + (b - m * scale)[None, :, None, None]
+    assert np.allclose(y, want, rtol=1e-13, atol=1e-13)
+    want_lib = F.batch_norm(T(x), T(m), T(v), T(g), T(b), False, 0.0, 1e-5).numpy()
+    assert np.allclose(y, want_lib, rtol=1e-13, atol=1e-13)
+
+
+def test_bn_train_statistics():
+    x = R.standard_normal((4, 3, 5, 5)) * 3 + 2
+    y, mean, var = orc.bn_train(x, np.ones(3), np.zeros(3), 1e-5)
+    assert np.allclose(mean, x.mean((0, 2, 3))) and np.allclose(var, x.var((0, 2, 3)))  # biased var
+    assert np.allclose(y.mean((0, 2, 3)), 0, atol=1e-13)
+    assert np.allclose(y.var((0, 2, 3)), var / (var + 1e-5), rtol=1e-12)
+    g, b = R.uniform(0.5, 1.5, 3), R.uniform(-1, 1, 3)
+    y2, _, _ = orc.bn_train(x, g, b, 1e-5)
+    want = F.batch_norm(T(x), None, None, T(g), T(b), True, 0.0, 1e-5).numpy()
+    assert np.allclose(y2, want, rtol=1e-12, atol=1e-12)
+
+
+def test_relu_properties():
+    x = R.standard_normal(1000)
+    y = orc.relu(x)
+    assert np.array_equal(orc.relu(y), y)                       # idempotent
+    assert np.array_equal(y - orc.relu(-x), x)                  # relu(x) - relu(-x) = x
+    assert y.min() == 0.0 and np.array_equal(y[x > 0], x[x > 0])
+
+
+# ---------------------------------------------------------------------------------- pools
+def test_maxpool_hand_worked_and_ties():
+    x = np.array([[1, 5, 2, 2], [5, 0, 2, 2], [-1, -2, -3, -4], [-2, -1, -4, -3]], float).reshape(1, 1, 4, 4)
+    y, a = orc.maxpool(x, (2, 2), (2, 2), (0, 0))
+    assert np.array_equal(y[0, 0], [[5, 2], [-1, -3]])
+    # ties: the first element in row-major window order wins; index is ih*W+iw in the input plane
+    assert np.array_equal(a[0, 0], [[1, 2], [8, 10]])
+
+
+def test_maxpool_constant_ramp_and_relu_commute():
+    c = np.full((1, 2, 6, 6), 3.25)
+    for k, s, p in ((2, 2, 0), (3, 2, 1), (3, 1, 1)):
+        y, a = orc.maxpool(c, (k, k), (s, s), (p, p))
+        assert np.all(y == 3.25)
+        ya = orc.avgpool(c, (k, k), (s, s), (p, p), count_pad=False)
+        assert np.allclose(ya, 3.25, rtol=1e-15)
+    up = np.arange(36, dtype=float).reshape(1, 1, 6, 6)
+    _, a = orc.maxpool(up, (2, 2), (2, 2), (0, 0))
+    assert np.array_equal(a[0, 0], [[7, 9, 11], [19, 21, 23], [31, 33, 35]])     # last element of window
+    _, a = orc.maxpool(-up, (2, 2), (2, 2), (0, 0))
+    assert np.array_equal(a[0, 0], [[0, 2, 4], [12, 14, 16], [24, 26, 28]])      # first element of window
+    # ReLU and max-pool commute (the paper's graph rewrite, Sec. III-A); also with -inf padding
+    x = R.standard_normal((2, 3, 9, 9))
+    for k, s, p in ((2, 2, 0), (3, 2, 1)):
+        assert np.array_equal(orc.maxpool(orc.relu(x), (k, k), (s, s), (p, p))[0],
+                              orc.relu(orc.maxpool(x, (k, k), (s, s), (p, p))[0]))
+
+
+@pytest.mark.parametrize("cfg", [(2, 2, 2, 2, 0, 0), (3, 3, 2, 2, 1, 1), (3, 2, 1, 2, 1, 0), (2, 3, 2, 1, 0, 1)])
+def test_pools_match_library(cfg):
+    kh, kw, sh, sw, ph, pw = cfg
+    x = np.round(R.standard_normal((2, 3, 9, 8)) * 2) / 2          # coarse grid -> many exact ties
+    y, a = orc.maxpool(x, (kh, kw), (sh, sw), (ph, pw))
+    wy, wa = F.max_pool2d(T(x), (kh, kw), (sh, sw), (ph, pw), return_indices=True)
+    assert np.array_equal(y, wy.numpy()) and np.array_equal(a, wa.numpy().astype(np.int32))
+    # argmax points at an element equal to the output, and nothing earlier in the plane-order ties it
+    flat = x.reshape(2, 3, -1)
+    assert np.array_equal(np.take_along_axis(flat, a.reshape(2, 3, -1).astype(np.int64), 2).reshape(y.shape), y)
+    for cp in (True, False):
+        ya = orc.avgpool(x, (kh, kw), (sh, sw), (ph, pw), cp)
+        wa_ = F.avg_pool2d(T(x), (kh, kw), (sh, sw), (ph, pw), count_include_pad=cp).numpy()
+        assert np.allclose(ya, wa_, rtol=1e-13, atol=1e-13)
+
+
+def test_avgpool_paper_listing_shape_and_ramp():
+    # the paper's pooling listing: 3x3 window, stride 1, divide by 9 (Sec. IV, AveragePooling listing),
+    # replayed on a linear ramp: the window mean of a ramp is the ramp at the window centre.
+    H = W = 16
+    ii, jj = np.meshgrid(np.arange(H), np.arange(W), indexing="ij")
+    ramp = (2.0 * ii + 0.5 * jj + 1.0).reshape(1, 1, H, W)
+    y = orc.avgpool(ramp, (3, 3), (1, 1), (0, 0), True)
+    assert y.shape == (1, 1, H - 2, W - 2)
+    assert np.allclose(y[0, 0], ramp[0, 0, 1:-1, 1:-1], rtol=1e-14)
+    # count-padding switch changes only the border outputs
+    a = orc.avgpool(ramp, (3, 3), (1, 1), (1, 1), True)
+    b = orc.avgpool(ramp, (3, 3), (1, 1), (1, 1), False)
+    assert np.array_equal(a[0, 0, 1:-1, 1:-1], b[0, 0, 1:-1, 1:-1])
+    assert np.allclose(a[0, 0, 0, 0] * 9, b[0, 0, 0, 0] * 4, rtol=1e-14)
+    assert np.allclose(orc.gap(ramp)[0, 0], ramp.mean(), rtol=1e-14)
+
+
+# ------------------------------------------------------------------------- linear, bf16
+def test_linear():
+    x = R.standard_normal((3, 6))
+    assert np.array_equal(orc.linear(x, np.eye(6)), x)
+    w, b = R.standard_normal((4, 6)), R.standard_normal(4)
+    assert np.allclose(orc.linear(x, w, b), x @ w.T + b, rtol=1e-13, atol=1e-13)
+    # equals a 1x1 convolution on a 1x1 image; weight layout [Out][In] vs [In][Out] is only storage
+    assert np.allclose(orc.linear(x, w, b), orc.conv2d(x.reshape(3, 6, 1, 1), w.reshape(4, 6, 1, 1), b)[:, :, 0, 0])
+    assert np.allclose(orc.linear(x, w, b), (np.ascontiguousarray(w.T).T @ x.T).T + b)
+
+
+def test_bf16_rounding():
+    e = 2.0 ** -8
+    assert orc.bf16(1.0 + e) == 1.0                      # tie -> even (mantissa 0)
+    assert orc.bf16(1.0 + 3 * e) == 1.0 + 4 * e          # tie -> even (mantissa 2)
+    assert orc.bf16(1.0 + 1.0001 * e) == 1.0 + 2 * e     # just above the tie
+    assert orc.bf16(-(1.0 + 3 * e)) == -(1.0 + 4 * e)
+    assert orc.bf16(255.0) == 255.0 and orc.bf16(257.0) == 256.0 and orc.bf16(259.0) == 260.0
+    assert orc.bf16(2.0 ** -133) == 2.0 ** -133          # smallest subnormal survives
+    assert orc.bf16(2.0 ** -134) == 0.0                  # tie to even (zero)
+    assert orc.bf16(1.5 * 2.0 ** -133) == 2.0 ** -132
+    assert orc.bf16(3.4e38) == math.inf and orc.bf16(-3.4e38) == -math.inf
+    big = float.fromhex("0x1.FEp127")
+    assert orc.bf16(big) == big
+    assert math.isnan(orc.bf16(math.nan)) and orc.bf16(math.inf) == math.inf
+    # against the tensor library's converter on fp32-representable values (no double rounding there)
+    v = (R.standard_normal(20000) * np.exp(R.uniform(-20, 20, 20000))).astype(np.float32)
+    want = torch.from_numpy(v).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(orc.round_bf16(v.astype(np.float64)), want)
+    # bf16 x bf16 products are exact in fp32/fp64: a short dot product of bf16 values has a closed form
+    a = orc.round_bf16(R.standard_normal(8))
+    assert orc.conv2d(a.reshape(1, 8, 1, 1), a.reshape(1, 8, 1, 1))[0, 0, 0, 0] == math.fsum(a * a)
+
+
+# ------------------------------------------------------------------- fused block, network
+def test_fused_block_and_residual():
+    l = {"kind": "conv", "cout": 4, "kh": 3, "kw": 3, "sh": 1, "sw": 1, "ph": 1, "pw": 1, "bn": True,
+         "act": "relu", "pool": {"kind": "max", "kh": 2, "kw": 2, "sh": 2, "sw": 2, "ph": 0, "pw": 0}}
+    x = R.standard_normal((2, 3, 8, 8))
+    p = {"w": R.standard_normal((4, 3, 3, 3)), "bias": R.standard_normal(4), "gamma": R.uniform(0.5, 1.5, 4),
+         "beta": R.uniform(-0.1, 0.1, 4), "mean": R.standard_normal(4) * 0.1, "var": R.uniform(0.5, 1.5, 4)}
+    res = R.standard_normal((2, 4, 8, 8))
+    y, arg, pre = orc.fused_conv(x, p, l, res, want_prepool=True)
+    t = F.conv2d(T(x), T(p["w"]), T(p["bias"]), padding=1)
+    t = F.batch_norm(t, T(p["mean"]), T(p["var"]), T(p["gamma"]), T(p["beta"]), False, 0.0, 1e-5)
+    t = F.relu(t + T(res))
+    assert np.allclose(pre, t.numpy(), rtol=1e-12, atol=1e-12)
+    wy, wa = F.max_pool2d(t, 2, 2, return_indices=True)
+    assert np.allclose(y, wy.numpy(), rtol=1e-12, atol=1e-12) and np.array_equal(arg, wa.numpy())
+    # zero weights: block output is relu(shift + residual)
+    p0 = dict(p, w=np.zeros_like(p["w"]), bias=np.zeros(4))
+    l0 = dict(l, pool=None, bn=False, act="none")
+    assert np.array_equal(orc.fused_conv(x, p0, l0, res)[0], res)
+
+
+def test_network_is_composition_and_batch_permutes():
+    from paper_2003_10688_amd import workloads as wl
+
+    wk = wl.config(1, batch=3, hw=8)
+    outs, args = orc.network_forward(wk.layers, wk.params, wk.x, return_all=True)
+    assert [o.shape for o in outs] == [(3, 32, 8, 8), (3, 32, 4, 4), (3, 64, 4, 4), (3, 64, 2, 2), (3, 64), (3, 10)]
+    assert args[1].dtype == np.int32 and args[0] is None
+    # same chain through the other code base's operators
+    t = T(wk.x)
+    for l, p in zip(wk.layers[:4], wk.params[:4]):
+        t = F.conv2d(t, T(p["w"]), T(p["bias"]), padding=1)
+        t = F.relu(F.batch_norm(t, T(p["mean"]), T(p["var"]), T(p["gamma"]), T(p["beta"]), False, 0.0, 1e-5))
+        if l["pool"]:
+            t = F.max_pool2d(t, 2, 2)
+    t = F.linear(t.mean((2, 3)), T(wk.params[5]["w"]), T(wk.params[5]["bias"]))
+    assert np.allclose(outs[-1], t.numpy(), rtol=1e-11, atol=1e-11)
+    perm = [2, 0, 1]
+    assert np.allclose(orc.network_forward(wk.layers, wk.params, wk.x[perm]), outs[-1][perm], rtol=1e-13)
+
+
+def test_resnet_shapes_and_residual_wiring():
+    from paper_2003_10688_amd import workloads as wl
+
+    wk = wl.config(3, batch=1, hw=32)
+    assert sum(l["kind"] == "conv" for l in wk.layers) == 53
+    outs = orc.network_forward(wk.layers, wk.params, wk.x, bf16=True, return_all=True)[0]
+    assert outs[0].shape == (1, 64, 16, 16) and outs[1].shape == (1, 64, 8, 8)
+    assert outs[-3].shape == (1, 2048, 1, 1) and outs[-1].shape == (1, 1000)
+    assert np.array_equal(orc.round_bf16(outs[-1]), outs[-1])       # every stored value is a bf16 number
+    wk18 = wl.config(2, batch=1, hw=32)
+    assert sum(l["kind"] == "conv" for l in wk18.layers) == 20
+    o18 = orc.network_forward(wk18.layers, wk18.params, wk18.x, bf16=True, return_all=True)[0]
+    assert o18[-3].shape == (1, 512, 1, 1)
+    # the library's own ResNet-18-shaped forward with the same tensors (fp64, no bf16 rounding)
+    o = orc.network_forward(wk18.layers, wk18.params, wk18.x, return_all=True)[0]
+    t = _torch_forward(wk18.layers, wk18.params, T(wk18.x))
+    assert np.allclose(o[-1], t.numpy(), rtol=1e-9, atol=1e-9)
+
+
+def _torch_forward(layers, params, x):
+    outs = []
+    for i, (l, p) in enumerate(zip(layers, params)):
+        s = l.get("src", -1)
+        t = (x if i == 0 else outs[i - 1]) if s == -1 else outs[s]
+        if l["kind"] == "conv":
+            t = F.conv2d(t, T(p["w"]), T(p["bias"]), stride=(l["sh"], l["sw"]), padding=(l["ph"], l["pw"]))
+            if l["bn"]:
+                t = F.batch_norm(t, T(p["mean"]), T(p["var"]), T(p["gamma"]), T(p["beta"]), False, 0.0, 1e-5)
+            if l["res"] >= 0:
+                t = t + outs[l["res"]]
+            if l["act"] == "relu":
+                t = F.relu(t)
+            if l["pool"]:
+                pd = l["pool"]
+                t = F.max_pool2d(t, (pd["kh"], pd["kw"]), (pd["sh"], pd["sw"]), (pd["ph"], pd["pw"]))
+        elif l["kind"] == "pool":
+            pd = l["pool"]
+            t = F.max_pool2d(t, (pd["kh"], pd["kw"]), (pd["sh"], pd["sw"]), (pd["ph"], pd["pw"]))
+        elif l["kind"] == "gap":
+            t = t.mean((2, 3))
+        else:
+            t = F.linear(t, T(p["w"]), T(p["bias"]))
+        outs.append(t)
+    return outs[-1]
+
+
+# ------------------------------------------------------------------------------ backward
+def _fd(f, x, h=1e-5):
+    """Central finite-difference gradient of scalar f at x."""
+    g = np.zeros_like(x)
+    it = np.nditer(x, flags=["multi_index"])
+    for _ in it:
+        i = it.multi_index
+        old = x[i]
+        x[i] = old + h
+        fp = f(x)
+        x[i] = old - h
+        fm = f(x)
+        x[i] = old
+        g[i] = (fp - fm) / (2 * h)
+    return g
+
+
+def test_conv_backward_fd_and_library():
+    x, w = R.standard_normal((2, 2, 5, 6)), R.standard_normal((3, 2, 3, 2))
+    st, pd = (2, 1), (1, 0)
+    gy = R.standard_normal(orc.conv2d(x, w, None, st, pd).shape)
+    dx = orc.conv2d_dgrad(gy, w, x.shape, st, pd)
+    dw, db = orc.conv2d_wgrad(x, gy, w.shape, st, pd)
+    assert np.allclose(dx, _fd(lambda a: (orc.conv2d(a, w, None, st, pd) * gy).sum(), x.copy()), rtol=1e-6, atol=1e-7)
+    assert np.allclose(dw, _fd(lambda a: (orc.conv2d(x, a, None, st, pd) * gy).sum(), w.copy()), rtol=1e-6, atol=1e-7)
+    assert np.allclose(db, gy.sum((0, 2, 3)))
+    tx, tw = T(x).requires_grad_(), T(w).requires_grad_()
+    (F.conv2d(tx, tw, None, st, pd) * T(gy)).sum().backward()
+    assert np.allclose(dx, tx.grad.numpy(), rtol=1e-12, atol=1e-12)
+    assert np.allclose(dw, tw.grad.numpy(), rtol=1e-12, atol=1e-12)
+    # delta input: wgrad closed form -- dw[k,c,r,s] picks one dy element per tap
+    xd = np.zeros((1, 1, 5, 5)); xd[0, 0, 2, 2] = 1.0
+    gy = R.standard_normal((1, 1, 5, 5))
+    dw, _ = orc.conv2d_wgrad(xd, gy, (1, 1, 3, 3), (1, 1), (1, 1))
+    assert np.array_equal(dw[0, 0], gy[0, 0, 1:4, 1:4][::-1, ::-1])
+
+
+def test_bn_backward_fd_library_and_invariants():
+    x = R.standard_normal((3, 2, 4, 3)) * 2 + 1
+    g, b = R.uniform(0.5, 1.5, 2), R.uniform(-1, 1, 2)
+    gy = R.standard_normal(x.shape)
+    _, mean, var = orc.bn_train(x, g, b, 1e-5)
+    dx, dg, dbt = orc.bn_train_bwd(x, gy, g, mean, var, 1e-5)
+    f = lambda a: (orc.bn_train(a, g, b, 1e-5)[0] * gy).sum()  # noqa: E731  (through the batch statistics)
+    assert np.allclose(dx, _fd(f, x.copy()), rtol=1e-5, atol=1e-7)
+    assert np.allclose(dg, _fd(lambda a: (orc.bn_train(x, a, b, 1e-5)[0] * gy).sum(), g.copy()), rtol=1e-6)
+    assert np.allclose(dbt, gy.sum((0, 2, 3)))
+    xh = (x - mean[None, :, None, None]) / np.sqrt(var + 1e-5)[None, :, None, None]
+    assert np.allclose(dx.sum((0, 2, 3)), 0, atol=1e-12)
+    # sum(dx*xhat) = gamma/sigma * dgamma * eps/(var+eps): zero up to the eps inside the square root
+    assert np.allclose((dx * xh).sum((0, 2, 3)), g / np.sqrt(var + 1e-5) * dg * 1e-5 / (var + 1e-5), atol=1e-11)
+    tx, tg, tb = T(x).requires_grad_(), T(g).requires_grad_(), T(b).requires_grad_()
+    (F.batch_norm(tx, None, None, tg, tb, True, 0.0, 1e-5) * T(gy)).sum().backward()
+    assert np.allclose(dx, tx.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(dg, tg.grad.numpy(), rtol=1e-10)
+
+
+def test_pool_relu_gap_linear_backward():
+    x = R.standard_normal((2, 2, 7, 6))
+    y, a = orc.maxpool(x, (3, 3), (2, 2), (1, 1))
+    gy = R.standard_normal(y.shape)
+    dx = orc.maxpool_bwd(gy, a, x.shape)
+    assert np.isclose(dx.sum(), gy.sum())                                    # gradient mass conserved
+    tx = T(x).requires_grad_()
+    (F.max_pool2d(tx, 3, 2, 1) * T(gy)).sum().backward()
+    assert np.allclose(dx, tx.grad.numpy(), rtol=1e-13, atol=1e-13)          # overlapping windows accumulate
+    for cp in (True, False):
+        dxa = orc.avgpool_bwd(gy, x.shape, (3, 3), (2, 2), (1, 1), cp)
+        tx = T(x).requires_grad_()
+        (F.avg_pool2d(tx, 3, 2, 1, count_include_pad=cp) * T(gy)).sum().backward()
+        assert np.allclose(dxa, tx.grad.numpy(), rtol=1e-13, atol=1e-13)
+    yr = orc.relu(x)
+    g2 = R.standard_normal(x.shape)
+    assert np.array_equal(orc.relu_bwd(yr, g2), np.where(x > 0, g2, 0.0))
+    gg = R.standard_normal((2, 2))
+    assert np.allclose(orc.gap_bwd(gg, x.shape), np.broadcast_to(gg[:, :, None, None] / 42.0, x.shape))
+    xl, wl_, gl = R.standard_normal((3, 5)), R.standard_normal((4, 5)), R.standard_normal((3, 4))
+    dxl, dwl, dbl = orc.linear_bwd(xl, wl_, gl)
+    assert np.allclose(dxl, gl @ wl_) and np.allclose(dwl, gl.T @ xl) and np.allclose(dbl, gl.sum(0))
+
+
+def test_softmax_ce_and_sgd():
+    loss, dz = orc.softmax_ce(np.zeros((4, 1000)), np.array([0, 5, 999, 17]))
+    assert abs(loss - math.log(1000.0)) < 1e-12                              # uniform logits -> ln K
+    z, lab = R.standard_normal((5, 7)) * 3, R.integers(0, 7, 5)
+    loss, dz = orc.softmax_ce(z, lab)
+    assert np.allclose(dz.sum(1), 0, atol=1e-15)
+    assert np.allclose(dz, _fd(lambda a: orc.softmax_ce(a, lab, False)[0], z.copy()), rtol=1e-6, atol=1e-9)
+    assert np.isclose(loss, F.cross_entropy(T(z), torch.from_numpy(lab).long()).item(), rtol=1e-13)
+    big, _ = orc.softmax_ce(z + 1000.0, lab)                                  # shift invariance / no overflow
+    assert np.isclose(big, loss, rtol=1e-10)
+    w0 = R.standard_normal(10); w, v, g = w0.copy(), np.zeros(10), R.standard_normal(10)
+    orc.sgd(w, v, g, 0.1, 0.9)
+    assert np.allclose(w, w0 - 0.1 * g) and np.array_equal(v, g)             # first step closed form
+    g2 = R.standard_normal(10)
+    orc.sgd(w, v, g2, 0.1, 0.9)
+    assert np.allclose(v, 0.9 * g + g2) and np.allclose(w, w0 - 0.1 * g - 0.1 * (0.9 * g + g2))
