@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark: ResNet-50-shaped inference forward, batch 64, bf16 storage / fp32 accumulate, one MI355X.
+
+A "step" is one pass of the whole hot path (every fused conv, the stem pool, the global average
+pool and the linear layer: 56 launches) over one resident batch of synthetic images.  Prints ONE
+JSON line with images/s, the roofline of the dominant kernel (the implicit-GEMM convolution,
+53 launches per step) and the CPU checker timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def layer_shapes(layers, in_shape, out_size):
+    """Logical NCHW input/output shape of every layer (bookkeeping for the algorithmic work counts)."""
+    shapes, ins = [], []
+    for i, l in enumerate(layers):
+        s = l.get("src", -1)
+        x = in_shape if (i == 0 and s == -1) else shapes[i - 1 if s == -1 else s]
+        if l["kind"] == "conv":
+            o = (x[0], l["cout"], out_size(x[2], l["kh"], l["sh"], l["ph"]), out_size(x[3], l["kw"], l["sw"], l["pw"]))
+        elif l["kind"] == "pool":
+            p = l["pool"]
+            o = (x[0], x[1], out_size(x[2], p["kh"], p["sh"], p["ph"]), out_size(x[3], p["kw"], p["sw"], p["pw"]))
+        elif l["kind"] == "gap":
+            o = (x[0], x[1], 1, 1)
+        else:
+            o = (x[0], l["out"], 1, 1)
+        ins.append(x)
+        shapes.append(o)
+    return ins, shapes
+
+
+def algorithmic_work(l, x, y, esize):
+    """(flops, bytes) the layer must perform/move: read input, weights and residual once, write output once."""
+    numel = lambda s: s[0] * s[1] * s[2] * s[3]  # noqa: E731
+    if l["kind"] == "conv":
+        k = l["kh"] * l["kw"] * x[1]
+        flops = 2.0 * y[0] * y[2] * y[3] * y[1] * k
+        byts = esize * (numel(x) + k * y[1] + numel(y) * (2 if l["res"] >= 0 else 1)) + 8 * y[1]
+        return flops, byts
+    if l["kind"] == "linear":
+        return 2.0 * x[0] * x[1] * y[1], esize * (numel(x) + x[1] * y[1] + numel(y)) + 4 * y[1]
+    return 0.0, esize * (numel(x) + numel(y))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=3, help="workload: 3 = ResNet-50-shaped bs64 (default), 2 = ResNet-18-shaped bs32")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--layer-reps", type=int, default=20, help="event-timed repetitions per layer for the roofline")
+    ap.add_argument("--cpu-sample", type=int, default=8, help="images the CPU checker is timed on (0 = skip)")
+    ap.add_argument("--layers", action="store_true", help="also print a per-layer table to stderr")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no multi-GPU sharding or collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2003_10688_amd import sol
+    from paper_2003_10688_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    sol.lib()
+    wk = wl.config(a.config, batch=a.batch)
+    dt = sol.BF16 if wk.bf16 else sol.F32
+    esize = 2 if wk.bf16 else 4
+    net = sol.Network(wk.layers, wk.in_shape, dt)
+    net.set_params(wk.params)
+    x = sol.to_device_nhwc(wk.x, dt)
+    stream = torch.cuda.current_stream()
+    torch.cuda.synchronize()
+
+    # ---- whole-step throughput -------------------------------------------------------------------
+    for _ in range(a.warmup):
+        net.forward(x, stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(a.steps):
+        net.forward(x, stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / a.steps
+    ev_ms = ev0.elapsed_time(ev1) / a.steps
+    batch = wk.in_shape[0]
+    imgs_per_s = batch / (wall_ms * 1e-3)
+
+    # ---- per-layer event timing (same stream) for the roofline of the dominant kernel ---------------
+    ins, outs = layer_shapes(wk.layers, wk.in_shape, sol.sol_out_size)
+    rows = []
+    for i, l in enumerate(wk.layers):
+        net.run_layer(i, x, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(a.layer_reps):
+            net.run_layer(i, x, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / a.layer_reps
+        fl, by = algorithmic_work(l, ins[i], outs[i], esize)
+        rows.append({"i": i, "kind": l["kind"], "us": us, "flops": fl, "bytes": by})
+    conv = [r for r in rows if r["kind"] == "conv"]
+    conv_us = sum(r["us"] for r in conv)
+    conv_fl = sum(r["flops"] for r in conv)
+    conv_by = sum(r["bytes"] for r in conv)
+    ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    mf = [r for r in conv if r["flops"] / r["bytes"] >= ridge]
+    hb = [r for r in conv if r["flops"] / r["bytes"] < ridge]
+    mem = [r for r in rows if r["kind"] in ("pool", "gap")]
+    tfl = conv_fl / (conv_us * 1e-6) / 1e12
+    roofline = {
+        "bound": "mfma", "kernel": "conv_igemm_kernel", "launches_per_step": len(conv),
+        "achieved": round(tfl, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl / PEAK_BF16_TFLOPS, 4),
+        "avg_launch_us": round(conv_us / max(len(conv), 1), 2), "algorithmic_gflop_per_launch": round(conv_fl / max(len(conv), 1) / 1e9, 3),
+        "traffic": None,
+        "mfma_bound_layers": {"n": len(mf), "tflops": round(sum(r["flops"] for r in mf) / max(sum(r["us"] for r in mf), 1e-9) / 1e6, 2),
+                              "frac": round(sum(r["flops"] for r in mf) / max(sum(r["us"] for r in mf), 1e-9) / 1e6 / PEAK_BF16_TFLOPS, 4)},
+        "hbm_bound_layers": {"n": len(hb), "gbs": round(sum(r["bytes"] for r in hb) / max(sum(r["us"] for r in hb), 1e-9) / 1e3, 1),
+                             "frac": round(sum(r["bytes"] for r in hb) / max(sum(r["us"] for r in hb), 1e-9) / 1e3 / PEAK_HBM_GBS, 4)},
+        "pool_gap_kernels": {"n": len(mem), "gbs": round(sum(r["bytes"] for r in mem) / max(sum(r["us"] for r in mem), 1e-9) / 1e3, 1),
+                             "frac": round(sum(r["bytes"] for r in mem) / max(sum(r["us"] for r in mem), 1e-9) / 1e3 / PEAK_HBM_GBS, 4)},
+        "conv_algorithmic_gb_per_step": round(conv_by / 1e9, 3),
+        "sum_layer_us": round(sum(r["us"] for r in rows), 1),
+    }
+    if a.layers:
+        for r, xi, yo in zip(rows, ins, outs):
+            ai = r["flops"] / r["bytes"]
+            print(f"L{r['i']:02d} {r['kind']:6s} in{xi} out{yo} {r['us']:8.1f} us  {r['flops'] / r['us'] / 1e6:8.1f} TFLOP/s"
+                  f"  {r['bytes'] / r['us'] / 1e3:8.1f} GB/s  AI {ai:6.0f}", file=sys.stderr)
+
+    # ---- CPU checker on a bounded sample of the same workload ------------------------------------------
+    cpu = None
+    if a.cpu_sample > 0:
+        import oracle
+
+        n = min(a.cpu_sample, batch)
+        t0 = time.perf_counter()
+        oracle.network_forward(wk.layers, wk.params, wk.x[:n], bf16=wk.bf16)
+        dt_s = time.perf_counter() - t0
+        cpu = {"value": round(n / dt_s, 3), "unit": "images/s", "cores": oracle.threads(), "kind": "oracle",
+               "sample": f"first {n} images of the batch, full network, one pass, {dt_s:.1f} s"}
+
+    out = {
+        "metric": "images/sec ResNet-50-shaped fwd bs64 on 1 GPU" if a.config == 3 and batch == 64 else f"images/sec {wk.name} fwd bs{batch} on 1 GPU",
+        "value": round(imgs_per_s, 1), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(wall_ms, 4), "event_ms_per_step": round(ev_ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if wk.bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{wk.name} batch {batch} input 3x{wk.in_shape[2]}x{wk.in_shape[3]} (seeded synthetic, He-normal weights)",
+                   "launches_per_step": len(wk.layers)},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

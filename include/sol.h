@@ -1,0 +1,182 @@
+/*
+ * libsol_mi355 -- C ABI of the fused CNN layer-chain engine for AMD MI355X (gfx950).
+ *
+ * The library executes what the paper's optimizing backend accelerates: the
+ * forward (and, for training, backward) pass of a CNN layer chain, with the
+ * convolution / linear layers run as dense contractions on the matrix cores
+ * and their memory-bound neighbours (batch-norm, bias, ReLU, residual add,
+ * pooling) fused into them (paper Sec. III-A: layer fusion that keeps data in
+ * registers and caches; conv/linear as the work-intensive layers).
+ *
+ * Boundary conventions, after the paper's runtime (Sec. III-B: kernels read and
+ * write the framework's tensors in place, the framework stays the only
+ * allocator; Sec. III-A: optimise once, call many times):
+ *
+ *  - every data pointer is a DEVICE pointer owned by the caller; the library
+ *    allocates no device memory and keeps no reference after a call returns,
+ *    except for the buffers explicitly bound to a sol_network;
+ *  - every call only enqueues work on `hip_stream` (a hipStream_t passed as
+ *    void*, NULL = default stream) and returns without synchronising;
+ *  - activations are dense NHWC: element (n,c,h,w) lives at ((n*H+h)*W+w)*C+c;
+ *    documentation and pooling argmax use logical (n,c,h,w) indices;
+ *  - arguments are validated before anything is launched; on error nothing was
+ *    enqueued, a status code is returned and sol_last_error() holds the text;
+ *  - device buffers must be 16-byte aligned; tensors hold fewer than 2^31 elements.
+ */
+#ifndef SOL_MI355_H
+#define SOL_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SOL_OK = 0,
+    SOL_ERR_NULL = 1,        /* a required pointer is NULL */
+    SOL_ERR_SHAPE = 2,       /* inconsistent or non-positive sizes */
+    SOL_ERR_DTYPE = 3,       /* unknown element type */
+    SOL_ERR_ALIGN = 4,       /* pointer not 16-byte aligned */
+    SOL_ERR_WORKSPACE = 5,   /* a caller-provided buffer is too small */
+    SOL_ERR_UNSUPPORTED = 6, /* valid request outside what the kernels implement */
+    SOL_ERR_HIP = 7          /* the HIP runtime reported an error */
+} sol_status;
+
+typedef enum { SOL_F32 = 0, SOL_BF16 = 1 } sol_dtype;  /* bf16 = bf16 storage, fp32 accumulate */
+typedef enum { SOL_ACT_NONE = 0, SOL_ACT_RELU = 1 } sol_act;
+typedef enum { SOL_POOL_NONE = 0, SOL_POOL_MAX = 1, SOL_POOL_AVG = 2 } sol_pool_kind;
+typedef enum { SOL_LAYER_CONV = 0, SOL_LAYER_POOL = 1, SOL_LAYER_GAP = 2, SOL_LAYER_LINEAR = 3 } sol_layer_kind;
+
+/* sliding-window pooling; floor-mode output size; count_pad selects the average-pool divisor
+ * (window area vs. number of in-range elements), the switch of the paper's pooling description
+ * (Sec. IV, AveragePooling listing: K.area(isCountPadding)) */
+typedef struct { int kind, kh, kw, sh, sw, ph, pw, count_pad; } sol_pool_desc;
+typedef struct { int n, h, w, c; int dtype; } sol_tensor_desc;       /* dense NHWC */
+typedef struct { int cout, cin, kh, kw, sh, sw, ph, pw; } sol_conv_desc;
+
+/* one entry of a layer list; src / res are absolute indices of the producing layer
+ * (src = -1: previous layer, or the network input for layer 0; res = -1: no residual) */
+typedef struct {
+    int kind;               /* sol_layer_kind */
+    sol_conv_desc conv;     /* CONV: cin is inferred and may be 0 */
+    int has_bn;             /* CONV: batch-norm follows the convolution */
+    int act;                /* CONV, LINEAR: sol_act */
+    sol_pool_desc pool;     /* CONV: pool fused behind the activation (kind NONE = none); POOL: the pool */
+    int out_features;       /* LINEAR */
+    int src, res;
+} sol_layer;
+
+typedef struct sol_network sol_network;
+
+const char *sol_last_error(void);   /* thread-local text of the last failure on this thread */
+const char *sol_version(void);
+
+/* ---- parameter preparation (run once per model: the paper's optimise step, Sec. III-A) -------- */
+
+/* Bytes of the packed form of a convolution weight: [cout][kh][kw][cin] in `dt`, each output
+ * channel's kh*kw*cin run zero-padded to a multiple of 64 (bf16) / 32 (fp32) elements. */
+size_t sol_packed_weight_bytes(const sol_conv_desc *cd, sol_dtype dt);
+
+/* w_oihw: device fp32 [cout][cin][kh][kw]  ->  w_packed (device, sol_packed_weight_bytes).
+ * bf16 packing rounds to nearest even. */
+sol_status sol_pack_conv_weights(const sol_conv_desc *cd, sol_dtype dt, const float *w_oihw,
+                                 void *w_packed, void *hip_stream);
+
+/* Inverse of the packing, widened to fp32 OIHW (used after an SGD step and by tests). */
+sol_status sol_unpack_conv_weights(const sol_conv_desc *cd, sol_dtype dt, const void *w_packed,
+                                   float *w_oihw, void *hip_stream);
+
+/* Fold inference batch-norm and the convolution bias into one per-channel affine map (fp32, device):
+ *   scale = gamma / sqrt(var + eps),  shift = beta - mean*scale + bias*scale.
+ * gamma/beta/mean/var may all be NULL (no BN: scale = 1, shift = bias); bias may be NULL (0). */
+sol_status sol_fold_bn(int c, const float *gamma, const float *beta, const float *mean,
+                       const float *var, const float *bias, float eps, float *scale, float *shift,
+                       void *hip_stream);
+
+/* ---- single fused layers ----------------------------------------------------------------------- */
+
+/* y = pool( act( scale[k] * conv(x, w)[.,k] + shift[k] + residual ) )
+ * (the fused block of the problem statement: conv, folded BN, residual, ReLU, optional pool).
+ *   xd, x      input NHWC, dtype xd->dtype (SOL_F32 or SOL_BF16); cd->cin must equal xd->c
+ *   w_packed   from sol_pack_conv_weights with the same cd and dtype
+ *   scale,shift device fp32 [cout]; NULL = 1 / 0
+ *   residual   NULL or NHWC [n][Ho][Wo][cout] of the same dtype (conv-output shape, before pooling)
+ *   pool       NULL or kind NONE = no pool.  Fused: max or avg, 2x2 window, stride 2, no padding
+ *              (floor mode: an odd last row/column is dropped); any other pool -> SOL_ERR_UNSUPPORTED
+ *              (run sol_pool on the result instead).
+ *   y          NHWC [n][Hy][Wy][cout], same dtype as x
+ *   pool_argmax NULL, or int32 NHWC like y (max pool only): logical index ih*Wo+iw of the winning
+ *              element inside its (n,k) conv-output plane; among equal values the first in row-major
+ *              window order wins.
+ *   prepool    NULL, or a buffer of the conv-output shape that receives act(...) before pooling
+ *              (same dtype as y; lets a caller check pooled values and indices on identical inputs).
+ * Accumulation is fp32 for both dtypes; fp32 inputs use true fp32 multiplies. */
+sol_status sol_conv2d_fused(const sol_tensor_desc *xd, const void *x, const sol_conv_desc *cd,
+                            const void *w_packed, const float *scale, const float *shift,
+                            const void *residual, int act, const sol_pool_desc *pool, void *y,
+                            int32_t *pool_argmax, void *prepool, void *hip_stream);
+
+/* y[m][o] = act( bias[o] + sum_i x[m][i] * w[o][i] ).  x [m][in_f], y [m][out_f] in `dt`;
+ * w: [out_f][in_f] packed as a 1x1 convolution weight (sol_pack_conv_weights with
+ * cd = {out_f, in_f, 1,1,1,1,0,0}); bias device fp32 [out_f] or NULL. */
+sol_status sol_linear(int m, int in_f, int out_f, sol_dtype dt, const void *x, const void *w_packed,
+                      const float *bias, int act, void *y, void *hip_stream);
+
+/* Stand-alone pooling over NHWC x (max with optional int32 argmax as above, or average).
+ * Padding acts as -inf for max and as 0 for average.  Requires pad < kernel. */
+sol_status sol_pool(const sol_tensor_desc *xd, const void *x, const sol_pool_desc *pd, void *y,
+                    int32_t *argmax, void *hip_stream);
+
+/* Global average pool: y[n][c] = mean over h,w of x[n][h][w][c]; y has x's dtype. */
+sol_status sol_global_avgpool(const sol_tensor_desc *xd, const void *x, void *y, void *hip_stream);
+
+/* Output extent of a sliding window, floor mode: (in + 2*pad - k) / stride + 1. */
+int sol_out_size(int in, int k, int stride, int pad);
+
+/* ---- whole networks: plan once, run many -------------------------------------------------------- */
+
+/* Validates the layer list against `input`, infers every shape, chooses per-layer kernels/tiles and
+ * lays out the parameter and activation buffers.  Host-only; allocates no device memory.
+ * flags: SOL_NET_KEEP_ACTIVATIONS keeps every layer's output alive in the workspace (otherwise a
+ * buffer is reused once its last consumer has run); SOL_NET_TRAINING implies it. */
+enum { SOL_NET_TRAINING = 1, SOL_NET_KEEP_ACTIVATIONS = 2 };
+sol_status sol_network_create(const sol_layer *layers, int n_layers, const sol_tensor_desc *input,
+                              int flags, sol_network **out);
+void sol_network_destroy(sol_network *net);
+
+size_t sol_network_param_bytes(const sol_network *net);      /* packed weights + folded scale/shift */
+size_t sol_network_workspace_bytes(const sol_network *net);  /* activations between layers */
+int sol_network_num_layers(const sol_network *net);
+/* shape of a layer's output (layer = -1: the network output) */
+sol_status sol_network_output_desc(const sol_network *net, int layer, sol_tensor_desc *out);
+
+/* Hands the network a caller-owned device buffer of at least sol_network_param_bytes() that must
+ * stay valid while the network is used. */
+sol_status sol_network_bind_params(sol_network *net, void *param_buf, size_t bytes);
+
+/* Packs one layer's parameters (device fp32, framework layout: conv w [cout][cin][kh][kw], linear
+ * w [out][in]) into the bound buffer and folds BN (gamma..var NULL when the layer has no BN). */
+sol_status sol_network_set_params(sol_network *net, int layer, const float *w, const float *gamma,
+                                  const float *beta, const float *mean, const float *var,
+                                  const float *bias, float eps, void *hip_stream);
+
+/* Runs the layer list: one launch per fused layer on the stream, activations ping-ponged inside
+ * `workspace`.  x: network input (NHWC), y: output of the last layer. */
+sol_status sol_network_forward(sol_network *net, const void *x, void *y, void *workspace,
+                               size_t workspace_bytes, void *hip_stream);
+
+/* Runs one layer only, on whatever its producers left in the workspace (profiling aid: lets a caller
+ * bracket a single layer with events).  Same arguments as sol_network_forward. */
+sol_status sol_network_run_layer(sol_network *net, int layer, const void *x, void *y, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream);
+
+/* Device address (inside the workspace passed to the last forward) of a layer's output; only
+ * meaningful after a forward of a network created with SOL_NET_KEEP_ACTIVATIONS. */
+sol_status sol_network_layer_output(const sol_network *net, int layer, void *workspace, void **ptr);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SOL_MI355_H */

@@ -109,6 +109,15 @@ def bn_infer(x, gamma, beta, mean, var, eps=1e-5):
     return y
 
 
+def bn_infer_points(v, ch, gamma, beta, mean, var, eps=1e-5):
+    v = _d(v)
+    ch = np.ascontiguousarray(ch, dtype=np.int32)
+    y = np.empty_like(v)
+    lib().orc_bn_infer_points(_p(v), _p(ch), _p(_d(gamma)), _p(_d(beta)), _p(_d(mean)), _p(_d(var)), C.c_double(eps),
+                              _p(y), C.c_int(v.size))
+    return y
+
+
 def bn_train(x, gamma, beta, eps=1e-5):
     x = _d(x)
     N, Cc = x.shape[:2]
@@ -300,6 +309,21 @@ def fused_conv(x, p, l, residual=None, bf16=False, want_prepool=False):
     if bf16:
         y = round_bf16(y)
     return y, arg, pre
+
+
+def fused_conv_points(x, p, l, coords, residual=None, bf16=False):
+    """The fused block (without pool) evaluated at output coordinates (n,k,p,q) only."""
+    coords = np.ascontiguousarray(coords, dtype=np.int32)
+    y = conv2d_points(x, p["w"], p.get("bias"), coords, (l["sh"], l["sw"]), (l["ph"], l["pw"]))
+    if l["bn"]:
+        y = bn_infer_points(y, coords[:, 1], p["gamma"], p["beta"], p["mean"], p["var"], p.get("eps", 1e-5))
+    if residual is not None:
+        y = add(y, _d(residual)[coords[:, 0], coords[:, 1], coords[:, 2], coords[:, 3]])
+    if l["act"] == "relu":
+        y = relu(y)
+    if bf16:
+        y = round_bf16(y)
+    return y
 
 
 def network_forward(layers, params, x, bf16=False, return_all=False):

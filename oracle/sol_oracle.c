@@ -80,6 +80,15 @@ void orc_bn_infer(const double *x, const double *gamma, const double *beta, cons
             }
 }
 
+/* the same map applied to a list of scalars, element i belonging to channel ch[i] */
+void orc_bn_infer_points(const double *x, const int32_t *ch, const double *gamma, const double *beta,
+                         const double *mean, const double *var, double eps, double *y, int n) {
+    for (int i = 0; i < n; i++) {
+        const int c = ch[i];
+        y[i] = gamma[c] * (x[i] - mean[c]) / sqrt(var[c] + eps) + beta[c];
+    }
+}
+
 /* training batch-norm: per-channel mean and biased variance over (N,H,W) */
 void orc_bn_train(const double *x, const double *gamma, const double *beta, double eps, double *y,
                   double *mean_out, double *var_out, int N, int C, int HW) {

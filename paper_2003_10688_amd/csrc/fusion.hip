@@ -1,0 +1,253 @@
+// Memory-bound kernels of the fusion engine: pooling, global average pooling, and the one-off
+// parameter preparation (weight packing, BN folding).  No matrix cores here: every kernel is one
+// coalesced NHWC pass with 16-byte accesses along the channel axis, the MI355X form of the paper's
+// fused loop nests for all non-contraction layers (Sec. III-A, depth-first fusion module; Sec. IV,
+// AveragePooling listing for the pooling semantics).
+#include <math.h>
+
+#include "common.h"
+
+namespace sol {
+
+// ---- parameter preparation ------------------------------------------------------------------------
+template <typename T>
+__global__ void pack_weights_kernel(const float *__restrict__ w, T *__restrict__ out, int K, int C, int R,
+                                    int S, int Kp) {
+    const long total = (long)K * Kp;
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const int k = (int)(i / Kp), j = (int)(i % Kp);
+        float v = 0.f;
+        if (j < R * S * C) {
+            const int c = j % C, tap = j / C, s = tap % S, r = tap / S;
+            v = w[(((long)k * C + c) * R + r) * S + s];
+        }
+        Elem<T>::store(out + i, v);
+    }
+}
+
+template <typename T>
+__global__ void unpack_weights_kernel(const T *__restrict__ in, float *__restrict__ w, int K, int C, int R,
+                                      int S, int Kp) {
+    const long total = (long)K * C * R * S;
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const int s = (int)(i % S);
+        long t = i / S;
+        const int r = (int)(t % R); t /= R;
+        const int c = (int)(t % C);
+        const int k = (int)(t / C);
+        w[i] = Elem<T>::load(in + (long)k * Kp + ((long)r * S + s) * C + c);
+    }
+}
+
+__global__ void fold_bn_kernel(int c, const float *gamma, const float *beta, const float *mean, const float *var,
+                               const float *bias, float eps, float *scale, float *shift) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= c) return;
+    const float b = bias ? bias[i] : 0.f;
+    if (gamma) {
+        const float sc = gamma[i] / sqrtf(var[i] + eps);
+        scale[i] = sc;
+        shift[i] = beta[i] - mean[i] * sc + b * sc;
+    } else {
+        scale[i] = 1.f;
+        shift[i] = b;
+    }
+}
+
+// ---- pooling ----------------------------------------------------------------------------------------
+template <typename T, int V> struct VecIO;
+template <> struct VecIO<float, 4> {
+    static __device__ __forceinline__ void load(const float *p, float v[4]) {
+        const float4 f = *reinterpret_cast<const float4 *>(p);
+        v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+    }
+    static __device__ __forceinline__ void store(float *p, const float v[4]) {
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <> struct VecIO<float, 1> {
+    static __device__ __forceinline__ void load(const float *p, float v[1]) { v[0] = *p; }
+    static __device__ __forceinline__ void store(float *p, const float v[1]) { *p = v[0]; }
+};
+template <> struct VecIO<bf16_t, 8> {
+    static __device__ __forceinline__ void load(const bf16_t *p, float v[8]) {
+        const uint4 u = *reinterpret_cast<const uint4 *>(p);
+        const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ void store(bf16_t *p, const float v[8]) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+        *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+template <> struct VecIO<bf16_t, 1> {
+    static __device__ __forceinline__ void load(const bf16_t *p, float v[1]) { v[0] = bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(bf16_t *p, const float v[1]) { *p = f32_to_bf16(v[0]); }
+};
+
+// One thread = one output pixel x V consecutive channels; consecutive lanes walk the channel axis
+// first, so every window tap is one coalesced 16-byte-per-lane access.
+template <typename T, int V>
+__global__ void __launch_bounds__(256) pool_kernel(const PoolArgs a) {
+    const int cg = a.C / V;
+    const long total = (long)a.N * a.Ho * a.Wo * cg;
+    const T *__restrict__ x = static_cast<const T *>(a.x);
+    T *__restrict__ y = static_cast<T *>(a.y);
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const int g = (int)(i % cg);
+        long t = i / cg;
+        const int q = (int)(t % a.Wo); t /= a.Wo;
+        const int p = (int)(t % a.Ho);
+        const int n = (int)(t / a.Ho);
+        float best[V];
+        int bi[V];
+#pragma unroll
+        for (int e = 0; e < V; e++) { best[e] = 0.f; bi[e] = -1; }
+        int cnt = 0;
+        for (int r = 0; r < a.kh; r++) {
+            const int ih = p * a.sh + r - a.ph;
+            if ((unsigned)ih >= (unsigned)a.H) continue;
+            for (int s = 0; s < a.kw; s++) {
+                const int iw = q * a.sw + s - a.pw;
+                if ((unsigned)iw >= (unsigned)a.W) continue;
+                float v[V];
+                VecIO<T, V>::load(x + (((long)n * a.H + ih) * a.W + iw) * a.C + g * V, v);
+                cnt++;
+                if (a.kind == SOL_POOL_MAX) {
+                    // row-major window scan, strict '>' : the first of equal maxima wins
+#pragma unroll
+                    for (int e = 0; e < V; e++)
+                        if (bi[e] < 0 || v[e] > best[e]) { best[e] = v[e]; bi[e] = ih * a.W + iw; }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < V; e++) best[e] += v[e];
+                }
+            }
+        }
+        if (a.kind == SOL_POOL_AVG) {
+            const float div = a.count_pad ? (float)(a.kh * a.kw) : (float)cnt;
+#pragma unroll
+            for (int e = 0; e < V; e++) best[e] = best[e] / div;
+        }
+        const long o = i * V;   // == (((n*Ho+p)*Wo+q)*C + g*V)
+        VecIO<T, V>::store(y + o, best);
+        if (a.argmax && a.kind == SOL_POOL_MAX) {
+#pragma unroll
+            for (int e = 0; e < V; e++) a.argmax[o + e] = bi[e];
+        }
+    }
+}
+
+template <typename T, int V>
+static void launch_pool_t(const PoolArgs &a, hipStream_t st) {
+    const long total = (long)a.N * a.Ho * a.Wo * (a.C / V);
+    if (total <= 0) return;
+    long blocks = (total + 255) / 256;
+    if (blocks > 256L * 64) blocks = 256L * 64;
+    hipLaunchKernelGGL((pool_kernel<T, V>), dim3((unsigned)blocks), dim3(256), 0, st, a);
+}
+
+sol_status launch_pool(const PoolArgs &a, int dt, hipStream_t st) {
+    if (dt == SOL_BF16) {
+        if (a.C % 8 == 0) launch_pool_t<bf16_t, 8>(a, st); else launch_pool_t<bf16_t, 1>(a, st);
+    } else {
+        if (a.C % 4 == 0) launch_pool_t<float, 4>(a, st); else launch_pool_t<float, 1>(a, st);
+    }
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+// ---- global average pool ------------------------------------------------------------------------------
+// One wavefront-row of lanes walks the channel axis (coalesced), SPLIT lanes-rows of a block share the
+// H*W axis and combine through LDS; the sum runs in fp32.
+template <typename T, int V>
+__global__ void __launch_bounds__(256) gap_kernel(const T *__restrict__ x, T *__restrict__ y, int N, int HW, int C) {
+    constexpr int SPLIT = 4;                       // 64 channel-vectors x 4 pixel slices per block
+    __shared__ float part[SPLIT][64][V];
+    const int cg = C / V;
+    const int gblocks = (cg + 63) / 64;
+    const int n = blockIdx.x / gblocks;
+    const int g = (blockIdx.x % gblocks) * 64 + (threadIdx.x & 63);
+    const int slice = threadIdx.x >> 6;
+    float acc[V];
+#pragma unroll
+    for (int e = 0; e < V; e++) acc[e] = 0.f;
+    if (g < cg) {
+        for (int i = slice; i < HW; i += SPLIT) {
+            float v[V];
+            VecIO<T, V>::load(x + ((long)n * HW + i) * C + g * V, v);
+#pragma unroll
+            for (int e = 0; e < V; e++) acc[e] += v[e];
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < V; e++) part[slice][threadIdx.x & 63][e] = acc[e];
+    __syncthreads();
+    if (slice == 0 && g < cg) {
+        float o[V];
+#pragma unroll
+        for (int e = 0; e < V; e++)
+            o[e] = (((part[0][threadIdx.x][e] + part[1][threadIdx.x][e]) + part[2][threadIdx.x][e]) + part[3][threadIdx.x][e]) / (float)HW;
+        VecIO<T, V>::store(y + (long)n * C + g * V, o);
+    }
+}
+
+template <typename T, int V>
+static void launch_gap_t(const void *x, void *y, int N, int HW, int C, hipStream_t st) {
+    const int gblocks = (C / V + 63) / 64;
+    if (N * gblocks <= 0) return;
+    hipLaunchKernelGGL((gap_kernel<T, V>), dim3(N * gblocks), dim3(256), 0, st, static_cast<const T *>(x),
+                       static_cast<T *>(y), N, HW, C);
+}
+
+sol_status launch_gap(const void *x, void *y, int N, int HW, int C, int dt, hipStream_t st) {
+    if (dt == SOL_BF16) {
+        if (C % 8 == 0) launch_gap_t<bf16_t, 8>(x, y, N, HW, C, st); else launch_gap_t<bf16_t, 1>(x, y, N, HW, C, st);
+    } else {
+        if (C % 4 == 0) launch_gap_t<float, 4>(x, y, N, HW, C, st); else launch_gap_t<float, 1>(x, y, N, HW, C, st);
+    }
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_pack(const sol_conv_desc &cd, int dt, const float *w, void *out, bool unpack, hipStream_t st) {
+    const int Kp = packed_k(cd, dt);
+    const long total = unpack ? (long)cd.cout * cd.cin * cd.kh * cd.kw : (long)cd.cout * Kp;
+    if (total <= 0) return SOL_OK;
+    long blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    if (dt == SOL_BF16) {
+        if (unpack)
+            hipLaunchKernelGGL((unpack_weights_kernel<bf16_t>), dim3((unsigned)blocks), dim3(256), 0, st,
+                               static_cast<const bf16_t *>(out), const_cast<float *>(w), cd.cout, cd.cin, cd.kh, cd.kw, Kp);
+        else
+            hipLaunchKernelGGL((pack_weights_kernel<bf16_t>), dim3((unsigned)blocks), dim3(256), 0, st, w,
+                               static_cast<bf16_t *>(out), cd.cout, cd.cin, cd.kh, cd.kw, Kp);
+    } else {
+        if (unpack)
+            hipLaunchKernelGGL((unpack_weights_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, st,
+                               static_cast<const float *>(out), const_cast<float *>(w), cd.cout, cd.cin, cd.kh, cd.kw, Kp);
+        else
+            hipLaunchKernelGGL((pack_weights_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, st, w,
+                               static_cast<float *>(out), cd.cout, cd.cin, cd.kh, cd.kw, Kp);
+    }
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_fold(int c, const float *gamma, const float *beta, const float *mean, const float *var,
+                       const float *bias, float eps, float *scale, float *shift, hipStream_t st) {
+    if (c <= 0) return SOL_OK;
+    hipLaunchKernelGGL(fold_bn_kernel, dim3((c + 255) / 256), dim3(256), 0, st, c, gamma, beta, mean, var, bias, eps,
+                       scale, shift);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+}  // namespace sol

@@ -1,0 +1,302 @@
+"""Thin Python binding of libsol_mi355.so (see include/sol.h): same names, argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the computation runs inside the HIP
+library.  There is no CPU fallback: if the library is missing or there is no GPU, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsol_mi355.so")
+
+F32, BF16 = 0, 1
+ACT_NONE, ACT_RELU = 0, 1
+POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
+LAYER_CONV, LAYER_POOL, LAYER_GAP, LAYER_LINEAR = 0, 1, 2, 3
+NET_TRAINING, NET_KEEP_ACTIVATIONS = 1, 2
+
+STATUS = {0: "SOL_OK", 1: "SOL_ERR_NULL", 2: "SOL_ERR_SHAPE", 3: "SOL_ERR_DTYPE", 4: "SOL_ERR_ALIGN",
+          5: "SOL_ERR_WORKSPACE", 6: "SOL_ERR_UNSUPPORTED", 7: "SOL_ERR_HIP"}
+
+
+class PoolDesc(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("kind", "kh", "kw", "sh", "sw", "ph", "pw", "count_pad")]
+
+
+class TensorDesc(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("n", "h", "w", "c", "dtype")]
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("cout", "cin", "kh", "kw", "sh", "sw", "ph", "pw")]
+
+
+class Layer(C.Structure):
+    _fields_ = [("kind", C.c_int), ("conv", ConvDesc), ("has_bn", C.c_int), ("act", C.c_int),
+                ("pool", PoolDesc), ("out_features", C.c_int), ("src", C.c_int), ("res", C.c_int)]
+
+
+class SolError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"{STATUS.get(status, status)}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Loads the HIP library; fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} not found: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        L.sol_last_error.restype = C.c_char_p
+        L.sol_version.restype = C.c_char_p
+        L.sol_packed_weight_bytes.restype = C.c_size_t
+        L.sol_packed_weight_bytes.argtypes = [C.POINTER(ConvDesc), C.c_int]
+        L.sol_network_param_bytes.restype = C.c_size_t
+        L.sol_network_param_bytes.argtypes = [C.c_void_p]
+        L.sol_network_workspace_bytes.restype = C.c_size_t
+        L.sol_network_workspace_bytes.argtypes = [C.c_void_p]
+        L.sol_network_num_layers.argtypes = [C.c_void_p]
+        L.sol_network_destroy.argtypes = [C.c_void_p]
+        L.sol_network_destroy.restype = None
+        L.sol_debug_set_conv_tile.restype = None
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != 0:
+        raise SolError(status, lib().sol_last_error().decode())
+
+
+def _ptr(t):
+    if t is None:
+        return C.c_void_p(0)
+    if isinstance(t, torch.Tensor):
+        assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous GPU tensors"
+        return C.c_void_p(t.data_ptr())
+    return C.c_void_p(int(t))
+
+
+def _stream(stream=None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def torch_dtype(dt):
+    return torch.bfloat16 if dt == BF16 else torch.float32
+
+
+def dtype_of(t):
+    return BF16 if t.dtype == torch.bfloat16 else F32
+
+
+# ---- layout marshalling (logical NCHW numpy  <->  NHWC device tensors) --------------------------------
+def to_device_nhwc(a, dt, device="cuda:0"):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    if t.dim() == 4:
+        t = t.permute(0, 2, 3, 1)
+    return t.contiguous().to(device=device, dtype=torch_dtype(dt))
+
+
+def to_host_nchw(t):
+    t = t.detach().to("cpu")
+    if t.dtype == torch.bfloat16:
+        t = t.to(torch.float32)
+    if t.dim() == 4:
+        t = t.permute(0, 3, 1, 2)
+    return t.contiguous().numpy()
+
+
+def dev_f32(a, device="cuda:0"):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+def pool_desc(pd):
+    if pd is None:
+        return None
+    kind = {"max": POOL_MAX, "avg": POOL_AVG, "none": POOL_NONE}[pd["kind"]] if isinstance(pd["kind"], str) else pd["kind"]
+    return PoolDesc(kind, pd["kh"], pd["kw"], pd["sh"], pd["sw"], pd["ph"], pd["pw"], int(pd.get("count_pad", 1)))
+
+
+def tensor_desc(t):
+    n, h, w, c = t.shape
+    return TensorDesc(n, h, w, c, dtype_of(t))
+
+
+# ---- single-layer entry points ------------------------------------------------------------------------
+def sol_out_size(n, k, s, p):
+    return lib().sol_out_size(C.c_int(n), C.c_int(k), C.c_int(s), C.c_int(p))
+
+
+def sol_packed_weight_bytes(cd, dt):
+    return lib().sol_packed_weight_bytes(C.byref(cd), C.c_int(dt))
+
+
+def sol_pack_conv_weights(cd, dt, w_oihw, stream=None):
+    """w_oihw: device fp32 [cout][cin][kh][kw] -> packed device buffer (uint8 tensor)."""
+    packed = torch.empty(sol_packed_weight_bytes(cd, dt), dtype=torch.uint8, device=w_oihw.device)
+    _check(lib().sol_pack_conv_weights(C.byref(cd), C.c_int(dt), _ptr(w_oihw), _ptr(packed), _stream(stream)))
+    return packed
+
+
+def sol_unpack_conv_weights(cd, dt, packed, stream=None):
+    w = torch.empty((cd.cout, cd.cin, cd.kh, cd.kw), dtype=torch.float32, device=packed.device)
+    _check(lib().sol_unpack_conv_weights(C.byref(cd), C.c_int(dt), _ptr(packed), _ptr(w), _stream(stream)))
+    return w
+
+
+def sol_fold_bn(c, gamma, beta, mean, var, bias, eps, device="cuda:0", stream=None):
+    scale = torch.empty(c, dtype=torch.float32, device=device)
+    shift = torch.empty(c, dtype=torch.float32, device=device)
+    _check(lib().sol_fold_bn(C.c_int(c), _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(var), _ptr(bias),
+                             C.c_float(eps), _ptr(scale), _ptr(shift), _stream(stream)))
+    return scale, shift
+
+
+def sol_conv2d_fused(x, cd, w_packed, scale=None, shift=None, residual=None, act=ACT_NONE, pool=None,
+                     want_argmax=False, want_prepool=False, stream=None):
+    """x: NHWC device tensor.  Returns (y, argmax or None, prepool or None)."""
+    n, h, w, _ = x.shape
+    ho, wo = sol_out_size(h, cd.kh, cd.sh, cd.ph), sol_out_size(w, cd.kw, cd.sw, cd.pw)
+    hy, wy = ho, wo
+    pd = pool if isinstance(pool, PoolDesc) or pool is None else pool_desc(pool)
+    if pd is not None and pd.kind != POOL_NONE:
+        hy, wy = sol_out_size(ho, pd.kh, pd.sh, pd.ph), sol_out_size(wo, pd.kw, pd.sw, pd.pw)
+    y = torch.empty((n, max(hy, 0), max(wy, 0), cd.cout), dtype=x.dtype, device=x.device)
+    arg = torch.empty(y.shape, dtype=torch.int32, device=x.device) if want_argmax else None
+    pre = torch.empty((n, max(ho, 0), max(wo, 0), cd.cout), dtype=x.dtype, device=x.device) if want_prepool else None
+    xd = tensor_desc(x)
+    _check(lib().sol_conv2d_fused(C.byref(xd), _ptr(x), C.byref(cd), _ptr(w_packed), _ptr(scale), _ptr(shift),
+                                  _ptr(residual), C.c_int(act), C.byref(pd) if pd is not None else None,
+                                  _ptr(y), _ptr(arg), _ptr(pre), _stream(stream)))
+    return y, arg, pre
+
+
+def sol_linear(x, w_packed, bias, out_f, act=ACT_NONE, stream=None):
+    m, in_f = x.shape
+    y = torch.empty((m, out_f), dtype=x.dtype, device=x.device)
+    _check(lib().sol_linear(C.c_int(m), C.c_int(in_f), C.c_int(out_f), C.c_int(dtype_of(x)), _ptr(x), _ptr(w_packed),
+                            _ptr(bias), C.c_int(act), _ptr(y), _stream(stream)))
+    return y
+
+
+def sol_pool(x, pd, want_argmax=False, stream=None):
+    pd = pd if isinstance(pd, PoolDesc) else pool_desc(pd)
+    n, h, w, c = x.shape
+    ho, wo = sol_out_size(h, pd.kh, pd.sh, pd.ph), sol_out_size(w, pd.kw, pd.sw, pd.pw)
+    y = torch.empty((n, max(ho, 0), max(wo, 0), c), dtype=x.dtype, device=x.device)
+    arg = torch.empty(y.shape, dtype=torch.int32, device=x.device) if want_argmax else None
+    xd = tensor_desc(x)
+    _check(lib().sol_pool(C.byref(xd), _ptr(x), C.byref(pd), _ptr(y), _ptr(arg), _stream(stream)))
+    return y, arg
+
+
+def sol_global_avgpool(x, stream=None):
+    n, h, w, c = x.shape
+    y = torch.empty((n, 1, 1, c), dtype=x.dtype, device=x.device)
+    xd = tensor_desc(x)
+    _check(lib().sol_global_avgpool(C.byref(xd), _ptr(x), _ptr(y), _stream(stream)))
+    return y
+
+
+def sol_debug_set_conv_tile(tile):
+    lib().sol_debug_set_conv_tile(C.c_int(tile))
+
+
+# ---- networks -----------------------------------------------------------------------------------------
+def make_layer_array(layers):
+    arr = (Layer * len(layers))()
+    for i, l in enumerate(layers):
+        a = arr[i]
+        a.src, a.res = l.get("src", -1), l.get("res", -1)
+        a.act = ACT_RELU if l.get("act") == "relu" else ACT_NONE
+        a.pool = PoolDesc(POOL_NONE, 0, 0, 0, 0, 0, 0, 0)
+        if l["kind"] == "conv":
+            a.kind = LAYER_CONV
+            a.conv = ConvDesc(l["cout"], 0, l["kh"], l["kw"], l["sh"], l["sw"], l["ph"], l["pw"])
+            a.has_bn = int(l["bn"])
+            if l.get("pool"):
+                a.pool = pool_desc(l["pool"])
+        elif l["kind"] == "pool":
+            a.kind = LAYER_POOL
+            a.pool = pool_desc(l["pool"])
+        elif l["kind"] == "gap":
+            a.kind = LAYER_GAP
+        elif l["kind"] == "linear":
+            a.kind = LAYER_LINEAR
+            a.out_features = l["out"]
+        else:
+            raise ValueError(l["kind"])
+    return arr
+
+
+class Network:
+    """sol_network_* wrapper: plan once (create + parameter packing), then forward many times."""
+
+    def __init__(self, layers, in_shape_nchw, dt, device="cuda:0", flags=0):
+        self.layers, self.dt, self.device = layers, dt, device
+        n, c, h, w = in_shape_nchw
+        self.in_desc = TensorDesc(n, h, w, c, dt)
+        self._h = C.c_void_p(0)
+        arr = make_layer_array(layers)
+        _check(lib().sol_network_create(arr, C.c_int(len(layers)), C.byref(self.in_desc), C.c_int(flags), C.byref(self._h)))
+        self.param_buf = torch.empty(max(lib().sol_network_param_bytes(self._h), 16), dtype=torch.uint8, device=device)
+        self.workspace = torch.empty(max(lib().sol_network_workspace_bytes(self._h), 16), dtype=torch.uint8, device=device)
+        _check(lib().sol_network_bind_params(self._h, _ptr(self.param_buf), C.c_size_t(self.param_buf.numel())))
+        od = self.output_desc(-1)
+        self.y = torch.empty((od.n, od.h, od.w, od.c), dtype=torch_dtype(dt), device=device)
+
+    def output_desc(self, layer=-1):
+        d = TensorDesc()
+        _check(lib().sol_network_output_desc(self._h, C.c_int(layer), C.byref(d)))
+        return d
+
+    def set_params(self, params, stream=None):
+        """params: per-layer dicts of numpy fp32 arrays in framework layout (w OIHW / [out][in])."""
+        for i, (l, p) in enumerate(zip(self.layers, params)):
+            if l["kind"] not in ("conv", "linear"):
+                continue
+            w = dev_f32(p["w"], self.device)
+            bn = l["kind"] == "conv" and l["bn"]
+            g, b, m, v = (dev_f32(p[k], self.device) for k in ("gamma", "beta", "mean", "var")) if bn else (None,) * 4
+            bias = dev_f32(p.get("bias"), self.device)
+            _check(lib().sol_network_set_params(self._h, C.c_int(i), _ptr(w), _ptr(g), _ptr(b), _ptr(m), _ptr(v),
+                                                _ptr(bias), C.c_float(p.get("eps", 1e-5)), _stream(stream)))
+        torch.cuda.synchronize()
+
+    def forward(self, x, stream=None):
+        """x: NHWC device tensor; returns the (reused) output tensor of the last layer."""
+        _check(lib().sol_network_forward(self._h, _ptr(x), _ptr(self.y), _ptr(self.workspace),
+                                         C.c_size_t(self.workspace.numel()), _stream(stream)))
+        return self.y
+
+    def run_layer(self, layer, x, stream=None):
+        """Runs one layer on whatever its producers left in the workspace (profiling aid)."""
+        _check(lib().sol_network_run_layer(self._h, C.c_int(layer), _ptr(x), _ptr(self.y), _ptr(self.workspace),
+                                           C.c_size_t(self.workspace.numel()), _stream(stream)))
+
+    def layer_output(self, layer):
+        """Output of an inner layer after a forward (network must keep its activations)."""
+        d = self.output_desc(layer)
+        p = C.c_void_p(0)
+        _check(lib().sol_network_layer_output(self._h, C.c_int(layer), _ptr(self.workspace), C.byref(p)))
+        off = p.value - self.workspace.data_ptr()
+        nbytes = d.n * d.h * d.w * d.c * (2 if self.dt == BF16 else 4)
+        return self.workspace[off:off + nbytes].view(torch_dtype(self.dt)).view(d.n, d.h, d.w, d.c)
+
+    def __del__(self):
+        try:
+            if self._h:
+                lib().sol_network_destroy(self._h)
+        except Exception:
+            pass

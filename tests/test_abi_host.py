@@ -1,0 +1,113 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares, and its
+host-side logic (argument validation, shape inference, buffer planning) behaves -- no kernel runs."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2003_10688_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def sol():
+    from paper_2003_10688_amd import sol as s
+
+    if not os.path.exists(s.LIB_PATH):
+        from paper_2003_10688_amd import build
+
+        build.build(verbose=False)
+    s.lib()
+    return s
+
+
+def test_exports_every_declared_symbol(sol):
+    hdr = open(os.path.join(ROOT, "include", "sol.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(sol_[a-z0-9_]+)\s*\(", hdr))
+    assert {"sol_conv2d_fused", "sol_linear", "sol_pool", "sol_network_forward", "sol_network_create"} <= names
+    for n in sorted(names):
+        assert hasattr(sol.lib(), n), f"{n} declared in include/sol.h but not exported"
+    assert b"gfx950" in sol.lib().sol_version()
+
+
+def test_out_size_and_packed_bytes(sol):
+    assert sol.sol_out_size(224, 7, 2, 3) == 112 and sol.sol_out_size(112, 3, 2, 1) == 56
+    assert sol.sol_out_size(5, 2, 2, 0) == 2 and sol.sol_out_size(7, 3, 1, 1) == 7
+    assert sol.sol_packed_weight_bytes(sol.ConvDesc(64, 3, 7, 7, 2, 2, 3, 3), sol.BF16) == 64 * 192 * 2   # 147 -> 192
+    assert sol.sol_packed_weight_bytes(sol.ConvDesc(64, 3, 7, 7, 2, 2, 3, 3), sol.F32) == 64 * 160 * 4    # 147 -> 160
+    assert sol.sol_packed_weight_bytes(sol.ConvDesc(256, 64, 1, 1, 1, 1, 0, 0), sol.BF16) == 256 * 64 * 2
+
+
+def _status(sol, fn, *args):
+    return fn(*args)
+
+
+def test_validation_rejects_before_launch(sol):
+    L = sol.lib()
+    xd = sol.TensorDesc(1, 8, 8, 16, sol.F32)
+    cd = sol.ConvDesc(8, 16, 3, 3, 1, 1, 1, 1)
+    null = C.c_void_p(0)
+    fake = C.c_void_p(0x1000)          # never dereferenced: validation fails first
+    call = lambda xd_, x, cd_, w, y, pool=None: L.sol_conv2d_fused(  # noqa: E731
+        C.byref(xd_), x, C.byref(cd_), w, null, null, null, 0, C.byref(pool) if pool else None, y, null, null, null)
+    assert call(xd, null, cd, fake, fake) == 1                                            # NULL x
+    assert b"NULL" in L.sol_last_error()
+    assert call(xd, fake, sol.ConvDesc(8, 4, 3, 3, 1, 1, 1, 1), fake, fake) == 2           # cin mismatch
+    assert call(xd, fake, sol.ConvDesc(8, 16, 3, 3, 0, 1, 1, 1), fake, fake) == 2          # zero stride
+    assert call(sol.TensorDesc(1, 8, 8, 16, 7), fake, cd, fake, fake) == 3                 # dtype
+    assert call(xd, C.c_void_p(0x1004), cd, fake, fake) == 4                               # alignment
+    assert call(xd, fake, cd, fake, fake, sol.PoolDesc(sol.POOL_MAX, 3, 3, 2, 2, 1, 1, 1)) == 6   # unfusable pool
+    assert call(sol.TensorDesc(1, 2, 2, 16, 0), fake, sol.ConvDesc(8, 16, 5, 5, 1, 1, 0, 0), fake, fake) == 2  # filter > input
+    big = sol.TensorDesc(65536, 512, 512, 16, sol.BF16)                                    # >= 2^31 elements
+    assert call(big, fake, cd, fake, fake) == 6
+    assert L.sol_pool(C.byref(xd), fake, C.byref(sol.PoolDesc(sol.POOL_MAX, 2, 2, 2, 2, 2, 2, 1)), fake, null, null) == 2
+    assert L.sol_linear(4, 0, 3, 0, fake, fake, null, 0, fake, null) == 2
+
+
+def _create(sol, layers, shape, dt, flags=0):
+    h = C.c_void_p(0)
+    n, c, hh, ww = shape
+    st = sol.lib().sol_network_create(sol.make_layer_array(layers), len(layers), C.byref(sol.TensorDesc(n, hh, ww, c, dt)),
+                                      flags, C.byref(h))
+    return st, h
+
+
+def test_planner_shapes_and_buffers(sol):
+    L = sol.lib()
+    wk = wl.config(3)
+    st, h = _create(sol, wk.layers, wk.in_shape, sol.BF16)
+    assert st == 0
+    d = sol.TensorDesc()
+    assert L.sol_network_output_desc(h, -1, C.byref(d)) == 0 and (d.n, d.h, d.w, d.c) == (64, 1, 1, 1000)
+    assert L.sol_network_output_desc(h, 0, C.byref(d)) == 0 and (d.n, d.h, d.w, d.c) == (64, 112, 112, 64)
+    assert L.sol_network_output_desc(h, 1, C.byref(d)) == 0 and (d.n, d.h, d.w, d.c) == (64, 56, 56, 64)
+    assert L.sol_network_output_desc(h, len(wk.layers) - 3, C.byref(d)) == 0 and (d.n, d.h, d.w, d.c) == (64, 7, 7, 2048)
+    assert L.sol_network_num_layers(h) == len(wk.layers)
+    ws = L.sol_network_workspace_bytes(h)
+    biggest = 64 * 56 * 56 * 256 * 2                      # largest live activation
+    assert 2 * biggest <= ws <= 5 * biggest               # buffers are reused, not one per layer
+    pb = L.sol_network_param_bytes(h)
+    assert 25.5e6 * 2 <= pb <= 25.5e6 * 2 * 1.1           # ~25.5 M bf16 weights plus scale/shift
+    st2, h2 = _create(sol, wk.layers, wk.in_shape, sol.BF16, sol.NET_KEEP_ACTIVATIONS)
+    assert st2 == 0 and L.sol_network_workspace_bytes(h2) > 4 * ws
+    L.sol_network_destroy(h)
+    L.sol_network_destroy(h2)
+
+
+def test_planner_rejects_bad_graphs(sol):
+    bad_res = [wl.conv(8, 3), wl.conv(16, 3, res=0)]                       # residual channel mismatch
+    assert _create(sol, bad_res, (1, 3, 8, 8), sol.F32)[0] == 2
+    fwd_ref = [wl.conv(8, 3, src=1), wl.conv(8, 3)]                        # src must be an earlier layer
+    assert _create(sol, fwd_ref, (1, 3, 8, 8), sol.F32)[0] == 2
+    lin = [wl.conv(8, 3), wl.linear(4)]                                    # linear needs [n,1,1,c]
+    assert _create(sol, lin, (1, 3, 8, 8), sol.F32)[0] == 6
+    assert _create(sol, [wl.conv(8, 9, p=0)], (1, 3, 4, 4), sol.F32)[0] == 2   # filter larger than input
+    st, h = _create(sol, wl.small_cnn_layers(), (64, 3, 32, 32), sol.F32)
+    assert st == 0
+    # forward without bound parameters / workspace is refused, nothing is launched
+    fake = C.c_void_p(0x1000)
+    assert sol.lib().sol_network_forward(h, fake, fake, fake, C.c_size_t(1 << 30), None) == 5
+    sol.lib().sol_network_destroy(h)

@@ -1,0 +1,352 @@
+"""Parity of the HIP library (through its C ABI) against the CPU checker, element by element on the
+same seeded inputs.  Tolerances: max relative error 1e-4 for fp32, 2e-2 for bf16 storage with fp32
+accumulate; integer results (pooling argmax) bit-exact.
+
+Relative error of a tensor: max_i |g_i - r_i| / max(|r_i|, rms(r)) -- the rms floor keeps the exact
+zeros a ReLU produces from turning rounding noise into infinite relative error."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+from paper_2003_10688_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def sol():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2003_10688_amd import sol as s
+
+    s.lib()
+    return s
+
+
+def rel_err(g, r):
+    g, r = np.asarray(g, np.float64), np.asarray(r, np.float64)
+    assert g.shape == r.shape, (g.shape, r.shape)
+    if r.size == 0:
+        return 0.0
+    floor = max(np.sqrt(np.mean(r * r)), 1e-30)
+    return float(np.max(np.abs(g - r) / np.maximum(np.abs(r), floor)))
+
+
+def _dt(sol, name):
+    return sol.BF16 if name == "bf16" else sol.F32
+
+
+def _grid(a, name):
+    return wl.to_bf16_grid(a) if name == "bf16" else np.asarray(a, np.float32)
+
+
+def make_block(sol, rng, dt, N, C, H, W, K, k, s, p, bn=True, act="relu", pool=None, res=False, bias_std=0.3):
+    l = wl.conv(K, k, s, p, bn=bn, act=act, pool=pool)
+    x = _grid(rng.standard_normal((N, C, H, W)), dt)
+    prm = {"w": _grid(rng.standard_normal((K, C, k, k)) * np.sqrt(2.0 / (C * k * k)), dt),
+           "bias": (rng.standard_normal(K) * bias_std).astype(np.float32)}
+    if bn:
+        prm.update(gamma=rng.uniform(0.5, 1.5, K).astype(np.float32), beta=rng.uniform(-0.1, 0.1, K).astype(np.float32),
+                   mean=(rng.standard_normal(K) * 0.1).astype(np.float32), var=rng.uniform(0.5, 1.5, K).astype(np.float32))
+    Ho, Wo = orc.out_size(H, k, s, p), orc.out_size(W, k, s, p)
+    r = _grid(rng.standard_normal((N, K, Ho, Wo)), dt) if res else None
+    return l, x, prm, r
+
+
+def run_block(sol, dt, l, x, prm, r, want_argmax=False, want_prepool=False):
+    d = _dt(sol, dt)
+    cd = sol.ConvDesc(l["cout"], x.shape[1], l["kh"], l["kw"], l["sh"], l["sw"], l["ph"], l["pw"])
+    wp = sol.sol_pack_conv_weights(cd, d, sol.dev_f32(prm["w"]))
+    bn = l["bn"]
+    scale, shift = sol.sol_fold_bn(l["cout"], *(sol.dev_f32(prm[k]) if bn else None for k in ("gamma", "beta", "mean", "var")),
+                                   sol.dev_f32(prm["bias"]), 1e-5)
+    y, arg, pre = sol.sol_conv2d_fused(sol.to_device_nhwc(x, d), cd, wp, scale, shift,
+                                       sol.to_device_nhwc(r, d) if r is not None else None,
+                                       sol.ACT_RELU if l["act"] == "relu" else sol.ACT_NONE, l["pool"],
+                                       want_argmax, want_prepool)
+    torch.cuda.synchronize()
+    return (sol.to_host_nchw(y), sol.to_host_nchw(arg) if arg is not None else None,
+            sol.to_host_nchw(pre) if pre is not None else None)
+
+
+CONV_CASES = [
+    # N, C, H, W, K, k, s, p, res      several tiles + ragged tails in pixels and channels
+    (2, 64, 19, 17, 96, 3, 1, 1, True),
+    (3, 128, 14, 14, 80, 1, 1, 0, True),
+    (2, 64, 23, 23, 64, 3, 2, 1, False),
+    (1, 256, 9, 9, 520, 1, 2, 0, False),
+    (2, 3, 37, 35, 64, 7, 2, 3, False),     # stem-like: Cin = 3 -> element gather path
+    (5, 3, 16, 16, 16, 3, 1, 1, False),
+    (1, 24, 11, 11, 40, 3, 1, 1, True),     # Cin not a multiple of the 128-byte chunk -> gather path
+    (2, 32, 12, 12, 32, 5, 1, 2, False),
+    (1, 64, 1, 1, 10, 1, 1, 0, False),      # degenerate 1x1 image, Cout not a multiple of 4
+    (130, 64, 2, 2, 64, 3, 1, 1, True),     # many tiny images
+]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_fused_matches_oracle(sol, dt, case):
+    N, C, H, W, K, k, s, p, res = case
+    rng = np.random.default_rng(hash(case) % (2 ** 31))
+    l, x, prm, r = make_block(sol, rng, dt, N, C, H, W, K, k, s, p, res=res)
+    want, _, _ = orc.fused_conv(x, prm, l, r, bf16=(dt == "bf16"))
+    got, _, _ = run_block(sol, dt, l, x, prm, r)
+    assert rel_err(got, want) <= TOL[dt]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_conv_no_bn_no_act_plain(sol, dt):
+    rng = np.random.default_rng(5)
+    l, x, prm, r = make_block(sol, rng, dt, 2, 64, 10, 10, 64, 3, 1, 1, bn=False, act="none")
+    want, _, _ = orc.fused_conv(x, prm, l, None, bf16=(dt == "bf16"))
+    got, _, _ = run_block(sol, dt, l, x, prm, None)
+    assert rel_err(got, want) <= TOL[dt]
+    assert (got < 0).any()                       # really no ReLU
+
+
+@pytest.mark.parametrize("tile", range(1, 9))
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_every_conv_tile(sol, dt, tile):
+    rng = np.random.default_rng(100 + tile)
+    l, x, prm, r = make_block(sol, rng, dt, 2, 64, 21, 20, 136, 3, 1, 1, res=True)
+    want, _, _ = orc.fused_conv(x, prm, l, r, bf16=(dt == "bf16"))
+    sol.sol_debug_set_conv_tile(tile)
+    try:
+        got, _, _ = run_block(sol, dt, l, x, prm, r)
+    finally:
+        sol.sol_debug_set_conv_tile(0)
+    assert rel_err(got, want) <= TOL[dt]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", ["max", "avg"])
+@pytest.mark.parametrize("shape", [(2, 3, 32, 32, 16), (3, 64, 15, 13, 72), (1, 32, 8, 8, 64)])
+def test_fused_pool_values(sol, dt, kind, shape):
+    """Random data: pooled values within tolerance; every argmax points into its own window at an
+    element whose pre-pool value equals the window maximum up to the tolerance."""
+    N, C, H, W, K = shape
+    rng = np.random.default_rng(11)
+    l, x, prm, _ = make_block(sol, rng, dt, N, C, H, W, K, 3, 1, 1, pool=wl.pool_desc(kind, 2, 2, 0))
+    want, warg, wpre = orc.fused_conv(x, prm, l, None, bf16=(dt == "bf16"), want_prepool=True)
+    got, garg, gpre = run_block(sol, dt, l, x, prm, None, want_argmax=(kind == "max"), want_prepool=True)
+    assert got.shape == (N, K, H // 2, W // 2)
+    assert rel_err(got, want) <= TOL[dt]
+    wpre_st = orc.round_bf16(wpre) if dt == "bf16" else wpre
+    assert rel_err(gpre[:, :, :H // 2 * 2, :W // 2 * 2], wpre_st[:, :, :H // 2 * 2, :W // 2 * 2]) <= TOL[dt]
+    if kind == "max":
+        ih, iw = garg // W, garg % W
+        pp, qq = np.meshgrid(np.arange(H // 2), np.arange(W // 2), indexing="ij")
+        assert np.all((ih // 2 == pp) & (iw // 2 == qq))
+        picked = np.take_along_axis(wpre.reshape(N, K, -1), garg.reshape(N, K, -1).astype(np.int64), 2).reshape(want.shape)
+        wmax = orc.maxpool(wpre, (2, 2), (2, 2), (0, 0))[0]
+        floor = np.sqrt(np.mean(wmax * wmax))
+        assert np.max(np.abs(picked - wmax) / np.maximum(np.abs(wmax), floor)) <= TOL[dt]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_fused_pool_argmax_bit_exact(sol, dt):
+    """Small-integer inputs, weights and affine map: every intermediate is exact in fp32, so the HIP
+    path and the checker see identical pre-pool values, full of exact ties (ReLU zeros and integer
+    collisions).  Values and argmax must then agree bit for bit (first maximum in window order wins)."""
+    rng = np.random.default_rng(3)
+    N, C, H, W, K = 2, 32, 14, 18, 48
+    l = wl.conv(K, 3, 1, 1, bn=False, act="relu", pool=wl.pool_desc("max", 2, 2, 0))
+    x = rng.integers(-2, 3, (N, C, H, W)).astype(np.float32)
+    prm = {"w": rng.integers(-1, 2, (K, C, 3, 3)).astype(np.float32), "bias": rng.integers(-3, 4, K).astype(np.float32)}
+    want, warg, wpre = orc.fused_conv(x, prm, l, None, bf16=False, want_prepool=True)
+    assert np.abs(wpre).max() <= 256 and (wpre == 0).mean() > 0.3          # exact in bf16 too; many ties
+    got, garg, gpre = run_block(sol, dt, l, x, prm, None, want_argmax=True, want_prepool=True)
+    assert np.array_equal(gpre, wpre)
+    assert np.array_equal(got, want)
+    assert np.array_equal(garg, warg)
+
+
+POOL_CASES = [("max", 3, 2, 1), ("max", 2, 2, 0), ("max", 3, 1, 1), ("avg", 3, 2, 1), ("avg", 2, 2, 0), ("max", 5, 3, 2)]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("cfg", POOL_CASES)
+@pytest.mark.parametrize("shape", [(2, 64, 29, 31), (1, 20, 9, 9), (3, 7, 6, 5)])
+def test_pool_matches_oracle(sol, dt, cfg, shape):
+    kind, k, s, p = cfg
+    rng = np.random.default_rng(17)
+    x = _grid(np.round(rng.standard_normal(shape) * 4) / 4, dt)            # coarse grid: many exact ties
+    d = _dt(sol, dt)
+    for cp in ((1, 0) if kind == "avg" else (1,)):
+        pd = wl.pool_desc(kind, k, s, p, cp)
+        y, arg = sol.sol_pool(sol.to_device_nhwc(x, d), pd, want_argmax=(kind == "max"))
+        torch.cuda.synchronize()
+        want, warg = orc.pool(x, pd)
+        if kind == "max":
+            assert np.array_equal(sol.to_host_nchw(y), want)               # selection only: exact
+            assert np.array_equal(sol.to_host_nchw(arg), warg)             # integer result: bit-exact
+        else:
+            want = orc.round_bf16(want) if dt == "bf16" else want
+            assert rel_err(sol.to_host_nchw(y), want) <= TOL[dt]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(64, 2048, 7, 7), (3, 64, 8, 8), (2, 10, 5, 3), (1, 8, 1, 1)])
+def test_global_avgpool(sol, dt, shape):
+    rng = np.random.default_rng(23)
+    x = _grid(rng.standard_normal(shape) + 0.5, dt)
+    y = sol.sol_global_avgpool(sol.to_device_nhwc(x, _dt(sol, dt)))
+    torch.cuda.synchronize()
+    want = orc.gap(x)
+    want = orc.round_bf16(want) if dt == "bf16" else want
+    assert rel_err(sol.to_host_nchw(y)[:, :, 0, 0], want) <= TOL[dt]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(64, 2048, 1000), (64, 64, 10), (5, 100, 33), (1, 7, 3)])
+def test_linear(sol, dt, shape):
+    M, I, O = shape
+    rng = np.random.default_rng(29)
+    d = _dt(sol, dt)
+    x = _grid(rng.standard_normal((M, I)), dt)
+    w = _grid(rng.standard_normal((O, I)) * np.sqrt(2.0 / I), dt)
+    b = rng.standard_normal(O).astype(np.float32)
+    cd = sol.ConvDesc(O, I, 1, 1, 1, 1, 0, 0)
+    wp = sol.sol_pack_conv_weights(cd, d, sol.dev_f32(w.reshape(O, I, 1, 1)))
+    for act in ("none", "relu"):
+        y = sol.sol_linear(sol.to_device_nhwc(x, d), wp, sol.dev_f32(b), O, sol.ACT_RELU if act == "relu" else sol.ACT_NONE)
+        torch.cuda.synchronize()
+        want = orc.linear(x, w, b)
+        want = orc.relu(want) if act == "relu" else want
+        want = orc.round_bf16(want) if dt == "bf16" else want
+        assert rel_err(sol.to_host_nchw(y), want) <= TOL[dt]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_pack_unpack_roundtrip(sol, dt):
+    rng = np.random.default_rng(31)
+    for (K, C, R, S) in [(16, 3, 3, 3), (64, 64, 3, 3), (10, 7, 1, 1), (64, 3, 7, 7)]:
+        w = _grid(rng.standard_normal((K, C, R, S)), dt)
+        cd = sol.ConvDesc(K, C, R, S, 1, 1, 0, 0)
+        wp = sol.sol_pack_conv_weights(cd, _dt(sol, dt), sol.dev_f32(w))
+        back = sol.sol_unpack_conv_weights(cd, _dt(sol, dt), wp)
+        torch.cuda.synchronize()
+        assert np.array_equal(back.cpu().numpy(), w)
+
+
+def test_empty_batch_and_errors(sol):
+    d = sol.F32
+    cd = sol.ConvDesc(8, 4, 3, 3, 1, 1, 1, 1)
+    wp = sol.sol_pack_conv_weights(cd, d, sol.dev_f32(np.zeros((8, 4, 3, 3), np.float32)))
+    x0 = torch.empty((0, 5, 5, 4), device="cuda:0")
+    y, _, _ = sol.sol_conv2d_fused(x0, cd, wp)
+    assert y.shape == (0, 5, 5, 8)
+    y, _ = sol.sol_pool(x0, wl.pool_desc("max", 2, 2, 0))
+    assert y.shape == (0, 2, 2, 4)
+    x = torch.zeros((1, 5, 5, 4), device="cuda:0")
+    with pytest.raises(sol.SolError) as e:
+        sol.sol_conv2d_fused(x, cd, wp, pool=wl.pool_desc("max", 3, 2, 1))
+    assert e.value.status == 6
+    with pytest.raises(sol.SolError) as e:
+        sol.sol_conv2d_fused(torch.zeros((1, 5, 5, 3), device="cuda:0"), cd, wp)
+    assert e.value.status == 2
+    with pytest.raises(sol.SolError) as e:                                   # misaligned pointer
+        sol.sol_conv2d_fused(torch.zeros(101, device="cuda:0")[1:].view(1, 5, 5, 4), cd, wp)
+    assert e.value.status == 4
+
+
+# ---------------------------------------------------------------------------------- whole networks
+def run_network(sol, wk, keep=True):
+    d = _dt(sol, wk.dtype)
+    net = sol.Network(wk.layers, wk.in_shape, d, flags=sol.NET_KEEP_ACTIVATIONS if keep else 0)
+    net.set_params(wk.params)
+    y = net.forward(sol.to_device_nhwc(wk.x, d))
+    torch.cuda.synchronize()
+    return net, sol.to_host_nchw(y)
+
+
+@pytest.mark.parametrize("cfg,batch,hw", [(0, None, None), (1, None, None), (1, 5, 18), (2, 2, 64), (3, 2, 64), (3, 1, 224)])
+def test_network_forward_every_layer(sol, cfg, batch, hw):
+    """End to end on the same seeded tensors; every layer's stored output is compared."""
+    wk = wl.config(cfg, batch=batch, hw=hw)
+    outs, _ = orc.network_forward(wk.layers, wk.params, wk.x, bf16=wk.bf16, return_all=True)
+    net, y = run_network(sol, wk)
+    errs = []
+    for i in range(len(wk.layers) - 1):
+        errs.append(rel_err(sol.to_host_nchw(net.layer_output(i)).reshape(outs[i].shape), outs[i]))
+    errs.append(rel_err(y.reshape(outs[-1].shape), outs[-1]))
+    print(f"cfg{cfg} per-layer rel err: max {max(errs):.3e} last {errs[-1]:.3e}")
+    assert max(errs) <= TOL[wk.dtype], errs
+    # the buffer-reusing plan gives the same final result, bit for bit
+    _, y2 = run_network(sol, wk, keep=False)
+    assert np.array_equal(y, y2)
+
+
+def test_network_deterministic(sol):
+    wk = wl.config(2, batch=2, hw=64)
+    _, y1 = run_network(sol, wk, keep=False)
+    _, y2 = run_network(sol, wk, keep=False)
+    assert np.array_equal(y1, y2)
+
+
+def _distinct_conv_shapes(wk):
+    """(layer index, input shape NCHW) of one representative per distinct convolution geometry."""
+    n, c, h, w = wk.in_shape
+    shapes, seen, out = [], {}, []
+    for i, l in enumerate(wk.layers):
+        s = l.get("src", -1)
+        ins = (n, c, h, w) if (i == 0 and s == -1) else shapes[i - 1 if s == -1 else s]
+        if l["kind"] == "conv":
+            o = (ins[0], l["cout"], orc.out_size(ins[2], l["kh"], l["sh"], l["ph"]), orc.out_size(ins[3], l["kw"], l["sw"], l["pw"]))
+            key = (ins, l["cout"], l["kh"], l["sh"], l["res"] >= 0, l["act"])
+            if key not in seen:
+                seen[key] = i
+                out.append((i, ins))
+        elif l["kind"] == "pool":
+            pd = l["pool"]
+            o = (ins[0], ins[1], orc.out_size(ins[2], pd["kh"], pd["sh"], pd["ph"]), orc.out_size(ins[3], pd["kw"], pd["sw"], pd["pw"]))
+        elif l["kind"] == "gap":
+            o = (ins[0], ins[1], 1, 1)
+        else:
+            o = (ins[0], l["out"], 1, 1)
+        shapes.append(o)
+    return out
+
+
+@pytest.mark.parametrize("cfg", [3, 2])
+def test_full_size_layers_sampled(sol, cfg):
+    """Every distinct convolution geometry of the ResNet-shaped configs at the full benchmark batch,
+    in the automatically planned launch configuration, on seeded synthetic inputs; 256 sampled outputs
+    per layer are recomputed one by one by the checker."""
+    wk = wl.config(cfg)
+    d = _dt(sol, wk.dtype)
+    rng = np.random.default_rng(wk.seed)
+    worst = 0.0
+    for i, ins in _distinct_conv_shapes(wk):
+        l, prm = wk.layers[i], wk.params[i]
+        x = wl.to_bf16_grid(rng.standard_normal(ins, dtype=np.float32))
+        K = l["cout"]
+        Ho, Wo = orc.out_size(ins[2], l["kh"], l["sh"], l["ph"]), orc.out_size(ins[3], l["kw"], l["sw"], l["pw"])
+        r = wl.to_bf16_grid(rng.standard_normal((ins[0], K, Ho, Wo), dtype=np.float32)) if l["res"] >= 0 else None
+        got, _, _ = run_block(sol, wk.dtype, dict(l, pool=None), x, prm, r)
+        coords = np.stack([rng.integers(0, s, 256) for s in (ins[0], K, Ho, Wo)], 1)
+        coords[:8] = [[0, 0, 0, 0], [ins[0] - 1, K - 1, Ho - 1, Wo - 1], [0, K - 1, 0, Wo - 1], [ins[0] - 1, 0, Ho - 1, 0],
+                      [0, 0, Ho - 1, Wo - 1], [ins[0] - 1, K - 1, 0, 0], [ins[0] // 2, K // 2, Ho // 2, Wo // 2], [0, 1, 0, 1]]
+        want = orc.fused_conv_points(x, prm, dict(l, pool=None), coords, r, bf16=True)
+        g = got[tuple(coords.T)]
+        floor = np.sqrt(np.mean(want * want)) + 1e-30
+        err = float(np.max(np.abs(g - want) / np.maximum(np.abs(want), floor)))
+        worst = max(worst, err)
+        assert err <= TOL["bf16"], (i, ins, l, err)
+        del x, got, r
+    print(f"cfg{cfg} full-size sampled layers: worst rel err {worst:.3e}")
+
+
+def test_full_size_stem_pool_and_gap(sol):
+    wk = wl.config(3)
+    rng = np.random.default_rng(1)
+    x = wl.to_bf16_grid(rng.standard_normal((64, 64, 112, 112), dtype=np.float32))
+    y, arg = sol.sol_pool(sol.to_device_nhwc(x, sol.BF16), wl.pool_desc("max", 3, 2, 1), want_argmax=True)
+    torch.cuda.synchronize()
+    y, arg = sol.to_host_nchw(y), sol.to_host_nchw(arg)
+    for n in (0, 37, 63):                                                   # whole images, exact
+        want, warg = orc.maxpool(x[n:n + 1], (3, 3), (2, 2), (1, 1))
+        assert np.array_equal(y[n:n + 1], want) and np.array_equal(arg[n:n + 1], warg)
