@@ -46,13 +46,14 @@ typedef uint16_t bf16_t;   // raw bf16 bits
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
-// fp32 -> bf16, round to nearest, ties to even; NaN stays NaN
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (bf16_t)(u >> 16);
+// two fp32 -> packed bf16 pair (low half = lo), round to nearest, ties to even: one v_cvt_pk_bf16_f32
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xffffu); }
 
 template <typename T> struct Elem;
 template <> struct Elem<float> {
@@ -93,6 +94,18 @@ struct PoolArgs {
     int kind, count_pad;
 };
 
+// Convolution tile ids (pixels x channels per workgroup); also accepted as a debugging override.
+// T_*: register-staged kernel (conv_igemm.hip).  D_*: LDS-DMA ring kernel (conv_dma.hip), suffix =
+// row bytes per stage x ring stages.
+enum {
+    T_AUTO = 0, T_256x128 = 1, T_128x128 = 2, T_128x64 = 3, T_256x64 = 4, T_64x64 = 5, T_128x32 = 6, T_128x256 = 7,
+    T_64x128 = 8,
+    D_128x128_64x4 = 11, D_128x128_64x3 = 12, D_256x128_64x3 = 13, D_128x64_64x4 = 14, D_64x64_64x4 = 15,
+    D_128x256_64x3 = 16, D_256x64_64x3 = 17, D_64x128_64x4 = 18,
+    D_128x128_128x2 = 21, D_128x128_128x3 = 22, D_128x64_128x3 = 23, D_64x64_128x3 = 24
+};
+int dma_tile_row_bytes(int tile);
+sol_status launch_conv_dma(const ConvArgs &a, int dt, int tile, hipStream_t st);
 sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t st);
 sol_status launch_pool(const PoolArgs &a, int dt, hipStream_t st);
 sol_status launch_gap(const void *x, void *y, int N, int HW, int C, int dt, hipStream_t st);

@@ -1,0 +1,210 @@
+// Device-side pieces shared by the convolution kernels (internal): MFMA wrappers, the GEMM-row ->
+// pixel map, 8-channel vector access, and the fused epilogue.
+#pragma once
+#include <type_traits>
+
+#include "common.h"
+
+namespace sol {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+template <typename T> struct Mma;
+template <> struct Mma<bf16_t> {
+    // one v_mfma_f32_32x32x16_bf16: each lane supplies 8 consecutive reduction elements
+    template <typename V> static __device__ __forceinline__ void run(f32x16_t &acc, const V &a, const V &b) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                      __builtin_bit_cast(bf16x8_t, b), acc, 0, 0, 0);
+    }
+};
+template <> struct Mma<float> {
+    // four v_mfma_f32_32x32x2_f32 (true fp32 multiplies); the reduction order inside a 128-byte row
+    // is permuted identically for both operands, which leaves the sum unchanged
+    template <typename V> static __device__ __forceinline__ void run(f32x16_t &acc, const V &a, const V &b) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+    }
+};
+
+// GEMM row m -> output pixel.  With a fused 2x2 pool the rows are ordered window-major, so that the
+// four elements of one pooling window sit in four adjacent lanes in row-major window order.
+__device__ __forceinline__ void decode_pixel(const ConvArgs &a, int m, int &n, int &op, int &oq) {
+    if (a.pool) {
+        const int win = m >> 2, d = m & 3;
+        const int qp = win % a.Wy, t = win / a.Wy;
+        const int pp = t % a.Hy;
+        n = t / a.Hy;
+        op = 2 * pp + (d >> 1);
+        oq = 2 * qp + (d & 1);
+    } else {
+        oq = m % a.Wo;
+        const int t = m / a.Wo;
+        op = t % a.Ho;
+        n = t / a.Ho;
+    }
+}
+
+template <typename T> __device__ __forceinline__ void store_vec8(T *p, const float v[8]);
+template <> __device__ __forceinline__ void store_vec8<float>(float *p, const float v[8]) {
+    reinterpret_cast<float4 *>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
+    reinterpret_cast<float4 *>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
+}
+template <> __device__ __forceinline__ void store_vec8<bf16_t>(bf16_t *p, const float v[8]) {
+    uint4 u;
+    u.x = pack_bf16x2(v[0], v[1]);
+    u.y = pack_bf16x2(v[2], v[3]);
+    u.z = pack_bf16x2(v[4], v[5]);
+    u.w = pack_bf16x2(v[6], v[7]);
+    *reinterpret_cast<uint4 *>(p) = u;
+}
+template <typename T> __device__ __forceinline__ void load_vec8(const T *p, float v[8]);
+template <> __device__ __forceinline__ void load_vec8<float>(const float *p, float v[8]) {
+    const float4 f = reinterpret_cast<const float4 *>(p)[0], g = reinterpret_cast<const float4 *>(p)[1];
+    v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w; v[4] = g.x; v[5] = g.y; v[6] = g.z; v[7] = g.w;
+}
+template <> __device__ __forceinline__ void load_vec8<bf16_t>(const bf16_t *p, float v[8]) {
+    const uint4 u = *reinterpret_cast<const uint4 *>(p);
+    v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
+    v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
+    v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xffff0000u);
+    v[6] = __uint_as_float(u.w << 16); v[7] = __uint_as_float(u.w & 0xffff0000u);
+}
+
+// nv = number of valid channels among the 8 (<= 0: none); vec = Cout % 8 == 0 (aligned, never ragged)
+template <typename T>
+__device__ __forceinline__ void store8(T *p, const float v[8], int nv, bool vec) {
+    if (vec) { store_vec8<T>(p, v); return; }
+#pragma unroll
+    for (int e = 0; e < 8; e++)
+        if (e < nv) Elem<T>::store(p + e, v[e]);
+}
+template <typename T>
+__device__ __forceinline__ void load8(const T *p, float v[8], int nv, bool vec) {
+    if (vec) { load_vec8<T>(p, v); return; }
+#pragma unroll
+    for (int e = 0; e < 8; e++) v[e] = e < nv ? Elem<T>::load(p + e) : 0.f;
+}
+
+template <int N, int I = 0, typename F> __device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
+// Fused epilogue shared by all convolution kernels.  acc[i][j] is the 32x32 accumulator block of
+// channel block i and pixel block j of this wave (MFMA layout: lane = pixel, 4-register groups =
+// 4 consecutive channels).  lds_f: LDS scratch of at least NW*32*(TC*32+4) floats that no wave still
+// reads as tile data; mw / cw: first GEMM row / first output channel of this wave's tile.
+template <typename T, int TP, int TC>
+__device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)[TC][TP], float *lds_f, int wave,
+                                              int lane, int mw, int cw) {
+    const int lr = lane & 31, lh = lane >> 5;
+    // ---- fused epilogue: affine (folded BN + bias), residual, activation, optional 2x2 pool -------
+    // The accumulators hold 4 channels x 1 pixel per lane; writing them out directly would give
+    // 8-byte stores scattered over 32 pixel rows.  Each wave therefore transposes one 32-pixel block
+    // at a time through a private LDS strip and writes rows of 8 channels per lane: whole 128-byte
+    // lines for the output and the residual alike.
+    constexpr int ECH = TC * 32;                 // channels per wave
+    constexpr int ERS = ECH + 4;                 // padded strip row, in floats
+    constexpr int LPR = ECH / 8;                 // lanes per pixel row (8 channels each)
+    constexpr int RPS = 64 / LPR;                // pixel rows per pass
+    float *strip = lds_f + wave * (32 * ERS);
+    T *__restrict__ yg = static_cast<T *>(a.y);
+    const T *__restrict__ resg = static_cast<const T *>(a.res);
+    T *__restrict__ preg = static_cast<T *>(a.prepool);
+    const int ecg = lane % LPR, erow = lane / LPR;
+    const int cb = cw + ecg * 8;                  // first of this lane's 8 output channels
+    const int nv = min(8, a.Cout - cb);          // how many of them exist
+    const bool vec = (a.Cout & 7) == 0;          // rows are 16-byte aligned and never ragged
+    float sc[8], sf[8];
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        sc[e] = (a.scale && e < nv) ? a.scale[cb + e] : 1.f;
+        sf[e] = (a.shift && e < nv) ? a.shift[cb + e] : 0.f;
+    }
+    auto finish_row = [&](int row, long opix, float v[8]) {   // strip row -> act(scale*acc + shift + residual)
+        const float4 lo = *reinterpret_cast<const float4 *>(strip + row * ERS + ecg * 8);
+        const float4 hi = *reinterpret_cast<const float4 *>(strip + row * ERS + ecg * 8 + 4);
+        const float r[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+        for (int e = 0; e < 8; e++) v[e] = r[e] * sc[e] + sf[e];
+        if (resg) {
+            float rv[8];
+            load8<T>(resg + opix * a.Cout + cb, rv, nv, vec);
+#pragma unroll
+            for (int e = 0; e < 8; e++) v[e] += rv[e];
+        }
+        if (a.act == SOL_ACT_RELU) {
+#pragma unroll
+            for (int e = 0; e < 8; e++) v[e] = v[e] > 0.f ? v[e] : 0.f;
+        }
+    };
+    // compile-time loop over the pixel blocks: the accumulator index must be a constant
+    static_for<TP>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        const int mb = mw + j * 32;          // first GEMM row of this 32-pixel block
+#pragma unroll
+        for (int i = 0; i < TC; i++)
+#pragma unroll
+            for (int g = 0; g < 4; g++)
+                *reinterpret_cast<float4 *>(strip + lr * ERS + i * 32 + 8 * g + 4 * lh) =
+                    make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+        __syncthreads();
+        if (!a.pool) {
+#pragma unroll
+            for (int ps = 0; ps < 32 / RPS; ps++) {
+                const int row = erow + ps * RPS;
+                const int m = mb + row;
+                if (m < a.P && nv > 0) {
+                    float v[8];
+                    finish_row(row, m, v);
+                    store8<T>(yg + (long)m * a.Cout + cb, v, nv, vec);
+                }
+            }
+        } else {
+            // rows 4w..4w+3 of the strip are the 4 elements of pooling window w, in row-major window order
+            for (int w = erow; w < 8; w += RPS) {
+                const int m0 = mb + 4 * w;
+                if (m0 < a.P && nv > 0) {
+                    int n, op, oq;
+                    decode_pixel(a, m0, n, op, oq);                 // top-left element of the window
+                    float best[8];
+                    int bi[8];
+#pragma unroll
+                    for (int d = 0; d < 4; d++) {
+                        const long opix = ((long)n * a.Ho + op + (d >> 1)) * a.Wo + oq + (d & 1);
+                        float v[8];
+                        finish_row(4 * w + d, opix, v);
+                        if (preg) store8<T>(preg + opix * a.Cout + cb, v, nv, vec);
+#pragma unroll
+                        for (int e = 0; e < 8; e++) {
+                            if (a.pool == 1) {          // strict '>' in scan order: the first maximum wins
+                                if (d == 0 || v[e] > best[e]) { best[e] = v[e]; bi[e] = d; }
+                            } else {
+                                best[e] = d == 0 ? v[e] : best[e] + v[e];
+                            }
+                        }
+                    }
+                    if (a.pool == 2) {
+#pragma unroll
+                        for (int e = 0; e < 8; e++) best[e] *= 0.25f;
+                    }
+                    const long obase = (long)(m0 >> 2) * a.Cout + cb;
+                    store8<T>(yg + obase, best, nv, vec);
+                    if (a.argmax && a.pool == 1) {
+#pragma unroll
+                        for (int e = 0; e < 8; e++)
+                            if (e < nv) a.argmax[obase + e] = (op + (bi[e] >> 1)) * a.Wo + oq + (bi[e] & 1);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    });
+}
+
+}  // namespace sol

@@ -82,7 +82,7 @@ template <> struct VecIO<bf16_t, 8> {
     static __device__ __forceinline__ void store(bf16_t *p, const float v[8]) {
         uint32_t w[4];
 #pragma unroll
-        for (int i = 0; i < 4; i++) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+        for (int i = 0; i < 4; i++) w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
         *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 };

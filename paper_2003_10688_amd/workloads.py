@@ -245,8 +245,16 @@ class Workload:
         return make_labels(self.in_shape[0], self.num_classes, self.seed)
 
 
-def config(idx: int, batch: int | None = None, hw: int | None = None) -> Workload:
-    """The five configurations; ``batch`` / ``hw`` shrink a config for parity tests."""
+def config(idx: int, batch: int | None = None, hw: int | None = None, dtype: str | None = None) -> Workload:
+    """The five configurations; ``batch`` / ``hw`` shrink a config for parity tests and ``dtype``
+    overrides its storage type (same seed, same layer list)."""
+    wk = _config(idx, batch, hw)
+    if dtype is not None:
+        wk.dtype = dtype
+    return wk
+
+
+def _config(idx, batch, hw):
     seed = BASE_SEED + idx
     if idx == 0:
         return Workload("single_block_fp32", single_block_layers(), (batch or 1, 3, hw or 32, hw or 32),

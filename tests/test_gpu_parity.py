@@ -107,7 +107,7 @@ def test_conv_no_bn_no_act_plain(sol, dt):
     assert (got < 0).any()                       # really no ReLU
 
 
-@pytest.mark.parametrize("tile", range(1, 9))
+@pytest.mark.parametrize("tile", list(range(1, 9)) + list(range(11, 19)) + list(range(21, 25)))
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 def test_every_conv_tile(sol, dt, tile):
     rng = np.random.default_rng(100 + tile)
@@ -232,6 +232,23 @@ def test_pack_unpack_roundtrip(sol, dt):
         assert np.array_equal(back.cpu().numpy(), w)
 
 
+def test_bf16_store_rounding_is_nearest_even(sol):
+    """Every fp32 -> bf16 store of the HIP path uses one conversion; check it bit for bit against the
+    checker's rounding on random magnitudes, exact ties, values next to ties, and tiny/huge values."""
+    rng = np.random.default_rng(37)
+    v = (rng.standard_normal(60000) * np.exp(rng.uniform(-30, 30, 60000))).astype(np.float32)
+    base = (rng.standard_normal(2000) * np.exp(rng.uniform(-10, 10, 2000))).astype(np.float32)
+    grid = wl.to_bf16_grid(base).view(np.uint32)
+    ties = (grid | 0x8000).view(np.float32)                      # exactly half way to the next bf16 value
+    near = np.concatenate([(grid | 0x8001).view(np.float32), (grid | 0x7fff).view(np.float32)])
+    w = np.concatenate([v, ties, near, np.float32([0.0, -0.0, 1e-40, -1e-40, 3.38e38, 1.0, -1.0])])
+    w = np.resize(w, (64, 1024 // 1, 1, 1)).astype(np.float32)
+    cd = sol.ConvDesc(64, 1024, 1, 1, 1, 1, 0, 0)
+    back = sol.sol_unpack_conv_weights(cd, sol.BF16, sol.sol_pack_conv_weights(cd, sol.BF16, sol.dev_f32(w)))
+    torch.cuda.synchronize()
+    assert np.array_equal(back.cpu().numpy().astype(np.float64), orc.round_bf16(w.astype(np.float64)))
+
+
 def test_empty_batch_and_errors(sol):
     d = sol.F32
     cd = sol.ConvDesc(8, 4, 3, 3, 1, 1, 1, 1)
@@ -263,19 +280,78 @@ def run_network(sol, wk, keep=True):
     return net, sol.to_host_nchw(y)
 
 
-@pytest.mark.parametrize("cfg,batch,hw", [(0, None, None), (1, None, None), (1, 5, 18), (2, 2, 64), (3, 2, 64), (3, 1, 224)])
-def test_network_forward_every_layer(sol, cfg, batch, hw):
-    """End to end on the same seeded tensors; every layer's stored output is compared."""
+def _layer_results(sol, net, y, outs):
+    got = [sol.to_host_nchw(net.layer_output(i)).reshape(outs[i].shape) for i in range(len(outs) - 1)]
+    got.append(y.reshape(outs[-1].shape))
+    return got
+
+
+def norm_err(g, r):
+    return float(np.linalg.norm(np.asarray(g, np.float64) - r) / max(np.linalg.norm(r), 1e-30))
+
+
+@pytest.mark.parametrize("cfg,batch,hw", [(0, None, None), (1, None, None), (1, 5, 18)])
+def test_network_forward_fp32_configs(sol, cfg, batch, hw):
+    """Configs 0 and 1 end to end at their full size; every layer's stored output is compared."""
     wk = wl.config(cfg, batch=batch, hw=hw)
-    outs, _ = orc.network_forward(wk.layers, wk.params, wk.x, bf16=wk.bf16, return_all=True)
+    outs, _ = orc.network_forward(wk.layers, wk.params, wk.x, return_all=True)
     net, y = run_network(sol, wk)
-    errs = []
-    for i in range(len(wk.layers) - 1):
-        errs.append(rel_err(sol.to_host_nchw(net.layer_output(i)).reshape(outs[i].shape), outs[i]))
-    errs.append(rel_err(y.reshape(outs[-1].shape), outs[-1]))
+    errs = [rel_err(g, r) for g, r in zip(_layer_results(sol, net, y, outs), outs)]
     print(f"cfg{cfg} per-layer rel err: max {max(errs):.3e} last {errs[-1]:.3e}")
-    assert max(errs) <= TOL[wk.dtype], errs
-    # the buffer-reusing plan gives the same final result, bit for bit
+    assert max(errs) <= TOL["f32"], errs
+    _, y2 = run_network(sol, wk, keep=False)          # the buffer-reusing plan gives the same result
+    assert np.array_equal(y, y2)
+
+
+@pytest.mark.parametrize("cfg,batch,hw", [(2, 2, 64), (3, 2, 64), (3, 1, 224)])
+def test_network_forward_resnets_fp32_arithmetic(sol, cfg, batch, hw):
+    """The ResNet-shaped layer lists in fp32 storage: no rounding points between layers, so the whole
+    chain (planner wiring, residual edges, every kernel template) must agree to 1e-4 end to end."""
+    wk = wl.config(cfg, batch=batch, hw=hw, dtype="f32")
+    outs, _ = orc.network_forward(wk.layers, wk.params, wk.x, return_all=True)
+    net, y = run_network(sol, wk)
+    errs = [rel_err(g, r) for g, r in zip(_layer_results(sol, net, y, outs), outs)]
+    print(f"cfg{cfg}/fp32 per-layer rel err: max {max(errs):.3e} last {errs[-1]:.3e}")
+    assert max(errs) <= TOL["f32"], errs
+
+
+@pytest.mark.parametrize("cfg,batch,hw", [(2, 2, 64), (3, 2, 64), (3, 1, 224), (2, 1, 224)])
+def test_network_forward_resnets_bf16(sol, cfg, batch, hw):
+    """bf16 storage, fp32 accumulate.  Two passes over the same seeded tensors:
+
+    (a) layer by layer inside the network object: every layer consumes the CHECKER's stored
+        activations (exact bf16 values) and its output must match element-wise within 2e-2;
+    (b) free running: the network consumes its own activations.  A bf16 store that rounds the other
+        way than the checker's (fp32 vs fp64 accumulation straddling a rounding boundary) perturbs the
+        next layer's sums, which flips more roundings; over 20-50 layers the element-wise maximum
+        over ~10^6 values drifts to several bf16 ulps although the typical element stays within one.
+        So (b) is gated on the norm-wise relative error (2e-2) at every layer and a loose element-wise
+        bound; the strict element-wise statement is (a)."""
+    wk = wl.config(cfg, batch=batch, hw=hw)
+    outs, _ = orc.network_forward(wk.layers, wk.params, wk.x, bf16=True, return_all=True)
+    net, y = run_network(sol, wk)
+    free = _layer_results(sol, net, y, outs)
+    e_free = [rel_err(g, r) for g, r in zip(free, outs)]
+    n_free = [norm_err(g, r) for g, r in zip(free, outs)]
+    # (a) teacher-forced: load the checker's activations into the workspace, run one layer at a time
+    nl = len(wk.layers)
+    x = sol.to_device_nhwc(wk.x, sol.BF16)
+    dev = [sol.to_device_nhwc(o if o.ndim == 4 else o[:, :, None, None], sol.BF16) for o in outs]
+    for i in range(nl - 1):
+        net.layer_output(i).copy_(dev[i])
+    e_forced = []
+    for i in range(nl):
+        net.run_layer(i, x)
+        torch.cuda.synchronize()
+        g = sol.to_host_nchw(net.y if i == nl - 1 else net.layer_output(i)).reshape(outs[i].shape)
+        e_forced.append(rel_err(g, outs[i]))
+        if i < nl - 1:
+            net.layer_output(i).copy_(dev[i])
+    print(f"cfg{cfg} bf16 b{batch} hw{hw}: layer-by-layer max {max(e_forced):.3e} | free-running element-wise max "
+          f"{max(e_free):.3e} last {e_free[-1]:.3e}, norm-wise max {max(n_free):.3e}")
+    assert max(e_forced) <= TOL["bf16"], e_forced
+    assert max(n_free) <= TOL["bf16"], n_free
+    assert max(e_free) <= 0.25, e_free
     _, y2 = run_network(sol, wk, keep=False)
     assert np.array_equal(y, y2)
 
@@ -335,6 +411,7 @@ def test_full_size_layers_sampled(sol, cfg):
         floor = np.sqrt(np.mean(want * want)) + 1e-30
         err = float(np.max(np.abs(g - want) / np.maximum(np.abs(want), floor)))
         worst = max(worst, err)
+        print(f"  L{i} in{ins} k{l['kh']} s{l['sh']} cout{K}: rel err {err:.3e} ({np.count_nonzero(g != want)} of {len(g)} differ)", flush=True)
         assert err <= TOL["bf16"], (i, ins, l, err)
         del x, got, r
     print(f"cfg{cfg} full-size sampled layers: worst rel err {worst:.3e}")
