@@ -106,6 +106,8 @@ enum {
 };
 int dma_tile_row_bytes(int tile);
 sol_status launch_conv_dma(const ConvArgs &a, int dt, int tile, hipStream_t st);
+bool stem_kernel_applies(const ConvArgs &a, int dt);
+sol_status launch_conv_stem(const ConvArgs &a, hipStream_t st);
 sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t st);
 sol_status launch_pool(const PoolArgs &a, int dt, hipStream_t st);
 sol_status launch_gap(const void *x, void *y, int N, int HW, int C, int dt, hipStream_t st);

@@ -99,9 +99,40 @@ template <int N, int I = 0, typename F> __device__ __forceinline__ void static_f
 // channel block i and pixel block j of this wave (MFMA layout: lane = pixel, 4-register groups =
 // 4 consecutive channels).  lds_f: LDS scratch of at least NW*32*(TC*32+4) floats that no wave still
 // reads as tile data; mw / cw: first GEMM row / first output channel of this wave's tile.
-template <typename T, int TP, int TC>
+// rowmap(m): output pixel index of tile row m (counted from mw), or -1 if the row is padding; only
+// consulted when no pool is fused (the fused pool relies on the window-major GEMM row order).
+struct LinearRows {
+    int P;
+    __device__ __forceinline__ long operator()(int m) const { return m < P ? (long)m : -1L; }
+};
+
+// Per-lane affine map of the epilogue (folded BN + bias of this lane's 8 output channels).  Loaded
+// ahead of the main loop so that the latency of these loads is hidden behind it.
+struct Affine8 {
+    float sc[8], sf[8];
+};
+template <int TC> __device__ __forceinline__ Affine8 load_affine(const ConvArgs &a, int lane, int cw) {
+    const int cb = cw + (lane % (TC * 4)) * 8;
+    const int nv = min(8, a.Cout - cb);
+    Affine8 f;
+    if (nv == 8 && a.scale && a.shift) {          // the usual case: two aligned 32-byte runs
+        const float4 s0 = *reinterpret_cast<const float4 *>(a.scale + cb), s1 = *reinterpret_cast<const float4 *>(a.scale + cb + 4);
+        const float4 h0 = *reinterpret_cast<const float4 *>(a.shift + cb), h1 = *reinterpret_cast<const float4 *>(a.shift + cb + 4);
+        f.sc[0] = s0.x; f.sc[1] = s0.y; f.sc[2] = s0.z; f.sc[3] = s0.w; f.sc[4] = s1.x; f.sc[5] = s1.y; f.sc[6] = s1.z; f.sc[7] = s1.w;
+        f.sf[0] = h0.x; f.sf[1] = h0.y; f.sf[2] = h0.z; f.sf[3] = h0.w; f.sf[4] = h1.x; f.sf[5] = h1.y; f.sf[6] = h1.z; f.sf[7] = h1.w;
+        return f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        f.sc[e] = (a.scale && e < nv) ? a.scale[cb + e] : 1.f;
+        f.sf[e] = (a.shift && e < nv) ? a.shift[cb + e] : 0.f;
+    }
+    return f;
+}
+
+template <typename T, int TP, int TC, typename RowMap>
 __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)[TC][TP], float *lds_f, int wave,
-                                              int lane, int mw, int cw) {
+                                              int lane, int mw, int cw, const Affine8 &aff, const RowMap &rowmap) {
     const int lr = lane & 31, lh = lane >> 5;
     // ---- fused epilogue: affine (folded BN + bias), residual, activation, optional 2x2 pool -------
     // The accumulators hold 4 channels x 1 pixel per lane; writing them out directly would give
@@ -120,12 +151,7 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
     const int cb = cw + ecg * 8;                  // first of this lane's 8 output channels
     const int nv = min(8, a.Cout - cb);          // how many of them exist
     const bool vec = (a.Cout & 7) == 0;          // rows are 16-byte aligned and never ragged
-    float sc[8], sf[8];
-#pragma unroll
-    for (int e = 0; e < 8; e++) {
-        sc[e] = (a.scale && e < nv) ? a.scale[cb + e] : 1.f;
-        sf[e] = (a.shift && e < nv) ? a.shift[cb + e] : 0.f;
-    }
+    const float *sc = aff.sc, *sf = aff.sf;
     auto finish_row = [&](int row, long opix, float v[8]) {   // strip row -> act(scale*acc + shift + residual)
         const float4 lo = *reinterpret_cast<const float4 *>(strip + row * ERS + ecg * 8);
         const float4 hi = *reinterpret_cast<const float4 *>(strip + row * ERS + ecg * 8 + 4);
@@ -158,11 +184,11 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
 #pragma unroll
             for (int ps = 0; ps < 32 / RPS; ps++) {
                 const int row = erow + ps * RPS;
-                const int m = mb + row;
-                if (m < a.P && nv > 0) {
+                const long m = rowmap(mb + row);        // output pixel index, or -1
+                if (m >= 0 && nv > 0) {
                     float v[8];
                     finish_row(row, m, v);
-                    store8<T>(yg + (long)m * a.Cout + cb, v, nv, vec);
+                    store8<T>(yg + m * a.Cout + cb, v, nv, vec);
                 }
             }
         } else {

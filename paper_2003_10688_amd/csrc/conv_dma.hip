@@ -127,6 +127,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
         if (++tcc == cpt) { tcc = 0; if (++ts == a.S) { ts = 0; ++tr; } }
     };
 
+    const Affine8 aff = load_affine<TC>(a, lane, c0 + wc * TC * 32);
     f32x16_t acc[TC][TP];
 #pragma unroll
     for (int i = 0; i < TC; i++)
@@ -182,7 +183,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
         });
     }
     __syncthreads();                               // every wave is done with the tiles: reuse LDS as strip
-    conv_epilogue<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32);
+    conv_epilogue<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, aff, LinearRows{a.P});
 }
 
 template <typename T, int BP, int BC, int WP, int WC, int ROWB, int NS>

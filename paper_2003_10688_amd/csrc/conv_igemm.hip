@@ -145,6 +145,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
         }
     };
 
+    const Affine8 aff = load_affine<TC>(a, lane, c0 + wc * TC * 32);
     f32x16_t acc[TC][TP];
 #pragma unroll
     for (int i = 0; i < TC; i++)
@@ -182,7 +183,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
     }
 
     static_assert((WP * WC) * 32 * (TC * 32 + 4) * 4 <= 2 * (BP + BC) * 128, "epilogue strip must fit in the tile buffers");
-    conv_epilogue<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32);
+    conv_epilogue<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, aff, LinearRows{a.P});
 }
 
 // ---- launcher / tile table ------------------------------------------------------------------------
@@ -239,6 +240,7 @@ template <typename T> static sol_status launch_typed(const ConvArgs &a, int tile
 
 sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t st) {
     if (a.P <= 0) return SOL_OK;   // empty batch: nothing to do
+    if (tile_override == T_AUTO && stem_kernel_applies(a, dt)) return launch_conv_stem(a, st);
     if (const int rowb = dma_tile_row_bytes(tile_override)) {
         SOL_REQUIRE(a.C % (rowb / (int)dtype_size(dt)) == 0 && a.Cout > 32, SOL_ERR_UNSUPPORTED,
                     "conv tile %d needs Cin %% %d == 0 and Cout > 32", tile_override, rowb / (int)dtype_size(dt));

@@ -1,0 +1,124 @@
+// Fused 7x7 / stride-2 / pad-3 convolution for 3-channel inputs (the ResNet-shaped stem), bf16.
+//
+// With Cin = 3 the reduction index (r, s, c) has no 16-byte-contiguous runs in NHWC, so the generic
+// implicit GEMM has to gather single elements.  Here a workgroup instead stages the input patch of
+// an 8 x 16 block of output pixels in LDS, widened to 4 channels per pixel (8 bytes, channel 3 = 0).
+// For a fixed filter row r the taps (s, c) of one output pixel are then 7 x 4 contiguous elements,
+// padded to 32: the reduction becomes 7 rows x 32 = 224 elements, and every MFMA fragment (8
+// consecutive reduction elements of one pixel) is one aligned 16-byte LDS read.  The weights are
+// re-laid-out once per workgroup into the same padded order (zeros at s = 7 and c = 3), and the
+// workgroup then walks many tiles (persistent grid), so that cost is paid once.
+#include "conv_common.h"
+
+namespace sol {
+
+struct StemRows {   // tile row (py*16+px) of the 8x16 output block -> output pixel index
+    int n, p0, q0, Ho, Wo;
+    __device__ __forceinline__ long operator()(int m) const {
+        const int p = p0 + (m >> 4), q = q0 + (m & 15);
+        return (p < Ho && q < Wo) ? ((long)n * Ho + p) * Wo + q : -1L;
+    }
+};
+
+constexpr int STEM_TH = 8, STEM_TW = 16;
+constexpr int STEM_IH = 2 * STEM_TH + 5, STEM_IW = 2 * STEM_TW + 6;   // patch extent (+1 zero column)
+constexpr int STEM_WROW = 232;                                         // padded weight row (bank spread)
+
+__global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int tiles_h, int tiles_w, int ntiles) {
+    __shared__ __align__(16) bf16_t wl[64 * STEM_WROW];                 // 29.0 KB
+    __shared__ __align__(16) bf16_t xl[STEM_IH * STEM_IW * 4];          //  6.4 KB
+    __shared__ __align__(16) float strip[4 * 32 * 68];                  // 34.0 KB epilogue transposer
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bf16_t *__restrict__ xg = static_cast<const bf16_t *>(a.x);
+    const bf16_t *__restrict__ wg = static_cast<const bf16_t *>(a.w);
+
+    // weights: packed [k][(r*7+s)*3+c] -> LDS [k][r*32 + s*4 + c], zero elsewhere
+    for (int i = tid; i < 64 * STEM_WROW; i += 256) {
+        const int k = i / STEM_WROW, kk = i % STEM_WROW;
+        const int r = kk >> 5, s = (kk & 31) >> 2, c = kk & 3;
+        bf16_t v = 0;
+        if (kk < 224 && s < 7 && c < 3 && k < a.Cout) v = wg[k * a.Kp + (r * 7 + s) * 3 + c];
+        wl[i] = v;
+    }
+    for (int i = tid; i < STEM_IH * STEM_IW * 4; i += 256) xl[i] = 0;   // incl. the never-written pad column
+
+    const int lr = lane & 31, lh = lane >> 5;
+    const int py = 2 * wave + (lr >> 4), px = lr & 15;                   // this lane's output pixel in the block
+    const unsigned xbase = ((2 * py) * STEM_IW + 2 * px) * 8;            // its patch origin, bytes
+    f32x16_t acc[2][1];
+    const Affine8 aff = load_affine<2>(a, lane, 0);
+
+    // Input patch of a tile: (2*TH+5) x (2*TW+5) pixels, 3 channels each, NP pixels per thread.
+    constexpr int NPIX = STEM_IH * (STEM_IW - 1), NP = (NPIX + 255) / 256;
+    uint2 pv[NP];
+    auto load_patch = [&](int tile) {             // global -> registers (issued one tile ahead)
+        const int tw = tile % tiles_w, t2 = tile / tiles_w;
+        const int th = t2 % tiles_h, n = t2 / tiles_h;
+#pragma unroll
+        for (int i = 0; i < NP; i++) {
+            const int e = tid + i * 256;
+            const int ih = e / (STEM_IW - 1), iw = e % (STEM_IW - 1);
+            const int gh = 2 * th * STEM_TH - 3 + ih, gw = 2 * tw * STEM_TW - 3 + iw;
+            pv[i] = make_uint2(0, 0);
+            if (e < NPIX && (unsigned)gh < (unsigned)a.H && (unsigned)gw < (unsigned)a.W) {
+                const bf16_t *p = xg + (((long)n * a.H + gh) * a.W + gw) * 3;
+                pv[i].x = (uint32_t)p[0] | ((uint32_t)p[1] << 16);
+                pv[i].y = (uint32_t)p[2];
+            }
+        }
+    };
+    auto store_patch = [&]() {                    // registers -> LDS, widened to 4 channels
+#pragma unroll
+        for (int i = 0; i < NP; i++) {
+            const int e = tid + i * 256;
+            if (e < NPIX) {
+                const int ih = e / (STEM_IW - 1), iw = e % (STEM_IW - 1);
+                *reinterpret_cast<uint2 *>(&xl[(ih * STEM_IW + iw) * 4]) = pv[i];
+            }
+        }
+    };
+
+    if ((int)blockIdx.x < ntiles) load_patch(blockIdx.x);
+    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int tw = tile % tiles_w, t2 = tile / tiles_w;
+        const int th = t2 % tiles_h, n = t2 / tiles_h;
+        const int p0 = th * STEM_TH, q0 = tw * STEM_TW;
+        __syncthreads();                                                 // previous tile's patch no longer read
+        store_patch();
+        __syncthreads();
+        if (tile + (int)gridDim.x < ntiles) load_patch(tile + gridDim.x);   // in flight under the MFMAs and the epilogue
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[i][0][e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 14; ks++) {
+            const int r = ks >> 1, s0 = (ks & 1) * 4 + lh * 2;           // 8 elements = pixels s0, s0+1 of row r
+            const uint4 fb = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(xl) + xbase +
+                                                             (r * STEM_IW + s0) * 8);
+#pragma unroll
+            for (int i = 0; i < 2; i++) {
+                const uint4 fa = *reinterpret_cast<const uint4 *>(&wl[(i * 32 + lr) * STEM_WROW + ks * 16 + lh * 8]);
+                Mma<bf16_t>::run(acc[i][0], fa, fb);
+            }
+        }
+        conv_epilogue<bf16_t, 1, 2>(a, acc, strip, wave, lane, wave * 32, 0, aff, StemRows{n, p0, q0, a.Ho, a.Wo});
+    }
+}
+
+bool stem_kernel_applies(const ConvArgs &a, int dt) {
+    return dt == SOL_BF16 && a.C == 3 && a.R == 7 && a.S == 7 && a.sh == 2 && a.sw == 2 && a.ph == 3 && a.pw == 3 &&
+           a.Cout <= 64 && a.pool == 0;
+}
+
+sol_status launch_conv_stem(const ConvArgs &a, hipStream_t st) {
+    const int tiles_h = ceil_div(a.Ho, STEM_TH), tiles_w = ceil_div(a.Wo, STEM_TW);
+    const int ntiles = a.N * tiles_h * tiles_w;
+    const int grid = ntiles < 512 ? ntiles : 512;                        // 2 persistent workgroups per CU
+    hipLaunchKernelGGL(conv_stem_kernel, dim3(grid), dim3(256), 0, st, a, tiles_h, tiles_w, ntiles);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+}  // namespace sol
