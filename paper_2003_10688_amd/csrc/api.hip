@@ -70,7 +70,7 @@ static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, cons
     SOL_REQUIRE(xd.h + 2 * cd.ph >= cd.kh && xd.w + 2 * cd.pw >= cd.kw && Ho > 0 && Wo > 0, SOL_ERR_SHAPE,
                 "filter %dx%d larger than padded input %dx%d", cd.kh, cd.kw, xd.h + 2 * cd.ph, xd.w + 2 * cd.pw);
     ConvArgs a;
-    memset(&a, 0, sizeof(a));
+    memset(static_cast<void *>(&a), 0, sizeof(a));
     a.pool = 0;
     a.Hy = Ho; a.Wy = Wo;
     if (pool && pool->kind != SOL_POOL_NONE) {
@@ -90,6 +90,9 @@ static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, cons
     a.x = x; a.w = w; a.scale = scale; a.shift = shift; a.res = res; a.y = y;
     a.argmax = a.pool == 1 ? argmax : nullptr;
     a.prepool = a.pool ? prepool : nullptr;
+#ifdef SOL_PHASE_TIMING
+    a.prepool = prepool;   // profiling build: receives per-phase cycle counts
+#endif
     a.N = xd.n; a.H = xd.h; a.W = xd.w; a.C = xd.c;
     a.Cout = cd.cout; a.R = cd.kh; a.S = cd.kw; a.sh = cd.sh; a.sw = cd.sw; a.ph = cd.ph; a.pw = cd.pw;
     a.Ho = Ho; a.Wo = Wo;
@@ -97,6 +100,8 @@ static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, cons
     a.Kp = packed_k(cd, xd.dtype);
     a.Ktot = cd.kh * cd.kw * cd.cin;
     a.act = act;
+    a.dw = FastDiv((uint32_t)(a.pool ? a.Wy : Wo));
+    a.dh = FastDiv((uint32_t)(a.pool ? a.Hy : Ho));
     return launch_conv(a, xd.dtype, tile, st);
 }
 

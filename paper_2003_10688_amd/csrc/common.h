@@ -66,6 +66,27 @@ template <> struct Elem<bf16_t> {
 };
 
 // ---- internal launchers (implemented in the .hip files) ------------------------------------------
+// Division of a 32-bit unsigned by a run-time constant (multiply-high and shifts instead of the
+// ~40-instruction software division; the divisor's magic number is computed on the host).
+struct FastDiv {
+    uint32_t d, mul, s1, s2;
+    FastDiv() : d(1), mul(1), s1(0), s2(0) {}
+    explicit FastDiv(uint32_t div) : d(div) {
+        uint32_t l = 0;
+        while ((1ull << l) < div) l++;
+        mul = (uint32_t)(((1ull << 32) * ((1ull << l) - div)) / div + 1);
+        s1 = l < 1 ? l : 1;
+        s2 = l > 0 ? l - 1 : 0;
+    }
+#if defined(__HIPCC__)
+    __device__ __forceinline__ uint32_t div(uint32_t n) const {
+        const uint32_t t = __umulhi(mul, n);
+        return (t + ((n - t) >> s1)) >> s2;
+    }
+    __device__ __forceinline__ void divmod(uint32_t n, uint32_t &q, uint32_t &r) const { q = div(n); r = n - q * d; }
+#endif
+};
+
 struct ConvArgs {
     const void *x, *w;
     const float *scale, *shift;
@@ -83,6 +104,7 @@ struct ConvArgs {
     int act, pool;           // pool: 0 none, 1 max 2x2/2, 2 avg 2x2/2
     int ntc;                 // number of channel tiles (set by the launcher)
     int ntiles;
+    FastDiv dw, dh;          // by Wo, Ho (by Wy, Hy with a fused pool): GEMM row -> pixel
 };
 
 struct PoolArgs {
@@ -102,7 +124,8 @@ enum {
     T_64x128 = 8,
     D_128x128_64x4 = 11, D_128x128_64x3 = 12, D_256x128_64x3 = 13, D_128x64_64x4 = 14, D_64x64_64x4 = 15,
     D_128x256_64x3 = 16, D_256x64_64x3 = 17, D_64x128_64x4 = 18,
-    D_128x128_128x2 = 21, D_128x128_128x3 = 22, D_128x64_128x3 = 23, D_64x64_128x3 = 24
+    D_128x128_128x2 = 21, D_128x128_128x3 = 22, D_128x64_128x3 = 23, D_64x64_128x3 = 24,
+    D_128x128_64x5 = 25, D_64x64_128x4 = 26, D_256x128_128x3 = 27, D_256x128_64x4 = 31, D_128x256_64x4 = 32, D_64x64_64x8 = 33
 };
 int dma_tile_row_bytes(int tile);
 sol_status launch_conv_dma(const ConvArgs &a, int dt, int tile, hipStream_t st);

@@ -32,18 +32,17 @@ template <> struct Mma<float> {
 // GEMM row m -> output pixel.  With a fused 2x2 pool the rows are ordered window-major, so that the
 // four elements of one pooling window sit in four adjacent lanes in row-major window order.
 __device__ __forceinline__ void decode_pixel(const ConvArgs &a, int m, int &n, int &op, int &oq) {
+    uint32_t t, x, nn, y;
+    a.dw.divmod((uint32_t)(a.pool ? m >> 2 : m), t, x);     // x = column (of the window / of the pixel)
+    a.dh.divmod(t, nn, y);
+    n = (int)nn;
     if (a.pool) {
-        const int win = m >> 2, d = m & 3;
-        const int qp = win % a.Wy, t = win / a.Wy;
-        const int pp = t % a.Hy;
-        n = t / a.Hy;
-        op = 2 * pp + (d >> 1);
-        oq = 2 * qp + (d & 1);
+        const int d = m & 3;
+        op = 2 * (int)y + (d >> 1);
+        oq = 2 * (int)x + (d & 1);
     } else {
-        oq = m % a.Wo;
-        const int t = m / a.Wo;
-        op = t % a.Ho;
-        n = t / a.Ho;
+        op = (int)y;
+        oq = (int)x;
     }
 }
 
@@ -98,13 +97,21 @@ template <int N, int I = 0, typename F> __device__ __forceinline__ void static_f
 // Fused epilogue shared by all convolution kernels.  acc[i][j] is the 32x32 accumulator block of
 // channel block i and pixel block j of this wave (MFMA layout: lane = pixel, 4-register groups =
 // 4 consecutive channels).  lds_f: LDS scratch of at least NW*32*(TC*32+4) floats that no wave still
-// reads as tile data; mw / cw: first GEMM row / first output channel of this wave's tile.
+// reads as tile data (each wave uses a private strip of it, so the epilogue needs no workgroup barrier); mw / cw: first GEMM row / first output channel of this wave's tile.
 // rowmap(m): output pixel index of tile row m (counted from mw), or -1 if the row is padding; only
 // consulted when no pool is fused (the fused pool relies on the window-major GEMM row order).
 struct LinearRows {
     int P;
     __device__ __forceinline__ long operator()(int m) const { return m < P ? (long)m : -1L; }
 };
+
+// Orders this wave's earlier LDS accesses before its later ones (wave-private scratch: the LDS unit
+// executes one wave's instructions in order, so only the compiler has to be kept from reordering).
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 // Per-lane affine map of the epilogue (folded BN + bias of this lane's 8 output channels).  Loaded
 // ahead of the main loop so that the latency of these loads is hidden behind it.
@@ -130,9 +137,55 @@ template <int TC> __device__ __forceinline__ Affine8 load_affine(const ConvArgs 
     return f;
 }
 
+// Residual rows of a wave's tile, fetched into registers ahead of the main loop (same lane -> 8-channel
+// mapping as the epilogue's output rows), so that their HBM latency overlaps the tile loads instead
+// of following them.  Only used without a fused pool and when rows are 16-byte aligned.
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> {
+    uint4 v;
+    __device__ __forceinline__ void load(const bf16_t *p) { v = *reinterpret_cast<const uint4 *>(p); }
+    __device__ __forceinline__ void get(float f[8]) const {
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+};
+template <> struct Raw8<float> {
+    float4 lo, hi;
+    __device__ __forceinline__ void load(const float *p) {
+        lo = reinterpret_cast<const float4 *>(p)[0]; hi = reinterpret_cast<const float4 *>(p)[1];
+    }
+    __device__ __forceinline__ void get(float f[8]) const {
+        f[0] = lo.x; f[1] = lo.y; f[2] = lo.z; f[3] = lo.w; f[4] = hi.x; f[5] = hi.y; f[6] = hi.z; f[7] = hi.w;
+    }
+};
+template <typename T, int TP, int TC> struct ResidualRegs {
+    static constexpr int PASSES = 32 / (64 / (TC * 4));
+    Raw8<T> r[TP][PASSES];
+    bool on;
+};
+template <typename T, int TP, int TC, typename RowMap>
+__device__ __forceinline__ void prefetch_residual(const ConvArgs &a, int lane, int mw, int cw, const RowMap &rowmap,
+                                                  ResidualRegs<T, TP, TC> &out) {
+    constexpr int LPR = TC * 4, RPS = 64 / LPR;
+    const T *__restrict__ resg = static_cast<const T *>(a.res);
+    const int cb = cw + (lane % LPR) * 8, erow = lane / LPR;
+    out.on = resg != nullptr && a.pool == 0 && (a.Cout & 7) == 0;
+    if (!out.on) return;
+#pragma unroll
+    for (int j = 0; j < TP; j++)
+#pragma unroll
+        for (int ps = 0; ps < 32 / RPS; ps++) {
+            const long m = rowmap(mw + j * 32 + erow + ps * RPS);
+            if (m >= 0 && cb < a.Cout) out.r[j][ps].load(resg + m * a.Cout + cb);
+        }
+}
+
 template <typename T, int TP, int TC, typename RowMap>
 __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)[TC][TP], float *lds_f, int wave,
-                                              int lane, int mw, int cw, const Affine8 &aff, const RowMap &rowmap) {
+                                              int lane, int mw, int cw, const Affine8 &aff, const RowMap &rowmap,
+                                              const ResidualRegs<T, TP, TC> &pre) {
     const int lr = lane & 31, lh = lane >> 5;
     // ---- fused epilogue: affine (folded BN + bias), residual, activation, optional 2x2 pool -------
     // The accumulators hold 4 channels x 1 pixel per lane; writing them out directly would give
@@ -152,13 +205,18 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
     const int nv = min(8, a.Cout - cb);          // how many of them exist
     const bool vec = (a.Cout & 7) == 0;          // rows are 16-byte aligned and never ragged
     const float *sc = aff.sc, *sf = aff.sf;
-    auto finish_row = [&](int row, long opix, float v[8]) {   // strip row -> act(scale*acc + shift + residual)
+    auto finish_row = [&](int row, long opix, float v[8], const Raw8<T> *pr = nullptr) {   // strip row -> act(scale*acc + shift + residual)
         const float4 lo = *reinterpret_cast<const float4 *>(strip + row * ERS + ecg * 8);
         const float4 hi = *reinterpret_cast<const float4 *>(strip + row * ERS + ecg * 8 + 4);
         const float r[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
         for (int e = 0; e < 8; e++) v[e] = r[e] * sc[e] + sf[e];
-        if (resg) {
+        if (pr) {
+            float rv[8];
+            pr->get(rv);
+#pragma unroll
+            for (int e = 0; e < 8; e++) v[e] += rv[e];
+        } else if (resg) {
             float rv[8];
             load8<T>(resg + opix * a.Cout + cb, rv, nv, vec);
 #pragma unroll
@@ -179,7 +237,7 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
             for (int g = 0; g < 4; g++)
                 *reinterpret_cast<float4 *>(strip + lr * ERS + i * 32 + 8 * g + 4 * lh) =
                     make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-        __syncthreads();
+        wave_lds_fence();
         if (!a.pool) {
 #pragma unroll
             for (int ps = 0; ps < 32 / RPS; ps++) {
@@ -187,7 +245,7 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
                 const long m = rowmap(mb + row);        // output pixel index, or -1
                 if (m >= 0 && nv > 0) {
                     float v[8];
-                    finish_row(row, m, v);
+                    finish_row(row, m, v, pre.on ? &pre.r[j][ps] : nullptr);
                     store8<T>(yg + m * a.Cout + cb, v, nv, vec);
                 }
             }
@@ -229,7 +287,7 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
                 }
             }
         }
-        __syncthreads();
+        wave_lds_fence();
     });
 }
 

@@ -1,24 +1,20 @@
 // Fused implicit-GEMM convolution, LDS-DMA pipeline (gfx950).
 //
 // Same GEMM view and epilogue as conv_igemm.hip, but the operand tiles travel HBM/L2 -> LDS
-// directly (global_load_lds_dwordx4: every lane fetches 16 bytes, a wave instruction fills one
+// directly (buffer_load_dwordx4 ... lds: every lane fetches 16 bytes, a wave instruction fills one
 // contiguous 1 KB LDS segment in lane order), without passing through registers.  That frees the
-// staging registers and the LDS-store issue slots, so a ring of NS stages can be kept in flight per
-// workgroup and several workgroups fit on a CU: the latency of HBM is covered by bytes in flight
-// instead of by occupancy alone.  This is what both regimes of a CNN layer chain need on MI355X:
-// the HBM-bound 1x1 layers need ~64 KB in flight per CU, the MFMA-bound 3x3 layers need the matrix
-// pipe never to wait for a tile.
+// staging registers and the LDS-store issue slots, so a ring of NS stages is kept in flight per
+// workgroup and several workgroups fit on a CU.
 //
 // LDS layout of one stage: BP pixel rows then BC weight rows, ROWB bytes each (one reduction chunk).
 // A row's 16-byte slots are XOR-permuted with the row index (which slot a lane's data lands in is
-// fixed by the DMA, so the permutation is applied to the global address each lane reads), making the
-// 16-byte MFMA fragment reads bank-conflict free.  Padding taps and rows beyond the tensor read a
-// 64-byte block of zeros instead.
+// fixed by the DMA, so the permutation is applied to the address each lane fetches), making the
+// 16-byte MFMA fragment reads bank-conflict free (16 lanes x 16 bytes per LDS read cycle).  Padding
+// taps and rows beyond the tensor are fetched with an out-of-range buffer offset, which the hardware
+// turns into zeros.
 #include "conv_common.h"
 
 namespace sol {
-
-__device__ __attribute__((used)) uint4 g_zero_block[4];   // zero-initialised; never written
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt = [15:14][3:0])
@@ -44,20 +40,25 @@ __device__ __forceinline__ unsigned lds_addr(const void *p) {
     return (unsigned)(size_t)(__attribute__((address_space(3))) const void *)p;
 }
 
-__device__ __forceinline__ void dma16(const void *g, unsigned char *l) {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                     (__attribute__((address_space(3))) void *)l, 16, 0, 0);
-}
-
 // T: element type; BP x BC: pixels x channels per workgroup; WP x WC: wave grid;
 // ROWB: bytes of reduction data per tile row and stage (64 or 128); NS: ring stages.
-// Requires Cin % (ROWB / sizeof(T)) == 0, so that every chunk lies inside one filter tap.
+// Requires Cin % (ROWB / sizeof(T)) == 0 (every chunk lies inside one filter tap), at most 32 filter
+// taps, and tensors smaller than 4 GB (32-bit buffer offsets).
+//
+// Address generation is the scarce resource of the main loop: every instruction a wave spends on
+// it delays the MFMAs behind it.  The DMA therefore uses buffer addressing: a per-lane byte offset
+// that is computed ONCE per tile row (voffset), a wave-uniform per-stage offset for the filter tap
+// and channel chunk (soffset, scalar), and the hardware range check for everything that must read
+// as zero -- rows beyond the tensor carry an out-of-range offset for good, padding taps get one by
+// OR-ing in a per-row bit mask of invalid taps.  One DMA costs 2 vector + 2 scalar instructions, and
+// the DMA of stage kc+NS-1 is spread between the MFMAs of stage kc.
 template <typename T, int BP, int BC, int WP, int WC, int ROWB, int NS>
 __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub (buffer types are device-only)
     constexpr int NW = WP * WC;
-    constexpr int BK = ROWB / (int)sizeof(T);      // reduction elements per stage
-    constexpr int EPC = 16 / (int)sizeof(T);       // elements per 16-byte slot
-    constexpr int SLOTS = ROWB / 16;               // slots per row
+    constexpr int ES = (int)sizeof(T);
+    constexpr int BK = ROWB / ES;                  // reduction elements per stage
+    constexpr int SLOTS = ROWB / 16;               // 16-byte slots per row
     constexpr int RSEG = 64 / SLOTS;               // tile rows per 1 KB DMA segment
     constexpr int XL = BP / RSEG / NW, WL = BC / RSEG / NW;   // DMA instructions per wave and stage
     constexpr int L = XL + WL;
@@ -66,11 +67,14 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
     constexpr int TP = BP / (WP * 32), TC = BC / (WC * 32);
     static_assert(ROWB == 64 || ROWB == 128, "row bytes");
     static_assert(BP % (RSEG * NW) == 0 && BC % (RSEG * NW) == 0, "tile rows must split evenly over the waves");
-    static_assert(NS >= 2 && (NS - 2) * L <= 63, "ring depth");
-    static_assert(NW * 32 * (TC * 32 + 4) * 4 <= NS * STAGE, "epilogue strip must fit in the ring");
+    static_assert(NS >= 2 && (NS - 2) * L <= 63, "ring depth is bounded by the 6-bit vmcnt");
+    static_assert(NW * 32 * (TC * 32 + 4) * 4 <= NS * STAGE, "epilogue strips must fit in the ring");
 
     __shared__ __align__(1024) unsigned char lds[NS * STAGE];
 
+#ifdef SOL_PHASE_TIMING
+    const long long tentry_ = __builtin_readcyclecounter();
+#endif
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wp = wave % WP, wc = wave / WP;
@@ -80,54 +84,74 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
     if (tile >= a.ntiles) return;
     const int p0 = (tile / a.ntc) * BP, c0 = (tile % a.ntc) * BC;
 
-    const T *__restrict__ xg = static_cast<const T *>(a.x);
-    const T *__restrict__ wg = static_cast<const T *>(a.w);
-    const T *zero = reinterpret_cast<const T *>(g_zero_block);
+    // Buffer resources.  The activation resource starts `bias` bytes before the tensor so that the
+    // offset of a row's window origin (which lies in the padding for border pixels) is never negative;
+    // only in-range taps are ever fetched through it.
+    const unsigned bias = (unsigned)((a.ph * a.W + a.pw) * a.C) * ES;
+    const unsigned xbytes = (unsigned)a.N * a.H * a.W * a.C * ES, wbytes = (unsigned)a.Cout * a.Kp * ES;
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char *>(static_cast<const unsigned char *>(a.x)) - bias, 0, (int)(xbytes + bias), 0x00020000);
+    const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, (int)wbytes, 0x00020000);
 
     // ---- this lane's share of every stage: XL pixel rows and WL weight rows, one 16-byte slot each
     const int lslot = lane % SLOTS, lrow = lane / SLOTS;
     auto swz = [](int row) { return ROWB == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
-    int rb[XL], rh[XL], rw[XL];
+    unsigned xo[XL], xinv[XL], wo[WL];             // byte offsets; bit t of xinv = filter tap t reads padding
 #pragma unroll
     for (int i = 0; i < XL; i++) {
         const int row = (wave * XL + i) * RSEG + lrow;
         const int m = p0 + row;
-        rb[i] = 0; rh[i] = -(1 << 20); rw[i] = -(1 << 20);
+        xo[i] = 0xffffffffu; xinv[i] = 0;
         if (m < a.P) {
             int n, op, oq;
             decode_pixel(a, m, n, op, oq);
-            rh[i] = op * a.sh - a.ph;
-            rw[i] = oq * a.sw - a.pw;
-            rb[i] = ((n * a.H + rh[i]) * a.W + rw[i]) * a.C + (lslot ^ swz(row)) * EPC;
+            const int ih0 = op * a.sh - a.ph, iw0 = oq * a.sw - a.pw;
+            xo[i] = (unsigned)(((n * a.H + ih0) * a.W + iw0) * a.C) * ES + bias + (lslot ^ swz(row)) * 16;
+            // taps s in [slo, shi) of every filter row r in [rlo, rhi) are inside the image
+            const int slo = max(0, -iw0), shi = min(a.S, a.W - iw0), rlo = max(0, -ih0), rhi = min(a.R, a.H - ih0);
+            const unsigned cval = shi > slo ? (unsigned)((1ull << shi) - 1ull) & ~((1u << slo) - 1u) : 0u;
+            unsigned val = 0;
+            for (int r = 0; r < a.R; r++) val |= (r >= rlo && r < rhi) ? cval << (r * a.S) : 0u;
+            xinv[i] = ~val;
         }
     }
-    int wb[WL];
 #pragma unroll
     for (int i = 0; i < WL; i++) {
         const int row = (wave * WL + i) * RSEG + lrow;
         const int co = c0 + row;
-        wb[i] = co < a.Cout ? co * a.Kp + (lslot ^ swz(row)) * EPC : -1;
+        wo[i] = co < a.Cout ? (unsigned)(co * a.Kp) * ES + (lslot ^ swz(row)) * 16 : 0xffffffffu;
     }
 
     const int cpt = a.C / BK;                      // chunks per filter tap
     const int nk = a.R * a.S * cpt;
-    int tr = 0, ts = 0, tcc = 0;                   // filter tap / chunk of the NEXT stage to issue
+    int tr = 0, ts = 0, tcc = 0, tap = 0;          // filter tap / chunk of the NEXT stage to issue
 
-    auto issue = [&](int kc, int buf) {
+    // the IDX-th DMA instruction of this wave for a stage; xsoff / wsoff: the stage's scalar offsets
+    auto issue_one = [&](auto IDX, int buf, unsigned xsoff, unsigned wsoff, int tapbit) {
+        constexpr int idx = decltype(IDX)::value;
         unsigned char *lx = lds + buf * STAGE, *lw = lx + BP * ROWB;
-        const int tapoff = (tr * a.W + ts) * a.C + tcc * BK;
-#pragma unroll
-        for (int i = 0; i < XL; i++) {
-            const bool ok = (unsigned)(rh[i] + tr) < (unsigned)a.H && (unsigned)(rw[i] + ts) < (unsigned)a.W;
-            dma16(ok ? xg + (rb[i] + tapoff) : zero, lx + (wave * XL + i) * 1024);
+        if constexpr (idx < XL) {
+            // sign-extended invalid-tap bit: all ones pushes the offset out of range -> zeros
+            const unsigned off = xo[idx] | (unsigned)__builtin_amdgcn_sbfe(xinv[idx], tapbit, 1);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(lx + (wave * XL + idx) * 1024),
+                                                     16, off, xsoff, 0, 0);
+        } else {
+            constexpr int wi = idx - XL;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void *)(lw + (wave * WL + wi) * 1024),
+                                                     16, wo[wi], wsoff, 0, 0);
         }
-#pragma unroll
-        for (int i = 0; i < WL; i++)
-            dma16(wb[i] >= 0 ? wg + (wb[i] + kc * BK) : zero, lw + (wave * WL + i) * 1024);
-        if (++tcc == cpt) { tcc = 0; if (++ts == a.S) { ts = 0; ++tr; } }
+    };
+    auto x_soff = [&]() { return (unsigned)((tr * a.W + ts) * a.C + tcc * BK) * ES; };
+    auto next_tap = [&]() { if (++tcc == cpt) { tcc = 0; ++tap; if (++ts == a.S) { ts = 0; ++tr; } } };
+    auto issue = [&](int kc, int buf) {
+        const unsigned xs = x_soff(), ws = (unsigned)(kc * BK) * ES;
+        static_for<L>([&](auto IDX) { issue_one(IDX, buf, xs, ws, tap); });
+        next_tap();
     };
 
     const Affine8 aff = load_affine<TC>(a, lane, c0 + wc * TC * 32);
+    ResidualRegs<T, TP, TC> resregs;
+    prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
     f32x16_t acc[TC][TP];
 #pragma unroll
     for (int i = 0; i < TC; i++)
@@ -138,8 +162,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
 
     const int lr = lane & 31, lh = lane >> 5;
     const int fsw = swz(lr);                       // tile row bases are multiples of 32: swizzle depends on lr only
-    // LDS byte offsets of this lane's fragment rows inside a stage, one per k-step
-    unsigned fx[KS], fw[KS];
+    unsigned fx[KS], fw[KS];                       // LDS byte offsets of this lane's fragment rows, per k-step
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
         const unsigned so = ((2 * ks + lh) ^ fsw) << 4;
@@ -153,37 +176,78 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
 
     // fragments of one k-step; two sets alternate so that the reads of step s+1 fly under the MFMAs of step s
     u32x4_t fa[2][TC], fb[2][TP];
-    auto read_frags = [&](auto SET, int ks_dyn_unused, unsigned ax, unsigned aw) {
+    auto read_frags = [&](auto SET, unsigned ax, unsigned aw) {
         constexpr int set = decltype(SET)::value;
         static_for<TC>([&](auto I) { lds_read16_async<decltype(I)::value * 32 * ROWB>(fa[set][decltype(I)::value], aw); });
         static_for<TP>([&](auto J) { lds_read16_async<decltype(J)::value * 32 * ROWB>(fb[set][decltype(J)::value], ax); });
     };
 
+#ifdef SOL_PHASE_TIMING
+    long long tw_ = 0, tb_ = 0, tc_ = 0, t0_ = 0, t1_ = 0, t2_ = 0, tstart_ = __builtin_readcyclecounter();
+#define PT(x) x = __builtin_readcyclecounter()
+#else
+#define PT(x)
+#endif
     for (int kc = 0; kc < nk; kc++) {
+        PT(t0_);
         // stage kc has landed once at most the (NS-2) stages issued after it are outstanding
         if (kc + NS - 2 < nk) wait_vmcnt<(NS - 2) * L>(); else wait_vmcnt<0>();
+        PT(t1_);
         __syncthreads();                           // ... for every wave; and stage kc-1 is no longer read
-        if (kc + NS - 1 < nk) issue(kc + NS - 1, (kc + NS - 1) % NS);
+        PT(t2_);
+        const bool more = kc + NS - 1 < nk;        // a stage to prefetch during this iteration?
+        const int nbuf = (kc + NS - 1) % NS, ntap = tap;
+        const unsigned nxs = x_soff(), nws = (unsigned)((kc + NS - 1) * BK) * ES;
         const unsigned sb = (kc % NS) * STAGE;
-        read_frags(std::integral_constant<int, 0>{}, 0, fx[0] + sb, fw[0] + sb);
+        read_frags(std::integral_constant<int, 0>{}, fx[0] + sb, fw[0] + sb);
         static_for<KS>([&](auto KSI) {
             constexpr int ks = decltype(KSI)::value, cur = ks & 1;
             if constexpr (ks + 1 < KS) {
-                read_frags(std::integral_constant<int, cur ^ 1>{}, 0, fx[ks + 1] + sb, fw[ks + 1] + sb);
+                read_frags(std::integral_constant<int, cur ^ 1>{}, fx[ks + 1] + sb, fw[ks + 1] + sb);
                 wait_lgkmcnt<TC + TP>();           // LDS returns in order: all but the newest TC+TP reads are done
             } else {
                 wait_lgkmcnt<0>();
             }
             static_for<TC>([&](auto I) { landed(fa[cur][decltype(I)::value]); });
             static_for<TP>([&](auto J) { landed(fb[cur][decltype(J)::value]); });
-#pragma unroll
-            for (int i = 0; i < TC; i++)
-#pragma unroll
-                for (int j = 0; j < TP; j++) Mma<T>::run(acc[i][j], fa[cur][i], fb[cur][j]);
+            // this k-step's share of the next stage's DMA, one instruction behind each of the first MFMAs
+            constexpr int dlo = ks * L / KS, dhi = (ks + 1) * L / KS;
+            static_for<TC * TP>([&](auto Q) {
+                constexpr int q = decltype(Q)::value, i = q / TP, j = q % TP;
+                Mma<T>::run(acc[i][j], fa[cur][i], fb[cur][j]);
+                if constexpr (dlo + q < dhi) {
+                    if (more) issue_one(std::integral_constant<int, dlo + q>{}, nbuf, nxs, nws, ntap);
+                }
+                if constexpr (q == TC * TP - 1) {  // more DMA than MFMAs in this step: the rest follows
+                    static_for<(dhi - dlo > TC * TP) ? dhi - dlo - TC * TP : 0>([&](auto E) {
+                        if (more) issue_one(std::integral_constant<int, dlo + TC * TP + decltype(E)::value>{}, nbuf, nxs, nws, ntap);
+                    });
+                }
+            });
         });
+        if (more) next_tap();
+#ifdef SOL_PHASE_TIMING
+        asm volatile("s_nop 0" ::: "memory");
+        tw_ += t1_ - t0_; tb_ += t2_ - t1_; PT(t0_); tc_ += t0_ - t2_;
+#endif
     }
-    __syncthreads();                               // every wave is done with the tiles: reuse LDS as strip
-    conv_epilogue<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, aff, LinearRows{a.P});
+#ifdef SOL_PHASE_TIMING
+    if (a.argmax == nullptr && a.prepool && lane == 0 && (blockIdx.x % 37) == 0 && wave < 4) {
+        long long *dbg = reinterpret_cast<long long *>(a.prepool) + ((blockIdx.x / 37) % 8 * 4 + wave) * 8;
+        dbg[0] = tw_; dbg[1] = tb_; dbg[2] = tstart_ - tentry_; dbg[3] = tc_; dbg[4] = __builtin_readcyclecounter() - tstart_; dbg[5] = nk;
+    }
+    const long long tepi_ = __builtin_readcyclecounter();
+#endif
+    __syncthreads();                               // every wave is done with the tiles: the ring becomes strips
+    conv_epilogue<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32,
+                             aff, LinearRows{a.P}, resregs);
+#ifdef SOL_PHASE_TIMING
+    if (a.argmax == nullptr && a.prepool && lane == 0 && (blockIdx.x % 37) == 0 && wave < 4) {
+        long long *dbg = reinterpret_cast<long long *>(a.prepool) + ((blockIdx.x / 37) % 8 * 4 + wave) * 8;
+        dbg[6] = __builtin_readcyclecounter() - tepi_; dbg[7] = __builtin_readcyclecounter() - tentry_;
+    }
+#endif
+#endif
 }
 
 template <typename T, int BP, int BC, int WP, int WC, int ROWB, int NS>
@@ -210,6 +274,12 @@ template <typename T> static sol_status launch_dma_typed(const ConvArgs &a, int 
         case D_128x128_128x3: return launch_dma_cfg<T, 128, 128, 2, 2, 128, 3>(a, st);
         case D_128x64_128x3: return launch_dma_cfg<T, 128, 64, 2, 2, 128, 3>(a, st);
         case D_64x64_128x3: return launch_dma_cfg<T, 64, 64, 2, 2, 128, 3>(a, st);
+        case D_128x128_64x5: return launch_dma_cfg<T, 128, 128, 2, 2, 64, 5>(a, st);
+        case D_64x64_128x4: return launch_dma_cfg<T, 64, 64, 2, 2, 128, 4>(a, st);
+        case D_256x128_128x3: return launch_dma_cfg<T, 256, 128, 2, 2, 128, 3>(a, st);
+        case D_256x128_64x4: return launch_dma_cfg<T, 256, 128, 2, 2, 64, 4>(a, st);
+        case D_128x256_64x4: return launch_dma_cfg<T, 128, 256, 2, 2, 64, 4>(a, st);
+        case D_64x64_64x8: return launch_dma_cfg<T, 64, 64, 2, 2, 64, 8>(a, st);
         default: SOL_FAIL(SOL_ERR_UNSUPPORTED, "unknown conv tile id %d", tile);
     }
 }
@@ -217,7 +287,9 @@ template <typename T> static sol_status launch_dma_typed(const ConvArgs &a, int 
 // Row bytes the tile id needs (the reduction chunk must divide Cin); 0 = not a DMA tile id.
 int dma_tile_row_bytes(int tile) {
     if (tile >= D_128x128_64x4 && tile <= D_64x128_64x4) return 64;
-    if (tile >= D_128x128_128x2 && tile <= D_64x64_128x3) return 128;
+    if (tile == D_128x128_64x5) return 64;
+    if (tile >= D_128x128_128x2 && tile <= D_256x128_128x3) return 128;
+    if (tile >= D_256x128_64x4 && tile <= D_64x64_64x8) return 64;
     return 0;
 }
 

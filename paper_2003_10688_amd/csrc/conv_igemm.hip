@@ -146,6 +146,8 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
     };
 
     const Affine8 aff = load_affine<TC>(a, lane, c0 + wc * TC * 32);
+    ResidualRegs<T, TP, TC> resregs;
+    prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
     f32x16_t acc[TC][TP];
 #pragma unroll
     for (int i = 0; i < TC; i++)
@@ -183,7 +185,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
     }
 
     static_assert((WP * WC) * 32 * (TC * 32 + 4) * 4 <= 2 * (BP + BC) * 128, "epilogue strip must fit in the tile buffers");
-    conv_epilogue<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, aff, LinearRows{a.P});
+    conv_epilogue<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, aff, LinearRows{a.P}, resregs);
 }
 
 // ---- launcher / tile table ------------------------------------------------------------------------
@@ -200,16 +202,24 @@ static sol_status launch_cfg(ConvArgs a, hipStream_t st) {
 // Planner heuristic: tile per layer shape, from per-layer timing sweeps on MI355X.  Small-Cin layers
 // use the element-gather kernel; everything else the LDS-DMA ring kernel with
 //   - 64x64 tiles (many resident workgroups) for narrow outputs and for layers with few tiles,
-//   - 128x128 tiles, 64-byte rows x 3 stages (3 workgroups per CU) for the big HBM-bound layers,
+//   - 128x64 / 64x64 tiles, 64-byte rows x 4 stages (3-5 workgroups per CU) for the big HBM-bound layers,
 //   - 128x128 tiles, 128-byte rows x 2 stages for the mid-sized, reuse-heavy layers.
+// The LDS-DMA kernel keeps one validity bit per filter tap in a 32-bit mask and addresses both
+// operands with 32-bit byte offsets.
+static bool dma_kernel_applies(const ConvArgs &a, int esize) {
+    const double xb = (double)a.N * a.H * a.W * a.C * esize + (double)(a.ph * a.W + a.pw) * a.C * esize;
+    return a.R * a.S <= 32 && xb < 4294967296.0 && (double)a.Cout * a.Kp * esize < 4294967296.0;
+}
+
 static int choose_tile(const ConvArgs &a, int esize) {
-    const bool dma128 = a.C % (128 / esize) == 0, dma64 = a.C % (64 / esize) == 0;
+    const bool dma_ok = dma_kernel_applies(a, esize);
+    const bool dma128 = dma_ok && a.C % (128 / esize) == 0, dma64 = dma_ok && a.C % (64 / esize) == 0;
     if (a.Cout <= 32 || !dma64) return a.C % (128 / esize) == 0 ? (a.Cout <= 32 ? T_128x32 : T_128x64)
                                                                  : (a.Cout <= 32 ? T_128x32 : T_128x64);
     const bool wide = a.R * a.S > 1;
     if (a.Cout <= 64) return (wide && dma128) ? D_64x64_128x3 : D_64x64_64x4;
     const long nt = (long)ceil_div(a.P, 128) * ceil_div(a.Cout, 128);
-    if (nt >= 1024) return D_128x128_64x3;
+    if (nt >= 1024) return a.res ? D_64x64_64x4 : D_128x64_64x4;   // HBM-bound: many small workgroups in flight
     if (nt >= 192) return dma128 ? D_128x128_128x2 : D_128x128_64x4;
     return dma128 ? D_64x64_128x3 : D_64x64_64x4;
 }
@@ -242,8 +252,9 @@ sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t
     if (a.P <= 0) return SOL_OK;   // empty batch: nothing to do
     if (tile_override == T_AUTO && stem_kernel_applies(a, dt)) return launch_conv_stem(a, st);
     if (const int rowb = dma_tile_row_bytes(tile_override)) {
-        SOL_REQUIRE(a.C % (rowb / (int)dtype_size(dt)) == 0 && a.Cout > 32, SOL_ERR_UNSUPPORTED,
-                    "conv tile %d needs Cin %% %d == 0 and Cout > 32", tile_override, rowb / (int)dtype_size(dt));
+        SOL_REQUIRE(a.C % (rowb / (int)dtype_size(dt)) == 0 && dma_kernel_applies(a, (int)dtype_size(dt)), SOL_ERR_UNSUPPORTED,
+                    "conv tile %d needs Cin %% %d == 0, at most 32 filter taps and tensors below 4 GB", tile_override,
+                    rowb / (int)dtype_size(dt));
         return launch_conv_dma(a, dt, tile_override, st);
     }
     if (dt == SOL_BF16) return launch_typed<bf16_t>(a, tile_override, st);

@@ -103,7 +103,10 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
                 Mma<bf16_t>::run(acc[i][0], fa, fb);
             }
         }
-        conv_epilogue<bf16_t, 1, 2>(a, acc, strip, wave, lane, wave * 32, 0, aff, StemRows{n, p0, q0, a.Ho, a.Wo});
+        const StemRows rows{n, p0, q0, a.Ho, a.Wo};
+        ResidualRegs<bf16_t, 1, 2> resregs;
+        prefetch_residual<bf16_t, 1, 2>(a, lane, wave * 32, 0, rows, resregs);
+        conv_epilogue<bf16_t, 1, 2>(a, acc, strip, wave, lane, wave * 32, 0, aff, rows, resregs);
     }
 }
 

@@ -12,7 +12,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsol_mi355.so")
+LIB_PATH = os.environ.get("SOL_MI355_LIB") or os.path.join(_HERE, "libsol_mi355.so")
 
 F32, BF16 = 0, 1
 ACT_NONE, ACT_RELU = 0, 1

@@ -107,7 +107,7 @@ def test_conv_no_bn_no_act_plain(sol, dt):
     assert (got < 0).any()                       # really no ReLU
 
 
-@pytest.mark.parametrize("tile", list(range(1, 9)) + list(range(11, 19)) + list(range(21, 25)))
+@pytest.mark.parametrize("tile", list(range(1, 9)) + list(range(11, 19)) + list(range(21, 28)) + [31, 32, 33])
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 def test_every_conv_tile(sol, dt, tile):
     rng = np.random.default_rng(100 + tile)
