@@ -71,6 +71,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
     static_assert(NW * 32 * (TC * 32 + 4) * 4 <= NS * STAGE, "epilogue strips must fit in the ring");
 
     __shared__ __align__(1024) unsigned char lds[NS * STAGE];
+    __shared__ __align__(256) unsigned char l2sink[NW * 256];   // write-only landing pad of the L2 warm-up loads
 
 #ifdef SOL_PHASE_TIMING
     const long long tentry_ = __builtin_readcyclecounter();
@@ -92,6 +93,20 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
     const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<unsigned char *>(static_cast<const unsigned char *>(a.x)) - bias, 0, (int)(xbytes + bias), 0x00020000);
     const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, (int)wbytes, 0x00020000);
+
+    // Warm this XCD's L2 with the layer's weights.  Inside a network the weights of a layer are cold when
+    // it starts, every workgroup streams the same rows in lock step, and each stage would stall on an
+    // HBM round trip; instead the workgroups of an XCD (blockIdx & 7) first touch one dword per
+    // 128-byte line of the whole packed weight array between them, all misses in flight at once.
+    {
+        const unsigned lines = wbytes >> 7, nx = gridDim.x >> 3;
+        const unsigned char *wbase = static_cast<const unsigned char *>(a.w);
+        // the touched dwords are dropped into a per-wave LDS sink (a load into a register would have to
+        // be waited for, a DMA does not)
+        for (unsigned l = (blockIdx.x >> 3) * (NW * 64) + tid; l < lines; l += nx * (NW * 64))
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wbase + ((size_t)l << 7)),
+                                             (__attribute__((address_space(3))) void *)(l2sink + wave * 256), 4, 0, 0);
+    }
 
     // ---- this lane's share of every stage: XL pixel rows and WL weight rows, one 16-byte slot each
     const int lslot = lane % SLOTS, lrow = lane / SLOTS;

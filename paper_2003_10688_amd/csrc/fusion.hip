@@ -61,17 +61,21 @@ template <> struct VecIO<float, 4> {
         const float4 f = *reinterpret_cast<const float4 *>(p);
         v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
     }
+    static __device__ __forceinline__ void unpack(const uint4 &u, float v[4]) {
+        v[0] = __uint_as_float(u.x); v[1] = __uint_as_float(u.y); v[2] = __uint_as_float(u.z); v[3] = __uint_as_float(u.w);
+    }
     static __device__ __forceinline__ void store(float *p, const float v[4]) {
         *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
     }
 };
 template <> struct VecIO<float, 1> {
+    static __device__ __forceinline__ void unpack(const uint4 &u, float v[1]) { v[0] = __uint_as_float(u.x); }
     static __device__ __forceinline__ void load(const float *p, float v[1]) { v[0] = *p; }
     static __device__ __forceinline__ void store(float *p, const float v[1]) { *p = v[0]; }
 };
 template <> struct VecIO<bf16_t, 8> {
-    static __device__ __forceinline__ void load(const bf16_t *p, float v[8]) {
-        const uint4 u = *reinterpret_cast<const uint4 *>(p);
+    static __device__ __forceinline__ void load(const bf16_t *p, float v[8]) { unpack(*reinterpret_cast<const uint4 *>(p), v); }
+    static __device__ __forceinline__ void unpack(const uint4 &u, float v[8]) {
         const uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
         for (int i = 0; i < 4; i++) {
@@ -87,6 +91,7 @@ template <> struct VecIO<bf16_t, 8> {
     }
 };
 template <> struct VecIO<bf16_t, 1> {
+    static __device__ __forceinline__ void unpack(const uint4 &u, float v[1]) { v[0] = bf16_to_f32((bf16_t)u.x); }
     static __device__ __forceinline__ void load(const bf16_t *p, float v[1]) { v[0] = bf16_to_f32(*p); }
     static __device__ __forceinline__ void store(bf16_t *p, const float v[1]) { *p = f32_to_bf16(v[0]); }
 };
@@ -144,12 +149,157 @@ __global__ void __launch_bounds__(256) pool_kernel(const PoolArgs a) {
     }
 }
 
+// Tiled variant for overlapping windows (kernel > stride): a workgroup owns a 4 x 8 block of output
+// pixels (all channels), so the rows and columns that neighbouring windows share are re-read from
+// its own L1, and consecutive workgroup ids -- which the hardware deals round-robin to the 8 XCDs --
+// are remapped so that every XCD works on one contiguous run of blocks: window halos shared between
+// blocks are then found in that XCD's L2 instead of being fetched from HBM once per XCD.
+// ARG: the argmax is wanted (max pool only); without it the maximum is a plain v_max per element.
+template <typename T, int V, bool ARG>
+__global__ void __launch_bounds__(256) pool_tiled_kernel(const PoolArgs a, int tiles_h, int tiles_w, int nblocks) {
+    constexpr int TH = 4, TW = 8;
+    const int per_xcd = (nblocks + 7) >> 3;
+    const int blk = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (blk >= nblocks) return;
+    const int tw = blk % tiles_w, t2 = blk / tiles_w;
+    const int th = t2 % tiles_h, n = t2 / tiles_h;
+    const int cg = a.C / V;
+    const T *__restrict__ x = static_cast<const T *>(a.x);
+    T *__restrict__ y = static_cast<T *>(a.y);
+    for (int it = threadIdx.x; it < TH * TW * cg; it += 256) {
+        const int g = it % cg, pix = it / cg;
+        const int p = th * TH + pix / TW, q = tw * TW + pix % TW;
+        if (p >= a.Ho || q >= a.Wo) continue;
+        float best[V];
+        int bi[V];
+#pragma unroll
+        for (int e = 0; e < V; e++) { best[e] = (!ARG && a.kind == SOL_POOL_MAX) ? -INFINITY : 0.f; bi[e] = -1; }
+        int cnt = 0;
+        for (int r = 0; r < a.kh; r++) {
+            const int ih = p * a.sh + r - a.ph;
+            if ((unsigned)ih >= (unsigned)a.H) continue;
+            for (int s = 0; s < a.kw; s++) {
+                const int iw = q * a.sw + s - a.pw;
+                if ((unsigned)iw >= (unsigned)a.W) continue;
+                float v[V];
+                VecIO<T, V>::load(x + (((long)n * a.H + ih) * a.W + iw) * a.C + g * V, v);
+                cnt++;
+                if (a.kind == SOL_POOL_MAX && ARG) {
+#pragma unroll
+                    for (int e = 0; e < V; e++)
+                        if (bi[e] < 0 || v[e] > best[e]) { best[e] = v[e]; bi[e] = ih * a.W + iw; }
+                } else if (a.kind == SOL_POOL_MAX) {
+#pragma unroll
+                    for (int e = 0; e < V; e++) best[e] = fmaxf(best[e], v[e]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < V; e++) best[e] += v[e];
+                }
+            }
+        }
+        if (a.kind == SOL_POOL_AVG) {
+            const float div = a.count_pad ? (float)(a.kh * a.kw) : (float)cnt;
+#pragma unroll
+            for (int e = 0; e < V; e++) best[e] = best[e] / div;
+        }
+        const long o = ((((long)n * a.Ho + p) * a.Wo + q) * cg + g) * V;
+        VecIO<T, V>::store(y + o, best);
+        if (ARG && a.argmax && a.kind == SOL_POOL_MAX) {
+#pragma unroll
+            for (int e = 0; e < V; e++) a.argmax[o + e] = bi[e];
+        }
+    }
+}
+
+// Compile-time window, unconditional loads: out-of-image taps read a clamped (valid) address and are
+// masked afterwards, so all KH*KW 16-byte loads of a thread are independent and in flight together --
+// with one load at a time the kernel is bound by memory latency, not bandwidth.
+template <typename T, int V, int KH, int KW, bool ARG>
+__global__ void __launch_bounds__(256) pool_window_kernel(const PoolArgs a, int tiles_h, int tiles_w, int nblocks) {
+    constexpr int TH = 4, TW = 8;
+    const int per_xcd = (nblocks + 7) >> 3;
+    const int blk = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    if (blk >= nblocks) return;
+    const int tw = blk % tiles_w, t2 = blk / tiles_w;
+    const int th = t2 % tiles_h, n = t2 / tiles_h;
+    const int cg = a.C / V;
+    const T *__restrict__ x = static_cast<const T *>(a.x);
+    T *__restrict__ y = static_cast<T *>(a.y);
+    for (int it = threadIdx.x; it < TH * TW * cg; it += 256) {
+        const int g = it % cg, pix = it / cg;
+        const int p = th * TH + pix / TW, q = tw * TW + pix % TW;
+        if (p >= a.Ho || q >= a.Wo) continue;
+        const int ih0 = p * a.sh - a.ph, iw0 = q * a.sw - a.pw;
+        const T *base = x + (long)n * a.H * a.W * a.C + g * V;
+        uint4 raw[KH * KW];
+        unsigned okmask = 0;
+#pragma unroll
+        for (int r = 0; r < KH; r++)
+#pragma unroll
+            for (int s = 0; s < KW; s++) {
+                const int ih = ih0 + r, iw = iw0 + s;
+                if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W) okmask |= 1u << (r * KW + s);
+                const int ch = min(max(ih, 0), a.H - 1), cw = min(max(iw, 0), a.W - 1);
+                raw[r * KW + s] = *reinterpret_cast<const uint4 *>(base + ((long)ch * a.W + cw) * a.C);
+            }
+        float best[V];
+        int bi[V];
+#pragma unroll
+        for (int e = 0; e < V; e++) { best[e] = (!ARG && a.kind == SOL_POOL_MAX) ? -INFINITY : 0.f; bi[e] = -1; }
+#pragma unroll
+        for (int k = 0; k < KH * KW; k++) {
+            const bool ok = (okmask >> k) & 1u;
+            float v[V];
+            VecIO<T, V>::unpack(raw[k], v);
+            if (a.kind == SOL_POOL_MAX && ARG) {
+                const int idx = (ih0 + k / KW) * a.W + iw0 + k % KW;
+#pragma unroll
+                for (int e = 0; e < V; e++)
+                    if (ok && (bi[e] < 0 || v[e] > best[e])) { best[e] = v[e]; bi[e] = idx; }
+            } else if (a.kind == SOL_POOL_MAX) {
+#pragma unroll
+                for (int e = 0; e < V; e++) best[e] = fmaxf(best[e], ok ? v[e] : -INFINITY);
+            } else {
+#pragma unroll
+                for (int e = 0; e < V; e++) best[e] += ok ? v[e] : 0.f;
+            }
+        }
+        if (a.kind == SOL_POOL_AVG) {
+            const float div = a.count_pad ? (float)(KH * KW) : (float)__builtin_popcount(okmask);
+#pragma unroll
+            for (int e = 0; e < V; e++) best[e] = best[e] / div;
+        }
+        const long o = ((((long)n * a.Ho + p) * a.Wo + q) * cg + g) * V;
+        VecIO<T, V>::store(y + o, best);
+        if (ARG && a.argmax && a.kind == SOL_POOL_MAX) {
+#pragma unroll
+            for (int e = 0; e < V; e++) a.argmax[o + e] = bi[e];
+        }
+    }
+}
+
 template <typename T, int V>
 static void launch_pool_t(const PoolArgs &a, hipStream_t st) {
     const long total = (long)a.N * a.Ho * a.Wo * (a.C / V);
     if (total <= 0) return;
     long blocks = (total + 255) / 256;
     if (blocks > 256L * 64) blocks = 256L * 64;
+    if (a.kh > a.sh || a.kw > a.sw) {             // overlapping windows: tiled, XCD-aware
+        const int tiles_h = ceil_div(a.Ho, 4), tiles_w = ceil_div(a.Wo, 8);
+        const int nb = a.N * tiles_h * tiles_w;
+        if (V > 1 && a.kh == 3 && a.kw == 3) {
+            if (a.argmax && a.kind == SOL_POOL_MAX)
+                hipLaunchKernelGGL((pool_window_kernel<T, V, 3, 3, true>), dim3((unsigned)(((nb + 7) / 8) * 8)), dim3(256), 0, st, a, tiles_h, tiles_w, nb);
+            else
+                hipLaunchKernelGGL((pool_window_kernel<T, V, 3, 3, false>), dim3((unsigned)(((nb + 7) / 8) * 8)), dim3(256), 0, st, a, tiles_h, tiles_w, nb);
+            return;
+        }
+        if (a.argmax && a.kind == SOL_POOL_MAX)
+            hipLaunchKernelGGL((pool_tiled_kernel<T, V, true>), dim3((unsigned)(((nb + 7) / 8) * 8)), dim3(256), 0, st, a, tiles_h, tiles_w, nb);
+        else
+            hipLaunchKernelGGL((pool_tiled_kernel<T, V, false>), dim3((unsigned)(((nb + 7) / 8) * 8)), dim3(256), 0, st, a, tiles_h, tiles_w, nb);
+        return;
+    }
     hipLaunchKernelGGL((pool_kernel<T, V>), dim3((unsigned)blocks), dim3(256), 0, st, a);
 }
 
