@@ -355,3 +355,123 @@ def network_forward(layers, params, x, bf16=False, return_all=False):
         outs.append(y)
         args.append(arg)
     return (outs, args) if return_all else outs[-1]
+
+
+# ------------------------------------------------------------------------ training step
+def _rnd(a, bf16):
+    return round_bf16(a) if bf16 else a
+
+
+def network_train_step(layers, params, x, labels, lr, mu, velocity=None, bf16=False, eps=1e-5):
+    """One training step of a layer list: forward with batch-statistics BN, softmax cross-entropy
+    (batch mean), full backward, SGD with momentum (v <- mu v + g ; w <- w - lr v).
+
+    Rounding points in bf16 mode (where the HIP path stores a tensor): the convolution output z that
+    the batch statistics are taken from, every layer output, every accumulated activation gradient
+    (a tensor with several consumers receives its contributions in descending consumer order, each
+    added to the stored value and stored again), dz of every BN; statistics, weight gradients,
+    master weights and velocities stay unrounded.  Fused pools are not part of the training path.
+
+    Returns a dict: loss, outs, grads (per layer: w, bias, gamma, beta), new_params, velocity,
+    stats (per layer: mean, var), dacts (stored gradient of every layer output).
+    """
+    x = _d(x)
+    n_layers = len(layers)
+    outs, saved = [], []
+    for i, l in enumerate(layers):
+        src = _src_of(i, l, outs, x)
+        sv = {}
+        if l["kind"] == "conv":
+            assert not l.get("pool"), "fused pool is not supported in training"
+            p = params[i]
+            z = conv2d(src, p["w"], p.get("bias"), (l["sh"], l["sw"]), (l["ph"], l["pw"]))
+            if l["bn"]:
+                z = _rnd(z, bf16)
+                y, mean, var = bn_train(z, p["gamma"], p["beta"], eps)
+                sv.update(z=z, mean=mean, var=var)
+            else:
+                y = z
+            if l.get("res", -1) >= 0:
+                y = add(y, outs[l["res"]])
+            if l["act"] == "relu":
+                y = relu(y)
+            y = _rnd(y, bf16)
+        elif l["kind"] == "pool":
+            y, arg = pool(src, l["pool"])
+            sv.update(arg=arg)
+            y = _rnd(y, bf16)
+        elif l["kind"] == "gap":
+            y = _rnd(gap(src), bf16)
+        elif l["kind"] == "linear":
+            y = linear(src.reshape(src.shape[0], -1), params[i]["w"], params[i].get("bias"))
+            if l.get("act") == "relu":
+                y = relu(y)
+            y = _rnd(y, bf16)
+        else:
+            raise ValueError(l["kind"])
+        outs.append(y)
+        saved.append(sv)
+
+    loss, dlogits = softmax_ce(outs[-1].reshape(outs[-1].shape[0], -1), labels)
+    dacts = [None] * n_layers
+    dacts[-1] = _rnd(dlogits.reshape(outs[-1].shape), bf16)
+
+    def contribute(t, c):
+        if t < 0:
+            return                      # gradient w.r.t. the network input is not needed
+        dacts[t] = _rnd(c, bf16) if dacts[t] is None else _rnd(add(dacts[t], c), bf16)
+
+    grads = [dict() for _ in layers]
+    for i in range(n_layers - 1, -1, -1):
+        l, p, sv = layers[i], params[i], saved[i]
+        s = l.get("src", -1)
+        t = (i - 1) if s == -1 else s
+        src = x if t < 0 else outs[t]
+        dy = dacts[i]
+        if dy is None:
+            continue
+        if l["kind"] == "linear":
+            g = relu_bwd(outs[i], dy) if l.get("act") == "relu" else dy
+            xin = src.reshape(src.shape[0], -1)
+            dx, dw, db = linear_bwd(xin, p["w"], g)
+            grads[i].update(w=dw, bias=db)
+            contribute(t, dx.reshape(src.shape))
+        elif l["kind"] == "gap":
+            contribute(t, gap_bwd(dy.reshape(dy.shape[0], dy.shape[1]), src.shape))
+        elif l["kind"] == "pool":
+            pd = l["pool"]
+            if pd["kind"] == "max":
+                contribute(t, maxpool_bwd(dy, sv["arg"], src.shape))
+            else:
+                contribute(t, avgpool_bwd(dy, src.shape, (pd["kh"], pd["kw"]), (pd["sh"], pd["sw"]),
+                                          (pd["ph"], pd["pw"]), bool(pd.get("count_pad", 1))))
+        elif l["kind"] == "conv":
+            g = relu_bwd(outs[i], dy) if l["act"] == "relu" else dy
+            if l.get("res", -1) >= 0:
+                contribute(l["res"], g)
+            if l["bn"]:
+                dz, dg, dbt = bn_train_bwd(sv["z"], g, p["gamma"], sv["mean"], sv["var"], eps)
+                grads[i].update(gamma=dg, beta=dbt)
+                dz = _rnd(dz, bf16)
+            else:
+                dz = g
+            dw, db = conv2d_wgrad(src, dz, p["w"].shape, (l["sh"], l["sw"]), (l["ph"], l["pw"]))
+            grads[i].update(w=dw)
+            if not l["bn"]:
+                grads[i].update(bias=db)
+            if t >= 0:
+                contribute(t, conv2d_dgrad(dz, p["w"], src.shape, (l["sh"], l["sw"]), (l["ph"], l["pw"])))
+
+    velocity = velocity if velocity is not None else [dict() for _ in layers]
+    new_params = []
+    for i, (p, g) in enumerate(zip(params, grads)):
+        q = dict(p)
+        for k, gk in g.items():
+            w = _d(p[k]).copy()
+            v = _d(velocity[i][k]).copy() if k in velocity[i] else np.zeros_like(w)
+            sgd(w, v, gk, lr, mu)
+            q[k] = w
+            velocity[i][k] = v
+        new_params.append(q)
+    return {"loss": loss, "outs": outs, "grads": grads, "new_params": new_params, "velocity": velocity,
+            "stats": [{k: sv[k] for k in ("mean", "var") if k in sv} for sv in saved], "dacts": dacts}

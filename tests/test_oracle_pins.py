@@ -407,3 +407,67 @@ def test_softmax_ce_and_sgd():
     g2 = R.standard_normal(10)
     orc.sgd(w, v, g2, 0.1, 0.9)
     assert np.allclose(v, 0.9 * g + g2) and np.allclose(w, w0 - 0.1 * g - 0.1 * (0.9 * g + g2))
+
+
+# ------------------------------------------------------------------------ training step
+def _tiny_resnet():
+    L = [wl.conv(8, 3, s=2, p=1), wl.pool("max", 3, 2, 1), wl.conv(8, 3, src=1),
+         wl.conv(16, 1, s=2, p=0, act="none", src=1), wl.conv(16, 3, s=2, src=2, res=3), wl.gap(), wl.linear(5)]
+    P = wl.make_params(L, 3, 123, bias_std=0.0)
+    return L, P
+
+
+def test_train_step_matches_autograd():
+    """Unrounded training step (batch-stat BN, residual, overlapping max pool, strided convs, CE loss)
+    against torch autograd in fp64: loss, every gradient, and the SGD-with-momentum update."""
+    import torch.nn.functional as F
+    L, P = _tiny_resnet()
+    x = wl.make_input((4, 3, 17, 19), 5)
+    lab = np.array([0, 3, 4, 1])
+    T = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    out = orc.network_train_step(L, P, x, lab, 0.1, 0.9)
+    tp = [{k: T(v).requires_grad_() for k, v in p.items() if isinstance(v, np.ndarray)} for p in P]
+    outs = []
+    for i, (l, p) in enumerate(zip(L, tp)):
+        s = l.get("src", -1)
+        t = (T(x) if i == 0 else outs[i - 1]) if s == -1 else outs[s]
+        if l["kind"] == "conv":
+            y = F.conv2d(t, p["w"], p["bias"], stride=(l["sh"], l["sw"]), padding=(l["ph"], l["pw"]))
+            if l["bn"]:
+                y = F.batch_norm(y, None, None, p["gamma"], p["beta"], True, 0.0, 1e-5)
+            if l["res"] >= 0:
+                y = y + outs[l["res"]]
+            if l["act"] == "relu":
+                y = F.relu(y)
+        elif l["kind"] == "pool":
+            y = F.max_pool2d(t, 3, 2, 1)
+        elif l["kind"] == "gap":
+            y = t.mean((2, 3))
+        else:
+            y = F.linear(t, p["w"], p["bias"])
+        outs.append(y)
+    loss = F.cross_entropy(outs[-1], torch.from_numpy(lab).long())
+    loss.backward()
+    assert abs(out["loss"] - loss.item()) < 1e-12
+    for i, (g, p) in enumerate(zip(out["grads"], tp)):
+        for k, v in g.items():
+            ref = p[k].grad.numpy()
+            assert np.abs(v - ref).max() <= 1e-12 * max(np.abs(ref).max(), 1.0), (i, k)
+            # first step from zero velocity: w1 = w0 - lr g ; second step uses v = mu g + g2
+            np.testing.assert_allclose(out["new_params"][i][k], p[k].detach().numpy() - 0.1 * ref, atol=1e-12)
+    out2 = orc.network_train_step(L, out["new_params"], x, lab, 0.1, 0.9, velocity=out["velocity"])
+    i, k = 2, "w"
+    v2 = 0.9 * out["grads"][i][k] + out2["grads"][i][k]
+    np.testing.assert_allclose(out2["new_params"][i][k], out["new_params"][i][k] - 0.1 * v2, atol=1e-12)
+
+
+def test_train_step_bf16_rounding_points():
+    """bf16 mode: every stored tensor lies on the bf16 grid, statistics and weight gradients do not."""
+    L, P = _tiny_resnet()
+    x = wl.to_bf16_grid(wl.make_input((4, 3, 17, 19), 5))
+    out = orc.network_train_step(L, P, x, np.array([0, 3, 4, 1]), 0.1, 0.9, bf16=True)
+    for t in out["outs"] + [d for d in out["dacts"] if d is not None]:
+        assert np.array_equal(t, orc.round_bf16(t))
+    assert not np.array_equal(out["grads"][2]["w"], orc.round_bf16(out["grads"][2]["w"]))
+    ref = orc.network_train_step(L, P, x, np.array([0, 3, 4, 1]), 0.1, 0.9)
+    assert abs(out["loss"] - ref["loss"]) < 2e-2
