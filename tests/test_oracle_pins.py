@@ -10,6 +10,7 @@ import torch
 import torch.nn.functional as F
 
 import oracle as orc
+from paper_2003_10688_amd import workloads as wl
 
 R = np.random.default_rng(7)
 T = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))  # noqa: E731
