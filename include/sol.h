@@ -176,6 +176,46 @@ sol_status sol_network_run_layer(sol_network *net, int layer, const void *x, voi
  * meaningful after a forward of a network created with SOL_NET_KEEP_ACTIVATIONS. */
 sol_status sol_network_layer_output(const sol_network *net, int layer, void *workspace, void **ptr);
 
+/* ---- training step (networks created with SOL_NET_TRAINING) ----------------------------------------
+ * The layer-wise training semantics are those of the framework the paper extends (Sec. V: the
+ * middleware inherits the framework's training loop; Sec. III: the forward layers above), with BN
+ * using batch statistics.  On such a network:
+ *   - fused pools are rejected at creation (the pool is a layer of its own), the last layer must produce
+ *     [n,1,1,classes] logits, and sol_network_set_params ignores mean/var (NULL allowed) and keeps fp32
+ *     master copies of w, gamma, beta, bias next to the packed weights, with zeroed velocities;
+ *   - sol_network_forward uses the batch statistics of each convolution output as stored (for bf16: after
+ *     rounding), keeps every layer output in the workspace and copies the logits to y.
+ *
+ * sol_network_backward: mean softmax cross-entropy of the logits left by the last forward against
+ * labels (device int32 [n], each in [0, classes); any other value makes the loss NaN), then the full
+ * backward pass.  *loss (device float, may be NULL) receives the loss.  Weight, gamma, beta and bias
+ * gradients are fp32; activation gradients are stored in the network dtype; a tensor with several
+ * consumers accumulates their contributions in descending layer order, the residual consumer of a
+ * layer before its convolution.  x, workspace: as passed to the forward.  Deterministic.
+ * SOL_ERR_UNSUPPORTED for inference networks. */
+sol_status sol_network_backward(sol_network *net, const void *x, const int32_t *labels, float *loss,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* v <- momentum * v + g ;  p <- p - lr * v  on every fp32 master parameter that received a gradient,
+ * then re-packs the weights the kernels read. */
+sol_status sol_network_sgd_step(sol_network *net, float lr, float momentum, void *hip_stream);
+
+/* Device address and element count of a layer's fp32 training tensors inside the bound parameter buffer
+ * (w and its gradient in framework layout [cout][cin][kh][kw]; the rest [cout]; mean / var: batch
+ * statistics of the last forward, var biased). */
+typedef enum sol_net_tensor {
+    SOL_NT_W = 0, SOL_NT_GAMMA = 1, SOL_NT_BETA = 2, SOL_NT_BIAS = 3, SOL_NT_GRAD_W = 4, SOL_NT_GRAD_GAMMA = 5,
+    SOL_NT_GRAD_BETA = 6, SOL_NT_GRAD_BIAS = 7, SOL_NT_MEAN = 8, SOL_NT_VAR = 9
+} sol_net_tensor;
+sol_status sol_network_tensor(const sol_network *net, int layer, int which, float **ptr, size_t *count);
+
+/* Device address (inside the workspace of the last forward) of the stored convolution output z of a
+ * convolution layer with BN: the tensor its batch statistics were taken from (conv-output shape). */
+sol_status sol_network_layer_preact(const sol_network *net, int layer, void *workspace, void **ptr);
+
+/* Device address (inside the workspace of the last backward) of the gradient w.r.t. a layer's output. */
+sol_status sol_network_layer_grad(const sol_network *net, int layer, void *workspace, void **ptr);
+
 #ifdef __cplusplus
 }
 #endif

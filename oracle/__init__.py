@@ -362,7 +362,7 @@ def _rnd(a, bf16):
     return round_bf16(a) if bf16 else a
 
 
-def network_train_step(layers, params, x, labels, lr, mu, velocity=None, bf16=False, eps=1e-5):
+def network_train_step(layers, params, x, labels, lr, mu, velocity=None, bf16=False, eps=1e-5, forced=None):
     """One training step of a layer list: forward with batch-statistics BN, softmax cross-entropy
     (batch mean), full backward, SGD with momentum (v <- mu v + g ; w <- w - lr v).
 
@@ -371,6 +371,10 @@ def network_train_step(layers, params, x, labels, lr, mu, velocity=None, bf16=Fa
     (a tensor with several consumers receives its contributions in descending consumer order, each
     added to the stored value and stored again), dz of every BN; statistics, weight gradients,
     master weights and velocities stay unrounded.  Fused pools are not part of the training path.
+
+    forced = {"outs": [...], "z": [...]} (entries may be None) replaces the stored forward tensors by the
+    given ones, layer by layer, before anything else reads them: the backward pass, which is linear in the
+    incoming gradient once the stored tensors are fixed, can then be compared on its own.
 
     Returns a dict: loss, outs, grads (per layer: w, bias, gamma, beta), new_params, velocity,
     stats (per layer: mean, var), dacts (stored gradient of every layer output).
@@ -387,6 +391,8 @@ def network_train_step(layers, params, x, labels, lr, mu, velocity=None, bf16=Fa
             z = conv2d(src, p["w"], p.get("bias"), (l["sh"], l["sw"]), (l["ph"], l["pw"]))
             if l["bn"]:
                 z = _rnd(z, bf16)
+                if forced is not None and forced["z"][i] is not None:
+                    z = _d(forced["z"][i]).reshape(z.shape)
                 y, mean, var = bn_train(z, p["gamma"], p["beta"], eps)
                 sv.update(z=z, mean=mean, var=var)
             else:
@@ -409,6 +415,8 @@ def network_train_step(layers, params, x, labels, lr, mu, velocity=None, bf16=Fa
             y = _rnd(y, bf16)
         else:
             raise ValueError(l["kind"])
+        if forced is not None and forced["outs"][i] is not None:
+            y = _d(forced["outs"][i]).reshape(y.shape)
         outs.append(y)
         saved.append(sv)
 

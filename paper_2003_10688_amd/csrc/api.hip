@@ -133,7 +133,18 @@ struct LayerPlan {
     size_t out_off, tmp_off;        // workspace offsets; out_off unused for the last layer
     int last_use;
     bool params_set;
+    // training networks only
+    size_t wT_off, master_off, vel_off, grad_off, vec_off;   // parameter buffer: flipped pack, fp32 master / velocity / gradient, per-channel arrays
+    size_t z_off, dact_off, arg_off;                          // workspace: conv output before BN, gradient of the output, pool winners
+    bool has_grad, need_dgrad, src_first, res_first, dilate;
+    sol_conv_desc dcd;                                        // data-gradient as a stride-1 convolution ...
+    sol_tensor_desc dzd;                                      // ... over dz (zero-inserted when the forward stride is > 1)
+    float eps;
 };
+
+// per-channel fp32 arrays of a trainable layer, each padded to 256 bytes
+enum { VEC_GAMMA, VEC_BETA, VEC_BIAS, VEC_V_GAMMA, VEC_V_BETA, VEC_V_BIAS, VEC_G_GAMMA, VEC_G_BETA, VEC_G_BIAS, VEC_MEAN,
+       VEC_VAR, VEC_INVSTD, VEC_COUNT };
 
 }  // namespace sol
 
@@ -144,6 +155,7 @@ struct sol_network {
     size_t param_bytes, ws_bytes;
     unsigned char *params;
     size_t params_size;
+    size_t dz_off, dil_off, part_off, loss_off;   // training: shared scratch inside the workspace
 };
 
 namespace sol {
@@ -187,6 +199,42 @@ struct Arena {
 
 static size_t tensor_bytes(const sol_tensor_desc &d) { return (size_t)d.n * d.h * d.w * d.c * dtype_size(d.dtype); }
 
+// Training: which layers receive a gradient, in which order a tensor's consumers contribute to it
+// (descending consumer index, residual before data-gradient), and the extra workspace.
+static sol_status plan_training(sol_network *net, Arena &ar) {
+    const int nl = (int)net->layers.size();
+    const sol_tensor_desc &lo = net->layers[nl - 1].out;
+    SOL_REQUIRE(lo.h == 1 && lo.w == 1, SOL_ERR_UNSUPPORTED, "training: the last layer must produce [n,1,1,classes] logits");
+    std::vector<char> seen(nl, 0);
+    seen[nl - 1] = 1;
+    size_t dz_max = 0, dil_max = 0, part_max = 0;
+    for (int i = nl - 1; i >= 0; i--) {
+        LayerPlan &lp = net->layers[i];
+        lp.has_grad = seen[i];
+        lp.dact_off = ar.alloc(tensor_bytes(lp.out));
+        const int kind = lp.L.kind;
+        if (kind == SOL_LAYER_POOL && lp.L.pool.kind == SOL_POOL_MAX)
+            lp.arg_off = ar.alloc((size_t)lp.out.n * lp.out.h * lp.out.w * lp.out.c * 4);
+        if (kind == SOL_LAYER_CONV || kind == SOL_LAYER_LINEAR) {
+            if (kind == SOL_LAYER_CONV && lp.L.has_bn) lp.z_off = ar.alloc(tensor_bytes(lp.conv_out));
+            dz_max = std::max(dz_max, tensor_bytes(lp.conv_out));
+            int ns; size_t pf;
+            wgrad_plan(lp.in, lp.cd, lp.conv_out.h, lp.conv_out.w, &ns, &pf);
+            const int rows = lp.conv_out.n * lp.conv_out.h * lp.conv_out.w;
+            part_max = std::max(part_max, std::max(pf * 4, (size_t)col_reduce_chunks(rows, nullptr) * 2 * lp.cd.cout * 4));
+            if (lp.dilate) dil_max = std::max(dil_max, tensor_bytes(lp.dzd));
+        }
+        if (!seen[i]) continue;
+        if (lp.res >= 0) { lp.res_first = !seen[lp.res]; seen[lp.res] = 1; }
+        if (lp.src >= 0) { lp.src_first = !seen[lp.src]; seen[lp.src] = 1; lp.need_dgrad = true; }
+    }
+    net->dz_off = ar.alloc(dz_max);
+    net->dil_off = ar.alloc(dil_max);
+    net->part_off = ar.alloc(part_max);
+    net->loss_off = ar.alloc(((size_t)net->input.n + 1) * 4);
+    return SOL_OK;
+}
+
 static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_layers) {
     const int dt = net->input.dtype;
     net->layers.resize(n_layers);
@@ -214,6 +262,8 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
                 lp.conv_out.w = out_size(lp.in.w, lp.cd.kw, lp.cd.sw, lp.cd.pw);
                 lp.conv_out.c = lp.cd.cout;
                 lp.out = lp.conv_out;
+                SOL_REQUIRE(!(net->training && L.pool.kind != SOL_POOL_NONE), SOL_ERR_UNSUPPORTED,
+                            "layer %d: training networks take the pool as a layer of its own", i);
                 if (L.pool.kind != SOL_POOL_NONE) {
                     SOL_TRY(check_pool(&L.pool));
                     lp.fuse_pool = pool_is_fusable(L.pool);
@@ -259,6 +309,26 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             lp.w_off = poff; poff += round_up(sol_packed_weight_bytes(&lp.cd, (sol_dtype)dt), 256);
             lp.scale_off = poff; poff += round_up((size_t)lp.cd.cout * 4, 256);
             lp.shift_off = poff; poff += round_up((size_t)lp.cd.cout * 4, 256);
+            if (net->training) {
+                const size_t wb = round_up((size_t)lp.cd.cout * lp.cd.cin * lp.cd.kh * lp.cd.kw * 4, 256);
+                lp.master_off = poff; poff += wb;
+                lp.vel_off = poff; poff += wb;
+                lp.grad_off = poff; poff += wb;
+                lp.vec_off = poff; poff += VEC_COUNT * round_up((size_t)lp.cd.cout * 4, 256);
+                if (lp.src >= 0) {
+                    SOL_REQUIRE(lp.cd.ph < lp.cd.kh && lp.cd.pw < lp.cd.kw, SOL_ERR_UNSUPPORTED,
+                                "layer %d: training needs padding smaller than the filter", i);
+                    // dx = stride-1 convolution of the zero-inserted dz with the flipped filter, padding k-1-p
+                    lp.dcd = sol_conv_desc{lp.cd.cin, lp.cd.cout, lp.cd.kh, lp.cd.kw, 1, 1, lp.cd.kh - 1 - lp.cd.ph,
+                                           lp.cd.kw - 1 - lp.cd.pw};
+                    lp.dzd = lp.conv_out;
+                    lp.dzd.h = lp.in.h + 2 * lp.cd.ph - lp.cd.kh + 1;
+                    lp.dzd.w = lp.in.w + 2 * lp.cd.pw - lp.cd.kw + 1;
+                    lp.dilate = lp.cd.sh > 1 || lp.cd.sw > 1;
+                    SOL_TRY(check_tensor(&lp.dzd, "zero-inserted gradient"));
+                    lp.wT_off = poff; poff += round_up(sol_packed_weight_bytes(&lp.dcd, (sol_dtype)dt), 256);
+                }
+            }
         }
         if (lp.src >= 0) net->layers[lp.src].last_use = i;
         if (lp.res >= 0) net->layers[lp.res].last_use = std::max(net->layers[lp.res].last_use, i);
@@ -270,12 +340,13 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
     for (int i = 0; i < n_layers; i++) {
         LayerPlan &lp = net->layers[i];
         if (lp.split_pool) lp.tmp_off = ar.alloc(tensor_bytes(lp.conv_out));
-        if (i + 1 < n_layers) lp.out_off = ar.alloc(tensor_bytes(lp.out));
+        if (i + 1 < n_layers || net->training) lp.out_off = ar.alloc(tensor_bytes(lp.out));
         if (lp.split_pool && !net->keep) ar.release(lp.tmp_off);
         if (!net->keep)
             for (int j = 0; j < i; j++)
                 if (net->layers[j].last_use == i && j + 1 < n_layers) ar.release(net->layers[j].out_off);
     }
+    if (net->training) SOL_TRY(plan_training(net, ar));
     net->ws_bytes = ar.top;
     return SOL_OK;
 }
@@ -358,13 +429,14 @@ sol_status sol_global_avgpool(const sol_tensor_desc *xd, const void *x, void *y,
 }
 
 // ---- network -----------------------------------------------------------------------------------------
+static float *vec_ptr(const sol_network *net, const LayerPlan &lp, int which);
+
 sol_status sol_network_create(const sol_layer *layers, int n_layers, const sol_tensor_desc *input, int flags,
                               sol_network **out) {
     const int training = flags & SOL_NET_TRAINING;
     SOL_REQUIRE(layers && out, SOL_ERR_NULL, "layers and out must not be NULL");
     SOL_REQUIRE(n_layers > 0, SOL_ERR_SHAPE, "empty layer list");
     SOL_TRY(check_tensor(input, "input"));
-    SOL_REQUIRE(!training, SOL_ERR_UNSUPPORTED, "training networks are not available in this build");
     sol_network *net = new (std::nothrow) sol_network();
     SOL_REQUIRE(net, SOL_ERR_HIP, "out of host memory");
     net->input = *input;
@@ -411,20 +483,163 @@ sol_status sol_network_set_params(sol_network *net, int layer, const float *w, c
     SOL_REQUIRE(net->params, SOL_ERR_WORKSPACE, "no parameter buffer bound (sol_network_bind_params)");
     SOL_REQUIRE(w, SOL_ERR_NULL, "w is NULL");
     const bool bn = lp.L.kind == SOL_LAYER_CONV && lp.L.has_bn;
-    SOL_REQUIRE(!bn || (gamma && beta && mean && var), SOL_ERR_NULL, "layer %d has batch-norm: gamma, beta, mean, var required", layer);
+    SOL_REQUIRE(!bn || (gamma && beta && (net->training || (mean && var))), SOL_ERR_NULL,
+                "layer %d has batch-norm: gamma, beta%s required", layer, net->training ? "" : ", mean, var");
     SOL_REQUIRE(bn || !(gamma || beta || mean || var), SOL_ERR_SHAPE, "layer %d has no batch-norm", layer);
     SOL_REQUIRE(aligned16(w) && aligned16(gamma) && aligned16(beta) && aligned16(mean) && aligned16(var) && aligned16(bias),
                 SOL_ERR_ALIGN, "device pointers must be 16-byte aligned");
     hipStream_t st = (hipStream_t)stream;
     SOL_TRY(launch_pack(lp.cd, net->input.dtype, w, net->params + lp.w_off, false, st));
+    if (net->training) {   // fp32 master copies, zero velocities, both packed orientations
+        const size_t wn = (size_t)lp.cd.cout * lp.cd.cin * lp.cd.kh * lp.cd.kw * 4, cb = (size_t)lp.cd.cout * 4;
+        SOL_HIP(hipMemcpyAsync(net->params + lp.master_off, w, wn, hipMemcpyDeviceToDevice, st));
+        SOL_HIP(hipMemsetAsync(net->params + lp.vel_off, 0, wn, st));
+        SOL_HIP(hipMemsetAsync(net->params + lp.vec_off, 0, VEC_COUNT * round_up(cb, 256), st));
+        if (bn) {
+            SOL_HIP(hipMemcpyAsync(vec_ptr(net, lp, VEC_GAMMA), gamma, cb, hipMemcpyDeviceToDevice, st));
+            SOL_HIP(hipMemcpyAsync(vec_ptr(net, lp, VEC_BETA), beta, cb, hipMemcpyDeviceToDevice, st));
+        }
+        if (bias) SOL_HIP(hipMemcpyAsync(vec_ptr(net, lp, VEC_BIAS), bias, cb, hipMemcpyDeviceToDevice, st));
+        if (lp.src >= 0) SOL_TRY(launch_pack_flip(lp.cd, net->input.dtype, w, net->params + lp.wT_off, st));
+        lp.eps = eps;
+        lp.params_set = true;
+        return SOL_OK;
+    }
     SOL_TRY(launch_fold(lp.cd.cout, gamma, beta, mean, var, bias, eps, reinterpret_cast<float *>(net->params + lp.scale_off),
                         reinterpret_cast<float *>(net->params + lp.shift_off), st));
     lp.params_set = true;
     return SOL_OK;
 }
 
+static float *vec_ptr(const sol_network *net, const LayerPlan &lp, int which) {
+    return reinterpret_cast<float *>(net->params + lp.vec_off + (size_t)which * round_up((size_t)lp.cd.cout * 4, 256));
+}
+
 static const void *layer_in(const sol_network *net, int idx, const void *x, const unsigned char *ws) {
     return idx < 0 ? x : static_cast<const void *>(ws + net->layers[idx].out_off);
+}
+
+// ---- training passes -----------------------------------------------------------------------------------
+// Forward with batch statistics: conv -> z (stored), statistics of the stored z, then BN + residual + act
+// in one elementwise pass.  Every output stays in the workspace for the backward pass.
+static sol_status train_forward(sol_network *net, const void *x, void *y, unsigned char *ws, hipStream_t st) {
+    const int nl = (int)net->layers.size(), dt = net->input.dtype;
+    float *part = reinterpret_cast<float *>(ws + net->part_off);
+    for (int i = 0; i < nl; i++) {
+        const LayerPlan &lp = net->layers[i];
+        const void *in = layer_in(net, lp.src, x, ws);
+        void *out = ws + lp.out_off;
+        switch (lp.L.kind) {
+            case SOL_LAYER_CONV:
+            case SOL_LAYER_LINEAR: {
+                const bool bn = lp.L.kind == SOL_LAYER_CONV && lp.L.has_bn;
+                const void *res = lp.res >= 0 ? layer_in(net, lp.res, x, ws) : nullptr;
+                const float *bias = vec_ptr(net, lp, VEC_BIAS);
+                if (!bn) {
+                    SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, nullptr, bias, res, lp.L.act, nullptr, out,
+                                            nullptr, nullptr, g_tile_override, st));
+                    break;
+                }
+                void *z = ws + lp.z_off;
+                SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, nullptr, bias, nullptr, SOL_ACT_NONE, nullptr, z,
+                                        nullptr, nullptr, g_tile_override, st));
+                const int rows = lp.conv_out.n * lp.conv_out.h * lp.conv_out.w, C = lp.cd.cout;
+                if (rows == 0) break;
+                SOL_TRY(launch_bn_stats(z, rows, C, dt, lp.eps, vec_ptr(net, lp, VEC_MEAN), vec_ptr(net, lp, VEC_VAR),
+                                        vec_ptr(net, lp, VEC_INVSTD), part, st));
+                SOL_TRY(launch_bn_apply(z, res, out, vec_ptr(net, lp, VEC_MEAN), vec_ptr(net, lp, VEC_INVSTD),
+                                        vec_ptr(net, lp, VEC_GAMMA), vec_ptr(net, lp, VEC_BETA), (long)rows * C, C,
+                                        lp.L.act == SOL_ACT_RELU, dt, st));
+                break;
+            }
+            case SOL_LAYER_POOL:
+                SOL_TRY(pool_impl(lp.in, in, lp.L.pool, out,
+                                  lp.L.pool.kind == SOL_POOL_MAX ? reinterpret_cast<int32_t *>(ws + lp.arg_off) : nullptr, st));
+                break;
+            case SOL_LAYER_GAP:
+                if (lp.in.n > 0) SOL_TRY(launch_gap(in, out, lp.in.n, lp.in.h * lp.in.w, lp.in.c, lp.in.dtype, st));
+                break;
+        }
+    }
+    const LayerPlan &ll = net->layers[nl - 1];
+    if (tensor_bytes(ll.out)) SOL_HIP(hipMemcpyAsync(y, ws + ll.out_off, tensor_bytes(ll.out), hipMemcpyDeviceToDevice, st));
+    return SOL_OK;
+}
+
+static sol_status train_backward(sol_network *net, const void *x, const int32_t *labels, float *loss, unsigned char *ws,
+                                 hipStream_t st) {
+    const int nl = (int)net->layers.size(), dt = net->input.dtype;
+    float *part = reinterpret_cast<float *>(ws + net->part_off);
+    float *row_loss = reinterpret_cast<float *>(ws + net->loss_off);
+    const LayerPlan &ll = net->layers[nl - 1];
+    if (ll.out.n == 0) return SOL_OK;
+    SOL_TRY(launch_softmax_ce(ws + ll.out_off, labels, ws + ll.dact_off, row_loss + 1, loss ? loss : row_loss, ll.out.n,
+                              ll.out.c, dt, st));
+    for (int i = nl - 1; i >= 0; i--) {
+        const LayerPlan &lp = net->layers[i];
+        if (!lp.has_grad) continue;
+        const void *in = layer_in(net, lp.src, x, ws);
+        const void *dy = ws + lp.dact_off;
+        void *dsrc = lp.src >= 0 ? static_cast<void *>(ws + net->layers[lp.src].dact_off) : nullptr;
+        switch (lp.L.kind) {
+            case SOL_LAYER_CONV:
+            case SOL_LAYER_LINEAR: {
+                const bool bn = lp.L.kind == SOL_LAYER_CONV && lp.L.has_bn;
+                const int relu = lp.L.act == SOL_ACT_RELU;
+                const int rows = lp.conv_out.n * lp.conv_out.h * lp.conv_out.w, C = lp.cd.cout;
+                const long total = (long)rows * C;
+                const void *yv = ws + lp.out_off;
+                void *dres = lp.res >= 0 ? static_cast<void *>(ws + net->layers[lp.res].dact_off) : nullptr;
+                const void *dz = ws + net->dz_off;
+                if (bn) {
+                    const void *z = ws + lp.z_off;
+                    SOL_TRY(launch_grad_col_sums(z, dy, yv, vec_ptr(net, lp, VEC_MEAN), vec_ptr(net, lp, VEC_INVSTD), rows, C,
+                                                 relu, dt, vec_ptr(net, lp, VEC_G_BETA), vec_ptr(net, lp, VEC_G_GAMMA), part, st));
+                    SOL_TRY(launch_act_bn_bwd(z, dy, yv, vec_ptr(net, lp, VEC_MEAN), vec_ptr(net, lp, VEC_INVSTD),
+                                              vec_ptr(net, lp, VEC_GAMMA), vec_ptr(net, lp, VEC_G_BETA),
+                                              vec_ptr(net, lp, VEC_G_GAMMA), ws + net->dz_off, dres, lp.res_first, total, C, relu,
+                                              1, rows, dt, st));
+                } else {
+                    if (relu || dres)
+                        SOL_TRY(launch_act_bn_bwd(nullptr, dy, yv, nullptr, nullptr, nullptr, nullptr, nullptr, ws + net->dz_off,
+                                                  dres, lp.res_first, total, C, relu, 0, rows, dt, st));
+                    else
+                        dz = dy;
+                    SOL_TRY(launch_grad_col_sums(nullptr, dz, nullptr, nullptr, nullptr, rows, C, 0, dt,
+                                                 vec_ptr(net, lp, VEC_G_BIAS), nullptr, part, st));
+                }
+                SOL_TRY(launch_wgrad(lp.in, in, lp.cd, dz, lp.conv_out.h, lp.conv_out.w,
+                                     reinterpret_cast<float *>(net->params + lp.grad_off), part, st));
+                if (lp.need_dgrad) {
+                    const void *g = dz;
+                    if (lp.dilate) {
+                        SOL_TRY(launch_dilate(dz, ws + net->dil_off, lp.conv_out.n, lp.conv_out.h, lp.conv_out.w, C, lp.dzd.h,
+                                              lp.dzd.w, lp.cd.sh, lp.cd.sw, dt, st));
+                        g = ws + net->dil_off;
+                    }
+                    SOL_TRY(conv_fused_impl(lp.dzd, g, lp.dcd, net->params + lp.wT_off, nullptr, nullptr,
+                                            lp.src_first ? nullptr : dsrc, SOL_ACT_NONE, nullptr, dsrc, nullptr, nullptr,
+                                            g_tile_override, st));
+                }
+                break;
+            }
+            case SOL_LAYER_POOL: {
+                if (!dsrc) break;
+                PoolArgs a;
+                const sol_pool_desc &pd = lp.L.pool;
+                a.x = nullptr; a.y = nullptr; a.argmax = reinterpret_cast<int32_t *>(ws + lp.arg_off);
+                a.N = lp.in.n; a.H = lp.in.h; a.W = lp.in.w; a.C = lp.in.c; a.Ho = lp.out.h; a.Wo = lp.out.w;
+                a.kh = pd.kh; a.kw = pd.kw; a.sh = pd.sh; a.sw = pd.sw; a.ph = pd.ph; a.pw = pd.pw;
+                a.kind = pd.kind; a.count_pad = pd.count_pad;
+                SOL_TRY(launch_pool_bwd(a, dy, dsrc, lp.src_first, dt, st));
+                break;
+            }
+            case SOL_LAYER_GAP:
+                if (dsrc) SOL_TRY(launch_gap_bwd(dy, dsrc, lp.in.n, lp.in.h * lp.in.w, lp.in.c, lp.src_first, dt, st));
+                break;
+        }
+    }
+    return SOL_OK;
 }
 
 static sol_status run_layers(sol_network *net, const void *x, void *y, void *workspace, size_t workspace_bytes,
@@ -442,6 +657,10 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
             SOL_REQUIRE(lp.params_set, SOL_ERR_WORKSPACE, "layer %d: parameters not set", i);
     }
     unsigned char *ws = static_cast<unsigned char *>(workspace);
+    if (net->training) {
+        SOL_REQUIRE(first == 0 && last == nl - 1, SOL_ERR_UNSUPPORTED, "training networks run whole passes only");
+        return train_forward(net, x, y, ws, st);
+    }
     for (int i = first; i <= last; i++) {
         const LayerPlan &lp = net->layers[i];
         const void *in = layer_in(net, lp.src, x, ws);
@@ -484,9 +703,92 @@ sol_status sol_network_run_layer(sol_network *net, int layer, const void *x, voi
 
 sol_status sol_network_layer_output(const sol_network *net, int layer, void *workspace, void **ptr) {
     SOL_REQUIRE(net && workspace && ptr, SOL_ERR_NULL, "net, workspace and ptr must not be NULL");
-    SOL_REQUIRE(layer >= 0 && layer + 1 < (int)net->layers.size(), SOL_ERR_SHAPE,
+    SOL_REQUIRE(layer >= 0 && layer + (net->training ? 0 : 1) < (int)net->layers.size(), SOL_ERR_SHAPE,
                 "layer %d has no workspace buffer (the last layer writes to y)", layer);
     *ptr = static_cast<unsigned char *>(workspace) + net->layers[layer].out_off;
+    return SOL_OK;
+}
+
+sol_status sol_network_backward(sol_network *net, const void *x, const int32_t *labels, float *loss, void *workspace,
+                                size_t workspace_bytes, void *stream) {
+    SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
+    SOL_REQUIRE(net->training, SOL_ERR_UNSUPPORTED, "network was not created with SOL_NET_TRAINING");
+    SOL_REQUIRE(x && labels && workspace, SOL_ERR_NULL, "x, labels and workspace must not be NULL");
+    SOL_REQUIRE(workspace_bytes >= net->ws_bytes, SOL_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, net->ws_bytes);
+    SOL_REQUIRE(aligned16(x) && aligned16(workspace) && (reinterpret_cast<uintptr_t>(labels) & 3u) == 0 &&
+                    (reinterpret_cast<uintptr_t>(loss) & 3u) == 0,
+                SOL_ERR_ALIGN, "x and workspace must be 16-byte aligned, labels and loss 4-byte aligned");
+    for (const auto &lp : net->layers)
+        if (lp.L.kind == SOL_LAYER_CONV || lp.L.kind == SOL_LAYER_LINEAR)
+            SOL_REQUIRE(lp.params_set, SOL_ERR_WORKSPACE, "parameters not set");
+    return train_backward(net, x, labels, loss, static_cast<unsigned char *>(workspace), (hipStream_t)stream);
+}
+
+sol_status sol_network_sgd_step(sol_network *net, float lr, float momentum, void *stream) {
+    SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
+    SOL_REQUIRE(net->training, SOL_ERR_UNSUPPORTED, "network was not created with SOL_NET_TRAINING");
+    SOL_REQUIRE(net->params, SOL_ERR_WORKSPACE, "no parameter buffer bound (sol_network_bind_params)");
+    hipStream_t st = (hipStream_t)stream;
+    for (const auto &lp : net->layers) {
+        if (!(lp.L.kind == SOL_LAYER_CONV || lp.L.kind == SOL_LAYER_LINEAR) || !lp.has_grad) continue;
+        SOL_REQUIRE(lp.params_set, SOL_ERR_WORKSPACE, "parameters not set");
+        const bool bn = lp.L.kind == SOL_LAYER_CONV && lp.L.has_bn;
+        float *w = reinterpret_cast<float *>(net->params + lp.master_off);
+        SOL_TRY(launch_sgd(w, reinterpret_cast<float *>(net->params + lp.vel_off),
+                           reinterpret_cast<const float *>(net->params + lp.grad_off),
+                           (long)lp.cd.cout * lp.cd.cin * lp.cd.kh * lp.cd.kw, lr, momentum, st));
+        if (bn) {
+            SOL_TRY(launch_sgd(vec_ptr(net, lp, VEC_GAMMA), vec_ptr(net, lp, VEC_V_GAMMA), vec_ptr(net, lp, VEC_G_GAMMA), lp.cd.cout, lr, momentum, st));
+            SOL_TRY(launch_sgd(vec_ptr(net, lp, VEC_BETA), vec_ptr(net, lp, VEC_V_BETA), vec_ptr(net, lp, VEC_G_BETA), lp.cd.cout, lr, momentum, st));
+        } else {
+            SOL_TRY(launch_sgd(vec_ptr(net, lp, VEC_BIAS), vec_ptr(net, lp, VEC_V_BIAS), vec_ptr(net, lp, VEC_G_BIAS), lp.cd.cout, lr, momentum, st));
+        }
+        SOL_TRY(launch_pack(lp.cd, net->input.dtype, w, net->params + lp.w_off, false, st));
+        if (lp.src >= 0) SOL_TRY(launch_pack_flip(lp.cd, net->input.dtype, w, net->params + lp.wT_off, st));
+    }
+    return SOL_OK;
+}
+
+sol_status sol_network_tensor(const sol_network *net, int layer, int which, float **ptr, size_t *count) {
+    SOL_REQUIRE(net && ptr && count, SOL_ERR_NULL, "net, ptr and count must not be NULL");
+    SOL_REQUIRE(net->training, SOL_ERR_UNSUPPORTED, "network was not created with SOL_NET_TRAINING");
+    SOL_REQUIRE(net->params, SOL_ERR_WORKSPACE, "no parameter buffer bound (sol_network_bind_params)");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    const LayerPlan &lp = net->layers[layer];
+    SOL_REQUIRE(lp.L.kind == SOL_LAYER_CONV || lp.L.kind == SOL_LAYER_LINEAR, SOL_ERR_SHAPE, "layer %d has no parameters", layer);
+    const size_t wn = (size_t)lp.cd.cout * lp.cd.cin * lp.cd.kh * lp.cd.kw;
+    switch (which) {
+        case SOL_NT_W: *ptr = reinterpret_cast<float *>(net->params + lp.master_off); *count = wn; break;
+        case SOL_NT_GRAD_W: *ptr = reinterpret_cast<float *>(net->params + lp.grad_off); *count = wn; break;
+        case SOL_NT_GAMMA: *ptr = vec_ptr(net, lp, VEC_GAMMA); *count = lp.cd.cout; break;
+        case SOL_NT_BETA: *ptr = vec_ptr(net, lp, VEC_BETA); *count = lp.cd.cout; break;
+        case SOL_NT_BIAS: *ptr = vec_ptr(net, lp, VEC_BIAS); *count = lp.cd.cout; break;
+        case SOL_NT_GRAD_GAMMA: *ptr = vec_ptr(net, lp, VEC_G_GAMMA); *count = lp.cd.cout; break;
+        case SOL_NT_GRAD_BETA: *ptr = vec_ptr(net, lp, VEC_G_BETA); *count = lp.cd.cout; break;
+        case SOL_NT_GRAD_BIAS: *ptr = vec_ptr(net, lp, VEC_G_BIAS); *count = lp.cd.cout; break;
+        case SOL_NT_MEAN: *ptr = vec_ptr(net, lp, VEC_MEAN); *count = lp.cd.cout; break;
+        case SOL_NT_VAR: *ptr = vec_ptr(net, lp, VEC_VAR); *count = lp.cd.cout; break;
+        default: SOL_FAIL(SOL_ERR_SHAPE, "unknown tensor id %d", which);
+    }
+    return SOL_OK;
+}
+
+sol_status sol_network_layer_preact(const sol_network *net, int layer, void *workspace, void **ptr) {
+    SOL_REQUIRE(net && workspace && ptr, SOL_ERR_NULL, "net, workspace and ptr must not be NULL");
+    SOL_REQUIRE(net->training, SOL_ERR_UNSUPPORTED, "network was not created with SOL_NET_TRAINING");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    const LayerPlan &lp = net->layers[layer];
+    SOL_REQUIRE(lp.L.kind == SOL_LAYER_CONV && lp.L.has_bn, SOL_ERR_SHAPE, "layer %d is not a convolution with BN", layer);
+    *ptr = static_cast<unsigned char *>(workspace) + lp.z_off;
+    return SOL_OK;
+}
+
+sol_status sol_network_layer_grad(const sol_network *net, int layer, void *workspace, void **ptr) {
+    SOL_REQUIRE(net && workspace && ptr, SOL_ERR_NULL, "net, workspace and ptr must not be NULL");
+    SOL_REQUIRE(net->training, SOL_ERR_UNSUPPORTED, "network was not created with SOL_NET_TRAINING");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    SOL_REQUIRE(net->layers[layer].has_grad, SOL_ERR_SHAPE, "layer %d receives no gradient", layer);
+    *ptr = static_cast<unsigned char *>(workspace) + net->layers[layer].dact_off;
     return SOL_OK;
 }
 

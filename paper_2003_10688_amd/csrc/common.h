@@ -138,4 +138,27 @@ sol_status launch_pack(const sol_conv_desc &cd, int dt, const float *w, void *pa
 sol_status launch_fold(int c, const float *gamma, const float *beta, const float *mean, const float *var,
                        const float *bias, float eps, float *scale, float *shift, hipStream_t st);
 
+// training step (train.hip); `part` is scratch for the two-stage reductions
+int col_reduce_chunks(int rows, int *rows_per_chunk);
+sol_status launch_bn_stats(const void *z, int rows, int C, int dt, float eps, float *mean, float *var, float *invstd,
+                           float *part, hipStream_t st);
+sol_status launch_bn_apply(const void *z, const void *res, void *y, const float *mean, const float *invstd,
+                           const float *gamma, const float *beta, long total, int C, int relu, int dt, hipStream_t st);
+sol_status launch_grad_col_sums(const void *z, const void *dy, const void *y, const float *mean, const float *invstd,
+                                int rows, int C, int relu, int dt, float *out0, float *out1, float *part, hipStream_t st);
+sol_status launch_act_bn_bwd(const void *z, const void *dy, const void *y, const float *mean, const float *invstd,
+                             const float *gamma, const float *dbeta, const float *dgamma, void *dz, void *dres,
+                             int res_first, long total, int C, int relu, int bn, int rows, int dt, hipStream_t st);
+sol_status launch_dilate(const void *dz, void *out, int N, int Ho, int Wo, int K, int Hd, int Wd, int sh, int sw, int dt,
+                         hipStream_t st);
+sol_status launch_pool_bwd(const PoolArgs &a, const void *dy, void *dx, int first, int dt, hipStream_t st);
+sol_status launch_gap_bwd(const void *dy, void *dx, int N, int HW, int C, int first, int dt, hipStream_t st);
+sol_status launch_softmax_ce(const void *logits, const int32_t *labels, void *dlogits, float *row_loss, float *loss, int N,
+                             int C, int dt, hipStream_t st);
+sol_status launch_sgd(float *w, float *v, const float *g, long n, float lr, float mu, hipStream_t st);
+sol_status launch_pack_flip(const sol_conv_desc &cd, int dt, const float *w, void *packed, hipStream_t st);
+void wgrad_plan(const sol_tensor_desc &xd, const sol_conv_desc &cd, int Ho, int Wo, int *nsplit, size_t *part_floats);
+sol_status launch_wgrad(const sol_tensor_desc &xd, const void *x, const sol_conv_desc &cd, const void *dz, int Ho, int Wo,
+                        float *dw, float *part, hipStream_t st);
+
 }  // namespace sol

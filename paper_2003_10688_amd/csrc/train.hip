@@ -1,0 +1,634 @@
+// Kernels of the training step: batch-statistics BN (forward statistics, apply, backward), the
+// softmax cross-entropy loss, the weight-gradient contraction, the data movement of the strided
+// data-gradient, pooling backward, and the SGD update.  The data-gradient contraction itself runs
+// on the forward convolution kernels with spatially flipped, transposed weights.
+//
+// Every reduction is split into fixed chunks whose partial results are summed in a fixed order by a
+// second launch, so results do not depend on scheduling (no floating-point atomics anywhere).
+#include <math.h>
+
+#include "conv_common.h"
+#include "vec_io.h"
+
+namespace sol {
+
+// ---- per-channel reductions over a [rows][C] tensor ----------------------------------------------
+// 256 threads = 64 channels x 4 row phases; a block reduces `rpc` rows and writes one partial pair.
+//   MODE 0: s0 = sum a
+//   MODE 1: s0 = sum (a - mean)^2
+//   MODE 2: g = relu ? (y > 0 ? b : 0) : b ;  s0 = sum g ;  s1 = sum g * (a - mean) * invstd  (a may be NULL)
+template <typename T, int MODE>
+__global__ void __launch_bounds__(256) col_reduce_kernel(const T *__restrict__ a, const T *__restrict__ b,
+                                                         const T *__restrict__ y, const float *__restrict__ mean,
+                                                         const float *__restrict__ invstd, float *__restrict__ part,
+                                                         int rows, int C, int rpc, int relu) {
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int c = blockIdx.y * 64 + tx;
+    const int r0 = blockIdx.x * rpc, r1 = min(rows, r0 + rpc);
+    float s0 = 0.f, s1 = 0.f;
+    if (c < C) {
+        const float m = (MODE >= 1 && mean) ? mean[c] : 0.f;
+        const float is = (MODE == 2 && invstd) ? invstd[c] : 0.f;
+        for (int r = r0 + ty; r < r1; r += 4) {
+            const size_t i = (size_t)r * C + c;
+            if (MODE == 0) {
+                s0 += Elem<T>::load(a + i);
+            } else if (MODE == 1) {
+                const float d = Elem<T>::load(a + i) - m;
+                s0 += d * d;
+            } else {
+                float g = Elem<T>::load(b + i);
+                if (relu && !(Elem<T>::load(y + i) > 0.f)) g = 0.f;
+                s0 += g;
+                if (a) s1 += g * ((Elem<T>::load(a + i) - m) * is);
+            }
+        }
+    }
+    __shared__ float red[2][4][64];
+    red[0][ty][tx] = s0;
+    red[1][ty][tx] = s1;
+    __syncthreads();
+    if (ty == 0 && c < C) {
+        s0 = ((red[0][0][tx] + red[0][1][tx]) + red[0][2][tx]) + red[0][3][tx];
+        s1 = ((red[1][0][tx] + red[1][1][tx]) + red[1][2][tx]) + red[1][3][tx];
+        part[((size_t)blockIdx.x * 2 + 0) * C + c] = s0;
+        part[((size_t)blockIdx.x * 2 + 1) * C + c] = s1;
+    }
+}
+
+// out0[c] = scale * sum_chunks part[chunk][0][c]; out1 likewise; with eps >= 0 also
+// inv[c] = 1 / sqrt(out0[c] + eps)   (out0 = biased variance then)
+__global__ void col_finalize_kernel(const float *__restrict__ part, int nchunks, int C, float scale,
+                                    float *__restrict__ out0, float *__restrict__ out1, float eps,
+                                    float *__restrict__ inv) {
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float s0 = 0.f, s1 = 0.f;
+    for (int k = 0; k < nchunks; k++) {
+        s0 += part[((size_t)k * 2 + 0) * C + c];
+        s1 += part[((size_t)k * 2 + 1) * C + c];
+    }
+    s0 *= scale;
+    s1 *= scale;
+    if (out0) out0[c] = s0;
+    if (out1) out1[c] = s1;
+    if (inv) inv[c] = 1.f / sqrtf(s0 + eps);
+}
+
+// ---- elementwise passes -----------------------------------------------------------------------------
+// y = act( gamma (z - mean) invstd + beta + res )        (BN with batch statistics, training forward)
+template <typename T, int V>
+__global__ void __launch_bounds__(256) bn_apply_kernel(const T *__restrict__ z, const T *__restrict__ res, T *__restrict__ y,
+                                                       const float *__restrict__ mean, const float *__restrict__ invstd,
+                                                       const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                       long nvec, int C, int relu) {
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+        const int c0 = (int)((i * V) % C);
+        float v[V], r[V];
+        VecIO<T, V>::load(z + i * V, v);
+        if (res) VecIO<T, V>::load(res + i * V, r);
+#pragma unroll
+        for (int e = 0; e < V; e++) {
+            float f = (v[e] - mean[c0 + e]) * invstd[c0 + e] * gamma[c0 + e] + beta[c0 + e];
+            if (res) f += r[e];
+            if (relu) f = fmaxf(f, 0.f);
+            v[e] = f;
+        }
+        VecIO<T, V>::store(y + i * V, v);
+    }
+}
+
+// Backward through act / residual / BN of one layer:
+//   g  = relu ? (y > 0 ? dy : 0) : dy
+//   dres (+)= g                                   (when the layer has a residual input)
+//   dz = gamma invstd (g - dbeta / M - xhat dgamma / M),   xhat = (z - mean) invstd      (BN)
+//   dz = g                                                                               (no BN)
+template <typename T, int V>
+__global__ void __launch_bounds__(256) act_bn_bwd_kernel(const T *__restrict__ z, const T *__restrict__ dy,
+                                                         const T *__restrict__ y, const float *__restrict__ mean,
+                                                         const float *__restrict__ invstd, const float *__restrict__ gamma,
+                                                         const float *__restrict__ dbeta, const float *__restrict__ dgamma,
+                                                         T *__restrict__ dz, T *dres, int res_first, long nvec, int C,
+                                                         int relu, int bn, float inv_m) {
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+        const int c0 = (int)((i * V) % C);
+        float g[V], t[V];
+        VecIO<T, V>::load(dy + i * V, g);
+        if (relu) {
+            VecIO<T, V>::load(y + i * V, t);
+#pragma unroll
+            for (int e = 0; e < V; e++)
+                if (!(t[e] > 0.f)) g[e] = 0.f;
+        }
+        if (dres) {
+            if (res_first) {
+                VecIO<T, V>::store(dres + i * V, g);
+            } else {
+                VecIO<T, V>::load(dres + i * V, t);
+#pragma unroll
+                for (int e = 0; e < V; e++) t[e] += g[e];
+                VecIO<T, V>::store(dres + i * V, t);
+            }
+        }
+        if (bn) {
+            VecIO<T, V>::load(z + i * V, t);
+#pragma unroll
+            for (int e = 0; e < V; e++) {
+                const float is = invstd[c0 + e];
+                const float xh = (t[e] - mean[c0 + e]) * is;
+                g[e] = gamma[c0 + e] * is * (g[e] - dbeta[c0 + e] * inv_m - xh * dgamma[c0 + e] * inv_m);
+            }
+        }
+        VecIO<T, V>::store(dz + i * V, g);
+    }
+}
+
+// Zero-insertion of dz for a strided convolution: out[n][h*sh][w*sw][k] = dz[n][h][w][k], zero elsewhere,
+// on an [N][Hd][Wd][K] grid; the data-gradient is then a stride-1 convolution over `out`.
+template <typename T, int V>
+__global__ void __launch_bounds__(256) dilate_kernel(const T *__restrict__ dz, T *__restrict__ out, int N, int Ho, int Wo,
+                                                     int K, int Hd, int Wd, int sh, int sw) {
+    const int kv = K / V;
+    const long total = (long)N * Hd * Wd * kv;
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const int k = (int)(i % kv);
+        long t = i / kv;
+        const int w = (int)(t % Wd); t /= Wd;
+        const int h = (int)(t % Hd);
+        const int n = (int)(t / Hd);
+        float v[V];
+#pragma unroll
+        for (int e = 0; e < V; e++) v[e] = 0.f;
+        if (h % sh == 0 && w % sw == 0 && h / sh < Ho && w / sw < Wo)
+            VecIO<T, V>::load(dz + ((((long)n * Ho + h / sh) * Wo + w / sw) * K + (long)k * V), v);
+        VecIO<T, V>::store(out + i * V, v);
+    }
+}
+
+// Pooling backward in gather form: an input pixel sums the gradients of the (few) windows that contain
+// it -- for max pooling those whose stored winner index names it -- in row-major window order.
+template <typename T, int V>
+__global__ void __launch_bounds__(256) pool_bwd_kernel(const PoolArgs a, const T *__restrict__ dy, T *dx, int first) {
+    const int cg = a.C / V;
+    const long total = (long)a.N * a.H * a.W * cg;
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const int g = (int)(i % cg);
+        long t = i / cg;
+        const int iw = (int)(t % a.W); t /= a.W;
+        const int ih = (int)(t % a.H);
+        const int n = (int)(t / a.H);
+        const int th = ih + a.ph - a.kh + 1, tw = iw + a.pw - a.kw + 1;
+        const int p_lo = th <= 0 ? 0 : (th + a.sh - 1) / a.sh, p_hi = min(a.Ho - 1, (ih + a.ph) / a.sh);
+        const int q_lo = tw <= 0 ? 0 : (tw + a.sw - 1) / a.sw, q_hi = min(a.Wo - 1, (iw + a.pw) / a.sw);
+        float sum[V];
+#pragma unroll
+        for (int e = 0; e < V; e++) sum[e] = 0.f;
+        for (int p = p_lo; p <= p_hi; p++)
+            for (int q = q_lo; q <= q_hi; q++) {
+                const long o = (((long)n * a.Ho + p) * a.Wo + q) * a.C + (long)g * V;
+                float d[V];
+                VecIO<T, V>::load(dy + o, d);
+                if (a.kind == SOL_POOL_MAX) {
+#pragma unroll
+                    for (int e = 0; e < V; e++)
+                        if (a.argmax[o + e] == ih * a.W + iw) sum[e] += d[e];
+                } else {
+                    int cnt = a.kh * a.kw;
+                    if (!a.count_pad) {
+                        const int h0 = max(p * a.sh - a.ph, 0), h1 = min(p * a.sh - a.ph + a.kh, a.H);
+                        const int w0 = max(q * a.sw - a.pw, 0), w1 = min(q * a.sw - a.pw + a.kw, a.W);
+                        cnt = (h1 - h0) * (w1 - w0);
+                    }
+                    const float inv = 1.f / (float)cnt;
+#pragma unroll
+                    for (int e = 0; e < V; e++) sum[e] += d[e] * inv;
+                }
+            }
+        if (!first) {
+            float old[V];
+            VecIO<T, V>::load(dx + i * V, old);
+#pragma unroll
+            for (int e = 0; e < V; e++) sum[e] += old[e];
+        }
+        VecIO<T, V>::store(dx + i * V, sum);
+    }
+}
+
+// dx[n][p][c] (+)= dy[n][c] / HW
+template <typename T, int V>
+__global__ void __launch_bounds__(256) gap_bwd_kernel(const T *__restrict__ dy, T *dx, int N, int HW, int C, int first) {
+    const int cg = C / V;
+    const long total = (long)N * HW * cg;
+    const float inv = 1.f / (float)HW;
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const int g = (int)(i % cg);
+        const int n = (int)(i / ((long)cg * HW));
+        float d[V], old[V];
+        VecIO<T, V>::load(dy + ((long)n * C + (long)g * V), d);
+        if (!first) VecIO<T, V>::load(dx + i * V, old);
+#pragma unroll
+        for (int e = 0; e < V; e++) d[e] = first ? d[e] * inv : old[e] + d[e] * inv;
+        VecIO<T, V>::store(dx + i * V, d);
+    }
+}
+
+// ---- softmax cross-entropy ------------------------------------------------------------------------------
+__device__ __forceinline__ float block_reduce(float v, float *sm, bool is_max) {
+    const int tid = threadIdx.x;
+    sm[tid] = v;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (tid < s) sm[tid] = is_max ? fmaxf(sm[tid], sm[tid + s]) : sm[tid] + sm[tid + s];
+        __syncthreads();
+    }
+    const float r = sm[0];
+    __syncthreads();
+    return r;
+}
+
+// One block per sample: row loss = logsumexp(l) - l[label]; dlogits = (softmax(l) - onehot) / N.
+// A label outside [0, C) makes that row's loss NaN.
+template <typename T>
+__global__ void __launch_bounds__(256) softmax_ce_kernel(const T *__restrict__ logits, const int32_t *__restrict__ labels,
+                                                         T *__restrict__ dlogits, float *__restrict__ row_loss, int N, int C) {
+    __shared__ float sm[256];
+    const int n = blockIdx.x, tid = threadIdx.x;
+    const T *l = logits + (long)n * C;
+    float mx = -INFINITY;
+    for (int c = tid; c < C; c += 256) mx = fmaxf(mx, Elem<T>::load(l + c));
+    mx = block_reduce(mx, sm, true);
+    float s = 0.f;
+    for (int c = tid; c < C; c += 256) s += expf(Elem<T>::load(l + c) - mx);
+    s = block_reduce(s, sm, false);
+    const int lab = labels[n];
+    const float inv_s = 1.f / s, inv_n = 1.f / (float)N;
+    for (int c = tid; c < C; c += 256) {
+        const float p = expf(Elem<T>::load(l + c) - mx) * inv_s;
+        Elem<T>::store(dlogits + (long)n * C + c, (p - (c == lab ? 1.f : 0.f)) * inv_n);
+    }
+    if (tid == 0) row_loss[n] = (lab >= 0 && lab < C) ? logf(s) + mx - Elem<T>::load(l + lab) : NAN;
+}
+
+__global__ void loss_mean_kernel(const float *__restrict__ row_loss, int N, float *__restrict__ loss) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        float s = 0.f;
+        for (int i = 0; i < N; i++) s += row_loss[i];
+        *loss = s / (float)N;
+    }
+}
+
+// ---- SGD with momentum ------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) sgd_kernel(float *__restrict__ w, float *__restrict__ v, const float *__restrict__ g,
+                                                  long n, float lr, float mu) {
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+        const float vel = mu * v[i] + g[i];
+        v[i] = vel;
+        w[i] -= lr * vel;
+    }
+}
+
+// Weights for the data-gradient: framework layout w[k][c][r][s] -> packed rows [c][((R-1-r)*S + (S-1-s))*K + k],
+// i.e. the packed weight of a convolution with K input and C output channels and the filter flipped.
+template <typename T>
+__global__ void pack_weights_flip_kernel(const float *__restrict__ w, T *__restrict__ out, int K, int C, int R, int S,
+                                         int Kp) {
+    const long total = (long)C * Kp;
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const int c = (int)(i / Kp), j = (int)(i % Kp);
+        float v = 0.f;
+        if (j < R * S * K) {
+            const int k = j % K, tap = j / K, s = S - 1 - tap % S, r = R - 1 - tap / S;
+            v = w[(((long)k * C + c) * R + r) * S + s];
+        }
+        Elem<T>::store(out + i, v);
+    }
+}
+
+// ---- weight gradient -------------------------------------------------------------------------------------
+// dW[k][r][s][c] = sum over output pixels of dz[pixel][k] * x[pixel shifted by tap (r,s)][c]: a GEMM whose
+// reduction runs over pixels, the slow axis of both NHWC operands.  A workgroup owns a 64 x 64 (k, c) block
+// of one tap and a contiguous range of pixel groups; MFMA fragments (16 bytes of consecutive pixels for one
+// channel) are gathered element-wise straight from global memory -- 32 lanes read 32 adjacent channels of one
+// pixel, so every load instruction touches two contiguous segments -- with out-of-range taps, channel tails
+// and row tails turned into zeros by the buffer range check.  Pixels are enumerated in groups of GP along an
+// output row (GP = elements per 16 bytes); each half-wave takes one group per step, so one step reduces
+// 2*GP pixels.  The four waves interleave steps and their accumulators are summed through LDS at the end;
+// the block then writes one fp32 partial [k][tap][c], and a second launch adds the partials in order.
+struct WgradArgs {
+    const void *x, *dz;
+    float *part;
+    int N, H, W, C, K, R, S, sh, sw, ph, pw, Ho, Wo;
+    int G, ngroups, nsteps, steps_per_split, nsplit, nkt, nct;
+    uint32_t x_bytes, dz_bytes;
+    FastDiv dG, dHo;
+};
+
+template <typename T> struct BufElem;
+template <> struct BufElem<bf16_t> {
+    static __device__ __forceinline__ uint32_t load(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+        return (uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)off, 0, 0);
+    }
+    static __device__ __forceinline__ uint4 pack(const uint32_t e[8]) {
+        return make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    }
+};
+template <> struct BufElem<float> {
+    static __device__ __forceinline__ uint32_t load(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+        return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0);
+    }
+    static __device__ __forceinline__ uint4 pack(const uint32_t e[4]) { return make_uint4(e[0], e[1], e[2], e[3]); }
+};
+
+template <typename T>
+__global__ void __launch_bounds__(256) wgrad_kernel(const WgradArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int GP = 16 / sizeof(T), ES = sizeof(T);
+    __shared__ float red[64][65];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, h = lane >> 5;
+    int bid = blockIdx.x;
+    const int kt = bid % a.nkt; bid /= a.nkt;
+    const int ct = bid % a.nct; bid /= a.nct;
+    const int tap = bid % (a.R * a.S);
+    const int split = bid / (a.R * a.S);
+    const int r = tap / a.S, s = tap % a.S;
+    const int k0 = kt * 64, c0 = ct * 64;
+
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, (int)a.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t zr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.dz), 0, (int)a.dz_bytes, 0x00020000);
+
+    f32x16_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+    const bool kok[2] = {k0 + lr < a.K, k0 + 32 + lr < a.K};
+    const bool cok[2] = {c0 + lr < a.C, c0 + 32 + lr < a.C};
+    const int s_begin = split * a.steps_per_split;
+    const int s_end = min(a.nsteps, s_begin + a.steps_per_split);
+    for (int t = s_begin + wave; t < s_end; t += 4) {
+        const uint32_t g = 2u * (uint32_t)t + (uint32_t)h;
+        uint32_t row, gq, n, op;
+        a.dG.divmod(g, row, gq);
+        a.dHo.divmod(row, n, op);
+        const int q0 = (int)gq * GP;
+        const bool gok = g < (uint32_t)a.ngroups;
+        const int ih = (int)op * a.sh + r - a.ph;
+        const bool rok = gok && (unsigned)ih < (unsigned)a.H;
+        const uint32_t zbase = ((row * (uint32_t)a.Wo + (uint32_t)q0) * (uint32_t)a.K + (uint32_t)(k0 + lr)) * ES;
+        const int iw0 = q0 * a.sw + s - a.pw;
+        const uint32_t xbase = (((n * (uint32_t)a.H + (uint32_t)ih) * (uint32_t)a.W + (uint32_t)iw0) * (uint32_t)a.C +
+                                (uint32_t)(c0 + lr)) * ES;
+        uint32_t ea[2][GP], eb[2][GP];
+#pragma unroll
+        for (int e = 0; e < GP; e++) {
+            const bool qok = gok && q0 + e < a.Wo;
+            const bool wok = rok && qok && (unsigned)(iw0 + e * a.sw) < (unsigned)a.W;
+#pragma unroll
+            for (int i = 0; i < 2; i++) {
+                const uint32_t oz = (qok && kok[i]) ? zbase + (uint32_t)(e * a.K + i * 32) * ES : 0xffffffffu;
+                const uint32_t ox = (wok && cok[i]) ? xbase + (uint32_t)(e * a.sw * a.C + i * 32) * ES : 0xffffffffu;
+                ea[i][e] = BufElem<T>::load(zr, oz);
+                eb[i][e] = BufElem<T>::load(xr, ox);
+            }
+        }
+        uint4 fa[2], fb[2];
+#pragma unroll
+        for (int i = 0; i < 2; i++) { fa[i] = BufElem<T>::pack(ea[i]); fb[i] = BufElem<T>::pack(eb[i]); }
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+            for (int j = 0; j < 2; j++) Mma<T>::run(acc[i][j], fa[i], fb[j]);
+    }
+
+    // accumulator register j of lane l holds D[row 8*(j/4) + 4*(l/32) + j%4][column l%32]; the waves add their
+    // blocks one after the other, so the sum order is fixed
+    for (int w = 0; w < 4; w++) {
+        if (wave == w) {
+#pragma unroll
+            for (int i = 0; i < 2; i++)
+#pragma unroll
+                for (int j = 0; j < 2; j++)
+#pragma unroll
+                    for (int e = 0; e < 16; e++) {
+                        float &d = red[i * 32 + 8 * (e / 4) + 4 * h + e % 4][j * 32 + lr];
+                        d = w == 0 ? acc[i][j][e] : d + acc[i][j][e];
+                    }
+        }
+        __syncthreads();
+    }
+    const size_t kstride = (size_t)a.R * a.S * a.C;
+    float *out = a.part + (size_t)split * a.K * kstride;
+    for (int i = tid; i < 64 * 64; i += 256) {
+        const int kk = i >> 6, cc = i & 63;
+        if (k0 + kk < a.K && c0 + cc < a.C)
+            out[(size_t)(k0 + kk) * kstride + (size_t)tap * a.C + c0 + cc] =
+                red[kk][cc];
+    }
+#endif
+}
+
+// dW[k][c][r][s] (framework layout) = sum over splits of part[split][k][r*S+s][c], added in split order
+__global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float *__restrict__ part, int nsplit, float *__restrict__ dw,
+                                                           int K, int C, int RS) {
+    const long total = (long)K * RS * C;
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        float s = 0.f;
+        for (int k = 0; k < nsplit; k++) s += part[(size_t)k * total + i];
+        const int c = (int)(i % C);
+        const long t = i / C;
+        const int tap = (int)(t % RS), ko = (int)(t / RS);
+        dw[((long)ko * C + c) * RS + tap] = s;
+    }
+}
+
+// ---- launchers ---------------------------------------------------------------------------------------------
+static inline int grid_for(long n) { return (int)std::min<long>((n + 255) / 256, 8192); }
+
+#define SOL_DISPATCH_TV(dt, C, STMT)                                       \
+    do {                                                                   \
+        if ((dt) == SOL_BF16) {                                            \
+            typedef bf16_t T;                                              \
+            if ((C) % 8 == 0) { constexpr int V = 8; STMT; } else { constexpr int V = 1; STMT; } \
+        } else {                                                           \
+            typedef float T;                                               \
+            if ((C) % 4 == 0) { constexpr int V = 4; STMT; } else { constexpr int V = 1; STMT; } \
+        }                                                                  \
+    } while (0)
+
+int col_reduce_chunks(int rows, int *rpc_out) {
+    int rpc = std::max(64, ceil_div(rows, 1024));
+    rpc = (rpc + 3) / 4 * 4;
+    if (rpc_out) *rpc_out = rpc;
+    return std::max(1, ceil_div(rows, rpc));
+}
+
+// mean / biased variance / 1/sqrt(var+eps) over the rows of z [rows][C]; part: 2*C*chunks floats
+sol_status launch_bn_stats(const void *z, int rows, int C, int dt, float eps, float *mean, float *var, float *invstd,
+                           float *part, hipStream_t st) {
+    int rpc;
+    const int nch = col_reduce_chunks(rows, &rpc);
+    const dim3 grid(nch, ceil_div(C, 64));
+    const int fg = ceil_div(C, 256);
+    if (dt == SOL_BF16) {
+        const bf16_t *p = static_cast<const bf16_t *>(z);
+        hipLaunchKernelGGL((col_reduce_kernel<bf16_t, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
+        hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(256), 0, st, part, nch, C, 1.f / rows, mean, nullptr, -1.f, nullptr);
+        hipLaunchKernelGGL((col_reduce_kernel<bf16_t, 1>), grid, dim3(256), 0, st, p, p, p, mean, nullptr, part, rows, C, rpc, 0);
+    } else {
+        const float *p = static_cast<const float *>(z);
+        hipLaunchKernelGGL((col_reduce_kernel<float, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
+        hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(256), 0, st, part, nch, C, 1.f / rows, mean, nullptr, -1.f, nullptr);
+        hipLaunchKernelGGL((col_reduce_kernel<float, 1>), grid, dim3(256), 0, st, p, p, p, mean, nullptr, part, rows, C, rpc, 0);
+    }
+    hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(256), 0, st, part, nch, C, 1.f / rows, var, nullptr, eps, invstd);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_bn_apply(const void *z, const void *res, void *y, const float *mean, const float *invstd,
+                           const float *gamma, const float *beta, long total, int C, int relu, int dt, hipStream_t st) {
+    SOL_DISPATCH_TV(dt, C, hipLaunchKernelGGL((bn_apply_kernel<T, V>), dim3(grid_for(total / V)), dim3(256), 0, st,
+                                              static_cast<const T *>(z), static_cast<const T *>(res), static_cast<T *>(y),
+                                              mean, invstd, gamma, beta, total / V, C, relu));
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+// s0 -> out0 = sum g, s1 -> out1 = sum g xhat  (z may be NULL: out1 unused)
+sol_status launch_grad_col_sums(const void *z, const void *dy, const void *y, const float *mean, const float *invstd,
+                                int rows, int C, int relu, int dt, float *out0, float *out1, float *part, hipStream_t st) {
+    int rpc;
+    const int nch = col_reduce_chunks(rows, &rpc);
+    const dim3 grid(nch, ceil_div(C, 64));
+    if (dt == SOL_BF16)
+        hipLaunchKernelGGL((col_reduce_kernel<bf16_t, 2>), grid, dim3(256), 0, st, static_cast<const bf16_t *>(z),
+                           static_cast<const bf16_t *>(dy), static_cast<const bf16_t *>(y), mean, invstd, part, rows, C, rpc, relu);
+    else
+        hipLaunchKernelGGL((col_reduce_kernel<float, 2>), grid, dim3(256), 0, st, static_cast<const float *>(z),
+                           static_cast<const float *>(dy), static_cast<const float *>(y), mean, invstd, part, rows, C, rpc, relu);
+    hipLaunchKernelGGL(col_finalize_kernel, dim3(ceil_div(C, 256)), dim3(256), 0, st, part, nch, C, 1.f, out0, out1, -1.f, nullptr);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_act_bn_bwd(const void *z, const void *dy, const void *y, const float *mean, const float *invstd,
+                             const float *gamma, const float *dbeta, const float *dgamma, void *dz, void *dres,
+                             int res_first, long total, int C, int relu, int bn, int rows, int dt, hipStream_t st) {
+    SOL_DISPATCH_TV(dt, C, hipLaunchKernelGGL((act_bn_bwd_kernel<T, V>), dim3(grid_for(total / V)), dim3(256), 0, st,
+                                              static_cast<const T *>(z), static_cast<const T *>(dy), static_cast<const T *>(y),
+                                              mean, invstd, gamma, dbeta, dgamma, static_cast<T *>(dz), static_cast<T *>(dres),
+                                              res_first, total / V, C, relu, bn, 1.f / rows));
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_dilate(const void *dz, void *out, int N, int Ho, int Wo, int K, int Hd, int Wd, int sh, int sw, int dt,
+                         hipStream_t st) {
+    const long total = (long)N * Hd * Wd * K;
+    SOL_DISPATCH_TV(dt, K, hipLaunchKernelGGL((dilate_kernel<T, V>), dim3(grid_for(total / V)), dim3(256), 0, st,
+                                              static_cast<const T *>(dz), static_cast<T *>(out), N, Ho, Wo, K, Hd, Wd, sh, sw));
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_pool_bwd(const PoolArgs &a, const void *dy, void *dx, int first, int dt, hipStream_t st) {
+    const long total = (long)a.N * a.H * a.W * a.C;
+    SOL_DISPATCH_TV(dt, a.C, hipLaunchKernelGGL((pool_bwd_kernel<T, V>), dim3(grid_for(total / V)), dim3(256), 0, st, a,
+                                                static_cast<const T *>(dy), static_cast<T *>(dx), first));
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_gap_bwd(const void *dy, void *dx, int N, int HW, int C, int first, int dt, hipStream_t st) {
+    const long total = (long)N * HW * C;
+    SOL_DISPATCH_TV(dt, C, hipLaunchKernelGGL((gap_bwd_kernel<T, V>), dim3(grid_for(total / V)), dim3(256), 0, st,
+                                              static_cast<const T *>(dy), static_cast<T *>(dx), N, HW, C, first));
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+// row_loss: N floats of scratch
+sol_status launch_softmax_ce(const void *logits, const int32_t *labels, void *dlogits, float *row_loss, float *loss, int N,
+                             int C, int dt, hipStream_t st) {
+    if (dt == SOL_BF16)
+        hipLaunchKernelGGL((softmax_ce_kernel<bf16_t>), dim3(N), dim3(256), 0, st, static_cast<const bf16_t *>(logits), labels,
+                           static_cast<bf16_t *>(dlogits), row_loss, N, C);
+    else
+        hipLaunchKernelGGL((softmax_ce_kernel<float>), dim3(N), dim3(256), 0, st, static_cast<const float *>(logits), labels,
+                           static_cast<float *>(dlogits), row_loss, N, C);
+    hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(64), 0, st, row_loss, N, loss);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_sgd(float *w, float *v, const float *g, long n, float lr, float mu, hipStream_t st) {
+    if (n <= 0) return SOL_OK;
+    hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(n)), dim3(256), 0, st, w, v, g, n, lr, mu);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_pack_flip(const sol_conv_desc &cd, int dt, const float *w, void *packed, hipStream_t st) {
+    // cd describes the forward convolution; the packed result belongs to {cout = cin, cin = cout, same filter}
+    const sol_conv_desc td{cd.cin, cd.cout, cd.kh, cd.kw, 1, 1, 0, 0};
+    const int Kp = packed_k(td, dt);
+    const long total = (long)cd.cin * Kp;
+    if (dt == SOL_BF16)
+        hipLaunchKernelGGL((pack_weights_flip_kernel<bf16_t>), dim3(grid_for(total)), dim3(256), 0, st, w,
+                           static_cast<bf16_t *>(packed), cd.cout, cd.cin, cd.kh, cd.kw, Kp);
+    else
+        hipLaunchKernelGGL((pack_weights_flip_kernel<float>), dim3(grid_for(total)), dim3(256), 0, st, w,
+                           static_cast<float *>(packed), cd.cout, cd.cin, cd.kh, cd.kw, Kp);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+// Split of the pixel reduction: enough workgroups to fill the chip, at least 16 steps each.
+void wgrad_plan(const sol_tensor_desc &xd, const sol_conv_desc &cd, int Ho, int Wo, int *nsplit, size_t *part_floats) {
+    const int GP = 16 / (int)dtype_size(xd.dtype);
+    const int G = ceil_div(Wo, GP);
+    const long ngroups = (long)xd.n * Ho * G;
+    const int nsteps = (int)((ngroups + 1) / 2);
+    const int tiles = ceil_div(cd.cout, 64) * ceil_div(cd.cin, 64) * cd.kh * cd.kw;
+    int ns = std::max(1, ceil_div(1024, tiles));
+    ns = std::min(ns, std::max(1, nsteps / 16));
+    *nsplit = ns;
+    *part_floats = (size_t)ns * cd.cout * cd.kh * cd.kw * cd.cin;
+}
+
+// dw: fp32 [cout][cin][kh][kw]; part: scratch of wgrad_plan's size
+sol_status launch_wgrad(const sol_tensor_desc &xd, const void *x, const sol_conv_desc &cd, const void *dz, int Ho, int Wo,
+                        float *dw, float *part, hipStream_t st) {
+    WgradArgs a;
+    memset(static_cast<void *>(&a), 0, sizeof(a));
+    const int ES = (int)dtype_size(xd.dtype), GP = 16 / ES;
+    const double xb = (double)xd.n * xd.h * xd.w * xd.c * ES, zb = (double)xd.n * Ho * Wo * cd.cout * ES;
+    SOL_REQUIRE(xb < 2147483648.0 && zb < 2147483648.0, SOL_ERR_UNSUPPORTED, "weight gradient: operand of 2 GiB or more");
+    a.x = x; a.dz = dz; a.part = part;
+    a.N = xd.n; a.H = xd.h; a.W = xd.w; a.C = xd.c; a.K = cd.cout; a.R = cd.kh; a.S = cd.kw;
+    a.sh = cd.sh; a.sw = cd.sw; a.ph = cd.ph; a.pw = cd.pw; a.Ho = Ho; a.Wo = Wo;
+    a.G = ceil_div(Wo, GP);
+    a.ngroups = xd.n * Ho * a.G;
+    a.nsteps = (a.ngroups + 1) / 2;
+    size_t pf;
+    wgrad_plan(xd, cd, Ho, Wo, &a.nsplit, &pf);
+    a.steps_per_split = ceil_div(a.nsteps, a.nsplit);
+    a.nkt = ceil_div(cd.cout, 64); a.nct = ceil_div(cd.cin, 64);
+    a.x_bytes = (uint32_t)xb; a.dz_bytes = (uint32_t)zb;
+    a.dG = FastDiv((uint32_t)a.G); a.dHo = FastDiv((uint32_t)Ho);
+    const int grid = a.nkt * a.nct * cd.kh * cd.kw * a.nsplit;
+    if (xd.dtype == SOL_BF16)
+        hipLaunchKernelGGL((wgrad_kernel<bf16_t>), dim3(grid), dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL((wgrad_kernel<float>), dim3(grid), dim3(256), 0, st, a);
+    const long total = (long)cd.cout * cd.kh * cd.kw * cd.cin;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for(total)), dim3(256), 0, st, part, a.nsplit, dw, cd.cout, cd.cin,
+                       cd.kh * cd.kw);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+}  // namespace sol

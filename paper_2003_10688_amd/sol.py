@@ -19,6 +19,7 @@ ACT_NONE, ACT_RELU = 0, 1
 POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
 LAYER_CONV, LAYER_POOL, LAYER_GAP, LAYER_LINEAR = 0, 1, 2, 3
 NET_TRAINING, NET_KEEP_ACTIVATIONS = 1, 2
+NT_W, NT_GAMMA, NT_BETA, NT_BIAS, NT_GRAD_W, NT_GRAD_GAMMA, NT_GRAD_BETA, NT_GRAD_BIAS, NT_MEAN, NT_VAR = range(10)
 
 STATUS = {0: "SOL_OK", 1: "SOL_ERR_NULL", 2: "SOL_ERR_SHAPE", 3: "SOL_ERR_DTYPE", 4: "SOL_ERR_ALIGN",
           5: "SOL_ERR_WORKSPACE", 6: "SOL_ERR_UNSUPPORTED", 7: "SOL_ERR_HIP"}
@@ -245,6 +246,7 @@ class Network:
 
     def __init__(self, layers, in_shape_nchw, dt, device="cuda:0", flags=0):
         self.layers, self.dt, self.device = layers, dt, device
+        self.training = bool(flags & NET_TRAINING)
         n, c, h, w = in_shape_nchw
         self.in_desc = TensorDesc(n, h, w, c, dt)
         self._h = C.c_void_p(0)
@@ -268,7 +270,8 @@ class Network:
                 continue
             w = dev_f32(p["w"], self.device)
             bn = l["kind"] == "conv" and l["bn"]
-            g, b, m, v = (dev_f32(p[k], self.device) for k in ("gamma", "beta", "mean", "var")) if bn else (None,) * 4
+            keys = ("gamma", "beta") if self.training else ("gamma", "beta", "mean", "var")
+            g, b, m, v = ([dev_f32(p[k], self.device) for k in keys] + [None, None])[:4] if bn else (None,) * 4
             bias = dev_f32(p.get("bias"), self.device)
             _check(lib().sol_network_set_params(self._h, C.c_int(i), _ptr(w), _ptr(g), _ptr(b), _ptr(m), _ptr(v),
                                                 _ptr(bias), C.c_float(p.get("eps", 1e-5)), _stream(stream)))
@@ -290,6 +293,42 @@ class Network:
         d = self.output_desc(layer)
         p = C.c_void_p(0)
         _check(lib().sol_network_layer_output(self._h, C.c_int(layer), _ptr(self.workspace), C.byref(p)))
+        off = p.value - self.workspace.data_ptr()
+        nbytes = d.n * d.h * d.w * d.c * (2 if self.dt == BF16 else 4)
+        return self.workspace[off:off + nbytes].view(torch_dtype(self.dt)).view(d.n, d.h, d.w, d.c)
+
+    # ---- training step (networks created with NET_TRAINING)
+    def backward(self, x, labels, stream=None):
+        """Loss + full backward on what the last forward left; labels: int32 device tensor [n].
+        Returns the device scalar holding the mean cross-entropy."""
+        if not hasattr(self, "loss"):
+            self.loss = torch.zeros(4, dtype=torch.float32, device=self.device)
+        _check(lib().sol_network_backward(self._h, _ptr(x), _ptr(labels), _ptr(self.loss), _ptr(self.workspace),
+                                          C.c_size_t(self.workspace.numel()), _stream(stream)))
+        return self.loss[:1]
+
+    def sgd_step(self, lr, momentum, stream=None):
+        _check(lib().sol_network_sgd_step(self._h, C.c_float(lr), C.c_float(momentum), _stream(stream)))
+
+    def tensor(self, layer, which):
+        """fp32 view (inside the parameter buffer) of a layer's master parameter, gradient or batch statistic."""
+        p, n = C.c_void_p(0), C.c_size_t(0)
+        _check(lib().sol_network_tensor(self._h, C.c_int(layer), C.c_int(which), C.byref(p), C.byref(n)))
+        off = p.value - self.param_buf.data_ptr()
+        return self.param_buf[off:off + 4 * n.value].view(torch.float32)
+
+    def layer_grad(self, layer):
+        """Gradient w.r.t. a layer's output after a backward (NHWC, network dtype)."""
+        return self._ws_view(layer, lib().sol_network_layer_grad)
+
+    def layer_preact(self, layer):
+        """Stored convolution output z of a conv+BN layer after a training forward (NHWC, network dtype)."""
+        return self._ws_view(layer, lib().sol_network_layer_preact)
+
+    def _ws_view(self, layer, fn):
+        d = self.output_desc(layer)
+        p = C.c_void_p(0)
+        _check(fn(self._h, C.c_int(layer), _ptr(self.workspace), C.byref(p)))
         off = p.value - self.workspace.data_ptr()
         nbytes = d.n * d.h * d.w * d.c * (2 if self.dt == BF16 else 4)
         return self.workspace[off:off + nbytes].view(torch_dtype(self.dt)).view(d.n, d.h, d.w, d.c)
