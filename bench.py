@@ -67,6 +67,8 @@ def main():
     ap.add_argument("--layer-reps", type=int, default=20, help="event-timed repetitions per layer for the roofline")
     ap.add_argument("--cpu-sample", type=int, default=8, help="images the CPU checker is timed on (0 = skip)")
     ap.add_argument("--layers", action="store_true", help="also print a per-layer table to stderr")
+    ap.add_argument("--train-steps", type=int, default=10,
+                    help="timed steps of the ResNet-18-shaped bs32 training step reported beside the headline (0 = skip)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no multi-GPU sharding or collectives); use --gpus 1",
@@ -160,6 +162,33 @@ def main():
         cpu = {"value": round(n / dt_s, 3), "unit": "images/s", "cores": oracle.threads(), "kind": "oracle",
                "sample": f"first {n} images of the batch, full network, one pass, {dt_s:.1f} s"}
 
+    # ---- training step (second workload, reported beside the headline number) -------------------------
+    training = None
+    if a.train_steps > 0:
+        del net
+        tw = wl.config(4)
+        tnet = sol.Network(tw.layers, tw.in_shape, sol.BF16, flags=sol.NET_TRAINING)
+        tnet.set_params(tw.params)
+        tx = sol.to_device_nhwc(tw.x, sol.BF16)
+        lab = torch.from_numpy(tw.labels).to("cuda:0")
+
+        def train_step():
+            tnet.forward(tx, stream)
+            tnet.backward(tx, lab, stream)
+            tnet.sgd_step(0.01, 0.9, stream)
+
+        for _ in range(3):
+            train_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.train_steps):
+            train_step()
+        torch.cuda.synchronize()
+        tms = (time.perf_counter() - t0) * 1e3 / a.train_steps
+        training = {"workload": f"{tw.name} batch {tw.in_shape[0]} input 3x224x224: forward (batch-stat BN) + loss + backward + SGD momentum",
+                    "images_per_s": round(tw.in_shape[0] / (tms * 1e-3), 1), "ms_per_step": round(tms, 3), "steps": a.train_steps,
+                    "loss_after": round(float(tnet.loss[0].cpu()), 4)}
+
     out = {
         "metric": "images/sec ResNet-50-shaped fwd bs64 on 1 GPU" if a.config == 3 and batch == 64 else f"images/sec {wk.name} fwd bs{batch} on 1 GPU",
         "value": round(imgs_per_s, 1), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -167,7 +196,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if wk.bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{wk.name} batch {batch} input 3x{wk.in_shape[2]}x{wk.in_shape[3]} (seeded synthetic, He-normal weights)",
                    "launches_per_step": len(wk.layers)},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "training_step": training,
     }
     print(json.dumps(out))
 

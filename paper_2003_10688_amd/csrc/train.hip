@@ -58,18 +58,24 @@ __global__ void __launch_bounds__(256) col_reduce_kernel(const T *__restrict__ a
 
 // out0[c] = scale * sum_chunks part[chunk][0][c]; out1 likewise; with eps >= 0 also
 // inv[c] = 1 / sqrt(out0[c] + eps)   (out0 = biased variance then)
-__global__ void col_finalize_kernel(const float *__restrict__ part, int nchunks, int C, float scale,
-                                    float *__restrict__ out0, float *__restrict__ out1, float eps,
-                                    float *__restrict__ inv) {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= C) return;
+__global__ void __launch_bounds__(256) col_finalize_kernel(const float *__restrict__ part, int nchunks, int C, float scale,
+                                                           float *__restrict__ out0, float *__restrict__ out1, float eps,
+                                                           float *__restrict__ inv) {
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + tx;
     float s0 = 0.f, s1 = 0.f;
-    for (int k = 0; k < nchunks; k++) {
-        s0 += part[((size_t)k * 2 + 0) * C + c];
-        s1 += part[((size_t)k * 2 + 1) * C + c];
-    }
-    s0 *= scale;
-    s1 *= scale;
+    if (c < C)
+        for (int k = ty; k < nchunks; k += 4) {
+            s0 += part[((size_t)k * 2 + 0) * C + c];
+            s1 += part[((size_t)k * 2 + 1) * C + c];
+        }
+    __shared__ float red[2][4][64];
+    red[0][ty][tx] = s0;
+    red[1][ty][tx] = s1;
+    __syncthreads();
+    if (ty != 0 || c >= C) return;
+    s0 = (((red[0][0][tx] + red[0][1][tx]) + red[0][2][tx]) + red[0][3][tx]) * scale;
+    s1 = (((red[1][0][tx] + red[1][1][tx]) + red[1][2][tx]) + red[1][3][tx]) * scale;
     if (out0) out0[c] = s0;
     if (out1) out1[c] = s1;
     if (inv) inv[c] = 1.f / sqrtf(s0 + eps);
@@ -459,7 +465,7 @@ static inline int grid_for(long n) { return (int)std::min<long>((n + 255) / 256,
     } while (0)
 
 int col_reduce_chunks(int rows, int *rpc_out) {
-    int rpc = std::max(64, ceil_div(rows, 1024));
+    int rpc = std::max(64, ceil_div(rows, 512));
     rpc = (rpc + 3) / 4 * 4;
     if (rpc_out) *rpc_out = rpc;
     return std::max(1, ceil_div(rows, rpc));
@@ -471,7 +477,7 @@ sol_status launch_bn_stats(const void *z, int rows, int C, int dt, float eps, fl
     int rpc;
     const int nch = col_reduce_chunks(rows, &rpc);
     const dim3 grid(nch, ceil_div(C, 64));
-    const int fg = ceil_div(C, 256);
+    const int fg = ceil_div(C, 64);
     if (dt == SOL_BF16) {
         const bf16_t *p = static_cast<const bf16_t *>(z);
         hipLaunchKernelGGL((col_reduce_kernel<bf16_t, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
@@ -509,7 +515,7 @@ sol_status launch_grad_col_sums(const void *z, const void *dy, const void *y, co
     else
         hipLaunchKernelGGL((col_reduce_kernel<float, 2>), grid, dim3(256), 0, st, static_cast<const float *>(z),
                            static_cast<const float *>(dy), static_cast<const float *>(y), mean, invstd, part, rows, C, rpc, relu);
-    hipLaunchKernelGGL(col_finalize_kernel, dim3(ceil_div(C, 256)), dim3(256), 0, st, part, nch, C, 1.f, out0, out1, -1.f, nullptr);
+    hipLaunchKernelGGL(col_finalize_kernel, dim3(ceil_div(C, 64)), dim3(256), 0, st, part, nch, C, 1.f, out0, out1, -1.f, nullptr);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }

@@ -194,8 +194,12 @@ def test_train_step_resnet18_reduced_bf16(sol):
     compound over 21 BN layers; at this reduced size the last stage normalises over 16 samples only, which
     amplifies them further: gate 5e-2).  Backward: the checker repeats its step with the library's stored
     forward tensors (z and every layer output) in place of its own, so that both sides differentiate the same
-    function at the same point; every activation gradient, parameter gradient and updated parameter must then
-    agree norm-wise within 2e-2."""
+    function at the same point.  What remains are bf16 stores of activation gradients that round the other way
+    on a small fraction of elements (2e-5 of them after one layer, 2e-2 after three in the short chains above,
+    each off by one to two ulps); the backward pass is linear, but every BN backward subtracts the projections
+    of g on 1 and on xhat, which shrinks the signal and not the perturbation, and the per-channel sums (dbeta,
+    dgamma) cancel heavily.  Over the 20 BN layers of this list the norm-wise error reaches ~1e-2 for activation
+    and weight gradients and ~2e-2 for dbeta, independent of batch and image size; the gate is 5e-2."""
     wk = wl.config(4, batch=4, hw=64)
     layers, params, x, labels = wk.layers, wk.params, wk.x, wk.labels
     _, got = gpu_train(sol, layers, params, x, labels, "bf16", lr=0.05)
@@ -205,7 +209,7 @@ def test_train_step_resnet18_reduced_bf16(sol):
     assert max(e) <= 5e-2, e
     ref = orc.network_train_step(layers, params, x, labels, 0.05, 0.9, bf16=True,
                                  forced={"outs": got[0]["outs"], "z": got[0]["z"]})
-    compare(got[0], ref, layers, "bf16", elementwise=False, tag="resnet18/bf16 backward at the stored forward state")
+    compare(got[0], ref, layers, "bf16", elementwise=False, tol=5e-2, tag="resnet18/bf16 backward at the stored forward state")
 
 
 def test_training_api_errors(sol):
