@@ -212,6 +212,103 @@ def test_train_step_resnet18_reduced_bf16(sol):
     compare(got[0], ref, layers, "bf16", elementwise=False, tol=5e-2, tag="resnet18/bf16 backward at the stored forward state")
 
 
+def test_train_step_full_size_at_stored_state(sol):
+    """The training configuration at its full size (ResNet-18-shaped, batch 32, 224x224, bf16), in the launch
+    configuration bench.py times.  The checker cannot repeat the whole step in seconds, so selected layers are
+    checked one by one on the tensors the library itself stored (inputs, z, outputs, output gradients): batch
+    statistics, BN + residual + ReLU output, z at sampled points, dgamma / dbeta, the complete weight gradient,
+    and -- for tensors with two consumers -- the accumulated activation gradient, contribution by contribution
+    in the documented order.  Covers the 3-channel stem, stride-1 and stride-2 3x3, the strided 1x1 projection,
+    the last 7x7-resolution block and the linear layer."""
+    wk = wl.config(4)
+    L, P = wk.layers, wk.params
+    d = sol.BF16
+    net = sol.Network(L, wk.in_shape, d, flags=sol.NET_TRAINING)
+    net.set_params(P)
+    xd = sol.to_device_nhwc(wk.x, d)
+    lab = torch.from_numpy(wk.labels).to("cuda:0")
+    net.forward(xd)
+    loss = float(net.backward(xd, lab).cpu()[0])
+    torch.cuda.synchronize()
+    out = lambda i: wk.x if i < 0 else sol.to_host_nchw(net.layer_output(i))            # noqa: E731
+    dact = lambda i: sol.to_host_nchw(net.layer_grad(i))                                 # noqa: E731
+    src_of = lambda i: (i - 1) if L[i].get("src", -1) == -1 else L[i]["src"]             # noqa: E731
+    rng = np.random.default_rng(5)
+
+    ref_loss, _ = orc.softmax_ce(out(len(L) - 1).reshape(wk.in_shape[0], -1), wk.labels)
+    assert abs(loss - ref_loss) <= 1e-4 * ref_loss, (loss, ref_loss)
+
+    memo = {}
+
+    def layer_state(i):
+        """Checker's backward of conv layer i from the stored tensors: g, dz (rounded), dgamma, dbeta, forward pieces."""
+        if i not in memo:
+            l, p = L[i], P[i]
+            y, dy, z = out(i), dact(i), sol.to_host_nchw(net.layer_preact(i))
+            ybn, mean, var = orc.bn_train(z, p["gamma"], p["beta"])
+            g = orc.relu_bwd(y, dy) if l["act"] == "relu" else np.asarray(dy, np.float64)
+            dz, dg, db = orc.bn_train_bwd(z, g, p["gamma"], mean, var)
+            memo[i] = dict(y=y, z=z, ybn=ybn, mean=mean, var=var, g=g, dz=orc.round_bf16(dz), dgamma=dg, dbeta=db)
+        return memo[i]
+
+    worst = {}
+
+    def gate(name, e, tol):
+        worst[name] = max(worst.get(name, 0.0), e)
+        assert e <= tol, (name, e)
+
+    for i in (0, 2, 6, 7, 20):
+        l, p, st = L[i], P[i], layer_state(i)
+        xin = out(src_of(i))
+        stride, pad = (l["sh"], l["sw"]), (l["ph"], l["pw"])
+        gate("mean", rel_err(net.tensor(i, sol.NT_MEAN).cpu().numpy(), st["mean"]), 1e-4)
+        gate("var", rel_err(net.tensor(i, sol.NT_VAR).cpu().numpy(), st["var"]), 1e-4)
+        yref = st["ybn"] + (out(l["res"]) if l["res"] >= 0 else 0.0)
+        yref = orc.round_bf16(orc.relu(yref) if l["act"] == "relu" else yref)
+        gate("y", rel_err(st["y"], yref), TOL["bf16"])
+        N, K, Ho, Wo = st["z"].shape
+        coords = np.stack([rng.integers(0, N, 400), rng.integers(0, K, 400), rng.integers(0, Ho, 400),
+                           rng.integers(0, Wo, 400)], 1).astype(np.int32)
+        coords[:8, 2:] = [[0, 0], [0, Wo - 1], [Ho - 1, 0], [Ho - 1, Wo - 1]] * 2          # padded corners
+        zs = orc.round_bf16(orc.conv2d_points(xin, p["w"], p.get("bias"), coords, stride, pad))
+        zg = st["z"][coords[:, 0], coords[:, 1], coords[:, 2], coords[:, 3]]
+        floor = np.sqrt(np.mean(st["z"].astype(np.float64) ** 2))
+        gate("z", float(np.max(np.abs(zg - zs) / np.maximum(np.abs(zs), floor))), TOL["bf16"])
+        gate("dgamma", rel_err(net.tensor(i, sol.NT_GRAD_GAMMA).cpu().numpy(), st["dgamma"]), 1e-3)
+        gate("dbeta", rel_err(net.tensor(i, sol.NT_GRAD_BETA).cpu().numpy(), st["dbeta"]), 1e-3)
+        dw, _ = orc.conv2d_wgrad(xin, st["dz"], p["w"].shape, stride, pad)
+        gate("dw", rel_err(net.tensor(i, sol.NT_GRAD_W).cpu().numpy().reshape(dw.shape), dw), TOL["bf16"])
+
+    def contributions(t):
+        """Gradient contributions to tensor t in the order the backward pass adds them."""
+        res = []
+        for i in range(len(L) - 1, t, -1):
+            if L[i]["kind"] != "conv":
+                continue
+            if L[i].get("res", -1) == t:
+                res.append(layer_state(i)["g"])
+            if src_of(i) == t:
+                l = L[i]
+                res.append(orc.conv2d_dgrad(layer_state(i)["dz"], P[i]["w"], out(t).shape, (l["sh"], l["sw"]), (l["ph"], l["pw"])))
+        return res
+
+    for t in (1, 5, 18):
+        cs = contributions(t)
+        assert len(cs) == 2
+        acc = orc.round_bf16(cs[0])
+        for c in cs[1:]:
+            acc = orc.round_bf16(acc + c)
+        gate(f"dact[{t}]", rel_err(dact(t), acc), TOL["bf16"])
+
+    i = len(L) - 1                                                     # linear layer
+    dy, xin = dact(i).reshape(wk.in_shape[0], -1), out(i - 1).reshape(wk.in_shape[0], -1)
+    dx, dw, db = orc.linear_bwd(xin, P[i]["w"], dy)
+    gate("linear dw", rel_err(net.tensor(i, sol.NT_GRAD_W).cpu().numpy().reshape(dw.shape), dw), 1e-3)
+    gate("linear db", rel_err(net.tensor(i, sol.NT_GRAD_BIAS).cpu().numpy(), db), 1e-3)
+    gate("linear dx", rel_err(dact(i - 1).reshape(dx.shape), orc.round_bf16(dx)), TOL["bf16"])
+    print("full-size training step, worst errors: " + ", ".join(f"{k} {v:.2e}" for k, v in worst.items()))
+
+
 def test_training_api_errors(sol):
     layers = [wl.conv(8, 3, pool=wl.pool_desc("max", 2, 2, 0)), wl.gap(), wl.linear(4)]
     with pytest.raises(sol.SolError) as e:                        # fused pool in a training network
