@@ -167,6 +167,18 @@ sol_status sol_network_set_params(sol_network *net, int layer, const float *w, c
 sol_status sol_network_forward(sol_network *net, const void *x, void *y, void *workspace,
                                size_t workspace_bytes, void *hip_stream);
 
+/* One forward pass recorded as a HIP graph (launch-bound inner loops: the ~56 launches of a ResNet-50-shaped
+ * pass replay as one submission).  sol_network_graph_create runs the pass once eagerly, then records the same
+ * launches with the given pointers baked in: x, y, workspace, the bound parameter buffer and the network must
+ * stay alive and unmoved while the graph is used (their CONTENTS may change between launches).  `hip_stream`
+ * must be a real stream (not NULL, which cannot be captured); inference networks only.
+ * sol_graph_launch enqueues one replay; launches on one stream run in order.  Records no memset nodes. */
+typedef struct sol_graph sol_graph;
+sol_status sol_network_graph_create(sol_network *net, const void *x, void *y, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream, sol_graph **out);
+sol_status sol_graph_launch(sol_graph *graph, void *hip_stream);
+void sol_graph_destroy(sol_graph *graph);
+
 /* Runs one layer only, on whatever its producers left in the workspace (profiling aid: lets a caller
  * bracket a single layer with events).  Same arguments as sol_network_forward. */
 sol_status sol_network_run_layer(sol_network *net, int layer, const void *x, void *y, void *workspace,

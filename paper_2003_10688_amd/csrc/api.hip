@@ -696,6 +696,50 @@ sol_status sol_network_forward(sol_network *net, const void *x, void *y, void *w
     return run_layers(net, x, y, workspace, workspace_bytes, 0, (int)net->layers.size() - 1, (hipStream_t)stream);
 }
 
+// ---- HIP graph of one forward pass -------------------------------------------------------------------------
+struct sol_graph {
+    hipGraphExec_t exec;
+};
+
+sol_status sol_network_graph_create(sol_network *net, const void *x, void *y, void *workspace, size_t workspace_bytes,
+                                    void *stream, sol_graph **out) {
+    SOL_REQUIRE(net && out, SOL_ERR_NULL, "net and out must not be NULL");
+    SOL_REQUIRE(!net->training, SOL_ERR_UNSUPPORTED, "graphs are recorded for inference networks only");
+    SOL_REQUIRE(stream, SOL_ERR_UNSUPPORTED, "a graph cannot be recorded on the NULL stream");
+    hipStream_t st = (hipStream_t)stream;
+    const int last = (int)net->layers.size() - 1;
+    // one eager pass first: validates the arguments and loads every kernel before the capture starts
+    SOL_TRY(run_layers(net, x, y, workspace, workspace_bytes, 0, last, st));
+    SOL_HIP(hipStreamSynchronize(st));
+    SOL_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+    const sol_status rs = run_layers(net, x, y, workspace, workspace_bytes, 0, last, st);
+    hipGraph_t graph = nullptr;
+    const hipError_t ce = hipStreamEndCapture(st, &graph);
+    if (rs != SOL_OK) { if (graph) hipGraphDestroy(graph); return rs; }
+    SOL_REQUIRE(ce == hipSuccess && graph, SOL_ERR_HIP, "hipStreamEndCapture: %s", hipGetErrorString(ce));
+    hipGraphExec_t exec = nullptr;
+    const hipError_t ie = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    hipGraphDestroy(graph);
+    SOL_REQUIRE(ie == hipSuccess && exec, SOL_ERR_HIP, "hipGraphInstantiate: %s", hipGetErrorString(ie));
+    sol_graph *g = new (std::nothrow) sol_graph();
+    if (!g) { hipGraphExecDestroy(exec); SOL_FAIL(SOL_ERR_HIP, "out of host memory"); }
+    g->exec = exec;
+    *out = g;
+    return SOL_OK;
+}
+
+sol_status sol_graph_launch(sol_graph *g, void *stream) {
+    SOL_REQUIRE(g, SOL_ERR_NULL, "graph is NULL");
+    SOL_HIP(hipGraphLaunch(g->exec, (hipStream_t)stream));
+    return SOL_OK;
+}
+
+void sol_graph_destroy(sol_graph *g) {
+    if (!g) return;
+    hipGraphExecDestroy(g->exec);
+    delete g;
+}
+
 sol_status sol_network_run_layer(sol_network *net, int layer, const void *x, void *y, void *workspace,
                                  size_t workspace_bytes, void *stream) {
     return run_layers(net, x, y, workspace, workspace_bytes, layer, layer, (hipStream_t)stream);

@@ -104,6 +104,7 @@ struct ConvArgs {
     int act, pool;           // pool: 0 none, 1 max 2x2/2, 2 avg 2x2/2
     int ntc;                 // number of channel tiles (set by the launcher)
     int ntiles;
+    int cpx;                 // > 0: each XCD owns cpx channel tiles (all pixel tiles); 0: a contiguous run of tiles
     FastDiv dw, dh;          // by Wo, Ho (by Wy, Hy with a fused pool): GEMM row -> pixel
 };
 
@@ -131,6 +132,8 @@ int dma_tile_row_bytes(int tile);
 sol_status launch_conv_dma(const ConvArgs &a, int dt, int tile, hipStream_t st);
 bool stem_kernel_applies(const ConvArgs &a, int dt);
 sol_status launch_conv_stem(const ConvArgs &a, hipStream_t st);
+bool linear_kernel_applies(const ConvArgs &a, int dt);
+sol_status launch_linear(const ConvArgs &a, int dt, hipStream_t st);
 sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t st);
 sol_status launch_pool(const PoolArgs &a, int dt, hipStream_t st);
 sol_status launch_gap(const void *x, void *y, int N, int HW, int C, int dt, hipStream_t st);

@@ -80,8 +80,18 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wp = wave % WP, wc = wave / WP;
 
-    const int per_xcd = (a.ntiles + 7) >> 3;       // XCD-aware tile order (see conv_igemm.hip)
-    const int tile = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
+    // XCD-aware tile order (workgroup ids go round-robin over the 8 XCDs, each with its own L2).  Usually an XCD
+    // takes a contiguous run of tiles: few pixel tiles, all their channel tiles, i.e. 1/8 of the input and all
+    // of the weights.  When the weights are the larger operand the split is by channel tile instead (cpx each):
+    // an XCD then reads 1/8 of the weights and all of the input, which is what fits its L2.
+    const int xcd = (int)(blockIdx.x & 7);
+    int tile;
+    if (a.cpx > 0) {
+        const int j = (int)(blockIdx.x >> 3);
+        tile = (j / a.cpx) * a.ntc + xcd * a.cpx + j % a.cpx;
+    } else {
+        tile = xcd * ((a.ntiles + 7) >> 3) + (int)(blockIdx.x >> 3);
+    }
     if (tile >= a.ntiles) return;
     const int p0 = (tile / a.ntc) * BP, c0 = (tile % a.ntc) * BC;
 
@@ -99,8 +109,11 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
     // HBM round trip; instead the workgroups of an XCD (blockIdx & 7) first touch one dword per
     // 128-byte line of the whole packed weight array between them, all misses in flight at once.
     {
-        const unsigned lines = wbytes >> 7, nx = gridDim.x >> 3;
-        const unsigned char *wbase = static_cast<const unsigned char *>(a.w);
+        const unsigned nx = gridDim.x >> 3;
+        // with the channel split only this XCD's rows of the packed weights
+        const unsigned slice = (unsigned)(a.cpx * BC * a.Kp) * ES, first = a.cpx > 0 ? min(wbytes, (unsigned)xcd * slice) : 0u;
+        const unsigned lines = (a.cpx > 0 ? min(slice, wbytes - first) : wbytes) >> 7;
+        const unsigned char *wbase = static_cast<const unsigned char *>(a.w) + first;
         // the touched dwords are dropped into a per-wave LDS sink (a load into a register would have to
         // be waited for, a DMA does not)
         for (unsigned l = (blockIdx.x >> 3) * (NW * 64) + tid; l < lines; l += nx * (NW * 64))
@@ -270,6 +283,8 @@ static sol_status launch_dma_cfg(ConvArgs a, hipStream_t st) {
     a.ntc = ceil_div(a.Cout, BC);
     a.ntiles = ceil_div(a.P, BP) * a.ntc;
     const int grid = ((a.ntiles + 7) / 8) * 8;
+    const double xbytes = (double)a.N * a.H * a.W * a.C * sizeof(T), wbytes = (double)a.Cout * a.Kp * sizeof(T);
+    a.cpx = (a.ntc % 8 == 0 && wbytes > xbytes && wbytes > 1.5 * 1048576) ? a.ntc / 8 : 0;
     hipLaunchKernelGGL((conv_dma_kernel<T, BP, BC, WP, WC, ROWB, NS>), dim3(grid), dim3(WP * WC * 64), 0, st, a);
     SOL_HIP(hipGetLastError());
     return SOL_OK;

@@ -251,6 +251,7 @@ template <typename T> static sol_status launch_typed(const ConvArgs &a, int tile
 sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t st) {
     if (a.P <= 0) return SOL_OK;   // empty batch: nothing to do
     if (tile_override == T_AUTO && stem_kernel_applies(a, dt)) return launch_conv_stem(a, st);
+    if (tile_override == T_AUTO && linear_kernel_applies(a, dt)) return launch_linear(a, dt, st);
     if (const int rowb = dma_tile_row_bytes(tile_override)) {
         SOL_REQUIRE(a.C % (rowb / (int)dtype_size(dt)) == 0 && dma_kernel_applies(a, (int)dtype_size(dt)), SOL_ERR_UNSUPPORTED,
                     "conv tile %d needs Cin %% %d == 0, at most 32 filter taps and tensors below 4 GB", tile_override,

@@ -69,6 +69,9 @@ def lib():
         L.sol_network_num_layers.argtypes = [C.c_void_p]
         L.sol_network_destroy.argtypes = [C.c_void_p]
         L.sol_network_destroy.restype = None
+        L.sol_graph_destroy.argtypes = [C.c_void_p]
+        L.sol_graph_destroy.restype = None
+        L.sol_graph_launch.argtypes = [C.c_void_p, C.c_void_p]
         L.sol_debug_set_conv_tile.restype = None
         _lib = L
     return _lib
@@ -283,6 +286,20 @@ class Network:
                                          C.c_size_t(self.workspace.numel()), _stream(stream)))
         return self.y
 
+    def graph(self, x, stream):
+        """Records one forward pass on `stream` (a torch.cuda.Stream other than the default one) as a HIP graph;
+        returns a callable that enqueues one replay on that stream and returns the output tensor."""
+        g = C.c_void_p(0)
+        _check(lib().sol_network_graph_create(self._h, _ptr(x), _ptr(self.y), _ptr(self.workspace),
+                                              C.c_size_t(self.workspace.numel()), _stream(stream), C.byref(g)))
+        self._graphs = getattr(self, "_graphs", []) + [g]
+        self._graph_keep = getattr(self, "_graph_keep", []) + [x]
+
+        def launch():
+            _check(lib().sol_graph_launch(g, _stream(stream)))
+            return self.y
+        return launch
+
     def run_layer(self, layer, x, stream=None):
         """Runs one layer on whatever its producers left in the workspace (profiling aid)."""
         _check(lib().sol_network_run_layer(self._h, C.c_int(layer), _ptr(x), _ptr(self.y), _ptr(self.workspace),
@@ -335,6 +352,8 @@ class Network:
 
     def __del__(self):
         try:
+            for g in getattr(self, "_graphs", []):
+                lib().sol_graph_destroy(g)
             if self._h:
                 lib().sol_network_destroy(self._h)
         except Exception:

@@ -107,6 +107,17 @@ def test_conv_no_bn_no_act_plain(sol, dt):
     assert (got < 0).any()                       # really no ReLU
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_conv_weight_heavy_layer(sol, dt):
+    """Weights larger than the input (and than 1.5 MB): the planner hands each XCD a set of channel tiles
+    instead of a run of pixel tiles; every output element is compared."""
+    rng = np.random.default_rng(77)
+    l, x, prm, r = make_block(sol, rng, dt, 3, 512, 7, 7, 1024, 3, 1, 1, res=True)
+    want, _, _ = orc.fused_conv(x, prm, l, r, bf16=(dt == "bf16"))
+    got, _, _ = run_block(sol, dt, l, x, prm, r)
+    assert rel_err(got, want) <= TOL[dt]
+
+
 @pytest.mark.parametrize("tile", list(range(1, 9)) + list(range(11, 19)) + list(range(21, 28)) + [31, 32, 33])
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 def test_every_conv_tile(sol, dt, tile):
@@ -201,7 +212,8 @@ def test_global_avgpool(sol, dt, shape):
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", [(64, 2048, 1000), (64, 64, 10), (5, 100, 33), (1, 7, 3)])
+@pytest.mark.parametrize("shape", [(64, 2048, 1000), (64, 64, 10), (5, 100, 33), (1, 7, 3), (130, 512, 1000), (200, 96, 40),
+                                   (1100, 64, 8)])
 def test_linear(sol, dt, shape):
     M, I, O = shape
     rng = np.random.default_rng(29)
@@ -427,3 +439,36 @@ def test_full_size_stem_pool_and_gap(sol):
     for n in (0, 37, 63):                                                   # whole images, exact
         want, warg = orc.maxpool(x[n:n + 1], (3, 3), (2, 2), (1, 1))
         assert np.array_equal(y[n:n + 1], want) and np.array_equal(arg[n:n + 1], warg)
+
+
+@pytest.mark.parametrize("cfg,batch,hw", [(1, 8, 32), (3, 2, 64)])
+def test_network_graph_replays(sol, cfg, batch, hw):
+    """A recorded forward pass, replayed several times with new input contents and eager work and
+    synchronisations between the replays, gives bit-identical results to the eager pass every time."""
+    wk = wl.config(cfg, batch=batch, hw=hw)
+    d = _dt(sol, wk.dtype)
+    net = sol.Network(wk.layers, wk.in_shape, d)
+    net.set_params(wk.params)
+    x = sol.to_device_nhwc(wk.x, d)
+    side = torch.cuda.Stream()
+    launch = net.graph(x, side)
+    rng = np.random.default_rng(3)
+    for it in range(4):
+        xi = _grid(rng.standard_normal(wk.in_shape), wk.dtype)
+        x.copy_(sol.to_device_nhwc(xi, d))
+        torch.cuda.synchronize()
+        eager = net.forward(x).clone()                     # eager pass on the current stream
+        torch.cuda.synchronize()
+        net.y.zero_()
+        junk = (torch.randn(1 << 16, device="cuda:0") * 2).sum()   # unrelated eager work between replays
+        torch.cuda.synchronize()
+        y = launch()
+        side.synchronize()
+        assert torch.equal(y, eager), f"replay {it} differs from the eager pass"
+        assert bool((y.float().abs().sum() > 0).item())
+        del junk
+    with pytest.raises(sol.SolError) as e:                       # the NULL stream cannot be captured
+        class _Null:
+            cuda_stream = 0
+        net.graph(x, _Null())
+    assert e.value.status == 6
