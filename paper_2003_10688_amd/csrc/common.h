@@ -126,10 +126,16 @@ enum {
     D_128x128_64x4 = 11, D_128x128_64x3 = 12, D_256x128_64x3 = 13, D_128x64_64x4 = 14, D_64x64_64x4 = 15,
     D_128x256_64x3 = 16, D_256x64_64x3 = 17, D_64x128_64x4 = 18,
     D_128x128_128x2 = 21, D_128x128_128x3 = 22, D_128x64_128x3 = 23, D_64x64_128x3 = 24,
-    D_128x128_64x5 = 25, D_64x64_128x4 = 26, D_256x128_128x3 = 27, D_256x128_64x4 = 31, D_128x256_64x4 = 32, D_64x64_64x8 = 33
+    D_128x128_64x5 = 25, D_64x64_128x4 = 26, D_256x128_128x3 = 27, D_256x128_64x4 = 31, D_128x256_64x4 = 32, D_64x64_64x8 = 33,
+    // H_*: 3x3 halo-in-LDS kernel (conv_halo.hip), suffix = patch DMA instructions per wave (s: single input chunk)
+    H_256x128_x5 = 41, H_128x128_x3 = 42, H_256x64_x5 = 43, H_256x64_x6s = 44, H_FIRST = 41, H_LAST = 59,
+    T_NO_HALO = 99   // automatic choice among the implicit-GEMM kernels only
 };
 int dma_tile_row_bytes(int tile);
 sol_status launch_conv_dma(const ConvArgs &a, int dt, int tile, hipStream_t st);
+bool halo_kernel_applies(const ConvArgs &a, int dt);
+int halo_choose_tile(const ConvArgs &a);
+sol_status launch_conv_halo(const ConvArgs &a, int tile, hipStream_t st);
 bool stem_kernel_applies(const ConvArgs &a, int dt);
 sol_status launch_conv_stem(const ConvArgs &a, hipStream_t st);
 bool linear_kernel_applies(const ConvArgs &a, int dt);

@@ -137,6 +137,20 @@ template <int TC> __device__ __forceinline__ Affine8 load_affine(const ConvArgs 
     return f;
 }
 
+// Branch-free variant for kernels whose launcher guarantees scale and shift are present and Cout % 8 == 0:
+// four unconditional 16-byte loads (lanes of a ragged channel tile read channel 0 and never use the values),
+// so that the compiler has no reason to wait for them before the first use in the epilogue.
+template <int TC> __device__ __forceinline__ Affine8 load_affine_unconditional(const ConvArgs &a, int lane, int cw) {
+    int cb = cw + (lane % (TC * 4)) * 8;
+    cb = cb + 8 <= a.Cout ? cb : 0;
+    const float4 s0 = *reinterpret_cast<const float4 *>(a.scale + cb), s1 = *reinterpret_cast<const float4 *>(a.scale + cb + 4);
+    const float4 h0 = *reinterpret_cast<const float4 *>(a.shift + cb), h1 = *reinterpret_cast<const float4 *>(a.shift + cb + 4);
+    Affine8 f;
+    f.sc[0] = s0.x; f.sc[1] = s0.y; f.sc[2] = s0.z; f.sc[3] = s0.w; f.sc[4] = s1.x; f.sc[5] = s1.y; f.sc[6] = s1.z; f.sc[7] = s1.w;
+    f.sf[0] = h0.x; f.sf[1] = h0.y; f.sf[2] = h0.z; f.sf[3] = h0.w; f.sf[4] = h1.x; f.sf[5] = h1.y; f.sf[6] = h1.z; f.sf[7] = h1.w;
+    return f;
+}
+
 // Residual rows of a wave's tile, fetched into registers ahead of the main loop (same lane -> 8-channel
 // mapping as the epilogue's output rows), so that their HBM latency overlaps the tile loads instead
 // of following them.  Only used without a fused pool and when rows are 16-byte aligned.
@@ -289,6 +303,64 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
         }
         wave_lds_fence();
     });
+}
+
+// Epilogue fast path for a wave tile that lies completely inside the output (all TP*32 rows below P, all TC*32
+// channels below Cout), Cout % 8 == 0 and no fused pool: same transposition through the wave-private strip as
+// conv_epilogue, but without per-row / per-channel range logic, with 32-bit element offsets (tensors are
+// limited to < 2^31 elements) and a branch-free activation.  RES: add the prefetched residual rows.
+template <typename T, int TP, int TC, bool RES>
+__device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16_t (&acc)[TC][TP], float *lds_f, int wave, int lane,
+                                                       int mw, int cw, const Affine8 &aff, const ResidualRegs<T, TP, TC> &pre) {
+    constexpr int ECH = TC * 32, ERS = ECH + 4, LPR = ECH / 8, RPS = 64 / LPR;
+    const int lr = lane & 31, lh = lane >> 5;
+    float *strip = lds_f + wave * (32 * ERS);
+    T *__restrict__ yg = static_cast<T *>(a.y);
+    const int ecg = lane % LPR, erow = lane / LPR;
+    const float lim = a.act == SOL_ACT_RELU ? 0.f : -__builtin_inff();
+    const unsigned cout = (unsigned)a.Cout;
+    unsigned off = (unsigned)(mw + erow) * cout + (unsigned)(cw + ecg * 8);    // element offset of this lane's first row
+    static_for<TP>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+#pragma unroll
+        for (int i = 0; i < TC; i++)
+#pragma unroll
+            for (int g = 0; g < 4; g++)
+                *reinterpret_cast<float4 *>(strip + lr * ERS + i * 32 + 8 * g + 4 * lh) =
+                    make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+        wave_lds_fence();
+#pragma unroll
+        for (int ps = 0; ps < 32 / RPS; ps++) {
+            const float *src = strip + (erow + ps * RPS) * ERS + ecg * 8;
+            const float4 lo = *reinterpret_cast<const float4 *>(src), hi = *reinterpret_cast<const float4 *>(src + 4);
+            const float r[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) v[e] = r[e] * aff.sc[e] + aff.sf[e];
+            if constexpr (RES) {
+                float rv[8];
+                pre.r[j][ps].get(rv);
+#pragma unroll
+                for (int e = 0; e < 8; e++) v[e] += rv[e];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; e++) v[e] = fmaxf(v[e], lim);
+            store_vec8<T>(yg + off, v);
+            off += RPS * cout;
+        }
+        wave_lds_fence();
+    });
+}
+
+// Chooses the interior fast path when the wave tile allows it (wave-uniform decision), else the general epilogue.
+template <typename T, int TP, int TC, typename RowMap>
+__device__ __forceinline__ void conv_epilogue_auto(const ConvArgs &a, f32x16_t (&acc)[TC][TP], float *lds_f, int wave, int lane,
+                                                   int mw, int cw, const Affine8 &aff, const RowMap &rowmap,
+                                                   const ResidualRegs<T, TP, TC> &pre) {
+    const bool interior = a.pool == 0 && (a.Cout & 7) == 0 && mw + TP * 32 <= a.P && cw + TC * 32 <= a.Cout && a.scale && a.shift;
+    if (interior && a.res == nullptr) conv_epilogue_interior<T, TP, TC, false>(a, acc, lds_f, wave, lane, mw, cw, aff, pre);
+    else if (interior && pre.on) conv_epilogue_interior<T, TP, TC, true>(a, acc, lds_f, wave, lane, mw, cw, aff, pre);
+    else conv_epilogue<T, TP, TC>(a, acc, lds_f, wave, lane, mw, cw, aff, rowmap, pre);
 }
 
 }  // namespace sol

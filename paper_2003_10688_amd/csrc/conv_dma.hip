@@ -177,9 +177,6 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
         next_tap();
     };
 
-    const Affine8 aff = load_affine<TC>(a, lane, c0 + wc * TC * 32);
-    ResidualRegs<T, TP, TC> resregs;
-    prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
     f32x16_t acc[TC][TP];
 #pragma unroll
     for (int i = 0; i < TC; i++)
@@ -201,6 +198,14 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
 #pragma unroll
     for (int s = 0; s < NS - 1; s++)
         if (s < nk) issue(s, s);
+
+    // Epilogue operands behind the first DMAs: the compiler waits for the scale / shift loads where their two code
+    // paths merge, and ahead of the DMAs that wait would put a whole memory round trip in front of the first tile
+    // load.  Issued here they are the youngest entries of the in-order vmcnt queue, which only makes the first
+    // iteration's wait stricter.
+    const Affine8 aff = load_affine<TC>(a, lane, c0 + wc * TC * 32);
+    ResidualRegs<T, TP, TC> resregs;
+    prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
 
     // fragments of one k-step; two sets alternate so that the reads of step s+1 fly under the MFMAs of step s
     u32x4_t fa[2][TC], fb[2][TP];

@@ -252,6 +252,15 @@ sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t
     if (a.P <= 0) return SOL_OK;   // empty batch: nothing to do
     if (tile_override == T_AUTO && stem_kernel_applies(a, dt)) return launch_conv_stem(a, st);
     if (tile_override == T_AUTO && linear_kernel_applies(a, dt)) return launch_linear(a, dt, st);
+    if (tile_override == T_AUTO && halo_kernel_applies(a, dt)) {
+        if (const int ht = halo_choose_tile(a)) return launch_conv_halo(a, ht, st);
+    }
+    if (tile_override >= H_FIRST && tile_override <= H_LAST) {
+        SOL_REQUIRE(halo_kernel_applies(a, dt), SOL_ERR_UNSUPPORTED,
+                    "conv tile %d needs a bf16 3x3 stride-1 pad-1 convolution with Cin %% 64 == 0 and no fused pool", tile_override);
+        return launch_conv_halo(a, tile_override, st);
+    }
+    if (tile_override == T_NO_HALO) tile_override = T_AUTO;
     if (const int rowb = dma_tile_row_bytes(tile_override)) {
         SOL_REQUIRE(a.C % (rowb / (int)dtype_size(dt)) == 0 && dma_kernel_applies(a, (int)dtype_size(dt)), SOL_ERR_UNSUPPORTED,
                     "conv tile %d needs Cin %% %d == 0, at most 32 filter taps and tensors below 4 GB", tile_override,

@@ -132,6 +132,72 @@ def test_every_conv_tile(sol, dt, tile):
     assert rel_err(got, want) <= TOL[dt]
 
 
+
+HALO_CASES = [
+    # N, C, H, W, K, res     3x3 / stride 1 / pad 1: ragged pixel and channel tails, several input chunks,
+    # tiles that span many images, image widths from 1 to 56
+    (2, 64, 21, 20, 136, True),
+    (3, 192, 14, 14, 256, False),
+    (5, 512, 7, 7, 128, True),
+    (130, 64, 2, 2, 64, True),
+    (3, 128, 1, 1, 64, False),
+    (2, 64, 5, 1, 72, False),
+    (1, 128, 28, 28, 128, False),
+    (2, 64, 33, 30, 64, True),
+]
+
+
+@pytest.mark.parametrize("tile", [41, 42, 43])
+@pytest.mark.parametrize("case", HALO_CASES)
+def test_halo_conv_tiles(sol, tile, case):
+    """The 3x3 halo-in-LDS kernel in each of its tile shapes against the checker, every output element."""
+    N, C, H, W, K, res = case
+    rng = np.random.default_rng(hash((tile,) + case) % (2 ** 31))
+    l, x, prm, r = make_block(sol, rng, "bf16", N, C, H, W, K, 3, 1, 1, res=res)
+    want, _, _ = orc.fused_conv(x, prm, l, r, bf16=True)
+    sol.sol_debug_set_conv_tile(tile)
+    try:
+        got, _, _ = run_block(sol, "bf16", l, x, prm, r)
+    finally:
+        sol.sol_debug_set_conv_tile(0)
+    assert rel_err(got, want) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("case", [(1, 64, 56, 56, 64, False), (2, 64, 33, 50, 72, True), (3, 64, 9, 61, 64, False)])
+def test_halo_conv_wide_single_chunk(sol, case):
+    """Wide images with one 64-channel input chunk (the first ResNet-50 stage) use the single-patch-buffer tile."""
+    N, C, H, W, K, res = case
+    rng = np.random.default_rng(hash(case) % (2 ** 31))
+    l, x, prm, r = make_block(sol, rng, "bf16", N, C, H, W, K, 3, 1, 1, res=res)
+    want, _, _ = orc.fused_conv(x, prm, l, r, bf16=True)
+    sol.sol_debug_set_conv_tile(44)
+    try:
+        got, _, _ = run_block(sol, "bf16", l, x, prm, r)
+    finally:
+        sol.sol_debug_set_conv_tile(0)
+    assert rel_err(got, want) <= TOL["bf16"]
+
+
+def test_halo_conv_exact_integers(sol):
+    """Small-integer inputs and weights: every product and partial sum is exact in fp32 and the outputs are exact
+    in bf16, so the halo kernel must agree with the checker bit for bit (a wrong tap, border mask or patch row
+    cannot hide inside the tolerance)."""
+    rng = np.random.default_rng(11)
+    N, C, H, W, K = 3, 128, 13, 11, 64
+    x = rng.integers(-2, 3, (N, C, H, W)).astype(np.float32)
+    w = (rng.integers(-1, 2, (K, C, 3, 3)) * (rng.random((K, C, 3, 3)) < 0.05)).astype(np.float32)
+    l = wl.conv(K, 3, 1, 1, bn=False, act="none")
+    prm = {"w": w, "bias": np.zeros(K, np.float32)}
+    want, _, _ = orc.fused_conv(x, prm, l, None, bf16=True)
+    assert np.abs(want).max() <= 256 and np.abs(want).max() > 4
+    for tile in (41, 42, 43):
+        sol.sol_debug_set_conv_tile(tile)
+        try:
+            got, _, _ = run_block(sol, "bf16", l, x, prm, None)
+        finally:
+            sol.sol_debug_set_conv_tile(0)
+        assert np.array_equal(got, want), tile
+
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("kind", ["max", "avg"])
 @pytest.mark.parametrize("shape", [(2, 3, 32, 32, 16), (3, 64, 15, 13, 72), (1, 32, 8, 8, 64)])
