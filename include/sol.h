@@ -167,6 +167,18 @@ sol_status sol_network_set_params(sol_network *net, int layer, const float *w, c
 sol_status sol_network_forward(sol_network *net, const void *x, void *y, void *workspace,
                                size_t workspace_bytes, void *hip_stream);
 
+/* Plan-time micro auto-tune (the paper's optimizer picks per-layer implementations by heuristics or a very short
+ * auto-tuning run when the model is optimized, Sec. III-A): times every kernel / tile shape that fits each
+ * convolution layer, `reps` launches each on the caller's buffers, and keeps the fastest per layer for all later
+ * sol_network_forward / sol_network_graph_create calls (the shape heuristic's choice stays unless a candidate is
+ * more than 3 % faster).  Runs whole passes over x / workspace / y (their contents are overwritten with valid
+ * activations), synchronises with the stream, allocates nothing on the device.  Every candidate computes the same
+ * layer within the library's tolerance; the accumulation order, hence the last bits, may differ between candidates.
+ * Inference networks only.  sol_network_layer_tile reports the chosen id (0 = heuristic). */
+sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *workspace,
+                                size_t workspace_bytes, int reps, void *hip_stream);
+sol_status sol_network_layer_tile(const sol_network *net, int layer, int *tile);
+
 /* One forward pass recorded as a HIP graph (launch-bound inner loops: the ~56 launches of a ResNet-50-shaped
  * pass replay as one submission).  sol_network_graph_create runs the pass once eagerly, then records the same
  * launches with the given pointers baked in: x, y, workspace, the bound parameter buffer and the network must

@@ -133,6 +133,7 @@ struct LayerPlan {
     size_t out_off, tmp_off;        // workspace offsets; out_off unused for the last layer
     int last_use;
     bool params_set;
+    int tile;                       // CONV / LINEAR: kernel + tile id chosen by sol_network_autotune (T_AUTO: shape heuristic)
     // training networks only
     size_t wT_off, master_off, vel_off, grad_off, vec_off;   // parameter buffer: flipped pack, fp32 master / velocity / gradient, per-channel arrays
     size_t z_off, dact_off, arg_off;                          // workspace: conv output before BN, gradient of the output, pool winners
@@ -446,6 +447,7 @@ sol_status sol_network_create(const sol_layer *layers, int n_layers, const sol_t
     net->params_size = 0;
     sol_status s = plan_network(net, layers, n_layers);
     if (s != SOL_OK) { delete net; return s; }
+    for (auto &lp : net->layers) lp.tile = T_AUTO;
     *out = net;
     return SOL_OK;
 }
@@ -672,14 +674,15 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
                 const void *res = lp.res >= 0 ? layer_in(net, lp.res, x, ws) : nullptr;
                 void *conv_dst = lp.split_pool ? static_cast<void *>(ws + lp.tmp_off) : out;
                 SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, scale, shift, res, lp.L.act,
-                                        lp.fuse_pool ? &lp.L.pool : nullptr, conv_dst, nullptr, nullptr, g_tile_override, st));
+                                        lp.fuse_pool ? &lp.L.pool : nullptr, conv_dst, nullptr, nullptr,
+                                        g_tile_override ? g_tile_override : lp.tile, st));
                 if (lp.split_pool) SOL_TRY(pool_impl(lp.conv_out, conv_dst, lp.L.pool, out, nullptr, st));
                 break;
             }
             case SOL_LAYER_LINEAR: {
                 const float *shift = reinterpret_cast<const float *>(net->params + lp.shift_off);
                 SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, nullptr, shift, nullptr, lp.L.act, nullptr,
-                                        out, nullptr, nullptr, g_tile_override, st));
+                                        out, nullptr, nullptr, g_tile_override ? g_tile_override : lp.tile, st));
                 break;
             }
             case SOL_LAYER_POOL: SOL_TRY(pool_impl(lp.in, in, lp.L.pool, out, nullptr, st)); break;
@@ -694,6 +697,67 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
 sol_status sol_network_forward(sol_network *net, const void *x, void *y, void *workspace, size_t workspace_bytes, void *stream) {
     SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
     return run_layers(net, x, y, workspace, workspace_bytes, 0, (int)net->layers.size() - 1, (hipStream_t)stream);
+}
+
+// ---- plan-time micro auto-tune ------------------------------------------------------------------------------
+// Every kernel / tile id a convolution layer may be launched with (the launchers reject what does not fit a layer).
+static const int kTuneCandidates[] = {
+    D_128x128_64x4, D_128x128_64x3, D_256x128_64x3, D_128x64_64x4, D_64x64_64x4, D_128x256_64x3, D_256x64_64x3, D_64x128_64x4,
+    D_128x128_128x2, D_128x128_128x3, D_128x64_128x3, D_64x64_128x3, D_128x128_64x5, D_64x64_128x4, D_256x128_128x3,
+    D_256x128_64x4, D_128x256_64x4, D_64x64_64x8,
+    H_256x128_x5, H_128x128_x3, H_256x64_x5, H_256x64_x6s,
+    G_128x128_k2, G_256x128, G_128x256, G_64x128_k4, G_128x64_k4, G_256x256_r64, G_256x128_r64, G_64x64_k4};
+
+sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *workspace, size_t workspace_bytes, int reps,
+                                void *stream) {
+    SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
+    SOL_REQUIRE(!net->training, SOL_ERR_UNSUPPORTED, "auto-tune covers inference networks");
+    SOL_REQUIRE(reps >= 1 && reps <= 1000, SOL_ERR_SHAPE, "reps %d out of range [1,1000]", reps);
+    hipStream_t st = (hipStream_t)stream;
+    const int nl = (int)net->layers.size();
+    for (auto &lp : net->layers) lp.tile = T_AUTO;
+    // one whole pass: validates the arguments and leaves finite activations of the right shape in every buffer
+    SOL_TRY(run_layers(net, x, y, workspace, workspace_bytes, 0, nl - 1, st));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    SOL_HIP(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); SOL_FAIL(SOL_ERR_HIP, "hipEventCreate failed"); }
+    sol_status rs = SOL_OK;
+    auto time_layer = [&](int i, float *ms) -> sol_status {   // reps launches of layer i between two events
+        for (int r = 0; r < 2; r++) SOL_TRY(run_layers(net, x, y, workspace, workspace_bytes, i, i, st));
+        SOL_HIP(hipEventRecord(e0, st));
+        for (int r = 0; r < reps; r++) SOL_TRY(run_layers(net, x, y, workspace, workspace_bytes, i, i, st));
+        SOL_HIP(hipEventRecord(e1, st));
+        SOL_HIP(hipEventSynchronize(e1));
+        SOL_HIP(hipEventElapsedTime(ms, e0, e1));
+        return SOL_OK;
+    };
+    for (int i = 0; i < nl && rs == SOL_OK; i++) {
+        LayerPlan &lp = net->layers[i];
+        if (lp.L.kind != SOL_LAYER_CONV || lp.in.n == 0) continue;
+        float best = 0.f;
+        rs = time_layer(i, &best);                            // the shape heuristic's choice is the incumbent
+        if (rs != SOL_OK) break;
+        int best_tile = T_AUTO;
+        for (int cand : kTuneCandidates) {
+            lp.tile = cand;
+            float ms = 0.f;
+            const sol_status cs = time_layer(i, &ms);
+            if (cs == SOL_ERR_HIP) { rs = cs; break; }
+            if (cs == SOL_OK && ms < 0.97f * best) { best = ms; best_tile = cand; }   // 3 % margin against timing noise
+        }
+        lp.tile = best_tile;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rs != SOL_OK) for (auto &lp : net->layers) lp.tile = T_AUTO;
+    return rs;
+}
+
+sol_status sol_network_layer_tile(const sol_network *net, int layer, int *tile) {
+    SOL_REQUIRE(net && tile, SOL_ERR_NULL, "net and tile must not be NULL");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    *tile = net->layers[layer].tile;
+    return SOL_OK;
 }
 
 // ---- HIP graph of one forward pass -------------------------------------------------------------------------

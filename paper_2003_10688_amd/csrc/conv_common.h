@@ -29,6 +29,32 @@ template <> struct Mma<float> {
     }
 };
 
+// Hand-ordered LDS pipeline pieces shared by the DMA-ring kernels.  The compiler cannot tell which ring stage an
+// LDS read touches and would make every fragment read wait for all outstanding DMA; the reads are therefore opaque
+// volatile statements ordered by hand (ds_read -> s_waitcnt lgkmcnt -> landed() -> use).
+namespace lds_pipe {
+
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_lgkmcnt() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
+template <int OFF> __device__ __forceinline__ void lds_read16(u32x4_t &dst, unsigned addr) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(OFF));
+}
+// ties a fragment to a point after the wait: every later use depends on it
+__device__ __forceinline__ void landed(u32x4_t &v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ unsigned lds_addr(const void *p) {
+    return (unsigned)(size_t)(__attribute__((address_space(3))) const void *)p;
+}
+// 16-byte slot permutation of a tile row (applied to the global address a DMA lane fetches): conflict-free
+// 16-byte fragment reads for rows of 128 bytes (8 slots) and of 64 bytes (4 slots)
+template <int ROWB> __device__ __forceinline__ int swz(int row) { return ROWB == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+
+}  // namespace lds_pipe
+
 // GEMM row m -> output pixel.  With a fused 2x2 pool the rows are ordered window-major, so that the
 // four elements of one pooling window sit in four adjacent lanes in row-major window order.
 __device__ __forceinline__ void decode_pixel(const ConvArgs &a, int m, int &n, int &op, int &oq) {

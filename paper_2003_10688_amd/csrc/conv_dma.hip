@@ -272,7 +272,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
     const long long tepi_ = __builtin_readcyclecounter();
 #endif
     __syncthreads();                               // every wave is done with the tiles: the ring becomes strips
-    conv_epilogue<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32,
+    conv_epilogue_auto<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32,
                              aff, LinearRows{a.P}, resregs);
 #ifdef SOL_PHASE_TIMING
     if (a.argmax == nullptr && a.prepool && lane == 0 && (blockIdx.x % 37) == 0 && wave < 4) {

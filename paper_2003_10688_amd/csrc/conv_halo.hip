@@ -24,26 +24,6 @@
 
 namespace sol {
 
-namespace halo {
-
-typedef __attribute__((ext_vector_type(4))) unsigned u32x4_t;
-
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    static_assert(N >= 0 && N < 64, "6-bit counter");
-    // only the vector-memory counter constrained (gfx9 encoding: vmcnt = [15:14][3:0])
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-template <int N> __device__ __forceinline__ void wait_lgkmcnt() { asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory"); }
-template <int OFF> __device__ __forceinline__ void lds_read16(u32x4_t &dst, unsigned addr) {
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(dst) : "v"(addr), "n"(OFF));
-}
-__device__ __forceinline__ void landed(u32x4_t &v) { asm volatile("" : "+v"(v)); }
-__device__ __forceinline__ unsigned lds_addr(const void *p) {
-    return (unsigned)(size_t)(__attribute__((address_space(3))) const void *)p;
-}
-__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
-
-}  // namespace halo
 
 // T: element type; WP x WC: wave grid (pixels x channels); TP x TC: 32x32 accumulator blocks per wave;
 // XL: patch DMA instructions per wave and chunk (patch rows = XL * waves * 8 >= BP + 2W + 2);
@@ -51,7 +31,7 @@ __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 template <typename T, int WP, int WC, int TP, int TC, int XL, int NSW, int NPB>
 __global__ void __launch_bounds__(WP *WC * 64) conv_halo_kernel(const ConvArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    using namespace halo;
+    using namespace lds_pipe;
     constexpr int NW = WP * WC, ES = (int)sizeof(T), ROWB = 128, BK = ROWB / ES;
     constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
     constexpr int WSTAGE = BC * ROWB;              // bytes of one weight stage
@@ -113,13 +93,13 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_halo_kernel(const ConvArgs a
     for (int i = 0; i < XL; i++) {
         const int row = (wave + NW * i) * 8 + lrow;
         const int pin = p0 - W - 1 + row;
-        xo[i] = (pin >= 0 && pin < a.P) ? (unsigned)pin * (unsigned)(a.C * ES) + ((lslot ^ swz(row)) << 4) : 0xffffffffu;
+        xo[i] = (pin >= 0 && pin < a.P) ? (unsigned)pin * (unsigned)(a.C * ES) + ((lslot ^ swz<ROWB>(row)) << 4) : 0xffffffffu;
     }
 #pragma unroll
     for (int i = 0; i < WL; i++) {
         const int row = (wave * WL + i) * 8 + lrow;
         const int co = c0 + row;
-        wo[i] = co < a.Cout ? (unsigned)co * (unsigned)(a.Kp * ES) + ((lslot ^ swz(row)) << 4) : 0xffffffffu;
+        wo[i] = co < a.Cout ? (unsigned)co * (unsigned)(a.Kp * ES) + ((lslot ^ swz<ROWB>(row)) << 4) : 0xffffffffu;
     }
     auto issue_patch = [&](auto I, int buf, unsigned soff, bool real) {
         constexpr int i = decltype(I)::value;
@@ -134,7 +114,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_halo_kernel(const ConvArgs a
                                                  16, wo[i], soff, 0, 0);
     };
 
-    const unsigned fw0 = lds_addr(wring) + (wc * TC * 32 + lr) * ROWB + ((lh ^ swz(lr)) << 4);
+    const unsigned fw0 = lds_addr(wring) + (wc * TC * 32 + lr) * ROWB + ((lh ^ swz<ROWB>(lr)) << 4);
 
     f32x16_t acc[TC][TP];
 #pragma unroll
@@ -177,7 +157,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_halo_kernel(const ConvArgs a
         for (int t = 0; t < 9; t++) {
             const int r = t / 3, sx = t % 3;
             const int row = mloc + r * W + sx;
-            const unsigned real = lds_addr(patch) + row * ROWB + ((lh ^ swz(row)) << 4);
+            const unsigned real = lds_addr(patch) + row * ROWB + ((lh ^ swz<ROWB>(row)) << 4);
             // arithmetic select (no divergent branch): zero_row + ok * (real - zero_row)
             ax[j][t] = zero_row + ((0u - (hok[r] & wok[sx])) & (real - zero_row));
         }

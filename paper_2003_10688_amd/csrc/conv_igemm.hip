@@ -185,7 +185,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
     }
 
     static_assert((WP * WC) * 32 * (TC * 32 + 4) * 4 <= 2 * (BP + BC) * 128, "epilogue strip must fit in the tile buffers");
-    conv_epilogue<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, aff, LinearRows{a.P}, resregs);
+    conv_epilogue_auto<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, aff, LinearRows{a.P}, resregs);
 }
 
 // ---- launcher / tile table ------------------------------------------------------------------------
@@ -259,6 +259,11 @@ sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t
         SOL_REQUIRE(halo_kernel_applies(a, dt), SOL_ERR_UNSUPPORTED,
                     "conv tile %d needs a bf16 3x3 stride-1 pad-1 convolution with Cin %% 64 == 0 and no fused pool", tile_override);
         return launch_conv_halo(a, tile_override, st);
+    }
+    if (tile_override >= G_FIRST && tile_override <= G_LAST) {
+        SOL_REQUIRE(gemm8_kernel_applies(a, dt), SOL_ERR_UNSUPPORTED,
+                    "conv tile %d needs a bf16 1x1 convolution without padding and Cin %% 32 == 0", tile_override);
+        return launch_conv_gemm8(a, tile_override, st);
     }
     if (tile_override == T_NO_HALO) tile_override = T_AUTO;
     if (const int rowb = dma_tile_row_bytes(tile_override)) {

@@ -286,6 +286,18 @@ class Network:
                                          C.c_size_t(self.workspace.numel()), _stream(stream)))
         return self.y
 
+    def autotune(self, x, reps=10, stream=None):
+        """Plan-time per-layer kernel/tile selection by timing (synchronous); returns {layer: tile id} of the changed layers."""
+        _check(lib().sol_network_autotune(self._h, _ptr(x), _ptr(self.y), _ptr(self.workspace),
+                                          C.c_size_t(self.workspace.numel()), C.c_int(reps), _stream(stream)))
+        out = {}
+        for i in range(len(self.layers)):
+            t = C.c_int(0)
+            _check(lib().sol_network_layer_tile(self._h, C.c_int(i), C.byref(t)))
+            if t.value:
+                out[i] = t.value
+        return out
+
     def graph(self, x, stream):
         """Records one forward pass on `stream` (a torch.cuda.Stream other than the default one) as a HIP graph;
         returns a callable that enqueues one replay on that stream and returns the output tensor."""

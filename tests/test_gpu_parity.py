@@ -198,6 +198,58 @@ def test_halo_conv_exact_integers(sol):
             sol.sol_debug_set_conv_tile(0)
         assert np.array_equal(got, want), tile
 
+
+GEMM8_CASES = [
+    # N, C, H, W, K, stride, res, pool     1x1 convolutions: ragged tails, long and short reductions, stride 2, fused pool
+    (2, 64, 21, 20, 136, 1, True, None),
+    (3, 256, 14, 14, 520, 2, False, None),
+    (5, 2048, 7, 7, 512, 1, False, None),
+    (2, 1024, 7, 7, 264, 1, True, None),
+    (1, 32, 9, 9, 40, 1, False, None),
+    (2, 64, 16, 16, 64, 1, False, "max"),
+    (70, 128, 3, 3, 128, 1, True, None),
+]
+
+
+@pytest.mark.parametrize("tile", list(range(61, 69)))
+@pytest.mark.parametrize("case", GEMM8_CASES)
+def test_gemm8_conv_tiles(sol, tile, case):
+    """The eight-wave 1x1 GEMM kernel in each tile shape (with and without the in-workgroup K split) against the
+    checker, every output element."""
+    N, C, H, W, K, st, res, pool = case
+    if C % 64 and tile not in (66, 67):
+        pytest.skip("128-byte-row tiles need Cin % 64 == 0")
+    rng = np.random.default_rng(hash((tile,) + case) % (2 ** 31))
+    pd = dict(kind=pool, kh=2, kw=2, sh=2, sw=2, ph=0, pw=0) if pool else None
+    l, x, prm, r = make_block(sol, rng, "bf16", N, C, H, W, K, 1, st, 0, res=res, pool=pd)
+    want, _, _ = orc.fused_conv(x, prm, l, r, bf16=True)
+    sol.sol_debug_set_conv_tile(tile)
+    try:
+        got, _, _ = run_block(sol, "bf16", l, x, prm, r)
+    finally:
+        sol.sol_debug_set_conv_tile(0)
+    assert rel_err(got, want) <= TOL["bf16"]
+
+
+def test_gemm8_conv_exact_integers(sol):
+    """Small-integer operands make every partial sum exact in fp32, so all tile shapes (any split of the
+    reduction) must reproduce the checker bit for bit."""
+    rng = np.random.default_rng(12)
+    N, C, H, W, K = 3, 512, 9, 7, 192
+    x = rng.integers(-2, 3, (N, C, H, W)).astype(np.float32)
+    w = (rng.integers(-1, 2, (K, C, 1, 1)) * (rng.random((K, C, 1, 1)) < 0.1)).astype(np.float32)
+    l = wl.conv(K, 1, 1, 0, bn=False, act="none")
+    prm = {"w": w, "bias": np.zeros(K, np.float32)}
+    want, _, _ = orc.fused_conv(x, prm, l, None, bf16=True)
+    assert 4 < np.abs(want).max() <= 256
+    for tile in range(61, 69):
+        sol.sol_debug_set_conv_tile(tile)
+        try:
+            got, _, _ = run_block(sol, "bf16", l, x, prm, None)
+        finally:
+            sol.sol_debug_set_conv_tile(0)
+        assert np.array_equal(got, want), tile
+
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("kind", ["max", "avg"])
 @pytest.mark.parametrize("shape", [(2, 3, 32, 32, 16), (3, 64, 15, 13, 72), (1, 32, 8, 8, 64)])
@@ -538,3 +590,33 @@ def test_network_graph_replays(sol, cfg, batch, hw):
             cuda_stream = 0
         net.graph(x, _Null())
     assert e.value.status == 6
+
+
+def test_network_autotune_keeps_results(sol):
+    """Plan-time auto-tune: whatever kernels it picks, every layer still matches the checker (layer by layer on the
+    checker's activations, element-wise) and a second pass reproduces the first bit for bit."""
+    wk = wl.config(3, batch=2, hw=64)
+    outs, _ = orc.network_forward(wk.layers, wk.params, wk.x, bf16=True, return_all=True)
+    net = sol.Network(wk.layers, wk.in_shape, sol.BF16, flags=sol.NET_KEEP_ACTIVATIONS)
+    net.set_params(wk.params)
+    x = sol.to_device_nhwc(wk.x, sol.BF16)
+    tuned = net.autotune(x, reps=3)
+    assert all(0 < t < 100 for t in tuned.values())
+    y1 = sol.to_host_nchw(net.forward(x)).copy()
+    y2 = sol.to_host_nchw(net.forward(x)).copy()
+    assert np.array_equal(y1, y2)
+    assert norm_err(y1.reshape(outs[-1].shape), outs[-1]) <= TOL["bf16"]
+    nl = len(wk.layers)
+    dev = [sol.to_device_nhwc(o if o.ndim == 4 else o[:, :, None, None], sol.BF16) for o in outs]
+    for i in range(nl - 1):
+        net.layer_output(i).copy_(dev[i])
+    errs = []
+    for i in range(nl):
+        net.run_layer(i, x)
+        torch.cuda.synchronize()
+        g = sol.to_host_nchw(net.y if i == nl - 1 else net.layer_output(i)).reshape(outs[i].shape)
+        errs.append(rel_err(g, outs[i]))
+        if i < nl - 1:
+            net.layer_output(i).copy_(dev[i])
+    print(f"autotuned layers {tuned}; layer-by-layer max rel err {max(errs):.3e}")
+    assert max(errs) <= TOL["bf16"], errs
