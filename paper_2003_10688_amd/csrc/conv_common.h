@@ -49,6 +49,13 @@ __device__ __forceinline__ void landed(u32x4_t &v) { asm volatile("" : "+v"(v));
 __device__ __forceinline__ unsigned lds_addr(const void *p) {
     return (unsigned)(size_t)(__attribute__((address_space(3))) const void *)p;
 }
+// (a ^ x) + b in one VALU instruction, opaque to the optimiser: fragment addresses are derived from one base per
+// row at the point of use instead of being hoisted into dozens of loop-invariant registers
+__device__ __forceinline__ unsigned xor_add(unsigned a, unsigned x, unsigned b) {
+    unsigned d;
+    asm volatile("v_xad_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(x), "v"(b));
+    return d;
+}
 // 16-byte slot permutation of a tile row (applied to the global address a DMA lane fetches): conflict-free
 // 16-byte fragment reads for rows of 128 bytes (8 slots) and of 64 bytes (4 slots)
 template <int ROWB> __device__ __forceinline__ int swz(int row) { return ROWB == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3); }

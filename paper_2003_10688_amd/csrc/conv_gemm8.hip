@@ -1,4 +1,5 @@
-// Fused 1x1 convolution (any stride) as an eight-wave GEMM with an LDS-DMA ring (gfx950).
+// Fused convolution (implicit GEMM over up to 32 filter taps, any stride / padding) as an eight-wave GEMM with an
+// LDS-DMA ring (gfx950).
 //
 // Same GEMM view, operand layout in LDS (rows of ROWB bytes, 16-byte slots XOR-permuted on the global
 // side) and epilogue as conv_dma.hip, but built for ONE workgroup of eight waves per CU instead of
@@ -43,7 +44,7 @@ __global__ void __launch_bounds__(512) conv_gemm8_kernel(const ConvArgs a) {
 
     // every kernel argument the prologue needs, fetched in one batch
     asm volatile("" ::"s"(a.x), "s"(a.w), "s"(a.scale), "s"(a.shift), "s"(a.res), "s"(a.y), "s"(a.P), "s"(a.C), "s"(a.Cout),
-                 "s"(a.H), "s"(a.W), "s"(a.Kp), "s"(a.ntc), "s"(a.ntiles), "s"(a.act), "s"(a.dw.mul), "s"(a.dh.mul), "s"(a.sh), "s"(a.pool));
+                 "s"(a.H), "s"(a.W), "s"(a.Kp), "s"(a.ntc), "s"(a.ntiles), "s"(a.act), "s"(a.dw.mul), "s"(a.dh.mul), "s"(a.sh), "s"(a.pool), "s"(a.R), "s"(a.S), "s"(a.ph));
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -65,22 +66,33 @@ __global__ void __launch_bounds__(512) conv_gemm8_kernel(const ConvArgs a) {
     if (tile >= a.ntiles) return;
     const int p0 = (tile / a.ntc) * BP, c0 = (tile % a.ntc) * BC;
 
+    // The activation resource starts `bias` bytes before the tensor so that the offset of a row's window origin
+    // (which lies in the padding for border pixels) is never negative; only in-range taps are fetched through it.
+    const unsigned bias = (unsigned)((a.ph * a.W + a.pw) * a.C) * ES;
     const unsigned xbytes = (unsigned)a.N * a.H * a.W * a.C * ES, wbytes = (unsigned)a.Cout * a.Kp * ES;
-    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, (int)xbytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned char *>(static_cast<const unsigned char *>(a.x)) - bias, 0, (int)(xbytes + bias), 0x00020000);
     const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, (int)wbytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t xnull = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, 0, 0x00020000);
     const __amdgpu_buffer_rsrc_t wnull = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, 0, 0x00020000);
 
-    // ---- DMA lane offsets (one 16-byte slot of XL pixel rows and WL weight rows per stage)
-    unsigned xo[XL], wo[WL];
+    // ---- DMA lane offsets (one 16-byte slot of XL pixel rows and WL weight rows per stage); bit t of xinv: filter
+    // tap t of that row reads padding (its offset is pushed out of range, the hardware returns zeros)
+    unsigned xo[XL], xinv[XL], wo[WL];
 #pragma unroll
     for (int i = 0; i < XL; i++) {
         const int row = (wave * XL + i) * RSEG + lrow;
         const int m = p0 + row;
         int n, op, oq;
         decode_pixel(a, m, n, op, oq);
-        const unsigned off = (unsigned)(((n * a.H + op * a.sh) * a.W + oq * a.sw) * a.C) * ES + ((lslot ^ swz<ROWB>(row)) << 4);
+        const int ih0 = op * a.sh - a.ph, iw0 = oq * a.sw - a.pw;
+        const unsigned off = (unsigned)(((n * a.H + ih0) * a.W + iw0) * a.C) * ES + bias + ((lslot ^ swz<ROWB>(row)) << 4);
+        const int slo = max(0, -iw0), shi = min(a.S, a.W - iw0), rlo = max(0, -ih0), rhi = min(a.R, a.H - ih0);
+        const unsigned cval = shi > slo ? (unsigned)((1ull << shi) - 1ull) & ~((1u << slo) - 1u) : 0u;
+        unsigned val = 0;
+        for (int r = 0; r < a.R; r++) val |= (r >= rlo && r < rhi) ? cval << (r * a.S) : 0u;
         xo[i] = m < a.P ? off : 0xffffffffu;
+        xinv[i] = ~val;
     }
 #pragma unroll
     for (int i = 0; i < WL; i++) {
@@ -88,24 +100,35 @@ __global__ void __launch_bounds__(512) conv_gemm8_kernel(const ConvArgs a) {
         const int co = c0 + row;
         wo[i] = co < a.Cout ? (unsigned)(co * a.Kp) * ES + ((lslot ^ swz<ROWB>(row)) << 4) : 0xffffffffu;
     }
-    // IDX-th DMA instruction of this wave for a stage (pixel rows first); soff: byte offset of the reduction chunk
-    auto issue_one = [&](auto IDX, int buf, unsigned soff, bool real) {
+    // IDX-th DMA instruction of this wave for a stage (pixel rows first); xsoff / wsoff: the stage's scalar byte offsets
+    // (filter tap + reduction chunk), tapbit: its filter tap
+    auto issue_one = [&](auto IDX, int buf, unsigned xsoff, unsigned wsoff, int tapbit, bool real) {
         constexpr int idx = decltype(IDX)::value;
         unsigned char *lx = lds + buf * STAGE, *lw = lx + BP * ROWB;
-        if constexpr (idx < XL)
+        if constexpr (idx < XL) {
+            const unsigned off = xo[idx] | (unsigned)__builtin_amdgcn_sbfe(xinv[idx], tapbit, 1);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? xr : xnull, (__attribute__((address_space(3))) void *)(lx + (wave * XL + idx) * 1024),
-                                                     16, xo[idx], soff, 0, 0);
-        else
+                                                     16, off, xsoff, 0, 0);
+        } else {
             __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? wr : wnull, (__attribute__((address_space(3))) void *)(lw + (wave * WL + idx - XL) * 1024),
-                                                     16, wo[idx - XL], soff, 0, 0);
+                                                     16, wo[idx - XL], wsoff, 0, 0);
+        }
     };
+    // filter tap / chunk of the next stage to issue
+    const int cpt = a.C / BK;
+    int tr = 0, ts = 0, tcc = 0, tap = 0;
+    auto x_soff = [&]() { return (unsigned)((tr * a.W + ts) * a.C + tcc * BK) * ES; };
+    auto next_tap = [&]() { if (++tcc == cpt) { tcc = 0; ++tap; if (++ts == a.S) { ts = 0; ++tr; } } };
 
-    const int nk = a.C / BK;
+    const int nk = a.R * a.S * cpt;
     // ---- prologue: the first D stages, then (behind them) the epilogue operands
 #pragma unroll
     for (int s = 0; s < D; s++) {
         const bool real = s < nk;
-        static_for<L>([&](auto I) { issue_one(I, s, (unsigned)(s * ROWB), real); });
+        const unsigned xs = x_soff();
+        const int tb = tap;
+        static_for<L>([&](auto I) { issue_one(I, s, xs, (unsigned)(s * ROWB), tb, real); });
+        next_tap();
     }
     const Affine8 aff = load_affine<TC>(a, lane, c0 + wc * TC * 32);
     ResidualRegs<T, TP, TC> resregs;
@@ -129,7 +152,7 @@ __global__ void __launch_bounds__(512) conv_gemm8_kernel(const ConvArgs a) {
     auto read_frags = [&](auto SET, auto Q, unsigned sb) {      // fragments of this wave's Q-th k-step of the stage at byte offset sb
         constexpr int set = decltype(SET)::value, q = decltype(Q)::value;
         const unsigned kx = (unsigned)((kq * NK + q) << 5);
-        const unsigned aw = (fw0 ^ kx) + sb, ax = (fx0 ^ kx) + sb;
+        const unsigned aw = xor_add(fw0, kx, sb), ax = xor_add(fx0, kx, sb);
         static_for<TC>([&](auto I) { lds_read16<decltype(I)::value * 32 * ROWB>(fa[set][decltype(I)::value], aw); });
         static_for<TP>([&](auto J) { lds_read16<decltype(J)::value * 32 * ROWB>(fb[set][decltype(J)::value], ax); });
     };
@@ -168,14 +191,14 @@ __global__ void __launch_bounds__(512) conv_gemm8_kernel(const ConvArgs a) {
             else read_frags(std::integral_constant<int, cur ^ 1>{}, std::integral_constant<int, 0>{}, sbn);
             wait_lgkmcnt<TC + TP>();
             if constexpr (q == BQ) {
-                const int buf = ibuf;
-                const unsigned so = isoff;
+                const int buf = ibuf, tb = tap;
+                const unsigned so = isoff, xs = x_soff();
                 mfmas(std::integral_constant<int, cur>{}, [&](auto M) {
                     constexpr int m = decltype(M)::value;
-                    if constexpr (m < L) issue_one(M, buf, so, real);
+                    if constexpr (m < L) issue_one(M, buf, xs, so, tb, real);
                     if constexpr (m == TC * TP - 1)
                         static_for<(L > TC * TP) ? L - TC * TP : 0>([&](auto E) {
-                            issue_one(std::integral_constant<int, TC * TP + decltype(E)::value>{}, buf, so, real);
+                            issue_one(std::integral_constant<int, TC * TP + decltype(E)::value>{}, buf, xs, so, tb, real);
                         });
                 });
             } else {
@@ -184,6 +207,7 @@ __global__ void __launch_bounds__(512) conv_gemm8_kernel(const ConvArgs a) {
         });
         ibuf = ibuf + 1 == NS ? 0 : ibuf + 1;
         isoff += ROWB;
+        next_tap();
         sb = sbn;
     };
     if constexpr (NK % 2 == 0) {
@@ -247,11 +271,11 @@ static sol_status launch_gemm8_cfg(ConvArgs a, hipStream_t st) {
     return SOL_OK;
 }
 
-// 1x1, no padding, bf16, Cin a multiple of 32, 32-bit byte offsets
+// bf16, at most 32 filter taps (one validity bit each), Cin a multiple of 32, 32-bit byte offsets
 bool gemm8_kernel_applies(const ConvArgs &a, int dt) {
     if (dt != SOL_BF16) return false;
-    const double xb = (double)a.N * a.H * a.W * a.C * 2.0, wb = (double)a.Cout * a.Kp * 2.0;
-    return a.R == 1 && a.S == 1 && a.ph == 0 && a.pw == 0 && a.C % 32 == 0 && xb < 4294967296.0 && wb < 4294967296.0;
+    const double xb = (double)a.N * a.H * a.W * a.C * 2.0 + (double)(a.ph * a.W + a.pw) * a.C * 2.0, wb = (double)a.Cout * a.Kp * 2.0;
+    return a.R * a.S <= 32 && a.C % 32 == 0 && xb < 4294967296.0 && wb < 4294967296.0;
 }
 
 sol_status launch_conv_gemm8(const ConvArgs &a, int tile, hipStream_t st) {

@@ -27,9 +27,10 @@ namespace sol {
 
 // T: element type; WP x WC: wave grid (pixels x channels); TP x TC: 32x32 accumulator blocks per wave;
 // XL: patch DMA instructions per wave and chunk (patch rows = XL * waves * 8 >= BP + 2W + 2);
+// MINW: waves per SIMD the register allocation must allow (4: two workgroups per CU);
 // NSW: weight ring stages; NPB: patch buffers (2, or 1 when Cin is a single chunk).
-template <typename T, int WP, int WC, int TP, int TC, int XL, int NSW, int NPB>
-__global__ void __launch_bounds__(WP *WC * 64) conv_halo_kernel(const ConvArgs a) {
+template <typename T, int WP, int WC, int TP, int TC, int XL, int NSW, int NPB, int MINW = 2>
+__global__ void __launch_bounds__(WP *WC * 64, MINW) conv_halo_kernel(const ConvArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
     using namespace lds_pipe;
     constexpr int NW = WP * WC, ES = (int)sizeof(T), ROWB = 128, BK = ROWB / ES;
@@ -137,7 +138,8 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_halo_kernel(const ConvArgs a
     // epilogue operands (scale / shift, residual rows) and the zero rows, all behind the first DMAs
     const Affine8 aff = load_affine_unconditional<TC>(a, lane, c0 + wc * TC * 32);
     ResidualRegs<T, TP, TC> resregs;
-    prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
+    resregs.on = false;                                  // tight register budgets fetch residual rows in the epilogue instead
+    if constexpr (MINW < 4) prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
     if (tid < NPB * 32) *reinterpret_cast<unsigned *>(patch + (tid >> 5) * PBYTES + PROWS * ROWB + (tid & 31) * 4) = 0u;
 
     // ---- fragment addresses (computed while the first DMAs are in flight).  ax[j][t]: LDS byte address (patch buffer 0, k-step 0) of tap t of this lane's
@@ -174,11 +176,11 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_halo_kernel(const ConvArgs a
     u32x4_t fa[2][TC], fb[2][TP];
     auto read_frags = [&](auto SET, auto TAP, auto KSI, unsigned wsoff, unsigned pboff) {
         constexpr int set = decltype(SET)::value, t = decltype(TAP)::value, ks = decltype(KSI)::value;
-        const unsigned aw = (fw0 ^ (unsigned)(ks << 5)) + wsoff;
+        const unsigned aw = xor_add(fw0, (unsigned)(ks << 5), wsoff);
         static_for<TC>([&](auto I) { lds_read16<decltype(I)::value * 32 * ROWB>(fa[set][decltype(I)::value], aw); });
         static_for<TP>([&](auto J) {
             constexpr int j = decltype(J)::value;
-            lds_read16<0>(fb[set][j], (ax[j][t] ^ (unsigned)(ks << 5)) + pboff);
+            lds_read16<0>(fb[set][j], xor_add(ax[j][t], (unsigned)(ks << 5), pboff));
         });
     };
     auto mfmas = [&](auto SET, auto &&between) {
@@ -276,7 +278,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_halo_kernel(const ConvArgs a
 #endif
 }
 
-template <typename T, int WP, int WC, int TP, int TC, int XL, int NSW, int NPB>
+template <typename T, int WP, int WC, int TP, int TC, int XL, int NSW, int NPB, int MINW = 2>
 static sol_status launch_halo_cfg(ConvArgs a, hipStream_t st) {
     constexpr int BP = WP * TP * 32, BC = WC * TC * 32, PROWS = XL * WP * WC * 8;
     SOL_REQUIRE(BP + 2 * a.W + 2 <= PROWS, SOL_ERR_UNSUPPORTED, "halo tile: image width %d needs %d patch rows, tile has %d", a.W,
@@ -285,7 +287,7 @@ static sol_status launch_halo_cfg(ConvArgs a, hipStream_t st) {
     a.ntc = ceil_div(a.Cout, BC);
     a.ntiles = ceil_div(a.P, BP) * a.ntc;
     const int grid = ((a.ntiles + 7) / 8) * 8;
-    hipLaunchKernelGGL((conv_halo_kernel<T, WP, WC, TP, TC, XL, NSW, NPB>), dim3(grid), dim3(WP * WC * 64), 0, st, a);
+    hipLaunchKernelGGL((conv_halo_kernel<T, WP, WC, TP, TC, XL, NSW, NPB, MINW>), dim3(grid), dim3(WP * WC * 64), 0, st, a);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }
@@ -313,6 +315,7 @@ sol_status launch_conv_halo(const ConvArgs &a, int tile, hipStream_t st) {
         case H_128x128_x3: return launch_halo_cfg<bf16_t, 2, 4, 2, 1, 3, 4, 2>(a, st);
         case H_256x64_x5: return launch_halo_cfg<bf16_t, 4, 2, 2, 1, 5, 4, 2>(a, st);
         case H_256x64_x6s: return launch_halo_cfg<bf16_t, 4, 2, 2, 1, 6, 4, 1>(a, st);
+        case H_256x64_x6s2: return launch_halo_cfg<bf16_t, 4, 2, 2, 1, 6, 3, 1, 4>(a, st);     // 74 KB, <= 128 VGPRs: two workgroups per CU
         default: SOL_FAIL(SOL_ERR_UNSUPPORTED, "unknown halo conv tile id %d", tile);
     }
 }

@@ -262,7 +262,7 @@ sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t
     }
     if (tile_override >= G_FIRST && tile_override <= G_LAST) {
         SOL_REQUIRE(gemm8_kernel_applies(a, dt), SOL_ERR_UNSUPPORTED,
-                    "conv tile %d needs a bf16 1x1 convolution without padding and Cin %% 32 == 0", tile_override);
+                    "conv tile %d needs a bf16 convolution with at most 32 filter taps and Cin %% 32 == 0", tile_override);
         return launch_conv_gemm8(a, tile_override, st);
     }
     if (tile_override == T_NO_HALO) tile_override = T_AUTO;

@@ -163,14 +163,15 @@ def test_halo_conv_tiles(sol, tile, case):
     assert rel_err(got, want) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("tile", [44, 45])
 @pytest.mark.parametrize("case", [(1, 64, 56, 56, 64, False), (2, 64, 33, 50, 72, True), (3, 64, 9, 61, 64, False)])
-def test_halo_conv_wide_single_chunk(sol, case):
+def test_halo_conv_wide_single_chunk(sol, case, tile):
     """Wide images with one 64-channel input chunk (the first ResNet-50 stage) use the single-patch-buffer tile."""
     N, C, H, W, K, res = case
     rng = np.random.default_rng(hash(case) % (2 ** 31))
     l, x, prm, r = make_block(sol, rng, "bf16", N, C, H, W, K, 3, 1, 1, res=res)
     want, _, _ = orc.fused_conv(x, prm, l, r, bf16=True)
-    sol.sol_debug_set_conv_tile(44)
+    sol.sol_debug_set_conv_tile(tile)
     try:
         got, _, _ = run_block(sol, "bf16", l, x, prm, r)
     finally:
@@ -200,28 +201,32 @@ def test_halo_conv_exact_integers(sol):
 
 
 GEMM8_CASES = [
-    # N, C, H, W, K, stride, res, pool     1x1 convolutions: ragged tails, long and short reductions, stride 2, fused pool
-    (2, 64, 21, 20, 136, 1, True, None),
-    (3, 256, 14, 14, 520, 2, False, None),
-    (5, 2048, 7, 7, 512, 1, False, None),
-    (2, 1024, 7, 7, 264, 1, True, None),
-    (1, 32, 9, 9, 40, 1, False, None),
-    (2, 64, 16, 16, 64, 1, False, "max"),
-    (70, 128, 3, 3, 128, 1, True, None),
+    # N, C, H, W, K, k, stride, res, pool     ragged tails, long and short reductions, stride 2, filter taps with padding, fused pool
+    (2, 64, 21, 20, 136, 1, 1, True, None),
+    (3, 256, 14, 14, 520, 1, 2, False, None),
+    (5, 2048, 7, 7, 512, 1, 1, False, None),
+    (2, 1024, 7, 7, 264, 1, 1, True, None),
+    (1, 32, 9, 9, 40, 1, 1, False, None),
+    (2, 64, 16, 16, 64, 1, 1, False, "max"),
+    (70, 128, 3, 3, 128, 1, 1, True, None),
+    (3, 128, 15, 14, 136, 3, 2, False, None),
+    (2, 64, 23, 23, 64, 3, 1, True, None),
+    (2, 64, 12, 12, 72, 5, 2, False, None),
+    (40, 512, 2, 2, 64, 3, 2, False, None),
 ]
 
 
 @pytest.mark.parametrize("tile", list(range(61, 69)))
 @pytest.mark.parametrize("case", GEMM8_CASES)
 def test_gemm8_conv_tiles(sol, tile, case):
-    """The eight-wave 1x1 GEMM kernel in each tile shape (with and without the in-workgroup K split) against the
+    """The eight-wave implicit-GEMM kernel in each tile shape (with and without the in-workgroup K split) against the
     checker, every output element."""
-    N, C, H, W, K, st, res, pool = case
+    N, C, H, W, K, k, st, res, pool = case
     if C % 64 and tile not in (66, 67):
         pytest.skip("128-byte-row tiles need Cin % 64 == 0")
     rng = np.random.default_rng(hash((tile,) + case) % (2 ** 31))
     pd = dict(kind=pool, kh=2, kw=2, sh=2, sw=2, ph=0, pw=0) if pool else None
-    l, x, prm, r = make_block(sol, rng, "bf16", N, C, H, W, K, 1, st, 0, res=res, pool=pd)
+    l, x, prm, r = make_block(sol, rng, "bf16", N, C, H, W, K, k, st, k // 2, res=res, pool=pd)
     want, _, _ = orc.fused_conv(x, prm, l, r, bf16=True)
     sol.sol_debug_set_conv_tile(tile)
     try:
