@@ -19,21 +19,24 @@
 // every DMA is issued unconditionally (beyond the end through a buffer resource of size 0, which the
 // hardware turns into zeros) so that the in-order vmcnt bookkeeping is static, and there is no branch
 // inside the loop.  Eight waves per workgroup (two per SIMD) keep the matrix cores fed while one wave
-// waits.
+// waits.  With KSPL > 1 the waves of a group split the k-steps of every stage between them and add
+// their accumulators through LDS at the end, which keeps 64x64 wave tiles for output tiles as small as
+// 64x128 (layers with few output pixels and a long reduction).
 #include "conv_common.h"
 
 namespace sol {
 
-
-// T: element type; WP x WC: wave grid (pixels x channels); TP x TC: 32x32 accumulator blocks per wave;
-// XL: patch DMA instructions per wave and chunk (patch rows = XL * waves * 8 >= BP + 2W + 2);
-// MINW: waves per SIMD the register allocation must allow (4: two workgroups per CU);
-// NSW: weight ring stages; NPB: patch buffers (2, or 1 when Cin is a single chunk).
-template <typename T, int WP, int WC, int TP, int TC, int XL, int NSW, int NPB, int MINW = 2>
-__global__ void __launch_bounds__(WP *WC * 64, MINW) conv_halo_kernel(const ConvArgs a) {
+// T: element type; WP x WC x KSPL: wave grid (pixels x channels x split of a stage's k-steps); TP x TC: 32x32
+// accumulator blocks per wave; XL: patch DMA instructions per wave and chunk (patch rows = XL * waves * 8 >=
+// BP + 2W + 2); NSW: weight ring stages; NPB: patch buffers (2, or 1 when Cin is a single chunk); MINW: waves per
+// SIMD the register allocation must allow (4: two workgroups per CU).
+template <typename T, int WP, int WC, int KSPL, int TP, int TC, int XL, int NSW, int NPB, int MINW = 2>
+__global__ void __launch_bounds__(WP *WC *KSPL * 64, MINW) conv_halo_kernel(const ConvArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
     using namespace lds_pipe;
-    constexpr int NW = WP * WC, ES = (int)sizeof(T), ROWB = 128, BK = ROWB / ES;
+    constexpr int NG = WP * WC, NW = NG * KSPL, ES = (int)sizeof(T), ROWB = 128, BK = ROWB / ES;
+    constexpr int KS = ROWB / 32, NK = KS / KSPL;  // k-steps per stage, and per wave
+    constexpr int BQ = NK / 2;                     // the publishing barrier precedes this k-step slot
     constexpr int BP = WP * TP * 32, BC = WC * TC * 32;
     constexpr int WSTAGE = BC * ROWB;              // bytes of one weight stage
     constexpr int WL = BC / 8 / NW;                // weight DMA instructions per wave and stage
@@ -41,20 +44,16 @@ __global__ void __launch_bounds__(WP *WC * 64, MINW) conv_halo_kernel(const Conv
     constexpr int PROWS = XL * NW * 8;             // patch rows fetched per chunk
     constexpr int PBYTES = PROWS * ROWB + 1024;    // patch buffer: rows, then a block whose first row stays zero
     constexpr int LDSB = NSW * WSTAGE + NPB * PBYTES;
+    constexpr int ACCB = TC * TP * 16 * 64 * 4;    // bytes of one wave's accumulators
+    constexpr int EPI0 = (KSPL - 1) * NG * ACCB;   // epilogue strips start behind the K-split partials
+    static_assert(KS % KSPL == 0 && (NK % 2 == 0 || NK == 1), "k-step split");
     static_assert(BC % (8 * NW) == 0, "a weight stage must split into whole 1 KB segments per wave");
-    static_assert(D >= 2 && NSW <= 8, "ring depth");
+    static_assert(D >= 2 && D <= 8, "ring depth");
     static_assert(LDSB <= 160 * 1024, "LDS");
-    static_assert(NW * 32 * (TC * 32 + 4) * 4 <= LDSB, "epilogue strips must fit");
+    static_assert(EPI0 + NG * 32 * (TC * 32 + 4) * 4 <= LDSB, "K-split partials and epilogue strips must fit");
     static_assert(NPB == 1 || XL <= 6, "the patch of the next chunk is issued during taps 0..XL-1");
 
     __shared__ __align__(1024) unsigned char lds[LDSB];
-#ifdef SOL_HALO_TIMING
-    const long long t_entry = __builtin_readcyclecounter();
-    long long t_wait = 0, t_a, t_b;
-#define HT(x) x = __builtin_readcyclecounter()
-#else
-#define HT(x)
-#endif
 
     // all kernel arguments the loop needs in scalar registers at once: fetched piecemeal, each batch would cost its
     // own round trip to the argument buffer
@@ -63,7 +62,8 @@ __global__ void __launch_bounds__(WP *WC * 64, MINW) conv_halo_kernel(const Conv
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wp = wave % WP, wc = wave / WP;
+    const int grp = wave % NG, kq = wave / NG;     // output sub-tile of the wave, and its share of the k-steps
+    const int wp = grp % WP, wc = grp / WP;
     const int lr = lane & 31, lh = lane >> 5;
     const int lslot = lane & 7, lrow = lane >> 3;
 
@@ -73,10 +73,6 @@ __global__ void __launch_bounds__(WP *WC * 64, MINW) conv_halo_kernel(const Conv
     if (tile >= a.ntiles) return;
     const int p0 = (tile / a.ntc) * BP, c0 = (tile % a.ntc) * BC;
     const int W = a.W;
-#ifdef SOL_HALO_TIMING
-    asm volatile("" ::"s"(p0), "s"(c0), "s"(W));
-    const long long t_args = __builtin_readcyclecounter();
-#endif
 
     const unsigned xbytes = (unsigned)a.P * a.C * ES, wbytes = (unsigned)a.Cout * a.Kp * ES;
     const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, (int)xbytes, 0x00020000);
@@ -86,7 +82,6 @@ __global__ void __launch_bounds__(WP *WC * 64, MINW) conv_halo_kernel(const Conv
     const __amdgpu_buffer_rsrc_t wnull = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, 0, 0x00020000);
 
     unsigned char *const wring = lds, *const patch = lds + NSW * WSTAGE;
-
 
     // ---- DMA lane offsets: XL patch segments and WL weight segments per wave, 8 rows x 8 slots each
     unsigned xo[XL], wo[WL];
@@ -139,12 +134,14 @@ __global__ void __launch_bounds__(WP *WC * 64, MINW) conv_halo_kernel(const Conv
     const Affine8 aff = load_affine_unconditional<TC>(a, lane, c0 + wc * TC * 32);
     ResidualRegs<T, TP, TC> resregs;
     resregs.on = false;                                  // tight register budgets fetch residual rows in the epilogue instead
-    if constexpr (MINW < 4) prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
+    if constexpr (MINW < 4) {
+        if (kq == 0) prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
+    }
     if (tid < NPB * 32) *reinterpret_cast<unsigned *>(patch + (tid >> 5) * PBYTES + PROWS * ROWB + (tid & 31) * 4) = 0u;
 
-    // ---- fragment addresses (computed while the first DMAs are in flight).  ax[j][t]: LDS byte address (patch buffer 0, k-step 0) of tap t of this lane's
-    // pixel in pixel block j, or of the zero row when that tap lies outside the image.  The k-step flips
-    // address bits 5-6 (slot ^ 2*ks), the patch buffer adds a multiple of 1 KB.
+    // ---- fragment addresses (computed while the first DMAs are in flight).  ax[j][t]: LDS byte address (patch
+    // buffer 0, k-step 0) of tap t of this lane's pixel in pixel block j, or of the zero row when that tap lies
+    // outside the image.  The k-step flips address bits 5-6 (slot ^ 2*ks), the patch buffer adds a multiple of 1 KB.
     unsigned ax[TP][9];
 #pragma unroll
     for (int j = 0; j < TP; j++) {
@@ -164,23 +161,19 @@ __global__ void __launch_bounds__(WP *WC * 64, MINW) conv_halo_kernel(const Conv
             ax[j][t] = zero_row + ((0u - (hok[r] & wok[sx])) & (real - zero_row));
         }
     }
-#ifdef SOL_HALO_TIMING
-    const long long t_issued = __builtin_readcyclecounter();
-#endif
     wait_vmcnt<0>();                                     // patch 0, the first weight stages and the epilogue operands have landed
-#ifdef SOL_HALO_TIMING
-    const long long t_landed = __builtin_readcyclecounter();
-#endif
     __builtin_amdgcn_s_barrier();                        // ... everyone's; the zero rows are written
 
     u32x4_t fa[2][TC], fb[2][TP];
-    auto read_frags = [&](auto SET, auto TAP, auto KSI, unsigned wsoff, unsigned pboff) {
-        constexpr int set = decltype(SET)::value, t = decltype(TAP)::value, ks = decltype(KSI)::value;
-        const unsigned aw = xor_add(fw0, (unsigned)(ks << 5), wsoff);
+    // fragments of this wave's Q-th k-step of a stage: tap TAP, weight ring offset wsoff, patch buffer offset pboff
+    auto read_frags = [&](auto SET, auto TAP, auto Q, unsigned wsoff, unsigned pboff) {
+        constexpr int set = decltype(SET)::value, t = decltype(TAP)::value, q = decltype(Q)::value;
+        const unsigned kx = (unsigned)((kq * NK + q) << 5);
+        const unsigned aw = xor_add(fw0, kx, wsoff);
         static_for<TC>([&](auto I) { lds_read16<decltype(I)::value * 32 * ROWB>(fa[set][decltype(I)::value], aw); });
         static_for<TP>([&](auto J) {
             constexpr int j = decltype(J)::value;
-            lds_read16<0>(fb[set][j], xor_add(ax[j][t], (unsigned)(ks << 5), pboff));
+            lds_read16<0>(fb[set][j], xor_add(ax[j][t], kx, pboff));
         });
     };
     auto mfmas = [&](auto SET, auto &&between) {
@@ -195,16 +188,15 @@ __global__ void __launch_bounds__(WP *WC * 64, MINW) conv_halo_kernel(const Conv
     };
     auto nothing = [](auto) {};
     using I0 = std::integral_constant<int, 0>;
-    using I1 = std::integral_constant<int, 1>;
 
     read_frags(I0{}, I0{}, I0{}, 0u, 0u);
-#ifdef SOL_HALO_TIMING
-    const long long t_loop = __builtin_readcyclecounter();
-#endif
 
     unsigned wsoff = 0;                                  // ring slot (bytes) of the current stage
     int islot = D % NSW;                                 // ring slot the next weight DMA goes to
-    for (int c = 0; c < nchunks; c++) {
+    // one chunk of input channels = nine stages; PAR: which fragment set holds the chunk's first k-step (the sets
+    // alternate per k-step, so with an odd number of k-steps per chunk it alternates per chunk)
+    auto chunk = [&](auto PAR, int c) {
+        constexpr int par = decltype(PAR)::value;
         const unsigned pboff = NPB == 2 ? (unsigned)(c & 1) * PBYTES : 0u;
         const unsigned pbnext = NPB == 2 ? (unsigned)((c + 1) & 1) * PBYTES : 0u;
         const bool more_chunks = c + 1 < nchunks;
@@ -213,81 +205,103 @@ __global__ void __launch_bounds__(WP *WC * 64, MINW) conv_halo_kernel(const Conv
             constexpr int tn = (t + 1) % 9;             // tap of the next stage
             constexpr int ti = (t + D) % 9, ci = (t + D) / 9;   // tap / chunk increment of the stage whose DMA is issued
             const unsigned wsnext = wsoff + WSTAGE == NSW * WSTAGE ? 0u : wsoff + WSTAGE;
-
-            read_frags(I1{}, TAP, I1{}, wsoff, pboff);
-            wait_lgkmcnt<TC + TP>();
-            mfmas(I0{}, nothing);
-
-            read_frags(I0{}, TAP, std::integral_constant<int, 2>{}, wsoff, pboff);
-            wait_lgkmcnt<TC + TP>();
-            mfmas(I1{}, nothing);
-
-            // The next stage's weights (issued D-1 stages ago) have landed once only the DMAs issued after them
-            // are outstanding: per stage WL weight instructions, then one patch instruction in taps 0..XL-1.
-            constexpr int P1 = (NPB == 2 && t >= 1 && t - 1 < XL) ? 1 : 0, P2 = (NPB == 2 && t >= 2 && t - 2 < XL) ? 1 : 0;
-            static_assert(D == 2 || D == 3, "outstanding-DMA bookkeeping below is written for 2 or 3 stages ahead");
-            HT(t_a);
-            wait_vmcnt<D == 3 ? WL + P1 + P2 : P1>();
-            __builtin_amdgcn_s_barrier();               // ... for every wave; and nobody still reads stage s-1 / the other patch
-            HT(t_b);
-#ifdef SOL_HALO_TIMING
-            t_wait += t_b - t_a;
-#endif
-
-            const bool wreal = ci == 0 ? true : (c + ci < nchunks);
-            const unsigned wsoffg = (unsigned)ti * tapstride + (unsigned)((c + ci) * ROWB);
-            const int slot = islot;
-            read_frags(I1{}, TAP, std::integral_constant<int, 3>{}, wsoff, pboff);
-            wait_lgkmcnt<TC + TP>();
-            mfmas(I0{}, [&](auto Q) {
-                constexpr int q = decltype(Q)::value;
-                if constexpr (q < WL) issue_w(Q, slot, wsoffg, wreal);
-                if constexpr (q == TC * TP - 1) {
-                    static_for<(WL > TC * TP) ? WL - TC * TP : 0>([&](auto E) {
-                        issue_w(std::integral_constant<int, TC * TP + decltype(E)::value>{}, slot, wsoffg, wreal);
+            static_for<NK>([&](auto Q) {
+                constexpr int q = decltype(Q)::value, cur = (par + t * NK + q) & 1;
+                if constexpr (q == BQ) {
+                    // The next stage's weights (issued D-1 stages ago) have landed once only the DMAs issued after
+                    // them are outstanding: per stage WL weight instructions, then one patch instruction in taps 0..XL-1.
+                    // (The stages issued since are s+2 .. s+D-1, issued during stages s-D+2 .. s-1; the patch instruction of
+                    // stage s-D+1 follows that stage's weights, i.e. the ones being waited for, so it counts as well.)
+                    constexpr int NPATCH = [] { int n = 0; for (int k = 1; k <= D - 1; k++) n += (NPB == 2 && t - k >= 0 && t - k < XL) ? 1 : 0; return n; }();
+                    // Before the last tap's barrier the next chunk's patch (last instruction issued in tap XL-1) must have
+                    // landed too: then at most the weights issued in taps XL..7 may be outstanding.
+                    constexpr int GEN = (D - 2) * WL + NPATCH, LASTTAP = (8 - XL) * WL;
+                    wait_vmcnt<(t == 8 && NPB == 2 && LASTTAP < GEN) ? LASTTAP : GEN>();
+                    __builtin_amdgcn_s_barrier();       // ... for every wave; and nobody still reads stage s-1 / the other patch
+                }
+                // fragments of the next k-step: of this stage, or (published by the barrier) the next stage's first
+                if constexpr (q + 1 < NK) read_frags(std::integral_constant<int, cur ^ 1>{}, TAP, std::integral_constant<int, q + 1>{}, wsoff, pboff);
+                else read_frags(std::integral_constant<int, cur ^ 1>{}, std::integral_constant<int, tn>{}, I0{}, wsnext, t == 8 ? pbnext : pboff);
+                wait_lgkmcnt<TC + TP>();
+                if constexpr (q == BQ) {
+                    const bool wreal = ci == 0 ? true : (c + ci < nchunks);
+                    const unsigned wsoffg = (unsigned)ti * tapstride + (unsigned)((c + ci) * ROWB);
+                    const int slot = islot;
+                    mfmas(std::integral_constant<int, cur>{}, [&](auto M) {
+                        constexpr int m = decltype(M)::value;
+                        if constexpr (m < WL) issue_w(M, slot, wsoffg, wreal);
+                        if constexpr (m == TC * TP - 1) {
+                            static_for<(WL > TC * TP) ? WL - TC * TP : 0>([&](auto E) {
+                                issue_w(std::integral_constant<int, TC * TP + decltype(E)::value>{}, slot, wsoffg, wreal);
+                            });
+                            if constexpr (NPB == 2 && t < XL) issue_patch(TAP, (c + 1) & 1, (unsigned)((c + 1) * ROWB), more_chunks);
+                        }
                     });
-                    if constexpr (NPB == 2 && t < XL) issue_patch(TAP, (c + 1) & 1, (unsigned)((c + 1) * ROWB), more_chunks);
+                } else {
+                    mfmas(std::integral_constant<int, cur>{}, nothing);
                 }
             });
             islot = islot + 1 == NSW ? 0 : islot + 1;
-
-            // first fragments of the next stage (published by the barrier above)
-            read_frags(I0{}, std::integral_constant<int, tn>{}, I0{}, wsnext, t == 8 ? pbnext : pboff);
-            wait_lgkmcnt<TC + TP>();
-            mfmas(I1{}, nothing);
             wsoff = wsnext;
         });
+    };
+    if constexpr (NK % 2 == 0) {
+        for (int c = 0; c < nchunks; c++) chunk(I0{}, c);
+    } else {
+        for (int c = 0; c < nchunks; c += 2) {
+            chunk(I0{}, c);
+            if (c + 1 < nchunks) chunk(std::integral_constant<int, 1>{}, c + 1);
+        }
     }
     wait_vmcnt<0>();                                     // the zero-fill DMAs of the tail
     wait_lgkmcnt<0>();
-    __builtin_amdgcn_s_barrier();                        // every wave is done with the ring: it becomes epilogue strips
-#ifdef SOL_HALO_TIMING
-    const long long t_epi = __builtin_readcyclecounter();
-#endif
-    conv_epilogue_auto<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32,
-                                  aff, LinearRows{a.P}, resregs);
-#ifdef SOL_HALO_TIMING
-    if (a.prepool && lane == 0) {   // harness build only: phase durations, entry/exit time stamps and the hardware id per wave
-        long long *dbg = reinterpret_cast<long long *>(a.prepool) + ((size_t)blockIdx.x * NW + wave) * 8;
-        dbg[0] = t_loop - t_entry; dbg[2] = ((t_args - t_entry) << 40) | ((t_issued - t_args) << 20) | (t_landed - t_issued); dbg[1] = t_epi - t_loop; (void)t_wait; dbg[3] = __builtin_readcyclecounter() - t_epi; dbg[4] = t_entry;
-        dbg[5] = __builtin_readcyclecounter();
-        dbg[6] = ((long long)__builtin_amdgcn_s_getreg(20 | (31 << 11)) << 32) | (unsigned)__builtin_amdgcn_s_getreg(4 | (31 << 11));
-        dbg[7] = __builtin_amdgcn_s_memrealtime();
+    __builtin_amdgcn_s_barrier();                        // every wave is done with the ring: it becomes partials and strips
+
+    if constexpr (KSPL > 1) {
+        // waves kq > 0 park their accumulators (lane-contiguous 16-byte pieces), wave kq == 0 of the group adds them
+        float *part = reinterpret_cast<float *>(lds);
+        if (kq > 0) {
+            float *dst = part + ((size_t)((kq - 1) * NG + grp) * (ACCB / 4)) + lane * 4;
+#pragma unroll
+            for (int i = 0; i < TC; i++)
+#pragma unroll
+                for (int j = 0; j < TP; j++)
+#pragma unroll
+                    for (int g = 0; g < 4; g++)
+                        *reinterpret_cast<float4 *>(dst + ((i * TP + j) * 4 + g) * 256) =
+                            make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+        }
+        __syncthreads();
+        if (kq > 0) return;
+#pragma unroll
+        for (int k = 1; k < KSPL; k++) {
+            const float *src = part + ((size_t)((k - 1) * NG + grp) * (ACCB / 4)) + lane * 4;
+#pragma unroll
+            for (int i = 0; i < TC; i++)
+#pragma unroll
+                for (int j = 0; j < TP; j++)
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        const float4 v = *reinterpret_cast<const float4 *>(src + ((i * TP + j) * 4 + g) * 256);
+                        acc[i][j][4 * g] += v.x; acc[i][j][4 * g + 1] += v.y; acc[i][j][4 * g + 2] += v.z; acc[i][j][4 * g + 3] += v.w;
+                    }
+        }
     }
-#endif
+    conv_epilogue_auto<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds + EPI0), grp, lane, p0 + wp * TP * 32, c0 + wc * TC * 32,
+                                  aff, LinearRows{a.P}, resregs);
 #endif
 }
 
-template <typename T, int WP, int WC, int TP, int TC, int XL, int NSW, int NPB, int MINW = 2>
+template <typename T, int WP, int WC, int KSPL, int TP, int TC, int XL, int NSW, int NPB, int MINW = 2>
 static sol_status launch_halo_cfg(ConvArgs a, hipStream_t st) {
-    constexpr int BP = WP * TP * 32, BC = WC * TC * 32, PROWS = XL * WP * WC * 8;
+    constexpr int BP = WP * TP * 32, BC = WC * TC * 32, PROWS = XL * WP * WC * KSPL * 8;
     SOL_REQUIRE(BP + 2 * a.W + 2 <= PROWS, SOL_ERR_UNSUPPORTED, "halo tile: image width %d needs %d patch rows, tile has %d", a.W,
                 BP + 2 * a.W + 2, PROWS);
     SOL_REQUIRE(NPB == 2 || a.C * (int)sizeof(T) == 128, SOL_ERR_UNSUPPORTED, "single patch buffer needs Cin = one 128-byte chunk");
     a.ntc = ceil_div(a.Cout, BC);
     a.ntiles = ceil_div(a.P, BP) * a.ntc;
     const int grid = ((a.ntiles + 7) / 8) * 8;
-    hipLaunchKernelGGL((conv_halo_kernel<T, WP, WC, TP, TC, XL, NSW, NPB, MINW>), dim3(grid), dim3(WP * WC * 64), 0, st, a);
+    hipLaunchKernelGGL((conv_halo_kernel<T, WP, WC, KSPL, TP, TC, XL, NSW, NPB, MINW>), dim3(grid), dim3(WP * WC * KSPL * 64), 0, st, a);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }
@@ -301,21 +315,29 @@ bool halo_kernel_applies(const ConvArgs &a, int dt) {
            a.scale && a.shift && a.Cout % 8 == 0 && a.Ho == a.H && a.Wo == a.W && a.W <= 62 && xb < 2147483648.0 && wb < 2147483648.0;
 }
 
+// Shape heuristic (sol_network_autotune refines it by timing): one workgroup per CU wants about 200 tiles or
+// several rounds of them.
 int halo_choose_tile(const ConvArgs &a) {
     const bool single = a.C == 64;
-    if (a.Cout <= 64) return a.W <= 30 ? H_256x64_x5 : (single ? H_256x64_x6s : 0);
+    if (a.Cout <= 64) return a.W <= 30 ? H_256x64_x5 : (single ? H_256x64_x6s2 : 0);
     if (a.W > 30) return 0;
     const long nt256 = (long)ceil_div(a.P, 256) * ceil_div(a.Cout, 128);
-    return nt256 >= 160 ? H_256x128_x5 : H_128x128_x3;
+    if (nt256 >= 160) return H_256x128_x5;
+    if (nt256 >= 80) return H_128x128_k2;
+    return H_64x128_k4;
 }
 
 sol_status launch_conv_halo(const ConvArgs &a, int tile, hipStream_t st) {
     switch (tile) {
-        case H_256x128_x5: return launch_halo_cfg<bf16_t, 4, 2, 2, 2, 5, 4, 2>(a, st);
-        case H_128x128_x3: return launch_halo_cfg<bf16_t, 2, 4, 2, 1, 3, 4, 2>(a, st);
-        case H_256x64_x5: return launch_halo_cfg<bf16_t, 4, 2, 2, 1, 5, 4, 2>(a, st);
-        case H_256x64_x6s: return launch_halo_cfg<bf16_t, 4, 2, 2, 1, 6, 4, 1>(a, st);
-        case H_256x64_x6s2: return launch_halo_cfg<bf16_t, 4, 2, 2, 1, 6, 3, 1, 4>(a, st);     // 74 KB, <= 128 VGPRs: two workgroups per CU
+        //                                                WP WC KSPL TP TC XL NSW NPB MINW
+        case H_256x128_x5: return launch_halo_cfg<bf16_t, 4, 2, 1, 2, 2, 5, 4, 2>(a, st);
+        case H_128x128_x3: return launch_halo_cfg<bf16_t, 2, 4, 1, 2, 1, 3, 4, 2>(a, st);
+        case H_256x64_x5: return launch_halo_cfg<bf16_t, 4, 2, 1, 2, 1, 5, 4, 2>(a, st);
+        case H_256x64_x6s: return launch_halo_cfg<bf16_t, 4, 2, 1, 2, 1, 6, 4, 1>(a, st);
+        case H_256x64_x6s2: return launch_halo_cfg<bf16_t, 4, 2, 1, 2, 1, 6, 3, 1, 4>(a, st);   // 74 KB, <= 128 VGPRs: two workgroups per CU
+        case H_128x128_k2: return launch_halo_cfg<bf16_t, 2, 2, 2, 2, 2, 3, 4, 2>(a, st);
+        case H_64x128_k4: return launch_halo_cfg<bf16_t, 1, 2, 4, 2, 2, 2, 5, 2>(a, st);
+        case H_128x64_k4: return launch_halo_cfg<bf16_t, 2, 1, 4, 2, 2, 3, 8, 2>(a, st);
         default: SOL_FAIL(SOL_ERR_UNSUPPORTED, "unknown halo conv tile id %d", tile);
     }
 }

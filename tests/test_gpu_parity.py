@@ -147,7 +147,7 @@ HALO_CASES = [
 ]
 
 
-@pytest.mark.parametrize("tile", [41, 42, 43])
+@pytest.mark.parametrize("tile", [41, 42, 43, 46, 47, 48])
 @pytest.mark.parametrize("case", HALO_CASES)
 def test_halo_conv_tiles(sol, tile, case):
     """The 3x3 halo-in-LDS kernel in each of its tile shapes against the checker, every output element."""
@@ -191,7 +191,7 @@ def test_halo_conv_exact_integers(sol):
     prm = {"w": w, "bias": np.zeros(K, np.float32)}
     want, _, _ = orc.fused_conv(x, prm, l, None, bf16=True)
     assert np.abs(want).max() <= 256 and np.abs(want).max() > 4
-    for tile in (41, 42, 43):
+    for tile in (41, 42, 43, 46, 47, 48):
         sol.sol_debug_set_conv_tile(tile)
         try:
             got, _, _ = run_block(sol, "bf16", l, x, prm, None)
