@@ -722,13 +722,23 @@ sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *
     SOL_HIP(hipEventCreate(&e0));
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); SOL_FAIL(SOL_ERR_HIP, "hipEventCreate failed"); }
     sol_status rs = SOL_OK;
-    auto time_layer = [&](int i, float *ms) -> sol_status {   // reps launches of layer i between two events
-        for (int r = 0; r < 2; r++) SOL_TRY(run_layers(net, x, y, workspace, workspace_bytes, i, i, st));
-        SOL_HIP(hipEventRecord(e0, st));
-        for (int r = 0; r < reps; r++) SOL_TRY(run_layers(net, x, y, workspace, workspace_bytes, i, i, st));
-        SOL_HIP(hipEventRecord(e1, st));
-        SOL_HIP(hipEventSynchronize(e1));
-        SOL_HIP(hipEventElapsedTime(ms, e0, e1));
+    // Layer i timed the way it runs inside a pass: directly behind its producer, whose traffic leaves the layer's
+    // input in the caches and pushes its weights out of L2 (a layer repeated back to back would find its weights
+    // hot and favour the wrong kernels).  One event pair per launch, `reps` launches.
+    auto time_layer = [&](int i, float *ms) -> sol_status {
+        const int prod = net->layers[i].src >= 0 ? net->layers[i].src : -1;
+        float total = 0.f;
+        for (int r = 0; r < reps + 1; r++) {
+            if (prod >= 0) SOL_TRY(run_layers(net, x, y, workspace, workspace_bytes, prod, prod, st));
+            SOL_HIP(hipEventRecord(e0, st));
+            SOL_TRY(run_layers(net, x, y, workspace, workspace_bytes, i, i, st));
+            SOL_HIP(hipEventRecord(e1, st));
+            SOL_HIP(hipEventSynchronize(e1));
+            float t = 0.f;
+            SOL_HIP(hipEventElapsedTime(&t, e0, e1));
+            if (r > 0) total += t;                          // the first launch is a warm-up
+        }
+        *ms = total;
         return SOL_OK;
     };
     for (int i = 0; i < nl && rs == SOL_OK; i++) {

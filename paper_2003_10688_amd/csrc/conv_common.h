@@ -62,6 +62,18 @@ template <int ROWB> __device__ __forceinline__ int swz(int row) { return ROWB ==
 
 }  // namespace lds_pipe
 
+// Warms this XCD's L2 with a range of the layer's packed weights.  Inside a network the weights of a layer are
+// cold when it starts, every workgroup streams the same rows in lock step, and each stage would stall on an HBM
+// round trip; instead the workgroups of an XCD (blockIdx & 7) touch one dword per 128-byte line of the range
+// between them at kernel entry, all misses in flight at once.  The touched dwords are dropped into a per-wave LDS
+// sink of 256 bytes (a load into a register would have to be waited for, a DMA does not).
+__device__ __forceinline__ void warm_l2(const unsigned char *base, unsigned bytes, unsigned char *sink_wave, int tid, int nthreads) {
+    const unsigned nx = gridDim.x >> 3, lines = bytes >> 7;
+    for (unsigned l = (blockIdx.x >> 3) * nthreads + tid; l < lines; l += nx * nthreads)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(base + ((size_t)l << 7)),
+                                         (__attribute__((address_space(3))) void *)sink_wave, 4, 0, 0);
+}
+
 // GEMM row m -> output pixel.  With a fused 2x2 pool the rows are ordered window-major, so that the
 // four elements of one pooling window sit in four adjacent lanes in row-major window order.
 __device__ __forceinline__ void decode_pixel(const ConvArgs &a, int m, int &n, int &op, int &oq) {

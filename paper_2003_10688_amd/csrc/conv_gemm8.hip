@@ -36,11 +36,12 @@ __global__ void __launch_bounds__(512) conv_gemm8_kernel(const ConvArgs a) {
     constexpr int EPI0 = (KSPL - 1) * NG * ACCB;           // epilogue strips start behind the K-split partials
     static_assert(WP * WC * KSPL == NW && KS % KSPL == 0, "wave grid");
     static_assert(BP % (RSEG * NW) == 0 && BC % (RSEG * NW) == 0, "tile rows must split into whole DMA segments per wave");
-    static_assert(NS >= 2 && NS * STAGE <= 160 * 1024, "ring");
+    static_assert(NS >= 2 && NS * STAGE + NW * 256 <= 160 * 1024, "ring");
     static_assert(EPI0 + NG * 32 * (TC * 32 + 4) * 4 <= NS * STAGE, "K-split partials and epilogue strips must fit in the ring");
     static_assert((D - 1) * L < 64, "vmcnt");
 
     __shared__ __align__(1024) unsigned char lds[NS * STAGE];
+    __shared__ __align__(256) unsigned char l2sink[NW * 256];   // write-only landing pad of the L2 warm-up loads
 
     // every kernel argument the prologue needs, fetched in one batch
     asm volatile("" ::"s"(a.x), "s"(a.w), "s"(a.scale), "s"(a.shift), "s"(a.res), "s"(a.y), "s"(a.P), "s"(a.C), "s"(a.Cout),
@@ -75,6 +76,12 @@ __global__ void __launch_bounds__(512) conv_gemm8_kernel(const ConvArgs a) {
     const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, (int)wbytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t xnull = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, 0, 0x00020000);
     const __amdgpu_buffer_rsrc_t wnull = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, 0, 0x00020000);
+
+    {   // warm this XCD's L2 with the weights it will stream (with the channel split: only its channel tiles' rows)
+        const unsigned slice = (unsigned)(a.cpx * BC * a.Kp) * ES, first = a.cpx > 0 ? min(wbytes, (unsigned)xcd * slice) : 0u;
+        warm_l2(static_cast<const unsigned char *>(a.w) + first, a.cpx > 0 ? min(slice, wbytes - first) : wbytes, l2sink + wave * 256,
+                tid, NW * 64);
+    }
 
     // ---- DMA lane offsets (one 16-byte slot of XL pixel rows and WL weight rows per stage); bit t of xinv: filter
     // tap t of that row reads padding (its offset is pushed out of range, the hardware returns zeros)

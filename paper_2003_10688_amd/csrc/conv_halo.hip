@@ -49,11 +49,12 @@ __global__ void __launch_bounds__(WP *WC *KSPL * 64, MINW) conv_halo_kernel(cons
     static_assert(KS % KSPL == 0 && (NK % 2 == 0 || NK == 1), "k-step split");
     static_assert(BC % (8 * NW) == 0, "a weight stage must split into whole 1 KB segments per wave");
     static_assert(D >= 2 && D <= 8, "ring depth");
-    static_assert(LDSB <= 160 * 1024, "LDS");
+    static_assert(LDSB + NW * 256 <= 160 * 1024, "LDS");
     static_assert(EPI0 + NG * 32 * (TC * 32 + 4) * 4 <= LDSB, "K-split partials and epilogue strips must fit");
     static_assert(NPB == 1 || XL <= 6, "the patch of the next chunk is issued during taps 0..XL-1");
 
     __shared__ __align__(1024) unsigned char lds[LDSB];
+    __shared__ __align__(256) unsigned char l2sink[NW * 256];   // write-only landing pad of the L2 warm-up loads
 
     // all kernel arguments the loop needs in scalar registers at once: fetched piecemeal, each batch would cost its
     // own round trip to the argument buffer
@@ -82,6 +83,7 @@ __global__ void __launch_bounds__(WP *WC *KSPL * 64, MINW) conv_halo_kernel(cons
     const __amdgpu_buffer_rsrc_t wnull = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, 0, 0x00020000);
 
     unsigned char *const wring = lds, *const patch = lds + NSW * WSTAGE;
+    warm_l2(static_cast<const unsigned char *>(a.w), wbytes, l2sink + wave * 256, tid, NW * 64);
 
     // ---- DMA lane offsets: XL patch segments and WL weight segments per wave, 8 rows x 8 slots each
     unsigned xo[XL], wo[WL];
