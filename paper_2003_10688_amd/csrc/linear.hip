@@ -2,10 +2,11 @@
 //
 // With a batch of a few dozen rows the GEMM has one or two pixel tiles, so the convolution kernels, which
 // parallelise over output tiles, leave most of the chip idle and walk the whole reduction in one workgroup.
-// Here a workgroup owns 64 rows x 32 output features and its eight waves split the reduction between them;
+// Here a workgroup owns 32 rows x 32 output features and its eight waves split the reduction between them;
 // MFMA fragments (16 bytes of consecutive reduction elements of one row) are loaded straight from global
-// memory into registers, eight steps in flight per wave (the kernel is latency-bound) -- x is tiny and
-// L2-resident, every weight row is read exactly once -- and the eight partial accumulators are added through LDS in a fixed order.
+// memory into registers, sixteen steps in flight per wave (the kernel is latency-bound: for 2048 inputs that is
+// the whole reduction in one round trip) -- x is tiny and
+// L2-resident -- and the eight partial accumulators are added through LDS in a fixed order behind one barrier.
 #include "conv_common.h"
 
 namespace sol {
@@ -13,79 +14,61 @@ namespace sol {
 template <typename T>
 __global__ void __launch_bounds__(512) linear_kernel(const ConvArgs a) {
     constexpr int EPC = 16 / (int)sizeof(T);       // reduction elements per fragment
-    constexpr int UN = 8, NWV = 8;                 // k-steps in flight per wave; waves per workgroup
-    __shared__ float red[64][33];
+    constexpr int UN = 16, NWV = 8;                // k-steps in flight per wave; waves per workgroup
+    __shared__ float red[NWV][32][33];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lr = lane & 31, lh = lane >> 5;
-    const int n0 = blockIdx.x * 32, m0 = blockIdx.y * 64;
+    const int n0 = blockIdx.x * 32, m0 = blockIdx.y * 32;
     const int M = a.P, K = a.C, N = a.Cout;
     const T *__restrict__ xg = static_cast<const T *>(a.x);
     const T *__restrict__ wg = static_cast<const T *>(a.w);
 
-    const bool wok = n0 + lr < N, xok0 = m0 + lr < M, xok1 = m0 + 32 + lr < M;
+    const bool wok = n0 + lr < N, xok = m0 + lr < M;
     const T *wp = wg + (size_t)(wok ? n0 + lr : 0) * a.Kp + lh * EPC;
-    const T *xp0 = xg + (size_t)(xok0 ? m0 + lr : 0) * K + lh * EPC;
-    const T *xp1 = xg + (size_t)(xok1 ? m0 + 32 + lr : 0) * K + lh * EPC;
+    const T *xp = xg + (size_t)(xok ? m0 + lr : 0) * K + lh * EPC;
     const uint4 zero = make_uint4(0, 0, 0, 0);
 
-    f32x16_t acc[2];
+    f32x16_t acc;
 #pragma unroll
-    for (int j = 0; j < 2; j++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) acc[j][e] = 0.f;
+    for (int e = 0; e < 16; e++) acc[e] = 0.f;
 
     const int nsteps = K / (2 * EPC);              // one step = 2*EPC reduction elements (both lane halves)
     for (int s0 = wave * UN; s0 < nsteps; s0 += NWV * UN) {
-        uint4 fa[UN], fb0[UN], fb1[UN];
+        uint4 fa[UN], fb[UN];
 #pragma unroll
         for (int u = 0; u < UN; u++) {
             const int k = (s0 + u) * 2 * EPC;
             const bool ok = s0 + u < nsteps;
             fa[u] = (ok && wok) ? *reinterpret_cast<const uint4 *>(wp + k) : zero;
-            fb0[u] = (ok && xok0) ? *reinterpret_cast<const uint4 *>(xp0 + k) : zero;
-            fb1[u] = (ok && xok1) ? *reinterpret_cast<const uint4 *>(xp1 + k) : zero;
+            fb[u] = (ok && xok) ? *reinterpret_cast<const uint4 *>(xp + k) : zero;
         }
 #pragma unroll
-        for (int u = 0; u < UN; u++) {
-            Mma<T>::run(acc[0], fa[u], fb0[u]);
-            Mma<T>::run(acc[1], fa[u], fb1[u]);
-        }
+        for (int u = 0; u < UN; u++) Mma<T>::run(acc, fa[u], fb[u]);
     }
 
-    // accumulator register e of lane l: feature 8*(e/4) + 4*(l/32) + e%4, row l%32 (+32 for the second block)
-    for (int w = 0; w < NWV; w++) {
-        if (wave == w) {
+    // accumulator register e of lane l: feature 8*(e/4) + 4*(l/32) + e%4, row l%32.  Every wave parks its partial
+    // block, then each of the first 256 threads adds the eight partials of 4 outputs in wave order.
 #pragma unroll
-            for (int j = 0; j < 2; j++)
-#pragma unroll
-                for (int e = 0; e < 16; e++) {
-                    float &d = red[j * 32 + lr][8 * (e / 4) + 4 * lh + e % 4];
-                    d = w == 0 ? acc[j][e] : d + acc[j][e];
-                }
-        }
-        __syncthreads();
-    }
+    for (int e = 0; e < 16; e++) red[wave][lr][8 * (e / 4) + 4 * lh + e % 4] = acc[e];
+    __syncthreads();
 
     if (tid >= 256) return;
-    const int row = tid >> 2, f0 = (tid & 3) * 8;
+    const int row = tid >> 3, f0 = (tid & 7) * 4;
     const int m = m0 + row;
     if (m >= M) return;
     T *__restrict__ yg = static_cast<T *>(a.y);
     const T *__restrict__ resg = static_cast<const T *>(a.res);
-    const int nv = min(8, N - (n0 + f0));
-    if (nv <= 0) return;
-    float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
+    for (int e = 0; e < 4; e++) {
         const int o = n0 + f0 + e;
-        float t = red[row][f0 + e];
-        if (e < nv) {
-            t = t * (a.scale ? a.scale[o] : 1.f) + (a.shift ? a.shift[o] : 0.f);
-            if (resg) t += Elem<T>::load(resg + (size_t)m * N + o);
-            if (a.act == SOL_ACT_RELU) t = t > 0.f ? t : 0.f;
-        }
-        v[e] = t;
+        if (o >= N) break;
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < NWV; w++) t += red[w][row][f0 + e];
+        t = t * (a.scale ? a.scale[o] : 1.f) + (a.shift ? a.shift[o] : 0.f);
+        if (resg) t += Elem<T>::load(resg + (size_t)m * N + o);
+        if (a.act == SOL_ACT_RELU) t = t > 0.f ? t : 0.f;
+        Elem<T>::store(yg + (size_t)m * N + o, t);
     }
-    store8<T>(yg + (size_t)m * N + n0 + f0, v, nv, (N & 7) == 0);
 }
 
 // 1x1 "convolution" over a [rows,1,1,C] tensor with few rows, reduction a whole number of MFMA steps
@@ -95,7 +78,7 @@ bool linear_kernel_applies(const ConvArgs &a, int dt) {
 }
 
 sol_status launch_linear(const ConvArgs &a, int dt, hipStream_t st) {
-    const dim3 grid(ceil_div(a.Cout, 32), ceil_div(a.P, 64));
+    const dim3 grid(ceil_div(a.Cout, 32), ceil_div(a.P, 32));
     if (dt == SOL_BF16)
         hipLaunchKernelGGL(linear_kernel<bf16_t>, grid, dim3(512), 0, st, a);
     else
