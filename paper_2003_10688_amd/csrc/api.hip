@@ -847,23 +847,64 @@ sol_status sol_network_sgd_step(sol_network *net, float lr, float momentum, void
     SOL_REQUIRE(net->training, SOL_ERR_UNSUPPORTED, "network was not created with SOL_NET_TRAINING");
     SOL_REQUIRE(net->params, SOL_ERR_WORKSPACE, "no parameter buffer bound (sol_network_bind_params)");
     hipStream_t st = (hipStream_t)stream;
+    // every tensor update in one launch, every re-pack in a second one (the tables travel in the kernel arguments;
+    // networks with more tensors than a table holds take several launches)
+    SgdBatch sb;
+    PackBatch pb;
+    sb.nseg = 0; sb.first_block[0] = 0;
+    pb.nseg = 0; pb.first_block[0] = 0;
+    auto flush_sgd = [&]() -> sol_status {
+        const sol_status r = launch_sgd_batch(sb, lr, momentum, st);
+        sb.nseg = 0; sb.first_block[0] = 0;
+        return r;
+    };
+    auto flush_pack = [&]() -> sol_status {
+        const sol_status r = launch_pack_batch(pb, net->input.dtype, st);
+        pb.nseg = 0; pb.first_block[0] = 0;
+        return r;
+    };
+    auto add_sgd = [&](float *w, float *v, const float *g, long n) -> sol_status {
+        if (n <= 0) return SOL_OK;
+        if (sb.nseg == SGD_MAX_SEG) SOL_TRY(flush_sgd());
+        const int i = sb.nseg++;
+        sb.w[i] = w; sb.v[i] = v; sb.g[i] = g; sb.n[i] = n;
+        sb.first_block[i + 1] = sb.first_block[i] + (int)((n + SGD_ELEMS_PER_BLOCK - 1) / SGD_ELEMS_PER_BLOCK);
+        return SOL_OK;
+    };
+    auto add_pack = [&](const float *w, void *out, const sol_conv_desc &cd, bool flip) -> sol_status {
+        const sol_conv_desc td{cd.cin, cd.cout, cd.kh, cd.kw, 1, 1, 0, 0};   // the flipped pack belongs to the transposed convolution
+        const int Kp = packed_k(flip ? td : cd, net->input.dtype);
+        const long total = (long)(flip ? cd.cin : cd.cout) * Kp;
+        if (total <= 0) return SOL_OK;
+        if (pb.nseg == PACK_MAX_SEG) SOL_TRY(flush_pack());
+        const int i = pb.nseg++;
+        pb.w[i] = w; pb.out[i] = out; pb.K[i] = cd.cout; pb.C[i] = cd.cin; pb.R[i] = cd.kh; pb.S[i] = cd.kw; pb.Kp[i] = Kp;
+        pb.flip[i] = flip ? 1 : 0;
+        pb.first_block[i + 1] = pb.first_block[i] + (int)((total + PACK_ELEMS_PER_BLOCK - 1) / PACK_ELEMS_PER_BLOCK);
+        return SOL_OK;
+    };
     for (const auto &lp : net->layers) {
         if (!(lp.L.kind == SOL_LAYER_CONV || lp.L.kind == SOL_LAYER_LINEAR) || !lp.has_grad) continue;
         SOL_REQUIRE(lp.params_set, SOL_ERR_WORKSPACE, "parameters not set");
         const bool bn = lp.L.kind == SOL_LAYER_CONV && lp.L.has_bn;
         float *w = reinterpret_cast<float *>(net->params + lp.master_off);
-        SOL_TRY(launch_sgd(w, reinterpret_cast<float *>(net->params + lp.vel_off),
-                           reinterpret_cast<const float *>(net->params + lp.grad_off),
-                           (long)lp.cd.cout * lp.cd.cin * lp.cd.kh * lp.cd.kw, lr, momentum, st));
+        SOL_TRY(add_sgd(w, reinterpret_cast<float *>(net->params + lp.vel_off), reinterpret_cast<const float *>(net->params + lp.grad_off),
+                        (long)lp.cd.cout * lp.cd.cin * lp.cd.kh * lp.cd.kw));
         if (bn) {
-            SOL_TRY(launch_sgd(vec_ptr(net, lp, VEC_GAMMA), vec_ptr(net, lp, VEC_V_GAMMA), vec_ptr(net, lp, VEC_G_GAMMA), lp.cd.cout, lr, momentum, st));
-            SOL_TRY(launch_sgd(vec_ptr(net, lp, VEC_BETA), vec_ptr(net, lp, VEC_V_BETA), vec_ptr(net, lp, VEC_G_BETA), lp.cd.cout, lr, momentum, st));
+            SOL_TRY(add_sgd(vec_ptr(net, lp, VEC_GAMMA), vec_ptr(net, lp, VEC_V_GAMMA), vec_ptr(net, lp, VEC_G_GAMMA), lp.cd.cout));
+            SOL_TRY(add_sgd(vec_ptr(net, lp, VEC_BETA), vec_ptr(net, lp, VEC_V_BETA), vec_ptr(net, lp, VEC_G_BETA), lp.cd.cout));
         } else {
-            SOL_TRY(launch_sgd(vec_ptr(net, lp, VEC_BIAS), vec_ptr(net, lp, VEC_V_BIAS), vec_ptr(net, lp, VEC_G_BIAS), lp.cd.cout, lr, momentum, st));
+            SOL_TRY(add_sgd(vec_ptr(net, lp, VEC_BIAS), vec_ptr(net, lp, VEC_V_BIAS), vec_ptr(net, lp, VEC_G_BIAS), lp.cd.cout));
         }
-        SOL_TRY(launch_pack(lp.cd, net->input.dtype, w, net->params + lp.w_off, false, st));
-        if (lp.src >= 0) SOL_TRY(launch_pack_flip(lp.cd, net->input.dtype, w, net->params + lp.wT_off, st));
     }
+    SOL_TRY(flush_sgd());
+    for (const auto &lp : net->layers) {           // behind the update on the same stream
+        if (!(lp.L.kind == SOL_LAYER_CONV || lp.L.kind == SOL_LAYER_LINEAR) || !lp.has_grad) continue;
+        const float *w = reinterpret_cast<const float *>(net->params + lp.master_off);
+        SOL_TRY(add_pack(w, net->params + lp.w_off, lp.cd, false));
+        if (lp.src >= 0) SOL_TRY(add_pack(w, net->params + lp.wT_off, lp.cd, true));
+    }
+    SOL_TRY(flush_pack());
     return SOL_OK;
 }
 

@@ -170,6 +170,28 @@ sol_status launch_gap_bwd(const void *dy, void *dx, int N, int HW, int C, int fi
 sol_status launch_softmax_ce(const void *logits, const int32_t *labels, void *dlogits, float *row_loss, float *loss, int N,
                              int C, int dt, hipStream_t st);
 sol_status launch_sgd(float *w, float *v, const float *g, long n, float lr, float mu, hipStream_t st);
+
+// Batched parameter update: up to SGD_MAX_SEG tensors updated, and up to PACK_MAX_SEG packed weight buffers rebuilt,
+// by one launch each (a ResNet-18-shaped step otherwise spends ~100 launches on them).  The segment tables travel
+// in the kernel arguments, so nothing is allocated or copied.
+constexpr int SGD_MAX_SEG = 96, PACK_MAX_SEG = 64;
+struct SgdBatch {
+    int nseg;
+    int first_block[SGD_MAX_SEG + 1];     // blocks [first_block[i], first_block[i+1]) work on segment i
+    float *w[SGD_MAX_SEG], *v[SGD_MAX_SEG];
+    const float *g[SGD_MAX_SEG];
+    long n[SGD_MAX_SEG];
+};
+struct PackBatch {
+    int nseg;
+    int first_block[PACK_MAX_SEG + 1];
+    const float *w[PACK_MAX_SEG];          // fp32 master, framework layout [K][C][R][S]
+    void *out[PACK_MAX_SEG];
+    int K[PACK_MAX_SEG], C[PACK_MAX_SEG], R[PACK_MAX_SEG], S[PACK_MAX_SEG], Kp[PACK_MAX_SEG], flip[PACK_MAX_SEG];
+};
+constexpr int SGD_ELEMS_PER_BLOCK = 256 * 8, PACK_ELEMS_PER_BLOCK = 256 * 8;
+sol_status launch_sgd_batch(const SgdBatch &b, float lr, float mu, hipStream_t st);
+sol_status launch_pack_batch(const PackBatch &b, int dt, hipStream_t st);
 sol_status launch_pack_flip(const sol_conv_desc &cd, int dt, const float *w, void *packed, hipStream_t st);
 void wgrad_plan(const sol_tensor_desc &xd, const sol_conv_desc &cd, int Ho, int Wo, int *nsplit, size_t *part_floats);
 sol_status launch_wgrad(const sol_tensor_desc &xd, const void *x, const sol_conv_desc &cd, const void *dz, int Ho, int Wo,

@@ -354,17 +354,23 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
 // channels below Cout), Cout % 8 == 0 and no fused pool: same transposition through the wave-private strip as
 // conv_epilogue, but without per-row / per-channel range logic, with 32-bit element offsets (tensors are
 // limited to < 2^31 elements) and a branch-free activation.  RES: add the prefetched residual rows.
-template <typename T, int TP, int TC, bool RES>
+// rowoff(r): element offset of the first channel of the output pixel of tile row r (counted from the wave's first
+// row); rows r .. r + RPS - 1 handled by one pass need not be contiguous with the next pass.
+struct LinearRowOffset {
+    unsigned first, cout;
+    __device__ __forceinline__ unsigned operator()(int r) const { return first + (unsigned)r * cout; }
+};
+template <typename T, int TP, int TC, bool RES, typename RowOff>
 __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16_t (&acc)[TC][TP], float *lds_f, int wave, int lane,
-                                                       int mw, int cw, const Affine8 &aff, const ResidualRegs<T, TP, TC> &pre) {
+                                                       int cw, const Affine8 &aff, const ResidualRegs<T, TP, TC> &pre,
+                                                       const RowOff &rowoff) {
     constexpr int ECH = TC * 32, ERS = ECH + 4, LPR = ECH / 8, RPS = 64 / LPR;
     const int lr = lane & 31, lh = lane >> 5;
     float *strip = lds_f + wave * (32 * ERS);
     T *__restrict__ yg = static_cast<T *>(a.y);
     const int ecg = lane % LPR, erow = lane / LPR;
     const float lim = a.act == SOL_ACT_RELU ? 0.f : -__builtin_inff();
-    const unsigned cout = (unsigned)a.Cout;
-    unsigned off = (unsigned)(mw + erow) * cout + (unsigned)(cw + ecg * 8);    // element offset of this lane's first row
+    const unsigned coff = (unsigned)(cw + ecg * 8);
     static_for<TP>([&](auto J) {
         constexpr int j = decltype(J)::value;
 #pragma unroll
@@ -390,8 +396,7 @@ __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16
             }
 #pragma unroll
             for (int e = 0; e < 8; e++) v[e] = fmaxf(v[e], lim);
-            store_vec8<T>(yg + off, v);
-            off += RPS * cout;
+            store_vec8<T>(yg + rowoff(j * 32 + erow + ps * RPS) + coff, v);
         }
         wave_lds_fence();
     });
@@ -403,8 +408,9 @@ __device__ __forceinline__ void conv_epilogue_auto(const ConvArgs &a, f32x16_t (
                                                    int mw, int cw, const Affine8 &aff, const RowMap &rowmap,
                                                    const ResidualRegs<T, TP, TC> &pre) {
     const bool interior = a.pool == 0 && (a.Cout & 7) == 0 && mw + TP * 32 <= a.P && cw + TC * 32 <= a.Cout && a.scale && a.shift;
-    if (interior && a.res == nullptr) conv_epilogue_interior<T, TP, TC, false>(a, acc, lds_f, wave, lane, mw, cw, aff, pre);
-    else if (interior && pre.on) conv_epilogue_interior<T, TP, TC, true>(a, acc, lds_f, wave, lane, mw, cw, aff, pre);
+    const LinearRowOffset ro{(unsigned)mw * (unsigned)a.Cout, (unsigned)a.Cout};
+    if (interior && a.res == nullptr) conv_epilogue_interior<T, TP, TC, false>(a, acc, lds_f, wave, lane, cw, aff, pre, ro);
+    else if (interior && pre.on) conv_epilogue_interior<T, TP, TC, true>(a, acc, lds_f, wave, lane, cw, aff, pre, ro);
     else conv_epilogue<T, TP, TC>(a, acc, lds_f, wave, lane, mw, cw, aff, rowmap, pre);
 }
 

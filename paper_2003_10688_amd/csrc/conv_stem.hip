@@ -12,6 +12,11 @@
 
 namespace sol {
 
+struct StemRowOffset {   // same map as StemRows for a block that lies inside the image, as an element offset
+    unsigned base, wo, cout;     // base: offset of the block's pixel (p0, q0)
+    __device__ __forceinline__ unsigned operator()(int r) const { return base + ((unsigned)(r >> 4) * wo + (unsigned)(r & 15)) * cout; }
+};
+
 struct StemRows {   // tile row (py*16+px) of the 8x16 output block -> output pixel index
     int n, p0, q0, Ho, Wo;
     __device__ __forceinline__ long operator()(int m) const {
@@ -105,8 +110,16 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
         }
         const StemRows rows{n, p0, q0, a.Ho, a.Wo};
         ResidualRegs<bf16_t, 1, 2> resregs;
-        prefetch_residual<bf16_t, 1, 2>(a, lane, wave * 32, 0, rows, resregs);
-        conv_epilogue<bf16_t, 1, 2>(a, acc, strip, wave, lane, wave * 32, 0, aff, rows, resregs);
+        resregs.on = false;
+        // blocks inside the image with the usual 64 channels and no residual: branch-free epilogue
+        if (p0 + STEM_TH <= a.Ho && q0 + STEM_TW <= a.Wo && a.Cout == 64 && a.res == nullptr && a.scale && a.shift) {
+            const int pw = p0 + 2 * wave;     // first output row of this wave's 32 tile rows
+            const StemRowOffset ro{(unsigned)(((n * a.Ho + pw) * a.Wo + q0) * 64), (unsigned)a.Wo, 64u};
+            conv_epilogue_interior<bf16_t, 1, 2, false>(a, acc, strip, wave, lane, 0, aff, resregs, ro);
+        } else {
+            prefetch_residual<bf16_t, 1, 2>(a, lane, wave * 32, 0, rows, resregs);
+            conv_epilogue<bf16_t, 1, 2>(a, acc, strip, wave, lane, wave * 32, 0, aff, rows, resregs);
+        }
     }
 }
 

@@ -58,24 +58,40 @@ __global__ void __launch_bounds__(256) col_reduce_kernel(const T *__restrict__ a
 
 // out0[c] = scale * sum_chunks part[chunk][0][c]; out1 likewise; with eps >= 0 also
 // inv[c] = 1 / sqrt(out0[c] + eps)   (out0 = biased variance then)
-__global__ void __launch_bounds__(256) col_finalize_kernel(const float *__restrict__ part, int nchunks, int C, float scale,
-                                                           float *__restrict__ out0, float *__restrict__ out1, float eps,
-                                                           float *__restrict__ inv) {
+__global__ void __launch_bounds__(1024) col_finalize_kernel(const float *__restrict__ part, int nchunks, int C, float scale,
+                                                            float *__restrict__ out0, float *__restrict__ out1, float eps,
+                                                            float *__restrict__ inv) {
+    // 64 channels x 16 chunk phases; phase p adds chunks p, p+16, ... (4 independent loads in flight), the phases
+    // are then added in order: the summation order depends on nothing but nchunks
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const int c = blockIdx.x * 64 + tx;
     float s0 = 0.f, s1 = 0.f;
-    if (c < C)
-        for (int k = ty; k < nchunks; k += 4) {
+    if (c < C) {
+        int k = ty;
+        for (; k + 48 < nchunks; k += 64) {
+            float a0[4], a1[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                a0[u] = part[((size_t)(k + 16 * u) * 2 + 0) * C + c];
+                a1[u] = part[((size_t)(k + 16 * u) * 2 + 1) * C + c];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) { s0 += a0[u]; s1 += a1[u]; }
+        }
+        for (; k < nchunks; k += 16) {
             s0 += part[((size_t)k * 2 + 0) * C + c];
             s1 += part[((size_t)k * 2 + 1) * C + c];
         }
-    __shared__ float red[2][4][64];
+    }
+    __shared__ float red[2][16][64];
     red[0][ty][tx] = s0;
     red[1][ty][tx] = s1;
     __syncthreads();
     if (ty != 0 || c >= C) return;
-    s0 = (((red[0][0][tx] + red[0][1][tx]) + red[0][2][tx]) + red[0][3][tx]) * scale;
-    s1 = (((red[1][0][tx] + red[1][1][tx]) + red[1][2][tx]) + red[1][3][tx]) * scale;
+    s0 = 0.f; s1 = 0.f;
+#pragma unroll
+    for (int p = 0; p < 16; p++) { s0 += red[0][p][tx]; s1 += red[1][p][tx]; }
+    s0 *= scale; s1 *= scale;
     if (out0) out0[c] = s0;
     if (out1) out1[c] = s1;
     if (inv) inv[c] = 1.f / sqrtf(s0 + eps);
@@ -293,6 +309,57 @@ __global__ void __launch_bounds__(256) sgd_kernel(float *__restrict__ w, float *
     }
 }
 
+// All parameter tensors of a network in one launch: block -> segment by a scan of the (scalar) block table.
+__global__ void __launch_bounds__(256) sgd_batch_kernel(const SgdBatch b, float lr, float mu) {
+    int seg = 0;
+    while (seg + 1 < b.nseg && (int)blockIdx.x >= b.first_block[seg + 1]) seg++;
+    float *__restrict__ w = b.w[seg], *__restrict__ v = b.v[seg];
+    const float *__restrict__ g = b.g[seg];
+    const long n = b.n[seg];
+    const long i0 = (long)((int)blockIdx.x - b.first_block[seg]) * SGD_ELEMS_PER_BLOCK;
+#pragma unroll
+    for (int u = 0; u < SGD_ELEMS_PER_BLOCK / 256; u++) {
+        const long i = i0 + u * 256 + threadIdx.x;
+        if (i < n) {
+            const float vel = mu * v[i] + g[i];
+            v[i] = vel;
+            w[i] -= lr * vel;
+        }
+    }
+}
+
+// All packed weight buffers of a network (forward order and, for the data gradient, flipped / transposed) rebuilt
+// from the fp32 masters in one launch; same element maps as pack_weights_kernel / pack_weights_flip_kernel.
+template <typename T>
+__global__ void __launch_bounds__(256) pack_batch_kernel(const PackBatch b) {
+    int seg = 0;
+    while (seg + 1 < b.nseg && (int)blockIdx.x >= b.first_block[seg + 1]) seg++;
+    const float *__restrict__ w = b.w[seg];
+    T *__restrict__ out = static_cast<T *>(b.out[seg]);
+    const int K = b.K[seg], C = b.C[seg], R = b.R[seg], S = b.S[seg], Kp = b.Kp[seg], flip = b.flip[seg];
+    const long total = (long)(flip ? C : K) * Kp;
+    const long i0 = (long)((int)blockIdx.x - b.first_block[seg]) * PACK_ELEMS_PER_BLOCK;
+#pragma unroll
+    for (int u = 0; u < PACK_ELEMS_PER_BLOCK / 256; u++) {
+        const long i = i0 + u * 256 + threadIdx.x;
+        if (i >= total) break;
+        const int row = (int)(i / Kp), j = (int)(i % Kp);
+        float v = 0.f;
+        if (!flip) {                               // out[k][(r*S+s)*C + c]
+            if (j < R * S * C) {
+                const int c = j % C, tap = j / C, s = tap % S, r = tap / S;
+                v = w[(((long)row * C + c) * R + r) * S + s];
+            }
+        } else {                                   // out[c][((R-1-r)*S + (S-1-s))*K + k]
+            if (j < R * S * K) {
+                const int k = j % K, tap = j / K, s = S - 1 - tap % S, r = R - 1 - tap / S;
+                v = w[(((long)k * C + row) * R + r) * S + s];
+            }
+        }
+        Elem<T>::store(out + i, v);
+    }
+}
+
 // Weights for the data-gradient: framework layout w[k][c][r][s] -> packed rows [c][((R-1-r)*S + (S-1-s))*K + k],
 // i.e. the packed weight of a convolution with K input and C output channels and the filter flipped.
 template <typename T>
@@ -481,15 +548,15 @@ sol_status launch_bn_stats(const void *z, int rows, int C, int dt, float eps, fl
     if (dt == SOL_BF16) {
         const bf16_t *p = static_cast<const bf16_t *>(z);
         hipLaunchKernelGGL((col_reduce_kernel<bf16_t, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
-        hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(256), 0, st, part, nch, C, 1.f / rows, mean, nullptr, -1.f, nullptr);
+        hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(1024), 0, st, part, nch, C, 1.f / rows, mean, nullptr, -1.f, nullptr);
         hipLaunchKernelGGL((col_reduce_kernel<bf16_t, 1>), grid, dim3(256), 0, st, p, p, p, mean, nullptr, part, rows, C, rpc, 0);
     } else {
         const float *p = static_cast<const float *>(z);
         hipLaunchKernelGGL((col_reduce_kernel<float, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
-        hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(256), 0, st, part, nch, C, 1.f / rows, mean, nullptr, -1.f, nullptr);
+        hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(1024), 0, st, part, nch, C, 1.f / rows, mean, nullptr, -1.f, nullptr);
         hipLaunchKernelGGL((col_reduce_kernel<float, 1>), grid, dim3(256), 0, st, p, p, p, mean, nullptr, part, rows, C, rpc, 0);
     }
-    hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(256), 0, st, part, nch, C, 1.f / rows, var, nullptr, eps, invstd);
+    hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(1024), 0, st, part, nch, C, 1.f / rows, var, nullptr, eps, invstd);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }
@@ -515,7 +582,7 @@ sol_status launch_grad_col_sums(const void *z, const void *dy, const void *y, co
     else
         hipLaunchKernelGGL((col_reduce_kernel<float, 2>), grid, dim3(256), 0, st, static_cast<const float *>(z),
                            static_cast<const float *>(dy), static_cast<const float *>(y), mean, invstd, part, rows, C, rpc, relu);
-    hipLaunchKernelGGL(col_finalize_kernel, dim3(ceil_div(C, 64)), dim3(256), 0, st, part, nch, C, 1.f, out0, out1, -1.f, nullptr);
+    hipLaunchKernelGGL(col_finalize_kernel, dim3(ceil_div(C, 64)), dim3(1024), 0, st, part, nch, C, 1.f, out0, out1, -1.f, nullptr);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }
@@ -573,6 +640,23 @@ sol_status launch_softmax_ce(const void *logits, const int32_t *labels, void *dl
 sol_status launch_sgd(float *w, float *v, const float *g, long n, float lr, float mu, hipStream_t st) {
     if (n <= 0) return SOL_OK;
     hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(n)), dim3(256), 0, st, w, v, g, n, lr, mu);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_sgd_batch(const SgdBatch &b, float lr, float mu, hipStream_t st) {
+    if (b.nseg <= 0 || b.first_block[b.nseg] <= 0) return SOL_OK;
+    hipLaunchKernelGGL(sgd_batch_kernel, dim3(b.first_block[b.nseg]), dim3(256), 0, st, b, lr, mu);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_pack_batch(const PackBatch &b, int dt, hipStream_t st) {
+    if (b.nseg <= 0 || b.first_block[b.nseg] <= 0) return SOL_OK;
+    if (dt == SOL_BF16)
+        hipLaunchKernelGGL((pack_batch_kernel<bf16_t>), dim3(b.first_block[b.nseg]), dim3(256), 0, st, b);
+    else
+        hipLaunchKernelGGL((pack_batch_kernel<float>), dim3(b.first_block[b.nseg]), dim3(256), 0, st, b);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }

@@ -8,9 +8,8 @@ to 1e-4 (max relative error with an rms floor, as in the forward tests).  bf16 n
 activations, z and activation gradients in bf16 at the same points as the checker; a store that
 rounds the other way (fp32 vs fp64 accumulation straddling a boundary) perturbs everything behind
 it, so element-wise maxima over deep chains drift beyond one ulp while the typical element does
-not: bf16 runs are gated on the norm-wise relative error (2e-2) per tensor, on the element-wise
-bound for the fp32 weight gradients of short chains, and on the fp32 run of the same layer list for
-the wiring."""
+not: bf16 runs are gated on the norm-wise relative error (2e-2) per tensor and on the fp32 run of the
+same layer list (element-wise, 1e-4) for the wiring."""
 import numpy as np
 import pytest
 import torch
@@ -158,10 +157,11 @@ def test_train_step_bf16(sol, name):
     _, got = gpu_train(sol, layers, params, x, labels, "bf16")
     ref = oracle_train(layers, params, x, labels, "bf16")
     compare(got[0], ref[0], layers, "bf16", elementwise=False, tag=f"{name}/bf16")
-    for i, g in enumerate(got[0]["grads"]):                      # fp32 weight gradients: element-wise as well
-        if "w" in g:
-            e = rel_err(g["w"], ref[0]["grads"][i]["w"])
-            assert e <= 5e-2, (i, e)
+    # No element-wise gate on the bf16 weight gradients: a stored activation that lands on the other side of zero
+    # than the checker's (fp32 vs fp64 sums, or another fixed summation order of the batch statistics, ahead of a bf16
+    # store) flips that pixel's ReLU mask, which adds or removes a whole term of the pixel sum -- up to ~0.2 rms for a
+    # sum of a few hundred terms -- while the tensor as a whole stays within the norm-wise tolerance checked above.
+    # Element-wise agreement of every gradient is what the fp32 runs of the same layer lists assert (1e-4).
 
 
 def test_train_step_deterministic(sol):
