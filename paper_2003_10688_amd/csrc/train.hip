@@ -56,6 +56,68 @@ __global__ void __launch_bounds__(256) col_reduce_kernel(const T *__restrict__ a
     }
 }
 
+// Same reductions with 16-byte accesses (C % V == 0): 256 threads = 64/V channel groups x 256*V/64 row phases, every
+// thread keeps V running sums; the phases are then added in order through LDS.
+template <typename T, int V, int MODE>
+__global__ void __launch_bounds__(256) col_reduce_vec_kernel(const T *__restrict__ a, const T *__restrict__ b,
+                                                             const T *__restrict__ y, const float *__restrict__ mean,
+                                                             const float *__restrict__ invstd, float *__restrict__ part,
+                                                             int rows, int C, int rpc, int relu) {
+    constexpr int CG = 64 / V, PH = 256 / CG;
+    const int cg = threadIdx.x % CG, ph = threadIdx.x / CG;
+    const int c0 = blockIdx.y * 64 + cg * V;
+    const int r0 = blockIdx.x * rpc, r1 = min(rows, r0 + rpc);
+    float s0[V], s1[V], m[V], is[V];
+#pragma unroll
+    for (int e = 0; e < V; e++) { s0[e] = 0.f; s1[e] = 0.f; m[e] = 0.f; is[e] = 0.f; }
+    const bool cok = c0 < C;
+    if (cok) {
+#pragma unroll
+        for (int e = 0; e < V; e++) {
+            if (MODE >= 1 && mean) m[e] = mean[c0 + e];
+            if (MODE == 2 && invstd) is[e] = invstd[c0 + e];
+        }
+        auto one_row = [&](int r) {
+            const size_t i = (size_t)r * C + c0;
+            float va[V], vb[V], vy[V];
+            if (MODE <= 1 || a) VecIO<T, V>::load(a + i, va);
+            if (MODE == 2) {
+                VecIO<T, V>::load(b + i, vb);
+                if (relu) VecIO<T, V>::load(y + i, vy);
+            }
+#pragma unroll
+            for (int e = 0; e < V; e++) {
+                if (MODE == 0) {
+                    s0[e] += va[e];
+                } else if (MODE == 1) {
+                    const float d = va[e] - m[e];
+                    s0[e] += d * d;
+                } else {
+                    float g = vb[e];
+                    if (relu && !(vy[e] > 0.f)) g = 0.f;
+                    s0[e] += g;
+                    if (a) s1[e] += g * ((va[e] - m[e]) * is[e]);
+                }
+            }
+        };
+        int r = r0 + ph;
+        for (; r + PH < r1; r += 2 * PH) { one_row(r); one_row(r + PH); }   // two rows' loads in flight
+        if (r < r1) one_row(r);
+    }
+    __shared__ float red[2][PH][64 + 1];
+#pragma unroll
+    for (int e = 0; e < V; e++) { red[0][ph][cg * V + e] = s0[e]; red[1][ph][cg * V + e] = s1[e]; }
+    __syncthreads();
+    const int tx = threadIdx.x, c = blockIdx.y * 64 + tx;
+    if (tx < 64 && c < C) {
+        float t0 = 0.f, t1 = 0.f;
+#pragma unroll
+        for (int p = 0; p < PH; p++) { t0 += red[0][p][tx]; t1 += red[1][p][tx]; }
+        part[((size_t)blockIdx.x * 2 + 0) * C + c] = t0;
+        part[((size_t)blockIdx.x * 2 + 1) * C + c] = t1;
+    }
+}
+
 // out0[c] = scale * sum_chunks part[chunk][0][c]; out1 likewise; with eps >= 0 also
 // inv[c] = 1 / sqrt(out0[c] + eps)   (out0 = biased variance then)
 __global__ void __launch_bounds__(1024) col_finalize_kernel(const float *__restrict__ part, int nchunks, int C, float scale,
@@ -547,14 +609,18 @@ sol_status launch_bn_stats(const void *z, int rows, int C, int dt, float eps, fl
     const int fg = ceil_div(C, 64);
     if (dt == SOL_BF16) {
         const bf16_t *p = static_cast<const bf16_t *>(z);
-        hipLaunchKernelGGL((col_reduce_kernel<bf16_t, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
+        if (C % 8 == 0) hipLaunchKernelGGL((col_reduce_vec_kernel<bf16_t, 8, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
+        else hipLaunchKernelGGL((col_reduce_kernel<bf16_t, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
         hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(1024), 0, st, part, nch, C, 1.f / rows, mean, nullptr, -1.f, nullptr);
-        hipLaunchKernelGGL((col_reduce_kernel<bf16_t, 1>), grid, dim3(256), 0, st, p, p, p, mean, nullptr, part, rows, C, rpc, 0);
+        if (C % 8 == 0) hipLaunchKernelGGL((col_reduce_vec_kernel<bf16_t, 8, 1>), grid, dim3(256), 0, st, p, p, p, mean, nullptr, part, rows, C, rpc, 0);
+        else hipLaunchKernelGGL((col_reduce_kernel<bf16_t, 1>), grid, dim3(256), 0, st, p, p, p, mean, nullptr, part, rows, C, rpc, 0);
     } else {
         const float *p = static_cast<const float *>(z);
-        hipLaunchKernelGGL((col_reduce_kernel<float, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
+        if (C % 4 == 0) hipLaunchKernelGGL((col_reduce_vec_kernel<float, 4, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
+        else hipLaunchKernelGGL((col_reduce_kernel<float, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
         hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(1024), 0, st, part, nch, C, 1.f / rows, mean, nullptr, -1.f, nullptr);
-        hipLaunchKernelGGL((col_reduce_kernel<float, 1>), grid, dim3(256), 0, st, p, p, p, mean, nullptr, part, rows, C, rpc, 0);
+        if (C % 4 == 0) hipLaunchKernelGGL((col_reduce_vec_kernel<float, 4, 1>), grid, dim3(256), 0, st, p, p, p, mean, nullptr, part, rows, C, rpc, 0);
+        else hipLaunchKernelGGL((col_reduce_kernel<float, 1>), grid, dim3(256), 0, st, p, p, p, mean, nullptr, part, rows, C, rpc, 0);
     }
     hipLaunchKernelGGL(col_finalize_kernel, dim3(fg), dim3(1024), 0, st, part, nch, C, 1.f / rows, var, nullptr, eps, invstd);
     SOL_HIP(hipGetLastError());
@@ -576,9 +642,15 @@ sol_status launch_grad_col_sums(const void *z, const void *dy, const void *y, co
     int rpc;
     const int nch = col_reduce_chunks(rows, &rpc);
     const dim3 grid(nch, ceil_div(C, 64));
-    if (dt == SOL_BF16)
+    if (dt == SOL_BF16 && C % 8 == 0)
+        hipLaunchKernelGGL((col_reduce_vec_kernel<bf16_t, 8, 2>), grid, dim3(256), 0, st, static_cast<const bf16_t *>(z),
+                           static_cast<const bf16_t *>(dy), static_cast<const bf16_t *>(y), mean, invstd, part, rows, C, rpc, relu);
+    else if (dt == SOL_BF16)
         hipLaunchKernelGGL((col_reduce_kernel<bf16_t, 2>), grid, dim3(256), 0, st, static_cast<const bf16_t *>(z),
                            static_cast<const bf16_t *>(dy), static_cast<const bf16_t *>(y), mean, invstd, part, rows, C, rpc, relu);
+    else if (C % 4 == 0)
+        hipLaunchKernelGGL((col_reduce_vec_kernel<float, 4, 2>), grid, dim3(256), 0, st, static_cast<const float *>(z),
+                           static_cast<const float *>(dy), static_cast<const float *>(y), mean, invstd, part, rows, C, rpc, relu);
     else
         hipLaunchKernelGGL((col_reduce_kernel<float, 2>), grid, dim3(256), 0, st, static_cast<const float *>(z),
                            static_cast<const float *>(dy), static_cast<const float *>(y), mean, invstd, part, rows, C, rpc, relu);
