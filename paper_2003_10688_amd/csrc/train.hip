@@ -565,6 +565,162 @@ __global__ void __launch_bounds__(256) wgrad_kernel(const WgradArgs a) {
 #endif
 }
 
+// Eight 2-byte LDS reads down a column of 128-byte rows = one MFMA fragment (rows 2q, 2q+1 -> low, high half of
+// register q).  Opaque to the compiler: the caller waits (lgkmcnt) and only then packs the fragment with
+// column8_landed() (anything that touched the registers before the data has landed would see stale values).  Plain
+// zero-extending reads plus a pack: half-register (d16) loads do not preserve the other half on parts with SRAM ECC.
+struct Column8 { unsigned e[8]; };
+__device__ __forceinline__ void read_column8(Column8 &f, unsigned addr) {
+    asm volatile("ds_read_u16 %0, %8 offset:0\n\t"
+                 "ds_read_u16 %1, %8 offset:128\n\t"
+                 "ds_read_u16 %2, %8 offset:256\n\t"
+                 "ds_read_u16 %3, %8 offset:384\n\t"
+                 "ds_read_u16 %4, %8 offset:512\n\t"
+                 "ds_read_u16 %5, %8 offset:640\n\t"
+                 "ds_read_u16 %6, %8 offset:768\n\t"
+                 "ds_read_u16 %7, %8 offset:896"
+                 : "=&v"(f.e[0]), "=&v"(f.e[1]), "=&v"(f.e[2]), "=&v"(f.e[3]), "=&v"(f.e[4]), "=&v"(f.e[5]), "=&v"(f.e[6]), "=&v"(f.e[7])
+                 : "v"(addr));
+}
+__device__ __forceinline__ uint4 column8_landed(Column8 &f) {
+    asm volatile("" : "+v"(f.e[0]), "+v"(f.e[1]), "+v"(f.e[2]), "+v"(f.e[3]), "+v"(f.e[4]), "+v"(f.e[5]), "+v"(f.e[6]), "+v"(f.e[7]));
+    return make_uint4(f.e[0] | (f.e[1] << 16), f.e[2] | (f.e[3] << 16), f.e[4] | (f.e[5] << 16), f.e[6] | (f.e[7] << 16));
+}
+
+// The same contraction with both operands staged through LDS (bf16, K % 8 == 0 and C % 8 == 0).  A stage is 64
+// consecutive output pixels: their dz rows (64 channels = 128 bytes each) and the tap-shifted x rows travel
+// HBM/L2 -> LDS by DMA, 16 bytes per lane, fully coalesced; rows that do not exist (pixel range end, padding taps,
+// channel tails) get an out-of-range buffer offset and arrive as zeros.  Each of the four waves then takes one
+// 16-pixel k-step of the stage: an MFMA fragment is 8 consecutive pixels of one channel, i.e. eight 2-byte LDS
+// reads down a column (the 32 lanes of a half-wave read 64 contiguous bytes of one row; rows 8..15 sit 64 bytes
+// further along than rows 0..7 -- slot ^ 4, applied on the global side of the DMA -- so the two half-waves use
+// disjoint banks).  Ring of NS stages, one barrier per stage; partial sums and the second-stage reduction as above.
+template <int NS>
+__global__ void __launch_bounds__(256) wgrad_lds_kernel(const WgradArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    using namespace lds_pipe;
+    constexpr int STAGE = 16384, L = 4;            // 8 KB of dz rows + 8 KB of x rows; DMA instructions per wave and stage
+    __shared__ __align__(1024) unsigned char lds[NS * STAGE];
+    static_assert(NS * STAGE >= 64 * 65 * 4, "the cross-wave reduction reuses the ring");
+    const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int bid = blockIdx.x;
+    const int kt = bid % a.nkt; bid /= a.nkt;
+    const int ct = bid % a.nct; bid /= a.nct;
+    const int tap = bid % (a.R * a.S);
+    const int split = bid / (a.R * a.S);
+    const int r = tap / a.S, s = tap % a.S;
+    const int k0 = kt * 64, c0 = ct * 64;
+
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, (int)a.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t zr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.dz), 0, (int)a.dz_bytes, 0x00020000);
+
+    const int s_begin = split * a.steps_per_split, s_end = min(a.nsteps, s_begin + a.steps_per_split);   // stages of 64 pixels
+    const int P = a.N * a.Ho * a.Wo;
+
+    // DMA lanes: segment = 8 rows x 8 slots of 16 bytes; wave w owns dz segments 2w, 2w+1 and x segments 2w, 2w+1
+    const int lslot = lane & 7, lrow = lane >> 3;
+    unsigned zbase[2];
+    int xrow[2], xslot[2];
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+        const int row = (wave * 2 + i) * 8 + lrow;
+        const int gs = lslot ^ (((row >> 3) & 1) << 2);        // global slot that lands in this lane's LDS slot
+        zbase[i] = k0 + gs * 8 < a.K ? (unsigned)(row * a.K + k0 + gs * 8) * 2u : 0x80000000u;
+        xrow[i] = row;
+        xslot[i] = c0 + gs * 8 < a.C ? (c0 + gs * 8) * 2 : -1;
+    }
+    auto issue = [&](int st, int buf) {
+        unsigned char *lz = lds + buf * STAGE, *lx = lz + 8192;
+        const bool live = st < s_end;
+        const unsigned zstage = (unsigned)st * 64u * (unsigned)a.K * 2u;
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+            const unsigned zo = live ? zbase[i] + zstage : 0xffffffffu;   // pixels >= P lie beyond the tensor: zeros
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(zr, (__attribute__((address_space(3))) void *)(lz + (wave * 2 + i) * 1024), 16, zo, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+            const uint32_t p = (uint32_t)st * 64u + (uint32_t)xrow[i];
+            uint32_t row, ow, n, oh;
+            a.dG.divmod(p, row, ow);                           // dG: division by Wo
+            a.dHo.divmod(row, n, oh);
+            const int ih = (int)oh * a.sh + r - a.ph, iw = (int)ow * a.sw + s - a.pw;
+            const bool ok = live && p < (uint32_t)P && xslot[i] >= 0 && (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            const unsigned xo = ok ? (unsigned)(((n * (uint32_t)a.H + (uint32_t)ih) * (uint32_t)a.W + (uint32_t)iw) * (uint32_t)a.C) * 2u + (unsigned)xslot[i]
+                                   : 0xffffffffu;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(lx + (wave * 2 + i) * 1024), 16, xo, 0, 0, 0);
+        }
+    };
+
+    f32x16_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+    // fragment base of this lane: rows 16*wave + 8*h .. +7, column lr of channel block i (slot ^ 4 for the upper rows)
+    unsigned fbase[2];
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+        fbase[i] = (unsigned)((16 * wave + 8 * h) * 128 + (((i * 4 + (lr >> 3)) ^ (h << 2)) << 4) + (lr & 7) * 2);
+
+#pragma unroll
+    for (int q = 0; q < NS - 1; q++) issue(s_begin + q, q);
+    int buf = 0;
+    for (int st = s_begin; st < s_end; st++) {
+        wait_vmcnt<(NS - 2) * L>();                            // this wave's share of stage st has landed
+        __builtin_amdgcn_s_barrier();                          // ... everyone's; and nobody still reads stage st-1 (a bare
+                                                               // barrier: __syncthreads would also wait for the DMA in flight)
+        issue(st + NS - 1, buf == 0 ? NS - 1 : buf - 1);
+        // Fragment reads as opaque instructions (the compiler would otherwise wait for ALL outstanding DMA before
+        // any LDS read): pixel e of a pair goes to the low half of a register, pixel e+1 to the high half.
+        const unsigned zb = lds_addr(lds) + (unsigned)(buf * STAGE), xb = zb + 8192u;
+        Column8 ca[2], cb[2];
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+            read_column8(ca[i], zb + fbase[i]);
+            read_column8(cb[i], xb + fbase[i]);
+        }
+        wait_lgkmcnt<0>();
+        uint4 fa[2], fb[2];
+#pragma unroll
+        for (int i = 0; i < 2; i++) { fa[i] = column8_landed(ca[i]); fb[i] = column8_landed(cb[i]); }
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+            for (int j = 0; j < 2; j++) Mma<bf16_t>::run(acc[i][j], fa[i], fb[j]);
+        buf = buf + 1 == NS ? 0 : buf + 1;
+    }
+    wait_vmcnt<0>();                                           // zero-fill DMAs of the tail
+    __syncthreads();                                           // the ring is dead: it becomes the reduction buffer
+
+    float(*red)[65] = reinterpret_cast<float(*)[65]>(lds);
+    for (int w = 0; w < 4; w++) {
+        if (wave == w) {
+#pragma unroll
+            for (int i = 0; i < 2; i++)
+#pragma unroll
+                for (int j = 0; j < 2; j++)
+#pragma unroll
+                    for (int e = 0; e < 16; e++) {
+                        float &d = red[i * 32 + 8 * (e / 4) + 4 * h + e % 4][j * 32 + lr];
+                        d = w == 0 ? acc[i][j][e] : d + acc[i][j][e];
+                    }
+        }
+        __syncthreads();
+    }
+    const size_t kstride = (size_t)a.R * a.S * a.C;
+    float *out = a.part + (size_t)split * a.K * kstride;
+    for (int i = tid; i < 64 * 64; i += 256) {
+        const int kk = i >> 6, cc = i & 63;
+        if (k0 + kk < a.K && c0 + cc < a.C) out[(size_t)(k0 + kk) * kstride + (size_t)tap * a.C + c0 + cc] = red[kk][cc];
+    }
+#endif
+}
+
 // dW[k][c][r][s] (framework layout) = sum over splits of part[split][k][r*S+s][c], added in split order
 __global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float *__restrict__ part, int nsplit, float *__restrict__ dw,
                                                            int K, int C, int RS) {
@@ -749,7 +905,21 @@ sol_status launch_pack_flip(const sol_conv_desc &cd, int dt, const float *w, voi
 }
 
 // Split of the pixel reduction: enough workgroups to fill the chip, at least 16 steps each.
+// bf16 with whole 16-byte slots of channels on both sides: the LDS-staged kernel (steps of 64 pixels)
+static bool wgrad_lds_applies(const sol_tensor_desc &xd, const sol_conv_desc &cd) {
+    return xd.dtype == SOL_BF16 && cd.cout % 8 == 0 && cd.cin % 8 == 0;
+}
+
 void wgrad_plan(const sol_tensor_desc &xd, const sol_conv_desc &cd, int Ho, int Wo, int *nsplit, size_t *part_floats) {
+    if (wgrad_lds_applies(xd, cd)) {
+        const int nsteps = (int)(((long)xd.n * Ho * Wo + 63) / 64);
+        const int tiles = ceil_div(cd.cout, 64) * ceil_div(cd.cin, 64) * cd.kh * cd.kw;
+        int ns = std::max(1, ceil_div(768, tiles));              // ~3 workgroups per CU, one round
+        ns = std::min(ns, std::max(1, nsteps / 8));
+        *nsplit = ns;
+        *part_floats = (size_t)ns * cd.cout * cd.kh * cd.kw * cd.cin;
+        return;
+    }
     const int GP = 16 / (int)dtype_size(xd.dtype);
     const int G = ceil_div(Wo, GP);
     const long ngroups = (long)xd.n * Ho * G;
@@ -772,9 +942,10 @@ sol_status launch_wgrad(const sol_tensor_desc &xd, const void *x, const sol_conv
     a.x = x; a.dz = dz; a.part = part;
     a.N = xd.n; a.H = xd.h; a.W = xd.w; a.C = xd.c; a.K = cd.cout; a.R = cd.kh; a.S = cd.kw;
     a.sh = cd.sh; a.sw = cd.sw; a.ph = cd.ph; a.pw = cd.pw; a.Ho = Ho; a.Wo = Wo;
-    a.G = ceil_div(Wo, GP);
+    const bool lds_path = wgrad_lds_applies(xd, cd);
+    a.G = lds_path ? Wo : ceil_div(Wo, GP);
     a.ngroups = xd.n * Ho * a.G;
-    a.nsteps = (a.ngroups + 1) / 2;
+    a.nsteps = lds_path ? (int)(((long)xd.n * Ho * Wo + 63) / 64) : (a.ngroups + 1) / 2;
     size_t pf;
     wgrad_plan(xd, cd, Ho, Wo, &a.nsplit, &pf);
     a.steps_per_split = ceil_div(a.nsteps, a.nsplit);
@@ -782,7 +953,9 @@ sol_status launch_wgrad(const sol_tensor_desc &xd, const void *x, const sol_conv
     a.x_bytes = (uint32_t)xb; a.dz_bytes = (uint32_t)zb;
     a.dG = FastDiv((uint32_t)a.G); a.dHo = FastDiv((uint32_t)Ho);
     const int grid = a.nkt * a.nct * cd.kh * cd.kw * a.nsplit;
-    if (xd.dtype == SOL_BF16)
+    if (lds_path)
+        hipLaunchKernelGGL((wgrad_lds_kernel<4>), dim3(grid), dim3(256), 0, st, a);
+    else if (xd.dtype == SOL_BF16)
         hipLaunchKernelGGL((wgrad_kernel<bf16_t>), dim3(grid), dim3(256), 0, st, a);
     else
         hipLaunchKernelGGL((wgrad_kernel<float>), dim3(grid), dim3(256), 0, st, a);
