@@ -582,6 +582,19 @@ __device__ __forceinline__ void read_column8(Column8 &f, unsigned addr) {
                  : "=&v"(f.e[0]), "=&v"(f.e[1]), "=&v"(f.e[2]), "=&v"(f.e[3]), "=&v"(f.e[4]), "=&v"(f.e[5]), "=&v"(f.e[6]), "=&v"(f.e[7])
                  : "v"(addr));
 }
+// the same for a column whose rows are 16 bytes apart (the widened stem patch)
+__device__ __forceinline__ void read_column8_16(Column8 &f, unsigned addr) {
+    asm volatile("ds_read_u16 %0, %8 offset:0\n\t"
+                 "ds_read_u16 %1, %8 offset:16\n\t"
+                 "ds_read_u16 %2, %8 offset:32\n\t"
+                 "ds_read_u16 %3, %8 offset:48\n\t"
+                 "ds_read_u16 %4, %8 offset:64\n\t"
+                 "ds_read_u16 %5, %8 offset:80\n\t"
+                 "ds_read_u16 %6, %8 offset:96\n\t"
+                 "ds_read_u16 %7, %8 offset:112"
+                 : "=&v"(f.e[0]), "=&v"(f.e[1]), "=&v"(f.e[2]), "=&v"(f.e[3]), "=&v"(f.e[4]), "=&v"(f.e[5]), "=&v"(f.e[6]), "=&v"(f.e[7])
+                 : "v"(addr));
+}
 __device__ __forceinline__ uint4 column8_landed(Column8 &f) {
     asm volatile("" : "+v"(f.e[0]), "+v"(f.e[1]), "+v"(f.e[2]), "+v"(f.e[3]), "+v"(f.e[4]), "+v"(f.e[5]), "+v"(f.e[6]), "+v"(f.e[7]));
     return make_uint4(f.e[0] | (f.e[1] << 16), f.e[2] | (f.e[3] << 16), f.e[4] | (f.e[5] << 16), f.e[6] | (f.e[7] << 16));
@@ -717,6 +730,143 @@ __global__ void __launch_bounds__(256) wgrad_lds_kernel(const WgradArgs a) {
     for (int i = tid; i < 64 * 64; i += 256) {
         const int kk = i >> 6, cc = i & 63;
         if (k0 + kk < a.K && c0 + cc < a.C) out[(size_t)(k0 + kk) * kstride + (size_t)tap * a.C + c0 + cc] = red[kk][cc];
+    }
+#endif
+}
+
+// Weight gradient of the 7x7 / stride-2 / pad-3 convolution over a 3-channel input (the ResNet-shaped stem), bf16.
+// With Cin = 3 the generic kernels fill 3 of 64 columns of their (k, c) block.  Here, as in the forward stem kernel,
+// a workgroup stages the input patch of an 8 x 16 block of output pixels in LDS widened to 4 channels, so that for
+// a fixed filter row r the 28 (s, c) taps of neighbouring output pixels are 16 bytes apart: the contraction becomes
+// D_r[k][s*4+c] = sum over pixels of dz[pixel][k] * patch[pixel, r][s*4+c], one 32-wide MFMA column block per filter
+// row, and an MFMA fragment (8 consecutive output pixels of a row) is eight 2-byte LDS reads 16 bytes apart.  The
+// block's dz rows arrive by DMA (double buffered); wave w accumulates filter rows w and w+4.  Persistent
+// workgroups walk the pixel blocks; each writes one fp32 partial [k][tap][c] that wgrad_reduce_kernel adds in order.
+constexpr int WS_TH = 8, WS_TW = 16, WS_IH = 2 * WS_TH + 5, WS_IW = 2 * WS_TW + 6;
+__global__ void __launch_bounds__(256) wgrad_stem_kernel(const WgradArgs a, int tiles_h, int tiles_w, int ntiles) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    using namespace lds_pipe;
+    __shared__ __align__(1024) unsigned char dzl[2][128 * 128];          // dz rows of the block, 64 channels each
+    __shared__ __align__(16) bf16_t xl[WS_IH * WS_IW * 4];               // widened input patch
+    const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bf16_t *__restrict__ xg = static_cast<const bf16_t *>(a.x);
+    const __amdgpu_buffer_rsrc_t zr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.dz), 0, (int)a.dz_bytes, 0x00020000);
+
+    for (int i = tid; i < WS_IH * WS_IW * 4; i += 256) xl[i] = 0;        // incl. the never-written pad column
+    __syncthreads();
+
+    // input patch of a block: (2*TH+5) x (2*TW+5) pixels of 3 channels, NP pixels per thread, one block ahead
+    constexpr int NPIX = WS_IH * (WS_IW - 1), NP = (NPIX + 255) / 256;
+    uint2 pv[NP];
+    auto load_patch = [&](int tile) {
+        const int tw = tile % tiles_w, t2 = tile / tiles_w;
+        const int th = t2 % tiles_h, n = t2 / tiles_h;
+#pragma unroll
+        for (int i = 0; i < NP; i++) {
+            const int e = tid + i * 256;
+            const int ih = e / (WS_IW - 1), iw = e % (WS_IW - 1);
+            const int gh = 2 * th * WS_TH - 3 + ih, gw = 2 * tw * WS_TW - 3 + iw;
+            pv[i] = make_uint2(0, 0);
+            if (e < NPIX && (unsigned)gh < (unsigned)a.H && (unsigned)gw < (unsigned)a.W) {
+                const bf16_t *p = xg + (((long)n * a.H + gh) * a.W + gw) * 3;
+                pv[i].x = (uint32_t)p[0] | ((uint32_t)p[1] << 16);
+                pv[i].y = (uint32_t)p[2];
+            }
+        }
+    };
+    auto store_patch = [&]() {
+#pragma unroll
+        for (int i = 0; i < NP; i++) {
+            const int e = tid + i * 256;
+            if (e < NPIX) {
+                const int ih = e / (WS_IW - 1), iw = e % (WS_IW - 1);
+                *reinterpret_cast<uint2 *>(&xl[(ih * WS_IW + iw) * 4]) = pv[i];
+            }
+        }
+    };
+    // dz rows of a block: row py*16+px <- dz[n][p0+py][q0+px][0..63]; 16 segments of 8 rows x 8 slots, 4 per wave
+    const int lslot = lane & 7, lrow = lane >> 3;
+    auto issue_dz = [&](int tile, int buf) {
+        const int tw = tile % tiles_w, t2 = tile / tiles_w;
+        const int th = t2 % tiles_h, n = t2 / tiles_h;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int row = (wave * 4 + i) * 8 + lrow;
+            const int p = th * WS_TH + (row >> 4), q = tw * WS_TW + (row & 15);
+            const int gs = lslot ^ (((row >> 3) & 1) << 2);
+            const bool ok = tile < ntiles && p < a.Ho && q < a.Wo && gs * 8 < a.K;
+            const unsigned off = ok ? (unsigned)((((n * a.Ho + p) * a.Wo + q) * a.K + gs * 8) * 2) : 0xffffffffu;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(zr, (__attribute__((address_space(3))) void *)(&dzl[buf][(wave * 4 + i) * 1024]), 16, off, 0, 0, 0);
+        }
+    };
+
+    f32x16_t acc[2][2];                                                   // [filter row slot][k block]
+#pragma unroll
+    for (int i = 0; i < 2; i++)
+#pragma unroll
+        for (int j = 0; j < 2; j++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+    const bool two_rows = wave + 4 < 7;                                   // waves 0..2 own filter rows w and w+4, wave 3 row 3
+
+    // fragment bases: dz column lr of k block i, rows 8h.. of a 16-pixel row of the block; patch taps lr = s*4+c
+    unsigned fz[2];
+#pragma unroll
+    for (int i = 0; i < 2; i++) fz[i] = (unsigned)((8 * h) * 128 + (((i * 4 + (lr >> 3)) ^ (h << 2)) << 4) + (lr & 7) * 2);
+    const unsigned fxl = lds_addr(xl) + (unsigned)((2 * 8 * h) * 8 + lr * 2);   // pixel 8h of the row, tap column lr
+
+    int buf = 0;
+    if ((int)blockIdx.x < ntiles) { load_patch(blockIdx.x); issue_dz(blockIdx.x, 0); }
+    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        __builtin_amdgcn_s_barrier();                                     // the previous block's patch and dz rows are no longer read
+        store_patch();
+        issue_dz(tile + gridDim.x, buf ^ 1);                              // the next block's dz rows (zeros past the end)
+        wait_vmcnt<4>();                                                  // this block's dz rows have landed (this wave's share)
+        wait_lgkmcnt<0>();                                                // ... and its patch stores
+        __builtin_amdgcn_s_barrier();                                     // bare barriers: the DMA just issued stays in flight
+        if (tile + (int)gridDim.x < ntiles) load_patch(tile + gridDim.x); // in flight under the MFMAs
+        const unsigned zb = lds_addr(&dzl[buf][0]);
+#pragma unroll
+        for (int py = 0; py < WS_TH; py++) {                              // one k-step = the 16 pixels of block row py
+            Column8 ca[2], cb[2];
+#pragma unroll
+            for (int i = 0; i < 2; i++) read_column8(ca[i], zb + (unsigned)(py * 16 * 128) + fz[i]);
+            read_column8_16(cb[0], fxl + (unsigned)(((2 * py + wave) * WS_IW) * 8));
+            if (two_rows) read_column8_16(cb[1], fxl + (unsigned)(((2 * py + wave + 4) * WS_IW) * 8));
+            wait_lgkmcnt<0>();
+            uint4 fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; i++) fa[i] = column8_landed(ca[i]);
+            fb[0] = column8_landed(cb[0]);
+#pragma unroll
+            for (int i = 0; i < 2; i++) Mma<bf16_t>::run(acc[0][i], fa[i], fb[0]);
+            if (two_rows) {
+                fb[1] = column8_landed(cb[1]);
+#pragma unroll
+                for (int i = 0; i < 2; i++) Mma<bf16_t>::run(acc[1][i], fa[i], fb[1]);
+            }
+        }
+        buf ^= 1;
+    }
+    wait_vmcnt<0>();
+
+    // partial of this workgroup: part[wg][k][tap = r*7+s][c]; accumulator register e of lane l holds
+    // D[k = 8*(e/4) + 4*(l/32) + e%4 (+32 i)][column l%32 = s*4 + c]
+    float *out = a.part + (size_t)blockIdx.x * a.K * 147;
+    const int sx = lr >> 2, c = lr & 3;
+#pragma unroll
+    for (int slot = 0; slot < 2; slot++) {
+        const int r = wave + 4 * slot;
+        if (r < 7 && sx < 7 && c < 3) {
+#pragma unroll
+            for (int i = 0; i < 2; i++)
+#pragma unroll
+                for (int e = 0; e < 16; e++) {
+                    const int k = i * 32 + 8 * (e / 4) + 4 * h + e % 4;
+                    if (k < a.K) out[((size_t)k * 49 + r * 7 + sx) * 3 + c] = acc[slot][i][e];
+                }
+        }
     }
 #endif
 }
@@ -910,7 +1060,22 @@ static bool wgrad_lds_applies(const sol_tensor_desc &xd, const sol_conv_desc &cd
     return xd.dtype == SOL_BF16 && cd.cout % 8 == 0 && cd.cin % 8 == 0;
 }
 
+// bf16 7x7 / stride 2 / pad 3 over 3 input channels, at most 64 output channels: the stem kernel
+static bool wgrad_stem_applies(const sol_tensor_desc &xd, const sol_conv_desc &cd) {
+    return xd.dtype == SOL_BF16 && xd.c == 3 && cd.cin == 3 && cd.kh == 7 && cd.kw == 7 && cd.sh == 2 && cd.sw == 2 && cd.ph == 3 &&
+           cd.pw == 3 && cd.cout <= 64 && cd.cout % 8 == 0;
+}
+static int wgrad_stem_grid(const sol_tensor_desc &xd, int Ho, int Wo) {
+    const long tiles = (long)xd.n * ceil_div(Ho, WS_TH) * ceil_div(Wo, WS_TW);
+    return (int)std::min<long>(tiles, 256);
+}
+
 void wgrad_plan(const sol_tensor_desc &xd, const sol_conv_desc &cd, int Ho, int Wo, int *nsplit, size_t *part_floats) {
+    if (wgrad_stem_applies(xd, cd)) {
+        *nsplit = std::max(1, wgrad_stem_grid(xd, Ho, Wo));
+        *part_floats = (size_t)*nsplit * cd.cout * 147;
+        return;
+    }
     if (wgrad_lds_applies(xd, cd)) {
         const int nsteps = (int)(((long)xd.n * Ho * Wo + 63) / 64);
         const int tiles = ceil_div(cd.cout, 64) * ceil_div(cd.cin, 64) * cd.kh * cd.kw;
@@ -942,6 +1107,19 @@ sol_status launch_wgrad(const sol_tensor_desc &xd, const void *x, const sol_conv
     a.x = x; a.dz = dz; a.part = part;
     a.N = xd.n; a.H = xd.h; a.W = xd.w; a.C = xd.c; a.K = cd.cout; a.R = cd.kh; a.S = cd.kw;
     a.sh = cd.sh; a.sw = cd.sw; a.ph = cd.ph; a.pw = cd.pw; a.Ho = Ho; a.Wo = Wo;
+    if (wgrad_stem_applies(xd, cd)) {
+        const int tiles_h = ceil_div(Ho, WS_TH), tiles_w = ceil_div(Wo, WS_TW), ntiles = xd.n * tiles_h * tiles_w;
+        size_t pf;
+        wgrad_plan(xd, cd, Ho, Wo, &a.nsplit, &pf);
+        a.dz_bytes = (uint32_t)zb; a.x_bytes = (uint32_t)xb;
+        if (ntiles > 0) {
+            hipLaunchKernelGGL(wgrad_stem_kernel, dim3(a.nsplit), dim3(256), 0, st, a, tiles_h, tiles_w, ntiles);
+            const long total = (long)cd.cout * 147;
+            hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for(total)), dim3(256), 0, st, part, a.nsplit, dw, cd.cout, cd.cin, 49);
+        }
+        SOL_HIP(hipGetLastError());
+        return SOL_OK;
+    }
     const bool lds_path = wgrad_lds_applies(xd, cd);
     a.G = lds_path ? Wo : ceil_div(Wo, GP);
     a.ngroups = xd.n * Ho * a.G;

@@ -126,6 +126,7 @@ def small_nets():
         "plain":    [c(6, 5, p=2, bn=False), p("avg", 2, 2, 0), c(10, 3, bn=False, act="none"), p("avg", 3, 2, 1, count_pad=0),
                      c(12, 1, p=0, bn=False), g(), fc(7, act="relu"), fc(4)],
         "wide":     [c(64, 3, s=1), c(64, 3, res=0), c(128, 3, s=2), c(128, 1, p=0, act="none"), g(), fc(32)],
+        "stem":     [c(64, 7, s=2, p=3), p("max", 3, 2, 1), c(64, 3), g(), fc(10)],   # 3-channel 7x7 / stride-2 stem
     }
 
 
@@ -142,7 +143,7 @@ def _make(name, dtype, N=4, H=17, W=19, cin=3, seed=11):
     return layers, params, x, labels
 
 
-@pytest.mark.parametrize("name", ["resblock", "identity", "plain", "wide"])
+@pytest.mark.parametrize("name", ["resblock", "identity", "plain", "wide", "stem"])
 def test_train_step_fp32(sol, name):
     layers, params, x, labels = _make(name, "f32")
     _, got = gpu_train(sol, layers, params, x, labels, "f32", steps=2)
@@ -151,7 +152,7 @@ def test_train_step_fp32(sol, name):
         compare(got[s], ref[s], layers, "f32", tag=f"{name}/fp32 step {s}")
 
 
-@pytest.mark.parametrize("name", ["resblock", "identity", "plain", "wide"])
+@pytest.mark.parametrize("name", ["resblock", "identity", "plain", "wide", "stem"])
 def test_train_step_bf16(sol, name):
     layers, params, x, labels = _make(name, "bf16", N=8, H=24, W=24)
     _, got = gpu_train(sol, layers, params, x, labels, "bf16")
