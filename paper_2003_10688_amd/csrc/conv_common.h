@@ -407,7 +407,7 @@ template <typename T, int TP, int TC, typename RowMap>
 __device__ __forceinline__ void conv_epilogue_auto(const ConvArgs &a, f32x16_t (&acc)[TC][TP], float *lds_f, int wave, int lane,
                                                    int mw, int cw, const Affine8 &aff, const RowMap &rowmap,
                                                    const ResidualRegs<T, TP, TC> &pre) {
-    const bool interior = a.pool == 0 && (a.Cout & 7) == 0 && mw + TP * 32 <= a.P && cw + TC * 32 <= a.Cout && a.scale && a.shift;
+    const bool interior = a.pool == 0 && (a.Cout & 7) == 0 && mw + TP * 32 <= a.P && cw + TC * 32 <= a.Cout;
     const LinearRowOffset ro{(unsigned)mw * (unsigned)a.Cout, (unsigned)a.Cout};
     if (interior && a.res == nullptr) conv_epilogue_interior<T, TP, TC, false>(a, acc, lds_f, wave, lane, cw, aff, pre, ro);
     else if (interior && pre.on) conv_epilogue_interior<T, TP, TC, true>(a, acc, lds_f, wave, lane, cw, aff, pre, ro);

@@ -133,7 +133,8 @@ __global__ void __launch_bounds__(WP *WC *KSPL * 64, MINW) conv_halo_kernel(cons
         static_for<WL>([&](auto I) { issue_w(I, s, (unsigned)s * tapstride, real); });
     }
     // epilogue operands (scale / shift, residual rows) and the zero rows, all behind the first DMAs
-    const Affine8 aff = load_affine_unconditional<TC>(a, lane, c0 + wc * TC * 32);
+    // (absent scale / shift -- the training forward stores the bare convolution -- read as 1 / 0)
+    const Affine8 aff = (a.scale && a.shift) ? load_affine_unconditional<TC>(a, lane, c0 + wc * TC * 32) : load_affine<TC>(a, lane, c0 + wc * TC * 32);
     ResidualRegs<T, TP, TC> resregs;
     resregs.on = false;                                  // tight register budgets fetch residual rows in the epilogue instead
     if constexpr (MINW < 4) {
@@ -314,7 +315,7 @@ bool halo_kernel_applies(const ConvArgs &a, int dt) {
     if (dt != SOL_BF16) return false;
     const double xb = (double)a.P * a.C * 2.0, wb = (double)a.Cout * a.Kp * 2.0;
     return a.R == 3 && a.S == 3 && a.sh == 1 && a.sw == 1 && a.ph == 1 && a.pw == 1 && a.pool == 0 && a.C % 64 == 0 &&
-           a.scale && a.shift && a.Cout % 8 == 0 && a.Ho == a.H && a.Wo == a.W && a.W <= 62 && xb < 2147483648.0 && wb < 2147483648.0;
+           a.Cout % 8 == 0 && a.Ho == a.H && a.Wo == a.W && a.W <= 62 && xb < 2147483648.0 && wb < 2147483648.0;
 }
 
 // Shape heuristic (sol_network_autotune refines it by timing): one workgroup per CU wants about 200 tiles or

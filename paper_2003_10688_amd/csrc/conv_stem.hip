@@ -112,7 +112,7 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
         ResidualRegs<bf16_t, 1, 2> resregs;
         resregs.on = false;
         // blocks inside the image with the usual 64 channels and no residual: branch-free epilogue
-        if (p0 + STEM_TH <= a.Ho && q0 + STEM_TW <= a.Wo && a.Cout == 64 && a.res == nullptr && a.scale && a.shift) {
+        if (p0 + STEM_TH <= a.Ho && q0 + STEM_TW <= a.Wo && a.Cout == 64 && a.res == nullptr) {
             const int pw = p0 + 2 * wave;     // first output row of this wave's 32 tile rows
             const StemRowOffset ro{(unsigned)(((n * a.Ho + pw) * a.Wo + q0) * 64), (unsigned)a.Wo, 64u};
             conv_epilogue_interior<bf16_t, 1, 2, false>(a, acc, strip, wave, lane, 0, aff, resregs, ro);

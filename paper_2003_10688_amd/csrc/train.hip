@@ -161,19 +161,31 @@ __global__ void __launch_bounds__(1024) col_finalize_kernel(const float *__restr
 
 // ---- elementwise passes -----------------------------------------------------------------------------
 // y = act( gamma (z - mean) invstd + beta + res )        (BN with batch statistics, training forward)
-template <typename T, int V>
+// FIXC: 256 * V is a multiple of C, so a thread's V channels are the same in every iteration of its grid-stride
+// loop and the per-channel operands are fetched once (otherwise they cost four loads per element of data).
+template <typename T, int V, bool FIXC>
 __global__ void __launch_bounds__(256) bn_apply_kernel(const T *__restrict__ z, const T *__restrict__ res, T *__restrict__ y,
                                                        const float *__restrict__ mean, const float *__restrict__ invstd,
                                                        const float *__restrict__ gamma, const float *__restrict__ beta,
                                                        long nvec, int C, int relu) {
+    float m[V], is[V], ga[V], be[V];
+    if (FIXC) {
+        const int c0 = (int)((threadIdx.x * V) % C);
+#pragma unroll
+        for (int e = 0; e < V; e++) { m[e] = mean[c0 + e]; is[e] = invstd[c0 + e]; ga[e] = gamma[c0 + e]; be[e] = beta[c0 + e]; }
+    }
     for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
-        const int c0 = (int)((i * V) % C);
+        if (!FIXC) {
+            const int c0 = (int)((i * V) % C);
+#pragma unroll
+            for (int e = 0; e < V; e++) { m[e] = mean[c0 + e]; is[e] = invstd[c0 + e]; ga[e] = gamma[c0 + e]; be[e] = beta[c0 + e]; }
+        }
         float v[V], r[V];
         VecIO<T, V>::load(z + i * V, v);
         if (res) VecIO<T, V>::load(res + i * V, r);
 #pragma unroll
         for (int e = 0; e < V; e++) {
-            float f = (v[e] - mean[c0 + e]) * invstd[c0 + e] * gamma[c0 + e] + beta[c0 + e];
+            float f = (v[e] - m[e]) * is[e] * ga[e] + be[e];
             if (res) f += r[e];
             if (relu) f = fmaxf(f, 0.f);
             v[e] = f;
@@ -187,15 +199,23 @@ __global__ void __launch_bounds__(256) bn_apply_kernel(const T *__restrict__ z, 
 //   dres (+)= g                                   (when the layer has a residual input)
 //   dz = gamma invstd (g - dbeta / M - xhat dgamma / M),   xhat = (z - mean) invstd      (BN)
 //   dz = g                                                                               (no BN)
-template <typename T, int V>
+template <typename T, int V, bool FIXC>
 __global__ void __launch_bounds__(256) act_bn_bwd_kernel(const T *__restrict__ z, const T *__restrict__ dy,
                                                          const T *__restrict__ y, const float *__restrict__ mean,
                                                          const float *__restrict__ invstd, const float *__restrict__ gamma,
                                                          const float *__restrict__ dbeta, const float *__restrict__ dgamma,
                                                          T *__restrict__ dz, T *dres, int res_first, long nvec, int C,
                                                          int relu, int bn, float inv_m) {
+    float m[V], is[V], ga[V], db[V], dg[V];          // per-channel operands (see bn_apply_kernel for FIXC)
+    auto fetch = [&](int c0) {
+#pragma unroll
+        for (int e = 0; e < V; e++) {
+            m[e] = mean[c0 + e]; is[e] = invstd[c0 + e]; ga[e] = gamma[c0 + e]; db[e] = dbeta[c0 + e]; dg[e] = dgamma[c0 + e];
+        }
+    };
+    if (FIXC && bn) fetch((int)((threadIdx.x * V) % C));
     for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
-        const int c0 = (int)((i * V) % C);
+        if (!FIXC && bn) fetch((int)((i * V) % C));
         float g[V], t[V];
         VecIO<T, V>::load(dy + i * V, g);
         if (relu) {
@@ -218,9 +238,8 @@ __global__ void __launch_bounds__(256) act_bn_bwd_kernel(const T *__restrict__ z
             VecIO<T, V>::load(z + i * V, t);
 #pragma unroll
             for (int e = 0; e < V; e++) {
-                const float is = invstd[c0 + e];
-                const float xh = (t[e] - mean[c0 + e]) * is;
-                g[e] = gamma[c0 + e] * is * (g[e] - dbeta[c0 + e] * inv_m - xh * dgamma[c0 + e] * inv_m);
+                const float xh = (t[e] - m[e]) * is[e];
+                g[e] = ga[e] * is[e] * (g[e] - db[e] * inv_m - xh * dg[e] * inv_m);
             }
         }
         VecIO<T, V>::store(dz + i * V, g);
@@ -405,7 +424,7 @@ __global__ void __launch_bounds__(256) pack_batch_kernel(const PackBatch b) {
     for (int u = 0; u < PACK_ELEMS_PER_BLOCK / 256; u++) {
         const long i = i0 + u * 256 + threadIdx.x;
         if (i >= total) break;
-        const int row = (int)(i / Kp), j = (int)(i % Kp);
+        const unsigned row = (unsigned)i / (unsigned)Kp, j = (unsigned)i % (unsigned)Kp;    // packed buffers hold < 2^31 elements
         float v = 0.f;
         if (!flip) {                               // out[k][(r*S+s)*C + c]
             if (j < R * S * C) {
@@ -935,9 +954,14 @@ sol_status launch_bn_stats(const void *z, int rows, int C, int dt, float eps, fl
 
 sol_status launch_bn_apply(const void *z, const void *res, void *y, const float *mean, const float *invstd,
                            const float *gamma, const float *beta, long total, int C, int relu, int dt, hipStream_t st) {
-    SOL_DISPATCH_TV(dt, C, hipLaunchKernelGGL((bn_apply_kernel<T, V>), dim3(grid_for(total / V)), dim3(256), 0, st,
-                                              static_cast<const T *>(z), static_cast<const T *>(res), static_cast<T *>(y),
-                                              mean, invstd, gamma, beta, total / V, C, relu));
+    SOL_DISPATCH_TV(dt, C, {
+        if ((256 * V) % C == 0)
+            hipLaunchKernelGGL((bn_apply_kernel<T, V, true>), dim3(grid_for(total / V)), dim3(256), 0, st, static_cast<const T *>(z),
+                               static_cast<const T *>(res), static_cast<T *>(y), mean, invstd, gamma, beta, total / V, C, relu);
+        else
+            hipLaunchKernelGGL((bn_apply_kernel<T, V, false>), dim3(grid_for(total / V)), dim3(256), 0, st, static_cast<const T *>(z),
+                               static_cast<const T *>(res), static_cast<T *>(y), mean, invstd, gamma, beta, total / V, C, relu);
+    });
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }
@@ -968,10 +992,16 @@ sol_status launch_grad_col_sums(const void *z, const void *dy, const void *y, co
 sol_status launch_act_bn_bwd(const void *z, const void *dy, const void *y, const float *mean, const float *invstd,
                              const float *gamma, const float *dbeta, const float *dgamma, void *dz, void *dres,
                              int res_first, long total, int C, int relu, int bn, int rows, int dt, hipStream_t st) {
-    SOL_DISPATCH_TV(dt, C, hipLaunchKernelGGL((act_bn_bwd_kernel<T, V>), dim3(grid_for(total / V)), dim3(256), 0, st,
-                                              static_cast<const T *>(z), static_cast<const T *>(dy), static_cast<const T *>(y),
-                                              mean, invstd, gamma, dbeta, dgamma, static_cast<T *>(dz), static_cast<T *>(dres),
-                                              res_first, total / V, C, relu, bn, 1.f / rows));
+    SOL_DISPATCH_TV(dt, C, {
+        if ((256 * V) % C == 0)
+            hipLaunchKernelGGL((act_bn_bwd_kernel<T, V, true>), dim3(grid_for(total / V)), dim3(256), 0, st,
+                               static_cast<const T *>(z), static_cast<const T *>(dy), static_cast<const T *>(y), mean, invstd, gamma,
+                               dbeta, dgamma, static_cast<T *>(dz), static_cast<T *>(dres), res_first, total / V, C, relu, bn, 1.f / rows);
+        else
+            hipLaunchKernelGGL((act_bn_bwd_kernel<T, V, false>), dim3(grid_for(total / V)), dim3(256), 0, st,
+                               static_cast<const T *>(z), static_cast<const T *>(dy), static_cast<const T *>(y), mean, invstd, gamma,
+                               dbeta, dgamma, static_cast<T *>(dz), static_cast<T *>(dres), res_first, total / V, C, relu, bn, 1.f / rows);
+    });
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }
