@@ -178,6 +178,10 @@ sol_status sol_network_forward(sol_network *net, const void *x, void *y, void *w
 sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *workspace,
                                 size_t workspace_bytes, int reps, void *hip_stream);
 sol_status sol_network_layer_tile(const sol_network *net, int layer, int *tile);
+/* Restores a choice that sol_network_autotune made earlier (same network, same machine): `tile` as reported by
+ * sol_network_layer_tile, 0 = shape heuristic.  An id that does not fit the layer makes the next forward fail with
+ * SOL_ERR_UNSUPPORTED before anything is launched for that layer. */
+sol_status sol_network_set_layer_tile(sol_network *net, int layer, int tile);
 
 /* One forward pass recorded as a HIP graph (launch-bound inner loops: the ~56 launches of a ResNet-50-shaped
  * pass replay as one submission).  sol_network_graph_create runs the pass once eagerly, then records the same

@@ -763,6 +763,14 @@ sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *
     return rs;
 }
 
+sol_status sol_network_set_layer_tile(sol_network *net, int layer, int tile) {
+    SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    SOL_REQUIRE(tile >= 0 && tile < 100, SOL_ERR_SHAPE, "tile id %d out of range", tile);
+    net->layers[layer].tile = tile;
+    return SOL_OK;
+}
+
 sol_status sol_network_layer_tile(const sol_network *net, int layer, int *tile) {
     SOL_REQUIRE(net && tile, SOL_ERR_NULL, "net and tile must not be NULL");
     SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);

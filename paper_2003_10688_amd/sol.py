@@ -298,6 +298,11 @@ class Network:
                 out[i] = t.value
         return out
 
+    def set_tiles(self, tiles):
+        """Restores per-layer kernel/tile ids from an earlier autotune() of the same network ({layer: tile id})."""
+        for i in range(len(self.layers)):
+            _check(lib().sol_network_set_layer_tile(self._h, C.c_int(i), C.c_int(int(tiles.get(i, tiles.get(str(i), 0))))))
+
     def graph(self, x, stream):
         """Records one forward pass on `stream` (a torch.cuda.Stream other than the default one) as a HIP graph;
         returns a callable that enqueues one replay on that stream and returns the output tensor."""
