@@ -65,7 +65,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=3, help="workload: 3 = ResNet-50-shaped bs64 (default), 2 = ResNet-18-shaped bs32")
+    ap.add_argument("--config", type=int, default=3, help="workload: 3 = ResNet-50-shaped bs64 (default), 2 = ResNet-18-shaped bs32, 5 = 3-layer MLP with 8192 features bs64")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--layer-reps", type=int, default=20, help="event-timed repetitions per layer for the roofline")
     ap.add_argument("--cpu-sample", type=int, default=8, help="images the CPU checker is timed on (0 = skip)")
@@ -154,30 +154,39 @@ def main():
         fl, by = algorithmic_work(l, ins[i], outs[i], esize)
         rows.append({"i": i, "kind": l["kind"], "us": us, "flops": fl, "bytes": by})
     conv = [r for r in rows if r["kind"] == "conv"]
-    conv_us = sum(r["us"] for r in conv)
-    conv_fl = sum(r["flops"] for r in conv)
-    conv_by = sum(r["bytes"] for r in conv)
-    ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
-    mf = [r for r in conv if r["flops"] / r["bytes"] >= ridge]
-    hb = [r for r in conv if r["flops"] / r["bytes"] < ridge]
     mem = [r for r in rows if r["kind"] in ("pool", "gap")]
-    tfl = conv_fl / (conv_us * 1e-6) / 1e12
-    roofline = {
-        "bound": "mfma", "kernel": "fused convolution kernels (conv_dma / conv_halo / conv_gemm8 / conv_stem)", "launches_per_step": len(conv),
-        "achieved": round(tfl, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl / PEAK_BF16_TFLOPS, 4),
-        "avg_launch_us": round(conv_us / max(len(conv), 1), 2), "algorithmic_gflop_per_launch": round(conv_fl / max(len(conv), 1) / 1e9, 3),
-        "traffic": ({"hbm_mb_per_launch": MEASURED_CONV_TRAFFIC_MB_PER_LAUNCH, "algorithmic_mb_per_launch": round(conv_by / max(len(conv), 1) / 1e6, 1),
-                     "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/conv_resnet50_bs64_hbm_traffic.md"}
-                    if a.config == 3 and wk.in_shape[0] == 64 else None),
-        "mfma_bound_layers": {"n": len(mf), "tflops": round(sum(r["flops"] for r in mf) / max(sum(r["us"] for r in mf), 1e-9) / 1e6, 2),
-                              "frac": round(sum(r["flops"] for r in mf) / max(sum(r["us"] for r in mf), 1e-9) / 1e6 / PEAK_BF16_TFLOPS, 4)},
-        "hbm_bound_layers": {"n": len(hb), "gbs": round(sum(r["bytes"] for r in hb) / max(sum(r["us"] for r in hb), 1e-9) / 1e3, 1),
-                             "frac": round(sum(r["bytes"] for r in hb) / max(sum(r["us"] for r in hb), 1e-9) / 1e3 / PEAK_HBM_GBS, 4)},
-        "pool_gap_kernels": {"n": len(mem), "gbs": round(sum(r["bytes"] for r in mem) / max(sum(r["us"] for r in mem), 1e-9) / 1e3, 1),
-                             "frac": round(sum(r["bytes"] for r in mem) / max(sum(r["us"] for r in mem), 1e-9) / 1e3 / PEAK_HBM_GBS, 4)},
-        "conv_algorithmic_gb_per_step": round(conv_by / 1e9, 3),
-        "sum_layer_us": round(sum(r["us"] for r in rows), 1),
-    }
+    if conv:
+        conv_us = sum(r["us"] for r in conv)
+        conv_fl = sum(r["flops"] for r in conv)
+        conv_by = sum(r["bytes"] for r in conv)
+        ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+        mf = [r for r in conv if r["flops"] / r["bytes"] >= ridge]
+        hb = [r for r in conv if r["flops"] / r["bytes"] < ridge]
+        tfl = conv_fl / (conv_us * 1e-6) / 1e12
+        grp = lambda rs, key, peak, scale: {"n": len(rs),  # noqa: E731
+                                            key: round(sum(r["flops" if key == "tflops" else "bytes"] for r in rs) / max(sum(r["us"] for r in rs), 1e-9) / scale, 2),
+                                            "frac": round(sum(r["flops" if key == "tflops" else "bytes"] for r in rs) / max(sum(r["us"] for r in rs), 1e-9) / scale / peak, 4)}
+        roofline = {
+            "bound": "mfma", "kernel": "fused convolution kernels (conv_dma / conv_halo / conv_gemm8 / conv_stem)", "launches_per_step": len(conv),
+            "achieved": round(tfl, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl / PEAK_BF16_TFLOPS, 4),
+            "avg_launch_us": round(conv_us / len(conv), 2), "algorithmic_gflop_per_launch": round(conv_fl / len(conv) / 1e9, 3),
+            "traffic": ({"hbm_mb_per_launch": MEASURED_CONV_TRAFFIC_MB_PER_LAUNCH, "algorithmic_mb_per_launch": round(conv_by / len(conv) / 1e6, 1),
+                         "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/conv_resnet50_bs64_hbm_traffic.md"}
+                        if a.config == 3 and wk.in_shape[0] == 64 else None),
+            "mfma_bound_layers": grp(mf, "tflops", PEAK_BF16_TFLOPS, 1e6),
+            "hbm_bound_layers": grp(hb, "gbs", PEAK_HBM_GBS, 1e3),
+            "pool_gap_kernels": grp(mem, "gbs", PEAK_HBM_GBS, 1e3),
+            "conv_algorithmic_gb_per_step": round(conv_by / 1e9, 3),
+            "sum_layer_us": round(sum(r["us"] for r in rows), 1),
+        }
+    else:   # no convolution (the MLP workload): the linear kernel streams its weights once, bound by HBM
+        lin = [r for r in rows if r["kind"] == "linear"]
+        lin_us, lin_by = sum(r["us"] for r in lin), sum(r["bytes"] for r in lin)
+        gbs = lin_by / max(lin_us, 1e-9) / 1e3
+        roofline = {"bound": "hbm", "kernel": "linear layers (linear_kernel, or the conv_gemm8 weight-streaming tile for large weight matrices)", "launches_per_step": len(lin), "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "avg_launch_us": round(lin_us / max(len(lin), 1), 2),
+                    "algorithmic_mb_per_launch": round(lin_by / max(len(lin), 1) / 1e6, 2), "traffic": None,
+                    "tflops": round(sum(r["flops"] for r in lin) / max(lin_us, 1e-9) / 1e6, 2), "sum_layer_us": round(sum(r["us"] for r in rows), 1)}
     if a.layers:
         for r, xi, yo in zip(rows, ins, outs):
             ai = r["flops"] / r["bytes"]
@@ -229,7 +238,7 @@ def main():
         "ms_per_step": round(wall_ms, 4), "event_ms_per_step": round(ev_ms, 4),
         "submission": "HIP graph replay" if a.graph else "eager launches", "eager_ms_per_step": round(eager_ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if wk.bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{wk.name} batch {batch} input 3x{wk.in_shape[2]}x{wk.in_shape[3]} (seeded synthetic, He-normal weights)",
+        "config": {"workload": f"{wk.name} batch {batch} input {wk.in_shape[1]}x{wk.in_shape[2]}x{wk.in_shape[3]} (seeded synthetic, He-normal weights)",
                    "launches_per_step": len(wk.layers), "autotuned_layers": len(tuned), "autotune_seconds": round(tune_s, 2)},
         "roofline": roofline, "cpu_baseline": cpu, "training_step": training,
     }

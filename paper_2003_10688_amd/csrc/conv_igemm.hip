@@ -251,7 +251,13 @@ template <typename T> static sol_status launch_typed(const ConvArgs &a, int tile
 sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t st) {
     if (a.P <= 0) return SOL_OK;   // empty batch: nothing to do
     if (tile_override == T_AUTO && stem_kernel_applies(a, dt)) return launch_conv_stem(a, st);
-    if (tile_override == T_AUTO && linear_kernel_applies(a, dt)) return launch_linear(a, dt, st);
+    if (tile_override == T_AUTO && linear_kernel_applies(a, dt)) {
+        // few rows, but a weight matrix of many megabytes (the MLP workload): the job is streaming the weights, which the
+        // eight-wave ring kernel does with whole 128-byte lines and eight stages in flight
+        const double wbytes = (double)a.Cout * a.Kp * dtype_size(dt);
+        if (wbytes >= 16.0 * 1048576 && gemm8_kernel_applies(a, dt) && a.C % 64 == 0) return launch_conv_gemm8(a, G_64x64_k4_deep, st);
+        return launch_linear(a, dt, st);
+    }
     if (tile_override == T_AUTO && halo_kernel_applies(a, dt)) {
         if (const int ht = halo_choose_tile(a)) return launch_conv_halo(a, ht, st);
     }

@@ -98,6 +98,12 @@ def small_cnn_layers():
     ]
 
 
+def mlp_layers(features, depth=3):
+    """`depth` linear layers of `features` x `features` with a ReLU between them (the paper's MLP workload,
+    Sec. V: three layers, 8192 features)."""
+    return [linear(features, act="relu" if i + 1 < depth else "none") for i in range(depth)]
+
+
 def _stem():
     # conv 7x7 stride 2 pad 3 + BN + ReLU, then max-pool 3x3 stride 2 pad 1
     return [conv(64, 7, s=2, p=3), pool("max", 3, 2, 1)]
@@ -246,7 +252,7 @@ class Workload:
 
 
 def config(idx: int, batch: int | None = None, hw: int | None = None, dtype: str | None = None) -> Workload:
-    """The five configurations; ``batch`` / ``hw`` shrink a config for parity tests and ``dtype``
+    """The five configurations of the benchmark plus the paper's MLP workload (5); ``batch`` / ``hw`` shrink a config for parity tests and ``dtype``
     overrides its storage type (same seed, same layer list)."""
     wk = _config(idx, batch, hw)
     if dtype is not None:
@@ -271,4 +277,6 @@ def _config(idx, batch, hw):
     if idx == 4:
         return Workload("resnet18_train_bf16", resnet18_layers(), (batch or 32, 3, hw or 224, hw or 224),
                         "bf16", seed, "normal", training=True, num_classes=1000)
+    if idx == 5:   # hw = number of features here (the input is [batch, features, 1, 1])
+        return Workload("mlp3_bf16", mlp_layers(hw or 8192), (batch or 64, hw or 8192, 1, 1), "bf16", seed, "normal")
     raise ValueError(idx)

@@ -111,3 +111,20 @@ def test_planner_rejects_bad_graphs(sol):
     fake = C.c_void_p(0x1000)
     assert sol.lib().sol_network_forward(h, fake, fake, fake, C.c_size_t(1 << 30), None) == 5
     sol.lib().sol_network_destroy(h)
+
+
+def test_plan_tile_api_validates(sol):
+    """Per-layer kernel/tile ids (set by the auto-tune, restorable by the caller) are range-checked on the host."""
+    L = sol.lib()
+    st, h = _create(sol, wl.small_cnn_layers(), (8, 3, 32, 32), sol.F32)
+    assert st == 0
+    t = C.c_int(-1)
+    assert L.sol_network_layer_tile(h, 0, C.byref(t)) == 0 and t.value == 0          # heuristic until tuned
+    assert L.sol_network_set_layer_tile(h, 1, 21) == 0
+    assert L.sol_network_layer_tile(h, 1, C.byref(t)) == 0 and t.value == 21
+    assert L.sol_network_set_layer_tile(h, 99, 21) == 2 and L.sol_network_set_layer_tile(h, 0, 1000) == 2
+    assert L.sol_network_layer_tile(None, 0, C.byref(t)) == 1
+    fake = C.c_void_p(0x1000)
+    assert L.sol_network_autotune(None, fake, fake, fake, C.c_size_t(0), 3, None) == 1
+    assert L.sol_network_autotune(h, fake, fake, fake, C.c_size_t(1 << 30), 0, None) == 2     # reps out of range
+    L.sol_network_destroy(h)

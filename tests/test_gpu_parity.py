@@ -216,7 +216,7 @@ GEMM8_CASES = [
 ]
 
 
-@pytest.mark.parametrize("tile", list(range(61, 69)))
+@pytest.mark.parametrize("tile", list(range(61, 70)))
 @pytest.mark.parametrize("case", GEMM8_CASES)
 def test_gemm8_conv_tiles(sol, tile, case):
     """The eight-wave implicit-GEMM kernel in each tile shape (with and without the in-workgroup K split) against the
@@ -247,7 +247,7 @@ def test_gemm8_conv_exact_integers(sol):
     prm = {"w": w, "bias": np.zeros(K, np.float32)}
     want, _, _ = orc.fused_conv(x, prm, l, None, bf16=True)
     assert 4 < np.abs(want).max() <= 256
-    for tile in range(61, 69):
+    for tile in range(61, 70):
         sol.sol_debug_set_conv_tile(tile)
         try:
             got, _, _ = run_block(sol, "bf16", l, x, prm, None)
@@ -625,3 +625,25 @@ def test_network_autotune_keeps_results(sol):
             net.layer_output(i).copy_(dev[i])
     print(f"autotuned layers {tuned}; layer-by-layer max rel err {max(errs):.3e}")
     assert max(errs) <= TOL["bf16"], errs
+
+
+@pytest.mark.parametrize("batch,features", [(64, 1024), (5, 320), (130, 512)])
+def test_mlp_workload(sol, batch, features):
+    """The paper's MLP workload (three linear layers with ReLU, Sec. V) at reduced width through the network object,
+    every layer element-wise against the checker on the checker's activations, and end to end."""
+    wk = wl.config(5, batch=batch, hw=features)
+    outs, _ = orc.network_forward(wk.layers, wk.params, wk.x, bf16=True, return_all=True)
+    net, y = run_network(sol, wk)
+    assert norm_err(y.reshape(outs[-1].shape), outs[-1]) <= TOL["bf16"]
+    x = sol.to_device_nhwc(wk.x, sol.BF16)
+    dev = [sol.to_device_nhwc(o if o.ndim == 4 else o[:, :, None, None], sol.BF16) for o in outs]
+    nl = len(wk.layers)
+    for i in range(nl - 1):
+        net.layer_output(i).copy_(dev[i])
+    for i in range(nl):
+        net.run_layer(i, x)
+        torch.cuda.synchronize()
+        g = sol.to_host_nchw(net.y if i == nl - 1 else net.layer_output(i)).reshape(outs[i].shape)
+        assert rel_err(g, outs[i]) <= TOL["bf16"], i
+        if i < nl - 1:
+            net.layer_output(i).copy_(dev[i])
