@@ -87,6 +87,20 @@ def conv2d(x, w, bias=None, stride=(1, 1), pad=(0, 0)):
     return y
 
 
+def dwconv2d(x, w, bias=None, stride=(1, 1), pad=(0, 0)):
+    """Depthwise convolution (groups == channels, one filter per channel); w: [C,1,R,S] or [C,R,S]."""
+    x, w = _d(x), _d(w)
+    bias = _d(bias) if bias is not None else None
+    N, Cc, H, W = x.shape
+    w = w.reshape(w.shape[0], w.shape[-2], w.shape[-1])
+    C2, R, S = w.shape
+    assert Cc == C2
+    Ho, Wo = out_size(H, R, stride[0], pad[0]), out_size(W, S, stride[1], pad[1])
+    y = np.empty((N, Cc, Ho, Wo), np.float64)
+    lib().orc_dwconv2d(_p(x), _p(np.ascontiguousarray(w)), _p(bias), _p(y), *_i(N, Cc, H, W, R, S, stride[0], stride[1], pad[0], pad[1]))
+    return y
+
+
 def conv2d_points(x, w, bias, coords, stride=(1, 1), pad=(0, 0)):
     """Convolution outputs at the given (n,k,p,q) coordinates only."""
     x, w = _d(x), _d(w)
@@ -296,7 +310,8 @@ def _src_of(i, l, outs, x):
 
 def fused_conv(x, p, l, residual=None, bf16=False, want_prepool=False):
     """conv -> explicit BN -> (+residual) -> act -> pool -> (bf16 store).  Returns (y, argmax, prepool)."""
-    y = conv2d(x, p["w"], p.get("bias"), (l["sh"], l["sw"]), (l["ph"], l["pw"]))
+    cv = dwconv2d if l.get("dw") else conv2d
+    y = cv(x, p["w"], p.get("bias"), (l["sh"], l["sw"]), (l["ph"], l["pw"]))
     if l["bn"]:
         y = bn_infer(y, p["gamma"], p["beta"], p["mean"], p["var"], p.get("eps", 1e-5))
     if residual is not None:

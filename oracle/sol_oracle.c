@@ -48,6 +48,28 @@ void orc_conv2d(const double *x, const double *w, const double *bias, double *y,
                 }
 }
 
+/* Depthwise convolution (as many groups as channels; the paper's optimizer hands exactly this case to its fused
+ * loop-nest module instead of a library, Sec. III-A): every channel is filtered on its own,
+ * y[n,c,p,q] = bias[c] + sum_{r,s} x[n,c,p*sh+r-ph,q*sw+s-pw] * w[c,r,s]; x outside = 0 */
+void orc_dwconv2d(const double *x, const double *w, const double *bias, double *y, int N, int C, int H, int W,
+                  int R, int S, int sh, int sw, int ph, int pw) {
+    const int Ho = orc_out_size(H, R, sh, ph), Wo = orc_out_size(W, S, sw, pw);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; n++)
+        for (int c = 0; c < C; c++)
+            for (int p = 0; p < Ho; p++)
+                for (int q = 0; q < Wo; q++) {
+                    double acc = bias ? bias[c] : 0.0;
+                    for (int r = 0; r < R; r++)
+                        for (int s = 0; s < S; s++) {
+                            const int ih = p * sh + r - ph, iw = q * sw + s - pw;
+                            if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+                            acc += x[IDX4(n, c, ih, iw, C, H, W)] * w[((size_t)c * R + r) * S + s];
+                        }
+                    y[IDX4(n, c, p, q, C, Ho, Wo)] = acc;
+                }
+}
+
 /* the same definition evaluated at a list of output coordinates (n,k,p,q) only */
 void orc_conv2d_points(const double *x, const double *w, const double *bias, const int32_t *coords,
                        int npts, double *out, int N, int C, int H, int W, int K, int R, int S, int sh,

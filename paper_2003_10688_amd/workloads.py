@@ -59,11 +59,12 @@ def pool_desc(kind="max", k=2, s=2, p=0, count_pad=1):
             "count_pad": int(count_pad)}
 
 
-def conv(cout, k, s=1, p=None, bn=True, act="relu", pool=None, src=-1, res=-1):
+def conv(cout, k, s=1, p=None, bn=True, act="relu", pool=None, src=-1, res=-1, dw=False):
+    """dw: depthwise (groups == channels, cout must equal the input channel count; weights [C,1,k,k])."""
     if p is None:
         p = (k - 1) // 2
     return {"kind": "conv", "cout": cout, "kh": k, "kw": k, "sh": s, "sw": s, "ph": p, "pw": p,
-            "bn": bool(bn), "act": act, "pool": pool, "src": src, "res": res}
+            "bn": bool(bn), "act": act, "pool": pool, "src": src, "res": res, "dw": bool(dw)}
 
 
 def pool(kind="max", k=2, s=2, p=0, count_pad=1, src=-1):
@@ -183,8 +184,9 @@ def make_params(layers, cin, seed, bf16=False, bias_std=0.0):
         c_in = cin if (src == -1 and i == 0) else ch[i - 1 if src == -1 else src]
         p = {}
         if l["kind"] == "conv":
-            fan_in = c_in * l["kh"] * l["kw"]
-            w = _rng(seed, i, _T_W).standard_normal((l["cout"], c_in, l["kh"], l["kw"]))
+            wc_in = 1 if l.get("dw") else c_in            # depthwise: one filter per channel
+            fan_in = wc_in * l["kh"] * l["kw"]
+            w = _rng(seed, i, _T_W).standard_normal((l["cout"], wc_in, l["kh"], l["kw"]))
             w = (w * np.sqrt(2.0 / fan_in)).astype(np.float32)
             p["w"] = to_bf16_grid(w) if bf16 else w
             b = _rng(seed, i, _T_BIAS).standard_normal(l["cout"]) * bias_std

@@ -94,6 +94,49 @@ def test_conv_matches_library(shape):
     assert np.array_equal(pts, got[tuple(coords.T)])
 
 
+# ------------------------------------------------------------------------- depthwise conv
+def test_dwconv_hand_worked():
+    # 2 channels 3x3, one 2x2 filter each, no pad, stride 1: channels never mix.
+    x = np.stack([np.arange(1, 10, dtype=float).reshape(3, 3), 10.0 * np.arange(1, 10, dtype=float).reshape(3, 3)])[None]
+    w = np.array([[[1, 0], [-1, 2]], [[0, 1], [1, 0]]], float).reshape(2, 1, 2, 2)
+    got = orc.dwconv2d(x, w, np.array([0.5, -1.0]))
+    want0 = np.array([[1 - 4 + 10, 2 - 5 + 12], [4 - 7 + 16, 5 - 8 + 18]], float) + 0.5       # as in test_conv_hand_worked
+    want1 = 10.0 * np.array([[2 + 4, 3 + 5], [5 + 7, 6 + 8]], float) - 1.0                      # x[p,q+1] + x[p+1,q]
+    assert np.array_equal(got[0, 0], want0) and np.array_equal(got[0, 1], want1)
+
+
+@pytest.mark.parametrize("shape", [(2, 5, 9, 8, 3, 3, 1, 1, 1, 1), (1, 7, 11, 6, 3, 3, 2, 2, 1, 1), (3, 4, 7, 7, 5, 3, 1, 2, 2, 0),
+                                   (1, 3, 4, 4, 1, 1, 1, 1, 0, 0)])
+def test_dwconv_is_block_diagonal_conv_and_matches_library(shape):
+    N, C, H, W, Rr, S, sh, sw, ph, pw = shape
+    x, w, b = R.standard_normal((N, C, H, W)), R.standard_normal((C, 1, Rr, S)), R.standard_normal(C)
+    got = orc.dwconv2d(x, w, b, (sh, sw), (ph, pw))
+    # the dense convolution (pinned above) whose weights are zero off the channel diagonal
+    wf = np.zeros((C, C, Rr, S))
+    for c in range(C):
+        wf[c, c] = w[c, 0]
+    assert np.allclose(got, orc.conv2d(x, wf, b, (sh, sw), (ph, pw)), rtol=1e-13, atol=1e-13)
+    # the framework's grouped convolution with groups == channels
+    want = F.conv2d(T(x), T(w), T(b), stride=(sh, sw), padding=(ph, pw), groups=C).numpy()
+    assert got.shape == want.shape and np.allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_dwconv_delta_ones_and_fused_block():
+    x = R.standard_normal((2, 6, 5, 7))
+    d = np.zeros((6, 1, 3, 3))
+    d[:, 0, 1, 1] = 1.0
+    assert np.array_equal(orc.dwconv2d(x, d, None, (1, 1), (1, 1)), x)                    # delta filter: identity
+    ones = orc.dwconv2d(np.ones((1, 2, 4, 5)), np.ones((2, 1, 3, 3)), None, (1, 1), (1, 1))
+    assert ones[0, 0, 0, 0] == 4 and ones[0, 1, 0, 2] == 6 and ones[0, 0, 2, 2] == 9        # in-range taps at corner / edge / interior
+    # fused block: depthwise conv -> explicit BN -> ReLU, composed from the pinned pieces
+    l = wl.conv(6, 3, dw=True)
+    prm = {"w": R.standard_normal((6, 1, 3, 3)), "bias": R.standard_normal(6), "gamma": R.uniform(0.5, 1.5, 6),
+           "beta": R.uniform(-0.1, 0.1, 6), "mean": R.standard_normal(6) * 0.1, "var": R.uniform(0.5, 1.5, 6)}
+    y, _, _ = orc.fused_conv(x, prm, l)
+    want = orc.relu(orc.bn_infer(orc.dwconv2d(x, prm["w"], prm["bias"], (1, 1), (1, 1)), prm["gamma"], prm["beta"], prm["mean"], prm["var"]))
+    assert np.array_equal(y, want)
+
+
 # ------------------------------------------------------------------------------- BN, ReLU
 def test_bn_identity_and_affine():
     x = R.standard_normal((2, 3, 4, 4))
