@@ -47,7 +47,7 @@ typedef enum {
 typedef enum { SOL_F32 = 0, SOL_BF16 = 1 } sol_dtype;  /* bf16 = bf16 storage, fp32 accumulate */
 typedef enum { SOL_ACT_NONE = 0, SOL_ACT_RELU = 1 } sol_act;
 typedef enum { SOL_POOL_NONE = 0, SOL_POOL_MAX = 1, SOL_POOL_AVG = 2 } sol_pool_kind;
-typedef enum { SOL_LAYER_CONV = 0, SOL_LAYER_POOL = 1, SOL_LAYER_GAP = 2, SOL_LAYER_LINEAR = 3 } sol_layer_kind;
+typedef enum { SOL_LAYER_CONV = 0, SOL_LAYER_POOL = 1, SOL_LAYER_GAP = 2, SOL_LAYER_LINEAR = 3, SOL_LAYER_DWCONV = 4 } sol_layer_kind;
 
 /* sliding-window pooling; floor-mode output size; count_pad selects the average-pool divisor
  * (window area vs. number of in-range elements), the switch of the paper's pooling description
@@ -60,9 +60,9 @@ typedef struct { int cout, cin, kh, kw, sh, sw, ph, pw; } sol_conv_desc;
  * (src = -1: previous layer, or the network input for layer 0; res = -1: no residual) */
 typedef struct {
     int kind;               /* sol_layer_kind */
-    sol_conv_desc conv;     /* CONV: cin is inferred and may be 0 */
-    int has_bn;             /* CONV: batch-norm follows the convolution */
-    int act;                /* CONV, LINEAR: sol_act */
+    sol_conv_desc conv;     /* CONV, DWCONV: cin is inferred and may be 0 (DWCONV: cout too) */
+    int has_bn;             /* CONV, DWCONV: batch-norm follows the convolution */
+    int act;                /* CONV, DWCONV, LINEAR: sol_act */
     sol_pool_desc pool;     /* CONV: pool fused behind the activation (kind NONE = none); POOL: the pool */
     int out_features;       /* LINEAR */
     int src, res;
@@ -117,6 +117,25 @@ sol_status sol_conv2d_fused(const sol_tensor_desc *xd, const void *x, const sol_
                             const void *w_packed, const float *scale, const float *shift,
                             const void *residual, int act, const sol_pool_desc *pool, void *y,
                             int32_t *pool_argmax, void *prepool, void *hip_stream);
+
+/* Depthwise convolution: a grouped convolution with one group -- one kh x kw filter -- per channel, which the
+ * paper assigns to the fusion engine as a pooling layer with learned window weights (Sec. III-A) instead of
+ * to the contraction path:
+ *   y[n,p,q,c] = act( scale[c] * sum_{r,s} x[n, p*sh+r-ph, q*sw+s-pw, c] * w[c,r,s] + shift[c] + residual[n,p,q,c] )
+ * (taps outside the image contribute 0).
+ *   sol_packed_dw_weight_bytes   size of the packed weights: [kh*kw][c] in `dt`, rounded up to 16 bytes
+ *   sol_pack_dwconv_weights      w_c1hw: device fp32 [c][1][kh][kw] -> w_packed (device); bf16 rounds to nearest even
+ *   sol_dwconv2d_fused           xd, x: input NHWC; cd->cin and cd->cout must both equal xd->c; scale, shift: device
+ *                                fp32 [c] or NULL (1 / 0); residual: NULL or NHWC of the output shape and dtype;
+ *                                y: NHWC [n][Ho][Wo][c], same dtype as x, written by the call; no pool is fused.
+ * fp32 accumulation in row-major tap order for both dtypes.  All buffers are the caller's; errors as elsewhere
+ * (status code + sol_last_error), nothing is launched on an error. */
+size_t sol_packed_dw_weight_bytes(int c, int kh, int kw, sol_dtype dt);
+sol_status sol_pack_dwconv_weights(int c, int kh, int kw, sol_dtype dt, const float *w_c1hw, void *w_packed,
+                                   void *hip_stream);
+sol_status sol_dwconv2d_fused(const sol_tensor_desc *xd, const void *x, const sol_conv_desc *cd,
+                              const void *w_packed, const float *scale, const float *shift,
+                              const void *residual, int act, void *y, void *hip_stream);
 
 /* y[m][o] = act( bias[o] + sum_i x[m][i] * w[o][i] ).  x [m][in_f], y [m][out_f] in `dt`;
  * w: [out_f][in_f] packed as a 1x1 convolution weight (sol_pack_conv_weights with

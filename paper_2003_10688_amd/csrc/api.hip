@@ -121,6 +121,31 @@ static sol_status pool_impl(const sol_tensor_desc &xd, const void *x, const sol_
     return launch_pool(a, xd.dtype, st);
 }
 
+static size_t dw_weight_bytes(int c, int kh, int kw, int dt) { return round_up((size_t)c * kh * kw * dtype_size(dt), 16); }
+
+// Shared by sol_dwconv2d_fused and the network executor.
+static sol_status dwconv_impl(const sol_tensor_desc &xd, const void *x, const sol_conv_desc &cd, const void *w,
+                              const float *scale, const float *shift, const void *res, int act, void *y, hipStream_t st) {
+    SOL_REQUIRE(cd.cin == xd.c && cd.cout == xd.c, SOL_ERR_SHAPE, "depthwise conv: cin %d and cout %d must both equal the input channels %d",
+                cd.cin, cd.cout, xd.c);
+    SOL_REQUIRE(act == SOL_ACT_NONE || act == SOL_ACT_RELU, SOL_ERR_SHAPE, "bad activation %d", act);
+    SOL_REQUIRE(cd.kh * cd.kw <= 1024, SOL_ERR_UNSUPPORTED, "depthwise filter %dx%d too large", cd.kh, cd.kw);
+    const int Ho = out_size(xd.h, cd.kh, cd.sh, cd.ph), Wo = out_size(xd.w, cd.kw, cd.sw, cd.pw);
+    SOL_REQUIRE(xd.h + 2 * cd.ph >= cd.kh && xd.w + 2 * cd.pw >= cd.kw && Ho > 0 && Wo > 0, SOL_ERR_SHAPE,
+                "filter %dx%d larger than padded input %dx%d", cd.kh, cd.kw, xd.h + 2 * cd.ph, xd.w + 2 * cd.pw);
+    SOL_REQUIRE((double)xd.n * Ho * Wo * xd.c < 2147483648.0, SOL_ERR_UNSUPPORTED, "output has 2^31 elements or more");
+    if (xd.n == 0) return SOL_OK;
+    SOL_REQUIRE(x && w && y, SOL_ERR_NULL, "x, w_packed and y must not be NULL");
+    SOL_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(scale) && aligned16(shift) && aligned16(res),
+                SOL_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    DwArgs a;
+    a.x = x; a.w = w; a.res = res; a.scale = scale; a.shift = shift; a.y = y;
+    a.N = xd.n; a.H = xd.h; a.W = xd.w; a.C = xd.c; a.Ho = Ho; a.Wo = Wo;
+    a.kh = cd.kh; a.kw = cd.kw; a.sh = cd.sh; a.sw = cd.sw; a.ph = cd.ph; a.pw = cd.pw;
+    a.act = act;
+    return launch_dwconv(a, xd.dtype, st);
+}
+
 // ---- network ---------------------------------------------------------------------------------------
 struct LayerPlan {
     sol_layer L;
@@ -284,6 +309,31 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
                 }
                 break;
             }
+            case SOL_LAYER_DWCONV: {
+                SOL_REQUIRE(!net->training, SOL_ERR_UNSUPPORTED, "layer %d: depthwise convolutions are inference-only", i);
+                SOL_REQUIRE(L.conv.cout == 0 || L.conv.cout == lp.in.c, SOL_ERR_SHAPE,
+                            "layer %d: a depthwise convolution keeps the channel count (%d), cout is %d", i, lp.in.c, L.conv.cout);
+                SOL_REQUIRE(L.pool.kind == SOL_POOL_NONE, SOL_ERR_UNSUPPORTED,
+                            "layer %d: a pool behind a depthwise convolution is a layer of its own", i);
+                lp.cd = L.conv;
+                lp.cd.cin = lp.cd.cout = lp.in.c;
+                SOL_TRY(check_conv(&lp.cd));
+                SOL_REQUIRE(lp.in.h + 2 * lp.cd.ph >= lp.cd.kh && lp.in.w + 2 * lp.cd.pw >= lp.cd.kw, SOL_ERR_SHAPE,
+                            "layer %d: filter larger than padded input", i);
+                lp.conv_out = lp.in;
+                lp.conv_out.h = out_size(lp.in.h, lp.cd.kh, lp.cd.sh, lp.cd.ph);
+                lp.conv_out.w = out_size(lp.in.w, lp.cd.kw, lp.cd.sw, lp.cd.pw);
+                lp.out = lp.conv_out;
+                if (L.res >= 0) {
+                    SOL_REQUIRE(L.res < i, SOL_ERR_SHAPE, "layer %d: residual %d must name an earlier layer", i, L.res);
+                    const sol_tensor_desc &r = net->layers[L.res].out;
+                    SOL_REQUIRE(r.n == lp.out.n && r.h == lp.out.h && r.w == lp.out.w && r.c == lp.out.c, SOL_ERR_SHAPE,
+                                "layer %d: residual shape [%d,%d,%d,%d] != output [%d,%d,%d,%d]", i, r.n, r.h, r.w, r.c,
+                                lp.out.n, lp.out.h, lp.out.w, lp.out.c);
+                    lp.res = L.res;
+                }
+                break;
+            }
             case SOL_LAYER_POOL:
                 SOL_TRY(check_pool(&L.pool));
                 SOL_REQUIRE(lp.in.h + 2 * L.pool.ph >= L.pool.kh && lp.in.w + 2 * L.pool.pw >= L.pool.kw, SOL_ERR_SHAPE,
@@ -306,6 +356,11 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             default: SOL_FAIL(SOL_ERR_SHAPE, "layer %d: unknown kind %d", i, L.kind);
         }
         SOL_TRY(check_tensor(&lp.out, "layer output"));
+        if (L.kind == SOL_LAYER_DWCONV) {
+            lp.w_off = poff; poff += round_up(dw_weight_bytes(lp.cd.cout, lp.cd.kh, lp.cd.kw, dt), 256);
+            lp.scale_off = poff; poff += round_up((size_t)lp.cd.cout * 4, 256);
+            lp.shift_off = poff; poff += round_up((size_t)lp.cd.cout * 4, 256);
+        }
         if (L.kind == SOL_LAYER_CONV || L.kind == SOL_LAYER_LINEAR) {
             lp.w_off = poff; poff += round_up(sol_packed_weight_bytes(&lp.cd, (sol_dtype)dt), 256);
             lp.scale_off = poff; poff += round_up((size_t)lp.cd.cout * 4, 256);
@@ -405,6 +460,26 @@ sol_status sol_conv2d_fused(const sol_tensor_desc *xd, const void *x, const sol_
                            g_tile_override, (hipStream_t)stream);
 }
 
+size_t sol_packed_dw_weight_bytes(int c, int kh, int kw, sol_dtype dt) {
+    if (c <= 0 || kh <= 0 || kw <= 0) return 0;
+    return dw_weight_bytes(c, kh, kw, dt);
+}
+
+sol_status sol_pack_dwconv_weights(int c, int kh, int kw, sol_dtype dt, const float *w_c1hw, void *w_packed, void *stream) {
+    SOL_REQUIRE(c > 0 && kh > 0 && kw > 0 && (double)c * kh * kw < 1073741824.0, SOL_ERR_SHAPE, "bad depthwise weight shape c=%d k=%dx%d", c, kh, kw);
+    SOL_REQUIRE(dt == SOL_F32 || dt == SOL_BF16, SOL_ERR_DTYPE, "unknown dtype %d", (int)dt);
+    SOL_REQUIRE(w_c1hw && w_packed, SOL_ERR_NULL, "weight pointers must not be NULL");
+    SOL_REQUIRE(aligned16(w_c1hw) && aligned16(w_packed), SOL_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    return launch_pack_dw(c, kh * kw, dt, w_c1hw, w_packed, (hipStream_t)stream);
+}
+
+sol_status sol_dwconv2d_fused(const sol_tensor_desc *xd, const void *x, const sol_conv_desc *cd, const void *w_packed,
+                              const float *scale, const float *shift, const void *residual, int act, void *y, void *stream) {
+    SOL_TRY(check_tensor(xd, "x"));
+    SOL_TRY(check_conv(cd));
+    return dwconv_impl(*xd, x, *cd, w_packed, scale, shift, residual, act, y, (hipStream_t)stream);
+}
+
 sol_status sol_linear(int m, int in_f, int out_f, sol_dtype dt, const void *x, const void *w_packed, const float *bias,
                       int act, void *y, void *stream) {
     SOL_REQUIRE(m >= 0 && in_f > 0 && out_f > 0, SOL_ERR_SHAPE, "bad linear shape m=%d in=%d out=%d", m, in_f, out_f);
@@ -481,17 +556,21 @@ sol_status sol_network_set_params(sol_network *net, int layer, const float *w, c
     SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
     SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
     LayerPlan &lp = net->layers[layer];
-    SOL_REQUIRE(lp.L.kind == SOL_LAYER_CONV || lp.L.kind == SOL_LAYER_LINEAR, SOL_ERR_SHAPE, "layer %d has no parameters", layer);
+    const bool dwl = lp.L.kind == SOL_LAYER_DWCONV;
+    SOL_REQUIRE(lp.L.kind == SOL_LAYER_CONV || lp.L.kind == SOL_LAYER_LINEAR || dwl, SOL_ERR_SHAPE, "layer %d has no parameters", layer);
     SOL_REQUIRE(net->params, SOL_ERR_WORKSPACE, "no parameter buffer bound (sol_network_bind_params)");
     SOL_REQUIRE(w, SOL_ERR_NULL, "w is NULL");
-    const bool bn = lp.L.kind == SOL_LAYER_CONV && lp.L.has_bn;
+    const bool bn = (lp.L.kind == SOL_LAYER_CONV || dwl) && lp.L.has_bn;
     SOL_REQUIRE(!bn || (gamma && beta && (net->training || (mean && var))), SOL_ERR_NULL,
                 "layer %d has batch-norm: gamma, beta%s required", layer, net->training ? "" : ", mean, var");
     SOL_REQUIRE(bn || !(gamma || beta || mean || var), SOL_ERR_SHAPE, "layer %d has no batch-norm", layer);
     SOL_REQUIRE(aligned16(w) && aligned16(gamma) && aligned16(beta) && aligned16(mean) && aligned16(var) && aligned16(bias),
                 SOL_ERR_ALIGN, "device pointers must be 16-byte aligned");
     hipStream_t st = (hipStream_t)stream;
-    SOL_TRY(launch_pack(lp.cd, net->input.dtype, w, net->params + lp.w_off, false, st));
+    if (dwl)
+        SOL_TRY(launch_pack_dw(lp.cd.cout, lp.cd.kh * lp.cd.kw, net->input.dtype, w, net->params + lp.w_off, st));
+    else
+        SOL_TRY(launch_pack(lp.cd, net->input.dtype, w, net->params + lp.w_off, false, st));
     if (net->training) {   // fp32 master copies, zero velocities, both packed orientations
         const size_t wn = (size_t)lp.cd.cout * lp.cd.cin * lp.cd.kh * lp.cd.kw * 4, cb = (size_t)lp.cd.cout * 4;
         SOL_HIP(hipMemcpyAsync(net->params + lp.master_off, w, wn, hipMemcpyDeviceToDevice, st));
@@ -655,7 +734,7 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
     SOL_REQUIRE(first >= 0 && first <= last && last < nl, SOL_ERR_SHAPE, "bad layer range [%d,%d]", first, last);
     for (int i = first; i <= last; i++) {
         const LayerPlan &lp = net->layers[i];
-        if (lp.L.kind == SOL_LAYER_CONV || lp.L.kind == SOL_LAYER_LINEAR)
+        if (lp.L.kind == SOL_LAYER_CONV || lp.L.kind == SOL_LAYER_LINEAR || lp.L.kind == SOL_LAYER_DWCONV)
             SOL_REQUIRE(lp.params_set, SOL_ERR_WORKSPACE, "layer %d: parameters not set", i);
     }
     unsigned char *ws = static_cast<unsigned char *>(workspace);
@@ -683,6 +762,13 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
                 const float *shift = reinterpret_cast<const float *>(net->params + lp.shift_off);
                 SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, nullptr, shift, nullptr, lp.L.act, nullptr,
                                         out, nullptr, nullptr, g_tile_override ? g_tile_override : lp.tile, st));
+                break;
+            }
+            case SOL_LAYER_DWCONV: {
+                const float *scale = reinterpret_cast<const float *>(net->params + lp.scale_off);
+                const float *shift = reinterpret_cast<const float *>(net->params + lp.shift_off);
+                const void *res = lp.res >= 0 ? layer_in(net, lp.res, x, ws) : nullptr;
+                SOL_TRY(dwconv_impl(lp.in, in, lp.cd, net->params + lp.w_off, scale, shift, res, lp.L.act, out, st));
                 break;
             }
             case SOL_LAYER_POOL: SOL_TRY(pool_impl(lp.in, in, lp.L.pool, out, nullptr, st)); break;

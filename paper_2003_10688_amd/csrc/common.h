@@ -117,6 +117,15 @@ struct PoolArgs {
     int kind, count_pad;
 };
 
+struct DwArgs {              // depthwise convolution: one filter per channel, weights [kh*kw][C]
+    const void *x, *w, *res;
+    const float *scale, *shift;
+    void *y;
+    int N, H, W, C, Ho, Wo;
+    int kh, kw, sh, sw, ph, pw;
+    int act;
+};
+
 // Convolution tile ids (pixels x channels per workgroup); also accepted as a debugging override.
 // T_*: register-staged kernel (conv_igemm.hip).  D_*: LDS-DMA ring kernel (conv_dma.hip), suffix =
 // row bytes per stage x ring stages.
@@ -147,6 +156,8 @@ bool linear_kernel_applies(const ConvArgs &a, int dt);
 sol_status launch_linear(const ConvArgs &a, int dt, hipStream_t st);
 sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t st);
 sol_status launch_pool(const PoolArgs &a, int dt, hipStream_t st);
+sol_status launch_dwconv(const DwArgs &a, int dt, hipStream_t st);
+sol_status launch_pack_dw(int C, int taps, int dt, const float *w, void *packed, hipStream_t st);
 sol_status launch_gap(const void *x, void *y, int N, int HW, int C, int dt, hipStream_t st);
 sol_status launch_pack(const sol_conv_desc &cd, int dt, const float *w, void *packed, bool unpack, hipStream_t st);
 sol_status launch_fold(int c, const float *gamma, const float *beta, const float *mean, const float *var,

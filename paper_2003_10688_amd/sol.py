@@ -17,7 +17,7 @@ LIB_PATH = os.environ.get("SOL_MI355_LIB") or os.path.join(_HERE, "libsol_mi355.
 F32, BF16 = 0, 1
 ACT_NONE, ACT_RELU = 0, 1
 POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
-LAYER_CONV, LAYER_POOL, LAYER_GAP, LAYER_LINEAR = 0, 1, 2, 3
+LAYER_CONV, LAYER_POOL, LAYER_GAP, LAYER_LINEAR, LAYER_DWCONV = 0, 1, 2, 3, 4
 NET_TRAINING, NET_KEEP_ACTIVATIONS = 1, 2
 NT_W, NT_GAMMA, NT_BETA, NT_BIAS, NT_GRAD_W, NT_GRAD_GAMMA, NT_GRAD_BETA, NT_GRAD_BIAS, NT_MEAN, NT_VAR = range(10)
 
@@ -62,6 +62,8 @@ def lib():
         L.sol_version.restype = C.c_char_p
         L.sol_packed_weight_bytes.restype = C.c_size_t
         L.sol_packed_weight_bytes.argtypes = [C.POINTER(ConvDesc), C.c_int]
+        L.sol_packed_dw_weight_bytes.restype = C.c_size_t
+        L.sol_packed_dw_weight_bytes.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int]
         L.sol_network_param_bytes.restype = C.c_size_t
         L.sol_network_param_bytes.argtypes = [C.c_void_p]
         L.sol_network_workspace_bytes.restype = C.c_size_t
@@ -186,6 +188,25 @@ def sol_conv2d_fused(x, cd, w_packed, scale=None, shift=None, residual=None, act
     return y, arg, pre
 
 
+def sol_pack_dwconv_weights(c, kh, kw, dt, w_c1hw, stream=None):
+    """w_c1hw: device fp32 [c][1][kh][kw] -> packed device buffer (uint8 tensor)."""
+    packed = torch.empty(lib().sol_packed_dw_weight_bytes(c, kh, kw, dt), dtype=torch.uint8, device=w_c1hw.device)
+    _check(lib().sol_pack_dwconv_weights(C.c_int(c), C.c_int(kh), C.c_int(kw), C.c_int(dt), _ptr(w_c1hw), _ptr(packed),
+                                         _stream(stream)))
+    return packed
+
+
+def sol_dwconv2d_fused(x, cd, w_packed, scale=None, shift=None, residual=None, act=ACT_NONE, stream=None):
+    """x: NHWC device tensor; cd.cin == cd.cout == channels.  Returns y."""
+    n, h, w, c = x.shape
+    ho, wo = sol_out_size(h, cd.kh, cd.sh, cd.ph), sol_out_size(w, cd.kw, cd.sw, cd.pw)
+    y = torch.empty((n, max(ho, 0), max(wo, 0), c), dtype=x.dtype, device=x.device)
+    xd = tensor_desc(x)
+    _check(lib().sol_dwconv2d_fused(C.byref(xd), _ptr(x), C.byref(cd), _ptr(w_packed), _ptr(scale), _ptr(shift),
+                                    _ptr(residual), C.c_int(act), _ptr(y), _stream(stream)))
+    return y
+
+
 def sol_linear(x, w_packed, bias, out_f, act=ACT_NONE, stream=None):
     m, in_f = x.shape
     y = torch.empty((m, out_f), dtype=x.dtype, device=x.device)
@@ -226,7 +247,7 @@ def make_layer_array(layers):
         a.act = ACT_RELU if l.get("act") == "relu" else ACT_NONE
         a.pool = PoolDesc(POOL_NONE, 0, 0, 0, 0, 0, 0, 0)
         if l["kind"] == "conv":
-            a.kind = LAYER_CONV
+            a.kind = LAYER_DWCONV if l.get("dw") else LAYER_CONV
             a.conv = ConvDesc(l["cout"], 0, l["kh"], l["kw"], l["sh"], l["sw"], l["ph"], l["pw"])
             a.has_bn = int(l["bn"])
             if l.get("pool"):
@@ -267,7 +288,7 @@ class Network:
         return d
 
     def set_params(self, params, stream=None):
-        """params: per-layer dicts of numpy fp32 arrays in framework layout (w OIHW / [out][in])."""
+        """params: per-layer dicts of numpy fp32 arrays in framework layout (w OIHW, depthwise [c][1][kh][kw], linear [out][in])."""
         for i, (l, p) in enumerate(zip(self.layers, params)):
             if l["kind"] not in ("conv", "linear"):
                 continue

@@ -105,6 +105,22 @@ def mlp_layers(features, depth=3):
     return [linear(features, act="relu" if i + 1 < depth else "none") for i in range(depth)]
 
 
+def separable_layers(num_classes=1000, widths=((64, 1), (128, 2), (128, 1), (256, 2), (256, 1), (512, 2), (512, 1), (512, 1),
+                                                 (512, 1), (512, 1), (512, 1), (1024, 2), (1024, 1)), stem=32):
+    """Config 6: a depthwise-separable chain of the MobileNet kind the paper names for its depthwise rule
+    (Sec. III-A): 3x3 stride-2 stem, then per (width, stride) a depthwise 3x3 + BN + ReLU followed by a
+    pointwise 1x1 + BN + ReLU, global average pool, linear."""
+    L = [conv(stem, 3, s=2)]
+    c = stem
+    for width, stride in widths:
+        L.append(conv(c, 3, s=stride, dw=True))
+        L.append(conv(width, 1, p=0))
+        c = width
+    L.append(gap())
+    L.append(linear(num_classes))
+    return L
+
+
 def _stem():
     # conv 7x7 stride 2 pad 3 + BN + ReLU, then max-pool 3x3 stride 2 pad 1
     return [conv(64, 7, s=2, p=3), pool("max", 3, 2, 1)]
@@ -254,7 +270,7 @@ class Workload:
 
 
 def config(idx: int, batch: int | None = None, hw: int | None = None, dtype: str | None = None) -> Workload:
-    """The five configurations of the benchmark plus the paper's MLP workload (5); ``batch`` / ``hw`` shrink a config for parity tests and ``dtype``
+    """The five configurations of the benchmark plus the paper's MLP workload (5) and a depthwise-separable chain (6); ``batch`` / ``hw`` shrink a config for parity tests and ``dtype``
     overrides its storage type (same seed, same layer list)."""
     wk = _config(idx, batch, hw)
     if dtype is not None:
@@ -281,4 +297,6 @@ def _config(idx, batch, hw):
                         "bf16", seed, "normal", training=True, num_classes=1000)
     if idx == 5:   # hw = number of features here (the input is [batch, features, 1, 1])
         return Workload("mlp3_bf16", mlp_layers(hw or 8192), (batch or 64, hw or 8192, 1, 1), "bf16", seed, "normal")
+    if idx == 6:
+        return Workload("separable_bf16", separable_layers(), (batch or 64, 3, hw or 224, hw or 224), "bf16", seed, "normal")
     raise ValueError(idx)

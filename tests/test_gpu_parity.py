@@ -438,7 +438,7 @@ def test_network_forward_fp32_configs(sol, cfg, batch, hw):
     assert np.array_equal(y, y2)
 
 
-@pytest.mark.parametrize("cfg,batch,hw", [(2, 2, 64), (3, 2, 64), (3, 1, 224)])
+@pytest.mark.parametrize("cfg,batch,hw", [(2, 2, 64), (3, 2, 64), (3, 1, 224), (6, 3, 64), (6, 1, 224)])
 def test_network_forward_resnets_fp32_arithmetic(sol, cfg, batch, hw):
     """The ResNet-shaped layer lists in fp32 storage: no rounding points between layers, so the whole
     chain (planner wiring, residual edges, every kernel template) must agree to 1e-4 end to end."""
@@ -450,7 +450,7 @@ def test_network_forward_resnets_fp32_arithmetic(sol, cfg, batch, hw):
     assert max(errs) <= TOL["f32"], errs
 
 
-@pytest.mark.parametrize("cfg,batch,hw", [(2, 2, 64), (3, 2, 64), (3, 1, 224), (2, 1, 224)])
+@pytest.mark.parametrize("cfg,batch,hw", [(2, 2, 64), (3, 2, 64), (3, 1, 224), (2, 1, 224), (6, 3, 64), (6, 1, 224)])
 def test_network_forward_resnets_bf16(sol, cfg, batch, hw):
     """bf16 storage, fp32 accumulate.  Two passes over the same seeded tensors:
 
@@ -647,3 +647,122 @@ def test_mlp_workload(sol, batch, features):
         assert rel_err(g, outs[i]) <= TOL["bf16"], i
         if i < nl - 1:
             net.layer_output(i).copy_(dev[i])
+
+
+# ---- depthwise convolution (the fusion engine's weighted pooling) -----------------------------------------------
+def make_dw_block(rng, dt, N, C, H, W, k, sh, sw, p, bn=True, act="relu", res=False, bias_std=0.3):
+    l = dict(wl.conv(C, k, 1, p, bn=bn, act=act, dw=True), sh=sh, sw=sw)
+    x = _grid(rng.standard_normal((N, C, H, W)), dt)
+    prm = {"w": _grid(rng.standard_normal((C, 1, k, k)) * np.sqrt(2.0 / (k * k)), dt),
+           "bias": (rng.standard_normal(C) * bias_std).astype(np.float32)}
+    if bn:
+        prm.update(gamma=rng.uniform(0.5, 1.5, C).astype(np.float32), beta=rng.uniform(-0.1, 0.1, C).astype(np.float32),
+                   mean=(rng.standard_normal(C) * 0.1).astype(np.float32), var=rng.uniform(0.5, 1.5, C).astype(np.float32))
+    Ho, Wo = orc.out_size(H, k, sh, p), orc.out_size(W, k, sw, p)
+    r = _grid(rng.standard_normal((N, C, Ho, Wo)), dt) if res else None
+    return l, x, prm, r
+
+
+def run_dw_block(sol, dt, l, x, prm, r):
+    d = _dt(sol, dt)
+    C = x.shape[1]
+    cd = sol.ConvDesc(C, C, l["kh"], l["kw"], l["sh"], l["sw"], l["ph"], l["pw"])
+    wp = sol.sol_pack_dwconv_weights(C, l["kh"], l["kw"], d, sol.dev_f32(prm["w"]))
+    scale, shift = sol.sol_fold_bn(C, *(sol.dev_f32(prm[k]) if l["bn"] else None for k in ("gamma", "beta", "mean", "var")),
+                                   sol.dev_f32(prm["bias"]), 1e-5)
+    y = sol.sol_dwconv2d_fused(sol.to_device_nhwc(x, d), cd, wp, scale, shift,
+                               sol.to_device_nhwc(r, d) if r is not None else None,
+                               sol.ACT_RELU if l["act"] == "relu" else sol.ACT_NONE)
+    torch.cuda.synchronize()
+    return sol.to_host_nchw(y)
+
+
+DW_CASES = [
+    # N, C, H, W, k, sh, sw, p, res, bn, act     strip kernels (3x3, sw 1 / 2), ragged strips, tiles and channel groups
+    (2, 32, 19, 17, 3, 1, 1, 1, False, True, "relu"),
+    (3, 72, 14, 30, 3, 1, 1, 1, True, True, "relu"),
+    (2, 64, 23, 23, 3, 2, 2, 1, False, True, "relu"),
+    (1, 520, 9, 9, 3, 2, 2, 1, True, True, "none"),
+    (2, 24, 11, 37, 3, 2, 1, 1, False, False, "relu"),     # vertical stride only
+    (2, 16, 12, 9, 3, 1, 2, 0, False, True, "relu"),       # no padding, horizontal stride only
+    (1, 1024, 7, 7, 3, 1, 1, 1, False, True, "relu"),
+    (2, 8, 1, 1, 3, 1, 1, 1, False, True, "relu"),         # a single pixel: 8 of 9 taps are padding
+    (1, 16, 3, 2, 3, 1, 1, 1, True, False, "none"),        # narrower than one strip
+    (4, 128, 66, 70, 3, 1, 1, 1, False, True, "relu"),     # several tile rows and columns per image
+    # runtime-window kernel: other filters, channel counts that are no multiple of the vector width
+    (2, 40, 13, 15, 5, 1, 1, 2, True, True, "relu"),
+    (2, 16, 9, 10, 1, 1, 1, 0, False, True, "relu"),
+    (3, 13, 10, 11, 3, 1, 1, 1, True, True, "relu"),
+    (2, 6, 12, 12, 3, 2, 2, 1, False, False, "none"),
+    (1, 8, 16, 16, 7, 3, 3, 3, False, True, "relu"),
+]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("case", DW_CASES)
+def test_dwconv_fused_matches_oracle(sol, dt, case):
+    N, C, H, W, k, sh, sw, p, res, bn, act = case
+    rng = np.random.default_rng(hash(case) % (2 ** 31))
+    l, x, prm, r = make_dw_block(rng, dt, N, C, H, W, k, sh, sw, p, bn=bn, act=act, res=res)
+    want, _, _ = orc.fused_conv(x, prm, l, r, bf16=(dt == "bf16"))
+    got = run_dw_block(sol, dt, l, x, prm, r)
+    assert rel_err(got, want) <= TOL[dt]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("geom", [(3, 1, 1), (3, 2, 1), (5, 1, 2)])
+def test_dwconv_exact_integers(sol, dt, geom):
+    """Small integers are exact in bf16 and their sums in fp32: the result must equal the checker's bit for bit,
+    so a tap read from the wrong pixel or channel cannot hide inside a tolerance."""
+    k, s, p = geom
+    rng = np.random.default_rng(11)
+    N, C, H, W = 2, 48, 21, 18
+    l = wl.conv(C, k, s, p, bn=False, act="none", dw=True)
+    x = rng.integers(-4, 5, (N, C, H, W)).astype(np.float32)
+    prm = {"w": rng.integers(-3, 4, (C, 1, k, k)).astype(np.float32), "bias": rng.integers(-8, 9, C).astype(np.float32)}
+    want, _, _ = orc.fused_conv(x, prm, l, None, bf16=(dt == "bf16"))
+    got = run_dw_block(sol, dt, l, x, prm, None)
+    assert np.array_equal(got, want)
+
+
+def test_dwconv_empty_batch_and_errors(sol):
+    d = sol.BF16
+    wp = sol.sol_pack_dwconv_weights(16, 3, 3, d, torch.zeros((16, 1, 3, 3), device="cuda"))
+    cd = sol.ConvDesc(16, 16, 3, 3, 1, 1, 1, 1)
+    y = sol.sol_dwconv2d_fused(torch.empty((0, 8, 8, 16), dtype=torch.bfloat16, device="cuda"), cd, wp)
+    assert y.shape == (0, 8, 8, 16)
+    x = torch.zeros((1, 8, 8, 16), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sol.SolError):          # a depthwise convolution keeps the channel count
+        sol.sol_dwconv2d_fused(x, sol.ConvDesc(32, 16, 3, 3, 1, 1, 1, 1), wp)
+    with pytest.raises(sol.SolError):          # filter larger than the padded input
+        sol.sol_dwconv2d_fused(x, sol.ConvDesc(16, 16, 11, 11, 1, 1, 0, 0), wp)
+    with pytest.raises(sol.SolError):          # missing weights
+        sol.sol_dwconv2d_fused(x, cd, None)
+    with pytest.raises(sol.SolError):          # depthwise layers are inference-only
+        sol.Network([wl.conv(16, 3, dw=True), wl.gap(), wl.linear(4)], (2, 16, 8, 8), d, flags=sol.NET_TRAINING)
+    with pytest.raises(sol.SolError):          # channel count must be kept
+        sol.Network([wl.conv(24, 3, dw=True)], (2, 16, 8, 8), d)
+
+
+def test_full_size_depthwise_layers(sol):
+    """Every distinct depthwise geometry of the separable chain at the full benchmark batch, in the launch
+    configuration the planner uses, against the checker's full output (the checker's plain loops finish a
+    layer in seconds: there is no reduction over channels)."""
+    wk = wl.config(6)
+    ch, hw, seen = wk.in_shape[1], wk.in_shape[2], set()
+    rng = np.random.default_rng(wk.seed)
+    for i, l in enumerate(wk.layers):
+        if l["kind"] != "conv":
+            break
+        key = (ch, hw, l["sh"])
+        if l.get("dw") and key not in seen:
+            seen.add(key)
+            x = wl.to_bf16_grid(rng.standard_normal((wk.in_shape[0], ch, hw, hw), dtype=np.float32))
+            want, _, _ = orc.fused_conv(x, wk.params[i], l, None, bf16=True)
+            got = run_dw_block(sol, "bf16", l, x, wk.params[i], None)
+            err = rel_err(got, want)
+            print(f"  L{i} C{ch} {hw}x{hw} s{l['sh']}: rel err {err:.3e}", flush=True)
+            assert err <= TOL["bf16"], (i, key, err)
+            del x, want, got
+        ch, hw = l["cout"], orc.out_size(hw, l["kh"], l["sh"], l["ph"])
+    assert len(seen) == 9
