@@ -50,6 +50,9 @@ def layer_shapes(layers, in_shape, out_size):
 def algorithmic_work(l, x, y, esize):
     """(flops, bytes) the layer must perform/move: read input, weights and residual once, write output once."""
     numel = lambda s: s[0] * s[1] * s[2] * s[3]  # noqa: E731
+    if l["kind"] == "conv" and l.get("dw"):     # one filter per channel: no reduction over channels
+        taps = l["kh"] * l["kw"]
+        return 2.0 * numel(y) * taps, esize * (numel(x) + taps * y[1] + numel(y) * (2 if l["res"] >= 0 else 1)) + 8 * y[1]
     if l["kind"] == "conv":
         k = l["kh"] * l["kw"] * x[1]
         flops = 2.0 * y[0] * y[2] * y[3] * y[1] * k
@@ -65,7 +68,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=3, help="workload: 3 = ResNet-50-shaped bs64 (default), 2 = ResNet-18-shaped bs32, 5 = 3-layer MLP with 8192 features bs64")
+    ap.add_argument("--config", type=int, default=3, help="workload: 3 = ResNet-50-shaped bs64 (default), 2 = ResNet-18-shaped bs32, 5 = 3-layer MLP with 8192 features bs64, 6 = depthwise-separable chain bs64")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--layer-reps", type=int, default=20, help="event-timed repetitions per layer for the roofline")
     ap.add_argument("--cpu-sample", type=int, default=8, help="images the CPU checker is timed on (0 = skip)")
@@ -152,9 +155,10 @@ def main():
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) * 1e3 / a.layer_reps
         fl, by = algorithmic_work(l, ins[i], outs[i], esize)
-        rows.append({"i": i, "kind": l["kind"], "us": us, "flops": fl, "bytes": by})
+        rows.append({"i": i, "kind": "dwconv" if l.get("dw") else l["kind"], "us": us, "flops": fl, "bytes": by})
     conv = [r for r in rows if r["kind"] == "conv"]
     mem = [r for r in rows if r["kind"] in ("pool", "gap")]
+    dwr = [r for r in rows if r["kind"] == "dwconv"]
     if conv:
         conv_us = sum(r["us"] for r in conv)
         conv_fl = sum(r["flops"] for r in conv)
@@ -176,6 +180,7 @@ def main():
             "mfma_bound_layers": grp(mf, "tflops", PEAK_BF16_TFLOPS, 1e6),
             "hbm_bound_layers": grp(hb, "gbs", PEAK_HBM_GBS, 1e3),
             "pool_gap_kernels": grp(mem, "gbs", PEAK_HBM_GBS, 1e3),
+            "depthwise_kernels": grp(dwr, "gbs", PEAK_HBM_GBS, 1e3) if dwr else None,
             "conv_algorithmic_gb_per_step": round(conv_by / 1e9, 3),
             "sum_layer_us": round(sum(r["us"] for r in rows), 1),
         }

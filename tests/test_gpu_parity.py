@@ -688,7 +688,10 @@ DW_CASES = [
     (1, 1024, 7, 7, 3, 1, 1, 1, False, True, "relu"),
     (2, 8, 1, 1, 3, 1, 1, 1, False, True, "relu"),         # a single pixel: 8 of 9 taps are padding
     (1, 16, 3, 2, 3, 1, 1, 1, True, False, "none"),        # narrower than one strip
-    (4, 128, 66, 70, 3, 1, 1, 1, False, True, "relu"),     # several tile rows and columns per image
+    (4, 128, 66, 70, 3, 1, 1, 1, False, True, "relu"),     # several row chunks per image, a short last chunk
+    (2, 12, 31, 9, 3, 1, 1, 1, True, True, "relu"),        # three channel quads, ragged strip
+    (3, 20, 29, 30, 3, 2, 2, 1, True, True, "relu"),
+    (2, 64, 8, 8, 3, 2, 2, 0, False, True, "none"),        # stride 2 without padding: the last input row / column is unused
     # runtime-window kernel: other filters, channel counts that are no multiple of the vector width
     (2, 40, 13, 15, 5, 1, 1, 2, True, True, "relu"),
     (2, 16, 9, 10, 1, 1, 1, 0, False, True, "relu"),
@@ -707,6 +710,18 @@ def test_dwconv_fused_matches_oracle(sol, dt, case):
     want, _, _ = orc.fused_conv(x, prm, l, r, bf16=(dt == "bf16"))
     got = run_dw_block(sol, dt, l, x, prm, r)
     assert rel_err(got, want) <= TOL[dt]
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_dwconv_long_row_walks(sol, stride):
+    """Enough columns of work that every thread walks the maximum of 16 output rows (and a 1-row last chunk)."""
+    rng = np.random.default_rng(5 + stride)
+    H = 33 if stride == 1 else 65
+    l, x, prm, r = make_dw_block(rng, "bf16", 64, 512, H, 64 * stride, 3, stride, stride, 1)
+    want, _, _ = orc.fused_conv(x, prm, l, r, bf16=True)
+    got = run_dw_block(sol, "bf16", l, x, prm, r)
+    assert got.shape == (64, 512, 33, 64)
+    assert rel_err(got, want) <= TOL["bf16"]
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
