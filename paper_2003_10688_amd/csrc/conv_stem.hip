@@ -1,4 +1,6 @@
-// Fused 7x7 / stride-2 / pad-3 convolution for 3-channel inputs (the ResNet-shaped stem), bf16.
+// Fused stride-2 convolutions over 3-channel inputs (network stems: 7x7 pad 3 of the ResNet-shaped lists, 3x3 of
+// the depthwise-separable chain), bf16.  The text below describes the 7x7 case; a 3x3 filter pads each filter
+// row to 16 reduction elements instead of 32.
 //
 // With Cin = 3 the reduction index (r, s, c) has no 16-byte-contiguous runs in NHWC, so the generic
 // implicit GEMM has to gather single elements.  Here a workgroup instead stages the input patch of
@@ -26,24 +28,29 @@ struct StemRows {   // tile row (py*16+px) of the 8x16 output block -> output pi
 };
 
 constexpr int STEM_TH = 8, STEM_TW = 16;
-constexpr int STEM_IH = 2 * STEM_TH + 5, STEM_IW = 2 * STEM_TW + 6;   // patch extent (+1 zero column)
-constexpr int STEM_WROW = 232;                                         // padded weight row (bank spread)
 
+// R x S filter, NC blocks of 32 output channels
+template <int R, int S, int NC>
 __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int tiles_h, int tiles_w, int ntiles) {
-    __shared__ __align__(16) bf16_t wl[64 * STEM_WROW];                 // 29.0 KB
+    constexpr int KROW = S * 4 <= 16 ? 16 : 32;                          // reduction elements per filter row (S x 4, padded)
+    constexpr int STEM_IH = 2 * (STEM_TH - 1) + R;                       // patch extent ...
+    constexpr int STEM_IW = 2 * STEM_TW + KROW / 4 - 2;                  // ... incl. the zero columns the row padding reads
+    constexpr int COLS = 2 * (STEM_TW - 1) + S;                          // columns that hold image data
+    constexpr int STEM_WROW = R * KROW + 8;                              // padded weight row (bank spread)
+    __shared__ __align__(16) bf16_t wl[NC * 32 * STEM_WROW];            // 7x7, 64 channels: 29.0 KB
     __shared__ __align__(16) bf16_t xl[STEM_IH * STEM_IW * 4];          //  6.4 KB
-    __shared__ __align__(16) float strip[4 * 32 * 68];                  // 34.0 KB epilogue transposer
+    __shared__ __align__(16) float strip[4 * 32 * (NC * 32 + 4)];       // 34.0 KB epilogue transposer
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bf16_t *__restrict__ xg = static_cast<const bf16_t *>(a.x);
     const bf16_t *__restrict__ wg = static_cast<const bf16_t *>(a.w);
 
-    // weights: packed [k][(r*7+s)*3+c] -> LDS [k][r*32 + s*4 + c], zero elsewhere
-    for (int i = tid; i < 64 * STEM_WROW; i += 256) {
+    // weights: packed [k][(r*S+s)*3+c] -> LDS [k][r*KROW + s*4 + c], zero elsewhere
+    for (int i = tid; i < NC * 32 * STEM_WROW; i += 256) {
         const int k = i / STEM_WROW, kk = i % STEM_WROW;
-        const int r = kk >> 5, s = (kk & 31) >> 2, c = kk & 3;
+        const int r = kk / KROW, s = (kk % KROW) >> 2, c = kk & 3;
         bf16_t v = 0;
-        if (kk < 224 && s < 7 && c < 3 && k < a.Cout) v = wg[k * a.Kp + (r * 7 + s) * 3 + c];
+        if (kk < R * KROW && s < S && c < 3 && k < a.Cout) v = wg[k * a.Kp + (r * S + s) * 3 + c];
         wl[i] = v;
     }
     for (int i = tid; i < STEM_IH * STEM_IW * 4; i += 256) xl[i] = 0;   // incl. the never-written pad column
@@ -51,11 +58,11 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
     const int lr = lane & 31, lh = lane >> 5;
     const int py = 2 * wave + (lr >> 4), px = lr & 15;                   // this lane's output pixel in the block
     const unsigned xbase = ((2 * py) * STEM_IW + 2 * px) * 8;            // its patch origin, bytes
-    f32x16_t acc[2][1];
-    const Affine8 aff = load_affine<2>(a, lane, 0);
+    f32x16_t acc[NC][1];
+    const Affine8 aff = load_affine<NC>(a, lane, 0);
 
-    // Input patch of a tile: (2*TH+5) x (2*TW+5) pixels, 3 channels each, NP pixels per thread.
-    constexpr int NPIX = STEM_IH * (STEM_IW - 1), NP = (NPIX + 255) / 256;
+    // Input patch of a tile: STEM_IH x COLS pixels, 3 channels each, NP pixels per thread.
+    constexpr int NPIX = STEM_IH * COLS, NP = (NPIX + 255) / 256;
     uint2 pv[NP];
     auto load_patch = [&](int tile) {             // global -> registers (issued one tile ahead)
         const int tw = tile % tiles_w, t2 = tile / tiles_w;
@@ -63,8 +70,8 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
 #pragma unroll
         for (int i = 0; i < NP; i++) {
             const int e = tid + i * 256;
-            const int ih = e / (STEM_IW - 1), iw = e % (STEM_IW - 1);
-            const int gh = 2 * th * STEM_TH - 3 + ih, gw = 2 * tw * STEM_TW - 3 + iw;
+            const int ih = e / COLS, iw = e % COLS;
+            const int gh = 2 * th * STEM_TH - a.ph + ih, gw = 2 * tw * STEM_TW - a.pw + iw;
             pv[i] = make_uint2(0, 0);
             if (e < NPIX && (unsigned)gh < (unsigned)a.H && (unsigned)gw < (unsigned)a.W) {
                 const bf16_t *p = xg + (((long)n * a.H + gh) * a.W + gw) * 3;
@@ -78,7 +85,7 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
         for (int i = 0; i < NP; i++) {
             const int e = tid + i * 256;
             if (e < NPIX) {
-                const int ih = e / (STEM_IW - 1), iw = e % (STEM_IW - 1);
+                const int ih = e / COLS, iw = e % COLS;
                 *reinterpret_cast<uint2 *>(&xl[(ih * STEM_IW + iw) * 4]) = pv[i];
             }
         }
@@ -94,37 +101,38 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
         __syncthreads();
         if (tile + (int)gridDim.x < ntiles) load_patch(tile + gridDim.x);   // in flight under the MFMAs and the epilogue
 #pragma unroll
-        for (int i = 0; i < 2; i++)
+        for (int i = 0; i < NC; i++)
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[i][0][e] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 14; ks++) {
-            const int r = ks >> 1, s0 = (ks & 1) * 4 + lh * 2;           // 8 elements = pixels s0, s0+1 of row r
+        for (int ks = 0; ks < R * KROW / 16; ks++) {
+            const int r = ks / (KROW / 16), s0 = (ks % (KROW / 16)) * 4 + lh * 2;   // 8 elements = pixels s0, s0+1 of row r
             const uint4 fb = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(xl) + xbase +
                                                              (r * STEM_IW + s0) * 8);
 #pragma unroll
-            for (int i = 0; i < 2; i++) {
+            for (int i = 0; i < NC; i++) {
                 const uint4 fa = *reinterpret_cast<const uint4 *>(&wl[(i * 32 + lr) * STEM_WROW + ks * 16 + lh * 8]);
                 Mma<bf16_t>::run(acc[i][0], fa, fb);
             }
         }
         const StemRows rows{n, p0, q0, a.Ho, a.Wo};
-        ResidualRegs<bf16_t, 1, 2> resregs;
+        ResidualRegs<bf16_t, 1, NC> resregs;
         resregs.on = false;
-        // blocks inside the image with the usual 64 channels and no residual: branch-free epilogue
-        if (p0 + STEM_TH <= a.Ho && q0 + STEM_TW <= a.Wo && a.Cout == 64 && a.res == nullptr) {
+        // blocks inside the image with all NC * 32 channels and no residual: branch-free epilogue
+        if (p0 + STEM_TH <= a.Ho && q0 + STEM_TW <= a.Wo && a.Cout == NC * 32 && a.res == nullptr) {
             const int pw = p0 + 2 * wave;     // first output row of this wave's 32 tile rows
-            const StemRowOffset ro{(unsigned)(((n * a.Ho + pw) * a.Wo + q0) * 64), (unsigned)a.Wo, 64u};
-            conv_epilogue_interior<bf16_t, 1, 2, false>(a, acc, strip, wave, lane, 0, aff, resregs, ro);
+            const StemRowOffset ro{(unsigned)(((n * a.Ho + pw) * a.Wo + q0) * (NC * 32)), (unsigned)a.Wo, (unsigned)(NC * 32)};
+            conv_epilogue_interior<bf16_t, 1, NC, false>(a, acc, strip, wave, lane, 0, aff, resregs, ro);
         } else {
-            prefetch_residual<bf16_t, 1, 2>(a, lane, wave * 32, 0, rows, resregs);
-            conv_epilogue<bf16_t, 1, 2>(a, acc, strip, wave, lane, wave * 32, 0, aff, rows, resregs);
+            prefetch_residual<bf16_t, 1, NC>(a, lane, wave * 32, 0, rows, resregs);
+            conv_epilogue<bf16_t, 1, NC>(a, acc, strip, wave, lane, wave * 32, 0, aff, rows, resregs);
         }
     }
 }
 
 bool stem_kernel_applies(const ConvArgs &a, int dt) {
-    return dt == SOL_BF16 && a.C == 3 && a.R == 7 && a.S == 7 && a.sh == 2 && a.sw == 2 && a.ph == 3 && a.pw == 3 &&
+    const bool k7 = a.R == 7 && a.S == 7, k3 = a.R == 3 && a.S == 3;
+    return dt == SOL_BF16 && a.C == 3 && (k7 || k3) && a.sh == 2 && a.sw == 2 && a.ph >= 0 && a.ph < a.R && a.pw >= 0 && a.pw < a.S &&
            a.Cout <= 64 && a.pool == 0;
 }
 
@@ -132,7 +140,14 @@ sol_status launch_conv_stem(const ConvArgs &a, hipStream_t st) {
     const int tiles_h = ceil_div(a.Ho, STEM_TH), tiles_w = ceil_div(a.Wo, STEM_TW);
     const int ntiles = a.N * tiles_h * tiles_w;
     const int grid = ntiles < 512 ? ntiles : 512;                        // 2 persistent workgroups per CU
-    hipLaunchKernelGGL(conv_stem_kernel, dim3(grid), dim3(256), 0, st, a, tiles_h, tiles_w, ntiles);
+    if (a.R == 7 && a.Cout > 32)
+        hipLaunchKernelGGL((conv_stem_kernel<7, 7, 2>), dim3(grid), dim3(256), 0, st, a, tiles_h, tiles_w, ntiles);
+    else if (a.R == 7)
+        hipLaunchKernelGGL((conv_stem_kernel<7, 7, 1>), dim3(grid), dim3(256), 0, st, a, tiles_h, tiles_w, ntiles);
+    else if (a.Cout > 32)
+        hipLaunchKernelGGL((conv_stem_kernel<3, 3, 2>), dim3(grid), dim3(256), 0, st, a, tiles_h, tiles_w, ntiles);
+    else
+        hipLaunchKernelGGL((conv_stem_kernel<3, 3, 1>), dim3(grid), dim3(256), 0, st, a, tiles_h, tiles_w, ntiles);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }

@@ -78,6 +78,10 @@ CONV_CASES = [
     (2, 64, 23, 23, 64, 3, 2, 1, False),
     (1, 256, 9, 9, 520, 1, 2, 0, False),
     (2, 3, 37, 35, 64, 7, 2, 3, False),     # stem-like: Cin = 3 -> element gather path
+    (2, 3, 37, 35, 32, 3, 2, 1, False),     # 3x3 stem of the separable chain (bf16: stem kernel, one 32-channel block)
+    (1, 3, 64, 48, 64, 3, 2, 1, True),
+    (2, 3, 20, 21, 24, 3, 2, 0, False),
+    (2, 3, 33, 40, 24, 7, 2, 3, False),
     (5, 3, 16, 16, 16, 3, 1, 1, False),
     (1, 24, 11, 11, 40, 3, 1, 1, True),     # Cin not a multiple of the 128-byte chunk -> gather path
     (2, 32, 12, 12, 32, 5, 1, 2, False),
