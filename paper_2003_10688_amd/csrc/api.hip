@@ -162,6 +162,7 @@ struct LayerPlan {
     // training networks only
     size_t wT_off, master_off, vel_off, grad_off, vec_off;   // parameter buffer: flipped pack, fp32 master / velocity / gradient, per-channel arrays
     size_t z_off, dact_off, arg_off;                          // workspace: conv output before BN, gradient of the output, pool winners
+    size_t wpart_off;                                         // workspace: split partials of this layer's weight gradient
     bool has_grad, need_dgrad, src_first, res_first, dilate;
     sol_conv_desc dcd;                                        // data-gradient as a stride-1 convolution ...
     sol_tensor_desc dzd;                                      // ... over dz (zero-inserted when the forward stride is > 1)
@@ -246,6 +247,7 @@ static sol_status plan_training(sol_network *net, Arena &ar) {
             dz_max = std::max(dz_max, tensor_bytes(lp.conv_out));
             int ns; size_t pf;
             wgrad_plan(lp.in, lp.cd, lp.conv_out.h, lp.conv_out.w, &ns, &pf);
+            lp.wpart_off = ar.alloc(pf * 4);       // kept until the end of the backward pass: all layers' partials are added by one launch
             const int rows = lp.conv_out.n * lp.conv_out.h * lp.conv_out.w;
             part_max = std::max(part_max, std::max(pf * 4, (size_t)col_reduce_chunks(rows, nullptr) * 2 * lp.cd.cout * 4));
             if (lp.dilate) dil_max = std::max(dil_max, tensor_bytes(lp.dzd));
@@ -656,6 +658,14 @@ static sol_status train_backward(sol_network *net, const void *x, const int32_t 
     if (ll.out.n == 0) return SOL_OK;
     SOL_TRY(launch_softmax_ce(ws + ll.out_off, labels, ws + ll.dact_off, row_loss + 1, loss ? loss : row_loss, ll.out.n,
                               ll.out.c, dt, st));
+    // every layer's weight-gradient partials stay in its own workspace region; one launch at the end adds them all
+    WgradReduceBatch wred;
+    wred.nseg = 0; wred.first_block[0] = 0;
+    auto flush_wred = [&]() -> sol_status {
+        const sol_status r = launch_wgrad_reduce_batch(wred, st);
+        wred.nseg = 0; wred.first_block[0] = 0;
+        return r;
+    };
     for (int i = nl - 1; i >= 0; i--) {
         const LayerPlan &lp = net->layers[i];
         if (!lp.has_grad) continue;
@@ -689,8 +699,21 @@ static sol_status train_backward(sol_network *net, const void *x, const int32_t 
                     SOL_TRY(launch_grad_col_sums(nullptr, dz, nullptr, nullptr, nullptr, rows, C, 0, dt,
                                                  vec_ptr(net, lp, VEC_G_BIAS), nullptr, part, st));
                 }
-                SOL_TRY(launch_wgrad(lp.in, in, lp.cd, dz, lp.conv_out.h, lp.conv_out.w,
-                                     reinterpret_cast<float *>(net->params + lp.grad_off), part, st));
+                float *dwp = reinterpret_cast<float *>(net->params + lp.grad_off);
+                if (rows > 0 && lp.cd.cin * lp.cd.kh * lp.cd.kw <= WRED_MAX_PLANE) {
+                    int ns = 0;
+                    float *wpart = reinterpret_cast<float *>(ws + lp.wpart_off);
+                    SOL_TRY(launch_wgrad(lp.in, in, lp.cd, dz, lp.conv_out.h, lp.conv_out.w, dwp, wpart, st, &ns));
+                    if (ns > 0) {
+                        if (wred.nseg == WRED_MAX_SEG) SOL_TRY(flush_wred());
+                        const int j = wred.nseg++;
+                        wred.part[j] = wpart; wred.dw[j] = dwp; wred.nsplit[j] = ns;
+                        wred.K[j] = lp.cd.cout; wred.C[j] = lp.cd.cin; wred.RS[j] = lp.cd.kh * lp.cd.kw;
+                        wred.first_block[j + 1] = wred.first_block[j] + lp.cd.cout;
+                    }
+                } else {
+                    SOL_TRY(launch_wgrad(lp.in, in, lp.cd, dz, lp.conv_out.h, lp.conv_out.w, dwp, part, st));
+                }
                 if (lp.need_dgrad) {
                     const void *g = dz;
                     if (lp.dilate) {
@@ -720,7 +743,7 @@ static sol_status train_backward(sol_network *net, const void *x, const int32_t 
                 break;
         }
     }
-    return SOL_OK;
+    return flush_wred();
 }
 
 static sol_status run_layers(sol_network *net, const void *x, void *y, void *workspace, size_t workspace_bytes,

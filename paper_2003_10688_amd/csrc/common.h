@@ -205,7 +205,20 @@ sol_status launch_sgd_batch(const SgdBatch &b, float lr, float mu, hipStream_t s
 sol_status launch_pack_batch(const PackBatch &b, int dt, hipStream_t st);
 sol_status launch_pack_flip(const sol_conv_desc &cd, int dt, const float *w, void *packed, hipStream_t st);
 void wgrad_plan(const sol_tensor_desc &xd, const sol_conv_desc &cd, int Ho, int Wo, int *nsplit, size_t *part_floats);
+// deferred_nsplit != NULL: only the first stage runs (split partials into `part`) and the number of splits is
+// returned; the caller adds the partials of many layers in one launch_wgrad_reduce_batch
 sol_status launch_wgrad(const sol_tensor_desc &xd, const void *x, const sol_conv_desc &cd, const void *dz, int Ho, int Wo,
-                        float *dw, float *part, hipStream_t st);
+                        float *dw, float *part, hipStream_t st, int *deferred_nsplit = nullptr);
+// Second stage of the weight gradients of up to WRED_MAX_SEG layers in one launch: one workgroup per output channel
+// of a layer adds that channel's split partials in split order and writes dW in framework layout.
+constexpr int WRED_MAX_SEG = 64, WRED_MAX_PLANE = 12288;   // floats of one output channel's [taps][cin] plane held in LDS
+struct WgradReduceBatch {
+    int nseg;
+    int first_block[WRED_MAX_SEG + 1];
+    const float *part[WRED_MAX_SEG];
+    float *dw[WRED_MAX_SEG];
+    int nsplit[WRED_MAX_SEG], K[WRED_MAX_SEG], C[WRED_MAX_SEG], RS[WRED_MAX_SEG];
+};
+sol_status launch_wgrad_reduce_batch(const WgradReduceBatch &b, hipStream_t st);
 
 }  // namespace sol

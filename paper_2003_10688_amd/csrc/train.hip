@@ -118,6 +118,115 @@ __global__ void __launch_bounds__(256) col_reduce_vec_kernel(const T *__restrict
     }
 }
 
+// Batch statistics in one trip over z: every block reduces its chunk of rows twice -- first to the chunk's sum,
+// then (the chunk is a few tens of KB and still in the caches) to the chunk's sum of squared deviations from its
+// own mean -- and col_merge_stats_kernel combines the chunks with the pairwise-update formula
+//   M2 = sum_k M2_k + n_k (mean_k - mean)^2,
+// which is as well conditioned as the two-pass definition but needs neither a second trip over HBM nor the
+// two extra launches of a mean pass followed by a variance pass.
+// part[chunk][0][c] = chunk mean, part[chunk][1][c] = chunk M2.
+template <typename T, int V>
+__global__ void __launch_bounds__(256) col_stats_vec_kernel(const T *__restrict__ a, float *__restrict__ part, int rows, int C, int rpc) {
+    constexpr int CG = 64 / V, PH = 256 / CG;
+    const int cg = threadIdx.x % CG, ph = threadIdx.x / CG;
+    const int c0 = blockIdx.y * 64 + cg * V;
+    const int r0 = blockIdx.x * rpc, r1 = min(rows, r0 + rpc);
+    const bool cok = c0 < C;
+    __shared__ float red[PH][64 + 1];
+    __shared__ float cmean[64];
+    float s[V], m[V];
+    auto reduce_rows = [&](bool second) {
+#pragma unroll
+        for (int e = 0; e < V; e++) s[e] = 0.f;
+        if (cok) {
+            auto one_row = [&](int r) {
+                float va[V];
+                VecIO<T, V>::load(a + (size_t)r * C + c0, va);
+#pragma unroll
+                for (int e = 0; e < V; e++) {
+                    const float d = va[e] - m[e];          // m = 0 in the first pass
+                    s[e] += second ? d * d : d;
+                }
+            };
+            int r = r0 + ph;
+            for (; r + PH < r1; r += 2 * PH) { one_row(r); one_row(r + PH); }
+            if (r < r1) one_row(r);
+        }
+#pragma unroll
+        for (int e = 0; e < V; e++) red[ph][cg * V + e] = s[e];
+        __syncthreads();
+    };
+#pragma unroll
+    for (int e = 0; e < V; e++) m[e] = 0.f;
+    reduce_rows(false);
+    const int tx = threadIdx.x, c = blockIdx.y * 64 + tx;
+    float csum = 0.f;
+    if (tx < 64) {
+#pragma unroll
+        for (int p = 0; p < PH; p++) csum += red[p][tx];
+        cmean[tx] = csum / (float)(r1 - r0);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < V; e++) m[e] = cmean[cg * V + e];
+    reduce_rows(true);
+    if (tx < 64 && c < C) {
+        float m2 = 0.f;
+#pragma unroll
+        for (int p = 0; p < PH; p++) m2 += red[p][tx];
+        part[((size_t)blockIdx.x * 2 + 0) * C + c] = cmean[tx];
+        part[((size_t)blockIdx.x * 2 + 1) * C + c] = m2;
+    }
+}
+
+// mean / biased variance / 1/sqrt(var + eps) from the chunk means and chunk M2 of col_stats_vec_kernel; chunk k holds
+// min(rpc, rows - k*rpc) rows.  64 channels x 16 chunk phases: phase p folds chunks p, p+16, ... into a running
+// (count, mean, M2) triple with the pairwise update (one pass over the partials, four chunks' loads in flight),
+// then one thread per channel folds the 16 phases in order.  The order depends on nothing but nchunks.
+struct RunStats {
+    float n, mean, m2;
+    __device__ __forceinline__ void fold(float nk, float meank, float m2k) {
+        const float nn = n + nk, d = meank - mean, f = nk / nn;     // nn > 0: nk >= 1 for every real chunk
+        mean += d * f;
+        m2 += m2k + d * d * n * f;
+        n = nn;
+    }
+};
+__global__ void __launch_bounds__(1024) col_merge_stats_kernel(const float *__restrict__ part, int nchunks, int C, int rows, int rpc,
+                                                               float eps, float *__restrict__ mean, float *__restrict__ var,
+                                                               float *__restrict__ inv) {
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + tx;
+    __shared__ float red[3][16][64];
+    RunStats rs{0.f, 0.f, 0.f};
+    if (c < C) {
+        int k = ty;
+        for (; k + 48 < nchunks; k += 64) {
+            float mk[4], qk[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                mk[u] = part[((size_t)(k + 16 * u) * 2 + 0) * C + c];
+                qk[u] = part[((size_t)(k + 16 * u) * 2 + 1) * C + c];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) rs.fold((float)min(rpc, rows - (k + 16 * u) * rpc), mk[u], qk[u]);
+        }
+        for (; k < nchunks; k += 16)
+            rs.fold((float)min(rpc, rows - k * rpc), part[((size_t)k * 2 + 0) * C + c], part[((size_t)k * 2 + 1) * C + c]);
+    }
+    red[0][ty][tx] = rs.n; red[1][ty][tx] = rs.mean; red[2][ty][tx] = rs.m2;
+    __syncthreads();
+    if (ty != 0 || c >= C) return;
+    RunStats t{0.f, 0.f, 0.f};
+#pragma unroll
+    for (int p = 0; p < 16; p++)
+        if (red[0][p][tx] > 0.f) t.fold(red[0][p][tx], red[1][p][tx], red[2][p][tx]);
+    const float v = t.m2 / (float)rows;
+    mean[c] = t.mean;
+    var[c] = v;
+    inv[c] = 1.f / sqrtf(v + eps);
+}
+
 // out0[c] = scale * sum_chunks part[chunk][0][c]; out1 likewise; with eps >= 0 also
 // inv[c] = 1 / sqrt(out0[c] + eps)   (out0 = biased variance then)
 __global__ void __launch_bounds__(1024) col_finalize_kernel(const float *__restrict__ part, int nchunks, int C, float scale,
@@ -904,6 +1013,73 @@ __global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float *__restri
     }
 }
 
+// The same sum for many layers at once.  A workgroup (1024 threads) owns one output channel ko of one layer.  Its
+// [taps][cin] plane has n floats in each of nsplit partials; small planes come with many splits (the 7x7 stem:
+// 147 floats x 256 splits), so the threads form PH phases x U units (a unit = 4 floats when n % 4 == 0, else 1):
+// phase p adds splits p, p+PH, ... (four loads in flight), the phases are added in order through LDS, and the plane
+// is written transposed to [cin][taps] -- contiguous in dW -- so both sides of the transposition are coalesced.
+// The order of every sum depends on the layer's shape only.
+__global__ void __launch_bounds__(1024) wgrad_reduce_batch_kernel(const WgradReduceBatch b) {
+    __shared__ __align__(16) float plane[WRED_MAX_PLANE];
+    int seg = 0;
+    while (seg + 1 < b.nseg && (int)blockIdx.x >= b.first_block[seg + 1]) seg++;
+    const int ko = (int)blockIdx.x - b.first_block[seg];
+    const int C = b.C[seg], RS = b.RS[seg], n = C * RS, nsplit = b.nsplit[seg];
+    const size_t total = (size_t)b.K[seg] * n;
+    const float *__restrict__ src = b.part[seg] + (size_t)ko * n;
+    const bool vec = (n & 3) == 0;
+    const int units = vec ? n >> 2 : n, upad = (units + 63) & ~63;
+    const int PH = max(1, min(min(1024 / upad, WRED_MAX_PLANE / n), nsplit));
+    const int ustride = upad * PH <= 1024 ? upad : 1024;     // PH == 1: all threads walk the units
+    const int ph = PH > 1 ? (int)threadIdx.x / upad : 0;
+    if (ph < PH) {
+        for (int u = PH > 1 ? (int)threadIdx.x - ph * upad : (int)threadIdx.x; u < units; u += ustride) {
+            if (vec) {
+                float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+                int k = ph;
+                for (; k + 3 * PH < nsplit; k += 4 * PH) {
+                    float4 v[4];
+#pragma unroll
+                    for (int j = 0; j < 4; j++) v[j] = *reinterpret_cast<const float4 *>(src + (size_t)(k + j * PH) * total + 4 * u);
+#pragma unroll
+                    for (int j = 0; j < 4; j++) { s.x += v[j].x; s.y += v[j].y; s.z += v[j].z; s.w += v[j].w; }
+                }
+                for (; k < nsplit; k += PH) {
+                    const float4 v = *reinterpret_cast<const float4 *>(src + (size_t)k * total + 4 * u);
+                    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+                }
+                *reinterpret_cast<float4 *>(plane + ph * n + 4 * u) = s;
+            } else {
+                float s = 0.f;
+                int k = ph;
+                for (; k + 3 * PH < nsplit; k += 4 * PH) {
+                    float v[4];
+#pragma unroll
+                    for (int j = 0; j < 4; j++) v[j] = src[(size_t)(k + j * PH) * total + u];
+                    s = (((s + v[0]) + v[1]) + v[2]) + v[3];
+                }
+                for (; k < nsplit; k += PH) s += src[(size_t)k * total + u];
+                plane[ph * n + u] = s;
+            }
+        }
+    }
+    __syncthreads();
+    float *__restrict__ dst = b.dw[seg] + (size_t)ko * n;
+    for (int o = threadIdx.x; o < n; o += 1024) {      // o = c * RS + tap
+        const int c = o / RS, tap = o - c * RS;
+        float s = 0.f;
+        for (int p = 0; p < PH; p++) s += plane[p * n + tap * C + c];
+        dst[o] = s;
+    }
+}
+
+sol_status launch_wgrad_reduce_batch(const WgradReduceBatch &b, hipStream_t st) {
+    if (b.nseg <= 0 || b.first_block[b.nseg] <= 0) return SOL_OK;
+    hipLaunchKernelGGL(wgrad_reduce_batch_kernel, dim3(b.first_block[b.nseg]), dim3(1024), 0, st, b);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
 // ---- launchers ---------------------------------------------------------------------------------------------
 static inline int grid_for(long n) { return (int)std::min<long>((n + 255) / 256, 8192); }
 
@@ -932,6 +1108,15 @@ sol_status launch_bn_stats(const void *z, int rows, int C, int dt, float eps, fl
     const int nch = col_reduce_chunks(rows, &rpc);
     const dim3 grid(nch, ceil_div(C, 64));
     const int fg = ceil_div(C, 64);
+    if ((dt == SOL_BF16 && C % 8 == 0) || (dt != SOL_BF16 && C % 4 == 0)) {     // one trip over z, two launches
+        if (dt == SOL_BF16)
+            hipLaunchKernelGGL((col_stats_vec_kernel<bf16_t, 8>), grid, dim3(256), 0, st, static_cast<const bf16_t *>(z), part, rows, C, rpc);
+        else
+            hipLaunchKernelGGL((col_stats_vec_kernel<float, 4>), grid, dim3(256), 0, st, static_cast<const float *>(z), part, rows, C, rpc);
+        hipLaunchKernelGGL(col_merge_stats_kernel, dim3(fg), dim3(1024), 0, st, part, nch, C, rows, rpc, eps, mean, var, invstd);
+        SOL_HIP(hipGetLastError());
+        return SOL_OK;
+    }
     if (dt == SOL_BF16) {
         const bf16_t *p = static_cast<const bf16_t *>(z);
         if (C % 8 == 0) hipLaunchKernelGGL((col_reduce_vec_kernel<bf16_t, 8, 0>), grid, dim3(256), 0, st, p, p, p, nullptr, nullptr, part, rows, C, rpc, 0);
@@ -1128,7 +1313,7 @@ void wgrad_plan(const sol_tensor_desc &xd, const sol_conv_desc &cd, int Ho, int 
 
 // dw: fp32 [cout][cin][kh][kw]; part: scratch of wgrad_plan's size
 sol_status launch_wgrad(const sol_tensor_desc &xd, const void *x, const sol_conv_desc &cd, const void *dz, int Ho, int Wo,
-                        float *dw, float *part, hipStream_t st) {
+                        float *dw, float *part, hipStream_t st, int *deferred_nsplit) {
     WgradArgs a;
     memset(static_cast<void *>(&a), 0, sizeof(a));
     const int ES = (int)dtype_size(xd.dtype), GP = 16 / ES;
@@ -1145,8 +1330,10 @@ sol_status launch_wgrad(const sol_tensor_desc &xd, const void *x, const sol_conv
         if (ntiles > 0) {
             hipLaunchKernelGGL(wgrad_stem_kernel, dim3(a.nsplit), dim3(256), 0, st, a, tiles_h, tiles_w, ntiles);
             const long total = (long)cd.cout * 147;
-            hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for(total)), dim3(256), 0, st, part, a.nsplit, dw, cd.cout, cd.cin, 49);
+            if (!deferred_nsplit)
+                hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for(total)), dim3(256), 0, st, part, a.nsplit, dw, cd.cout, cd.cin, 49);
         }
+        if (deferred_nsplit) *deferred_nsplit = ntiles > 0 ? a.nsplit : 0;
         SOL_HIP(hipGetLastError());
         return SOL_OK;
     }
@@ -1168,8 +1355,11 @@ sol_status launch_wgrad(const sol_tensor_desc &xd, const void *x, const sol_conv
     else
         hipLaunchKernelGGL((wgrad_kernel<float>), dim3(grid), dim3(256), 0, st, a);
     const long total = (long)cd.cout * cd.kh * cd.kw * cd.cin;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for(total)), dim3(256), 0, st, part, a.nsplit, dw, cd.cout, cd.cin,
-                       cd.kh * cd.kw);
+    if (deferred_nsplit)
+        *deferred_nsplit = a.nsplit;
+    else
+        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for(total)), dim3(256), 0, st, part, a.nsplit, dw, cd.cout, cd.cin,
+                           cd.kh * cd.kw);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }
