@@ -997,7 +997,7 @@ sol_status sol_network_sgd_step(sol_network *net, float lr, float momentum, void
         const int i = pb.nseg++;
         pb.w[i] = w; pb.out[i] = out; pb.K[i] = cd.cout; pb.C[i] = cd.cin; pb.R[i] = cd.kh; pb.S[i] = cd.kw; pb.Kp[i] = Kp;
         pb.flip[i] = flip ? 1 : 0;
-        pb.first_block[i + 1] = pb.first_block[i] + (int)((total + PACK_ELEMS_PER_BLOCK - 1) / PACK_ELEMS_PER_BLOCK);
+        pb.first_block[i + 1] = pb.first_block[i] + pack_segment_blocks(cd.cout, cd.cin, cd.kh, cd.kw, Kp, pb.flip[i], &pb.mode[i]);
         return SOL_OK;
     };
     for (const auto &lp : net->layers) {

@@ -199,7 +199,10 @@ struct PackBatch {
     const float *w[PACK_MAX_SEG];          // fp32 master, framework layout [K][C][R][S]
     void *out[PACK_MAX_SEG];
     int K[PACK_MAX_SEG], C[PACK_MAX_SEG], R[PACK_MAX_SEG], S[PACK_MAX_SEG], Kp[PACK_MAX_SEG], flip[PACK_MAX_SEG];
+    int mode[PACK_MAX_SEG];                // how the segment's blocks are cut, set by pack_segment_blocks
 };
+// number of workgroups a segment takes in pack_batch_kernel (and the block-cutting mode, written to *mode)
+int pack_segment_blocks(int K, int C, int R, int S, int Kp, int flip, int *mode);
 constexpr int SGD_ELEMS_PER_BLOCK = 256 * 8, PACK_ELEMS_PER_BLOCK = 256 * 8;
 sol_status launch_sgd_batch(const SgdBatch &b, float lr, float mu, hipStream_t st);
 sol_status launch_pack_batch(const PackBatch &b, int dt, hipStream_t st);

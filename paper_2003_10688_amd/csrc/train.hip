@@ -520,15 +520,51 @@ __global__ void __launch_bounds__(256) sgd_batch_kernel(const SgdBatch b, float 
 
 // All packed weight buffers of a network (forward order and, for the data gradient, flipped / transposed) rebuilt
 // from the fp32 masters in one launch; same element maps as pack_weights_kernel / pack_weights_flip_kernel.
+// Both maps transpose the channel axis against the filter taps, so a segment is cut into blocks whose reads AND
+// writes are contiguous runs, with the transposition done in LDS:
+//   mode 1 (forward pack): one block per output channel k; its [C][taps] plane is one contiguous run of the
+//          master and becomes the contiguous packed row [taps][C] (+ zero padding);
+//   mode 2 (flipped pack, C % 8 == 0, K % 64 == 0): one block per 8 input channels x KT output channels; the master
+//          is read in runs of 8 x taps floats (one per k), the packed rows are written in runs of KT elements;
+//   mode 0: any other shape, one gathered element per thread.
+constexpr int PACK_PLANE = 9216;                   // floats of LDS per block
 template <typename T>
 __global__ void __launch_bounds__(256) pack_batch_kernel(const PackBatch b) {
+    __shared__ float tile[PACK_PLANE + 128];
     int seg = 0;
     while (seg + 1 < b.nseg && (int)blockIdx.x >= b.first_block[seg + 1]) seg++;
     const float *__restrict__ w = b.w[seg];
     T *__restrict__ out = static_cast<T *>(b.out[seg]);
-    const int K = b.K[seg], C = b.C[seg], R = b.R[seg], S = b.S[seg], Kp = b.Kp[seg], flip = b.flip[seg];
+    const int K = b.K[seg], C = b.C[seg], R = b.R[seg], S = b.S[seg], Kp = b.Kp[seg], flip = b.flip[seg], mode = b.mode[seg];
+    const int blk = (int)blockIdx.x - b.first_block[seg], RS = R * S;
+    if (mode == 1) {
+        const int n = C * RS;
+        const float *src = w + (size_t)blk * n;
+        for (int i = threadIdx.x; i < n; i += 256) tile[i] = src[i];              // i = c * RS + tap
+        __syncthreads();
+        T *dst = out + (size_t)blk * Kp;
+        for (int j = threadIdx.x; j < Kp; j += 256) {                               // j = tap * C + c
+            const int tap = j / C, c = j - tap * C;
+            Elem<T>::store(dst + j, j < n ? tile[c * RS + tap] : 0.f);
+        }
+        return;
+    }
+    if (mode == 2) {
+        const int KT = K % 128 == 0 ? 128 : 64, nkb = K / KT, run = 8 * RS, pitch = run + 1;
+        const int cb = blk / nkb, kb = blk - cb * nkb, c0 = cb * 8, k0 = kb * KT;
+        for (int i = threadIdx.x; i < KT * run; i += 256) {
+            const int kk = i / run, rem = i - kk * run;                             // rem = cc * RS + tap
+            tile[kk * pitch + rem] = w[((size_t)(k0 + kk) * C + c0) * RS + rem];
+        }
+        __syncthreads();
+        for (int o = threadIdx.x; o < KT * run; o += 256) {
+            const int kk = o % KT, t2 = o / KT, tap = t2 % RS, cc = t2 / RS;        // tap: position in the flipped filter
+            Elem<T>::store(out + (size_t)(c0 + cc) * Kp + (size_t)tap * K + k0 + kk, tile[kk * pitch + cc * RS + (RS - 1 - tap)]);
+        }
+        return;
+    }
     const long total = (long)(flip ? C : K) * Kp;
-    const long i0 = (long)((int)blockIdx.x - b.first_block[seg]) * PACK_ELEMS_PER_BLOCK;
+    const long i0 = (long)blk * PACK_ELEMS_PER_BLOCK;
 #pragma unroll
     for (int u = 0; u < PACK_ELEMS_PER_BLOCK / 256; u++) {
         const long i = i0 + u * 256 + threadIdx.x;
@@ -548,6 +584,18 @@ __global__ void __launch_bounds__(256) pack_batch_kernel(const PackBatch b) {
         }
         Elem<T>::store(out + i, v);
     }
+}
+
+int pack_segment_blocks(int K, int C, int R, int S, int Kp, int flip, int *mode) {
+    const int RS = R * S;
+    if (!flip && (long)C * RS <= PACK_PLANE) { *mode = 1; return K; }
+    if (flip && C % 8 == 0 && K % 64 == 0 && (K % 128 == 0 ? 128 : 64) * (8 * RS + 1) <= PACK_PLANE + 128 && Kp == RS * K) {
+        *mode = 2;
+        return (C / 8) * (K / (K % 128 == 0 ? 128 : 64));
+    }
+    *mode = 0;
+    const long total = (long)(flip ? C : K) * Kp;
+    return (int)((total + PACK_ELEMS_PER_BLOCK - 1) / PACK_ELEMS_PER_BLOCK);
 }
 
 // Weights for the data-gradient: framework layout w[k][c][r][s] -> packed rows [c][((R-1-r)*S + (S-1-s))*K + k],
