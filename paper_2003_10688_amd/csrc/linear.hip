@@ -31,13 +31,13 @@ __global__ void __launch_bounds__(512) linear_kernel(const ConvArgs a) {
 #pragma unroll
     for (int e = 0; e < 16; e++) acc[e] = 0.f;
 
-    const int nsteps = K / (2 * EPC);              // one step = 2*EPC reduction elements (both lane halves)
+    const int nsteps = (K + 2 * EPC - 1) / (2 * EPC);   // one step = 2*EPC reduction elements (both lane halves); K % EPC == 0
     for (int s0 = wave * UN; s0 < nsteps; s0 += NWV * UN) {
         uint4 fa[UN], fb[UN];
 #pragma unroll
         for (int u = 0; u < UN; u++) {
             const int k = (s0 + u) * 2 * EPC;
-            const bool ok = s0 + u < nsteps;
+            const bool ok = k + lh * EPC < K;          // also false for steps past the end; a ragged last step feeds zeros to the upper lanes
             fa[u] = (ok && wok) ? *reinterpret_cast<const uint4 *>(wp + k) : zero;
             fb[u] = (ok && xok) ? *reinterpret_cast<const uint4 *>(xp + k) : zero;
         }
@@ -71,10 +71,10 @@ __global__ void __launch_bounds__(512) linear_kernel(const ConvArgs a) {
     }
 }
 
-// 1x1 "convolution" over a [rows,1,1,C] tensor with few rows, reduction a whole number of MFMA steps
+// 1x1 "convolution" over a [rows,1,1,C] tensor with few rows, rows a whole number of 16-byte fragments
 bool linear_kernel_applies(const ConvArgs &a, int dt) {
-    const int step = 2 * (16 / (int)dtype_size(dt));
-    return a.R == 1 && a.S == 1 && a.H == 1 && a.W == 1 && a.pool == 0 && a.P <= 1024 && a.C % step == 0;
+    const int frag = 16 / (int)dtype_size(dt);     // a fragment is 16 bytes of one row: rows must be whole fragments
+    return a.R == 1 && a.S == 1 && a.H == 1 && a.W == 1 && a.pool == 0 && a.P <= 1024 && a.C % frag == 0;
 }
 
 sol_status launch_linear(const ConvArgs &a, int dt, hipStream_t st) {

@@ -340,7 +340,7 @@ def test_global_avgpool(sol, dt, shape):
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("shape", [(64, 2048, 1000), (64, 64, 10), (5, 100, 33), (1, 7, 3), (130, 512, 1000), (200, 96, 40),
-                                   (1100, 64, 8)])
+                                   (1100, 64, 8), (32, 1000, 512), (9, 24, 16)])     # the last two: rows end in half an MFMA step
 def test_linear(sol, dt, shape):
     M, I, O = shape
     rng = np.random.default_rng(29)
