@@ -219,6 +219,8 @@ def main():
         tnet.set_params(tw.params)
         tx = sol.to_device_nhwc(tw.x, sol.BF16)
         lab = torch.from_numpy(tw.labels).to("cuda:0")
+        if a.tune_reps > 0:      # plan time, not timed: per-layer tiles for the forward and data-gradient convolutions
+            tnet.autotune(tx, reps=a.tune_reps, stream=stream)
 
         def train_step():
             tnet.forward(tx, stream)

@@ -193,7 +193,10 @@ sol_status sol_network_forward(sol_network *net, const void *x, void *y, void *w
  * more than 3 % faster).  Runs whole passes over x / workspace / y (their contents are overwritten with valid
  * activations), synchronises with the stream, allocates nothing on the device.  Every candidate computes the same
  * layer within the library's tolerance; the accumulation order, hence the last bits, may differ between candidates.
- * Inference networks only.  sol_network_layer_tile reports the chosen id (0 = heuristic). */
+ * Training networks (SOL_NET_TRAINING): every convolution layer gets one choice for its forward convolution and
+ * one for its data-gradient convolution, used by later sol_network_forward / sol_network_backward calls; the timed
+ * launches overwrite activations and gradient buffers, so run a forward pass before the next backward.
+ * sol_network_layer_tile reports the id chosen for the forward convolution (0 = heuristic). */
 sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *workspace,
                                 size_t workspace_bytes, int reps, void *hip_stream);
 sol_status sol_network_layer_tile(const sol_network *net, int layer, int *tile);

@@ -159,6 +159,7 @@ struct LayerPlan {
     int last_use;
     bool params_set;
     int tile;                       // CONV / LINEAR: kernel + tile id chosen by sol_network_autotune (T_AUTO: shape heuristic)
+    int tile_dgrad;                 // training: the same for the data-gradient convolution
     // training networks only
     size_t wT_off, master_off, vel_off, grad_off, vec_off;   // parameter buffer: flipped pack, fp32 master / velocity / gradient, per-channel arrays
     size_t z_off, dact_off, arg_off;                          // workspace: conv output before BN, gradient of the output, pool winners
@@ -183,6 +184,7 @@ struct sol_network {
     unsigned char *params;
     size_t params_size;
     size_t dz_off, dil_off, part_off, loss_off;   // training: shared scratch inside the workspace
+    size_t dz_bytes, dil_bytes;
 };
 
 namespace sol {
@@ -258,6 +260,7 @@ static sol_status plan_training(sol_network *net, Arena &ar) {
     }
     net->dz_off = ar.alloc(dz_max);
     net->dil_off = ar.alloc(dil_max);
+    net->dz_bytes = dz_max; net->dil_bytes = dil_max;
     net->part_off = ar.alloc(part_max);
     net->loss_off = ar.alloc(((size_t)net->input.n + 1) * 4);
     return SOL_OK;
@@ -524,7 +527,7 @@ sol_status sol_network_create(const sol_layer *layers, int n_layers, const sol_t
     net->params_size = 0;
     sol_status s = plan_network(net, layers, n_layers);
     if (s != SOL_OK) { delete net; return s; }
-    for (auto &lp : net->layers) lp.tile = T_AUTO;
+    for (auto &lp : net->layers) lp.tile = lp.tile_dgrad = T_AUTO;
     *out = net;
     return SOL_OK;
 }
@@ -603,6 +606,28 @@ static const void *layer_in(const sol_network *net, int idx, const void *x, cons
 }
 
 // ---- training passes -----------------------------------------------------------------------------------
+// The convolution launch of a training forward (BN layers store the bare convolution z) and of a training backward
+// (data gradient into the producer's gradient buffer); shared by the passes and by the auto-tuner.
+static sol_status train_conv_fwd(const sol_network *net, const LayerPlan &lp, const void *x, unsigned char *ws, int tile,
+                                 hipStream_t st) {
+    const void *in = layer_in(net, lp.src, x, ws);
+    const bool bn = lp.L.kind == SOL_LAYER_CONV && lp.L.has_bn;
+    const float *bias = vec_ptr(net, lp, VEC_BIAS);
+    if (bn)
+        return conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, nullptr, bias, nullptr, SOL_ACT_NONE, nullptr, ws + lp.z_off,
+                               nullptr, nullptr, tile, st);
+    const void *res = lp.res >= 0 ? layer_in(net, lp.res, x, ws) : nullptr;
+    return conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, nullptr, bias, res, lp.L.act, nullptr, ws + lp.out_off, nullptr,
+                           nullptr, tile, st);
+}
+
+static sol_status train_conv_dgrad(const sol_network *net, const LayerPlan &lp, const void *g, unsigned char *ws, int tile,
+                                   hipStream_t st) {
+    void *dsrc = ws + net->layers[lp.src].dact_off;
+    return conv_fused_impl(lp.dzd, g, lp.dcd, net->params + lp.wT_off, nullptr, nullptr, lp.src_first ? nullptr : dsrc, SOL_ACT_NONE,
+                           nullptr, dsrc, nullptr, nullptr, tile, st);
+}
+
 // Forward with batch statistics: conv -> z (stored), statistics of the stored z, then BN + residual + act
 // in one elementwise pass.  Every output stays in the workspace for the backward pass.
 static sol_status train_forward(sol_network *net, const void *x, void *y, unsigned char *ws, hipStream_t st) {
@@ -617,15 +642,9 @@ static sol_status train_forward(sol_network *net, const void *x, void *y, unsign
             case SOL_LAYER_LINEAR: {
                 const bool bn = lp.L.kind == SOL_LAYER_CONV && lp.L.has_bn;
                 const void *res = lp.res >= 0 ? layer_in(net, lp.res, x, ws) : nullptr;
-                const float *bias = vec_ptr(net, lp, VEC_BIAS);
-                if (!bn) {
-                    SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, nullptr, bias, res, lp.L.act, nullptr, out,
-                                            nullptr, nullptr, g_tile_override, st));
-                    break;
-                }
+                SOL_TRY(train_conv_fwd(net, lp, x, ws, g_tile_override ? g_tile_override : lp.tile, st));
+                if (!bn) break;
                 void *z = ws + lp.z_off;
-                SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, nullptr, bias, nullptr, SOL_ACT_NONE, nullptr, z,
-                                        nullptr, nullptr, g_tile_override, st));
                 const int rows = lp.conv_out.n * lp.conv_out.h * lp.conv_out.w, C = lp.cd.cout;
                 if (rows == 0) break;
                 SOL_TRY(launch_bn_stats(z, rows, C, dt, lp.eps, vec_ptr(net, lp, VEC_MEAN), vec_ptr(net, lp, VEC_VAR),
@@ -721,9 +740,7 @@ static sol_status train_backward(sol_network *net, const void *x, const int32_t 
                                               lp.dzd.w, lp.cd.sh, lp.cd.sw, dt, st));
                         g = ws + net->dil_off;
                     }
-                    SOL_TRY(conv_fused_impl(lp.dzd, g, lp.dcd, net->params + lp.wT_off, nullptr, nullptr,
-                                            lp.src_first ? nullptr : dsrc, SOL_ACT_NONE, nullptr, dsrc, nullptr, nullptr,
-                                            g_tile_override, st));
+                    SOL_TRY(train_conv_dgrad(net, lp, g, ws, g_tile_override ? g_tile_override : lp.tile_dgrad, st));
                 }
                 break;
             }
@@ -814,14 +831,75 @@ static const int kTuneCandidates[] = {
     D_128x128_64x4, D_128x128_64x3, D_256x128_64x3, D_128x64_64x4, D_64x64_64x4, D_128x256_64x3, D_256x64_64x3, D_64x128_64x4,
     D_128x128_128x2, D_128x128_128x3, D_128x64_128x3, D_64x64_128x3, D_128x128_64x5, D_64x64_128x4, D_256x128_128x3,
     D_256x128_64x4, D_128x256_64x4, D_64x64_64x8,
-    H_256x128_x5, H_128x128_x3, H_256x64_x5, H_256x64_x6s, H_256x64_x6s2, H_128x128_k2, H_64x128_k4, H_128x64_k4,
+    H_256x128_x5, H_128x128_x3, H_256x64_x5, H_256x64_x6s, H_256x64_x6s2, H_128x128_k2, H_64x128_k4, H_128x64_k4, H_64x64_k4,
     G_128x128_k2, G_256x128, G_128x256, G_64x128_k4, G_128x64_k4, G_256x256_r64, G_256x128_r64, G_64x64_k4, G_64x64_k4_deep};
+
+// Training networks: the forward convolution of every layer and its data-gradient convolution get a tile each.
+// A candidate is timed right behind another convolution of similar size that evicts its weights from L2 (the
+// producer's forward convolution; for the data gradient the layer's own forward convolution), as it runs in a step.
+// The timed launches overwrite activations and gradients: a forward pass must follow before the next backward.
+static sol_status autotune_training(sol_network *net, const void *x, void *y, void *workspace, size_t workspace_bytes, int reps,
+                                    hipStream_t st) {
+    const int nl = (int)net->layers.size();
+    for (auto &lp : net->layers) lp.tile = lp.tile_dgrad = T_AUTO;
+    SOL_TRY(run_layers(net, x, y, workspace, workspace_bytes, 0, nl - 1, st));   // validates; fills every activation
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    SOL_HIP(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); SOL_FAIL(SOL_ERR_HIP, "hipEventCreate failed"); }
+    sol_status rs = SOL_OK;
+    // dg: time layer i's data gradient (else its forward convolution) with tile `tile`
+    auto time_conv = [&](int i, bool dg, int tile, float *ms) -> sol_status {
+        const LayerPlan &lp = net->layers[i];
+        const int before = dg ? i : lp.src;
+        const bool conv_before = before >= 0 && (net->layers[before].L.kind == SOL_LAYER_CONV);
+        const void *g = ws + (lp.dilate ? net->dil_off : net->dz_off);
+        float total = 0.f;
+        for (int r = 0; r < reps + 1; r++) {
+            if (conv_before) SOL_TRY(train_conv_fwd(net, net->layers[before], x, ws, net->layers[before].tile, st));
+            SOL_HIP(hipEventRecord(e0, st));
+            SOL_TRY(dg ? train_conv_dgrad(net, lp, g, ws, tile, st) : train_conv_fwd(net, lp, x, ws, tile, st));
+            SOL_HIP(hipEventRecord(e1, st));
+            SOL_HIP(hipEventSynchronize(e1));
+            float t = 0.f;
+            SOL_HIP(hipEventElapsedTime(&t, e0, e1));
+            if (r > 0) total += t;
+        }
+        *ms = total;
+        return SOL_OK;
+    };
+    // the gradient operands are whatever the workspace holds: make them finite numbers first
+    if (net->dz_bytes) SOL_HIP(hipMemsetAsync(ws + net->dz_off, 0, net->dz_bytes, st));
+    if (net->dil_bytes) SOL_HIP(hipMemsetAsync(ws + net->dil_off, 0, net->dil_bytes, st));
+    for (int i = 0; i < nl && rs == SOL_OK; i++) {
+        LayerPlan &lp = net->layers[i];
+        if (lp.L.kind != SOL_LAYER_CONV || lp.in.n == 0) continue;
+        for (int dg = 0; dg < 2 && rs == SOL_OK; dg++) {
+            if (dg && !(lp.has_grad && lp.need_dgrad)) continue;
+            float best = 0.f;
+            rs = time_conv(i, dg, T_AUTO, &best);
+            if (rs != SOL_OK) break;
+            int best_tile = T_AUTO;
+            for (int cand : kTuneCandidates) {
+                float ms = 0.f;
+                const sol_status cs = time_conv(i, dg, cand, &ms);
+                if (cs == SOL_ERR_HIP) { rs = cs; break; }
+                if (cs == SOL_OK && ms < 0.97f * best) { best = ms; best_tile = cand; }
+            }
+            (dg ? lp.tile_dgrad : lp.tile) = best_tile;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rs != SOL_OK) for (auto &lp : net->layers) lp.tile = lp.tile_dgrad = T_AUTO;
+    return rs;
+}
 
 sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *workspace, size_t workspace_bytes, int reps,
                                 void *stream) {
     SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
-    SOL_REQUIRE(!net->training, SOL_ERR_UNSUPPORTED, "auto-tune covers inference networks");
     SOL_REQUIRE(reps >= 1 && reps <= 1000, SOL_ERR_SHAPE, "reps %d out of range [1,1000]", reps);
+    if (net->training) return autotune_training(net, x, y, workspace, workspace_bytes, reps, (hipStream_t)stream);
     hipStream_t st = (hipStream_t)stream;
     const int nl = (int)net->layers.size();
     for (auto &lp : net->layers) lp.tile = T_AUTO;

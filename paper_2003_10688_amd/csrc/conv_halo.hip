@@ -341,6 +341,7 @@ sol_status launch_conv_halo(const ConvArgs &a, int tile, hipStream_t st) {
         case H_128x128_k2: return launch_halo_cfg<bf16_t, 2, 2, 2, 2, 2, 3, 4, 2>(a, st);
         case H_64x128_k4: return launch_halo_cfg<bf16_t, 1, 2, 4, 2, 2, 2, 5, 2>(a, st);
         case H_128x64_k4: return launch_halo_cfg<bf16_t, 2, 1, 4, 2, 2, 3, 8, 2>(a, st);
+        case H_64x64_k4: return launch_halo_cfg<bf16_t, 1, 1, 4, 2, 2, 4, 5, 2>(a, st);   // four waves, 75 KB: two workgroups per CU
         default: SOL_FAIL(SOL_ERR_UNSUPPORTED, "unknown halo conv tile id %d", tile);
     }
 }

@@ -151,7 +151,7 @@ HALO_CASES = [
 ]
 
 
-@pytest.mark.parametrize("tile", [41, 42, 43, 46, 47, 48])
+@pytest.mark.parametrize("tile", [41, 42, 43, 46, 47, 48, 49])
 @pytest.mark.parametrize("case", HALO_CASES)
 def test_halo_conv_tiles(sol, tile, case):
     """The 3x3 halo-in-LDS kernel in each of its tile shapes against the checker, every output element."""

@@ -47,12 +47,14 @@ def norm_err(g, r):
     return float(np.linalg.norm(np.asarray(g, np.float64) - r) / max(np.linalg.norm(r), 1e-6 * np.sqrt(np.size(r))))
 
 
-def gpu_train(sol, layers, params, x, labels, dtype, lr=0.1, mu=0.9, steps=1):
+def gpu_train(sol, layers, params, x, labels, dtype, lr=0.1, mu=0.9, steps=1, autotune=False):
     """Runs `steps` training steps; returns what the checker's network_train_step returns, per step."""
     d = sol.BF16 if dtype == "bf16" else sol.F32
     net = sol.Network(layers, x.shape, d, flags=sol.NET_TRAINING)
     net.set_params(params)
     xd = sol.to_device_nhwc(x, d)
+    if autotune:
+        net.autotune(xd, reps=2)
     lab = torch.from_numpy(np.asarray(labels, np.int32)).to("cuda:0")
     res = []
     for _ in range(steps):
@@ -163,6 +165,17 @@ def test_train_step_bf16(sol, name):
     # store) flips that pixel's ReLU mask, which adds or removes a whole term of the pixel sum -- up to ~0.2 rms for a
     # sum of a few hundred terms -- while the tensor as a whole stays within the norm-wise tolerance checked above.
     # Element-wise agreement of every gradient is what the fp32 runs of the same layer lists assert (1e-4).
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_train_step_after_autotune(sol, dtype):
+    """The plan-time auto-tune of a training network (one tile for each forward and each data-gradient convolution)
+    changes kernels, not results: the step that follows it meets the same bounds as an untuned one."""
+    layers, params, x, labels = _make("wide", dtype, N=16, H=28, W=28)
+    net, got = gpu_train(sol, layers, params, x, labels, dtype, steps=2, autotune=True)
+    ref = oracle_train(layers, params, x, labels, dtype, steps=2)
+    for s in range(2 if dtype == "f32" else 1):
+        compare(got[s], ref[s], layers, dtype, elementwise=dtype == "f32", tag=f"wide/{dtype} tuned step {s}")
 
 
 def test_train_step_deterministic(sol):
