@@ -776,14 +776,35 @@ __device__ __forceinline__ uint4 column8_landed(Column8 &f) {
     return make_uint4(f.e[0] | (f.e[1] << 16), f.e[2] | (f.e[3] << 16), f.e[4] | (f.e[5] << 16), f.e[6] | (f.e[7] << 16));
 }
 
+// One MFMA fragment -- 8 consecutive rows (pixels) of one 2-byte column (channel) per lane -- with two transposing LDS
+// reads (ds_read_b64_tr_b16).  Within a group of 16 lanes, lane s supplies the address of 8 bytes (4 columns of one
+// row) and lane i receives, as element j, column i % 4 of the 8 bytes that lane 4 * j + i / 4 addressed (lane layout
+// measured on the part).  So when lane s addresses row s / 4, columns 4 * (s % 4) .. + 3, lane i ends up with rows
+// 0..3 of column i: four consecutive pixels of its channel, low half of a register first, as the MFMA wants them.
+// `addr` is that address for rows 0..3; rows 4..7 are 512 bytes (four 128-byte rows) further on.  Opaque to the
+// compiler like Column8: wait (lgkmcnt), then tr8_landed().
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+struct Tr8 { u32x2_t lo, hi; };
+__device__ __forceinline__ void read_tr8(Tr8 &f, unsigned addr) {
+    asm volatile("ds_read_b64_tr_b16 %0, %2 offset:0\n\t"
+                 "ds_read_b64_tr_b16 %1, %2 offset:512"
+                 : "=&v"(f.lo), "=&v"(f.hi)
+                 : "v"(addr));
+}
+__device__ __forceinline__ uint4 tr8_landed(Tr8 &f) {
+    asm volatile("" : "+v"(f.lo), "+v"(f.hi));
+    return make_uint4(f.lo.x, f.lo.y, f.hi.x, f.hi.y);
+}
+
 // The same contraction with both operands staged through LDS (bf16, K % 8 == 0 and C % 8 == 0).  A stage is 64
 // consecutive output pixels: their dz rows (64 channels = 128 bytes each) and the tap-shifted x rows travel
 // HBM/L2 -> LDS by DMA, 16 bytes per lane, fully coalesced; rows that do not exist (pixel range end, padding taps,
 // channel tails) get an out-of-range buffer offset and arrive as zeros.  Each of the four waves then takes one
-// 16-pixel k-step of the stage: an MFMA fragment is 8 consecutive pixels of one channel, i.e. eight 2-byte LDS
-// reads down a column (the 32 lanes of a half-wave read 64 contiguous bytes of one row; rows 8..15 sit 64 bytes
-// further along than rows 0..7 -- slot ^ 4, applied on the global side of the DMA -- so the two half-waves use
-// disjoint banks).  Ring of NS stages, one barrier per stage; partial sums and the second-stage reduction as above.
+// 16-pixel k-step of the stage: an MFMA fragment is 8 consecutive pixels of one channel, fetched by two transposing
+// LDS reads (read_tr8).  One such read has 32 lanes fetch 64 contiguous bytes of each of 4 consecutive rows; rows
+// 2, 3, 6, 7, ... sit 64 bytes further along than rows 0, 1, 4, 5, ... -- slot ^ 4, applied on the global side of the
+// DMA -- so that the four rows cover all 64 banks once.  Ring of NS stages, one barrier per stage; partial sums and
+// the second-stage reduction as above.
 template <int NS>
 __global__ void __launch_bounds__(256) wgrad_lds_kernel(const WgradArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -814,7 +835,7 @@ __global__ void __launch_bounds__(256) wgrad_lds_kernel(const WgradArgs a) {
 #pragma unroll
     for (int i = 0; i < 2; i++) {
         const int row = (wave * 2 + i) * 8 + lrow;
-        const int gs = lslot ^ (((row >> 3) & 1) << 2);        // global slot that lands in this lane's LDS slot
+        const int gs = lslot ^ (((row >> 1) & 1) << 2);        // global slot that lands in this lane's LDS slot
         zbase[i] = k0 + gs * 8 < a.K ? (unsigned)(row * a.K + k0 + gs * 8) * 2u : 0x80000000u;
         xrow[i] = row;
         xslot[i] = c0 + gs * 8 < a.C ? (c0 + gs * 8) * 2 : -1;
@@ -850,11 +871,17 @@ __global__ void __launch_bounds__(256) wgrad_lds_kernel(const WgradArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-    // fragment base of this lane: rows 16*wave + 8*h .. +7, column lr of channel block i (slot ^ 4 for the upper rows)
+    // transposing-read address of this lane for channel block i: row 16*wave + 8*h + s/4 (s = lane % 16), the 8 bytes
+    // of channels 32*i + 16*((lane/16)%2) + 4*(s%4) .. +3, slot ^ 4 in rows whose bit 1 is set
     unsigned fbase[2];
+    {
+        const int sl = lane & 15, frow = 16 * wave + 8 * h + (sl >> 2);
 #pragma unroll
-    for (int i = 0; i < 2; i++)
-        fbase[i] = (unsigned)((16 * wave + 8 * h) * 128 + (((i * 4 + (lr >> 3)) ^ (h << 2)) << 4) + (lr & 7) * 2);
+        for (int i = 0; i < 2; i++) {
+            const int slot = (i * 4 + ((lane >> 4) & 1) * 2 + ((sl & 3) >> 1)) ^ (((frow >> 1) & 1) << 2);
+            fbase[i] = (unsigned)(frow * 128 + (slot << 4) + (sl & 1) * 8);
+        }
+    }
 
 #pragma unroll
     for (int q = 0; q < NS - 1; q++) issue(s_begin + q, q);
@@ -867,16 +894,16 @@ __global__ void __launch_bounds__(256) wgrad_lds_kernel(const WgradArgs a) {
         // Fragment reads as opaque instructions (the compiler would otherwise wait for ALL outstanding DMA before
         // any LDS read): pixel e of a pair goes to the low half of a register, pixel e+1 to the high half.
         const unsigned zb = lds_addr(lds) + (unsigned)(buf * STAGE), xb = zb + 8192u;
-        Column8 ca[2], cb[2];
+        Tr8 ca[2], cb[2];
 #pragma unroll
         for (int i = 0; i < 2; i++) {
-            read_column8(ca[i], zb + fbase[i]);
-            read_column8(cb[i], xb + fbase[i]);
+            read_tr8(ca[i], zb + fbase[i]);
+            read_tr8(cb[i], xb + fbase[i]);
         }
         wait_lgkmcnt<0>();
         uint4 fa[2], fb[2];
 #pragma unroll
-        for (int i = 0; i < 2; i++) { fa[i] = column8_landed(ca[i]); fb[i] = column8_landed(cb[i]); }
+        for (int i = 0; i < 2; i++) { fa[i] = tr8_landed(ca[i]); fb[i] = tr8_landed(cb[i]); }
 #pragma unroll
         for (int i = 0; i < 2; i++)
 #pragma unroll
