@@ -1074,6 +1074,153 @@ __global__ void __launch_bounds__(256) wgrad_stem_kernel(const WgradArgs a, int 
 #endif
 }
 
+// ---- 3x3 / stride 1 / pad 1: one workgroup per filter ROW -------------------------------------------------------
+// wgrad_lds_kernel gives every filter tap its own workgroups, so the dz tile of a stage is fetched nine times and
+// the x tile once per tap: 16 KB through the DMA path per 16 MFMAs, which is what bounds it.  Here a workgroup owns
+// the three taps of one filter row r.  A stage is nr = 64 / W whole output rows (nr * W <= 64 pixels): their dz rows
+// and ONE run of x pixels -- output pixel m with tap s reads patch row m + s, the flattened-shift trick of the halo
+// forward kernel (input pixel index = output pixel index + (r-1) W + (s-1)) -- serve 36 MFMAs per 17 KB.  Because a
+// stage is whole image rows, a lane's pixels keep their column from stage to stage: taps that leave the image on
+// the left / right are redirected, once and for all, to a patch row that the DMA always zero-fills, and rows whose
+// input row oh + r - 1 lies outside the image have their dz row zero-filled by the DMA instead (x then holds a
+// neighbouring image's finite values, times zero).  Nothing in the loop computes an address: LDS offsets are per-lane
+// constants plus an immediate (the ring is unrolled), DMA offsets a per-lane constant plus a scalar.
+// Wave w owns the 32 x 32 block (w % 2, w / 2) of the 64 x 64 tile for all three taps and all four 16-pixel k-steps
+// of a stage, so there is no cross-wave sum at the end.
+constexpr int WR_NS = 3, WR_XROWS = 96, WR_STAGE = 8192 + WR_XROWS * 128, WR_L = 5, WR_ZROW = WR_XROWS - 1;
+template <int IMM> __device__ __forceinline__ void read_tr4(u32x2_t &d, unsigned addr) {
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=&v"(d) : "v"(addr), "n"(IMM));
+}
+__global__ void __launch_bounds__(256) wgrad_row_kernel(const WgradArgs a, int nr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    using namespace lds_pipe;
+    static_assert(WR_NS * WR_STAGE + 1024 <= 65536, "LDS offsets are 16-bit immediates");
+    __shared__ __align__(1024) unsigned char lds[WR_NS * WR_STAGE];
+    const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, sl = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int bid = blockIdx.x;
+    const int kt = bid % a.nkt; bid /= a.nkt;
+    const int ct = bid % a.nct; bid /= a.nct;
+    const int r = bid % a.R;
+    const int split = bid / a.R;
+    const int k0 = kt * 64, c0 = ct * 64, kc = wave & 1, cc = wave >> 1;
+    const int W = a.W, H = a.H, G = a.N * H, npx = nr * W;
+
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, (int)a.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t zr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.dz), 0, (int)a.dz_bytes, 0x00020000);
+    const int s_begin = split * a.steps_per_split, s_end = min(a.nsteps, s_begin + a.steps_per_split);
+
+    // ---- DMA lanes: a segment is 8 rows x 8 slots of 16 bytes.  Wave w owns dz segments 2w, 2w+1 and x segments
+    // 2w, 2w+1, 8+w.  slot ^ 4 in rows whose bit 1 is set (bank spread of the transposing reads).
+    const int lslot = lane & 7, lrow = lane >> 3;
+    unsigned zoff[2], xoff[3];
+    int zrow_g[2], zrow_oh[2];                     // global (n, oh) row index of this lane's dz row, and its oh
+#pragma unroll
+    for (int i = 0; i < 2; i++) {
+        const int m = (wave * 2 + i) * 8 + lrow, gs = lslot ^ (((m >> 1) & 1) << 2);
+        zoff[i] = (m < npx && k0 + gs * 8 < a.K) ? (unsigned)(m * a.K + k0 + gs * 8) * 2u : 0x80000000u;
+        zrow_g[i] = s_begin * nr + m / W;
+        zrow_oh[i] = zrow_g[i] % H;
+    }
+#pragma unroll
+    for (int i = 0; i < 3; i++) {
+        const int j = (i < 2 ? wave * 2 + i : 8 + wave) * 8 + lrow, gs = lslot ^ (((j >> 1) & 1) << 2);
+        // patch row j of stage st = input pixel st * npx + (r - 1) W - 1 + j (negative: wraps out of range -> zeros)
+        xoff[i] = (j < npx + 2 && c0 + gs * 8 < a.C) ? (unsigned)(((r - 1) * W - 1 + j) * a.C + c0 + gs * 8) * 2u : 0x80000000u;
+    }
+    const int nr_mod = nr % H;
+    auto issue = [&](int st, int buf) {
+        unsigned char *lz = lds + buf * WR_STAGE, *lx = lz + 8192;
+        const bool live = st < s_end;
+        const unsigned zstage = (unsigned)st * (unsigned)npx * (unsigned)a.K * 2u, xstage = (unsigned)st * (unsigned)npx * (unsigned)a.C * 2u;
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+            const bool ok = live && zrow_g[i] < G && (unsigned)(zrow_oh[i] + r - 1) < (unsigned)H;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(zr, (__attribute__((address_space(3))) void *)(lz + (wave * 2 + i) * 1024), 16,
+                                                     ok ? zoff[i] + zstage : 0xffffffffu, 0, 0, 0);
+            zrow_g[i] += nr;                       // the next stage this lane issues is st + 1
+            zrow_oh[i] += nr_mod;
+            zrow_oh[i] -= zrow_oh[i] >= H ? H : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < 3; i++)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, (__attribute__((address_space(3))) void *)(lx + (i < 2 ? wave * 2 + i : 8 + wave) * 1024), 16,
+                                                     live ? xoff[i] + xstage : 0xffffffffu, 0, 0, 0);
+    };
+
+    // ---- transposing-read addresses (per-lane constants, stage buffer 0): lane sl of a 16-lane group addresses
+    // pixel row (sl >> 2) [+4 for the upper half] of its k-step, the 8 bytes of channels 4 (sl & 3) .. +3 of its block
+    unsigned zaddr[4], xaddr[4][3][2];
+    {
+        const int slot_z = kc * 4 + ((lane >> 4) & 1) * 2 + ((sl & 3) >> 1), slot_x = cc * 4 + ((lane >> 4) & 1) * 2 + ((sl & 3) >> 1);
+        const unsigned lo = (unsigned)(sl & 1) * 8u, base = lds_addr(lds);
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+            const int m0 = 16 * ks + 8 * h + (sl >> 2);
+            zaddr[ks] = base + (unsigned)(m0 * 128 + ((slot_z ^ (((m0 >> 1) & 1) << 2)) << 4)) + lo;
+#pragma unroll
+            for (int e = 0; e < 2; e++) {
+                const int m = m0 + 4 * e, ow = m % W;
+#pragma unroll
+                for (int t = 0; t < 3; t++) {
+                    const bool ok = (unsigned)(ow + t - 1) < (unsigned)W;
+                    const int j = ok ? m + t : WR_ZROW;
+                    xaddr[ks][t][e] = base + 8192u + (unsigned)(j * 128 + ((slot_x ^ (((j >> 1) & 1) << 2)) << 4)) + lo;
+                }
+            }
+        }
+    }
+
+    f32x16_t acc[3];
+#pragma unroll
+    for (int t = 0; t < 3; t++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) acc[t][e] = 0.f;
+
+    issue(s_begin, 0);
+    issue(s_begin + 1, 1);
+    auto stage = [&](auto BUF, int st) {
+        constexpr int buf = decltype(BUF)::value, IMM = buf * WR_STAGE;
+        wait_vmcnt<(WR_NS - 2) * WR_L>();                      // this wave's share of stage st has landed
+        __builtin_amdgcn_s_barrier();                          // ... everyone's; and nobody still reads stage st-1
+        issue(st + WR_NS - 1, (buf + WR_NS - 1) % WR_NS);
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+            Tr8 fz, fx[3];
+            read_tr4<IMM>(fz.lo, zaddr[ks]);
+            read_tr4<IMM + 512>(fz.hi, zaddr[ks]);
+#pragma unroll
+            for (int t = 0; t < 3; t++) {
+                read_tr4<IMM>(fx[t].lo, xaddr[ks][t][0]);
+                read_tr4<IMM>(fx[t].hi, xaddr[ks][t][1]);
+            }
+            wait_lgkmcnt<0>();
+            const uint4 fa = tr8_landed(fz);
+#pragma unroll
+            for (int t = 0; t < 3; t++) Mma<bf16_t>::run(acc[t], fa, tr8_landed(fx[t]));
+        }
+    };
+    // whole rounds of the ring; stages past s_end are zero-filled by the DMA and add nothing
+    for (int st = s_begin; st < s_end; st += WR_NS) {
+        stage(std::integral_constant<int, 0>{}, st);
+        stage(std::integral_constant<int, 1>{}, st + 1);
+        stage(std::integral_constant<int, 2>{}, st + 2);
+    }
+    wait_vmcnt<0>();                                           // zero-fill DMAs of the tail
+
+    const size_t kstride = (size_t)a.R * a.S * a.C;
+    float *out = a.part + (size_t)split * a.K * kstride;
+    const int cw = c0 + cc * 32 + (lane & 31);
+#pragma unroll
+    for (int t = 0; t < 3; t++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+            const int kk = k0 + kc * 32 + 8 * (e / 4) + 4 * h + e % 4;
+            if (kk < a.K && cw < a.C) out[(size_t)kk * kstride + (size_t)(r * 3 + t) * a.C + cw] = acc[t][e];
+        }
+#endif
+}
+
 // dW[k][c][r][s] (framework layout) = sum over splits of part[split][k][r*S+s][c], added in split order
 __global__ void __launch_bounds__(256) wgrad_reduce_kernel(const float *__restrict__ part, int nsplit, float *__restrict__ dw,
                                                            int K, int C, int RS) {
@@ -1350,6 +1497,18 @@ static bool wgrad_lds_applies(const sol_tensor_desc &xd, const sol_conv_desc &cd
     return xd.dtype == SOL_BF16 && cd.cout % 8 == 0 && cd.cin % 8 == 0;
 }
 
+// bf16 3x3 / stride 1 / pad 1 with at most 62 pixels per image row: the filter-row kernel (stages of whole image rows)
+static bool wgrad_row_applies(const sol_tensor_desc &xd, const sol_conv_desc &cd) {
+    return xd.dtype == SOL_BF16 && cd.cout % 8 == 0 && cd.cin % 8 == 0 && cd.kh == 3 && cd.kw == 3 && cd.sh == 1 && cd.sw == 1 &&
+           cd.ph == 1 && cd.pw == 1 && xd.w <= 62 && xd.n > 0;
+}
+static void wgrad_row_plan(const sol_tensor_desc &xd, const sol_conv_desc &cd, int *nr, int *nstages, int *nsplit) {
+    *nr = std::max(1, 64 / xd.w);
+    *nstages = ceil_div(xd.n * xd.h, *nr);
+    const int tiles = ceil_div(cd.cout, 64) * ceil_div(cd.cin, 64) * 3;
+    *nsplit = std::max(1, std::min(ceil_div(384, tiles), std::max(1, *nstages / 6)));
+}
+
 // bf16 7x7 / stride 2 / pad 3 over 3 input channels, at most 64 output channels: the stem kernel
 static bool wgrad_stem_applies(const sol_tensor_desc &xd, const sol_conv_desc &cd) {
     return xd.dtype == SOL_BF16 && xd.c == 3 && cd.cin == 3 && cd.kh == 7 && cd.kw == 7 && cd.sh == 2 && cd.sw == 2 && cd.ph == 3 &&
@@ -1366,10 +1525,17 @@ void wgrad_plan(const sol_tensor_desc &xd, const sol_conv_desc &cd, int Ho, int 
         *part_floats = (size_t)*nsplit * cd.cout * 147;
         return;
     }
+    if (wgrad_row_applies(xd, cd)) {
+        int nr, nst, ns;
+        wgrad_row_plan(xd, cd, &nr, &nst, &ns);
+        *nsplit = ns;
+        *part_floats = (size_t)ns * cd.cout * 9 * cd.cin;
+        return;
+    }
     if (wgrad_lds_applies(xd, cd)) {
         const int nsteps = (int)(((long)xd.n * Ho * Wo + 63) / 64);
         const int tiles = ceil_div(cd.cout, 64) * ceil_div(cd.cin, 64) * cd.kh * cd.kw;
-        int ns = std::max(1, ceil_div(768, tiles));              // ~3 workgroups per CU, one round
+        int ns = std::max(1, ceil_div(384, tiles));              // 1.5 workgroups per CU measured best (two fit; fewer splits also mean fewer partials)
         ns = std::min(ns, std::max(1, nsteps / 8));
         *nsplit = ns;
         *part_floats = (size_t)ns * cd.cout * cd.kh * cd.kw * cd.cin;
@@ -1409,6 +1575,21 @@ sol_status launch_wgrad(const sol_tensor_desc &xd, const void *x, const sol_conv
                 hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for(total)), dim3(256), 0, st, part, a.nsplit, dw, cd.cout, cd.cin, 49);
         }
         if (deferred_nsplit) *deferred_nsplit = ntiles > 0 ? a.nsplit : 0;
+        SOL_HIP(hipGetLastError());
+        return SOL_OK;
+    }
+    if (wgrad_row_applies(xd, cd)) {
+        int nr;
+        wgrad_row_plan(xd, cd, &nr, &a.nsteps, &a.nsplit);
+        a.steps_per_split = ceil_div(a.nsteps, a.nsplit);
+        a.nkt = ceil_div(cd.cout, 64); a.nct = ceil_div(cd.cin, 64);
+        a.x_bytes = (uint32_t)xb; a.dz_bytes = (uint32_t)zb;
+        hipLaunchKernelGGL(wgrad_row_kernel, dim3(a.nkt * a.nct * 3 * a.nsplit), dim3(256), 0, st, a, nr);
+        if (deferred_nsplit)
+            *deferred_nsplit = a.nsplit;
+        else
+            hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(grid_for((long)cd.cout * 9 * cd.cin)), dim3(256), 0, st, part, a.nsplit, dw,
+                               cd.cout, cd.cin, 9);
         SOL_HIP(hipGetLastError());
         return SOL_OK;
     }
