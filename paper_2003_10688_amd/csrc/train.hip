@@ -1184,21 +1184,31 @@ __global__ void __launch_bounds__(256) wgrad_row_kernel(const WgradArgs a, int n
         wait_vmcnt<(WR_NS - 2) * WR_L>();                      // this wave's share of stage st has landed
         __builtin_amdgcn_s_barrier();                          // ... everyone's; and nobody still reads stage st-1
         issue(st + WR_NS - 1, (buf + WR_NS - 1) % WR_NS);
-#pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
-            Tr8 fz, fx[3];
-            read_tr4<IMM>(fz.lo, zaddr[ks]);
-            read_tr4<IMM + 512>(fz.hi, zaddr[ks]);
+        // fragments of k-step ks+1 are requested before the MFMAs of k-step ks are issued
+        Tr8 fz[2], fx[2][3];
+        auto request = [&](auto KS) {
+            constexpr int ks = decltype(KS)::value, set = ks & 1;
+            read_tr4<IMM>(fz[set].lo, zaddr[ks]);
+            read_tr4<IMM + 512>(fz[set].hi, zaddr[ks]);
 #pragma unroll
             for (int t = 0; t < 3; t++) {
-                read_tr4<IMM>(fx[t].lo, xaddr[ks][t][0]);
-                read_tr4<IMM>(fx[t].hi, xaddr[ks][t][1]);
+                read_tr4<IMM>(fx[set][t].lo, xaddr[ks][t][0]);
+                read_tr4<IMM>(fx[set][t].hi, xaddr[ks][t][1]);
             }
-            wait_lgkmcnt<0>();
-            const uint4 fa = tr8_landed(fz);
+        };
+        request(std::integral_constant<int, 0>{});
+        static_for<4>([&](auto KS) {
+            constexpr int ks = decltype(KS)::value, set = ks & 1;
+            if constexpr (ks + 1 < 4) {
+                request(std::integral_constant<int, ks + 1>{});
+                wait_lgkmcnt<8>();                             // only the eight reads just requested may be outstanding
+            } else {
+                wait_lgkmcnt<0>();
+            }
+            const uint4 fa = tr8_landed(fz[set]);
 #pragma unroll
-            for (int t = 0; t < 3; t++) Mma<bf16_t>::run(acc[t], fa, tr8_landed(fx[t]));
-        }
+            for (int t = 0; t < 3; t++) Mma<bf16_t>::run(acc[t], fa, tr8_landed(fx[set][t]));
+        });
     };
     // whole rounds of the ring; stages past s_end are zero-filled by the DMA and add nothing
     for (int st = s_begin; st < s_end; st += WR_NS) {
@@ -1506,7 +1516,7 @@ static void wgrad_row_plan(const sol_tensor_desc &xd, const sol_conv_desc &cd, i
     *nr = std::max(1, 64 / xd.w);
     *nstages = ceil_div(xd.n * xd.h, *nr);
     const int tiles = ceil_div(cd.cout, 64) * ceil_div(cd.cin, 64) * 3;
-    *nsplit = std::max(1, std::min(ceil_div(384, tiles), std::max(1, *nstages / 6)));
+    *nsplit = std::max(1, std::min(ceil_div(256, tiles), std::max(1, *nstages / 6)));
 }
 
 // bf16 7x7 / stride 2 / pad 3 over 3 input channels, at most 64 output channels: the stem kernel
