@@ -140,7 +140,7 @@ enum {
     H_256x128_x5 = 41, H_128x128_x3 = 42, H_256x64_x5 = 43, H_256x64_x6s = 44, H_256x64_x6s2 = 45, H_128x128_k2 = 46, H_64x128_k4 = 47, H_128x64_k4 = 48, H_64x64_k4 = 49, H_FIRST = 41, H_LAST = 59,
     // G_*: eight-wave 1x1 GEMM kernel (conv_gemm8.hip); kN: reduction split N ways inside the workgroup, r64: 64-byte rows
     G_128x128_k2 = 61, G_256x128 = 62, G_128x256 = 63, G_64x128_k4 = 64, G_128x64_k4 = 65, G_256x256_r64 = 66, G_256x128_r64 = 67,
-    G_64x64_k4 = 68, G_64x64_k4_deep = 69, G_FIRST = 61, G_LAST = 79,
+    G_64x64_k4 = 68, G_64x64_k4_deep = 69, G_64x32_k4_r256 = 70, G_FIRST = 61, G_LAST = 79,
     T_NO_HALO = 99   // automatic choice among the implicit-GEMM kernels only
 };
 int dma_tile_row_bytes(int tile);

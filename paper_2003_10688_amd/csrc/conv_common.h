@@ -58,7 +58,7 @@ __device__ __forceinline__ unsigned xor_add(unsigned a, unsigned x, unsigned b) 
 }
 // 16-byte slot permutation of a tile row (applied to the global address a DMA lane fetches): conflict-free
 // 16-byte fragment reads for rows of 128 bytes (8 slots) and of 64 bytes (4 slots)
-template <int ROWB> __device__ __forceinline__ int swz(int row) { return ROWB == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+template <int ROWB> __device__ __forceinline__ int swz(int row) { return ROWB == 256 ? (row & 15) : ROWB == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
 
 }  // namespace lds_pipe
 

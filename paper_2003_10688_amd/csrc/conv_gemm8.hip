@@ -297,6 +297,7 @@ sol_status launch_conv_gemm8(const ConvArgs &a, int tile, hipStream_t st) {
         case G_256x128_r64: return launch_gemm8_cfg<bf16_t, 4, 2, 1, 2, 2, 64, 6>(a, st);
         case G_64x64_k4: return launch_gemm8_cfg<bf16_t, 2, 1, 4, 1, 2, 128, 6>(a, st);
         case G_64x64_k4_deep: return launch_gemm8_cfg<bf16_t, 2, 1, 4, 1, 2, 128, 9>(a, st);   // weight streaming: 8 stages in flight
+        case G_64x32_k4_r256: return launch_gemm8_cfg<bf16_t, 2, 1, 4, 1, 1, 256, 6>(a, st);   // ... for matrices with < 200 tiles of 64 rows
         default: SOL_FAIL(SOL_ERR_UNSUPPORTED, "unknown gemm8 conv tile id %d", tile);
     }
 }

@@ -255,7 +255,11 @@ sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t
         // few rows, but a weight matrix of many megabytes (the MLP workload): the job is streaming the weights, which the
         // eight-wave ring kernel does with whole 128-byte lines and eight stages in flight
         const double wbytes = (double)a.Cout * a.Kp * dtype_size(dt);
-        if (wbytes >= 16.0 * 1048576 && gemm8_kernel_applies(a, dt) && a.C % 64 == 0) return launch_conv_gemm8(a, G_64x64_k4_deep, st);
+        if (wbytes >= 16.0 * 1048576 && gemm8_kernel_applies(a, dt) && a.C % 64 == 0) {
+            // enough workgroups for every CU: 32-row weight tiles when 64-row tiles would leave CUs idle
+            if (a.C % 128 == 0 && ceil_div(a.P, 64) * ceil_div(a.Cout, 64) < 200) return launch_conv_gemm8(a, G_64x32_k4_r256, st);
+            return launch_conv_gemm8(a, G_64x64_k4_deep, st);
+        }
         return launch_linear(a, dt, st);
     }
     if (tile_override == T_AUTO && halo_kernel_applies(a, dt)) {
