@@ -128,3 +128,32 @@ def test_plan_tile_api_validates(sol):
     assert L.sol_network_autotune(None, fake, fake, fake, C.c_size_t(0), 3, None) == 1
     assert L.sol_network_autotune(h, fake, fake, fake, C.c_size_t(1 << 30), 0, None) == 2     # reps out of range
     L.sol_network_destroy(h)
+
+
+def test_depthwise_planning_and_validation(sol):
+    """Depthwise layers: shape inference keeps the channel count, parameters are [taps][c] + scale/shift, bad
+    descriptors are refused on the host."""
+    L = sol.lib()
+    assert L.sol_packed_dw_weight_bytes(32, 3, 3, sol.BF16) == 32 * 9 * 2
+    assert L.sol_packed_dw_weight_bytes(8, 5, 3, sol.F32) == 8 * 15 * 4 and L.sol_packed_dw_weight_bytes(0, 3, 3, sol.F32) == 0
+    assert L.sol_packed_dw_weight_bytes(3, 3, 3, sol.BF16) == 64                     # 54 bytes, rounded up to 16
+    wk = wl.config(6)
+    st, h = _create(sol, wk.layers, wk.in_shape, sol.BF16)
+    assert st == 0
+    d = sol.TensorDesc()
+    assert L.sol_network_output_desc(h, 1, C.byref(d)) == 0 and (d.n, d.h, d.w, d.c) == (64, 112, 112, 32)    # depthwise s1
+    assert L.sol_network_output_desc(h, 3, C.byref(d)) == 0 and (d.n, d.h, d.w, d.c) == (64, 56, 56, 64)      # depthwise s2
+    assert L.sol_network_output_desc(h, -1, C.byref(d)) == 0 and (d.n, d.h, d.w, d.c) == (64, 1, 1, 1000)
+    # 4.2 M parameters: pointwise + classifier weights dominate, 9 values per channel for the depthwise layers
+    assert 4.2e6 * 2 <= L.sol_network_param_bytes(h) <= 4.2e6 * 2 * 1.15
+    L.sol_network_destroy(h)
+    assert _create(sol, [wl.conv(24, 3, dw=True)], (2, 16, 8, 8), sol.BF16)[0] == 2                            # channel count must be kept
+    assert _create(sol, [wl.conv(16, 3, dw=True, pool=wl.pool_desc("max", 2, 2, 0))], (2, 16, 8, 8), sol.BF16)[0] == 6
+    assert _create(sol, [wl.conv(16, 3, dw=True), wl.gap(), wl.linear(4)], (2, 16, 8, 8), sol.BF16, sol.NET_TRAINING)[0] == 6
+    xd = sol.TensorDesc(1, 8, 8, 16, sol.BF16)
+    fake, null = C.c_void_p(0x1000), C.c_void_p(0)
+    call = lambda cd, x=fake, w=fake, y=fake: L.sol_dwconv2d_fused(C.byref(xd), x, C.byref(cd), w, null, null, null, 0, y, null)  # noqa: E731
+    assert call(sol.ConvDesc(32, 16, 3, 3, 1, 1, 1, 1)) == 2                          # cout != channels
+    assert call(sol.ConvDesc(16, 16, 3, 3, 1, 1, 1, 1), w=null) == 1                  # NULL weights
+    assert call(sol.ConvDesc(16, 16, 3, 3, 1, 1, 1, 1), x=C.c_void_p(0x1008)) == 4    # misaligned x
+    assert call(sol.ConvDesc(16, 16, 11, 11, 1, 1, 0, 0)) == 2                        # filter larger than the input
