@@ -71,7 +71,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload: 3 = ResNet-50-shaped bs64 (default), 2 = ResNet-18-shaped bs32, 5 = 3-layer MLP with 8192 features bs64, 6 = depthwise-separable chain bs64")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--layer-reps", type=int, default=20, help="event-timed repetitions per layer for the roofline")
-    ap.add_argument("--cpu-sample", type=int, default=8, help="images the CPU checker is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=32, help="images the CPU checker is timed on (0 = skip); 32 is 10-15 s of CPU work")
     ap.add_argument("--layers", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--graph", action="store_true", help="time HIP-graph replays of the pass instead of plain launches")
     ap.add_argument("--tune-reps", type=int, default=10,
