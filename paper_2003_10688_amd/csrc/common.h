@@ -180,7 +180,6 @@ sol_status launch_pool_bwd(const PoolArgs &a, const void *dy, void *dx, int firs
 sol_status launch_gap_bwd(const void *dy, void *dx, int N, int HW, int C, int first, int dt, hipStream_t st);
 sol_status launch_softmax_ce(const void *logits, const int32_t *labels, void *dlogits, float *row_loss, float *loss, int N,
                              int C, int dt, hipStream_t st);
-sol_status launch_sgd(float *w, float *v, const float *g, long n, float lr, float mu, hipStream_t st);
 
 // Batched parameter update: up to SGD_MAX_SEG tensors updated, and up to PACK_MAX_SEG packed weight buffers rebuilt,
 // by one launch each (a ResNet-18-shaped step otherwise spends ~100 launches on them).  The segment tables travel

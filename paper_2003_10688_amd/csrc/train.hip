@@ -489,16 +489,7 @@ __global__ void loss_mean_kernel(const float *__restrict__ row_loss, int N, floa
     }
 }
 
-// ---- SGD with momentum ------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) sgd_kernel(float *__restrict__ w, float *__restrict__ v, const float *__restrict__ g,
-                                                  long n, float lr, float mu) {
-    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
-        const float vel = mu * v[i] + g[i];
-        v[i] = vel;
-        w[i] -= lr * vel;
-    }
-}
-
+// ---- SGD with momentum: v <- mu v + g ; w <- w - lr v ---------------------------------------------------------
 // All parameter tensors of a network in one launch: block -> segment by a scan of the (scalar) block table.
 __global__ void __launch_bounds__(256) sgd_batch_kernel(const SgdBatch b, float lr, float mu) {
     int seg = 0;
@@ -1458,13 +1449,6 @@ sol_status launch_softmax_ce(const void *logits, const int32_t *labels, void *dl
         hipLaunchKernelGGL((softmax_ce_kernel<float>), dim3(N), dim3(256), 0, st, static_cast<const float *>(logits), labels,
                            static_cast<float *>(dlogits), row_loss, N, C);
     hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(64), 0, st, row_loss, N, loss);
-    SOL_HIP(hipGetLastError());
-    return SOL_OK;
-}
-
-sol_status launch_sgd(float *w, float *v, const float *g, long n, float lr, float mu, hipStream_t st) {
-    if (n <= 0) return SOL_OK;
-    hipLaunchKernelGGL(sgd_kernel, dim3(grid_for(n)), dim3(256), 0, st, w, v, g, n, lr, mu);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }
