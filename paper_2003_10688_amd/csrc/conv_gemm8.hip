@@ -36,7 +36,7 @@ __global__ void __launch_bounds__(512) conv_gemm8_kernel(const ConvArgs a) {
     constexpr int EPI0 = (KSPL - 1) * NG * ACCB;           // epilogue strips start behind the K-split partials
     static_assert(WP * WC * KSPL == NW && KS % KSPL == 0, "wave grid");
     static_assert(BP % (RSEG * NW) == 0 && BC % (RSEG * NW) == 0, "tile rows must split into whole DMA segments per wave");
-    static_assert(NS >= 2 && NS * STAGE + NW * 256 <= 160 * 1024, "ring");
+    static_assert(NS >= 3 && NS * STAGE + NW * 256 <= 160 * 1024, "ring: the stage published by the mid-stage barrier was issued a whole stage earlier");
     static_assert(EPI0 + NG * 32 * (TC * 32 + 4) * 4 <= NS * STAGE, "K-split partials and epilogue strips must fit in the ring");
     static_assert((D - 1) * L < 64, "vmcnt");
 
