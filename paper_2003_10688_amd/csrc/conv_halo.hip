@@ -140,7 +140,7 @@ __global__ void __launch_bounds__(WP *WC *KSPL * 64, MINW) conv_halo_kernel(cons
     if constexpr (MINW < 4) {
         if (kq == 0) prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
     }
-    if (tid < NPB * 32) *reinterpret_cast<unsigned *>(patch + (tid >> 5) * PBYTES + PROWS * ROWB + (tid & 31) * 4) = 0u;
+    if (tid < NPB * 64) *reinterpret_cast<unsigned *>(patch + (tid >> 6) * PBYTES + PROWS * ROWB + (tid & 63) * 4) = 0u;   // two zero rows
 
     // ---- fragment addresses (computed while the first DMAs are in flight).  ax[j][t]: LDS byte address (patch
     // buffer 0, k-step 0) of tap t of this lane's pixel in pixel block j, or of the zero row when that tap lies
@@ -154,12 +154,15 @@ __global__ void __launch_bounds__(WP *WC *KSPL * 64, MINW) conv_halo_kernel(cons
         const unsigned inside = m < a.P ? 1u : 0u;
         const unsigned hok[3] = {inside & (h >= 1 ? 1u : 0u), inside, inside & (h + 1 < a.H ? 1u : 0u)};
         const unsigned wok[3] = {w >= 1 ? 1u : 0u, 1u, w + 1 < W ? 1u : 0u};
-        const unsigned zero_row = lds_addr(patch) + PROWS * ROWB + (lh << 4);
+        const unsigned zero_base = lds_addr(patch) + PROWS * ROWB;   // 256 zero bytes = one pass over all 64 banks
 #pragma unroll
         for (int t = 0; t < 9; t++) {
             const int r = t / 3, sx = t % 3;
             const int row = mloc + r * W + sx;
             const unsigned real = lds_addr(patch) + row * ROWB + ((lh ^ swz<ROWB>(row)) << 4);
+            // A redirected lane reads the zero bytes that lie in the banks of the patch slot it would have read (same
+            // offset within a 256-byte bank pass), so a redirect never adds a bank conflict to the wave's read.
+            const unsigned zero_row = zero_base + (real & 255u);
             // arithmetic select (no divergent branch): zero_row + ok * (real - zero_row)
             ax[j][t] = zero_row + ((0u - (hok[r] & wok[sx])) & (real - zero_row));
         }
