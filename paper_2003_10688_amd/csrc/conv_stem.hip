@@ -11,6 +11,7 @@
 // re-laid-out once per workgroup into the same padded order (zeros at s = 7 and c = 3), and the
 // workgroup then walks many tiles (persistent grid), so that cost is paid once.
 #include "conv_common.h"
+#include <type_traits>
 
 namespace sol {
 
@@ -38,7 +39,7 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
     constexpr int COLS = 2 * (STEM_TW - 1) + S;                          // columns that hold image data
     constexpr int STEM_WROW = R * KROW + 8;                              // padded weight row (bank spread)
     __shared__ __align__(16) bf16_t wl[NC * 32 * STEM_WROW];            // 7x7, 64 channels: 29.0 KB
-    __shared__ __align__(16) bf16_t xl[STEM_IH * STEM_IW * 4];          //  6.4 KB
+    __shared__ __align__(16) bf16_t xl[2][STEM_IH * STEM_IW * 4];       //  2 x 6.4 KB: the next tile's patch lands while this one is read
     __shared__ __align__(16) float strip[4 * 32 * (NC * 32 + 4)];       // 34.0 KB epilogue transposer
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -53,7 +54,7 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
         if (kk < R * KROW && s < S && c < 3 && k < a.Cout) v = wg[k * a.Kp + (r * S + s) * 3 + c];
         wl[i] = v;
     }
-    for (int i = tid; i < STEM_IH * STEM_IW * 4; i += 256) xl[i] = 0;   // incl. the never-written pad column
+    for (int i = tid; i < 2 * STEM_IH * STEM_IW * 4; i += 256) xl[0][i] = 0;   // incl. the never-written pad columns
 
     const int lr = lane & 31, lh = lane >> 5;
     const int py = 2 * wave + (lr >> 4), px = lr & 15;                   // this lane's output pixel in the block
@@ -80,54 +81,75 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
             }
         }
     };
-    auto store_patch = [&]() {                    // registers -> LDS, widened to 4 channels
+    auto store_patch = [&](int buf) {             // registers -> LDS, widened to 4 channels
 #pragma unroll
         for (int i = 0; i < NP; i++) {
             const int e = tid + i * 256;
             if (e < NPIX) {
                 const int ih = e / COLS, iw = e % COLS;
-                *reinterpret_cast<uint2 *>(&xl[(ih * STEM_IW + iw) * 4]) = pv[i];
+                *reinterpret_cast<uint2 *>(&xl[buf][(ih * STEM_IW + iw) * 4]) = pv[i];
             }
         }
     };
 
+    // Wait bookkeeping: the compiler derives every vmcnt wait itself, and where paths join it assumes the worst of
+    // them.  So everything loaded before the loop (affine constants, first patch) is drained here; inside the loop
+    // a patch is written to LDS at the END of the iteration that issued its loads; and the loop exists twice, so
+    // that the common one (every block inside the image, all channels, no residual) is straight-line code in which
+    // the only memory operations younger than the patch loads are the block's 2 * NC output stores: those stay in
+    // flight across the wait instead of stalling the next tile.  The explicit waits in the loop only tell the
+    // compiler, at a point every lane passes, what it would otherwise have to assume at the next join; it still
+    // adds any wait it needs itself.
     if ((int)blockIdx.x < ntiles) load_patch(blockIdx.x);
-    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int tw = tile % tiles_w, t2 = tile / tiles_w;
-        const int th = t2 % tiles_h, n = t2 / tiles_h;
-        const int p0 = th * STEM_TH, q0 = tw * STEM_TW;
-        __syncthreads();                                                 // previous tile's patch no longer read
-        store_patch();
-        __syncthreads();
-        if (tile + (int)gridDim.x < ntiles) load_patch(tile + gridDim.x);   // in flight under the MFMAs and the epilogue
+    __builtin_amdgcn_s_waitcnt(0x0F70);                                  // vmcnt(0)
+    __syncthreads();                                                     // zero fill done before patch pixels are written
+    store_patch(0);
+
+    auto run_tiles = [&](auto interior_tag) {
+        constexpr bool INTERIOR = decltype(interior_tag)::value;
+        int cur = 0;
+        for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x, cur ^= 1) {
+            const int tw = tile % tiles_w, t2 = tile / tiles_w;
+            const int th = t2 % tiles_h, n = t2 / tiles_h;
+            const int p0 = th * STEM_TH, q0 = tw * STEM_TW;
+            const bool more = tile + (int)gridDim.x < ntiles;
+            __syncthreads();                                             // xl[cur] written; xl[cur ^ 1] no longer read
+            if (more) load_patch(tile + gridDim.x);                      // in flight under the MFMAs and the epilogue
+            const unsigned char *xc = reinterpret_cast<const unsigned char *>(xl[cur]);
 #pragma unroll
-        for (int i = 0; i < NC; i++)
+            for (int i = 0; i < NC; i++)
 #pragma unroll
-            for (int e = 0; e < 16; e++) acc[i][0][e] = 0.f;
+                for (int e = 0; e < 16; e++) acc[i][0][e] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < R * KROW / 16; ks++) {
-            const int r = ks / (KROW / 16), s0 = (ks % (KROW / 16)) * 4 + lh * 2;   // 8 elements = pixels s0, s0+1 of row r
-            const uint4 fb = *reinterpret_cast<const uint4 *>(reinterpret_cast<const unsigned char *>(xl) + xbase +
-                                                             (r * STEM_IW + s0) * 8);
+            for (int ks = 0; ks < R * KROW / 16; ks++) {
+                const int r = ks / (KROW / 16), s0 = (ks % (KROW / 16)) * 4 + lh * 2;   // 8 elements = pixels s0, s0+1 of row r
+                const uint4 fb = *reinterpret_cast<const uint4 *>(xc + xbase + (r * STEM_IW + s0) * 8);
 #pragma unroll
-            for (int i = 0; i < NC; i++) {
-                const uint4 fa = *reinterpret_cast<const uint4 *>(&wl[(i * 32 + lr) * STEM_WROW + ks * 16 + lh * 8]);
-                Mma<bf16_t>::run(acc[i][0], fa, fb);
+                for (int i = 0; i < NC; i++) {
+                    const uint4 fa = *reinterpret_cast<const uint4 *>(&wl[(i * 32 + lr) * STEM_WROW + ks * 16 + lh * 8]);
+                    Mma<bf16_t>::run(acc[i][0], fa, fb);
+                }
             }
+            ResidualRegs<bf16_t, 1, NC> resregs;
+            resregs.on = false;
+            if constexpr (INTERIOR) {                                    // branch-free epilogue
+                const int pw = p0 + 2 * wave;     // first output row of this wave's 32 tile rows
+                const StemRowOffset ro{(unsigned)(((n * a.Ho + pw) * a.Wo + q0) * (NC * 32)), (unsigned)a.Wo, (unsigned)(NC * 32)};
+                conv_epilogue_interior<bf16_t, 1, NC, false>(a, acc, strip, wave, lane, 0, aff, resregs, ro);
+                __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * NC));           // vmcnt(2 * NC), outside the lane-masked regions below
+            } else {
+                const StemRows rows{n, p0, q0, a.Ho, a.Wo};
+                prefetch_residual<bf16_t, 1, NC>(a, lane, wave * 32, 0, rows, resregs);
+                conv_epilogue<bf16_t, 1, NC>(a, acc, strip, wave, lane, wave * 32, 0, aff, rows, resregs);
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+            }
+            if (more) store_patch(cur ^ 1);
         }
-        const StemRows rows{n, p0, q0, a.Ho, a.Wo};
-        ResidualRegs<bf16_t, 1, NC> resregs;
-        resregs.on = false;
-        // blocks inside the image with all NC * 32 channels and no residual: branch-free epilogue
-        if (p0 + STEM_TH <= a.Ho && q0 + STEM_TW <= a.Wo && a.Cout == NC * 32 && a.res == nullptr) {
-            const int pw = p0 + 2 * wave;     // first output row of this wave's 32 tile rows
-            const StemRowOffset ro{(unsigned)(((n * a.Ho + pw) * a.Wo + q0) * (NC * 32)), (unsigned)a.Wo, (unsigned)(NC * 32)};
-            conv_epilogue_interior<bf16_t, 1, NC, false>(a, acc, strip, wave, lane, 0, aff, resregs, ro);
-        } else {
-            prefetch_residual<bf16_t, 1, NC>(a, lane, wave * 32, 0, rows, resregs);
-            conv_epilogue<bf16_t, 1, NC>(a, acc, strip, wave, lane, wave * 32, 0, aff, rows, resregs);
-        }
-    }
+    };
+    if (a.Ho % STEM_TH == 0 && a.Wo % STEM_TW == 0 && a.Cout == NC * 32 && a.res == nullptr)
+        run_tiles(std::true_type{});
+    else
+        run_tiles(std::false_type{});
 }
 
 bool stem_kernel_applies(const ConvArgs &a, int dt) {
