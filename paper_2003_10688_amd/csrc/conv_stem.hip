@@ -46,16 +46,6 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
     const bf16_t *__restrict__ xg = static_cast<const bf16_t *>(a.x);
     const bf16_t *__restrict__ wg = static_cast<const bf16_t *>(a.w);
 
-    // weights: packed [k][(r*S+s)*3+c] -> LDS [k][r*KROW + s*4 + c], zero elsewhere
-    for (int i = tid; i < NC * 32 * STEM_WROW; i += 256) {
-        const int k = i / STEM_WROW, kk = i % STEM_WROW;
-        const int r = kk / KROW, s = (kk % KROW) >> 2, c = kk & 3;
-        bf16_t v = 0;
-        if (kk < R * KROW && s < S && c < 3 && k < a.Cout) v = wg[k * a.Kp + (r * S + s) * 3 + c];
-        wl[i] = v;
-    }
-    for (int i = tid; i < 2 * STEM_IH * STEM_IW * 4; i += 256) xl[0][i] = 0;   // incl. the never-written pad columns
-
     const int lr = lane & 31, lh = lane >> 5;
     const int py = 2 * wave + (lr >> 4), px = lr & 15;                   // this lane's output pixel in the block
     const unsigned xbase = ((2 * py) * STEM_IW + 2 * px) * 8;            // its patch origin, bytes
@@ -65,17 +55,24 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
     // Input patch of a tile: STEM_IH x COLS pixels, 3 channels each, NP pixels per thread.
     constexpr int NPIX = STEM_IH * COLS, NP = (NPIX + 255) / 256;
     uint2 pv[NP];
-    auto load_patch = [&](int tile) {             // global -> registers (issued one tile ahead)
+    int rel[NP], pih[NP], piw[NP];                // this thread's patch pixels: element offset from the patch origin, row, column
+#pragma unroll
+    for (int i = 0; i < NP; i++) {
+        const int e = tid + i * 256;
+        pih[i] = e < NPIX ? e / COLS : -(1 << 20);                       // past the patch: fails every bounds check
+        piw[i] = e % COLS;
+        rel[i] = (pih[i] * a.W + piw[i]) * 3;
+    }
+    auto load_patch = [&](int tile) {             // global -> registers (issued one tile ahead); 32-bit element offsets
         const int tw = tile % tiles_w, t2 = tile / tiles_w;
         const int th = t2 % tiles_h, n = t2 / tiles_h;
+        const int gh0 = 2 * th * STEM_TH - a.ph, gw0 = 2 * tw * STEM_TW - a.pw;
+        const int base = ((n * a.H + gh0) * a.W + gw0) * 3;
 #pragma unroll
         for (int i = 0; i < NP; i++) {
-            const int e = tid + i * 256;
-            const int ih = e / COLS, iw = e % COLS;
-            const int gh = 2 * th * STEM_TH - a.ph + ih, gw = 2 * tw * STEM_TW - a.pw + iw;
             pv[i] = make_uint2(0, 0);
-            if (e < NPIX && (unsigned)gh < (unsigned)a.H && (unsigned)gw < (unsigned)a.W) {
-                const bf16_t *p = xg + (((long)n * a.H + gh) * a.W + gw) * 3;
+            if ((unsigned)(gh0 + pih[i]) < (unsigned)a.H && (unsigned)(gw0 + piw[i]) < (unsigned)a.W) {
+                const bf16_t *p = xg + (base + rel[i]);
                 pv[i].x = (uint32_t)p[0] | ((uint32_t)p[1] << 16);
                 pv[i].y = (uint32_t)p[2];
             }
@@ -92,18 +89,66 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
         }
     };
 
+    // Prologue, all of its memory latencies overlapped: first patch and affine constants (above) are in flight while
+    // the weights are fetched.  Packed weights [k][(r*S+s)*3+c] -> LDS [k][r*KROW + s*4 + c], zero at s >= S and
+    // c = 3: the packed rows are first copied as they are, by LDS DMA with every load in flight at once, into the
+    // (still unused) epilogue transposer; the re-layout then runs LDS to LDS, one (k, r) filter row per thread and
+    // trip.  (A gather straight from global memory costs one exposed round trip per element and used to take longer
+    // than all the tiles of a workgroup together.)  The 8 pad elements that end each LDS row are never read.
+    if ((int)blockIdx.x < ntiles) load_patch(blockIdx.x);
+    {
+        // Kp <= 256: at most NC * 16 KB, as NC * 4 DMA instructions of 1 KB per wave; chunks past the last row read zeros
+        const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(wg), 0, a.Cout * a.Kp * 2, 0x00020000);
+        unsigned char *stage = reinterpret_cast<unsigned char *>(strip);
+#pragma unroll
+        for (int j = 0; j < NC * 4; j++)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, (__attribute__((address_space(3))) void *)(stage + (j * 4 + wave) * 1024), 16,
+                                                     ((j * 4 + wave) * 64 + lane) * 16, 0, 0, 0);
+    }
+    static_assert(STEM_IW % 2 == 0, "patch buffers are whole 16-byte units");
+    for (int i = tid; i < STEM_IH * STEM_IW; i += 256)                   // incl. the never-written pad columns
+        reinterpret_cast<uint4 *>(&xl[0][0])[i] = make_uint4(0, 0, 0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                                  // vmcnt(0): weights staged, patch and constants here
+    __syncthreads();                                                     // ... for every wave; zero fill done
+    {
+        const bf16_t *raw = reinterpret_cast<const bf16_t *>(strip);
+        for (int i = tid; i < NC * 32 * R; i += 256) {
+            const int k = i / R, r = i % R;
+            __align__(16) bf16_t row[KROW];
+#pragma unroll
+            for (int j = 0; j < KROW; j++) row[j] = 0;
+            if (k < a.Cout) {
+#pragma unroll
+                for (int j = 0; j < S * 3; j++) row[(j / 3) * 4 + j % 3] = raw[k * a.Kp + r * S * 3 + j];
+            }
+#pragma unroll
+            for (int j = 0; j < KROW / 8; j++)
+                *reinterpret_cast<uint4 *>(&wl[k * STEM_WROW + r * KROW + j * 8]) = *reinterpret_cast<const uint4 *>(&row[j * 8]);
+        }
+    }
+    store_patch(0);
+    // (the barrier that opens the first tile publishes wl and the patch, and orders the staging reads above before
+    // any epilogue write to the transposer)
+
     // Wait bookkeeping: the compiler derives every vmcnt wait itself, and where paths join it assumes the worst of
-    // them.  So everything loaded before the loop (affine constants, first patch) is drained here; inside the loop
+    // them.  So everything loaded before the loop (affine constants, first patch) is drained in the prologue; inside the loop
     // a patch is written to LDS at the END of the iteration that issued its loads; and the loop exists twice, so
     // that the common one (every block inside the image, all channels, no residual) is straight-line code in which
     // the only memory operations younger than the patch loads are the block's 2 * NC output stores: those stay in
     // flight across the wait instead of stalling the next tile.  The explicit waits in the loop only tell the
     // compiler, at a point every lane passes, what it would otherwise have to assume at the next join; it still
     // adds any wait it needs itself.
-    if ((int)blockIdx.x < ntiles) load_patch(blockIdx.x);
-    __builtin_amdgcn_s_waitcnt(0x0F70);                                  // vmcnt(0)
-    __syncthreads();                                                     // zero fill done before patch pixels are written
-    store_patch(0);
+    using namespace lds_pipe;
+    constexpr int NKS = R * KROW / 16, DEPTH = 2;
+    static_assert(sizeof(strip) >= NC * 16384, "weight staging area");
+    static_assert(NKS >= DEPTH, "pipeline deeper than the reduction");
+    u32x4_t fb[DEPTH + 1], fa[DEPTH + 1][NC];
+    const unsigned aw = lds_addr(wl) + (lr * STEM_WROW + lh * 8) * 2;
+    auto issue_step = [&](auto KS, unsigned ax) {
+        constexpr int ks = decltype(KS)::value, slot = ks % (DEPTH + 1);
+        lds_read16<((ks / (KROW / 16)) * STEM_IW + (ks % (KROW / 16)) * 4) * 8>(fb[slot], ax);
+        static_for<NC>([&](auto I) { lds_read16<(decltype(I)::value * 32 * STEM_WROW + ks * 16) * 2>(fa[slot][decltype(I)::value], aw); });
+    };
 
     auto run_tiles = [&](auto interior_tag) {
         constexpr bool INTERIOR = decltype(interior_tag)::value;
@@ -115,21 +160,27 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
             const bool more = tile + (int)gridDim.x < ntiles;
             __syncthreads();                                             // xl[cur] written; xl[cur ^ 1] no longer read
             if (more) load_patch(tile + gridDim.x);                      // in flight under the MFMAs and the epilogue
-            const unsigned char *xc = reinterpret_cast<const unsigned char *>(xl[cur]);
 #pragma unroll
             for (int i = 0; i < NC; i++)
 #pragma unroll
                 for (int e = 0; e < 16; e++) acc[i][0][e] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < R * KROW / 16; ks++) {
-                const int r = ks / (KROW / 16), s0 = (ks % (KROW / 16)) * 4 + lh * 2;   // 8 elements = pixels s0, s0+1 of row r
-                const uint4 fb = *reinterpret_cast<const uint4 *>(xc + xbase + (r * STEM_IW + s0) * 8);
+            // Reduction step ks covers 16 elements of filter row r = ks / (KROW / 16): 8 per lane half, i.e. patch
+            // pixels s0, s0 + 1 with s0 = (ks % (KROW / 16)) * 4 + 2 * lh.  The fragment reads are issued by hand
+            // DEPTH steps ahead of the MFMAs that consume them (left to itself the compiler issues them just in
+            // time and every step waits out a full LDS round trip).
+            const unsigned ax = lds_addr(xl[cur]) + xbase + lh * 16;
+            static_for<DEPTH>([&](auto KS) { issue_step(KS, ax); });
+            static_for<NKS>([&](auto KS) {
+                constexpr int ks = decltype(KS)::value, slot = ks % (DEPTH + 1);
+                if constexpr (ks + DEPTH < NKS) issue_step(std::integral_constant<int, ks + DEPTH>{}, ax);
+                wait_lgkmcnt<(ks + DEPTH < NKS ? DEPTH : NKS - 1 - ks) * (1 + NC)>();
+                landed(fb[slot]);
 #pragma unroll
                 for (int i = 0; i < NC; i++) {
-                    const uint4 fa = *reinterpret_cast<const uint4 *>(&wl[(i * 32 + lr) * STEM_WROW + ks * 16 + lh * 8]);
-                    Mma<bf16_t>::run(acc[i][0], fa, fb);
+                    landed(fa[slot][i]);
+                    Mma<bf16_t>::run(acc[i][0], fa[slot][i], fb[slot]);
                 }
-            }
+            });
             ResidualRegs<bf16_t, 1, NC> resregs;
             resregs.on = false;
             if constexpr (INTERIOR) {                                    // branch-free epilogue
@@ -155,7 +206,8 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
 bool stem_kernel_applies(const ConvArgs &a, int dt) {
     const bool k7 = a.R == 7 && a.S == 7, k3 = a.R == 3 && a.S == 3;
     return dt == SOL_BF16 && a.C == 3 && (k7 || k3) && a.sh == 2 && a.sw == 2 && a.ph >= 0 && a.ph < a.R && a.pw >= 0 && a.pw < a.S &&
-           a.Cout <= 64 && a.pool == 0;
+           a.Cout <= 64 && a.pool == 0 && (long)a.N * a.H * a.W * 3 < (1L << 31) &&   // the patch loader uses 32-bit offsets
+           a.Kp % 8 == 0 && a.Kp <= 256;   // the packed rows are staged whole in the transposer: 17 KB per 32 channels
 }
 
 sol_status launch_conv_stem(const ConvArgs &a, hipStream_t st) {
