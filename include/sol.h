@@ -104,8 +104,12 @@ sol_status sol_fold_bn(int c, const float *gamma, const float *beta, const float
  *   scale,shift device fp32 [cout]; NULL = 1 / 0
  *   residual   NULL or NHWC [n][Ho][Wo][cout] of the same dtype (conv-output shape, before pooling)
  *   pool       NULL or kind NONE = no pool.  Fused: max or avg, 2x2 window, stride 2, no padding
- *              (floor mode: an odd last row/column is dropped); any other pool -> SOL_ERR_UNSUPPORTED
- *              (run sol_pool on the result instead).
+ *              (floor mode: an odd last row/column is dropped), behind any convolution; or a 3x3
+ *              stride-2 pad-1 max pool behind a bf16 7x7 stride-2 convolution of a 3-channel input
+ *              with 64 filters, ReLU and no residual (the ResNet-shaped stem pair, run depth-first
+ *              in one kernel: y is [n][Hy][Wy][64] with Hy = sol_out_size(Ho, 3, 2, 1); pool_argmax
+ *              and prepool must be NULL).  Any other pool -> SOL_ERR_UNSUPPORTED (run sol_pool on
+ *              the result instead).
  *   y          NHWC [n][Hy][Wy][cout], same dtype as x
  *   pool_argmax NULL, or int32 NHWC like y (max pool only): logical index ih*Wo+iw of the winning
  *              element inside its (n,k) conv-output plane; among equal values the first in row-major
@@ -216,6 +220,14 @@ sol_status sol_network_graph_create(sol_network *net, const void *x, void *y, vo
                                     size_t workspace_bytes, void *hip_stream, sol_graph **out);
 sol_status sol_graph_launch(sol_graph *graph, void *hip_stream);
 void sol_graph_destroy(sol_graph *graph);
+
+/* Depth-first layer pairs (the paper's layer-chain fusion, Sec. III-A and IV): when a network keeps no
+ * activations (flags 0), a bf16 7x7 stride-2 convolution of a 3-channel input with 64 filters, ReLU and no
+ * residual whose only consumer is a 3x3 stride-2 pad-1 max-pool LAYER runs in one kernel with that pool; the
+ * convolution's output is never stored.  *into = index of the layer whose launch produces `layer`'s output:
+ * `layer` itself, or layer - 1 for such a pool layer (sol_network_run_layer on it launches nothing; the layer
+ * in front writes its output). */
+sol_status sol_network_layer_fused_into(const sol_network *net, int layer, int *into);
 
 /* Runs one layer only, on whatever its producers left in the workspace (profiling aid: lets a caller
  * bracket a single layer with events).  Same arguments as sol_network_forward. */

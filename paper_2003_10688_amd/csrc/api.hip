@@ -71,15 +71,29 @@ static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, cons
                 "filter %dx%d larger than padded input %dx%d", cd.kh, cd.kw, xd.h + 2 * cd.ph, xd.w + 2 * cd.pw);
     ConvArgs a;
     memset(static_cast<void *>(&a), 0, sizeof(a));
+    a.N = xd.n; a.H = xd.h; a.W = xd.w; a.C = xd.c;
+    a.Cout = cd.cout; a.R = cd.kh; a.S = cd.kw; a.sh = cd.sh; a.sw = cd.sw; a.ph = cd.ph; a.pw = cd.pw;
+    a.Ho = Ho; a.Wo = Wo;
+    a.Kp = packed_k(cd, xd.dtype);
+    a.Ktot = cd.kh * cd.kw * cd.cin;
+    a.act = act;
+    a.res = res;
     a.pool = 0;
     a.Hy = Ho; a.Wy = Wo;
     if (pool && pool->kind != SOL_POOL_NONE) {
         SOL_TRY(check_pool(pool));
-        SOL_REQUIRE(pool_is_fusable(*pool), SOL_ERR_UNSUPPORTED,
-                    "only a 2x2 stride-2 unpadded pool can be fused into the convolution; run sol_pool separately");
-        a.pool = pool->kind == SOL_POOL_MAX ? 1 : 2;
-        a.Hy = Ho / 2; a.Wy = Wo / 2;
-        SOL_REQUIRE(a.Hy > 0 && a.Wy > 0, SOL_ERR_SHAPE, "conv output %dx%d too small for a 2x2 pool", Ho, Wo);
+        if (pool_is_fusable(*pool)) {
+            a.pool = pool->kind == SOL_POOL_MAX ? 1 : 2;
+            a.Hy = Ho / 2; a.Wy = Wo / 2;
+            SOL_REQUIRE(a.Hy > 0 && a.Wy > 0, SOL_ERR_SHAPE, "conv output %dx%d too small for a 2x2 pool", Ho, Wo);
+        } else {
+            SOL_REQUIRE(stem_pool_applies(a, xd.dtype, *pool), SOL_ERR_UNSUPPORTED,
+                        "a pool fused into the convolution is 2x2 stride 2 unpadded, or a 3x3 stride-2 pad-1 max pool behind a bf16 "
+                        "7x7 stride-2 convolution of 3 channels with 64 filters, ReLU and no residual; run sol_pool separately");
+            SOL_REQUIRE(!argmax && !prepool, SOL_ERR_UNSUPPORTED, "the fused stem pool stores neither winners nor the pre-pool tensor");
+            a.pool = 3;
+            a.Hy = out_size(Ho, 3, 2, 1); a.Wy = out_size(Wo, 3, 2, 1);
+        }
     }
     SOL_REQUIRE((double)xd.n * Ho * Wo * cd.cout < 2147483648.0, SOL_ERR_UNSUPPORTED, "output has 2^31 elements or more");
     if (xd.n == 0) return SOL_OK;
@@ -87,21 +101,17 @@ static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, cons
     SOL_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(scale) && aligned16(shift) && aligned16(res) &&
                     aligned16(argmax) && aligned16(prepool),
                 SOL_ERR_ALIGN, "device pointers must be 16-byte aligned");
-    a.x = x; a.w = w; a.scale = scale; a.shift = shift; a.res = res; a.y = y;
+    a.x = x; a.w = w; a.scale = scale; a.shift = shift; a.y = y;
+    const bool quad = a.pool == 1 || a.pool == 2;
     a.argmax = a.pool == 1 ? argmax : nullptr;
-    a.prepool = a.pool ? prepool : nullptr;
+    a.prepool = quad ? prepool : nullptr;
 #ifdef SOL_PHASE_TIMING
     a.prepool = prepool;   // profiling build: receives per-phase cycle counts
 #endif
-    a.N = xd.n; a.H = xd.h; a.W = xd.w; a.C = xd.c;
-    a.Cout = cd.cout; a.R = cd.kh; a.S = cd.kw; a.sh = cd.sh; a.sw = cd.sw; a.ph = cd.ph; a.pw = cd.pw;
-    a.Ho = Ho; a.Wo = Wo;
-    a.P = a.pool ? xd.n * a.Hy * a.Wy * 4 : xd.n * Ho * Wo;
-    a.Kp = packed_k(cd, xd.dtype);
-    a.Ktot = cd.kh * cd.kw * cd.cin;
-    a.act = act;
-    a.dw = FastDiv((uint32_t)(a.pool ? a.Wy : Wo));
-    a.dh = FastDiv((uint32_t)(a.pool ? a.Hy : Ho));
+    a.P = quad ? xd.n * a.Hy * a.Wy * 4 : xd.n * Ho * Wo;
+    a.dw = FastDiv((uint32_t)(quad ? a.Wy : Wo));
+    a.dh = FastDiv((uint32_t)(quad ? a.Hy : Ho));
+    if (a.pool == 3) return launch_conv_stem_pool(a, st);   // one kernel, no tile choice
     return launch_conv(a, xd.dtype, tile, st);
 }
 
@@ -154,6 +164,7 @@ struct LayerPlan {
     sol_conv_desc cd;               // CONV / LINEAR (as 1x1)
     int src, res;                   // resolved producer indices, -1 = network input
     bool fuse_pool, split_pool;     // CONV with pool: fused into the epilogue, or run as a second launch
+    bool absorbs_next, elided;      // a stem convolution that also computes the max-pool layer behind it / that pool layer
     size_t w_off, scale_off, shift_off;
     size_t out_off, tmp_off;        // workspace offsets; out_off unused for the last layer
     int last_use;
@@ -266,6 +277,17 @@ static sol_status plan_training(sol_network *net, Arena &ar) {
     return SOL_OK;
 }
 
+// can this convolution layer run fused with the 3x3 stride-2 max pool `p` behind it (conv_stem_pool_kernel)?
+static bool stem_pool_plan_ok(const sol_tensor_desc &in, const sol_conv_desc &cd, const sol_layer &L, const sol_pool_desc &p) {
+    ConvArgs a;
+    memset(static_cast<void *>(&a), 0, sizeof(a));
+    a.N = in.n; a.H = in.h; a.W = in.w; a.C = in.c;
+    a.Cout = cd.cout; a.R = cd.kh; a.S = cd.kw; a.sh = cd.sh; a.sw = cd.sw; a.ph = cd.ph; a.pw = cd.pw;
+    a.Kp = packed_k(cd, in.dtype);
+    a.act = L.act;
+    return L.res < 0 && stem_pool_applies(a, in.dtype, p);
+}
+
 static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_layers) {
     const int dt = net->input.dtype;
     net->layers.resize(n_layers);
@@ -297,7 +319,7 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
                             "layer %d: training networks take the pool as a layer of its own", i);
                 if (L.pool.kind != SOL_POOL_NONE) {
                     SOL_TRY(check_pool(&L.pool));
-                    lp.fuse_pool = pool_is_fusable(L.pool);
+                    lp.fuse_pool = pool_is_fusable(L.pool) || stem_pool_plan_ok(lp.in, lp.cd, L, L.pool);
                     lp.split_pool = !lp.fuse_pool;
                     SOL_REQUIRE(lp.conv_out.h + 2 * L.pool.ph >= L.pool.kh && lp.conv_out.w + 2 * L.pool.pw >= L.pool.kw,
                                 SOL_ERR_SHAPE, "layer %d: pool window larger than its input", i);
@@ -396,16 +418,33 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
     }
     net->param_bytes = poff;
 
+    // Depth-first pair (the paper's layer-chain fusion, Sec. III-A / IV): a stem convolution whose output feeds
+    // nothing but the max-pool layer behind it runs in one kernel with that pool; the convolution's output, the
+    // largest tensor of the list, never exists.  Not when every activation is kept for the caller or for training.
+    if (!net->training && !net->keep)
+        for (int i = 0; i + 1 < n_layers; i++) {
+            LayerPlan &c = net->layers[i], &q = net->layers[i + 1];
+            if (c.L.kind == SOL_LAYER_CONV && c.L.pool.kind == SOL_POOL_NONE && q.L.kind == SOL_LAYER_POOL && q.src == i &&
+                c.last_use == i + 1 && stem_pool_plan_ok(c.in, c.cd, c.L, q.L.pool)) {
+                c.absorbs_next = true;
+                q.elided = true;
+            }
+        }
+
     // activation layout: inference reuses buffers once their last consumer has run, training keeps all
     Arena ar;
     for (int i = 0; i < n_layers; i++) {
         LayerPlan &lp = net->layers[i];
         if (lp.split_pool) lp.tmp_off = ar.alloc(tensor_bytes(lp.conv_out));
-        if (i + 1 < n_layers || net->training) lp.out_off = ar.alloc(tensor_bytes(lp.out));
+        if (lp.absorbs_next) {          // writes the pool layer's output: that buffer has to exist while this layer runs
+            if (i + 2 < n_layers) net->layers[i + 1].out_off = ar.alloc(tensor_bytes(net->layers[i + 1].out));
+        } else if (!lp.elided && (i + 1 < n_layers || net->training)) {
+            lp.out_off = ar.alloc(tensor_bytes(lp.out));
+        }
         if (lp.split_pool && !net->keep) ar.release(lp.tmp_off);
         if (!net->keep)
             for (int j = 0; j < i; j++)
-                if (net->layers[j].last_use == i && j + 1 < n_layers) ar.release(net->layers[j].out_off);
+                if (net->layers[j].last_use == i && j + 1 < n_layers && !net->layers[j].absorbs_next) ar.release(net->layers[j].out_off);
     }
     if (net->training) SOL_TRY(plan_training(net, ar));
     net->ws_bytes = ar.top;
@@ -784,16 +823,19 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
     }
     for (int i = first; i <= last; i++) {
         const LayerPlan &lp = net->layers[i];
+        if (lp.elided) continue;                            // computed by the convolution in front of it
         const void *in = layer_in(net, lp.src, x, ws);
-        void *out = i + 1 == nl ? y : static_cast<void *>(ws + lp.out_off);
+        const int oi = lp.absorbs_next ? i + 1 : i;         // the layer whose output this launch writes
+        void *out = oi + 1 == nl ? y : static_cast<void *>(ws + net->layers[oi].out_off);
         switch (lp.L.kind) {
             case SOL_LAYER_CONV: {
                 const float *scale = reinterpret_cast<const float *>(net->params + lp.scale_off);
                 const float *shift = reinterpret_cast<const float *>(net->params + lp.shift_off);
                 const void *res = lp.res >= 0 ? layer_in(net, lp.res, x, ws) : nullptr;
                 void *conv_dst = lp.split_pool ? static_cast<void *>(ws + lp.tmp_off) : out;
+                const sol_pool_desc *fused = lp.absorbs_next ? &net->layers[i + 1].L.pool : lp.fuse_pool ? &lp.L.pool : nullptr;
                 SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, scale, shift, res, lp.L.act,
-                                        lp.fuse_pool ? &lp.L.pool : nullptr, conv_dst, nullptr, nullptr,
+                                        fused, conv_dst, nullptr, nullptr,
                                         g_tile_override ? g_tile_override : lp.tile, st));
                 if (lp.split_pool) SOL_TRY(pool_impl(lp.conv_out, conv_dst, lp.L.pool, out, nullptr, st));
                 break;
@@ -931,6 +973,7 @@ sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *
     for (int i = 0; i < nl && rs == SOL_OK; i++) {
         LayerPlan &lp = net->layers[i];
         if (lp.L.kind != SOL_LAYER_CONV || lp.in.n == 0) continue;
+        if (lp.absorbs_next || (lp.fuse_pool && !pool_is_fusable(lp.L.pool))) continue;   // stem + pool: one kernel, nothing to choose
         float best = 0.f;
         rs = time_layer(i, &best);                            // the shape heuristic's choice is the incumbent
         if (rs != SOL_OK) break;
@@ -1007,6 +1050,13 @@ void sol_graph_destroy(sol_graph *g) {
     if (!g) return;
     hipGraphExecDestroy(g->exec);
     delete g;
+}
+
+sol_status sol_network_layer_fused_into(const sol_network *net, int layer, int *into) {
+    SOL_REQUIRE(net && into, SOL_ERR_NULL, "net / into is NULL");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    *into = net->layers[layer].elided ? layer - 1 : layer;
+    return SOL_OK;
 }
 
 sol_status sol_network_run_layer(sol_network *net, int layer, const void *x, void *y, void *workspace,

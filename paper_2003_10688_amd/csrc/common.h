@@ -101,7 +101,7 @@ struct ConvArgs {
     int P;                   // GEMM rows: N*Ho*Wo, or N*Hy*Wy*4 with a fused 2x2 pool
     int Kp;                  // padded reduction length of a packed weight row
     int Ktot;                // R*S*C
-    int act, pool;           // pool: 0 none, 1 max 2x2/2, 2 avg 2x2/2
+    int act, pool;           // pool: 0 none, 1 max 2x2/2, 2 avg 2x2/2 (in the epilogue of any kernel), 3 max 3x3/2 pad 1 (stem-pool kernel only)
     int ntc;                 // number of channel tiles (set by the launcher)
     int ntiles;
     int cpx;                 // > 0: each XCD owns cpx channel tiles (all pixel tiles); 0: a contiguous run of tiles
@@ -152,6 +152,8 @@ int halo_choose_tile(const ConvArgs &a);
 sol_status launch_conv_halo(const ConvArgs &a, int tile, hipStream_t st);
 bool stem_kernel_applies(const ConvArgs &a, int dt);
 sol_status launch_conv_stem(const ConvArgs &a, hipStream_t st);
+bool stem_pool_applies(const ConvArgs &a, int dt, const sol_pool_desc &p);   // stem + ReLU + 3x3/2 max pool in one kernel
+sol_status launch_conv_stem_pool(const ConvArgs &a, hipStream_t st);
 bool linear_kernel_applies(const ConvArgs &a, int dt);
 sol_status launch_linear(const ConvArgs &a, int dt, hipStream_t st);
 sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t st);

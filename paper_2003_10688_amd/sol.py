@@ -338,6 +338,13 @@ class Network:
             return self.y
         return launch
 
+    def fused_into(self, layer):
+        """Index of the layer whose launch produces `layer`'s output (itself unless the plan fused it into
+        the layer in front, as for the max pool behind a stem convolution)."""
+        t = C.c_int(0)
+        _check(lib().sol_network_layer_fused_into(self._h, C.c_int(layer), C.byref(t)))
+        return t.value
+
     def run_layer(self, layer, x, stream=None):
         """Runs one layer on whatever its producers left in the workspace (profiling aid)."""
         _check(lib().sol_network_run_layer(self._h, C.c_int(layer), _ptr(x), _ptr(self.y), _ptr(self.workspace),

@@ -130,6 +130,45 @@ def test_plan_tile_api_validates(sol):
     L.sol_network_destroy(h)
 
 
+def test_plan_fuses_stem_and_pool_only_when_it_may(sol):
+    """The depth-first stem + max-pool pair is a plan-time decision taken on the host: bf16 7x7/2 stem with 64
+    filters and ReLU whose only consumer is a 3x3/2 pad-1 max-pool layer, and no kept activations."""
+    L = sol.lib()
+    t = C.c_int(-1)
+
+    def fused(layers, shape, dt, flags=0):
+        st, h = _create(sol, layers, shape, dt, flags)
+        assert st == 0
+        r = []
+        for i in range(len(layers)):
+            assert L.sol_network_layer_fused_into(h, i, C.byref(t)) == 0
+            r.append(t.value)
+        assert L.sol_network_layer_fused_into(h, len(layers), C.byref(t)) == 2
+        ws = L.sol_network_workspace_bytes(h)
+        L.sol_network_destroy(h)
+        return r, ws
+
+    wk = wl.config(3)
+    n = len(wk.layers)
+    r, ws = fused(wk.layers, wk.in_shape, sol.BF16)
+    assert r == [0, 0] + list(range(2, n))
+    r_keep, ws_keep = fused(wk.layers, wk.in_shape, sol.BF16, sol.NET_KEEP_ACTIVATIONS)
+    assert r_keep == list(range(n)) and ws_keep > ws
+    assert fused(wk.layers, wk.in_shape, sol.BF16, sol.NET_TRAINING)[0] == list(range(n))
+    assert fused(wk.layers, wk.in_shape, sol.F32)[0] == list(range(n))                     # fp32: no stem kernel
+    stem, pool = wl.conv(64, 7, 2, 3), wl.pool("max", 3, 2, 1)
+    tail = [wl.conv(8, 1)]
+    assert fused([stem, pool] + tail, (2, 3, 40, 40), sol.BF16)[0] == [0, 0, 2]
+    assert fused([stem, pool], (2, 3, 40, 40), sol.BF16)[0] == [0, 0]                      # the pool is the network output
+    assert fused([stem, wl.pool("max", 2, 2, 0)] + tail, (2, 3, 40, 40), sol.BF16)[0] == [0, 1, 2]
+    assert fused([stem, wl.pool("avg", 3, 2, 1)] + tail, (2, 3, 40, 40), sol.BF16)[0] == [0, 1, 2]
+    assert fused([wl.conv(32, 7, 2, 3), pool] + tail, (2, 3, 40, 40), sol.BF16)[0] == [0, 1, 2]
+    assert fused([wl.conv(64, 7, 2, 3, act="none"), pool] + tail, (2, 3, 40, 40), sol.BF16)[0] == [0, 1, 2]
+    # a second consumer of the stem's output keeps it alive: no fusion
+    assert fused([stem, pool, wl.conv(8, 1, src=0)], (2, 3, 40, 40), sol.BF16)[0] == [0, 1, 2]
+    assert L.sol_network_layer_fused_into(None, 0, C.byref(t)) == 1
+
+
 def test_depthwise_planning_and_validation(sol):
     """Depthwise layers: shape inference keeps the channel count, parameters are [taps][c] + scale/shift, bad
     descriptors are refused on the host."""

@@ -655,6 +655,67 @@ def test_mlp_workload(sol, batch, features):
             net.layer_output(i).copy_(dev[i])
 
 
+# ---- stem convolution + max pool as one depth-first kernel ---------------------------------------------------------
+STEM_POOL_CASES = [
+    # N, H, W, pad      whole blocks, ragged pool blocks, odd conv extents (last pool window one row short), tiny images
+    (2, 64, 64, 3), (1, 61, 75, 3), (3, 30, 44, 2), (2, 17, 19, 3), (1, 9, 9, 3), (1, 224, 224, 3),
+]
+
+
+@pytest.mark.parametrize("case", STEM_POOL_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_stem_pool_fused(sol, case):
+    """7x7/2 stem + BN + ReLU + 3x3/2 pad-1 max pool in one kernel: against the checker, and bit for bit against
+    the same library's two launches (convolution stored in bf16, then sol_pool)."""
+    N, H, W, p = case
+    rng = np.random.default_rng(1234 + H * W)
+    pd = wl.pool_desc("max", 3, 2, 1)
+    l, x, prm, _ = make_block(sol, rng, "bf16", N, 3, H, W, 64, 7, 2, p, pool=pd)
+    want, _, _ = orc.fused_conv(x, prm, l, None, bf16=True)
+    got, _, _ = run_block(sol, "bf16", l, x, prm, None)
+    assert got.shape == want.shape
+    assert rel_err(got, want) <= TOL["bf16"]
+    conv_only, _, _ = run_block(sol, "bf16", dict(l, pool=None), x, prm, None)
+    two, _ = sol.sol_pool(sol.to_device_nhwc(conv_only, sol.BF16), pd)
+    torch.cuda.synchronize()
+    assert np.array_equal(got, sol.to_host_nchw(two))
+
+
+def test_stem_pool_fused_rejects_what_it_cannot_do(sol):
+    rng = np.random.default_rng(5)
+    pd = wl.pool_desc("max", 3, 2, 1)
+    for kw in (dict(act="none"), dict(res=True), dict(K=32), dict(k=5)):
+        K, k = kw.pop("K", 64), kw.pop("k", 7)
+        l, x, prm, r = make_block(sol, rng, "bf16", 1, 3, 20, 20, K, k, 2, k // 2, pool=pd, **kw)
+        with pytest.raises(sol.SolError) as e:
+            run_block(sol, "bf16", l, x, prm, r)
+        assert e.value.status == 6
+    l, x, prm, r = make_block(sol, rng, "bf16", 1, 3, 20, 20, 64, 7, 2, 3, pool=pd)
+    with pytest.raises(sol.SolError) as e:
+        run_block(sol, "bf16", l, x, prm, r, want_argmax=True)
+    assert e.value.status == 6
+    with pytest.raises(sol.SolError) as e:                                   # average pool of that shape
+        run_block(sol, "bf16", dict(l, pool=wl.pool_desc("avg", 3, 2, 1)), x, prm, r)
+    assert e.value.status == 6
+
+
+def test_network_fuses_stem_and_pool(sol):
+    """A ResNet-shaped list without kept activations runs stem and pool as one launch (the pool layer reports the
+    stem as its producer and launches nothing); same output as the plan that keeps every activation, bit for bit,
+    and as the checker within tolerance."""
+    wk = wl.config(2, batch=3, hw=64)
+    outs, _ = orc.network_forward(wk.layers, wk.params, wk.x, bf16=True, return_all=True)
+    net_keep, y_keep = run_network(sol, wk, keep=True)
+    net, y = run_network(sol, wk, keep=False)
+    kinds = [l["kind"] for l in wk.layers]
+    assert kinds[0] == "conv" and kinds[1] == "pool"
+    assert net.fused_into(1) == 0 and net.fused_into(0) == 0 and net.fused_into(2) == 2
+    assert all(net_keep.fused_into(i) == i for i in range(len(kinds)))
+    assert np.array_equal(y, y_keep)
+    assert norm_err(y.reshape(outs[-1].shape), outs[-1]) <= TOL["bf16"]
+    net.run_layer(1, sol.to_device_nhwc(wk.x, sol.BF16))                      # the elided layer: nothing to run, no error
+    torch.cuda.synchronize()
+
+
 # ---- depthwise convolution (the fusion engine's weighted pooling) -----------------------------------------------
 def make_dw_block(rng, dt, N, C, H, W, k, sh, sw, p, bn=True, act="relu", res=False, bias_std=0.3):
     l = dict(wl.conv(C, k, 1, p, bn=bn, act=act, dw=True), sh=sh, sw=sw)
