@@ -254,6 +254,10 @@ sol_status sol_network_layer_output(const sol_network *net, int layer, void *wor
  * gradients are fp32; activation gradients are stored in the network dtype; a tensor with several
  * consumers accumulates their contributions in descending layer order, the residual consumer of a
  * layer before its convolution.  x, workspace: as passed to the forward.  Deterministic.
+ * The weight-gradient kernels run on a second stream owned by the network (created on the first call,
+ * default priority, destroyed with the network) beside the chain of data gradients; everything is
+ * ordered by events against `hip_stream`, so to the caller the call behaves as if it ran on that stream
+ * alone.  Not capturable into a HIP graph.
  * SOL_ERR_UNSUPPORTED for inference networks. */
 sol_status sol_network_backward(sol_network *net, const void *x, const int32_t *labels, float *loss,
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
