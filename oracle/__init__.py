@@ -215,6 +215,21 @@ def pool(x, pd):
     raise ValueError(pd["kind"])
 
 
+def concat(a, b):
+    """Channel concatenation of two NCHW tensors of equal n, h, w: out[:, :Ca] = a, out[:, Ca:] = b (the join of
+    parallel branches in the SqueezeNet / DenseNet-shaped networks of the paper's evaluation, Sec. VI)."""
+    a, b = _d(a), _d(b)
+    if a.shape[0] != b.shape[0] or a.shape[2:] != b.shape[2:]:
+        raise ValueError(f"concat: {a.shape} vs {b.shape}")
+    out = np.empty((a.shape[0], a.shape[1] + b.shape[1]) + a.shape[2:], np.float64)
+    for n in range(a.shape[0]):
+        for c in range(a.shape[1]):
+            out[n, c] = a[n, c]
+        for c in range(b.shape[1]):
+            out[n, a.shape[1] + c] = b[n, c]
+    return out
+
+
 # ----------------------------------------------------------------- backward layers
 def conv2d_dgrad(dy, w, x_shape, stride=(1, 1), pad=(0, 0)):
     dy, w = _d(dy), _d(w)
@@ -359,6 +374,8 @@ def network_forward(layers, params, x, bf16=False, return_all=False):
             y = gap(src)
             if bf16:
                 y = round_bf16(y)
+        elif l["kind"] == "concat":
+            y = concat(src, outs[l["res"]])             # stored values only move: nothing to round
         elif l["kind"] == "linear":
             y = linear(src.reshape(src.shape[0], -1), params[i]["w"], params[i].get("bias"))
             if l.get("act") == "relu":

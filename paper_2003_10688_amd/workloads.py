@@ -71,6 +71,11 @@ def pool(kind="max", k=2, s=2, p=0, count_pad=1, src=-1):
     return {"kind": "pool", "pool": pool_desc(kind, k, s, p, count_pad), "src": src}
 
 
+def concat(src, res):
+    """Channel concatenation [layer src | layer res] (absolute layer indices; src = -1: the previous layer)."""
+    return {"kind": "concat", "src": src, "res": res}
+
+
 def gap(src=-1):
     return {"kind": "gap", "src": src}
 
@@ -118,6 +123,31 @@ def separable_layers(num_classes=1000, widths=((64, 1), (128, 2), (128, 1), (256
         c = width
     L.append(gap())
     L.append(linear(num_classes))
+    return L
+
+
+def fire_layers(base, src, squeeze, expand):
+    """One fire module appended behind layer `src` (base = index the first new layer will get): 1x1 squeeze + ReLU,
+    then a 1x1 and a 3x3 expand + ReLU side by side on the squeezed tensor, joined by channel concatenation."""
+    return [conv(squeeze, 1, p=0, bn=False, src=src),
+            conv(expand, 1, p=0, bn=False, src=base),
+            conv(expand, 3, bn=False, src=base),
+            concat(base + 1, base + 2)]
+
+
+def squeezenet_layers(num_classes=1000):
+    """Config 7: a SqueezeNet-1.1-shaped list (one of the evaluation networks of the paper, Sec. VI, where the
+    branches of every fire module are joined by a channel concatenation): 3x3 stride-2 stem of 64 filters, then
+    max pools (3x3 stride 2, floor mode here) and eight fire modules, a 1x1 classifier convolution + ReLU and a
+    global average pool.  No batch norm: bias + ReLU epilogues."""
+    L = [conv(64, 3, s=2, p=0, bn=False), pool("max", 3, 2, 0)]
+    for group in (((16, 64), (16, 64)), ((32, 128), (32, 128)), ((48, 192), (48, 192), (64, 256), (64, 256))):
+        for sq, ex in group:
+            L += fire_layers(len(L), len(L) - 1, sq, ex)
+        if group[0][0] != 48:
+            L.append(pool("max", 3, 2, 0))
+    L.append(conv(num_classes, 1, p=0, bn=False))
+    L.append(gap())
     return L
 
 
@@ -184,6 +214,8 @@ def layer_channels(layers, cin):
             ch.append(l["cout"])
         elif l["kind"] == "linear":
             ch.append(l["out"])
+        elif l["kind"] == "concat":
+            ch.append(c_in + ch[l["res"]])
         else:
             ch.append(c_in)
     return ch
@@ -270,7 +302,7 @@ class Workload:
 
 
 def config(idx: int, batch: int | None = None, hw: int | None = None, dtype: str | None = None) -> Workload:
-    """The five configurations of the benchmark plus the paper's MLP workload (5) and a depthwise-separable chain (6); ``batch`` / ``hw`` shrink a config for parity tests and ``dtype``
+    """The five configurations of the benchmark plus the paper's MLP workload (5), a depthwise-separable chain (6) and a SqueezeNet-shaped list with channel concatenations (7); ``batch`` / ``hw`` shrink a config for parity tests and ``dtype``
     overrides its storage type (same seed, same layer list)."""
     wk = _config(idx, batch, hw)
     if dtype is not None:
@@ -299,4 +331,6 @@ def _config(idx, batch, hw):
         return Workload("mlp3_bf16", mlp_layers(hw or 8192), (batch or 64, hw or 8192, 1, 1), "bf16", seed, "normal")
     if idx == 6:
         return Workload("separable_bf16", separable_layers(), (batch or 64, 3, hw or 224, hw or 224), "bf16", seed, "normal")
+    if idx == 7:
+        return Workload("squeezenet_bf16", squeezenet_layers(), (batch or 64, 3, hw or 224, hw or 224), "bf16", seed, "normal")
     raise ValueError(idx)

@@ -137,6 +137,46 @@ def test_dwconv_delta_ones_and_fused_block():
     assert np.array_equal(y, want)
 
 
+# ------------------------------------------------------------------------------- channel concatenation
+def test_concat_placement_linearity_and_in_a_network():
+    a = np.array([1.0, 2.0]).reshape(1, 2, 1, 1)
+    b = np.array([3.0]).reshape(1, 1, 1, 1)
+    assert orc.concat(a, b).ravel().tolist() == [1.0, 2.0, 3.0] and orc.concat(b, a).ravel().tolist() == [3.0, 1.0, 2.0]
+    a, b = R.standard_normal((2, 3, 4, 5)), R.standard_normal((2, 2, 4, 5))
+    c = orc.concat(a, b)
+    assert np.array_equal(c, torch.cat([T(a), T(b)], 1).numpy())                      # the library's routine
+    # a 1x1 convolution of a concatenation is the sum of the 1x1 convolutions of its parts with the split filter
+    w = R.standard_normal((4, 5, 1, 1))
+    whole = orc.conv2d(c, w, None, (1, 1), (0, 0))
+    parts = orc.conv2d(a, w[:, :3], None, (1, 1), (0, 0)) + orc.conv2d(b, w[:, 3:], None, (1, 1), (0, 0))
+    assert np.allclose(whole, parts, rtol=1e-13, atol=1e-13)
+    with pytest.raises(ValueError):
+        orc.concat(a, R.standard_normal((2, 2, 4, 6)))
+    # inside a layer list: a fire module equals its pieces composed by hand
+    layers = wl.fire_layers(0, -1, 4, 6)
+    prm = wl.make_params(layers, 3, 77, bias_std=0.3)
+    x = R.standard_normal((2, 3, 6, 6))
+    outs, _ = orc.network_forward(layers, prm, x, return_all=True)
+    sq = orc.relu(orc.conv2d(x, prm[0]["w"], prm[0]["bias"], (1, 1), (0, 0)))
+    e1 = orc.relu(orc.conv2d(sq, prm[1]["w"], prm[1]["bias"], (1, 1), (0, 0)))
+    e3 = orc.relu(orc.conv2d(sq, prm[2]["w"], prm[2]["bias"], (1, 1), (1, 1)))
+    assert outs[3].shape == (2, 12, 6, 6)
+    assert np.array_equal(outs[3][:, :6], e1) and np.array_equal(outs[3][:, 6:], e3)
+
+
+def test_squeezenet_shaped_list_is_wired_like_the_published_network():
+    """Channel counts after every fire module and the classifier, as published for SqueezeNet 1.1."""
+    L = wl.squeezenet_layers()
+    ch = wl.layer_channels(L, 3)
+    joins = [ch[i] for i, l in enumerate(L) if l["kind"] == "concat"]
+    assert joins == [128, 128, 256, 256, 384, 384, 512, 512]
+    assert sum(l["kind"] == "pool" for l in L) == 3 and ch[-1] == 1000 and L[-1]["kind"] == "gap"
+    for i, l in enumerate(L):
+        if l["kind"] == "concat":                        # both inputs are the expand convolutions of one squeeze layer
+            assert L[l["src"]]["src"] == L[l["res"]]["src"] == l["src"] - 1
+            assert (L[l["src"]]["kh"], L[l["res"]]["kh"]) == (1, 3)
+
+
 # ------------------------------------------------------------------------------- BN, ReLU
 def test_bn_identity_and_affine():
     x = R.standard_normal((2, 3, 4, 4))
