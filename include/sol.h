@@ -47,7 +47,8 @@ typedef enum {
 typedef enum { SOL_F32 = 0, SOL_BF16 = 1 } sol_dtype;  /* bf16 = bf16 storage, fp32 accumulate */
 typedef enum { SOL_ACT_NONE = 0, SOL_ACT_RELU = 1 } sol_act;
 typedef enum { SOL_POOL_NONE = 0, SOL_POOL_MAX = 1, SOL_POOL_AVG = 2 } sol_pool_kind;
-typedef enum { SOL_LAYER_CONV = 0, SOL_LAYER_POOL = 1, SOL_LAYER_GAP = 2, SOL_LAYER_LINEAR = 3, SOL_LAYER_DWCONV = 4 } sol_layer_kind;
+typedef enum { SOL_LAYER_CONV = 0, SOL_LAYER_POOL = 1, SOL_LAYER_GAP = 2, SOL_LAYER_LINEAR = 3, SOL_LAYER_DWCONV = 4,
+               SOL_LAYER_CONCAT = 5 } sol_layer_kind;
 
 /* sliding-window pooling; floor-mode output size; count_pad selects the average-pool divisor
  * (window area vs. number of in-range elements), the switch of the paper's pooling description
@@ -57,7 +58,10 @@ typedef struct { int n, h, w, c; int dtype; } sol_tensor_desc;       /* dense NH
 typedef struct { int cout, cin, kh, kw, sh, sw, ph, pw; } sol_conv_desc;
 
 /* one entry of a layer list; src / res are absolute indices of the producing layer
- * (src = -1: previous layer, or the network input for layer 0; res = -1: no residual) */
+ * (src = -1: previous layer, or the network input for layer 0; res = -1: no residual).
+ * CONCAT: output channels = [channels of layer src | channels of layer res], two different earlier layers of
+ * equal n, h, w (the join of parallel branches in the SqueezeNet / DenseNet-shaped networks of the paper's
+ * evaluation, Sec. VI); inference networks only; no parameters. */
 typedef struct {
     int kind;               /* sol_layer_kind */
     sol_conv_desc conv;     /* CONV, DWCONV: cin is inferred and may be 0 (DWCONV: cout too) */
@@ -228,6 +232,13 @@ void sol_graph_destroy(sol_graph *graph);
  * `layer` itself, or layer - 1 for such a pool layer (sol_network_run_layer on it launches nothing; the layer
  * in front writes its output). */
 sol_status sol_network_layer_fused_into(const sol_network *net, int layer, int *into);
+
+/* Concatenation in place: when a network keeps no activations, a convolution (no fused pool, channel count a
+ * multiple of 8) whose output is read by one CONCAT layer only writes its channels straight into that layer's
+ * buffer, provided its slice starts on a multiple of 8 channels and the joined count is one too; the other
+ * inputs are copied into place when the CONCAT layer runs.  *parts = how many of the two inputs of CONCAT layer
+ * `layer` are written in place (2: the layer launches nothing).  SOL_ERR_SHAPE if `layer` is not a CONCAT. */
+sol_status sol_network_concat_in_place(const sol_network *net, int layer, int *parts);
 
 /* Runs one layer only, on whatever its producers left in the workspace (profiling aid: lets a caller
  * bracket a single layer with events).  Same arguments as sol_network_forward. */

@@ -63,7 +63,7 @@ static bool pool_is_fusable(const sol_pool_desc &p) {
 static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, const sol_conv_desc &cd, const void *w,
                                   const float *scale, const float *shift, const void *res, int act,
                                   const sol_pool_desc *pool, void *y, int32_t *argmax, void *prepool, int tile,
-                                  hipStream_t st) {
+                                  hipStream_t st, int ldy = 0) {   // ldy: elements between output pixels in y, 0 = cout (dense)
     SOL_REQUIRE(cd.cin == xd.c, SOL_ERR_SHAPE, "conv cin %d != input channels %d", cd.cin, xd.c);
     SOL_REQUIRE(act == SOL_ACT_NONE || act == SOL_ACT_RELU, SOL_ERR_SHAPE, "bad activation %d", act);
     const int Ho = out_size(xd.h, cd.kh, cd.sh, cd.ph), Wo = out_size(xd.w, cd.kw, cd.sw, cd.pw);
@@ -95,7 +95,14 @@ static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, cons
             a.Hy = out_size(Ho, 3, 2, 1); a.Wy = out_size(Wo, 3, 2, 1);
         }
     }
-    SOL_REQUIRE((double)xd.n * Ho * Wo * cd.cout < 2147483648.0, SOL_ERR_UNSUPPORTED, "output has 2^31 elements or more");
+    a.ldy = cd.cout;
+    if (ldy != 0 && ldy != cd.cout) {
+        SOL_REQUIRE(ldy > cd.cout && ldy % 8 == 0 && cd.cout % 8 == 0, SOL_ERR_SHAPE,
+                    "output pitch %d: a multiple of 8 above cout (%d, itself a multiple of 8)", ldy, cd.cout);
+        SOL_REQUIRE(a.pool == 0, SOL_ERR_UNSUPPORTED, "a convolution with a fused pool writes a dense output");
+        a.ldy = ldy;
+    }
+    SOL_REQUIRE((double)xd.n * Ho * Wo * a.ldy < 2147483648.0, SOL_ERR_UNSUPPORTED, "output spans 2^31 elements or more");
     if (xd.n == 0) return SOL_OK;
     SOL_REQUIRE(x && w && y, SOL_ERR_NULL, "x, w_packed and y must not be NULL");
     SOL_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(scale) && aligned16(shift) && aligned16(res) &&
@@ -165,6 +172,10 @@ struct LayerPlan {
     int src, res;                   // resolved producer indices, -1 = network input
     bool fuse_pool, split_pool;     // CONV with pool: fused into the epilogue, or run as a second launch
     bool absorbs_next, elided;      // a stem convolution that also computes the max-pool layer behind it / that pool layer
+    int nuse;                       // how many layer inputs (src or res) read this layer's output
+    int cout_real, cin_real;        // CONV: channel counts of the caller's weights when the plan padded cd.cout / cd.cin (else 0)
+    int concat_into, concat_off;    // CONV: writes its output as channels concat_off.. of that CONCAT layer's buffer (-1: own buffer)
+    bool prealloc;                  // CONCAT: buffer laid out when its first in-place producer ran
     size_t w_off, scale_off, shift_off;
     size_t out_off, tmp_off;        // workspace offsets; out_off unused for the last layer
     int last_use;
@@ -307,6 +318,26 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
     const int dt = net->input.dtype;
     net->layers.resize(n_layers);
     size_t poff = 0;
+    // Channel padding (the paper's layout selection, Sec. III-A: feed every layer the layout it is fastest with).  The
+    // fast convolution kernels fetch the reduction in 64-byte runs of channels; a producer with, say, 16 or 48
+    // filters would push every convolution behind it onto the element-gather path (5-10x slower).  Such a
+    // convolution, when only convolutions read it, stores its output with the channel count rounded up to 32: its
+    // extra filters and its consumers' extra input channels are zero weights, so every real value is unchanged.
+    std::vector<int> pad_to(n_layers, 0);
+    if (!net->training && !net->keep)
+        for (int i = 0; i + 1 < n_layers; i++) {
+            const sol_layer &L = layers[i];
+            if (L.kind != SOL_LAYER_CONV || L.pool.kind != SOL_POOL_NONE || L.res >= 0 || L.conv.cout < 16 || L.conv.cout % 32 == 0) continue;
+            int readers = 0;
+            bool ok = true;
+            for (int j = i + 1; j < n_layers; j++) {
+                const int sj = layers[j].src == -1 ? j - 1 : layers[j].src;
+                if (sj == i) { readers++; ok = ok && layers[j].kind == SOL_LAYER_CONV; }
+                if (layers[j].res == i && (layers[j].kind == SOL_LAYER_CONV || layers[j].kind == SOL_LAYER_DWCONV ||
+                                           layers[j].kind == SOL_LAYER_CONCAT)) ok = false;
+            }
+            if (ok && readers > 0) pad_to[i] = (int)round_up((size_t)L.conv.cout, 32);
+        }
     for (int i = 0; i < n_layers; i++) {
         LayerPlan &lp = net->layers[i];
         memset(&lp, 0, sizeof(lp));
@@ -315,6 +346,7 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
         SOL_REQUIRE(L.src >= -1 && L.src < i, SOL_ERR_SHAPE, "layer %d: src %d must name an earlier layer", i, L.src);
         lp.src = L.src == -1 ? i - 1 : L.src;
         lp.res = -1;
+        lp.concat_into = -1;
         lp.in = lp.src < 0 ? net->input : net->layers[lp.src].out;
         lp.out = lp.in;
         lp.last_use = i;
@@ -322,6 +354,8 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             case SOL_LAYER_CONV: {
                 lp.cd = L.conv;
                 lp.cd.cin = lp.in.c;
+                if (lp.src >= 0 && net->layers[lp.src].cout_real) lp.cin_real = net->layers[lp.src].cout_real;
+                if (pad_to[i]) { lp.cout_real = lp.cd.cout; lp.cd.cout = pad_to[i]; }
                 SOL_TRY(check_conv(&lp.cd));
                 SOL_REQUIRE(lp.in.h + 2 * lp.cd.ph >= lp.cd.kh && lp.in.w + 2 * lp.cd.pw >= lp.cd.kw, SOL_ERR_SHAPE,
                             "layer %d: filter larger than padded input", i);
@@ -386,6 +420,18 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             case SOL_LAYER_GAP:
                 lp.out.h = lp.out.w = 1;
                 break;
+            case SOL_LAYER_CONCAT: {
+                SOL_REQUIRE(!net->training, SOL_ERR_UNSUPPORTED, "layer %d: concatenations are inference-only", i);
+                SOL_REQUIRE(lp.src >= 0 && L.res >= 0 && L.res < i && L.res != lp.src, SOL_ERR_SHAPE,
+                            "layer %d: a concatenation joins two different earlier layers (src %d, res %d)", i, lp.src, L.res);
+                const sol_tensor_desc &b = net->layers[L.res].out;
+                SOL_REQUIRE(b.n == lp.in.n && b.h == lp.in.h && b.w == lp.in.w, SOL_ERR_SHAPE,
+                            "layer %d: concatenation of [%d,%d,%d,%d] and [%d,%d,%d,%d]", i, lp.in.n, lp.in.h, lp.in.w, lp.in.c, b.n,
+                            b.h, b.w, b.c);
+                lp.res = L.res;
+                lp.out.c = lp.in.c + b.c;
+                break;
+            }
             case SOL_LAYER_LINEAR:
                 SOL_REQUIRE(L.out_features > 0, SOL_ERR_SHAPE, "layer %d: out_features %d", i, L.out_features);
                 SOL_REQUIRE(lp.in.h == 1 && lp.in.w == 1, SOL_ERR_UNSUPPORTED,
@@ -428,8 +474,8 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
                 }
             }
         }
-        if (lp.src >= 0) net->layers[lp.src].last_use = i;
-        if (lp.res >= 0) net->layers[lp.res].last_use = std::max(net->layers[lp.res].last_use, i);
+        if (lp.src >= 0) { net->layers[lp.src].last_use = i; net->layers[lp.src].nuse++; }
+        if (lp.res >= 0) { net->layers[lp.res].last_use = std::max(net->layers[lp.res].last_use, i); net->layers[lp.res].nuse++; }
     }
     net->param_bytes = poff;
 
@@ -446,6 +492,26 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             }
         }
 
+    // Concatenation in place: a convolution whose output is read by one concatenation only writes its channels
+    // straight into that layer's buffer (row pitch = the joined channel count), so the join costs nothing.  Slices
+    // start and end on 16-byte boundaries; anything else (pools, depthwise layers, shared producers, kept
+    // activations) is copied into place when the concatenation layer runs.
+    if (!net->training && !net->keep)
+        for (int i = 0; i < n_layers; i++) {
+            LayerPlan &cc = net->layers[i];
+            if (cc.L.kind != SOL_LAYER_CONCAT || cc.out.c % 8 != 0) continue;
+            int off = 0;
+            for (int part : {cc.src, cc.res}) {
+                LayerPlan &p = net->layers[part];
+                if (p.L.kind == SOL_LAYER_CONV && p.L.pool.kind == SOL_POOL_NONE && !p.absorbs_next && p.nuse == 1 &&
+                    p.out.c % 8 == 0 && off % 8 == 0) {
+                    p.concat_into = i;
+                    p.concat_off = off;
+                }
+                off += p.out.c;
+            }
+        }
+
     // activation layout: inference reuses buffers once their last consumer has run, training keeps all
     Arena ar;
     for (int i = 0; i < n_layers; i++) {
@@ -453,13 +519,18 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
         if (lp.split_pool) lp.tmp_off = ar.alloc(tensor_bytes(lp.conv_out));
         if (lp.absorbs_next) {          // writes the pool layer's output: that buffer has to exist while this layer runs
             if (i + 2 < n_layers) net->layers[i + 1].out_off = ar.alloc(tensor_bytes(net->layers[i + 1].out));
-        } else if (!lp.elided && (i + 1 < n_layers || net->training)) {
+        } else if (lp.concat_into >= 0) {   // ... and so does the concatenation's, from its first in-place producer on
+            LayerPlan &cc = net->layers[lp.concat_into];
+            if (!cc.prealloc && lp.concat_into + 1 < n_layers) { cc.out_off = ar.alloc(tensor_bytes(cc.out)); cc.prealloc = true; }
+        } else if (!lp.elided && !lp.prealloc && (i + 1 < n_layers || net->training)) {
             lp.out_off = ar.alloc(tensor_bytes(lp.out));
         }
         if (lp.split_pool && !net->keep) ar.release(lp.tmp_off);
         if (!net->keep)
-            for (int j = 0; j < i; j++)
-                if (net->layers[j].last_use == i && j + 1 < n_layers && !net->layers[j].absorbs_next) ar.release(net->layers[j].out_off);
+            for (int j = 0; j < i; j++) {
+                const LayerPlan &lj = net->layers[j];
+                if (lj.last_use == i && j + 1 < n_layers && !lj.absorbs_next && lj.concat_into < 0) ar.release(lj.out_off);
+            }
     }
     if (net->training) SOL_TRY(plan_training(net, ar));
     net->ws_bytes = ar.top;
@@ -629,7 +700,7 @@ sol_status sol_network_set_params(sol_network *net, int layer, const float *w, c
     if (dwl)
         SOL_TRY(launch_pack_dw(lp.cd.cout, lp.cd.kh * lp.cd.kw, net->input.dtype, w, net->params + lp.w_off, st));
     else
-        SOL_TRY(launch_pack(lp.cd, net->input.dtype, w, net->params + lp.w_off, false, st));
+        SOL_TRY(launch_pack(lp.cd, net->input.dtype, w, net->params + lp.w_off, false, st, lp.cout_real, lp.cin_real));
     if (net->training) {   // fp32 master copies, zero velocities, both packed orientations
         const size_t wn = (size_t)lp.cd.cout * lp.cd.cin * lp.cd.kh * lp.cd.kw * 4, cb = (size_t)lp.cd.cout * 4;
         SOL_HIP(hipMemcpyAsync(net->params + lp.master_off, w, wn, hipMemcpyDeviceToDevice, st));
@@ -645,8 +716,12 @@ sol_status sol_network_set_params(sol_network *net, int layer, const float *w, c
         lp.params_set = true;
         return SOL_OK;
     }
-    SOL_TRY(launch_fold(lp.cd.cout, gamma, beta, mean, var, bias, eps, reinterpret_cast<float *>(net->params + lp.scale_off),
-                        reinterpret_cast<float *>(net->params + lp.shift_off), st));
+    if (lp.cout_real) {     // padding channels: zero filters, shift 0 (scale irrelevant) -> they store 0 with or without ReLU
+        SOL_HIP(hipMemsetAsync(net->params + lp.scale_off, 0, (size_t)lp.cd.cout * 4, st));
+        SOL_HIP(hipMemsetAsync(net->params + lp.shift_off, 0, (size_t)lp.cd.cout * 4, st));
+    }
+    SOL_TRY(launch_fold(lp.cout_real ? lp.cout_real : lp.cd.cout, gamma, beta, mean, var, bias, eps,
+                        reinterpret_cast<float *>(net->params + lp.scale_off), reinterpret_cast<float *>(net->params + lp.shift_off), st));
     lp.params_set = true;
     return SOL_OK;
 }
@@ -875,8 +950,14 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
         const LayerPlan &lp = net->layers[i];
         if (lp.elided) continue;                            // computed by the convolution in front of it
         const void *in = layer_in(net, lp.src, x, ws);
-        const int oi = lp.absorbs_next ? i + 1 : i;         // the layer whose output this launch writes
+        const int oi = lp.absorbs_next ? i + 1 : lp.concat_into >= 0 ? lp.concat_into : i;   // the layer whose buffer this launch writes
         void *out = oi + 1 == nl ? y : static_cast<void *>(ws + net->layers[oi].out_off);
+        const size_t es = dtype_size(lp.in.dtype);
+        int ldy = 0;
+        if (lp.concat_into >= 0) {
+            out = static_cast<unsigned char *>(out) + (size_t)lp.concat_off * es;
+            ldy = net->layers[oi].out.c;
+        }
         switch (lp.L.kind) {
             case SOL_LAYER_CONV: {
                 const float *scale = reinterpret_cast<const float *>(net->params + lp.scale_off);
@@ -886,7 +967,7 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
                 const sol_pool_desc *fused = lp.absorbs_next ? &net->layers[i + 1].L.pool : lp.fuse_pool ? &lp.L.pool : nullptr;
                 SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, scale, shift, res, lp.L.act,
                                         fused, conv_dst, nullptr, nullptr,
-                                        g_tile_override ? g_tile_override : lp.tile, st));
+                                        g_tile_override ? g_tile_override : lp.tile, st, ldy));
                 if (lp.split_pool) SOL_TRY(pool_impl(lp.conv_out, conv_dst, lp.L.pool, out, nullptr, st));
                 break;
             }
@@ -907,6 +988,17 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
             case SOL_LAYER_GAP:
                 if (lp.in.n > 0) SOL_TRY(launch_gap(in, out, lp.in.n, lp.in.h * lp.in.w, lp.in.c, lp.in.dtype, st));
                 break;
+            case SOL_LAYER_CONCAT: {    // only the parts their producers did not write in place
+                int off = 0;
+                for (int part : {lp.src, lp.res}) {
+                    const LayerPlan &p = net->layers[part];
+                    if (p.concat_into != i)
+                        SOL_TRY(launch_concat_copy(layer_in(net, part, x, ws), out, (long)lp.out.n * lp.out.h * lp.out.w, p.out.c,
+                                                   lp.out.c, off, lp.out.dtype, st));
+                    off += p.out.c;
+                }
+                break;
+            }
         }
     }
     return SOL_OK;
@@ -1106,6 +1198,15 @@ sol_status sol_network_layer_fused_into(const sol_network *net, int layer, int *
     SOL_REQUIRE(net && into, SOL_ERR_NULL, "net / into is NULL");
     SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
     *into = net->layers[layer].elided ? layer - 1 : layer;
+    return SOL_OK;
+}
+
+sol_status sol_network_concat_in_place(const sol_network *net, int layer, int *parts) {
+    SOL_REQUIRE(net && parts, SOL_ERR_NULL, "net / parts is NULL");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    const LayerPlan &lp = net->layers[layer];
+    SOL_REQUIRE(lp.L.kind == SOL_LAYER_CONCAT, SOL_ERR_SHAPE, "layer %d is not a concatenation", layer);
+    *parts = (net->layers[lp.src].concat_into == layer) + (net->layers[lp.res].concat_into == layer);
     return SOL_OK;
 }
 

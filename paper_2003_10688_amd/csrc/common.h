@@ -98,6 +98,8 @@ struct ConvArgs {
     int Cout, R, S, sh, sw, ph, pw;
     int Ho, Wo;              // convolution output extent
     int Hy, Wy;              // stored output extent (pooled when pool != 0)
+    int ldy;                 // elements between consecutive output pixels in y: Cout, or more when y is a channel slice of a
+                             // wider tensor (a concatenation written in place); pool == 0 only
     int P;                   // GEMM rows: N*Ho*Wo, or N*Hy*Wy*4 with a fused 2x2 pool
     int Kp;                  // padded reduction length of a packed weight row
     int Ktot;                // R*S*C
@@ -161,7 +163,11 @@ sol_status launch_pool(const PoolArgs &a, int dt, hipStream_t st);
 sol_status launch_dwconv(const DwArgs &a, int dt, hipStream_t st);
 sol_status launch_pack_dw(int C, int taps, int dt, const float *w, void *packed, hipStream_t st);
 sol_status launch_gap(const void *x, void *y, int N, int HW, int C, int dt, hipStream_t st);
-sol_status launch_pack(const sol_conv_desc &cd, int dt, const float *w, void *packed, bool unpack, hipStream_t st);
+// copies a dense [rows][c] tensor into channels off .. off + c - 1 of a [rows][ldy] tensor (one part of a concatenation)
+sol_status launch_concat_copy(const void *x, void *y, long rows, int c, int ldy, int off, int dt, hipStream_t st);
+// cout_real / cin_real > 0: w holds that many filters / input channels, the rest of cd's are zero padding (pack only)
+sol_status launch_pack(const sol_conv_desc &cd, int dt, const float *w, void *packed, bool unpack, hipStream_t st, int cout_real = 0,
+                       int cin_real = 0);
 sol_status launch_fold(int c, const float *gamma, const float *beta, const float *mean, const float *var,
                        const float *bias, float eps, float *scale, float *shift, hipStream_t st);
 

@@ -305,7 +305,7 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
                 if (m >= 0 && nv > 0) {
                     float v[8];
                     finish_row(row, m, v, pre.on ? &pre.r[j][ps] : nullptr);
-                    store8<T>(yg + m * a.Cout + cb, v, nv, vec);
+                    store8<T>(yg + m * a.ldy + cb, v, nv, vec);
                 }
             }
         } else {
@@ -408,7 +408,7 @@ __device__ __forceinline__ void conv_epilogue_auto(const ConvArgs &a, f32x16_t (
                                                    int mw, int cw, const Affine8 &aff, const RowMap &rowmap,
                                                    const ResidualRegs<T, TP, TC> &pre) {
     const bool interior = a.pool == 0 && (a.Cout & 7) == 0 && mw + TP * 32 <= a.P && cw + TC * 32 <= a.Cout;
-    const LinearRowOffset ro{(unsigned)mw * (unsigned)a.Cout, (unsigned)a.Cout};
+    const LinearRowOffset ro{(unsigned)mw * (unsigned)a.ldy, (unsigned)a.ldy};
     if (interior && a.res == nullptr) conv_epilogue_interior<T, TP, TC, false>(a, acc, lds_f, wave, lane, cw, aff, pre, ro);
     else if (interior && pre.on) conv_epilogue_interior<T, TP, TC, true>(a, acc, lds_f, wave, lane, cw, aff, pre, ro);
     else conv_epilogue<T, TP, TC>(a, acc, lds_f, wave, lane, mw, cw, aff, rowmap, pre);

@@ -185,7 +185,7 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
             resregs.on = false;
             if constexpr (INTERIOR) {                                    // branch-free epilogue
                 const int pw = p0 + 2 * wave;     // first output row of this wave's 32 tile rows
-                const StemRowOffset ro{(unsigned)(((n * a.Ho + pw) * a.Wo + q0) * (NC * 32)), (unsigned)a.Wo, (unsigned)(NC * 32)};
+                const StemRowOffset ro{(unsigned)(((n * a.Ho + pw) * a.Wo + q0) * a.ldy), (unsigned)a.Wo, (unsigned)a.ldy};
                 conv_epilogue_interior<bf16_t, 1, NC, false>(a, acc, strip, wave, lane, 0, aff, resregs, ro);
                 __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * NC));           // vmcnt(2 * NC), outside the lane-masked regions below
             } else {

@@ -13,14 +13,15 @@ namespace sol {
 // ---- parameter preparation ------------------------------------------------------------------------
 template <typename T>
 __global__ void pack_weights_kernel(const float *__restrict__ w, T *__restrict__ out, int K, int C, int R,
-                                    int S, int Kp) {
+                                    int S, int Kp, int Kr, int Cr) {
+    // w holds Kr x Cr filters (Kr <= K, Cr <= C): output and input channels the planner added as padding are zero
     const long total = (long)K * Kp;
     for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
         const int k = (int)(i / Kp), j = (int)(i % Kp);
         float v = 0.f;
         if (j < R * S * C) {
             const int c = j % C, tap = j / C, s = tap % S, r = tap / S;
-            v = w[(((long)k * C + c) * R + r) * S + s];
+            if (k < Kr && c < Cr) v = w[(((long)k * Cr + c) * R + r) * S + s];
         }
         Elem<T>::store(out + i, v);
     }
@@ -326,7 +327,38 @@ sol_status launch_gap(const void *x, void *y, int N, int HW, int C, int dt, hipS
     return SOL_OK;
 }
 
-sol_status launch_pack(const sol_conv_desc &cd, int dt, const float *w, void *out, bool unpack, hipStream_t st) {
+// One part of a channel concatenation: x [rows][cv] -> y [rows][ldv] at column offv, in units of V.  The planner
+// lets the producers write their slices themselves whenever it can; this copy is for the parts it cannot (a
+// producer with other consumers, a pool or a depthwise layer in front, kept activations).
+template <typename V>
+__global__ void __launch_bounds__(256) concat_copy_kernel(const V *__restrict__ x, V *__restrict__ y, long total, int cv, int ldv, int offv) {
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const long r = i / cv;
+        const int c = (int)(i - r * cv);
+        y[r * ldv + offv + c] = x[i];
+    }
+}
+
+sol_status launch_concat_copy(const void *x, void *y, long rows, int c, int ldy, int off, int dt, hipStream_t st) {
+    if (rows <= 0 || c <= 0) return SOL_OK;
+    const int es = (int)dtype_size(dt);
+    auto go = [&](auto tag, int unit) {
+        using V = decltype(tag);
+        const long total = rows * (c * es / unit);
+        long blocks = (total + 255) / 256;
+        if (blocks > 16384) blocks = 16384;
+        hipLaunchKernelGGL(concat_copy_kernel<V>, dim3((unsigned)blocks), dim3(256), 0, st, static_cast<const V *>(x), static_cast<V *>(y),
+                           total, c * es / unit, ldy * es / unit, off * es / unit);
+    };
+    if ((c * es) % 16 == 0 && (ldy * es) % 16 == 0 && (off * es) % 16 == 0) go(uint4{}, 16);
+    else if (es == 4) go(uint32_t{}, 4);
+    else go(uint16_t{}, 2);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+sol_status launch_pack(const sol_conv_desc &cd, int dt, const float *w, void *out, bool unpack, hipStream_t st, int cout_real, int cin_real) {
+    const int Kr = cout_real > 0 ? cout_real : cd.cout, Cr = cin_real > 0 ? cin_real : cd.cin;
     const int Kp = packed_k(cd, dt);
     const long total = unpack ? (long)cd.cout * cd.cin * cd.kh * cd.kw : (long)cd.cout * Kp;
     if (total <= 0) return SOL_OK;
@@ -338,14 +370,14 @@ sol_status launch_pack(const sol_conv_desc &cd, int dt, const float *w, void *ou
                                static_cast<const bf16_t *>(out), const_cast<float *>(w), cd.cout, cd.cin, cd.kh, cd.kw, Kp);
         else
             hipLaunchKernelGGL((pack_weights_kernel<bf16_t>), dim3((unsigned)blocks), dim3(256), 0, st, w,
-                               static_cast<bf16_t *>(out), cd.cout, cd.cin, cd.kh, cd.kw, Kp);
+                               static_cast<bf16_t *>(out), cd.cout, cd.cin, cd.kh, cd.kw, Kp, Kr, Cr);
     } else {
         if (unpack)
             hipLaunchKernelGGL((unpack_weights_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, st,
                                static_cast<const float *>(out), const_cast<float *>(w), cd.cout, cd.cin, cd.kh, cd.kw, Kp);
         else
             hipLaunchKernelGGL((pack_weights_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, st, w,
-                               static_cast<float *>(out), cd.cout, cd.cin, cd.kh, cd.kw, Kp);
+                               static_cast<float *>(out), cd.cout, cd.cin, cd.kh, cd.kw, Kp, Kr, Cr);
     }
     SOL_HIP(hipGetLastError());
     return SOL_OK;

@@ -67,7 +67,7 @@ __global__ void __launch_bounds__(512) linear_kernel(const ConvArgs a) {
         t = t * (a.scale ? a.scale[o] : 1.f) + (a.shift ? a.shift[o] : 0.f);
         if (resg) t += Elem<T>::load(resg + (size_t)m * N + o);
         if (a.act == SOL_ACT_RELU) t = t > 0.f ? t : 0.f;
-        Elem<T>::store(yg + (size_t)m * N + o, t);
+        Elem<T>::store(yg + (size_t)m * a.ldy + o, t);
     }
 }
 

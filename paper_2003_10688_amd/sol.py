@@ -17,7 +17,7 @@ LIB_PATH = os.environ.get("SOL_MI355_LIB") or os.path.join(_HERE, "libsol_mi355.
 F32, BF16 = 0, 1
 ACT_NONE, ACT_RELU = 0, 1
 POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
-LAYER_CONV, LAYER_POOL, LAYER_GAP, LAYER_LINEAR, LAYER_DWCONV = 0, 1, 2, 3, 4
+LAYER_CONV, LAYER_POOL, LAYER_GAP, LAYER_LINEAR, LAYER_DWCONV, LAYER_CONCAT = 0, 1, 2, 3, 4, 5
 NET_TRAINING, NET_KEEP_ACTIVATIONS = 1, 2
 NT_W, NT_GAMMA, NT_BETA, NT_BIAS, NT_GRAD_W, NT_GRAD_GAMMA, NT_GRAD_BETA, NT_GRAD_BIAS, NT_MEAN, NT_VAR = range(10)
 
@@ -257,6 +257,8 @@ def make_layer_array(layers):
             a.pool = pool_desc(l["pool"])
         elif l["kind"] == "gap":
             a.kind = LAYER_GAP
+        elif l["kind"] == "concat":
+            a.kind = LAYER_CONCAT
         elif l["kind"] == "linear":
             a.kind = LAYER_LINEAR
             a.out_features = l["out"]
@@ -343,6 +345,12 @@ class Network:
         the layer in front, as for the max pool behind a stem convolution)."""
         t = C.c_int(0)
         _check(lib().sol_network_layer_fused_into(self._h, C.c_int(layer), C.byref(t)))
+        return t.value
+
+    def concat_in_place(self, layer):
+        """How many of the two inputs of concatenation layer `layer` their producers write in place (0..2)."""
+        t = C.c_int(0)
+        _check(lib().sol_network_concat_in_place(self._h, C.c_int(layer), C.byref(t)))
         return t.value
 
     def run_layer(self, layer, x, stream=None):

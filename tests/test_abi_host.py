@@ -169,6 +169,33 @@ def test_plan_fuses_stem_and_pool_only_when_it_may(sol):
     assert L.sol_network_layer_fused_into(None, 0, C.byref(t)) == 1
 
 
+def test_concat_planning_and_validation(sol):
+    """Channel concatenation layers: shapes, refusals, and which producers the plan lets write in place."""
+    L = sol.lib()
+    c, cat = wl.conv, wl.concat
+    fire = wl.fire_layers(1, 0, 8, 16)
+    layers = [c(16, 3)] + fire + [c(8, 1, p=0)]
+    st, h = _create(sol, layers, (2, 3, 12, 12), sol.BF16)
+    assert st == 0
+    d = sol.TensorDesc()
+    assert L.sol_network_output_desc(h, 4, C.byref(d)) == 0 and (d.n, d.h, d.w, d.c) == (2, 12, 12, 32)
+    t = C.c_int(-1)
+    assert L.sol_network_concat_in_place(h, 4, C.byref(t)) == 0 and t.value == 2
+    assert L.sol_network_concat_in_place(h, 3, C.byref(t)) == 2            # not a concatenation
+    assert L.sol_network_concat_in_place(h, 99, C.byref(t)) == 2 and L.sol_network_concat_in_place(None, 4, C.byref(t)) == 1
+    ws = L.sol_network_workspace_bytes(h)
+    L.sol_network_destroy(h)
+    st, h = _create(sol, layers, (2, 3, 12, 12), sol.BF16, sol.NET_KEEP_ACTIVATIONS)
+    assert st == 0 and L.sol_network_concat_in_place(h, 4, C.byref(t)) == 0 and t.value == 0
+    assert L.sol_network_workspace_bytes(h) > ws                         # the expand outputs exist twice when everything is kept
+    L.sol_network_destroy(h)
+    assert _create(sol, layers, (2, 3, 12, 12), sol.BF16, sol.NET_TRAINING)[0] == 6                     # inference only
+    assert _create(sol, [c(8, 3), cat(0, 0)], (1, 3, 8, 8), sol.F32)[0] == 2                            # one layer twice
+    assert _create(sol, [c(8, 3), c(8, 3, s=2, src=0), cat(0, 1)], (1, 3, 8, 8), sol.F32)[0] == 2       # extents differ
+    assert _create(sol, [c(8, 3), cat(0, 2), c(8, 3)], (1, 3, 8, 8), sol.F32)[0] == 2                   # names a later layer
+    assert _create(sol, [cat(-1, 0)], (1, 3, 8, 8), sol.F32)[0] == 2                                    # nothing to join
+
+
 def test_depthwise_planning_and_validation(sol):
     """Depthwise layers: shape inference keeps the channel count, parameters are [taps][c] + scale/shift, bad
     descriptors are refused on the host."""

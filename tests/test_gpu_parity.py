@@ -716,6 +716,89 @@ def test_network_fuses_stem_and_pool(sol):
     torch.cuda.synchronize()
 
 
+# ---- channel concatenation, written in place by the producers where the plan allows ----------------------------------
+def _concat_nets():
+    c, cat, pool = wl.conv, wl.concat, wl.pool
+    fire = lambda sq, ex: wl.fire_layers(1, 0, sq, ex)  # noqa: E731
+    return {
+        # name: (layers, (n, c, h, w), dtype, in-place parts per concat layer with flags 0)
+        "fire_1x1_3x3": ([c(16, 3)] + fire(8, 16) + [c(8, 1, p=0)], (3, 3, 20, 24), "bf16", [2]),
+        "fire_fp32": ([c(16, 3)] + fire(8, 16) + [c(8, 1, p=0)], (2, 3, 12, 12), "f32", [2]),
+        "wide_1x1": ([c(256, 1, p=0)] + fire(64, 128) + [c(32, 1, p=0)], (4, 64, 28, 28), "bf16", [2]),
+        "ragged_channels": ([c(16, 3)] + fire(8, 12) + [c(8, 1, p=0)], (2, 3, 10, 10), "bf16", [0]),      # 12 + 12: slices off the 16-byte grid
+        "unequal_unaligned": ([c(16, 3), c(12, 1, p=0, src=0), c(20, 3, src=0), cat(1, 2), c(8, 1, p=0)], (2, 3, 10, 10), "bf16", [0]),
+        "shared_producer": ([c(16, 3), c(16, 1, p=0, src=0), c(16, 3, src=0), cat(1, 2), c(8, 1, p=0, src=3), c(8, 1, p=0, src=1, res=4)],
+                            (2, 3, 12, 12), "bf16", [1]),
+        "pool_and_conv": ([c(16, 3), pool("max", 2, 2, 0), c(16, 3, s=2, src=0), cat(1, 2), c(8, 1, p=0)], (2, 3, 16, 16), "bf16", [1]),
+        "concat_is_output": ([c(16, 3)] + fire(8, 16), (2, 3, 9, 11), "bf16", [2]),
+        "nested": ([c(16, 3)] + fire(8, 16) + [c(32, 1, p=0, src=0), cat(4, 5), c(8, 1, p=0)], (2, 3, 12, 12), "bf16", [2, 1]),
+    }
+
+
+@pytest.mark.parametrize("name", sorted(_concat_nets()))
+def test_concat_networks(sol, name):
+    """Joins written in place by their producers, copied, or half and half: the plan's choice is as documented, the
+    result is the same bits either way and matches the checker."""
+    layers, shape, dt, want_parts = _concat_nets()[name]
+    bf16 = dt == "bf16"
+    rng = np.random.default_rng(len(name) * 7 + 3)
+    x = _grid(rng.standard_normal(shape), dt)
+    prm = wl.make_params(layers, shape[1], 4242, bf16=bf16, bias_std=0.3)
+    outs, _ = orc.network_forward(layers, prm, x, bf16=bf16, return_all=True)
+    d = _dt(sol, dt)
+    res = {}
+    for keep in (False, True):
+        net = sol.Network(layers, shape, d, flags=sol.NET_KEEP_ACTIVATIONS if keep else 0)
+        net.set_params(prm)
+        y = sol.to_host_nchw(net.forward(sol.to_device_nhwc(x, d)))
+        torch.cuda.synchronize()
+        cats = [i for i, l in enumerate(layers) if l["kind"] == "concat"]
+        parts = [net.concat_in_place(i) for i in cats]
+        assert parts == (want_parts if not keep else [0] * len(cats)), (name, keep, parts)
+        res[keep] = y
+        if keep:
+            for i in cats:
+                got = sol.to_host_nchw(net.layer_output(i)) if i + 1 < len(layers) else y
+                assert rel_err(got.reshape(outs[i].shape), outs[i]) <= TOL[dt]
+    # in place or copied is the same arithmetic; the plan without kept activations may also pad channel counts to
+    # multiples of 32 (other kernels, other accumulation order), hence a tolerance and not equality
+    assert rel_err(res[False], res[True].astype(np.float64)) <= TOL[dt]
+    assert rel_err(res[False].reshape(outs[-1].shape), outs[-1]) <= TOL[dt] * (4 if bf16 else 1)
+
+
+def test_stem_writes_slices(sol):
+    """The 7x7 stem kernel (interior and ragged blocks) and a 3x3 convolution as in-place producers of one join."""
+    c = wl.conv
+    for hw in (64, 50):
+        # a 3-channel 1x1 layer in front, so that both stems can name one producer
+        layers = [c(3, 1, p=0, bn=False, act="none"), c(64, 7, s=2, p=3, src=0), c(64, 3, s=2, p=1, src=0), wl.concat(1, 2), c(8, 1, p=0)]
+        shape = (2, 3, hw, hw)
+        x = _grid(np.random.default_rng(hw).standard_normal(shape), "bf16")
+        prm = wl.make_params(layers, 3, 99, bf16=True, bias_std=0.3)
+        outs, _ = orc.network_forward(layers, prm, x, bf16=True, return_all=True)
+        ys = []
+        for keep in (False, True):
+            net = sol.Network(layers, shape, sol.BF16, flags=sol.NET_KEEP_ACTIVATIONS if keep else 0)
+            net.set_params(prm)
+            ys.append(sol.to_host_nchw(net.forward(sol.to_device_nhwc(x, sol.BF16))))
+            assert net.concat_in_place(3) == (0 if keep else 2)
+        assert np.array_equal(ys[0], ys[1])                 # no channel count here is padded: the same kernels, the same bits
+        assert rel_err(ys[0].reshape(outs[-1].shape), outs[-1]) <= 4 * TOL["bf16"]
+
+
+def test_squeezenet_shaped_network(sol):
+    """Config 7 at a reduced size: every fire module's join is written in place; output against the checker."""
+    wk = wl.config(7, batch=2, hw=96)
+    outs, _ = orc.network_forward(wk.layers, wk.params, wk.x, bf16=True, return_all=True)
+    net, y = run_network(sol, wk, keep=False)
+    cats = [i for i, l in enumerate(wk.layers) if l["kind"] == "concat"]
+    assert len(cats) == 8 and all(net.concat_in_place(i) == 2 for i in cats)
+    _, y_keep = run_network(sol, wk, keep=True)
+    assert norm_err(y, y_keep.astype(np.float64)) <= TOL["bf16"]     # squeeze outputs of 16 / 48 channels are padded to 32 / 64 in the lean plan
+    assert norm_err(y.reshape(outs[-1].shape), outs[-1]) <= TOL["bf16"]
+    assert norm_err(y_keep.reshape(outs[-1].shape), outs[-1]) <= TOL["bf16"]
+
+
 # ---- depthwise convolution (the fusion engine's weighted pooling) -----------------------------------------------
 def make_dw_block(rng, dt, N, C, H, W, k, sh, sw, p, bn=True, act="relu", res=False, bias_std=0.3):
     l = dict(wl.conv(C, k, 1, p, bn=bn, act=act, dw=True), sh=sh, sw=sw)
