@@ -279,39 +279,53 @@ sol_status launch_pool(const PoolArgs &a, int dt, hipStream_t st) {
 // H*W axis and combine through LDS; the sum runs in fp32.
 template <typename T, int V>
 __global__ void __launch_bounds__(256) gap_kernel(const T *__restrict__ x, T *__restrict__ y, int N, int HW, int C) {
-    constexpr int SPLIT = 4;                       // 64 channel-vectors x 4 pixel slices per block
-    __shared__ float part[SPLIT][64][V];
+    constexpr int SPLIT = 16, CGB = 16;            // 16 channel-vectors x 16 pixel slices per block: the tensor is small
+    __shared__ float part[SPLIT][CGB][V + 1];      // (7-26 MB here), so the job is to have enough loads in flight chip-wide
     const int cg = C / V;
-    const int gblocks = (cg + 63) / 64;
+    const int gblocks = (cg + CGB - 1) / CGB;
     const int n = blockIdx.x / gblocks;
-    const int g = (blockIdx.x % gblocks) * 64 + (threadIdx.x & 63);
-    const int slice = threadIdx.x >> 6;
+    const int lg = threadIdx.x % CGB, slice = threadIdx.x / CGB;
+    const int g = (blockIdx.x % gblocks) * CGB + lg;
     float acc[V];
 #pragma unroll
     for (int e = 0; e < V; e++) acc[e] = 0.f;
     if (g < cg) {
-        for (int i = slice; i < HW; i += SPLIT) {
+        const T *p = x + (long)n * HW * C + g * V;
+        int i = slice;
+        for (; i + 3 * SPLIT < HW; i += 4 * SPLIT) {          // four independent loads per trip, added in pixel order
+            float v[4][V];
+#pragma unroll
+            for (int u = 0; u < 4; u++) VecIO<T, V>::load(p + (long)(i + u * SPLIT) * C, v[u]);
+#pragma unroll
+            for (int u = 0; u < 4; u++)
+#pragma unroll
+                for (int e = 0; e < V; e++) acc[e] += v[u][e];
+        }
+        for (; i < HW; i += SPLIT) {
             float v[V];
-            VecIO<T, V>::load(x + ((long)n * HW + i) * C + g * V, v);
+            VecIO<T, V>::load(p + (long)i * C, v);
 #pragma unroll
             for (int e = 0; e < V; e++) acc[e] += v[e];
         }
     }
 #pragma unroll
-    for (int e = 0; e < V; e++) part[slice][threadIdx.x & 63][e] = acc[e];
+    for (int e = 0; e < V; e++) part[slice][lg][e] = acc[e];
     __syncthreads();
     if (slice == 0 && g < cg) {
         float o[V];
 #pragma unroll
-        for (int e = 0; e < V; e++)
-            o[e] = (((part[0][threadIdx.x][e] + part[1][threadIdx.x][e]) + part[2][threadIdx.x][e]) + part[3][threadIdx.x][e]) / (float)HW;
+        for (int e = 0; e < V; e++) {
+            float t = part[0][lg][e];
+#pragma unroll
+            for (int s2 = 1; s2 < SPLIT; s2++) t += part[s2][lg][e];   // fixed order
+            o[e] = t / (float)HW;
+        }
         VecIO<T, V>::store(y + (long)n * C + g * V, o);
     }
 }
 
-template <typename T, int V>
-static void launch_gap_t(const void *x, void *y, int N, int HW, int C, hipStream_t st) {
-    const int gblocks = (C / V + 63) / 64;
+template <typename T, int V> static void launch_gap_t(const void *x, void *y, int N, int HW, int C, hipStream_t st) {
+    const int gblocks = (C / V + 15) / 16;
     if (N * gblocks <= 0) return;
     hipLaunchKernelGGL((gap_kernel<T, V>), dim3(N * gblocks), dim3(256), 0, st, static_cast<const T *>(x),
                        static_cast<T *>(y), N, HW, C);
