@@ -384,11 +384,18 @@ __global__ void __launch_bounds__(256) pool_bwd_kernel(const PoolArgs a, const T
     const int cg = a.C / V;
     const long total = (long)a.N * a.H * a.W * cg;
     for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
-        const int g = (int)(i % cg);
-        long t = i / cg;
-        const int iw = (int)(t % a.W); t /= a.W;
-        const int ih = (int)(t % a.H);
-        const int n = (int)(t / a.H);
+        int g, iw, ih, n;
+        if (total < (1L << 31)) {           // the usual case: 32-bit divisions (a 64-bit division is a long instruction sequence)
+            const unsigned u = (unsigned)i, t0 = u / (unsigned)cg, t1 = t0 / (unsigned)a.W;
+            g = (int)(u - t0 * (unsigned)cg); iw = (int)(t0 - t1 * (unsigned)a.W);
+            n = (int)(t1 / (unsigned)a.H); ih = (int)(t1 - (unsigned)n * (unsigned)a.H);
+        } else {
+            g = (int)(i % cg);
+            long t = i / cg;
+            iw = (int)(t % a.W); t /= a.W;
+            ih = (int)(t % a.H);
+            n = (int)(t / a.H);
+        }
         const int th = ih + a.ph - a.kh + 1, tw = iw + a.pw - a.kw + 1;
         const int p_lo = th <= 0 ? 0 : (th + a.sh - 1) / a.sh, p_hi = min(a.Ho - 1, (ih + a.ph) / a.sh);
         const int q_lo = tw <= 0 ? 0 : (tw + a.sw - 1) / a.sw, q_hi = min(a.Wo - 1, (iw + a.pw) / a.sw);
@@ -401,9 +408,20 @@ __global__ void __launch_bounds__(256) pool_bwd_kernel(const PoolArgs a, const T
                 float d[V];
                 VecIO<T, V>::load(dy + o, d);
                 if (a.kind == SOL_POOL_MAX) {
+                    int win[V];
+                    if constexpr (V % 4 == 0) {     // o is a multiple of V: 16-byte loads of the winners
+#pragma unroll
+                        for (int e = 0; e < V; e += 4) {
+                            const int4 w4 = *reinterpret_cast<const int4 *>(a.argmax + o + e);
+                            win[e] = w4.x; win[e + 1] = w4.y; win[e + 2] = w4.z; win[e + 3] = w4.w;
+                        }
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < V; e++) win[e] = a.argmax[o + e];
+                    }
 #pragma unroll
                     for (int e = 0; e < V; e++)
-                        if (a.argmax[o + e] == ih * a.W + iw) sum[e] += d[e];
+                        if (win[e] == ih * a.W + iw) sum[e] += d[e];
                 } else {
                     int cnt = a.kh * a.kw;
                     if (!a.count_pad) {
