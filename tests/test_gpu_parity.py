@@ -570,7 +570,7 @@ def test_full_size_stem_pool_and_gap(sol):
         assert np.array_equal(y[n:n + 1], want) and np.array_equal(arg[n:n + 1], warg)
 
 
-@pytest.mark.parametrize("cfg,batch,hw", [(1, 8, 32), (3, 2, 64)])
+@pytest.mark.parametrize("cfg,batch,hw", [(1, 8, 32), (3, 2, 64), (7, 2, 64)])
 def test_network_graph_replays(sol, cfg, batch, hw):
     """A recorded forward pass, replayed several times with new input contents and eager work and
     synchronisations between the replays, gives bit-identical results to the eager pass every time."""
