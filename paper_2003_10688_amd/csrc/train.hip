@@ -549,7 +549,15 @@ __global__ void __launch_bounds__(256) pack_batch_kernel(const PackBatch b) {
     if (mode == 1) {
         const int n = C * RS;
         const float *src = w + (size_t)blk * n;
-        for (int i = threadIdx.x; i < n; i += 256) tile[i] = src[i];              // i = c * RS + tap
+        // eight loads in flight per thread (a plain copy loop waits for every load before it issues the next)
+        for (int i0 = threadIdx.x; i0 < n; i0 += 256 * 8) {                        // i = c * RS + tap
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) v[u] = src[min(i0 + u * 256, n - 1)];
+#pragma unroll
+            for (int u = 0; u < 8; u++)
+                if (i0 + u * 256 < n) tile[i0 + u * 256] = v[u];
+        }
         __syncthreads();
         T *dst = out + (size_t)blk * Kp;
         for (int j = threadIdx.x; j < Kp; j += 256) {                               // j = tap * C + c
@@ -561,9 +569,19 @@ __global__ void __launch_bounds__(256) pack_batch_kernel(const PackBatch b) {
     if (mode == 2) {
         const int KT = K % 128 == 0 ? 128 : 64, nkb = K / KT, run = 8 * RS, pitch = run + 1;
         const int cb = blk / nkb, kb = blk - cb * nkb, c0 = cb * 8, k0 = kb * KT;
-        for (int i = threadIdx.x; i < KT * run; i += 256) {
-            const int kk = i / run, rem = i - kk * run;                             // rem = cc * RS + tap
-            tile[kk * pitch + rem] = w[((size_t)(k0 + kk) * C + c0) * RS + rem];
+        for (int i0 = threadIdx.x; i0 < KT * run; i0 += 256 * 8) {                // eight loads in flight per thread
+            float v[8];
+            int dst[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) {
+                const int i = min(i0 + u * 256, KT * run - 1);
+                const int kk = i / run, rem = i - kk * run;                         // rem = cc * RS + tap
+                dst[u] = kk * pitch + rem;
+                v[u] = w[((size_t)(k0 + kk) * C + c0) * RS + rem];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; u++)
+                if (i0 + u * 256 < KT * run) tile[dst[u]] = v[u];
         }
         __syncthreads();
         for (int o = threadIdx.x; o < KT * run; o += 256) {
