@@ -7,6 +7,7 @@
 // second launch, so results do not depend on scheduling (no floating-point atomics anywhere).
 #include <math.h>
 
+#include <type_traits>
 #include "conv_common.h"
 #include "vec_io.h"
 
@@ -77,32 +78,58 @@ __global__ void __launch_bounds__(256) col_reduce_vec_kernel(const T *__restrict
             if (MODE >= 1 && mean) m[e] = mean[c0 + e];
             if (MODE == 2 && invstd) is[e] = invstd[c0 + e];
         }
-        auto one_row = [&](int r) {
-            const size_t i = (size_t)r * C + c0;
-            float va[V], vb[V], vy[V];
-            if (MODE <= 1 || a) VecIO<T, V>::load(a + i, va);
-            if (MODE == 2) {
-                VecIO<T, V>::load(b + i, vb);
-                if (relu) VecIO<T, V>::load(y + i, vy);
-            }
-#pragma unroll
-            for (int e = 0; e < V; e++) {
-                if (MODE == 0) {
-                    s0[e] += va[e];
-                } else if (MODE == 1) {
-                    const float d = va[e] - m[e];
-                    s0[e] += d * d;
-                } else {
-                    float g = vb[e];
-                    if (relu && !(vy[e] > 0.f)) g = 0.f;
-                    s0[e] += g;
-                    if (a) s1[e] += g * ((va[e] - m[e]) * is[e]);
+        // Which tensors a row needs is fixed for the launch, so the row loop is instantiated per combination with
+        // unconditional loads: behind a run-time condition every load would be waited for on the spot.  Four rows'
+        // loads are issued before the first is used; the sums still run in row order.
+        auto rows_loop = [&](auto HAS_A, auto RELU) {
+            constexpr bool ha = decltype(HAS_A)::value, rl = decltype(RELU)::value;
+            auto fetch = [&](int r, float (&va)[V], float (&vb)[V], float (&vy)[V]) {
+                const size_t i = (size_t)r * C + c0;
+                if constexpr (ha) VecIO<T, V>::load(a + i, va);
+                if constexpr (MODE == 2) {
+                    VecIO<T, V>::load(b + i, vb);
+                    if constexpr (rl) VecIO<T, V>::load(y + i, vy);
                 }
+            };
+            auto add = [&](const float (&va)[V], const float (&vb)[V], const float (&vy)[V]) {
+#pragma unroll
+                for (int e = 0; e < V; e++) {
+                    if constexpr (MODE == 0) {
+                        s0[e] += va[e];
+                    } else if constexpr (MODE == 1) {
+                        const float d = va[e] - m[e];
+                        s0[e] += d * d;
+                    } else {
+                        float g = vb[e];
+                        if constexpr (rl) { if (!(vy[e] > 0.f)) g = 0.f; }
+                        s0[e] += g;
+                        if constexpr (ha) s1[e] += g * ((va[e] - m[e]) * is[e]);
+                    }
+                }
+            };
+            int r = r0 + ph;
+            for (; r + 3 * PH < r1; r += 4 * PH) {
+                float va[4][V], vb[4][V], vy[4][V];
+#pragma unroll
+                for (int u = 0; u < 4; u++) fetch(r + u * PH, va[u], vb[u], vy[u]);
+#pragma unroll
+                for (int u = 0; u < 4; u++) add(va[u], vb[u], vy[u]);
+            }
+            for (; r < r1; r += PH) {
+                float va[V], vb[V], vy[V];
+                fetch(r, va, vb, vy);
+                add(va, vb, vy);
             }
         };
-        int r = r0 + ph;
-        for (; r + PH < r1; r += 2 * PH) { one_row(r); one_row(r + PH); }   // two rows' loads in flight
-        if (r < r1) one_row(r);
+        using std::true_type;
+        using std::false_type;
+        if constexpr (MODE <= 1) {
+            rows_loop(true_type{}, false_type{});
+        } else if (a) {
+            if (relu) rows_loop(true_type{}, true_type{}); else rows_loop(true_type{}, false_type{});
+        } else {
+            if (relu) rows_loop(false_type{}, true_type{}); else rows_loop(false_type{}, false_type{});
+        }
     }
     __shared__ float red[2][PH][64 + 1];
 #pragma unroll
