@@ -429,6 +429,30 @@ __global__ void __launch_bounds__(256) pool_bwd_kernel(const PoolArgs a, const T
         float sum[V];
 #pragma unroll
         for (int e = 0; e < V; e++) sum[e] = 0.f;
+        if (a.kind == SOL_POOL_MAX && V % 4 == 0 && p_hi - p_lo <= 1 && q_hi - q_lo <= 1) {
+            // at most 2 x 2 windows hold this pixel (window <= 2 strides): all their loads are issued together, from
+            // clamped (always valid) addresses, and the windows that do not exist are masked out afterwards
+            float d[4][V];
+            int win[4][V];
+            bool on[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int p = p_lo + (u >> 1), q = q_lo + (u & 1);
+                on[u] = p <= p_hi && q <= q_hi;
+                const long o = (((long)n * a.Ho + min(p, a.Ho - 1)) * a.Wo + min(q, a.Wo - 1)) * a.C + (long)g * V;
+                VecIO<T, V>::load(dy + o, d[u]);
+#pragma unroll
+                for (int e = 0; e < V; e += 4) {
+                    const int4 w4 = *reinterpret_cast<const int4 *>(a.argmax + o + e);
+                    win[u][e] = w4.x; win[u][e + 1] = w4.y; win[u][e + 2] = w4.z; win[u][e + 3] = w4.w;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++)                    // row-major window order, as the loop below
+#pragma unroll
+                for (int e = 0; e < V; e++)
+                    if (on[u] && win[u][e] == ih * a.W + iw) sum[e] += d[u][e];
+        } else
         for (int p = p_lo; p <= p_hi; p++)
             for (int q = q_lo; q <= q_hi; q++) {
                 const long o = (((long)n * a.Ho + p) * a.Wo + q) * a.C + (long)g * V;
