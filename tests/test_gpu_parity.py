@@ -558,6 +558,39 @@ def test_full_size_layers_sampled(sol, cfg):
     print(f"cfg{cfg} full-size sampled layers: worst rel err {worst:.3e}")
 
 
+def test_full_size_fused_stem_pair_sampled(sol):
+    """The depth-first stem + max-pool kernel at the benchmark's size (64 x 3 x 224 x 224, the launch the timed pass
+    makes): sampled pooled outputs against the checker, each from the (up to) nine convolution points under its
+    window -- convolution, explicit BN, ReLU, bf16 rounding, maximum."""
+    wk = wl.config(3)
+    l, prm = wk.layers[0], wk.params[0]
+    pd = wk.layers[1]["pool"]
+    assert (l["kh"], l["sh"], pd["kh"], pd["sh"], pd["ph"]) == (7, 2, 3, 2, 1)
+    rng = np.random.default_rng(wk.seed + 5)
+    x = wl.to_bf16_grid(rng.standard_normal(wk.in_shape, dtype=np.float32))
+    got, _, _ = run_block(sol, "bf16", dict(l, pool=pd), x, prm, None)
+    N, K, Ho, Wo = wk.in_shape[0], l["cout"], 112, 112
+    Hy, Wy = got.shape[2], got.shape[3]
+    assert got.shape == (N, K, 56, 56)
+    pts = np.stack([rng.integers(0, s, 192) for s in (N, K, Hy, Wy)], 1)
+    pts[:6] = [[0, 0, 0, 0], [N - 1, K - 1, Hy - 1, Wy - 1], [0, K - 1, 0, Wy - 1], [N - 1, 0, Hy - 1, 0], [N // 2, 31, 6, 7], [1, 32, 7, 8]]
+    coords, owner = [], []
+    for j, (n, k, py, px) in enumerate(pts):
+        for dy in range(3):
+            for dx in range(3):
+                q, p = 2 * py - 1 + dy, 2 * px - 1 + dx
+                if 0 <= q < Ho and 0 <= p < Wo:
+                    coords.append((n, k, q, p)); owner.append(j)
+    vals = orc.fused_conv_points(x, prm, dict(l, pool=None), np.array(coords), None, bf16=True)
+    want = np.full(len(pts), -np.inf)
+    np.maximum.at(want, np.array(owner), vals)
+    g = got[tuple(pts.T)]
+    floor = np.sqrt(np.mean(want * want)) + 1e-30
+    err = float(np.max(np.abs(g - want) / np.maximum(np.abs(want), floor)))
+    print(f"fused stem pair, full size: rel err {err:.3e} ({np.count_nonzero(g != want)} of {len(g)} differ)")
+    assert err <= TOL["bf16"]
+
+
 def test_full_size_stem_pool_and_gap(sol):
     wk = wl.config(3)
     rng = np.random.default_rng(1)
