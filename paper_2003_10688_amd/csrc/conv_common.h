@@ -359,6 +359,7 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
 struct LinearRowOffset {
     unsigned first, cout;
     __device__ __forceinline__ unsigned operator()(int r) const { return first + (unsigned)r * cout; }
+    __device__ __forceinline__ bool valid(int) const { return true; }     // every row of an interior tile is stored
 };
 template <typename T, int TP, int TC, bool RES, typename RowOff>
 __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16_t (&acc)[TC][TP], float *lds_f, int wave, int lane,
@@ -396,7 +397,7 @@ __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16
             }
 #pragma unroll
             for (int e = 0; e < 8; e++) v[e] = fmaxf(v[e], lim);
-            store_vec8<T>(yg + rowoff(j * 32 + erow + ps * RPS) + coff, v);
+            if (rowoff.valid(j * 32 + erow + ps * RPS)) store_vec8<T>(yg + rowoff(j * 32 + erow + ps * RPS) + coff, v);
         }
         wave_lds_fence();
     });

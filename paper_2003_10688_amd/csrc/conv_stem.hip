@@ -15,9 +15,11 @@
 
 namespace sol {
 
-struct StemRowOffset {   // same map as StemRows for a block that lies inside the image, as an element offset
-    unsigned base, wo, cout;     // base: offset of the block's pixel (p0, q0)
+struct StemRowOffset {   // same map as StemRows as an element offset; rows past the image's last row / column are not stored
+    unsigned base, wo, cout;     // base: offset of the wave's first pixel; cout: elements between pixels
+    int hleft, wleft;            // output rows / columns from that pixel to the image border
     __device__ __forceinline__ unsigned operator()(int r) const { return base + ((unsigned)(r >> 4) * wo + (unsigned)(r & 15)) * cout; }
+    __device__ __forceinline__ bool valid(int r) const { return (r >> 4) < hleft && (r & 15) < wleft; }
 };
 
 struct StemRows {   // tile row (py*16+px) of the 8x16 output block -> output pixel index
@@ -133,7 +135,7 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
     // Wait bookkeeping: the compiler derives every vmcnt wait itself, and where paths join it assumes the worst of
     // them.  So everything loaded before the loop (affine constants, first patch) is drained in the prologue; inside the loop
     // a patch is written to LDS at the END of the iteration that issued its loads; and the loop exists twice, so
-    // that the common one (every block inside the image, all channels, no residual) is straight-line code in which
+    // that the common one (all NC * 32 channels, no residual; rows past the image border are masked) is straight-line code in which
     // the only memory operations younger than the patch loads are the block's 2 * NC output stores: those stay in
     // flight across the wait instead of stalling the next tile.  The explicit waits in the loop only tell the
     // compiler, at a point every lane passes, what it would otherwise have to assume at the next join; it still
@@ -185,7 +187,7 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
             resregs.on = false;
             if constexpr (INTERIOR) {                                    // branch-free epilogue
                 const int pw = p0 + 2 * wave;     // first output row of this wave's 32 tile rows
-                const StemRowOffset ro{(unsigned)(((n * a.Ho + pw) * a.Wo + q0) * a.ldy), (unsigned)a.Wo, (unsigned)a.ldy};
+                const StemRowOffset ro{(unsigned)(((n * a.Ho + pw) * a.Wo + q0) * a.ldy), (unsigned)a.Wo, (unsigned)a.ldy, a.Ho - pw, a.Wo - q0};
                 conv_epilogue_interior<bf16_t, 1, NC, false>(a, acc, strip, wave, lane, 0, aff, resregs, ro);
                 __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * NC));           // vmcnt(2 * NC), outside the lane-masked regions below
             } else {
@@ -197,7 +199,7 @@ __global__ void __launch_bounds__(256) conv_stem_kernel(const ConvArgs a, int ti
             if (more) store_patch(cur ^ 1);
         }
     };
-    if (a.Ho % STEM_TH == 0 && a.Wo % STEM_TW == 0 && a.Cout == NC * 32 && a.res == nullptr)
+    if (a.Cout == NC * 32 && a.res == nullptr)       // ragged image extents are handled by the row mask of the fast epilogue
         run_tiles(std::true_type{});
     else
         run_tiles(std::false_type{});
