@@ -162,9 +162,14 @@ def main():
         us = e0.elapsed_time(e1) * 1e3 / a.layer_reps
         absorbs = i + 1 < len(into) and into[i + 1] == i
         fl, by = algorithmic_work(l, ins[i], outs[i], esize)
-        if absorbs:   # a fused pair stores only the pooled tensor
-            numel = lambda t: t[0] * t[1] * t[2] * t[3]  # noqa: E731
+        numel = lambda t: t[0] * t[1] * t[2] * t[3]  # noqa: E731
+        if absorbs:   # a fused stem pair stores only the pooled tensor
             by += esize * (numel(outs[i + 1]) - numel(outs[i]))
+        for j in range(i):   # a projection shortcut computed inside this launch: its work, minus the write and the re-read of its output
+            if into[j] == i:
+                fj, bj = algorithmic_work(wk.layers[j], ins[j], outs[j], esize)
+                fl += fj
+                by += bj - 2 * esize * numel(outs[j])
         rows.append({"i": i, "kind": "dwconv" if l.get("dw") else l["kind"], "us": us, "flops": fl, "bytes": by})
     conv = [r for r in rows if r["kind"] == "conv"]
     mem = [r for r in rows if r["kind"] in ("pool", "gap")]

@@ -59,11 +59,15 @@ static bool pool_is_fusable(const sol_pool_desc &p) {
         if (s_ != SOL_OK) return s_;    \
     } while (0)
 
+// second operand set of a fused projection pair: y = act(scale * conv(x, w) + shift + scale2 * conv(x2, w2) + shift2)
+struct PairOperand { const void *x2, *w2; const float *scale2, *shift2; };
+
 // Shared by sol_conv2d_fused and the network executor.
 static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, const sol_conv_desc &cd, const void *w,
                                   const float *scale, const float *shift, const void *res, int act,
                                   const sol_pool_desc *pool, void *y, int32_t *argmax, void *prepool, int tile,
-                                  hipStream_t st, int ldy = 0) {   // ldy: elements between output pixels in y, 0 = cout (dense)
+                                  hipStream_t st, int ldy = 0,     // ldy: elements between output pixels in y, 0 = cout (dense)
+                                  const PairOperand *pair = nullptr) {
     SOL_REQUIRE(cd.cin == xd.c, SOL_ERR_SHAPE, "conv cin %d != input channels %d", cd.cin, xd.c);
     SOL_REQUIRE(act == SOL_ACT_NONE || act == SOL_ACT_RELU, SOL_ERR_SHAPE, "bad activation %d", act);
     const int Ho = out_size(xd.h, cd.kh, cd.sh, cd.ph), Wo = out_size(xd.w, cd.kw, cd.sw, cd.pw);
@@ -119,6 +123,12 @@ static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, cons
     a.dw = FastDiv((uint32_t)(quad ? a.Wy : Wo));
     a.dh = FastDiv((uint32_t)(quad ? a.Hy : Ho));
     if (a.pool == 3) return launch_conv_stem_pool(a, st);   // one kernel, no tile choice
+    if (pair) {
+        SOL_REQUIRE(res == nullptr && pair_k64_applies(a, xd.dtype), SOL_ERR_UNSUPPORTED,
+                    "a fused projection pair is two bf16 1x1 stride-1 convolutions over 64 channels");
+        SOL_REQUIRE(pair->x2 && pair->w2 && aligned16(pair->x2) && aligned16(pair->w2), SOL_ERR_NULL, "pair operands");
+        return launch_conv_pair_k64(a, pair->x2, pair->w2, pair->scale2, pair->shift2, st);
+    }
     return launch_conv(a, xd.dtype, tile, st);
 }
 
@@ -176,6 +186,9 @@ struct LayerPlan {
     int cout_real, cin_real;        // CONV: channel counts of the caller's weights when the plan padded cd.cout / cd.cin (else 0)
     int concat_into, concat_off;    // CONV: writes its output as channels concat_off.. of that CONCAT layer's buffer (-1: own buffer)
     bool prealloc;                  // CONCAT: buffer laid out when its first in-place producer ran
+    int pair;                       // CONV: index of the projection convolution this launch also computes (-1: none)
+    int fused_into;                 // index of the layer whose launch produces this layer's output (itself unless elided)
+    bool no_buffer;                 // elided, and nobody allocates an output for it either
     size_t w_off, scale_off, shift_off;
     size_t out_off, tmp_off;        // workspace offsets; out_off unused for the last layer
     int last_use;
@@ -347,6 +360,8 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
         lp.src = L.src == -1 ? i - 1 : L.src;
         lp.res = -1;
         lp.concat_into = -1;
+        lp.pair = -1;
+        lp.fused_into = i;
         lp.in = lp.src < 0 ? net->input : net->layers[lp.src].out;
         lp.out = lp.in;
         lp.last_use = i;
@@ -489,6 +504,29 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
                 c.last_use == i + 1 && stem_pool_plan_ok(c.in, c.cd, c.L, q.L.pool)) {
                 c.absorbs_next = true;
                 q.elided = true;
+                q.fused_into = i;
+            }
+        }
+
+    // Projection pair: the 1x1 shortcut convolution of a block whose only reader is the residual input of the
+    // block's last 1x1 convolution runs inside that convolution's launch (both over 64 channels: conv_pair.hip);
+    // its output, as large as the block output, is neither written nor read back.
+    if (!net->training && !net->keep && dt == SOL_BF16)
+        for (int i = 0; i < n_layers; i++) {
+            LayerPlan &c = net->layers[i];
+            if (c.L.kind != SOL_LAYER_CONV || c.res < 0 || c.L.pool.kind != SOL_POOL_NONE || c.cout_real || c.cin_real) continue;
+            LayerPlan &p = net->layers[c.res];
+            const auto k64 = [](const LayerPlan &l) {
+                return l.cd.kh == 1 && l.cd.kw == 1 && l.cd.sh == 1 && l.cd.sw == 1 && l.cd.ph == 0 && l.cd.pw == 0 && l.cd.cin == 64;
+            };
+            if (p.L.kind == SOL_LAYER_CONV && p.L.act == SOL_ACT_NONE && p.res < 0 && p.L.pool.kind == SOL_POOL_NONE && p.nuse == 1 &&
+                !p.elided && !p.absorbs_next && !p.cout_real && !p.cin_real && k64(p) && k64(c) && c.cd.cout % 8 == 0 &&
+                packed_k(c.cd, dt) == 64 && c.src != c.res) {
+                c.pair = c.res;
+                p.elided = true;
+                p.no_buffer = true;
+                p.fused_into = i;
+                if (p.src >= 0) net->layers[p.src].last_use = std::max(net->layers[p.src].last_use, i);   // read by layer i now
             }
         }
 
@@ -503,8 +541,8 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             int off = 0;
             for (int part : {cc.src, cc.res}) {
                 LayerPlan &p = net->layers[part];
-                if (p.L.kind == SOL_LAYER_CONV && p.L.pool.kind == SOL_POOL_NONE && !p.absorbs_next && p.nuse == 1 &&
-                    p.out.c % 8 == 0 && off % 8 == 0) {
+                if (p.L.kind == SOL_LAYER_CONV && p.L.pool.kind == SOL_POOL_NONE && !p.absorbs_next && !p.elided && p.pair < 0 &&
+                    p.nuse == 1 && p.out.c % 8 == 0 && off % 8 == 0) {
                     p.concat_into = i;
                     p.concat_off = off;
                 }
@@ -529,7 +567,7 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
         if (!net->keep)
             for (int j = 0; j < i; j++) {
                 const LayerPlan &lj = net->layers[j];
-                if (lj.last_use == i && j + 1 < n_layers && !lj.absorbs_next && lj.concat_into < 0) ar.release(lj.out_off);
+                if (lj.last_use == i && j + 1 < n_layers && !lj.absorbs_next && lj.concat_into < 0 && !lj.no_buffer) ar.release(lj.out_off);
             }
     }
     if (net->training) SOL_TRY(plan_training(net, ar));
@@ -965,6 +1003,15 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
                 const void *res = lp.res >= 0 ? layer_in(net, lp.res, x, ws) : nullptr;
                 void *conv_dst = lp.split_pool ? static_cast<void *>(ws + lp.tmp_off) : out;
                 const sol_pool_desc *fused = lp.absorbs_next ? &net->layers[i + 1].L.pool : lp.fuse_pool ? &lp.L.pool : nullptr;
+                if (lp.pair >= 0) {     // this launch also computes the projection shortcut it adds
+                    const LayerPlan &pp = net->layers[lp.pair];
+                    const PairOperand po{layer_in(net, pp.src, x, ws), net->params + pp.w_off,
+                                         reinterpret_cast<const float *>(net->params + pp.scale_off),
+                                         reinterpret_cast<const float *>(net->params + pp.shift_off)};
+                    SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, scale, shift, nullptr, lp.L.act, nullptr, conv_dst,
+                                            nullptr, nullptr, T_AUTO, st, ldy, &po));
+                    break;
+                }
                 SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, scale, shift, res, lp.L.act,
                                         fused, conv_dst, nullptr, nullptr,
                                         g_tile_override ? g_tile_override : lp.tile, st, ldy));
@@ -1116,6 +1163,7 @@ sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *
         LayerPlan &lp = net->layers[i];
         if (lp.L.kind != SOL_LAYER_CONV || lp.in.n == 0) continue;
         if (lp.absorbs_next || (lp.fuse_pool && !pool_is_fusable(lp.L.pool))) continue;   // stem + pool: one kernel, nothing to choose
+        if (lp.elided || lp.pair >= 0) continue;                                          // projection pair: likewise
         float best = 0.f;
         rs = time_layer(i, &best);                            // the shape heuristic's choice is the incumbent
         if (rs != SOL_OK) break;
@@ -1197,7 +1245,7 @@ void sol_graph_destroy(sol_graph *g) {
 sol_status sol_network_layer_fused_into(const sol_network *net, int layer, int *into) {
     SOL_REQUIRE(net && into, SOL_ERR_NULL, "net / into is NULL");
     SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
-    *into = net->layers[layer].elided ? layer - 1 : layer;
+    *into = net->layers[layer].fused_into;
     return SOL_OK;
 }
 

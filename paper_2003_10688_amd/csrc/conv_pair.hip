@@ -1,0 +1,140 @@
+// Projection shortcut and the 1x1 convolution it is added to, as one kernel (bf16, both reductions 64 channels):
+//
+//     out[m][k] = act( scale3[k] * sum_c y2[m][c] w3[k][c] + shift3[k] + scale_d[k] * sum_c x[m][c] wd[k][c] + shift_d[k] )
+//
+// In the first bottleneck of a ResNet-shaped list the shortcut is a 1x1 convolution of the block input whose only
+// reader is the residual add of the block's last 1x1 convolution.  Run as two layers, its output -- as large as the
+// block output, the largest tensor of the stage -- is written once and read back once.  Here a workgroup fetches
+// the two pixel tiles and the two weight tiles of a 128 x 128 output block (four 16 KB operands, every DMA in flight
+// at once), runs both contractions into accumulators of their own, combines them in fp32 in the accumulator
+// layout and hands the sum to the usual branch-free epilogue with an identity affine map.  The shortcut is
+// never rounded to bf16, which the two-layer path does when it stores it: results differ from that path by at
+// most one bf16 rounding of the shortcut term (well inside the tolerance of the library).
+// Overlap of loads, MFMAs and stores comes from two resident workgroups per CU; the job is bound by HBM.
+#include "conv_common.h"
+
+namespace sol {
+
+constexpr int PR_BP = 128, PR_BC = 128, PR_ROWB = 128;           // output block; bytes of reduction per row (64 bf16)
+constexpr int PR_OPB = 128 * PR_ROWB;                            // bytes of one operand tile
+
+__global__ void __launch_bounds__(256) conv_pair_k64_kernel(const ConvArgs a, const void *x2v, const void *w2v,
+                                                            const float *__restrict__ scale2, const float *__restrict__ shift2) {
+    using namespace lds_pipe;
+    constexpr int TP = 2, TC = 2, KS = PR_ROWB / 32;
+    __shared__ __align__(1024) unsigned char lds[4 * PR_OPB];   // y2 | w3 | x | wd tiles; later the epilogue strips
+    __shared__ __align__(16) float chan[3][PR_BC];               // scale3, scale_d, shift3 + shift_d of the block's channels
+    static_assert(4 * 32 * (TC * 32 + 4) * 4 <= 4 * PR_OPB, "epilogue strips fit in the operand area");
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wp = wave & 1, wc = wave >> 1;
+    const int xcd = (int)(blockIdx.x & 7);
+    const int tile = xcd * ((a.ntiles + 7) >> 3) + (int)(blockIdx.x >> 3);   // an XCD takes a contiguous run of blocks
+    if (tile >= a.ntiles) return;
+    const int p0 = (tile / a.ntc) * PR_BP, c0 = (tile % a.ntc) * PR_BC;
+
+    // operand o: 0 = y2 (a.x), 1 = w3 (a.w), 2 = x (x2v), 3 = wd (w2v); rows past the tensors read zeros
+    const unsigned pbytes = (unsigned)a.P * 64u * 2u, wbytes = (unsigned)a.Cout * (unsigned)a.Kp * 2u;
+    const __amdgpu_buffer_rsrc_t rs[4] = {
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, (int)pbytes, 0x00020000),
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, (int)wbytes, 0x00020000),
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(x2v), 0, (int)pbytes, 0x00020000),
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(w2v), 0, (int)wbytes, 0x00020000)};
+    const int lslot = lane & 7, lrow = lane >> 3;              // a 1 KB DMA segment = 8 rows x 8 slots of 16 bytes
+    auto swz = [](int row) { return (row >> 1) & 7; };
+#pragma unroll
+    for (int o = 0; o < 4; o++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) {                           // 16 segments per operand, 4 per wave
+            const int seg = i * 4 + wave, row = seg * 8 + lrow;
+            const bool pix = (o & 1) == 0;
+            const int g = (pix ? p0 : c0) + row;
+            const bool ok = g < (pix ? a.P : a.Cout);
+            const unsigned off = ok ? (unsigned)g * (pix ? 128u : (unsigned)a.Kp * 2u) + (unsigned)((lslot ^ swz(row)) << 4) : 0xffffffffu;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs[o], (__attribute__((address_space(3))) void *)(lds + o * PR_OPB + seg * 1024), 16,
+                                                     off, 0, 0, 0);
+        }
+    if (tid < PR_BC) {
+        const int c = min(c0 + tid, a.Cout - 1);
+        chan[0][tid] = a.scale ? a.scale[c] : 1.f;
+        chan[1][tid] = scale2 ? scale2[c] : 1.f;
+        chan[2][tid] = (a.shift ? a.shift[c] : 0.f) + (shift2 ? shift2[c] : 0.f);
+    }
+
+    f32x16_t acc3[TC][TP], accd[TC][TP];
+#pragma unroll
+    for (int i = 0; i < TC; i++)
+#pragma unroll
+        for (int j = 0; j < TP; j++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) { acc3[i][j][e] = 0.f; accd[i][j][e] = 0.f; }
+
+    const int lr = lane & 31, lh = lane >> 5;
+    const int fsw = swz(lr);                                    // tile row bases are multiples of 32
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    auto contract = [&](f32x16_t (&acc)[TC][TP], const unsigned char *xt, const unsigned char *wt) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) {
+            const unsigned so = (unsigned)(((2 * ks + lh) ^ fsw) << 4);
+            uint4 fa[TC], fb[TP];
+#pragma unroll
+            for (int i = 0; i < TC; i++) fa[i] = *reinterpret_cast<const uint4 *>(wt + (wc * TC * 32 + i * 32 + lr) * PR_ROWB + so);
+#pragma unroll
+            for (int j = 0; j < TP; j++) fb[j] = *reinterpret_cast<const uint4 *>(xt + (wp * TP * 32 + j * 32 + lr) * PR_ROWB + so);
+#pragma unroll
+            for (int i = 0; i < TC; i++)
+#pragma unroll
+                for (int j = 0; j < TP; j++) Mma<bf16_t>::run(acc[i][j], fa[i], fb[j]);
+        }
+    };
+    contract(acc3, lds, lds + PR_OPB);
+    contract(accd, lds + 2 * PR_OPB, lds + 3 * PR_OPB);
+
+    // accumulator register e of lane l: channel 32 i + 8 (e / 4) + 4 (l / 32) + e % 4 of the wave's block
+#pragma unroll
+    for (int i = 0; i < TC; i++)
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            const int c = wc * TC * 32 + 32 * i + 8 * g + 4 * lh;
+            const float4 s3 = *reinterpret_cast<const float4 *>(&chan[0][c]), sd = *reinterpret_cast<const float4 *>(&chan[1][c]);
+            const float4 sh = *reinterpret_cast<const float4 *>(&chan[2][c]);
+#pragma unroll
+            for (int j = 0; j < TP; j++) {
+                acc3[i][j][4 * g + 0] = acc3[i][j][4 * g + 0] * s3.x + (accd[i][j][4 * g + 0] * sd.x + sh.x);
+                acc3[i][j][4 * g + 1] = acc3[i][j][4 * g + 1] * s3.y + (accd[i][j][4 * g + 1] * sd.y + sh.y);
+                acc3[i][j][4 * g + 2] = acc3[i][j][4 * g + 2] * s3.z + (accd[i][j][4 * g + 2] * sd.z + sh.z);
+                acc3[i][j][4 * g + 3] = acc3[i][j][4 * g + 3] * s3.w + (accd[i][j][4 * g + 3] * sd.w + sh.w);
+            }
+        }
+    Affine8 unit;
+#pragma unroll
+    for (int e = 0; e < 8; e++) { unit.sc[e] = 1.f; unit.sf[e] = 0.f; }
+    ResidualRegs<bf16_t, TP, TC> none;
+    none.on = false;
+    __syncthreads();                                            // every wave is done with the operand tiles: they become strips
+    conv_epilogue_auto<bf16_t, TP, TC>(a, acc3, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, unit,
+                                       LinearRows{a.P}, none);
+}
+
+// a: the convolution that carries the residual (its x, w, scale, shift, y); both convolutions 1x1 stride 1 unpadded over
+// 64 channels, a.res unused
+bool pair_k64_applies(const ConvArgs &a, int dt) {
+    return dt == SOL_BF16 && a.R == 1 && a.S == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0 && a.C == 64 && a.Kp == 64 &&
+           a.pool == 0 && a.Cout % 8 == 0 && (double)a.P * a.ldy < 4294967296.0;
+}
+
+sol_status launch_conv_pair_k64(ConvArgs a, const void *x2, const void *w2, const float *scale2, const float *shift2, hipStream_t st) {
+    if (a.P <= 0) return SOL_OK;
+    a.res = nullptr;
+    a.ntc = ceil_div(a.Cout, PR_BC);
+    a.ntiles = ceil_div(a.P, PR_BP) * a.ntc;
+    const int grid = ((a.ntiles + 7) / 8) * 8;
+    hipLaunchKernelGGL(conv_pair_k64_kernel, dim3(grid), dim3(256), 0, st, a, x2, w2, scale2, shift2);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
+}
+
+}  // namespace sol
