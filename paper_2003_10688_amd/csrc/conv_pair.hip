@@ -18,7 +18,7 @@ namespace sol {
 constexpr int PR_BP = 128, PR_BC = 128, PR_ROWB = 128;           // output block; bytes of reduction per row (64 bf16)
 constexpr int PR_OPB = 128 * PR_ROWB;                            // bytes of one operand tile
 
-__global__ void __launch_bounds__(256) conv_pair_k64_kernel(const ConvArgs a, const void *x2v, const void *w2v,
+__global__ void __launch_bounds__(256, 2) conv_pair_k64_kernel(const ConvArgs a, const void *x2v, const void *w2v,
                                                             const float *__restrict__ scale2, const float *__restrict__ shift2) {
     using namespace lds_pipe;
     constexpr int TP = 2, TC = 2, KS = PR_ROWB / 32;
@@ -55,12 +55,11 @@ __global__ void __launch_bounds__(256) conv_pair_k64_kernel(const ConvArgs a, co
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs[o], (__attribute__((address_space(3))) void *)(lds + o * PR_OPB + seg * 1024), 16,
                                                      off, 0, 0, 0);
         }
-    if (tid < PR_BC) {
-        const int c = min(c0 + tid, a.Cout - 1);
-        chan[0][tid] = a.scale ? a.scale[c] : 1.f;
-        chan[1][tid] = scale2 ? scale2[c] : 1.f;
-        chan[2][tid] = (a.shift ? a.shift[c] : 0.f) + (shift2 ? shift2[c] : 0.f);
-    }
+    // per-channel constants: fetched by every thread (uniform instruction count per wave), parked in LDS only after
+    // the contractions -- a store to LDS right here would make the compiler wait for everything issued above
+    const int cc = min(c0 + (tid & (PR_BC - 1)), a.Cout - 1);
+    const float k_s3 = a.scale ? a.scale[cc] : 1.f, k_sd = scale2 ? scale2[cc] : 1.f;
+    const float k_h3 = a.shift ? a.shift[cc] : 0.f, k_hd = shift2 ? shift2[cc] : 0.f;   // first used behind the contractions
 
     f32x16_t acc3[TC][TP], accd[TC][TP];
 #pragma unroll
@@ -72,18 +71,24 @@ __global__ void __launch_bounds__(256) conv_pair_k64_kernel(const ConvArgs a, co
 
     const int lr = lane & 31, lh = lane >> 5;
     const int fsw = swz(lr);                                    // tile row bases are multiples of 32
-    wait_vmcnt<0>();
-    __syncthreads();
+    // the first contraction starts when its two operands are here (8 of this wave's 16 DMA instructions; whatever else
+    // is in flight is younger), the other two land under its MFMAs
+    wait_vmcnt<8>();
+    __builtin_amdgcn_s_barrier();     // bare barriers: a fence would drain the loads that are meant to stay in flight
 
+    // The fragment reads are opaque statements: the compiler, which cannot tell the operands apart, would make every
+    // LDS read wait for all outstanding DMA, also those of the operands the second contraction uses.
     auto contract = [&](f32x16_t (&acc)[TC][TP], const unsigned char *xt, const unsigned char *wt) {
+        const unsigned ax = lds_addr(xt) + (wp * TP * 32 + lr) * PR_ROWB, aw = lds_addr(wt) + (wc * TC * 32 + lr) * PR_ROWB;
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
             const unsigned so = (unsigned)(((2 * ks + lh) ^ fsw) << 4);
-            uint4 fa[TC], fb[TP];
-#pragma unroll
-            for (int i = 0; i < TC; i++) fa[i] = *reinterpret_cast<const uint4 *>(wt + (wc * TC * 32 + i * 32 + lr) * PR_ROWB + so);
-#pragma unroll
-            for (int j = 0; j < TP; j++) fb[j] = *reinterpret_cast<const uint4 *>(xt + (wp * TP * 32 + j * 32 + lr) * PR_ROWB + so);
+            u32x4_t fa[TC], fb[TP];
+            static_for<TC>([&](auto I) { lds_read16<decltype(I)::value * 32 * PR_ROWB>(fa[decltype(I)::value], aw + so); });
+            static_for<TP>([&](auto J) { lds_read16<decltype(J)::value * 32 * PR_ROWB>(fb[decltype(J)::value], ax + so); });
+            wait_lgkmcnt<0>();
+            static_for<TC>([&](auto I) { landed(fa[decltype(I)::value]); });
+            static_for<TP>([&](auto J) { landed(fb[decltype(J)::value]); });
 #pragma unroll
             for (int i = 0; i < TC; i++)
 #pragma unroll
@@ -91,7 +96,11 @@ __global__ void __launch_bounds__(256) conv_pair_k64_kernel(const ConvArgs a, co
         }
     };
     contract(acc3, lds, lds + PR_OPB);
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
     contract(accd, lds + 2 * PR_OPB, lds + 3 * PR_OPB);
+    if (tid < PR_BC) { chan[0][tid] = k_s3; chan[1][tid] = k_sd; chan[2][tid] = k_h3 + k_hd; }
+    __syncthreads();
 
     // accumulator register e of lane l: channel 32 i + 8 (e / 4) + 4 (l / 32) + e % 4 of the wave's block
 #pragma unroll
