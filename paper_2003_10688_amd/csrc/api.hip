@@ -60,7 +60,7 @@ static bool pool_is_fusable(const sol_pool_desc &p) {
     } while (0)
 
 // second operand set of a fused projection pair: y = act(scale * conv(x, w) + shift + scale2 * conv(x2, w2) + shift2)
-struct PairOperand { const void *x2, *w2; const float *scale2, *shift2; };
+struct PairOperand { const void *x2, *w2; const float *scale2, *shift2; int H2, W2, K2, Kp2, stride; };
 
 // Shared by sol_conv2d_fused and the network executor.
 static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, const sol_conv_desc &cd, const void *w,
@@ -124,10 +124,10 @@ static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, cons
     a.dh = FastDiv((uint32_t)(quad ? a.Hy : Ho));
     if (a.pool == 3) return launch_conv_stem_pool(a, st);   // one kernel, no tile choice
     if (pair) {
-        SOL_REQUIRE(res == nullptr && pair_k64_applies(a, xd.dtype), SOL_ERR_UNSUPPORTED,
-                    "a fused projection pair is two bf16 1x1 stride-1 convolutions over 64 channels");
+        SOL_REQUIRE(res == nullptr && pair_applies(a, xd.dtype, pair->H2, pair->W2, pair->K2, pair->Kp2, pair->stride), SOL_ERR_UNSUPPORTED,
+                    "a fused projection pair is two bf16 unpadded 1x1 convolutions over multiples of 64 channels");
         SOL_REQUIRE(pair->x2 && pair->w2 && aligned16(pair->x2) && aligned16(pair->w2), SOL_ERR_NULL, "pair operands");
-        return launch_conv_pair_k64(a, pair->x2, pair->w2, pair->scale2, pair->shift2, st);
+        return launch_conv_pair(a, pair->x2, pair->w2, pair->scale2, pair->shift2, pair->H2, pair->W2, pair->K2, pair->Kp2, pair->stride, st);
     }
     return launch_conv(a, xd.dtype, tile, st);
 }
@@ -516,12 +516,12 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             LayerPlan &c = net->layers[i];
             if (c.L.kind != SOL_LAYER_CONV || c.res < 0 || c.L.pool.kind != SOL_POOL_NONE || c.cout_real || c.cin_real) continue;
             LayerPlan &p = net->layers[c.res];
-            const auto k64 = [](const LayerPlan &l) {
-                return l.cd.kh == 1 && l.cd.kw == 1 && l.cd.sh == 1 && l.cd.sw == 1 && l.cd.ph == 0 && l.cd.pw == 0 && l.cd.cin == 64;
+            const auto pointwise = [](const LayerPlan &l) {      // unpadded 1x1 over a multiple of 64 channels
+                return l.cd.kh == 1 && l.cd.kw == 1 && l.cd.ph == 0 && l.cd.pw == 0 && l.cd.cin % 64 == 0 && l.cd.sh == l.cd.sw;
             };
             if (p.L.kind == SOL_LAYER_CONV && p.L.act == SOL_ACT_NONE && p.res < 0 && p.L.pool.kind == SOL_POOL_NONE && p.nuse == 1 &&
-                !p.elided && !p.absorbs_next && !p.cout_real && !p.cin_real && k64(p) && k64(c) && c.cd.cout % 8 == 0 &&
-                packed_k(c.cd, dt) == 64 && c.src != c.res) {
+                !p.elided && !p.absorbs_next && !p.cout_real && !p.cin_real && pointwise(p) && pointwise(c) && c.cd.sh == 1 &&
+                c.cd.cout % 8 == 0 && c.src != c.res && tensor_bytes(p.in) < (1u << 31) && tensor_bytes(c.in) < (1u << 31)) {
                 c.pair = c.res;
                 p.elided = true;
                 p.no_buffer = true;
@@ -1007,7 +1007,8 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
                     const LayerPlan &pp = net->layers[lp.pair];
                     const PairOperand po{layer_in(net, pp.src, x, ws), net->params + pp.w_off,
                                          reinterpret_cast<const float *>(net->params + pp.scale_off),
-                                         reinterpret_cast<const float *>(net->params + pp.shift_off)};
+                                         reinterpret_cast<const float *>(net->params + pp.shift_off),
+                                         pp.in.h, pp.in.w, pp.cd.cin, packed_k(pp.cd, pp.in.dtype), pp.cd.sh};
                     SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, scale, shift, nullptr, lp.L.act, nullptr, conv_dst,
                                             nullptr, nullptr, T_AUTO, st, ldy, &po));
                     break;

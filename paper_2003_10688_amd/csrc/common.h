@@ -154,9 +154,10 @@ int halo_choose_tile(const ConvArgs &a);
 sol_status launch_conv_halo(const ConvArgs &a, int tile, hipStream_t st);
 bool stem_kernel_applies(const ConvArgs &a, int dt);
 sol_status launch_conv_stem(const ConvArgs &a, hipStream_t st);
-// projection shortcut + the 1x1 convolution it is added to, both over 64 channels, in one kernel (conv_pair.hip)
-bool pair_k64_applies(const ConvArgs &a, int dt);
-sol_status launch_conv_pair_k64(ConvArgs a, const void *x2, const void *w2, const float *scale2, const float *shift2, hipStream_t st);
+// projection shortcut (1x1, stride s, K2 channels on an H2 x W2 grid) + the 1x1 convolution it is added to, in one kernel (conv_pair.hip)
+bool pair_applies(const ConvArgs &a, int dt, int H2, int W2, int K2, int Kp2, int stride);
+sol_status launch_conv_pair(ConvArgs a, const void *x2, const void *w2, const float *scale2, const float *shift2, int H2, int W2, int K2,
+                            int Kp2, int stride, hipStream_t st);
 bool stem_pool_applies(const ConvArgs &a, int dt, const sol_pool_desc &p);   // stem + ReLU + 3x3/2 max pool in one kernel
 sol_status launch_conv_stem_pool(const ConvArgs &a, hipStream_t st);
 bool linear_kernel_applies(const ConvArgs &a, int dt);

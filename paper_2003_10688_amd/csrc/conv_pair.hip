@@ -128,11 +128,171 @@ __global__ void __launch_bounds__(256, 2) conv_pair_k64_kernel(const ConvArgs a,
                                        LinearRows{a.P}, none);
 }
 
+// The same pair for reductions of any multiple of 64 channels and a strided shortcut (the first bottleneck of the later
+// stages: the shortcut reads every second pixel of the previous stage's output).  The reduction runs in chunks of 64
+// channels -- first those of the main convolution, then those of the shortcut, each into its own accumulators --
+// through two LDS stages of one pixel tile + one weight tile; the DMA of chunk c + 1 is in flight while chunk c is
+// contracted, and two workgroups share a CU.
+struct PairGeom {
+    const void *x2, *w2;
+    const float *scale2, *shift2;
+    int H2, W2, K2, Kp2, stride;            // shortcut input extent, channels, packed row length, stride
+};
+
+__global__ void __launch_bounds__(256, 2) conv_pair_kernel(const ConvArgs a, const PairGeom g) {
+    using namespace lds_pipe;
+    constexpr int TP = 2, TC = 2, KS = PR_ROWB / 32, STG = 2 * PR_OPB;
+    __shared__ __align__(1024) unsigned char lds[2 * STG];      // two stages of [pixel tile | weight tile]; later the strips
+    __shared__ __align__(16) float chan[3][PR_BC];
+    static_assert(4 * 32 * (TC * 32 + 4) * 4 <= 2 * STG, "epilogue strips fit in the stages");
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wp = wave & 1, wc = wave >> 1;
+    const int xcd = (int)(blockIdx.x & 7);
+    const int tile = xcd * ((a.ntiles + 7) >> 3) + (int)(blockIdx.x >> 3);
+    if (tile >= a.ntiles) return;
+    const int p0 = (tile / a.ntc) * PR_BP, c0 = (tile % a.ntc) * PR_BC;
+    const int n3 = a.C / 64, nd = g.K2 / 64, nchunk = n3 + nd;
+
+    const __amdgpu_buffer_rsrc_t r_y = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, (int)((unsigned)a.P * a.C * 2u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_w3 = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w), 0, (int)((unsigned)a.Cout * a.Kp * 2u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_x = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(g.x2), 0,
+                                                                         (int)((unsigned)a.N * g.H2 * g.W2 * g.K2 * 2u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_wd = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(g.w2), 0, (int)((unsigned)a.Cout * g.Kp2 * 2u), 0x00020000);
+
+    // this lane's four rows of a pixel tile and of a weight tile: byte offset of the row's chunk 0, slot permuted; rows past
+    // the tensors get an offset beyond every buffer (all buffers are below 2 GB) and read zeros
+    const int lslot = lane & 7, lrow = lane >> 3;
+    auto swz = [](int row) { return (row >> 1) & 7; };
+    constexpr unsigned OOB = 0x80000000u;
+    unsigned oy[4], ox[4], o3[4], od[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        const int row = (i * 4 + wave) * 8 + lrow;
+        const unsigned sl = (unsigned)((lslot ^ swz(row)) << 4);
+        const int m = p0 + row, co = c0 + row;
+        oy[i] = ox[i] = o3[i] = od[i] = OOB;
+        if (m < a.P) {
+            int n, p, q;
+            decode_pixel(a, m, n, p, q);
+            oy[i] = (unsigned)m * (unsigned)a.C * 2u + sl;
+            ox[i] = (unsigned)((n * g.H2 + p * g.stride) * g.W2 + q * g.stride) * (unsigned)g.K2 * 2u + sl;
+        }
+        if (co < a.Cout) {
+            o3[i] = (unsigned)co * (unsigned)a.Kp * 2u + sl;
+            od[i] = (unsigned)co * (unsigned)g.Kp2 * 2u + sl;
+        }
+    }
+    auto issue = [&](int c, int buf) {          // chunk c of the concatenated reduction into stage buf: 8 DMA instructions per wave
+        const bool main = c < n3;
+        const unsigned col = (unsigned)(main ? c : c - n3) * 128u;
+        unsigned char *st = lds + buf * STG;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const int seg = i * 4 + wave;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(main ? r_y : r_x, (__attribute__((address_space(3))) void *)(st + seg * 1024), 16,
+                                                     (main ? oy[i] : ox[i]) + col, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(main ? r_w3 : r_wd, (__attribute__((address_space(3))) void *)(st + PR_OPB + seg * 1024),
+                                                     16, (main ? o3[i] : od[i]) + col, 0, 0, 0);
+        }
+    };
+    issue(0, 0);
+    const int cc = min(c0 + (tid & (PR_BC - 1)), a.Cout - 1);
+    const float k_s3 = a.scale ? a.scale[cc] : 1.f, k_sd = g.scale2 ? g.scale2[cc] : 1.f;
+    const float k_h3 = a.shift ? a.shift[cc] : 0.f, k_hd = g.shift2 ? g.shift2[cc] : 0.f;   // first used behind the loop
+
+    f32x16_t acc3[TC][TP], accd[TC][TP];
+#pragma unroll
+    for (int i = 0; i < TC; i++)
+#pragma unroll
+        for (int j = 0; j < TP; j++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) { acc3[i][j][e] = 0.f; accd[i][j][e] = 0.f; }
+
+    const int lr = lane & 31, lh = lane >> 5;
+    const int fsw = swz(lr);
+    auto contract = [&](f32x16_t (&acc)[TC][TP], unsigned stage) {
+        const unsigned ax = stage + (wp * TP * 32 + lr) * PR_ROWB, aw = stage + PR_OPB + (wc * TC * 32 + lr) * PR_ROWB;
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) {
+            const unsigned so = (unsigned)(((2 * ks + lh) ^ fsw) << 4);
+            u32x4_t fa[TC], fb[TP];
+            static_for<TC>([&](auto I) { lds_read16<decltype(I)::value * 32 * PR_ROWB>(fa[decltype(I)::value], aw + so); });
+            static_for<TP>([&](auto J) { lds_read16<decltype(J)::value * 32 * PR_ROWB>(fb[decltype(J)::value], ax + so); });
+            wait_lgkmcnt<0>();
+            static_for<TC>([&](auto I) { landed(fa[decltype(I)::value]); });
+            static_for<TP>([&](auto J) { landed(fb[decltype(J)::value]); });
+#pragma unroll
+            for (int i = 0; i < TC; i++)
+#pragma unroll
+                for (int j = 0; j < TP; j++) Mma<bf16_t>::run(acc[i][j], fa[i], fb[j]);
+        }
+    };
+    const unsigned lbase = lds_addr(lds);
+    for (int c = 0; c < nchunk; c++) {
+        __builtin_amdgcn_s_barrier();                           // every wave has contracted chunk c - 1: its stage is free
+        if (c + 1 < nchunk) { issue(c + 1, (c + 1) & 1); wait_vmcnt<8>(); } else { wait_vmcnt<0>(); }
+        __builtin_amdgcn_s_barrier();                           // chunk c has landed for every wave (bare barriers: the DMA stays in flight)
+        if (c < n3) contract(acc3, lbase + (c & 1) * STG); else contract(accd, lbase + (c & 1) * STG);
+    }
+    if (tid < PR_BC) { chan[0][tid] = k_s3; chan[1][tid] = k_sd; chan[2][tid] = k_h3 + k_hd; }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TC; i++)
+#pragma unroll
+        for (int gq = 0; gq < 4; gq++) {
+            const int c = wc * TC * 32 + 32 * i + 8 * gq + 4 * lh;
+            const float4 s3 = *reinterpret_cast<const float4 *>(&chan[0][c]), sd = *reinterpret_cast<const float4 *>(&chan[1][c]);
+            const float4 sh = *reinterpret_cast<const float4 *>(&chan[2][c]);
+#pragma unroll
+            for (int j = 0; j < TP; j++) {
+                acc3[i][j][4 * gq + 0] = acc3[i][j][4 * gq + 0] * s3.x + (accd[i][j][4 * gq + 0] * sd.x + sh.x);
+                acc3[i][j][4 * gq + 1] = acc3[i][j][4 * gq + 1] * s3.y + (accd[i][j][4 * gq + 1] * sd.y + sh.y);
+                acc3[i][j][4 * gq + 2] = acc3[i][j][4 * gq + 2] * s3.z + (accd[i][j][4 * gq + 2] * sd.z + sh.z);
+                acc3[i][j][4 * gq + 3] = acc3[i][j][4 * gq + 3] * s3.w + (accd[i][j][4 * gq + 3] * sd.w + sh.w);
+            }
+        }
+    Affine8 unit;
+#pragma unroll
+    for (int e = 0; e < 8; e++) { unit.sc[e] = 1.f; unit.sf[e] = 0.f; }
+    ResidualRegs<bf16_t, TP, TC> none;
+    none.on = false;
+    __syncthreads();
+    conv_epilogue_auto<bf16_t, TP, TC>(a, acc3, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, unit,
+                                       LinearRows{a.P}, none);
+}
+
 // a: the convolution that carries the residual (its x, w, scale, shift, y); both convolutions 1x1 stride 1 unpadded over
 // 64 channels, a.res unused
 bool pair_k64_applies(const ConvArgs &a, int dt) {
     return dt == SOL_BF16 && a.R == 1 && a.S == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0 && a.C == 64 && a.Kp == 64 &&
            a.pool == 0 && a.Cout % 8 == 0 && (double)a.P * a.ldy < 4294967296.0;
+}
+
+sol_status launch_conv_pair_k64(ConvArgs a, const void *x2, const void *w2, const float *scale2, const float *shift2, hipStream_t st);
+
+// a: the main convolution (1x1 stride 1 unpadded, Cin a multiple of 64); shortcut: 1x1, stride s in both directions, unpadded,
+// K2 input channels (a multiple of 64) on an H2 x W2 grid whose strided samples are a's output pixels
+bool pair_applies(const ConvArgs &a, int dt, int H2, int W2, int K2, int Kp2, int stride) {
+    return dt == SOL_BF16 && a.R == 1 && a.S == 1 && a.sh == 1 && a.sw == 1 && a.ph == 0 && a.pw == 0 && a.C % 64 == 0 && a.Kp == a.C &&
+           K2 % 64 == 0 && Kp2 == K2 && stride >= 1 && (a.Ho - 1) * stride < H2 && (a.Wo - 1) * stride < W2 && a.pool == 0 &&
+           a.Cout % 8 == 0 && (double)a.P * a.ldy < 4294967296.0 && (double)a.P * a.C * 2 < 2147483648.0 &&
+           (double)a.N * H2 * W2 * K2 * 2 < 2147483648.0 && (double)a.Cout * (a.Kp > Kp2 ? a.Kp : Kp2) * 2 < 2147483648.0;
+}
+
+sol_status launch_conv_pair(ConvArgs a, const void *x2, const void *w2, const float *scale2, const float *shift2, int H2, int W2, int K2,
+                            int Kp2, int stride, hipStream_t st) {
+    if (a.P <= 0) return SOL_OK;
+    if (a.C == 64 && K2 == 64 && stride == 1 && H2 == a.Ho && W2 == a.Wo) return launch_conv_pair_k64(a, x2, w2, scale2, shift2, st);
+    a.res = nullptr;
+    a.ntc = ceil_div(a.Cout, PR_BC);
+    a.ntiles = ceil_div(a.P, PR_BP) * a.ntc;
+    const int grid = ((a.ntiles + 7) / 8) * 8;
+    const PairGeom g{x2, w2, scale2, shift2, H2, W2, K2, Kp2, stride};
+    hipLaunchKernelGGL(conv_pair_kernel, dim3(grid), dim3(256), 0, st, a, g);
+    SOL_HIP(hipGetLastError());
+    return SOL_OK;
 }
 
 sol_status launch_conv_pair_k64(ConvArgs a, const void *x2, const void *w2, const float *scale2, const float *shift2, hipStream_t st) {

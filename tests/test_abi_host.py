@@ -151,11 +151,15 @@ def test_plan_fuses_stem_and_pool_only_when_it_may(sol):
     wk = wl.config(3)
     n = len(wk.layers)
     r, ws = fused(wk.layers, wk.in_shape, sol.BF16)
-    # the pool runs inside the stem's launch; the stride-1 projection shortcut of the first bottleneck (layer 4, 64
-    # channels in) runs inside the launch of the 1x1 convolution that adds it (layer 5); the strided ones do not
+    # the pool runs inside the stem's launch; the projection shortcut of every stage's first bottleneck (a 1x1
+    # convolution without activation, read only as a residual) runs inside the launch of the 1x1 convolution that adds it
     want = list(range(n))
-    want[1], want[4] = 0, 5
-    assert wk.layers[5]["res"] == 4 and r == want
+    want[1] = 0
+    shortcuts = [l["res"] for l in wk.layers if l["kind"] == "conv" and l.get("res", -1) >= 0 and wk.layers[l["res"]]["act"] == "none"]
+    assert len(shortcuts) == 4 and shortcuts[0] == 4
+    for j in shortcuts:
+        want[j] = j + 1
+    assert r == want
     r_keep, ws_keep = fused(wk.layers, wk.in_shape, sol.BF16, sol.NET_KEEP_ACTIVATIONS)
     assert r_keep == list(range(n)) and ws_keep > ws
     assert fused(wk.layers, wk.in_shape, sol.BF16, sol.NET_TRAINING)[0] == list(range(n))

@@ -780,6 +780,29 @@ def test_projection_pair(sol, shape, cout):
     assert norm_err(ys[False], ys[True].astype(np.float64)) <= TOL["bf16"] / 4
 
 
+@pytest.mark.parametrize("cp,cm,stride,cout,hw", [(128, 64, 2, 256, (20, 24)), (64, 128, 1, 128, (9, 7)), (192, 64, 2, 72, (21, 19)),
+                                                  (256, 128, 2, 512, (14, 14))])
+def test_projection_pair_general(sol, cp, cm, stride, cout, hw):
+    """The same pair with reductions of several 64-channel chunks and a strided shortcut (the shape of the first
+    bottleneck of a later stage): x(cp) -> 1x1 cm -> 3x3/stride cm -> 1x1 cout (+ 1x1/stride shortcut of x) -> ReLU."""
+    c = wl.conv
+    layers = [c(cp, 3), c(cm, 1, p=0, src=0), c(cm, 3, s=stride, src=1), c(cout, 1, s=stride, p=0, act="none", src=0),
+              c(cout, 1, p=0, src=2, res=3), c(16, 1, p=0)]
+    rng = np.random.default_rng(cp + cout)
+    x = _grid(rng.standard_normal((2, 3) + hw), "bf16")
+    prm = wl.make_params(layers, 3, 77 + cout, bf16=True, bias_std=0.3)
+    outs, _ = orc.network_forward(layers, prm, x, bf16=True, return_all=True)
+    ys = {}
+    for keep in (False, True):
+        net = sol.Network(layers, x.shape, sol.BF16, flags=sol.NET_KEEP_ACTIVATIONS if keep else 0)
+        net.set_params(prm)
+        ys[keep] = sol.to_host_nchw(net.forward(sol.to_device_nhwc(x, sol.BF16)))
+        torch.cuda.synchronize()
+        assert [net.fused_into(i) for i in range(6)] == ([0, 1, 2, 3, 4, 5] if keep else [0, 1, 2, 4, 4, 5])
+    assert rel_err(ys[False].reshape(outs[-1].shape), outs[-1]) <= 2 * TOL["bf16"]
+    assert norm_err(ys[False], ys[True].astype(np.float64)) <= TOL["bf16"] / 4
+
+
 # ---- channel concatenation, written in place by the producers where the plan allows ----------------------------------
 def _concat_nets():
     c, cat, pool = wl.conv, wl.concat, wl.pool
