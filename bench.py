@@ -24,7 +24,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM bytes per convolution launch of the ResNet-50-shaped batch-64 pass, from the FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/conv_resnet50_bs64_hbm_traffic.md (calibrated on the stem pool kernel of the same runs)
-MEASURED_CONV_TRAFFIC_MB_PER_LAUNCH = 71.7
+MEASURED_CONV_TRAFFIC_MB_PER_LAUNCH = 72.2
 
 
 def layer_shapes(layers, in_shape, out_size):

@@ -229,9 +229,9 @@ void sol_graph_destroy(sol_graph *graph);
  * (flags 0), bf16:
  *   - a 7x7 stride-2 convolution of a 3-channel input with 64 filters, ReLU and no residual whose only consumer is
  *     a 3x3 stride-2 pad-1 max-pool LAYER runs in one kernel with that pool; the convolution's output is never stored;
- *   - a 1x1 stride-1 convolution over 64 channels without activation (a projection shortcut) whose only reader is
- *     the residual input of a later 1x1 stride-1 convolution over 64 channels runs inside that convolution's
- *     launch; its output is never stored, and never rounded to the storage type either (the result differs from
+ *   - an unpadded 1x1 convolution (any stride) over a multiple of 64 channels without activation (a projection
+ *     shortcut) whose only reader is the residual input of a later unpadded 1x1 stride-1 convolution over a multiple
+ *     of 64 channels runs inside that convolution's launch; its output is never stored, and never rounded to the storage type either (the result differs from
  *     the two-launch result by at most one rounding of the shortcut term).
  * *into = index of the layer whose launch produces `layer`'s output: `layer` itself, the layer in front for such a
  * pool layer, the later convolution for such a shortcut (sol_network_run_layer on a fused layer launches nothing). */
