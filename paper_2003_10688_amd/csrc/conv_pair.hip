@@ -12,6 +12,7 @@
 // most one bf16 rounding of the shortcut term (well inside the tolerance of the library).
 // Overlap of loads, MFMAs and stores comes from two resident workgroups per CU; the job is bound by HBM.
 #include "conv_common.h"
+#include <type_traits>
 
 namespace sol {
 
@@ -80,20 +81,30 @@ __global__ void __launch_bounds__(256, 2) conv_pair_k64_kernel(const ConvArgs a,
     // LDS read wait for all outstanding DMA, also those of the operands the second contraction uses.
     auto contract = [&](f32x16_t (&acc)[TC][TP], const unsigned char *xt, const unsigned char *wt) {
         const unsigned ax = lds_addr(xt) + (wp * TP * 32 + lr) * PR_ROWB, aw = lds_addr(wt) + (wc * TC * 32 + lr) * PR_ROWB;
-#pragma unroll
-        for (int ks = 0; ks < KS; ks++) {
+        // two fragment sets alternate: the reads of k-step ks + 1 fly under the MFMAs of k-step ks
+        u32x4_t fa[2][TC], fb[2][TP];
+        auto read_set = [&](auto SET, int ks) {
+            constexpr int set = decltype(SET)::value;
             const unsigned so = (unsigned)(((2 * ks + lh) ^ fsw) << 4);
-            u32x4_t fa[TC], fb[TP];
-            static_for<TC>([&](auto I) { lds_read16<decltype(I)::value * 32 * PR_ROWB>(fa[decltype(I)::value], aw + so); });
-            static_for<TP>([&](auto J) { lds_read16<decltype(J)::value * 32 * PR_ROWB>(fb[decltype(J)::value], ax + so); });
-            wait_lgkmcnt<0>();
-            static_for<TC>([&](auto I) { landed(fa[decltype(I)::value]); });
-            static_for<TP>([&](auto J) { landed(fb[decltype(J)::value]); });
+            static_for<TC>([&](auto I) { lds_read16<decltype(I)::value * 32 * PR_ROWB>(fa[set][decltype(I)::value], aw + so); });
+            static_for<TP>([&](auto J) { lds_read16<decltype(J)::value * 32 * PR_ROWB>(fb[set][decltype(J)::value], ax + so); });
+        };
+        read_set(std::integral_constant<int, 0>{}, 0);
+        static_for<KS>([&](auto KSI) {
+            constexpr int ks = decltype(KSI)::value, cur = ks & 1;
+            if constexpr (ks + 1 < KS) {
+                read_set(std::integral_constant<int, cur ^ 1>{}, ks + 1);
+                wait_lgkmcnt<TC + TP>();           // LDS returns in order: all but the newest TC + TP reads are done
+            } else {
+                wait_lgkmcnt<0>();
+            }
+            static_for<TC>([&](auto I) { landed(fa[cur][decltype(I)::value]); });
+            static_for<TP>([&](auto J) { landed(fb[cur][decltype(J)::value]); });
 #pragma unroll
             for (int i = 0; i < TC; i++)
 #pragma unroll
-                for (int j = 0; j < TP; j++) Mma<bf16_t>::run(acc[i][j], fa[i], fb[j]);
-        }
+                for (int j = 0; j < TP; j++) Mma<bf16_t>::run(acc[i][j], fa[cur][i], fb[cur][j]);
+        });
     };
     contract(acc3, lds, lds + PR_OPB);
     wait_vmcnt<0>();
@@ -214,6 +225,8 @@ __global__ void __launch_bounds__(256, 2) conv_pair_kernel(const ConvArgs a, con
     const int fsw = swz(lr);
     auto contract = [&](f32x16_t (&acc)[TC][TP], unsigned stage) {
         const unsigned ax = stage + (wp * TP * 32 + lr) * PR_ROWB, aw = stage + PR_OPB + (wc * TC * 32 + lr) * PR_ROWB;
+        // one fragment set here: a second set (reads of the next k-step under these MFMAs) pays in the 64-channel
+        // kernel above, but with this kernel's per-lane gather offsets live it spills registers and runs slower
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
             const unsigned so = (unsigned)(((2 * ks + lh) ^ fsw) << 4);
