@@ -186,7 +186,7 @@ def main():
                                             key: round(sum(r["flops" if key == "tflops" else "bytes"] for r in rs) / max(sum(r["us"] for r in rs), 1e-9) / scale, 2),
                                             "frac": round(sum(r["flops" if key == "tflops" else "bytes"] for r in rs) / max(sum(r["us"] for r in rs), 1e-9) / scale / peak, 4)}
         roofline = {
-            "bound": "mfma", "kernel": "fused convolution kernels (conv_dma / conv_halo / conv_gemm8 / conv_stem)", "launches_per_step": len(conv),
+            "bound": "mfma", "kernel": "fused convolution kernels (conv_dma / conv_halo / conv_gemm8 / conv_stem_pool / conv_pair)", "launches_per_step": len(conv),
             "achieved": round(tfl, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl / PEAK_BF16_TFLOPS, 4),
             "avg_launch_us": round(conv_us / len(conv), 2), "algorithmic_gflop_per_launch": round(conv_fl / len(conv) / 1e9, 3),
             "traffic": ({"hbm_mb_per_launch": MEASURED_CONV_TRAFFIC_MB_PER_LAUNCH, "algorithmic_mb_per_launch": round(conv_by / len(conv) / 1e6, 1),
