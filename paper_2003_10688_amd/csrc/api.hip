@@ -116,9 +116,6 @@ static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, cons
     const bool quad = a.pool == 1 || a.pool == 2;
     a.argmax = a.pool == 1 ? argmax : nullptr;
     a.prepool = quad ? prepool : nullptr;
-#ifdef SOL_PHASE_TIMING
-    a.prepool = prepool;   // profiling build: receives per-phase cycle counts
-#endif
     a.P = quad ? xd.n * a.Hy * a.Wy * 4 : xd.n * Ho * Wo;
     a.dw = FastDiv((uint32_t)(quad ? a.Wy : Wo));
     a.dh = FastDiv((uint32_t)(quad ? a.Hy : Ho));

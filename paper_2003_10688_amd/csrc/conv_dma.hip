@@ -73,9 +73,6 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
     __shared__ __align__(1024) unsigned char lds[NS * STAGE];
     __shared__ __align__(256) unsigned char l2sink[NW * 256];   // write-only landing pad of the L2 warm-up loads
 
-#ifdef SOL_PHASE_TIMING
-    const long long tentry_ = __builtin_readcyclecounter();
-#endif
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wp = wave % WP, wc = wave / WP;
@@ -215,19 +212,10 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
         static_for<TP>([&](auto J) { lds_read16_async<decltype(J)::value * 32 * ROWB>(fb[set][decltype(J)::value], ax); });
     };
 
-#ifdef SOL_PHASE_TIMING
-    long long tw_ = 0, tb_ = 0, tc_ = 0, t0_ = 0, t1_ = 0, t2_ = 0, tstart_ = __builtin_readcyclecounter();
-#define PT(x) x = __builtin_readcyclecounter()
-#else
-#define PT(x)
-#endif
     for (int kc = 0; kc < nk; kc++) {
-        PT(t0_);
         // stage kc has landed once at most the (NS-2) stages issued after it are outstanding
         if (kc + NS - 2 < nk) wait_vmcnt<(NS - 2) * L>(); else wait_vmcnt<0>();
-        PT(t1_);
         __syncthreads();                           // ... for every wave; and stage kc-1 is no longer read
-        PT(t2_);
         const bool more = kc + NS - 1 < nk;        // a stage to prefetch during this iteration?
         const int nbuf = (kc + NS - 1) % NS, ntap = tap;
         const unsigned nxs = x_soff(), nws = (unsigned)((kc + NS - 1) * BK) * ES;
@@ -259,27 +247,10 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
             });
         });
         if (more) next_tap();
-#ifdef SOL_PHASE_TIMING
-        asm volatile("s_nop 0" ::: "memory");
-        tw_ += t1_ - t0_; tb_ += t2_ - t1_; PT(t0_); tc_ += t0_ - t2_;
-#endif
     }
-#ifdef SOL_PHASE_TIMING
-    if (a.argmax == nullptr && a.prepool && lane == 0 && (blockIdx.x % 37) == 0 && wave < 4) {
-        long long *dbg = reinterpret_cast<long long *>(a.prepool) + ((blockIdx.x / 37) % 8 * 4 + wave) * 8;
-        dbg[0] = tw_; dbg[1] = tb_; dbg[2] = tstart_ - tentry_; dbg[3] = tc_; dbg[4] = __builtin_readcyclecounter() - tstart_; dbg[5] = nk;
-    }
-    const long long tepi_ = __builtin_readcyclecounter();
-#endif
     __syncthreads();                               // every wave is done with the tiles: the ring becomes strips
     conv_epilogue_auto<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds), wave, lane, p0 + wp * TP * 32, c0 + wc * TC * 32,
                              aff, LinearRows{a.P}, resregs);
-#ifdef SOL_PHASE_TIMING
-    if (a.argmax == nullptr && a.prepool && lane == 0 && (blockIdx.x % 37) == 0 && wave < 4) {
-        long long *dbg = reinterpret_cast<long long *>(a.prepool) + ((blockIdx.x / 37) % 8 * 4 + wave) * 8;
-        dbg[6] = __builtin_readcyclecounter() - tepi_; dbg[7] = __builtin_readcyclecounter() - tentry_;
-    }
-#endif
 #endif
 }
 
