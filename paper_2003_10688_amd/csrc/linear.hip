@@ -23,8 +23,8 @@ __global__ void __launch_bounds__(512) linear_kernel(const ConvArgs a) {
     const T *__restrict__ wg = static_cast<const T *>(a.w);
 
     const bool wok = n0 + lr < N, xok = m0 + lr < M;
-    const T *wp = wg + (size_t)(wok ? n0 + lr : 0) * a.Kp + lh * EPC;
-    const T *xp = xg + (size_t)(xok ? m0 + lr : 0) * K + lh * EPC;
+    const T *wp = wg + (size_t)(wok ? n0 + lr : 0) * a.Kp;
+    const T *xp = xg + (size_t)(xok ? m0 + lr : 0) * K;
     const uint4 zero = make_uint4(0, 0, 0, 0);
 
     f32x16_t acc;
@@ -33,16 +33,23 @@ __global__ void __launch_bounds__(512) linear_kernel(const ConvArgs a) {
 
     const int nsteps = (K + 2 * EPC - 1) / (2 * EPC);   // one step = 2*EPC reduction elements (both lane halves); K % EPC == 0
     for (int s0 = wave * UN; s0 < nsteps; s0 += NWV * UN) {
+        // Every lane loads every step, from a clamped address (the start of a valid row), and what it must not use is
+        // replaced by zeros after the last load is issued: a load behind a condition, or a use of its value between
+        // the loads, makes the compiler wait for it before it issues the next one.
         uint4 fa[UN], fb[UN];
+        auto k_of = [&](int u) { return (s0 + u) * 2 * EPC + lh * EPC; };   // < K, or: past the end / ragged last step
 #pragma unroll
         for (int u = 0; u < UN; u++) {
-            const int k = (s0 + u) * 2 * EPC;
-            const bool ok = k + lh * EPC < K;          // also false for steps past the end; a ragged last step feeds zeros to the upper lanes
-            fa[u] = (ok && wok) ? *reinterpret_cast<const uint4 *>(wp + k) : zero;
-            fb[u] = (ok && xok) ? *reinterpret_cast<const uint4 *>(xp + k) : zero;
+            const int k = k_of(u), kk = k < K ? k : 0;
+            fa[u] = *reinterpret_cast<const uint4 *>(wp + kk);
+            fb[u] = *reinterpret_cast<const uint4 *>(xp + kk);
         }
+        __builtin_amdgcn_sched_barrier(0);             // all 2 * UN loads are in flight before the first value is needed
 #pragma unroll
-        for (int u = 0; u < UN; u++) Mma<T>::run(acc, fa[u], fb[u]);
+        for (int u = 0; u < UN; u++) {
+            const bool ok = k_of(u) < K;
+            Mma<T>::run(acc, (ok && wok) ? fa[u] : zero, (ok && xok) ? fb[u] : zero);
+        }
     }
 
     // accumulator register e of lane l: feature 8*(e/4) + 4*(l/32) + e%4, row l%32.  Every wave parks its partial
