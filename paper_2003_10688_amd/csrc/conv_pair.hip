@@ -244,9 +244,9 @@ __global__ void __launch_bounds__(256, 2) conv_pair_kernel(const ConvArgs a, con
     };
     const unsigned lbase = lds_addr(lds);
     for (int c = 0; c < nchunk; c++) {
-        __builtin_amdgcn_s_barrier();                           // every wave has contracted chunk c - 1: its stage is free
-        if (c + 1 < nchunk) { issue(c + 1, (c + 1) & 1); wait_vmcnt<8>(); } else { wait_vmcnt<0>(); }
-        __builtin_amdgcn_s_barrier();                           // chunk c has landed for every wave (bare barriers: the DMA stays in flight)
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();                           // chunk c has landed for every wave, and every wave has contracted chunk c - 1
+        if (c + 1 < nchunk) issue(c + 1, (c + 1) & 1);
         if (c < n3) contract(acc3, lbase + (c & 1) * STG); else contract(accd, lbase + (c & 1) * STG);
     }
     if (tid < PR_BC) { chan[0][tid] = k_s3; chan[1][tid] = k_sd; chan[2][tid] = k_h3 + k_hd; }
