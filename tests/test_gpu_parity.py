@@ -342,7 +342,8 @@ def test_global_avgpool(sol, dt, shape):
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("shape", [(64, 2048, 1000), (64, 64, 10), (5, 100, 33), (1, 7, 3), (130, 512, 1000), (200, 96, 40),
-                                   (1100, 64, 8), (32, 1000, 512), (9, 24, 16)])     # the last two: rows end in half an MFMA step
+                                   (1100, 64, 8), (32, 1000, 512), (9, 24, 16),      # the last two: rows end in half an MFMA step
+                                   (3, 8, 5), (33, 16, 31), (64, 8200, 40)])         # one fragment per row; rounds that run past the end
 def test_linear(sol, dt, shape):
     M, I, O = shape
     rng = np.random.default_rng(29)
