@@ -194,6 +194,21 @@ sol_status sol_network_set_params(sol_network *net, int layer, const float *w, c
 sol_status sol_network_forward(sol_network *net, const void *x, void *y, void *workspace,
                                size_t workspace_bytes, void *hip_stream);
 
+/* For callers that cannot allocate device memory or hold a workspace of their own (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): sol_network_forward with the activations between the layers
+ * kept in a static device array of the library, SOL_STATIC_WORKSPACE_BYTES per GPU, resident from the library's load
+ * until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no allocating library routine).
+ *   net     an inference network (SOL_ERR_UNSUPPORTED for SOL_NET_TRAINING) whose sol_network_workspace_bytes() is at
+ *           most SOL_STATIC_WORKSPACE_BYTES (else SOL_ERR_WORKSPACE, nothing launched)
+ *   x, y    device pointers as for sol_network_forward (caller-owned input and output of the last layer)
+ * Runs on the current device (the stream must belong to it).  Results are those of sol_network_forward bit for bit.
+ * Every call on one GPU uses the same array, which keeps the previous call's contents; every buffer of a pass is
+ * written before it is read, so nothing needs clearing, but two calls whose execution overlaps on one GPU (different
+ * streams, or different threads) race on it: serialise them.  Kept activations (sol_network_layer_output) are not
+ * reachable through this call. */
+#define SOL_STATIC_WORKSPACE_BYTES (32u << 20)
+sol_status sol_network_forward_static(sol_network *net, const void *x, void *y, void *hip_stream);
+
 /* Plan-time micro auto-tune (the paper's optimizer picks per-layer implementations by heuristics or a very short
  * auto-tuning run when the model is optimized, Sec. III-A): times every kernel / tile shape that fits each
  * convolution layer, `reps` launches each on the caller's buffers, and keeps the fastest per layer for all later

@@ -3,6 +3,7 @@
 #include <stdarg.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1052,6 +1053,41 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
 sol_status sol_network_forward(sol_network *net, const void *x, void *y, void *workspace, size_t workspace_bytes, void *stream) {
     SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
     return run_layers(net, x, y, workspace, workspace_bytes, 0, (int)net->layers.size() - 1, (hipStream_t)stream);
+}
+
+// ---- forward pass with the activations in a static device array (allocates nothing, needs no caller workspace) ---------
+// `scratch` below is a host-side stand-in for the device array: only the address hipGetSymbolAddress returns for
+// the current device may be handed to kernels.  It is looked up once per device (every GPU holds its own copy of
+// the array at its own address) and kept.
+static __device__ __align__(256) unsigned char scratch[SOL_STATIC_WORKSPACE_BYTES];
+static constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static unsigned char *g_scratch_ptr[kMaxDevices];      // per device, nullptr until that device's first call
+
+static sol_status static_scratch(unsigned char **out) {
+    int dev = -1;
+    SOL_HIP(hipGetDevice(&dev));
+    SOL_REQUIRE(dev >= 0 && dev < kMaxDevices, SOL_ERR_UNSUPPORTED, "device ordinal %d beyond the %d this library keeps scratch addresses for", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        SOL_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        SOL_REQUIRE(p && aligned16(p), SOL_ERR_HIP, "hipGetSymbolAddress returned %p for the static workspace", p);
+        g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return SOL_OK;
+}
+
+sol_status sol_network_forward_static(sol_network *net, const void *x, void *y, void *stream) {
+    SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
+    SOL_REQUIRE(!net->training, SOL_ERR_UNSUPPORTED, "the static-workspace forward runs inference networks only (a backward pass needs the caller's workspace)");
+    SOL_REQUIRE(net->ws_bytes <= (size_t)SOL_STATIC_WORKSPACE_BYTES, SOL_ERR_WORKSPACE,
+                "network needs %zu bytes of workspace, the static workspace holds %zu (SOL_STATIC_WORKSPACE_BYTES); use sol_network_forward", net->ws_bytes,
+                (size_t)SOL_STATIC_WORKSPACE_BYTES);
+    unsigned char *ws = nullptr;
+    SOL_TRY(static_scratch(&ws));
+    return run_layers(net, x, y, ws, (size_t)SOL_STATIC_WORKSPACE_BYTES, 0, (int)net->layers.size() - 1, (hipStream_t)stream);
 }
 
 // ---- plan-time micro auto-tune ------------------------------------------------------------------------------

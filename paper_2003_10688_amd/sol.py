@@ -75,6 +75,7 @@ def lib():
         L.sol_graph_destroy.restype = None
         L.sol_graph_launch.argtypes = [C.c_void_p, C.c_void_p]
         L.sol_debug_set_conv_tile.restype = None
+        L.sol_network_forward_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -307,6 +308,11 @@ class Network:
         """x: NHWC device tensor; returns the (reused) output tensor of the last layer."""
         _check(lib().sol_network_forward(self._h, _ptr(x), _ptr(self.y), _ptr(self.workspace),
                                          C.c_size_t(self.workspace.numel()), _stream(stream)))
+        return self.y
+
+    def forward_static(self, x, stream=None):
+        """sol_network_forward_static: the same pass with the library's static device array as workspace."""
+        _check(lib().sol_network_forward_static(self._h, _ptr(x), _ptr(self.y), _stream(stream)))
         return self.y
 
     def autotune(self, x, reps=10, stream=None):
