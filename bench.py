@@ -2,9 +2,11 @@
 """Benchmark: ResNet-50-shaped inference forward, batch 64, bf16 storage / fp32 accumulate, one MI355X.
 
 A "step" is one pass of the whole hot path (every fused conv, the stem pool, the global average
-pool and the linear layer: 56 launches) over one resident batch of synthetic images.  Prints ONE
-JSON line with images/s, the roofline of the dominant kernel (the implicit-GEMM convolution,
-53 launches per step) and the CPU checker timed on a bounded sample of the same workload.
+pool and the linear layer: 56 layers, fewer launches where the plan fuses layers -- the JSON line
+says how many) over one resident batch of synthetic images.  Prints ONE JSON line with images/s, the
+roofline of the dominant kernel (the fused convolution launches) from durations measured inside whole
+passes, the machine's measured ceilings, the CPU checker timed on a bounded sample of the same workload,
+and the error of the timed network's output against that checker run.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 """
@@ -22,9 +24,19 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
-# HBM bytes per convolution launch of the ResNet-50-shaped batch-64 pass, from the FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/conv_resnet50_bs64_hbm_traffic.md (calibrated on the stem pool kernel of the same runs)
-MEASURED_CONV_TRAFFIC_MB_PER_LAUNCH = 72.2
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "conv_resnet50_bs64_hbm_traffic.md")
+
+
+def measured_traffic():
+    """HBM bytes per convolution launch of the ResNet-50-shaped batch-64 pass, read from the committed summary of the
+    FETCH_SIZE / WRITE_SIZE counter runs (its line "per launch <x> MB"); None when the summary is not there."""
+    import re
+    try:
+        with open(TRAFFIC_SUMMARY) as f:
+            m = re.search(r"convolution launches of one pass:.*?per launch ([0-9.]+) MB", f.read())
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
 
 
 def layer_shapes(layers, in_shape, out_size):
@@ -73,6 +85,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload: 3 = ResNet-50-shaped bs64 (default), 2 = ResNet-18-shaped bs32, 5 = 3-layer MLP with 8192 features bs64, 6 = depthwise-separable chain bs64, 7 = SqueezeNet-shaped bs64 (channel concatenations)")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--layer-reps", type=int, default=20, help="event-timed repetitions per layer for the roofline")
+    ap.add_argument("--pass-reps", type=int, default=20, help="whole passes with an event in front of every launch (in-pass durations for the roofline)")
     ap.add_argument("--cpu-sample", type=int, default=32, help="images the CPU checker is timed on (0 = skip); 32 is 10-15 s of CPU work")
     ap.add_argument("--layers", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--graph", action="store_true", help="time HIP-graph replays of the pass instead of plain launches")
@@ -119,7 +132,7 @@ def main():
             json.dump(tuned, f)
 
     # ---- whole-step throughput -------------------------------------------------------------------
-    # One step = one forward pass: 56 plain launches on one stream.  --graph replays the same pass from a HIP
+    # One step = one forward pass: plain launches on one stream.  --graph replays the same pass from a HIP
     # graph recorded through the library instead (sol_network_graph_create); measured, it makes no difference
     # here -- the step is bound by the kernels and the drain between dependent launches, not by submission.
     def timed(step_fn, st):
@@ -171,11 +184,66 @@ def main():
                 fl += fj
                 by += bj - 2 * esize * numel(outs[j])
         rows.append({"i": i, "kind": "dwconv" if l.get("dw") else l["kind"], "us": us, "flops": fl, "bytes": by})
+    # ---- the same launches timed inside whole passes (cold weights, inputs as the producer left them): an event in
+    # front of every launch of a pass.  A long register-only kernel goes first so that the host has queued the whole
+    # pass before its first launch starts (an event otherwise also measures the wait for the next submission).
+    launched = [r for r in rows if r["kind"] != "fused"]
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+    acc_us = [0.0] * len(launched)
+    for _ in range(a.pass_reps):
+        sol.sol_debug_probe_mfma(40000, 256, sink, stream)           # about 3 ms
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(len(launched) + 1)]
+        for k, r in enumerate(launched):
+            evs[k].record(stream)
+            net.run_layer(r["i"], x, stream)
+        evs[-1].record(stream)
+        torch.cuda.synchronize()
+        for k in range(len(launched)):
+            acc_us[k] += evs[k].elapsed_time(evs[k + 1]) * 1e3
+    for k, r in enumerate(launched):
+        r["us_pass"] = acc_us[k] / max(a.pass_reps, 1) if a.pass_reps > 0 else r["us"]
+    # An event between two launches costs about 3 us that the timed passes do not pay (it keeps the next launch from
+    # being set up under the tail of the previous one), so the instrumented pass is longer than the timed one.  The
+    # per-launch durations are scaled by one common factor so that they add up to the timed pass: the timed region
+    # itself is what the roofline figures divide by.
+    marker_scale = (eager_ev_ms * 1e3) / max(sum(r["us_pass"] for r in launched), 1e-9) if a.pass_reps > 0 else 1.0
+    marker_scale = min(marker_scale, 1.0)
+    for r in launched:
+        r["us_pass_raw"] = r["us_pass"]
+        r["us_pass"] *= marker_scale
+    for r in rows:
+        r.setdefault("us_pass", 0.0)
+
+    # ---- measured ceilings of this machine: a plain 100 MB copy and a register-resident MFMA loop
+    cbuf = torch.empty(2 * 100 * (1 << 20), dtype=torch.uint8, device="cuda:0")
+    src_b, dst_b = cbuf[:100 << 20], cbuf[100 << 20:]
+
+    def ev_time(fn, reps):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+    copy_s = ev_time(lambda: sol.sol_debug_probe_copy(dst_b, src_b, stream), 20)
+    flop_box = [0.0]
+
+    def mfma_once():
+        flop_box[0] = sol.sol_debug_probe_mfma(4000, 1024, sink, stream)
+    mfma_s = ev_time(mfma_once, 5)
+    measured_peak = {"hbm_copy_gbs": round(2 * (100 << 20) / copy_s / 1e9, 1), "hbm_copy_mb": 104.9,
+                     "mfma_bf16_tflops": round(flop_box[0] / mfma_s / 1e12, 1),
+                     "source": "sol_debug_probe_copy / sol_debug_probe_mfma, this run"}
+    del cbuf
+
     conv = [r for r in rows if r["kind"] == "conv"]
     mem = [r for r in rows if r["kind"] in ("pool", "gap")]
     dwr = [r for r in rows if r["kind"] == "dwconv"]
     if conv:
-        conv_us = sum(r["us"] for r in conv)
+        conv_us = sum(r["us_pass"] for r in conv)           # durations inside whole passes
+        conv_us_hot = sum(r["us"] for r in conv)            # the same launches repeated back to back on hot buffers
         conv_fl = sum(r["flops"] for r in conv)
         conv_by = sum(r["bytes"] for r in conv)
         ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
@@ -183,30 +251,34 @@ def main():
         hb = [r for r in conv if r["flops"] / r["bytes"] < ridge]
         tfl = conv_fl / (conv_us * 1e-6) / 1e12
         grp = lambda rs, key, peak, scale: {"n": len(rs),  # noqa: E731
-                                            key: round(sum(r["flops" if key == "tflops" else "bytes"] for r in rs) / max(sum(r["us"] for r in rs), 1e-9) / scale, 2),
-                                            "frac": round(sum(r["flops" if key == "tflops" else "bytes"] for r in rs) / max(sum(r["us"] for r in rs), 1e-9) / scale / peak, 4)}
+                                            key: round(sum(r["flops" if key == "tflops" else "bytes"] for r in rs) / max(sum(r["us_pass"] for r in rs), 1e-9) / scale, 2),
+                                            "frac": round(sum(r["flops" if key == "tflops" else "bytes"] for r in rs) / max(sum(r["us_pass"] for r in rs), 1e-9) / scale / peak, 4)}
+        traffic_mb = measured_traffic() if a.config == 3 and wk.in_shape[0] == 64 else None
         roofline = {
             "bound": "mfma", "kernel": "fused convolution kernels (conv_dma / conv_halo / conv_gemm8 / conv_stem_pool / conv_pair)", "launches_per_step": len(conv),
             "achieved": round(tfl, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl / PEAK_BF16_TFLOPS, 4),
             "avg_launch_us": round(conv_us / len(conv), 2), "algorithmic_gflop_per_launch": round(conv_fl / len(conv) / 1e9, 3),
-            "traffic": ({"hbm_mb_per_launch": MEASURED_CONV_TRAFFIC_MB_PER_LAUNCH, "algorithmic_mb_per_launch": round(conv_by / len(conv) / 1e6, 1),
-                         "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/conv_resnet50_bs64_hbm_traffic.md"}
-                        if a.config == 3 and wk.in_shape[0] == 64 else None),
+            "timing": f"HIP events around every launch inside {a.pass_reps} whole passes, scaled by {marker_scale:.3f} so that the launches add up to the timed pass (the events between launches cost time the timed passes do not pay)",
+            "frac_hot_repeats": round(conv_fl / (conv_us_hot * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "measured_peak": measured_peak,
+            "traffic": ({"hbm_mb_per_launch": traffic_mb, "algorithmic_mb_per_launch": round(conv_by / len(conv) / 1e6, 1),
+                         "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary read from profiles/conv_resnet50_bs64_hbm_traffic.md (a run of its own, same workload)"}
+                        if traffic_mb is not None else None),
             "mfma_bound_layers": grp(mf, "tflops", PEAK_BF16_TFLOPS, 1e6),
             "hbm_bound_layers": grp(hb, "gbs", PEAK_HBM_GBS, 1e3),
             "pool_gap_kernels": grp(mem, "gbs", PEAK_HBM_GBS, 1e3),
             "depthwise_kernels": grp(dwr, "gbs", PEAK_HBM_GBS, 1e3) if dwr else None,
             "conv_algorithmic_gb_per_step": round(conv_by / 1e9, 3),
-            "sum_layer_us": round(sum(r["us"] for r in rows), 1),
+            "sum_layer_us": round(sum(r["us_pass"] for r in rows), 1),
         }
     else:   # no convolution (the MLP workload): the linear kernel streams its weights once, bound by HBM
         lin = [r for r in rows if r["kind"] == "linear"]
-        lin_us, lin_by = sum(r["us"] for r in lin), sum(r["bytes"] for r in lin)
+        lin_us, lin_by = sum(r["us_pass"] for r in lin), sum(r["bytes"] for r in lin)
         gbs = lin_by / max(lin_us, 1e-9) / 1e3
         roofline = {"bound": "hbm", "kernel": "linear layers (linear_kernel, or the conv_gemm8 weight-streaming tile for large weight matrices)", "launches_per_step": len(lin), "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "avg_launch_us": round(lin_us / max(len(lin), 1), 2),
-                    "algorithmic_mb_per_launch": round(lin_by / max(len(lin), 1) / 1e6, 2), "traffic": None,
-                    "tflops": round(sum(r["flops"] for r in lin) / max(lin_us, 1e-9) / 1e6, 2), "sum_layer_us": round(sum(r["us"] for r in rows), 1)}
+                    "algorithmic_mb_per_launch": round(lin_by / max(len(lin), 1) / 1e6, 2), "traffic": None, "measured_peak": measured_peak,
+                    "tflops": round(sum(r["flops"] for r in lin) / max(lin_us, 1e-9) / 1e6, 2), "sum_layer_us": round(sum(r["us_pass"] for r in rows), 1)}
     if a.layers:
         for r, xi, yo in zip(rows, ins, outs):
             if r["kind"] == "fused":
@@ -214,20 +286,36 @@ def main():
                                            else f"(computed by the launch of L{into[r['i']]:02d})"), file=sys.stderr)
                 continue
             ai = r["flops"] / r["bytes"]
-            print(f"L{r['i']:02d} {r['kind']:6s} in{xi} out{yo} {r['us']:8.1f} us  {r['flops'] / r['us'] / 1e6:8.1f} TFLOP/s"
-                  f"  {r['bytes'] / r['us'] / 1e3:8.1f} GB/s  AI {ai:6.0f}", file=sys.stderr)
+            up = max(r["us_pass"], 1e-9)
+            t_roof = max(r["flops"] / (PEAK_BF16_TFLOPS * 1e6), r["bytes"] / (PEAK_HBM_GBS * 1e3))      # us at min(MFMA, HBM) roof
+            print(f"L{r['i']:02d} {r['kind']:6s} in{xi} out{yo} in-pass {up:7.1f} us (hot {r['us']:6.1f})  {r['flops'] / up / 1e6:7.1f} TFLOP/s"
+                  f"  {r['bytes'] / up / 1e3:7.1f} GB/s  AI {ai:5.0f}  {'mfma' if r['flops'] / r['bytes'] >= PEAK_BF16_TFLOPS / PEAK_HBM_GBS * 1e3 else 'hbm '}"
+                  f" roof {t_roof:5.1f} us = {100 * t_roof / up:4.1f} %", file=sys.stderr)
 
     # ---- CPU checker on a bounded sample of the same workload ------------------------------------------
-    cpu = None
+    cpu, parity = None, None
     if a.cpu_sample > 0:
         import oracle
 
+        import numpy as np
+
         n = min(a.cpu_sample, batch)
         t0 = time.perf_counter()
-        oracle.network_forward(wk.layers, wk.params, wk.x[:n], bf16=wk.bf16)
+        ref = oracle.network_forward(wk.layers, wk.params, wk.x[:n], bf16=wk.bf16)
         dt_s = time.perf_counter() - t0
         cpu = {"value": round(n / dt_s, 3), "unit": "images/s", "cores": oracle.threads(), "kind": "oracle",
                "sample": f"first {n} images of the batch, full network, one pass, {dt_s:.1f} s"}
+        # the timed plan (tuned tiles, fused pairs, reused buffers) against that run: images of a batch are independent
+        got = sol.to_host_nchw(net.forward(x, stream))[:n].astype(np.float64).reshape(ref.shape)
+        torch.cuda.synchronize()
+        floor = max(float(np.sqrt(np.mean(ref * ref))), 1e-30)
+        tol = 2e-2 if wk.bf16 else 1e-4
+        parity = {"n_images": n, "normwise": float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)),
+                  "elementwise_max": float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), floor))), "tolerance": tol,
+                  "gate": "normwise" if wk.bf16 else "elementwise_max",
+                  "what": "output of the timed network (free running, tuned plan) vs the CPU checker on the same images"}
+        parity["ok"] = bool(parity[parity["gate"]] <= tol)
+        parity["normwise"], parity["elementwise_max"] = float(f"{parity['normwise']:.3e}"), float(f"{parity['elementwise_max']:.3e}")
 
     # ---- training step (second workload, reported beside the headline number) -------------------------
     training = None
@@ -244,7 +332,7 @@ def main():
         def train_step():
             tnet.forward(tx, stream)
             tnet.backward(tx, lab, stream)
-            tnet.sgd_step(0.01, 0.9, stream)
+            tnet.sgd_step(0.1, 0.9, stream)                      # the workload's optimiser setting
 
         for _ in range(3):
             train_step()
@@ -254,9 +342,21 @@ def main():
             train_step()
         torch.cuda.synchronize()
         tms = (time.perf_counter() - t0) * 1e3 / a.train_steps
-        training = {"workload": f"{tw.name} batch {tw.in_shape[0]} input 3x224x224: forward (batch-stat BN) + loss + backward + SGD momentum",
+        # algorithmic contraction work of a step: forward + weight gradient of every convolution / linear layer, data
+        # gradient of all but the first (its input needs none)
+        tin, tout = layer_shapes(tw.layers, tw.in_shape, sol.sol_out_size)
+        tfl, first = 0.0, True
+        for l, xi, yo in zip(tw.layers, tin, tout):
+            f, _ = algorithmic_work(l, xi, yo, 2)
+            if f > 0:
+                tfl += f * (2 if first else 3)
+                first = False
+        training = {"workload": f"{tw.name} batch {tw.in_shape[0]} input 3x224x224: forward (batch-stat BN) + loss + backward + SGD lr 0.1 momentum 0.9",
                     "images_per_s": round(tw.in_shape[0] / (tms * 1e-3), 1), "ms_per_step": round(tms, 3), "steps": a.train_steps,
-                    "loss_after": round(float(tnet.loss[0].cpu()), 4)}
+                    "loss_after": round(float(tnet.loss[0].cpu()), 4),
+                    "roofline": {"bound": "mfma", "achieved": round(tfl / (tms * 1e-3) / 1e12, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                                 "frac": round(tfl / (tms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4), "algorithmic_gflop_per_step": round(tfl / 1e9, 1),
+                                 "what": "contraction FLOPs of the step (forward, data and weight gradients) over the whole step time, BN / loss / update launches included"}}
 
     out = {
         "metric": "images/sec ResNet-50-shaped fwd bs64 on 1 GPU" if a.config == 3 and batch == 64 else f"images/sec {wk.name} fwd bs{batch} on 1 GPU",
@@ -266,9 +366,12 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if wk.bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{wk.name} batch {batch} input {wk.in_shape[1]}x{wk.in_shape[2]}x{wk.in_shape[3]} (seeded synthetic, He-normal weights)",
                    "launches_per_step": sum(1 for r in rows if r["kind"] != "fused"), "autotuned_layers": len(tuned), "autotune_seconds": round(tune_s, 2)},
-        "roofline": roofline, "cpu_baseline": cpu, "training_step": training,
+        "roofline": roofline, "cpu_baseline": cpu, "parity": parity, "training_step": training,
     }
     print(json.dumps(out))
+    if parity is not None and not parity["ok"]:
+        print(f"bench.py: the timed network's output is outside the tolerance: {parity}", file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

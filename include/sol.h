@@ -209,6 +209,20 @@ sol_status sol_network_forward(sol_network *net, const void *x, void *y, void *w
 #define SOL_STATIC_WORKSPACE_BYTES (32u << 20)
 sol_status sol_network_forward_static(sol_network *net, const void *x, void *y, void *hip_stream);
 
+/* Debugging / sweeping aid for tests and tuning scripts (not a part of the layer semantics): forces the convolution
+ * kernel / tile id used by later sol_conv2d_fused, sol_linear and sol_network_* calls of the CALLING THREAD
+ * (0 = the library's own choice).  An id that does not fit a layer makes that call fail with SOL_ERR_UNSUPPORTED. */
+void sol_debug_set_conv_tile(int tile);
+
+/* Measured ceilings for the roofline report (benchmark aid; no layer arithmetic).
+ *   sol_debug_probe_copy   a plain device-to-device copy of `bytes` (multiple of 16; 16-byte aligned, non-overlapping
+ *                          device buffers) by a simple kernel: what HBM delivers, 2 * bytes of traffic per call;
+ *   sol_debug_probe_mfma   `workgroups` workgroups of eight waves, each wave `iters` rounds of four independent
+ *                          32x32x16 bf16 matrix instructions on register operands; *flop (host) receives the
+ *                          floating-point operations of the launch; sink: device float the kernel may write. */
+sol_status sol_debug_probe_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
+sol_status sol_debug_probe_mfma(int iters, int workgroups, float *sink, double *flop, void *hip_stream);
+
 /* Plan-time micro auto-tune (the paper's optimizer picks per-layer implementations by heuristics or a very short
  * auto-tuning run when the model is optimized, Sec. III-A): times every kernel / tile shape that fits each
  * convolution layer, `reps` launches each on the caller's buffers, and keeps the fastest per layer for all later
@@ -228,7 +242,7 @@ sol_status sol_network_layer_tile(const sol_network *net, int layer, int *tile);
  * SOL_ERR_UNSUPPORTED before anything is launched for that layer. */
 sol_status sol_network_set_layer_tile(sol_network *net, int layer, int tile);
 
-/* One forward pass recorded as a HIP graph (launch-bound inner loops: the ~56 launches of a ResNet-50-shaped
+/* One forward pass recorded as a HIP graph (launch-bound inner loops: the about fifty launches of a ResNet-50-shaped
  * pass replay as one submission).  sol_network_graph_create runs the pass once eagerly, then records the same
  * launches with the given pointers baked in: x, y, workspace, the bound parameter buffer and the network must
  * stay alive and unmoved while the graph is used (their CONTENTS may change between launches).  `hip_stream`
@@ -301,7 +315,8 @@ sol_status sol_network_sgd_step(sol_network *net, float lr, float momentum, void
  * statistics of the last forward, var biased). */
 typedef enum sol_net_tensor {
     SOL_NT_W = 0, SOL_NT_GAMMA = 1, SOL_NT_BETA = 2, SOL_NT_BIAS = 3, SOL_NT_GRAD_W = 4, SOL_NT_GRAD_GAMMA = 5,
-    SOL_NT_GRAD_BETA = 6, SOL_NT_GRAD_BIAS = 7, SOL_NT_MEAN = 8, SOL_NT_VAR = 9
+    SOL_NT_GRAD_BETA = 6, SOL_NT_GRAD_BIAS = 7, SOL_NT_MEAN = 8, SOL_NT_VAR = 9,
+    SOL_NT_VEL_W = 10, SOL_NT_VEL_GAMMA = 11, SOL_NT_VEL_BETA = 12, SOL_NT_VEL_BIAS = 13   /* momentum buffers of the SGD step */
 } sol_net_tensor;
 sol_status sol_network_tensor(const sol_network *net, int layer, int which, float **ptr, size_t *count);
 

@@ -20,7 +20,7 @@ void set_error(const char *fmt, ...) {
     va_end(ap);
 }
 
-static int g_tile_override = 0;   // debugging / sweeping aid, see sol_debug_set_conv_tile
+static thread_local int g_tile_override = 0;   // debugging / sweeping aid of the calling thread, see sol_debug_set_conv_tile
 
 static sol_status check_tensor(const sol_tensor_desc *d, const char *what) {
     SOL_REQUIRE(d, SOL_ERR_NULL, "%s descriptor is NULL", what);
@@ -583,7 +583,7 @@ const char *sol_last_error(void) { return g_err; }
 const char *sol_version(void) { return "libsol_mi355 0.1 (gfx950)"; }
 int sol_out_size(int in, int k, int stride, int pad) { return out_size(in, k, stride, pad); }
 
-// Debugging / sweeping aid: force the convolution tile (0 = automatic).  Not part of the stable ABI.
+// Debugging / sweeping aid: force the convolution tile for later calls of the calling thread (0 = automatic).
 void sol_debug_set_conv_tile(int tile) { g_tile_override = tile; }
 
 size_t sol_packed_weight_bytes(const sol_conv_desc *cd, sol_dtype dt) {
@@ -966,6 +966,7 @@ static sol_status train_backward(sol_network *net, const void *x, const int32_t 
 static sol_status run_layers(sol_network *net, const void *x, void *y, void *workspace, size_t workspace_bytes,
                              int first, int last, hipStream_t st) {
     SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
+    if (net->input.n == 0) return SOL_OK;                  // empty batch: every tensor is empty (allocators hand out NULL for them)
     SOL_REQUIRE(x && y, SOL_ERR_NULL, "x and y must not be NULL");
     SOL_REQUIRE(workspace || net->ws_bytes == 0, SOL_ERR_NULL, "workspace is NULL");
     SOL_REQUIRE(workspace_bytes >= net->ws_bytes, SOL_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, net->ws_bytes);
@@ -1405,6 +1406,10 @@ sol_status sol_network_tensor(const sol_network *net, int layer, int which, floa
         case SOL_NT_GRAD_BIAS: *ptr = vec_ptr(net, lp, VEC_G_BIAS); *count = lp.cd.cout; break;
         case SOL_NT_MEAN: *ptr = vec_ptr(net, lp, VEC_MEAN); *count = lp.cd.cout; break;
         case SOL_NT_VAR: *ptr = vec_ptr(net, lp, VEC_VAR); *count = lp.cd.cout; break;
+        case SOL_NT_VEL_W: *ptr = reinterpret_cast<float *>(net->params + lp.vel_off); *count = wn; break;
+        case SOL_NT_VEL_GAMMA: *ptr = vec_ptr(net, lp, VEC_V_GAMMA); *count = lp.cd.cout; break;
+        case SOL_NT_VEL_BETA: *ptr = vec_ptr(net, lp, VEC_V_BETA); *count = lp.cd.cout; break;
+        case SOL_NT_VEL_BIAS: *ptr = vec_ptr(net, lp, VEC_V_BIAS); *count = lp.cd.cout; break;
         default: SOL_FAIL(SOL_ERR_SHAPE, "unknown tensor id %d", which);
     }
     return SOL_OK;

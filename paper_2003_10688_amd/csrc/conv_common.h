@@ -353,7 +353,7 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
 // Epilogue fast path for a wave tile that lies completely inside the output (all TP*32 rows below P, all TC*32
 // channels below Cout), Cout % 8 == 0 and no fused pool: same transposition through the wave-private strip as
 // conv_epilogue, but without per-row / per-channel range logic, with 32-bit element offsets (tensors are
-// limited to < 2^31 elements) and a branch-free activation.  RES: add the prefetched residual rows.
+// limited to < 2^31 elements) and a select for the activation (same NaN behaviour as conv_epilogue).  RES: add the prefetched residual rows.
 // rowoff(r): element offset of the first channel of the output pixel of tile row r (counted from the wave's first
 // row); rows r .. r + RPS - 1 handled by one pass need not be contiguous with the next pass.
 struct LinearRowOffset {
@@ -370,7 +370,7 @@ __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16
     float *strip = lds_f + wave * (32 * ERS);
     T *__restrict__ yg = static_cast<T *>(a.y);
     const int ecg = lane % LPR, erow = lane / LPR;
-    const float lim = a.act == SOL_ACT_RELU ? 0.f : -__builtin_inff();
+    const bool relu = a.act == SOL_ACT_RELU;     // wave-uniform
     const unsigned coff = (unsigned)(cw + ecg * 8);
     static_for<TP>([&](auto J) {
         constexpr int j = decltype(J)::value;
@@ -396,7 +396,7 @@ __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16
                 for (int e = 0; e < 8; e++) v[e] += rv[e];
             }
 #pragma unroll
-            for (int e = 0; e < 8; e++) v[e] = fmaxf(v[e], lim);
+            for (int e = 0; e < 8; e++) v[e] = (relu && !(v[e] > 0.f)) ? 0.f : v[e];   // as the general epilogue: NaN stays NaN without ReLU, ReLU maps it to 0
             if (rowoff.valid(j * 32 + erow + ps * RPS)) store_vec8<T>(yg + rowoff(j * 32 + erow + ps * RPS) + coff, v);
         }
         wave_lds_fence();

@@ -78,10 +78,13 @@ __global__ void __launch_bounds__(512) linear_kernel(const ConvArgs a) {
     }
 }
 
-// 1x1 "convolution" over a [rows,1,1,C] tensor with few rows, rows a whole number of 16-byte fragments
+// unpadded 1x1 "convolution" over a [rows,1,1,C] tensor with few rows, rows a whole number of 16-byte fragments.  The
+// kernel reads x as P dense rows: with padding a [n,1,1,C] input has more output pixels than input rows (the padding
+// pixels hold act(shift + residual)), which the gather kernels handle.
 bool linear_kernel_applies(const ConvArgs &a, int dt) {
     const int frag = 16 / (int)dtype_size(dt);     // a fragment is 16 bytes of one row: rows must be whole fragments
-    return a.R == 1 && a.S == 1 && a.H == 1 && a.W == 1 && a.pool == 0 && a.P <= 1024 && a.C % frag == 0;
+    return a.R == 1 && a.S == 1 && a.H == 1 && a.W == 1 && a.ph == 0 && a.pw == 0 && a.Ho == 1 && a.Wo == 1 && a.P == a.N &&
+           a.pool == 0 && a.P <= 1024 && a.C % frag == 0;
 }
 
 sol_status launch_linear(const ConvArgs &a, int dt, hipStream_t st) {

@@ -20,6 +20,7 @@ POOL_NONE, POOL_MAX, POOL_AVG = 0, 1, 2
 LAYER_CONV, LAYER_POOL, LAYER_GAP, LAYER_LINEAR, LAYER_DWCONV, LAYER_CONCAT = 0, 1, 2, 3, 4, 5
 NET_TRAINING, NET_KEEP_ACTIVATIONS = 1, 2
 NT_W, NT_GAMMA, NT_BETA, NT_BIAS, NT_GRAD_W, NT_GRAD_GAMMA, NT_GRAD_BETA, NT_GRAD_BIAS, NT_MEAN, NT_VAR = range(10)
+NT_VEL_W, NT_VEL_GAMMA, NT_VEL_BETA, NT_VEL_BIAS = range(10, 14)
 
 STATUS = {0: "SOL_OK", 1: "SOL_ERR_NULL", 2: "SOL_ERR_SHAPE", 3: "SOL_ERR_DTYPE", 4: "SOL_ERR_ALIGN",
           5: "SOL_ERR_WORKSPACE", 6: "SOL_ERR_UNSUPPORTED", 7: "SOL_ERR_HIP"}
@@ -75,6 +76,8 @@ def lib():
         L.sol_graph_destroy.restype = None
         L.sol_graph_launch.argtypes = [C.c_void_p, C.c_void_p]
         L.sol_debug_set_conv_tile.restype = None
+        L.sol_debug_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.sol_debug_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_double), C.c_void_p]
         L.sol_network_forward_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
@@ -237,6 +240,19 @@ def sol_global_avgpool(x, stream=None):
 
 def sol_debug_set_conv_tile(tile):
     lib().sol_debug_set_conv_tile(C.c_int(tile))
+
+
+def sol_debug_probe_copy(dst, src, stream=None):
+    """Plain device-to-device copy of src into dst (uint8 tensors of equal size, a multiple of 16 bytes)."""
+    assert dst.numel() * dst.element_size() == src.numel() * src.element_size()
+    _check(lib().sol_debug_probe_copy(_ptr(dst), _ptr(src), C.c_size_t(src.numel() * src.element_size()), _stream(stream)))
+
+
+def sol_debug_probe_mfma(iters, workgroups, sink, stream=None):
+    """Register-resident bf16 MFMA loop; returns the floating-point operations of the launch."""
+    flop = C.c_double(0.0)
+    _check(lib().sol_debug_probe_mfma(C.c_int(iters), C.c_int(workgroups), _ptr(sink), C.byref(flop), _stream(stream)))
+    return flop.value
 
 
 # ---- networks -----------------------------------------------------------------------------------------

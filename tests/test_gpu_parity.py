@@ -86,6 +86,8 @@ CONV_CASES = [
     (1, 24, 11, 11, 40, 3, 1, 1, True),     # Cin not a multiple of the 128-byte chunk -> gather path
     (2, 32, 12, 12, 32, 5, 1, 2, False),
     (1, 64, 1, 1, 10, 1, 1, 0, False),      # degenerate 1x1 image, Cout not a multiple of 4
+    (2, 64, 1, 1, 10, 1, 1, 1, True),       # ... with padding: 3x3 output pixels per image, eight of them act(shift + residual)
+    (3, 32, 1, 1, 16, 1, 2, 2, False),      # ... padded and strided
     (130, 64, 2, 2, 64, 3, 1, 1, True),     # many tiny images
 ]
 
@@ -412,6 +414,40 @@ def test_empty_batch_and_errors(sol):
     assert e.value.status == 4
 
 
+def test_network_on_an_empty_batch(sol):
+    """A network planned for batch 0 (concatenation, fused stem pair and projection pair included) accepts the NULL
+    pointers an allocator hands out for empty tensors and launches nothing, like the single-layer calls."""
+    c = wl.conv
+    layers = [c(64, 7, s=2, p=3), wl.pool("max", 3, 2, 1), c(64, 1, p=0), c(64, 3), c(256, 1, p=0, act="none", src=1),
+              c(256, 1, p=0, src=3, res=4), c(32, 1, p=0, bn=False, src=5), c(32, 3, bn=False, src=5), wl.concat(6, 7), wl.gap(),
+              wl.linear(10)]
+    for flags in (0, sol.NET_KEEP_ACTIVATIONS):
+        net = sol.Network(layers, (0, 3, 64, 64), sol.BF16, flags=flags)
+        net.set_params(wl.make_params(layers, 3, 1, True))
+        x0 = torch.empty((0, 64, 64, 3), dtype=torch.bfloat16, device="cuda:0")
+        assert x0.data_ptr() == 0 or x0.numel() == 0
+        y = net.forward(x0)
+        torch.cuda.synchronize()
+        assert tuple(y.shape) == (0, 1, 1, 10)
+        assert net.autotune(x0, reps=1) == {}
+        assert tuple(net.forward_static(x0).shape) == (0, 1, 1, 10)
+
+
+def test_nan_propagates_alike_through_both_epilogues(sol):
+    """A NaN in the input reaches every output it feeds as NaN when no activation follows, in interior tiles (fast
+    epilogue) and in ragged edge tiles (general epilogue) alike; behind a ReLU both store 0 (v > 0 is false for NaN)."""
+    rng = np.random.default_rng(2)
+    for dt in ("f32", "bf16"):
+        for act, cout in (("none", 64), ("relu", 64), ("none", 72)):
+            l, x, prm, _ = make_block(sol, rng, dt, 2, 64, 13, 11, cout, 1, 1, 0, bn=True, act=act)
+            x[:, 5] = np.nan                       # one input channel: every output pixel sees it
+            got, _, _ = run_block(sol, dt, l, x, prm, None)
+            if act == "none":
+                assert np.isnan(got).all(), (dt, act, cout, np.count_nonzero(~np.isnan(got)))
+            else:
+                assert (got == 0).all(), (dt, act, cout)
+
+
 # ---------------------------------------------------------------------------------- whole networks
 def run_network(sol, wk, keep=True):
     d = _dt(sol, wk.dtype)
@@ -562,6 +598,68 @@ def test_full_size_layers_sampled(sol, cfg):
     print(f"cfg{cfg} full-size sampled layers: worst rel err {worst:.3e}")
 
 
+def test_full_size_projection_pairs_in_the_tuned_plan(sol):
+    """The four projection-pair launches of the ResNet-50-shaped pass at batch 64, inside the lean network object and
+    after the plan-time auto-tune (the launch configuration bench.py times): both input tensors of a pair are
+    overwritten with seeded values, the pair layer is run alone, and 256 sampled outputs are recomputed by the checker
+    from both convolutions.  Strict statement: against the checker's pieces with the shortcut left unrounded, as the
+    kernel computes it (2e-2); the checker's own definition, which stores -- and so rounds -- the shortcut, within
+    twice that.  The other layers of the tuned plan are covered by the sampled checks above and by bench.py's own
+    comparison of the timed output with the checker."""
+    wk = wl.config(3)
+    net = sol.Network(wk.layers, wk.in_shape, sol.BF16)              # lean plan: pairs fused, buffers reused
+    net.set_params(wk.params)
+    x = sol.to_device_nhwc(wk.x, sol.BF16)
+    net.autotune(x, reps=2)
+    net.forward(x)
+    torch.cuda.synchronize()
+    L, P = wk.layers, wk.params
+    ins, outs = {}, {}
+    shp = wk.in_shape
+    for i, l in enumerate(L):                                        # logical shapes, by bookkeeping only
+        s = l.get("src", -1)
+        xin = shp if (i == 0 and s == -1) else outs[i - 1 if s == -1 else s]
+        ins[i] = xin
+        if l["kind"] == "conv":
+            outs[i] = (xin[0], l["cout"], orc.out_size(xin[2], l["kh"], l["sh"], l["ph"]), orc.out_size(xin[3], l["kw"], l["sw"], l["pw"]))
+        elif l["kind"] == "pool":
+            pd = l["pool"]
+            outs[i] = (xin[0], xin[1], orc.out_size(xin[2], pd["kh"], pd["sh"], pd["ph"]), orc.out_size(xin[3], pd["kw"], pd["sw"], pd["pw"]))
+        elif l["kind"] == "gap":
+            outs[i] = (xin[0], xin[1], 1, 1)
+        else:
+            outs[i] = (xin[0], l["out"], 1, 1)
+    pairs = [(j, net.fused_into(j)) for j in range(len(L)) if L[j]["kind"] == "conv" and net.fused_into(j) != j]
+    assert len(pairs) == 4, pairs
+    rng = np.random.default_rng(wk.seed + 9)
+    src_of = lambda i: (i - 1) if L[i].get("src", -1) == -1 else L[i]["src"]   # noqa: E731
+    for j, i in pairs:
+        assert L[i]["res"] == j and L[j]["kh"] == 1 and L[i]["kh"] == 1
+        xm = wl.to_bf16_grid(rng.standard_normal(ins[i], dtype=np.float32))     # input of the main 1x1 convolution
+        xp = wl.to_bf16_grid(rng.standard_normal(ins[j], dtype=np.float32))     # block input, read by the shortcut
+        net.layer_output(src_of(i)).copy_(sol.to_device_nhwc(xm, sol.BF16))
+        net.layer_output(src_of(j)).copy_(sol.to_device_nhwc(xp, sol.BF16))
+        net.run_layer(i, x)
+        torch.cuda.synchronize()
+        got = sol.to_host_nchw(net.layer_output(i))
+        N, K, Ho, Wo = outs[i]
+        assert got.shape == (N, K, Ho, Wo)
+        coords = np.stack([rng.integers(0, s, 256) for s in (N, K, Ho, Wo)], 1).astype(np.int32)
+        coords[:4] = [[0, 0, 0, 0], [N - 1, K - 1, Ho - 1, Wo - 1], [0, K - 1, 0, Wo - 1], [N - 1, 0, Ho - 1, 0]]
+        lj, li = dict(L[j], pool=None), dict(L[i], pool=None)
+        short = orc.fused_conv_points(xp, P[j], lj, coords, None, bf16=False)                       # conv + BN, no ReLU, unrounded
+        main = orc.fused_conv_points(xm, P[i], dict(li, act="none"), coords, None, bf16=False)      # conv + BN of the main branch
+        strict = orc.round_bf16(orc.relu(orc.add(main, short)))
+        stored = orc.round_bf16(orc.relu(orc.add(main, orc.round_bf16(short))))                     # the checker's definition: the shortcut is a stored tensor
+        g = got[tuple(coords.T)]
+        floor = np.sqrt(np.mean(strict * strict)) + 1e-30
+        e_strict = float(np.max(np.abs(g - strict) / np.maximum(np.abs(strict), floor)))
+        e_stored = float(np.max(np.abs(g - stored) / np.maximum(np.abs(stored), floor)))
+        print(f"  pair L{j}+L{i} in{ins[i]}/{ins[j]} -> {outs[i]}: strict {e_strict:.3e}, against the stored-shortcut definition {e_stored:.3e}", flush=True)
+        assert e_strict <= TOL["bf16"], (j, i, e_strict)
+        assert e_stored <= 2 * TOL["bf16"], (j, i, e_stored)
+
+
 def test_full_size_fused_stem_pair_sampled(sol):
     """The depth-first stem + max-pool kernel at the benchmark's size (64 x 3 x 224 x 224, the launch the timed pass
     makes): sampled pooled outputs against the checker, each from the (up to) nine convolution points under its
@@ -670,9 +768,10 @@ def test_network_autotune_keeps_results(sol):
     assert max(errs) <= TOL["bf16"], errs
 
 
-@pytest.mark.parametrize("batch,features", [(64, 1024), (5, 320), (130, 512)])
+@pytest.mark.parametrize("batch,features", [(64, 1024), (5, 320), (130, 512), (64, 8192)])
 def test_mlp_workload(sol, batch, features):
-    """The paper's MLP workload (three linear layers with ReLU, Sec. V) at reduced width through the network object,
+    """The paper's MLP workload (three linear layers with ReLU, Sec. V) through the network object -- at reduced widths
+    and at its real size (batch 64, 8192 features: the weight-streaming route that matrices of 16 MB and more take) --
     every layer element-wise against the checker on the checker's activations, and end to end."""
     wk = wl.config(5, batch=batch, hw=features)
     outs, _ = orc.network_forward(wk.layers, wk.params, wk.x, bf16=True, return_all=True)

@@ -320,6 +320,53 @@ def test_train_step_full_size_at_stored_state(sol):
     gate("linear dw", rel_err(net.tensor(i, sol.NT_GRAD_W).cpu().numpy().reshape(dw.shape), dw), 1e-3)
     gate("linear db", rel_err(net.tensor(i, sol.NT_GRAD_BIAS).cpu().numpy(), db), 1e-3)
     gate("linear dx", rel_err(dact(i - 1).reshape(dx.shape), orc.round_bf16(dx)), TOL["bf16"])
+    # ---- the SGD update at full size (learning rate 0.1, momentum 0.9, the workload's setting): two steps, so that the
+    # momentum term is exercised.  Reference = the checker's update rule applied to the initial parameters with the
+    # checker's own gradients of the checked layers (weight gradients recomputed above from the stored dz; dgamma /
+    # dbeta from its BN backward); second step: the same rule on the gradients of the second backward pass.
+    checked = (0, 2, 6, 7, 20)
+    ref_g = {}
+    for i in checked:
+        l, st = L[i], layer_state(i)
+        dw, _ = orc.conv2d_wgrad(out(src_of(i)), st["dz"], P[i]["w"].shape, (l["sh"], l["sw"]), (l["ph"], l["pw"]))
+        ref_g[i] = {"w": dw, "gamma": st["dgamma"], "beta": st["dbeta"]}
+    gpu_g1 = {i: {k: net.tensor(i, getattr(sol, GRAD_KEYS[k])).cpu().numpy().astype(np.float64).reshape(np.shape(P[i][k]))
+                  for k in ("w", "gamma", "beta")} for i in checked}
+    lr, mu = 0.1, 0.9
+    net.sgd_step(lr, mu)
+    torch.cuda.synchronize()
+    vel = {}
+    for i in checked:
+        for k in ("w", "gamma", "beta"):
+            w1 = np.asarray(P[i][k], np.float64).copy()
+            v1 = np.zeros_like(w1)
+            orc.sgd(w1, v1, ref_g[i][k], lr, mu)
+            got_w = net.tensor(i, getattr(sol, PARAM_KEYS[k])).cpu().numpy().reshape(w1.shape)
+            got_v = net.tensor(i, getattr(sol, "NT_VEL_" + k.upper())).cpu().numpy().reshape(w1.shape)
+            gate(f"sgd1 {k}", rel_err(got_w, w1), 1e-3 if k == "w" else 1e-4)
+            gate(f"sgd1 v_{k}", rel_err(got_v, v1), TOL["bf16"] if k == "w" else 1e-3)
+            # the update arithmetic itself, on the gradient the library holds: exact up to fp32 rounding
+            w1g = np.asarray(P[i][k], np.float64).copy()
+            v1g = np.zeros_like(w1g)
+            orc.sgd(w1g, v1g, gpu_g1[i][k], lr, mu)
+            gate(f"sgd1 arithmetic {k}", rel_err(got_w, w1g), 1e-6)
+            vel[(i, k)] = (w1g, v1g)
+    # second step: new forward / backward on the updated weights, then the momentum update  v2 = mu v1 + g2
+    net.forward(xd)
+    net.backward(xd, lab)
+    torch.cuda.synchronize()
+    gpu_g2 = {i: {k: net.tensor(i, getattr(sol, GRAD_KEYS[k])).cpu().numpy().astype(np.float64).reshape(np.shape(P[i][k]))
+                  for k in ("w", "gamma", "beta")} for i in checked}
+    net.sgd_step(lr, mu)
+    torch.cuda.synchronize()
+    for i in checked:
+        for k in ("w", "gamma", "beta"):
+            w2, v2 = vel[(i, k)][0].astype(np.float32).astype(np.float64), vel[(i, k)][1].astype(np.float32).astype(np.float64)
+            orc.sgd(w2, v2, gpu_g2[i][k], lr, mu)
+            got_w = net.tensor(i, getattr(sol, PARAM_KEYS[k])).cpu().numpy().reshape(w2.shape)
+            got_v = net.tensor(i, getattr(sol, "NT_VEL_" + k.upper())).cpu().numpy().reshape(w2.shape)
+            gate(f"sgd2 arithmetic {k}", rel_err(got_w, w2), 1e-5)
+            gate(f"sgd2 arithmetic v_{k}", rel_err(got_v, v2), 1e-5)
     print("full-size training step, worst errors: " + ", ".join(f"{k} {v:.2e}" for k, v in worst.items()))
 
 

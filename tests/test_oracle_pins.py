@@ -328,6 +328,51 @@ def test_fused_block_and_residual():
     assert np.array_equal(orc.fused_conv(x, p0, l0, res)[0], res)
 
 
+def test_bn_points_and_fused_block_points_agree_with_the_full_tensors():
+    """The sampled evaluations used against full-size GPU outputs: bn_infer_points is the pinned per-channel map at
+    scattered elements (library batch-norm and the folded affine form as independent references), and
+    fused_conv_points equals the pinned full fused block at random coordinates -- with residual, ReLU, stride,
+    padding and the bf16 store -- exactly."""
+    g, b, m, v = R.uniform(0.5, 1.5, 5), R.uniform(-1, 1, 5), R.standard_normal(5), R.uniform(0.5, 1.5, 5)
+    x = R.standard_normal((3, 5, 4, 6))
+    full = orc.bn_infer(x, g, b, m, v, 1e-5)
+    coords = np.stack([R.integers(0, d, 60) for d in x.shape], 1).astype(np.int32)
+    pts = orc.bn_infer_points(x[tuple(coords.T)], coords[:, 1], g, b, m, v, 1e-5)
+    assert np.array_equal(pts, full[tuple(coords.T)])
+    lib = F.batch_norm(T(x), T(m), T(v), T(g), T(b), False, 0.0, 1e-5).numpy()
+    assert np.allclose(pts, lib[tuple(coords.T)], rtol=1e-13, atol=1e-13)
+    scale = g / np.sqrt(v + 1e-5)
+    assert np.allclose(pts, x[tuple(coords.T)] * scale[coords[:, 1]] + (b - m * scale)[coords[:, 1]], rtol=1e-13, atol=1e-13)
+    # a wrong channel index (e.g. the batch index used as channel) must show: channels differ in every parameter
+    assert not np.allclose(orc.bn_infer_points(x[tuple(coords.T)], coords[:, 0], g, b, m, v, 1e-5), full[tuple(coords.T)])
+
+    for (k, sh, ph, bn, act, with_res, bf) in [(3, 1, 1, True, "relu", True, False), (1, 2, 0, True, "none", False, True),
+                                               (3, 2, 1, False, "relu", True, True), (5, 1, 2, True, "relu", False, False)]:
+        l = {"kind": "conv", "cout": 6, "kh": k, "kw": k, "sh": sh, "sw": sh, "ph": ph, "pw": ph, "bn": bn, "act": act, "pool": None}
+        xx = orc.round_bf16(R.standard_normal((2, 4, 9, 11))) if bf else R.standard_normal((2, 4, 9, 11))
+        p = {"w": R.standard_normal((6, 4, k, k)), "bias": R.standard_normal(6), "gamma": R.uniform(0.5, 1.5, 6),
+             "beta": R.uniform(-0.1, 0.1, 6), "mean": R.standard_normal(6) * 0.1, "var": R.uniform(0.5, 1.5, 6)}
+        ho, wo = orc.out_size(9, k, sh, ph), orc.out_size(11, k, sh, ph)
+        res = R.standard_normal((2, 6, ho, wo)) if with_res else None
+        full, _, _ = orc.fused_conv(xx, p, l, res, bf16=bf)
+        assert full.shape == (2, 6, ho, wo)
+        cs = np.stack([R.integers(0, d, 80) for d in full.shape], 1).astype(np.int32)
+        got = orc.fused_conv_points(xx, p, l, cs, res, bf16=bf)
+        assert np.array_equal(got, full[tuple(cs.T)])
+        if bf:
+            assert np.array_equal(got, orc.round_bf16(got))          # stored values are bf16 numbers
+        # against the library composition (not through the checker's own full-tensor code)
+        t = F.conv2d(T(xx), T(p["w"]), T(p["bias"]), stride=sh, padding=ph)
+        if bn:
+            t = F.batch_norm(t, T(p["mean"]), T(p["var"]), T(p["gamma"]), T(p["beta"]), False, 0.0, 1e-5)
+        if with_res:
+            t = t + T(res)
+        if act == "relu":
+            t = F.relu(t)
+        tol = 2.0 ** -7 if bf else 1e-12
+        assert np.allclose(got, t.numpy()[tuple(cs.T)], rtol=tol, atol=tol * 1e-3 if bf else tol)
+
+
 def test_network_is_composition_and_batch_permutes():
     from paper_2003_10688_amd import workloads as wl
 
