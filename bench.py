@@ -122,7 +122,7 @@ def main():
     t0 = time.perf_counter()
     if a.load_plan:
         with open(a.load_plan) as f:
-            tuned = {int(k): v for k, v in json.load(f).items()}
+            tuned = {(k if k.endswith("b") else int(k)): v for k, v in json.load(f).items()}
         net.set_tiles(tuned)
     else:
         tuned = net.autotune(x, reps=a.tune_reps, stream=stream) if a.tune_reps > 0 else {}
@@ -178,11 +178,14 @@ def main():
         numel = lambda t: t[0] * t[1] * t[2] * t[3]  # noqa: E731
         if absorbs:   # a fused stem pair stores only the pooled tensor
             by += esize * (numel(outs[i + 1]) - numel(outs[i]))
-        for j in range(i):   # a projection shortcut computed inside this launch: its work, minus the write and the re-read of its output
-            if into[j] == i:
+        for j in range(i):   # layers computed inside this launch (a projection shortcut, the first two convolutions of a
+            if into[j] == i:  # bottleneck): their work, minus the write and the re-read of their outputs
                 fj, bj = algorithmic_work(wk.layers[j], ins[j], outs[j], esize)
                 fl += fj
                 by += bj - 2 * esize * numel(outs[j])
+                sj = wk.layers[j].get("src", -1)
+                if l.get("res", -1) >= 0 and (j - 1 if sj == -1 else sj) == l["res"]:
+                    by -= esize * numel(outs[l["res"]])      # ... and the shortcut is the block input, which is read once
         rows.append({"i": i, "kind": "dwconv" if l.get("dw") else l["kind"], "us": us, "flops": fl, "bytes": by})
     # ---- the same launches timed inside whole passes (cold weights, inputs as the producer left them): an event in
     # front of every launch of a pass.  A long register-only kernel goes first so that the host has queued the whole
@@ -255,7 +258,7 @@ def main():
                                             "frac": round(sum(r["flops" if key == "tflops" else "bytes"] for r in rs) / max(sum(r["us_pass"] for r in rs), 1e-9) / scale / peak, 4)}
         traffic_mb = measured_traffic() if a.config == 3 and wk.in_shape[0] == 64 else None
         roofline = {
-            "bound": "mfma", "kernel": "fused convolution kernels (conv_dma / conv_halo / conv_gemm8 / conv_stem_pool / conv_pair)", "launches_per_step": len(conv),
+            "bound": "mfma", "kernel": "fused convolution kernels (conv_dma / conv_halo / conv_gemm8 / conv_stem_pool / conv_pair / conv_block)", "launches_per_step": len(conv),
             "achieved": round(tfl, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl / PEAK_BF16_TFLOPS, 4),
             "avg_launch_us": round(conv_us / len(conv), 2), "algorithmic_gflop_per_launch": round(conv_fl / len(conv) / 1e9, 3),
             "timing": f"HIP events around every launch inside {a.pass_reps} whole passes, scaled by {marker_scale:.3f} so that the launches add up to the timed pass (the events between launches cost time the timed passes do not pay)",
@@ -365,7 +368,7 @@ def main():
         "submission": "HIP graph replay" if a.graph else "eager launches", "eager_ms_per_step": round(eager_ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if wk.bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{wk.name} batch {batch} input {wk.in_shape[1]}x{wk.in_shape[2]}x{wk.in_shape[3]} (seeded synthetic, He-normal weights)",
-                   "launches_per_step": sum(1 for r in rows if r["kind"] != "fused"), "autotuned_layers": len(tuned), "autotune_seconds": round(tune_s, 2)},
+                   "launches_per_step": sum(1 for r in rows if r["kind"] != "fused"), "autotuned_layers": sum(1 for k in tuned if not str(k).endswith("b")), "fused_bottlenecks": sum(1 for k, v in tuned.items() if str(k).endswith("b") and v), "autotune_seconds": round(tune_s, 2)},
         "roofline": roofline, "cpu_baseline": cpu, "parity": parity, "training_step": training,
     }
     print(json.dumps(out))

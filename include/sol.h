@@ -126,6 +126,23 @@ sol_status sol_conv2d_fused(const sol_tensor_desc *xd, const void *x, const sol_
                             const void *residual, int act, const sol_pool_desc *pool, void *y,
                             int32_t *pool_argmax, void *prepool, void *hip_stream);
 
+/* A whole residual bottleneck as one depth-first kernel (the paper's layer-chain fusion, Sec. III-A: a chain of layers
+ * is run over a block of data while it sits in registers and on-chip memory, here across three contractions):
+ *   t1 = relu(scale1 * conv1x1(x,  w1) + shift1)           c   -> mid channels
+ *   t2 = relu(scale2 * conv3x3(t1, w2) + shift2)           mid -> mid, stride 1, pad 1
+ *   y  = relu(scale3 * conv1x1(t2, w3) + shift3 + x)       mid -> c,   identity shortcut
+ * t1 and t2 never reach device memory; they are rounded to the storage type where the layer-by-layer path stores them.
+ *   xd, x       block input NHWC, SOL_BF16
+ *   mid         64 or 128; xd->c a multiple of 128; xd->w at most 126 (mid 64) / 79 (mid 128) columns; anything
+ *               else -> SOL_ERR_UNSUPPORTED (run the three layers through sol_conv2d_fused)
+ *   w1_packed   sol_pack_conv_weights of cd = {mid, c, 1,1, 1,1, 0,0};  w2_packed: {mid, mid, 3,3, 1,1, 1,1};
+ *               w3_packed: {c, mid, 1,1, 1,1, 0,0}
+ *   scale*, shift*  device fp32 per output channel of each convolution (sol_fold_bn), all required
+ *   y           NHWC like x, written by the call; must not alias x */
+sol_status sol_bottleneck_fused(const sol_tensor_desc *xd, const void *x, int mid, const void *w1_packed, const float *scale1,
+                                const float *shift1, const void *w2_packed, const float *scale2, const float *shift2,
+                                const void *w3_packed, const float *scale3, const float *shift3, void *y, void *hip_stream);
+
 /* Depthwise convolution: a grouped convolution with one group -- one kh x kw filter -- per channel, which the
  * paper assigns to the fusion engine as a pooling layer with learned window weights (Sec. III-A) instead of
  * to the contraction path:
@@ -242,6 +259,17 @@ sol_status sol_network_layer_tile(const sol_network *net, int layer, int *tile);
  * SOL_ERR_UNSUPPORTED before anything is launched for that layer. */
 sol_status sol_network_set_layer_tile(sol_network *net, int layer, int tile);
 
+/* Whole bottlenecks in one launch.  When a network keeps no activations (flags 0), bf16: a 1x1 convolution + ReLU, a
+ * 3x3 stride-1 pad-1 convolution + ReLU and a 1x1 convolution + ReLU whose residual is the first one's input, each
+ * intermediate read by the next layer only, with shapes sol_bottleneck_fused accepts, can run as that one depth-first
+ * kernel; the plan decides by a shape heuristic, sol_network_autotune by timing both ways.  sol_network_layer_fused_into
+ * reports the last convolution's index for the first two while the block runs fused.  sol_network_set_layer_block
+ * restores / forces the choice for the block that ends in convolution `layer` (fused != 0: one launch;
+ * SOL_ERR_UNSUPPORTED if `layer` ends no such block). */
+sol_status sol_network_set_layer_block(sol_network *net, int layer, int fused);
+/* *state = -1: `layer` ends no such block; 0: the block runs layer by layer; 1: as one launch */
+sol_status sol_network_layer_block(const sol_network *net, int layer, int *state);
+
 /* One forward pass recorded as a HIP graph (launch-bound inner loops: the about fifty launches of a ResNet-50-shaped
  * pass replay as one submission).  sol_network_graph_create runs the pass once eagerly, then records the same
  * launches with the given pointers baked in: x, y, workspace, the bound parameter buffer and the network must
@@ -263,7 +291,8 @@ void sol_graph_destroy(sol_graph *graph);
  *     of 64 channels runs inside that convolution's launch; its output is never stored, and never rounded to the storage type either (the result differs from
  *     the two-launch result by at most one rounding of the shortcut term).
  * *into = index of the layer whose launch produces `layer`'s output: `layer` itself, the layer in front for such a
- * pool layer, the later convolution for such a shortcut (sol_network_run_layer on a fused layer launches nothing). */
+ * pool layer, the later convolution for such a shortcut, the last convolution of a bottleneck that runs as one launch
+ * (see sol_network_set_layer_block) for its first two (sol_network_run_layer on a fused layer launches nothing). */
 sol_status sol_network_layer_fused_into(const sol_network *net, int layer, int *into);
 
 /* Concatenation in place: when a network keeps no activations, a convolution (no fused pool, channel count a

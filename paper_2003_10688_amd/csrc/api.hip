@@ -185,6 +185,9 @@ struct LayerPlan {
     int concat_into, concat_off;    // CONV: writes its output as channels concat_off.. of that CONCAT layer's buffer (-1: own buffer)
     bool prealloc;                  // CONCAT: buffer laid out when its first in-place producer ran
     int pair;                       // CONV: index of the projection convolution this launch also computes (-1: none)
+    int block_c1, block_c2;         // CONV (last 1x1 of a bottleneck): the reduce and 3x3 convolutions that one depth-first launch can compute with it (-1: none)
+    int block_c3;                   // CONV (reduce / 3x3 of such a bottleneck): that last convolution (-1: none)
+    bool use_block;                 // on the last convolution: the plan runs the bottleneck as one launch (heuristic or sol_network_autotune)
     int fused_into;                 // index of the layer whose launch produces this layer's output (itself unless elided)
     bool no_buffer;                 // elided, and nobody allocates an output for it either
     size_t w_off, scale_off, shift_off;
@@ -359,6 +362,7 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
         lp.res = -1;
         lp.concat_into = -1;
         lp.pair = -1;
+        lp.block_c1 = lp.block_c2 = lp.block_c3 = -1;
         lp.fused_into = i;
         lp.in = lp.src < 0 ? net->input : net->layers[lp.src].out;
         lp.out = lp.in;
@@ -548,6 +552,31 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             }
         }
 
+    // Depth-first bottleneck (the paper's layer-chain fusion, Sec. III-A, across three contractions): 1x1 reduce + ReLU,
+    // 3x3 stride 1 + ReLU, 1x1 expand + identity shortcut + ReLU, every intermediate read by the next layer only, can run
+    // as one launch that never stores the two intermediates (conv_block.hip).  The three layers keep their buffers, so
+    // the plan can run them one by one as well: the shape heuristic below picks, sol_network_autotune measures.
+    if (!net->training && !net->keep && dt == SOL_BF16)
+        for (int i = 0; i < n_layers; i++) {
+            LayerPlan &c3 = net->layers[i];
+            const auto plain = [](const LayerPlan &l) {
+                return l.L.kind == SOL_LAYER_CONV && l.L.pool.kind == SOL_POOL_NONE && l.L.act == SOL_ACT_RELU && !l.cout_real && !l.cin_real &&
+                       l.concat_into < 0 && l.pair < 0 && !l.elided && !l.absorbs_next && l.cd.sh == 1 && l.cd.sw == 1;
+            };
+            const auto pointwise = [](const LayerPlan &l) { return l.cd.kh == 1 && l.cd.kw == 1 && l.cd.ph == 0 && l.cd.pw == 0; };
+            if (!plain(c3) || !pointwise(c3) || c3.res < 0 || c3.src < 0) continue;
+            LayerPlan &c2 = net->layers[c3.src];
+            if (!plain(c2) || c2.res >= 0 || c2.nuse != 1 || c2.src < 0 || c2.cd.kh != 3 || c2.cd.kw != 3 || c2.cd.ph != 1 || c2.cd.pw != 1) continue;
+            LayerPlan &c1 = net->layers[c2.src];
+            if (!plain(c1) || !pointwise(c1) || c1.res >= 0 || c1.nuse != 1 || c1.src != c3.res || c1.src < 0) continue;
+            if (c1.cd.cout != c2.cd.cout || c3.cd.cout != c1.cd.cin) continue;
+            if (!block_kernel_applies(dt, c1.in.n, c1.in.h, c1.in.w, c1.in.c, c1.cd.cout)) continue;
+            c3.block_c1 = c2.src; c3.block_c2 = c3.src;
+            c1.block_c3 = c2.block_c3 = i;
+            // heuristic: worth it where the pixels fill the chip several times over (the weights travel once per tile)
+            c3.use_block = (long)c1.in.n * c1.in.h * c1.in.w >= 40000;
+        }
+
     // activation layout: inference reuses buffers once their last consumer has run, training keeps all
     Arena ar;
     for (int i = 0; i < n_layers; i++) {
@@ -624,6 +653,26 @@ sol_status sol_conv2d_fused(const sol_tensor_desc *xd, const void *x, const sol_
     SOL_TRY(check_conv(cd));
     return conv_fused_impl(*xd, x, *cd, w_packed, scale, shift, residual, act, pool, y, pool_argmax, prepool,
                            g_tile_override, (hipStream_t)stream);
+}
+
+sol_status sol_bottleneck_fused(const sol_tensor_desc *xd, const void *x, int mid, const void *w1_packed, const float *scale1,
+                                const float *shift1, const void *w2_packed, const float *scale2, const float *shift2,
+                                const void *w3_packed, const float *scale3, const float *shift3, void *y, void *stream) {
+    SOL_TRY(check_tensor(xd, "x"));
+    SOL_REQUIRE(mid > 0, SOL_ERR_SHAPE, "bad mid channel count %d", mid);
+    SOL_REQUIRE(block_kernel_applies(xd->dtype, xd->n, xd->h, xd->w, xd->c, mid), SOL_ERR_UNSUPPORTED,
+                "the fused bottleneck runs bf16 blocks with 64 or 128 mid channels, a multiple of 128 block channels and images of at "
+                "most %d columns (got dtype %d, %d mid channels, %d channels, %d columns); run the three layers one by one",
+                mid == 64 ? 126 : 79, xd->dtype, mid, xd->c, xd->w);
+    if (xd->n == 0) return SOL_OK;
+    SOL_REQUIRE(x && y && w1_packed && w2_packed && w3_packed && scale1 && shift1 && scale2 && shift2 && scale3 && shift3, SOL_ERR_NULL,
+                "x, y, the three packed weights and the six scale / shift vectors must not be NULL");
+    SOL_REQUIRE(aligned16(x) && aligned16(y) && aligned16(w1_packed) && aligned16(w2_packed) && aligned16(w3_packed) && aligned16(scale1) &&
+                    aligned16(shift1) && aligned16(scale2) && aligned16(shift2) && aligned16(scale3) && aligned16(shift3),
+                SOL_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    SOL_REQUIRE(x != y, SOL_ERR_SHAPE, "the block cannot run in place: neighbouring tiles read x rows that others have already overwritten");
+    const BlockLaunch b{x, y, w1_packed, w2_packed, w3_packed, scale1, shift1, scale2, shift2, scale3, shift3, xd->n, xd->h, xd->w, xd->c, mid};
+    return launch_conv_block(b, (hipStream_t)stream);
 }
 
 size_t sol_packed_dw_weight_bytes(int c, int kh, int kw, sol_dtype dt) {
@@ -986,6 +1035,7 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
     for (int i = first; i <= last; i++) {
         const LayerPlan &lp = net->layers[i];
         if (lp.elided) continue;                            // computed by the convolution in front of it
+        if (lp.block_c3 >= 0 && net->layers[lp.block_c3].use_block && !g_tile_override) continue;   // ... by the bottleneck launch behind it
         const void *in = layer_in(net, lp.src, x, ws);
         const int oi = lp.absorbs_next ? i + 1 : lp.concat_into >= 0 ? lp.concat_into : i;   // the layer whose buffer this launch writes
         void *out = oi + 1 == nl ? y : static_cast<void *>(ws + net->layers[oi].out_off);
@@ -1002,6 +1052,15 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
                 const void *res = lp.res >= 0 ? layer_in(net, lp.res, x, ws) : nullptr;
                 void *conv_dst = lp.split_pool ? static_cast<void *>(ws + lp.tmp_off) : out;
                 const sol_pool_desc *fused = lp.absorbs_next ? &net->layers[i + 1].L.pool : lp.fuse_pool ? &lp.L.pool : nullptr;
+                if (lp.block_c1 >= 0 && lp.use_block && !g_tile_override) {     // the whole bottleneck in one launch
+                    const LayerPlan &b1 = net->layers[lp.block_c1], &b2 = net->layers[lp.block_c2];
+                    const auto fp = [&](size_t off) { return reinterpret_cast<const float *>(net->params + off); };
+                    const BlockLaunch bl{layer_in(net, b1.src, x, ws), conv_dst, net->params + b1.w_off, net->params + b2.w_off, net->params + lp.w_off,
+                                         fp(b1.scale_off), fp(b1.shift_off), fp(b2.scale_off), fp(b2.shift_off), scale, shift,
+                                         b1.in.n, b1.in.h, b1.in.w, b1.in.c, b1.cd.cout};
+                    SOL_TRY(launch_conv_block(bl, st));
+                    break;
+                }
                 if (lp.pair >= 0) {     // this launch also computes the projection shortcut it adds
                     const LayerPlan &pp = net->layers[lp.pair];
                     const PairOperand po{layer_in(net, pp.src, x, ws), net->params + pp.w_off,
@@ -1168,7 +1227,7 @@ sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *
     if (net->training) return autotune_training(net, x, y, workspace, workspace_bytes, reps, (hipStream_t)stream);
     hipStream_t st = (hipStream_t)stream;
     const int nl = (int)net->layers.size();
-    for (auto &lp : net->layers) lp.tile = T_AUTO;
+    for (auto &lp : net->layers) { lp.tile = T_AUTO; lp.use_block = false; }   // every layer is tuned on its own first
     // one whole pass: validates the arguments and leaves finite activations of the right shape in every buffer
     SOL_TRY(run_layers(net, x, y, workspace, workspace_bytes, 0, nl - 1, st));
     hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -1212,10 +1271,50 @@ sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *
         }
         lp.tile = best_tile;
     }
+    // bottlenecks: one depth-first launch against the three tuned launches, both right behind the block's producer
+    for (int i = 0; i < nl && rs == SOL_OK; i++) {
+        LayerPlan &lp = net->layers[i];
+        if (lp.block_c1 < 0 || lp.in.n == 0) continue;
+        const int c1 = lp.block_c1, c2 = lp.block_c2, prod = net->layers[c1].src;
+        float t[2] = {0.f, 0.f};
+        for (int fused = 0; fused < 2 && rs == SOL_OK; fused++) {
+            lp.use_block = fused != 0;
+            for (int r = 0; r < reps + 1 && rs == SOL_OK; r++) {
+                if (prod >= 0) rs = run_layers(net, x, y, workspace, workspace_bytes, prod, prod, st);
+                if (rs != SOL_OK) break;
+                SOL_HIP(hipEventRecord(e0, st));
+                for (int j : {c1, c2, i})
+                    if (rs == SOL_OK) rs = run_layers(net, x, y, workspace, workspace_bytes, j, j, st);
+                SOL_HIP(hipEventRecord(e1, st));
+                SOL_HIP(hipEventSynchronize(e1));
+                float ms = 0.f;
+                SOL_HIP(hipEventElapsedTime(&ms, e0, e1));
+                if (r > 0) t[fused] += ms;
+            }
+        }
+        lp.use_block = t[1] < t[0];
+    }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (rs != SOL_OK) for (auto &lp : net->layers) lp.tile = T_AUTO;
     return rs;
+}
+
+sol_status sol_network_layer_block(const sol_network *net, int layer, int *state) {
+    SOL_REQUIRE(net && state, SOL_ERR_NULL, "net and state must not be NULL");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    const LayerPlan &lp = net->layers[layer];
+    *state = lp.block_c1 < 0 ? -1 : (lp.use_block ? 1 : 0);
+    return SOL_OK;
+}
+
+sol_status sol_network_set_layer_block(sol_network *net, int layer, int fused) {
+    SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    LayerPlan &lp = net->layers[layer];
+    SOL_REQUIRE(lp.block_c1 >= 0 || !fused, SOL_ERR_UNSUPPORTED, "layer %d is not the last convolution of a bottleneck the depth-first kernel can run", layer);
+    lp.use_block = fused != 0;
+    return SOL_OK;
 }
 
 sol_status sol_network_set_layer_tile(sol_network *net, int layer, int tile) {
@@ -1280,7 +1379,8 @@ void sol_graph_destroy(sol_graph *g) {
 sol_status sol_network_layer_fused_into(const sol_network *net, int layer, int *into) {
     SOL_REQUIRE(net && into, SOL_ERR_NULL, "net / into is NULL");
     SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
-    *into = net->layers[layer].fused_into;
+    const LayerPlan &lp = net->layers[layer];
+    *into = (lp.block_c3 >= 0 && net->layers[lp.block_c3].use_block) ? lp.block_c3 : lp.fused_into;
     return SOL_OK;
 }
 

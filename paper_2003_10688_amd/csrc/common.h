@@ -70,7 +70,7 @@ template <> struct Elem<bf16_t> {
 // ~40-instruction software division; the divisor's magic number is computed on the host).
 struct FastDiv {
     uint32_t d, mul, s1, s2;
-    FastDiv() : d(1), mul(1), s1(0), s2(0) {}
+    __host__ __device__ FastDiv() : d(1), mul(1), s1(0), s2(0) {}
     explicit FastDiv(uint32_t div) : d(div) {
         uint32_t l = 0;
         while ((1ull << l) < div) l++;
@@ -160,6 +160,15 @@ sol_status launch_conv_pair(ConvArgs a, const void *x2, const void *w2, const fl
                             int Kp2, int stride, hipStream_t st);
 bool stem_pool_applies(const ConvArgs &a, int dt, const sol_pool_desc &p);   // stem + ReLU + 3x3/2 max pool in one kernel
 sol_status launch_conv_stem_pool(const ConvArgs &a, hipStream_t st);
+// a whole stride-1 bottleneck (1x1 reduce, 3x3, 1x1 expand + identity shortcut, folded BN and ReLU each) in one kernel (conv_block.hip)
+struct BlockLaunch {
+    const void *x; void *y;                          // block input / output, NHWC [N][H][W][C4]
+    const void *w1, *w2, *w3;                        // packed weights of the three convolutions
+    const float *s1, *h1, *s2, *h2, *s3, *h3;        // their folded scale / shift
+    int N, H, W, C4, WM;                             // WM: mid channels
+};
+bool block_kernel_applies(int dt, int N, int H, int W, int C4, int WM);
+sol_status launch_conv_block(const BlockLaunch &b, hipStream_t st);
 bool linear_kernel_applies(const ConvArgs &a, int dt);
 sol_status launch_linear(const ConvArgs &a, int dt, hipStream_t st);
 sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t st);

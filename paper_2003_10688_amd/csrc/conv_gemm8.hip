@@ -140,7 +140,12 @@ __global__ void __launch_bounds__(512) conv_gemm8_kernel(const ConvArgs a) {
     const Affine8 aff = load_affine<TC>(a, lane, c0 + wc * TC * 32);
     ResidualRegs<T, TP, TC> resregs;
     resregs.on = false;
-    if (kq == 0) prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
+    // With a four-way K split the accumulators of three partner waves pass through this wave's registers at the end:
+    // no room to hold residual rows across the loop as well (they would be spilled to scratch memory and back); such
+    // tiles fetch the residual in the epilogue.  The same holds for wave tiles of eight accumulator blocks.
+    if constexpr (KSPL < 4 && TC * TP < 8) {
+        if (kq == 0) prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
+    }
 
     f32x16_t acc[TC][TP];
 #pragma unroll
@@ -252,11 +257,14 @@ __global__ void __launch_bounds__(512) conv_gemm8_kernel(const ConvArgs a) {
             for (int i = 0; i < TC; i++)
 #pragma unroll
                 for (int j = 0; j < TP; j++)
+                {
 #pragma unroll
                     for (int g = 0; g < 4; g++) {
                         const float4 v = *reinterpret_cast<const float4 *>(src + ((i * TP + j) * 4 + g) * 256);
                         acc[i][j][4 * g] += v.x; acc[i][j][4 * g + 1] += v.y; acc[i][j][4 * g + 2] += v.z; acc[i][j][4 * g + 3] += v.w;
                     }
+                    asm volatile("" : "+v"(acc[i][j]) : : "memory");   // one accumulator block at a time (with every partner's loads hoisted the registers run out): the sums must exist here, later loads stay behind
+                }
         }
     }
     conv_epilogue_auto<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds + EPI0), grp, lane, p0 + wp * TP * 32, c0 + wc * TC * 32,

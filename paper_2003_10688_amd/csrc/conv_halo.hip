@@ -137,7 +137,7 @@ __global__ void __launch_bounds__(WP *WC *KSPL * 64, MINW) conv_halo_kernel(cons
     const Affine8 aff = (a.scale && a.shift) ? load_affine_unconditional<TC>(a, lane, c0 + wc * TC * 32) : load_affine<TC>(a, lane, c0 + wc * TC * 32);
     ResidualRegs<T, TP, TC> resregs;
     resregs.on = false;                                  // tight register budgets fetch residual rows in the epilogue instead
-    if constexpr (MINW < 4) {
+    if constexpr (MINW < 4 && KSPL < 4) {          // a four-way K split needs the registers for its partners' accumulators
         if (kq == 0) prefetch_residual<T, TP, TC>(a, lane, p0 + wp * TP * 32, c0 + wc * TC * 32, LinearRows{a.P}, resregs);
     }
     if (tid < NPB * 64) *reinterpret_cast<unsigned *>(patch + (tid >> 6) * PBYTES + PROWS * ROWB + (tid & 63) * 4) = 0u;   // two zero rows
@@ -286,11 +286,14 @@ __global__ void __launch_bounds__(WP *WC *KSPL * 64, MINW) conv_halo_kernel(cons
             for (int i = 0; i < TC; i++)
 #pragma unroll
                 for (int j = 0; j < TP; j++)
+                {
 #pragma unroll
                     for (int g = 0; g < 4; g++) {
                         const float4 v = *reinterpret_cast<const float4 *>(src + ((i * TP + j) * 4 + g) * 256);
                         acc[i][j][4 * g] += v.x; acc[i][j][4 * g + 1] += v.y; acc[i][j][4 * g + 2] += v.z; acc[i][j][4 * g + 3] += v.w;
                     }
+                    asm volatile("" : "+v"(acc[i][j]) : : "memory");   // one accumulator block at a time (with every partner's loads hoisted the registers run out): the sums must exist here, later loads stay behind
+                }
         }
     }
     conv_epilogue_auto<T, TP, TC>(a, acc, reinterpret_cast<float *>(lds + EPI0), grp, lane, p0 + wp * TP * 32, c0 + wc * TC * 32,

@@ -192,6 +192,15 @@ def sol_conv2d_fused(x, cd, w_packed, scale=None, shift=None, residual=None, act
     return y, arg, pre
 
 
+def sol_bottleneck_fused(x, mid, w1, s1, h1, w2, s2, h2, w3, s3, h3, stream=None):
+    """x: NHWC bf16 device tensor; w*: packed weights; s*/h*: folded scale / shift.  Returns y (same shape as x)."""
+    y = torch.empty_like(x)
+    xd = tensor_desc(x)
+    _check(lib().sol_bottleneck_fused(C.byref(xd), _ptr(x), C.c_int(mid), _ptr(w1), _ptr(s1), _ptr(h1), _ptr(w2), _ptr(s2), _ptr(h2),
+                                      _ptr(w3), _ptr(s3), _ptr(h3), _ptr(y), _stream(stream)))
+    return y
+
+
 def sol_pack_dwconv_weights(c, kh, kw, dt, w_c1hw, stream=None):
     """w_c1hw: device fp32 [c][1][kh][kw] -> packed device buffer (uint8 tensor)."""
     packed = torch.empty(lib().sol_packed_dw_weight_bytes(c, kh, kw, dt), dtype=torch.uint8, device=w_c1hw.device)
@@ -341,12 +350,17 @@ class Network:
             _check(lib().sol_network_layer_tile(self._h, C.c_int(i), C.byref(t)))
             if t.value:
                 out[i] = t.value
+            b = self.block_state(i)
+            if b >= 0:
+                out[f"{i}b"] = b          # bottleneck ending in layer i: 1 = one depth-first launch, 0 = layer by layer
         return out
 
     def set_tiles(self, tiles):
         """Restores per-layer kernel/tile ids from an earlier autotune() of the same network ({layer: tile id})."""
         for i in range(len(self.layers)):
             _check(lib().sol_network_set_layer_tile(self._h, C.c_int(i), C.c_int(int(tiles.get(i, tiles.get(str(i), 0))))))
+            if f"{i}b" in tiles:
+                self.set_block(i, tiles[f"{i}b"])
 
     def graph(self, x, stream):
         """Records one forward pass on `stream` (a torch.cuda.Stream other than the default one) as a HIP graph;
@@ -361,6 +375,16 @@ class Network:
             _check(lib().sol_graph_launch(g, _stream(stream)))
             return self.y
         return launch
+
+    def block_state(self, layer):
+        """-1: `layer` ends no bottleneck the depth-first kernel can run; 0: runs layer by layer; 1: as one launch."""
+        t = C.c_int(0)
+        _check(lib().sol_network_layer_block(self._h, C.c_int(layer), C.byref(t)))
+        return t.value
+
+    def set_block(self, layer, fused):
+        """Runs the bottleneck that ends in convolution `layer` as one depth-first launch (fused) or layer by layer."""
+        _check(lib().sol_network_set_layer_block(self._h, C.c_int(layer), C.c_int(int(bool(fused)))))
 
     def fused_into(self, layer):
         """Index of the layer whose launch produces `layer`'s output (itself unless the plan fused it into

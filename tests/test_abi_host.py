@@ -159,7 +159,22 @@ def test_plan_fuses_stem_and_pool_only_when_it_may(sol):
     assert len(shortcuts) == 4 and shortcuts[0] == 4
     for j in shortcuts:
         want[j] = j + 1
+    # the identity bottlenecks of stages 0 and 1 (mid widths 64 / 128, enough pixels at batch 64) run as one
+    # depth-first launch: their first two convolutions are produced by the launch of the third
+    ends = [i for i, l in enumerate(wk.layers) if l["kind"] == "conv" and l.get("res", -1) >= 0 and wk.layers[l["res"]]["act"] != "none"
+            and l["cout"] in (256, 512)]
+    assert len(ends) == 5
+    for i in ends:
+        want[i - 2] = want[i - 1] = i
     assert r == want
+    st_, h_ = _create(sol, wk.layers, wk.in_shape, sol.BF16, 0)
+    bs = C.c_int(-2)
+    assert [L.sol_network_layer_block(h_, i, C.byref(bs)) or bs.value for i in ends] == [1] * 5
+    assert L.sol_network_layer_block(h_, 0, C.byref(bs)) == 0 and bs.value == -1
+    assert L.sol_network_set_layer_block(h_, ends[0], 0) == 0 and L.sol_network_layer_block(h_, ends[0], C.byref(bs)) == 0 and bs.value == 0
+    assert L.sol_network_layer_fused_into(h_, ends[0] - 1, C.byref(t)) == 0 and t.value == ends[0] - 1
+    assert L.sol_network_set_layer_block(h_, 0, 1) == 6 and L.sol_network_set_layer_block(h_, 0, 0) == 0
+    L.sol_network_destroy(h_)
     r_keep, ws_keep = fused(wk.layers, wk.in_shape, sol.BF16, sol.NET_KEEP_ACTIVATIONS)
     assert r_keep == list(range(n)) and ws_keep > ws
     assert fused(wk.layers, wk.in_shape, sol.BF16, sol.NET_TRAINING)[0] == list(range(n))
