@@ -21,7 +21,7 @@
 // workgroup barrier per stage, fragment reads as opaque statements ordered by hand (the compiler would make every
 // LDS read wait for all outstanding DMA), every DMA issued unconditionally (beyond the end through a size-0 buffer
 // resource) so that the in-order vmcnt bookkeeping is static.  The first stages of the next phase are issued before
-// the epilogue of the current one.
+// the epilogue of the current one, which therefore writes LDS with bare ds_write statements.
 #include <algorithm>
 
 #include "conv_common.h"
@@ -57,15 +57,19 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
     static_assert(WM % 64 == 0 && TCA == 1 && WPA * TPA * 32 >= PRA && PRA % 16 == 0, "phase A tiling");
     static_assert(WPB * TPB == NBO && WCB * TCB * 32 == WM, "phase B tiling");
     static_assert(NBO % WPC == 0, "phase C tiling");
-    // LDS map: [t1 planes (rows + 256 zero bytes each), later t2 planes][ring slots / epilogue strips][dump]
+    // LDS map (overlaid: the phases never need everything at once)
+    //   phase A:  [ring of NSA slots ...........................................]            (t1 is written after the loop)
+    //   phase B:  [t1 planes: rows, zero block          ][ring of NSB weight slots]
+    //   phase C:  [t2 planes                            ][two W3 buffers][epilogue strips]
     constexpr int PLANE1 = PRA * 128 + 256, PLANE2 = NBO * 32 * 128;
     constexpr int R0 = (CH * PLANE1 > CH * PLANE2 ? CH * PLANE1 : CH * PLANE2);
     constexpr int XROWB = 64;                                         // phase A: bytes of reduction per row and stage
     constexpr int SLOTA = (PRA + WM) * XROWB, SLOTB = WM * 128, PCBUF = PC * WM * 2;
     constexpr int STRIPS = NW * 32 * (32 + 4) * 4;
-    constexpr int R1A = NSA * SLOTA, R1B = NSB * SLOTB, R1C = 2 * PCBUF + STRIPS;
-    constexpr int R1 = R1A > R1B ? (R1A > R1C ? R1A : R1C) : (R1B > R1C ? R1B : R1C);
-    constexpr int LDSB = R0 + R1 + 1024;
+    constexpr int R1B = NSB * SLOTB, R1C = 2 * PCBUF + STRIPS;
+    constexpr int LBC = R0 + (R1B > R1C ? R1B : R1C);
+    constexpr int LMAIN = NSA * SLOTA > LBC ? NSA * SLOTA : LBC;
+    constexpr int LDSB = LMAIN + 1024;
     static_assert(LDSB <= 160 * 1024, "LDS");
     static_assert(R0 % 256 == 0 && PCBUF == 16384, "alignment of the ring area; one pass of W3 is sixteen 1 KB DMA segments");
     // DMA instructions per wave and stage
@@ -74,7 +78,7 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
     static_assert(LB >= 1 && LC >= 1 && (NSA - 1) * LA < 64 && (NSB - 1) * LB < 64, "vmcnt");
 
     __shared__ __align__(1024) unsigned char lds[LDSB];
-    unsigned char *const t1 = lds, *const ring = lds + R0, *const dump = lds + R0 + R1;
+    unsigned char *const t1 = lds, *const ringA = lds, *const ring = lds + R0, *const dump = lds + LMAIN;
 
     asm volatile("" ::"s"(a.x), "s"(a.y), "s"(a.w1), "s"(a.w2), "s"(a.w3), "s"(a.s1), "s"(a.h1), "s"(a.s2), "s"(a.h2), "s"(a.s3),
                  "s"(a.h3), "s"(a.P), "s"(a.H), "s"(a.W), "s"(a.C4), "s"(a.bp), "s"(a.ntiles), "s"(a.dw.mul), "s"(a.dh.mul));
@@ -95,16 +99,14 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
     const __amdgpu_buffer_rsrc_t w3r = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.w3), 0, C4 * WM * 2, 0x00020000);
     const __amdgpu_buffer_rsrc_t nullr = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, 0, 0x00020000);   // size 0: zeros
 
-    // zero rows of the t1 planes (no DMA ever writes them); ahead of the first DMA, or the compiler would wait for it here
-    if (tid < CH * 64) *reinterpret_cast<unsigned *>(t1 + (tid >> 6) * PLANE1 + PRA * 128 + (tid & 63) * 4) = 0u;
-
     // the weights are cold when the block starts: touch one dword per 128-byte line, spread over the XCD's workgroups
     warm_l2(static_cast<const unsigned char *>(a.w1), (unsigned)(WM * C4 * 2), dump + (wave & 3) * 256, tid, NW * 64);
     warm_l2(static_cast<const unsigned char *>(a.w2), (unsigned)(WM * 9 * WM * 2), dump + (wave & 3) * 256, tid, NW * 64);
     warm_l2(static_cast<const unsigned char *>(a.w3), (unsigned)(C4 * WM * 2), dump + (wave & 3) * 256, tid, NW * 64);
 
-    // ================================================================ phase A: t1 = relu(bn1(x . W1)) over the patch rows
-    // DMA lane offsets; rows of 64 bytes: one instruction = 16 rows x 4 slots of 16 bytes
+    // ---- DMA lane offsets of all three phases (a few registers each), so that a phase's first stages can be issued
+    // before the epilogue of the phase in front of it
+    // phase A, rows of 64 bytes: one instruction = 16 rows x 4 slots of 16 bytes
     unsigned xoA[XLA], woA[WLA];
     {
         const int lslot = lane & 3, lrow = lane >> 2;
@@ -121,8 +123,23 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
             woA[i] = idx < NWIA ? (unsigned)row * (unsigned)(C4 * 2) + (unsigned)((lslot ^ swz<XROWB>(row)) << 4) : 0xffffffffu;
         }
     }
+    // phases B and C, rows of 128 bytes: one instruction = 8 rows x 8 slots
+    unsigned woB[LB], woC[LC];
+    {
+        const int lslot = lane & 7, lrow = lane >> 3;
+#pragma unroll
+        for (int i = 0; i < LB; i++) {
+            const int row = (wave * LB + i) * 8 + lrow;
+            woB[i] = (unsigned)row * (unsigned)(9 * WM * 2) + (unsigned)((lslot ^ swz<128>(row)) << 4);
+        }
+#pragma unroll
+        for (int i = 0; i < LC; i++) {
+            const int idx = wave * LC + i, c = idx / (PC / 8), row = (idx % (PC / 8)) * 8 + lrow;   // plane c, row of the pass
+            woC[i] = (unsigned)row * (unsigned)(WM * 2) + (unsigned)(c * 128) + (unsigned)((lslot ^ swz<128>(row)) << 4);
+        }
+    }
     auto issueA = [&](int slot, unsigned soff, bool real) {
-        unsigned char *base = ring + slot * SLOTA;
+        unsigned char *base = ringA + slot * SLOTA;
         static_for<XLA>([&](auto I) {
             constexpr int i = decltype(I)::value;
             const int idx = wave + NW * i;
@@ -136,6 +153,40 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
             __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w1r : nullr, (__attribute__((address_space(3))) void *)dst, 16, woA[i], soff, 0, 0);
         });
     };
+    constexpr int nB = 9 * CH;
+    auto issueB = [&](int slot, int sidx, bool real) {      // stage sidx = chunk * 9 + tap
+        const int c = sidx / 9, tp = sidx - 9 * c;
+        const unsigned soff = (unsigned)((tp * WM + c * 64) * 2);
+        static_for<LB>([&](auto I) {
+            constexpr int i = decltype(I)::value;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w2r : nullr,
+                                                     (__attribute__((address_space(3))) void *)(ring + slot * SLOTB + (wave * LB + i) * 1024), 16,
+                                                     woB[i], soff, 0, 0);
+        });
+    };
+    const int npass = C4 / PC;
+    auto issueC = [&](int buf, int q, bool real) {
+        const unsigned soff = (unsigned)(q * PC * WM * 2);
+        static_for<LC>([&](auto I) {
+            constexpr int i = decltype(I)::value;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w3r : nullr,
+                                                     (__attribute__((address_space(3))) void *)(ring + buf * PCBUF + (wave * LC + i) * 1024), 16,
+                                                     woC[i], soff, 0, 0);
+        });
+    };
+    // BN + ReLU of a lane's four channels of one accumulator group, packed to bf16, stored at its place in a t1 / t2 plane
+    // (row r, channel ch: plane ch / 64, 16-byte slot (ch % 64) / 8 permuted with the row, as the fragment reads expect).
+    // A bare ds_write: a store the compiler knows of would wait for the next phase's DMAs, which are already in flight.
+    auto park = [&](const f32x16_t &acc, int g, const float4 &sc, const float4 &sh, unsigned plane_bytes, int row, int ch) {
+        float v0 = acc[4 * g] * sc.x + sh.x, v1 = acc[4 * g + 1] * sc.y + sh.y, v2 = acc[4 * g + 2] * sc.z + sh.z, v3 = acc[4 * g + 3] * sc.w + sh.w;
+        v0 = v0 > 0.f ? v0 : 0.f; v1 = v1 > 0.f ? v1 : 0.f; v2 = v2 > 0.f ? v2 : 0.f; v3 = v3 > 0.f ? v3 : 0.f;
+        const unsigned long long pk = (unsigned long long)pack_bf16x2(v0, v1) | ((unsigned long long)pack_bf16x2(v2, v3) << 32);
+        const unsigned dst = lds_addr(t1) + (unsigned)(ch >> 6) * plane_bytes + (unsigned)(row * 128) +
+                             (unsigned)((((ch & 63) >> 3) ^ swz<128>(row)) << 4) + (unsigned)((ch & 7) * 2);
+        asm volatile("ds_write_b64 %0, %1" ::"v"(dst), "v"(pk) : "memory");
+    };
+
+    // ================================================================ phase A: t1 = relu(bn1(x . W1)) over the patch rows
     const int nA = C4 / 32;
     // per-lane BN constants of phase A (16 channels: 4 groups of 4), loaded ahead of the DMAs: older loads never
     // disturb the static counts of the ring
@@ -173,7 +224,11 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
             ax[j][tp] = zero_row + ((0u - (hok[r] & wok[sx])) & (real - zero_row));
         }
     }
+    // the compiler's own bookkeeping learns here that the BN constants have arrived (they are older than every DMA above)
+#pragma unroll
+    for (int g = 0; g < 4; g++) asm volatile("" ::"v"(scA[g].x), "v"(scA[g].w), "v"(shA[g].x), "v"(shA[g].w));
 
+    float4 scB[TCB][4], shB[TCB][4];
     {
         f32x16_t acc[TPA];
 #pragma unroll
@@ -181,8 +236,8 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[j][e] = 0.f;
         const unsigned fsw = (unsigned)swz<XROWB>(lr);
-        const unsigned fx0 = lds_addr(ring) + (unsigned)((wpA * TPA * 32 + lr) * XROWB) + ((lh ^ fsw) << 4);
-        const unsigned fw0 = lds_addr(ring) + (unsigned)(PRA * XROWB + (wcA * 32 + lr) * XROWB) + ((lh ^ fsw) << 4);
+        const unsigned fx0 = lds_addr(ringA) + (unsigned)((wpA * TPA * 32 + lr) * XROWB) + ((lh ^ fsw) << 4);
+        const unsigned fw0 = lds_addr(ringA) + (unsigned)(PRA * XROWB + (wcA * 32 + lr) * XROWB) + ((lh ^ fsw) << 4);
         u32x4_t fa[2], fb[2][TPA];
         auto readA = [&](auto SET, unsigned kx, unsigned sb) {
             constexpr int set = decltype(SET)::value;
@@ -212,61 +267,55 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
             islot = islot + 1 == NSA ? 0 : islot + 1;
         }
         wait_vmcnt<0>();
-        __syncthreads();                                  // the ring is dead
-        // ---- epilogue of A: BN + ReLU, bf16, into the t1 planes (row r, channel ch: plane ch / 64, 16-byte slot
-        // (ch % 64) / 8 permuted with the row, as the fragment reads of phase B expect)
+        __syncthreads();                                  // the ring is dead: its space becomes t1 and the ring of phase B
+        // zero rows of the t1 planes (no DMA of phase B writes them), BN constants and first weight stages of phase B,
+        // all under the epilogue of A
+        if (tid < CH * 64) *reinterpret_cast<unsigned *>(t1 + (tid >> 6) * PLANE1 + PRA * 128 + (tid & 63) * 4) = 0u;
+#pragma unroll
+        for (int i = 0; i < TCB; i++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                scB[i][g] = *reinterpret_cast<const float4 *>(a.s2 + (wcB * TCB + i) * 32 + 8 * g + 4 * lh);
+                shB[i][g] = *reinterpret_cast<const float4 *>(a.h2 + (wcB * TCB + i) * 32 + 8 * g + 4 * lh);
+            }
+#pragma unroll
+        for (int s = 0; s < NSB - 1; s++) issueB(s, s, s < nB);
+        // ---- epilogue of A
 #pragma unroll
         for (int j = 0; j < TPA; j++) {
             const int row = (wpA * TPA + j) * 32 + lr;
             if (row < PRA) {
 #pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    const int ch = wcA * 32 + 8 * g + 4 * lh;
-                    float v0 = acc[j][4 * g] * scA[g].x + shA[g].x, v1 = acc[j][4 * g + 1] * scA[g].y + shA[g].y;
-                    float v2 = acc[j][4 * g + 2] * scA[g].z + shA[g].z, v3 = acc[j][4 * g + 3] * scA[g].w + shA[g].w;
-                    v0 = v0 > 0.f ? v0 : 0.f; v1 = v1 > 0.f ? v1 : 0.f; v2 = v2 > 0.f ? v2 : 0.f; v3 = v3 > 0.f ? v3 : 0.f;
-                    uint2 pk;
-                    pk.x = pack_bf16x2(v0, v1);
-                    pk.y = pack_bf16x2(v2, v3);
-                    unsigned char *dst = t1 + (ch >> 6) * PLANE1 + row * 128 + ((((ch & 63) >> 3) ^ swz<128>(row)) << 4) + (ch & 7) * 2;
-                    *reinterpret_cast<uint2 *>(dst) = pk;
-                }
+                for (int g = 0; g < 4; g++) park(acc[j], g, scA[g], shA[g], PLANE1, row, wcA * 32 + 8 * g + 4 * lh);
             }
         }
+        wait_lgkmcnt<0>();
     }
-    __syncthreads();                                      // t1 is complete
+    __builtin_amdgcn_s_barrier();                         // t1 is complete (every wave's stores have been executed)
 
     // ================================================================ phase B: t2 = relu(bn2(conv3x3(t1)))
-    unsigned woB[LB];
-    {
-        const int lslot = lane & 7, lrow = lane >> 3;
-#pragma unroll
-        for (int i = 0; i < LB; i++) {
-            const int row = (wave * LB + i) * 8 + lrow;
-            woB[i] = (unsigned)row * (unsigned)(9 * WM * 2) + (unsigned)((lslot ^ swz<128>(row)) << 4);
-        }
-    }
-    auto issueB = [&](int slot, int sidx, bool real) {      // stage sidx = chunk * 9 + tap
-        const int c = sidx / 9, tp = sidx - 9 * c;
-        const unsigned soff = (unsigned)((tp * WM + c * 64) * 2);
-        static_for<LB>([&](auto I) {
-            constexpr int i = decltype(I)::value;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w2r : nullr,
-                                                     (__attribute__((address_space(3))) void *)(ring + slot * SLOTB + (wave * LB + i) * 1024), 16,
-                                                     woB[i], soff, 0, 0);
-        });
-    };
-    constexpr int nB = 9 * CH;
-    float4 scB[TCB][4], shB[TCB][4];
 #pragma unroll
     for (int i = 0; i < TCB; i++)
 #pragma unroll
-        for (int g = 0; g < 4; g++) {
-            scB[i][g] = *reinterpret_cast<const float4 *>(a.s2 + (wcB * TCB + i) * 32 + 8 * g + 4 * lh);
-            shB[i][g] = *reinterpret_cast<const float4 *>(a.h2 + (wcB * TCB + i) * 32 + 8 * g + 4 * lh);
-        }
+        for (int g = 0; g < 4; g++) asm volatile("" ::"v"(scB[i][g].x), "v"(scB[i][g].w), "v"(shB[i][g].x), "v"(shB[i][g].w));
+    // phase C state that is set up before the epilogue of B
+    const int wpC = wave % WPC, wcC = wave / WPC;
+    const int mwC = p0 + wpC * TPC * 32;
+    const bf16_t *__restrict__ xres = static_cast<const bf16_t *>(a.x);
+    ResidualRegs<bf16_t, TPC, 1> res[2];                  // shortcut rows of the current and of the next pass
+    res[0].on = res[1].on = true;
+    constexpr int NRES = TPC * 2;                         // loads per lane and pass, always issued (clamped addresses)
+    auto load_res = [&](auto SET, int q) {
+        constexpr int set = decltype(SET)::value;
+        const int erow = lane >> 2, cb = min(q * PC + wcC * 32, C4 - 32) + (lane & 3) * 8;     // beyond the last pass: any valid channels
 #pragma unroll
-    for (int s = 0; s < NSB - 1; s++) issueB(s, s, s < nB);
+        for (int j = 0; j < TPC; j++)
+#pragma unroll
+            for (int ps = 0; ps < 2; ps++) {
+                const int m = min(mwC + j * 32 + erow + ps * 16, pend - 1);                      // rows beyond the tile are never stored
+                res[set].r[j][ps].load(xres + (size_t)m * C4 + cb);
+            }
+    };
     {
         f32x16_t acc[TCB][TPB];
 #pragma unroll
@@ -319,62 +368,32 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
         }
         wait_vmcnt<0>();
         __syncthreads();                                  // every wave is done with t1 and the ring: t2 goes over t1
-        // ---- epilogue of B: BN + ReLU, bf16, into the t2 planes (same row layout, NBO * 32 rows per plane)
+        // first W3 rows and shortcut rows of phase C, under the epilogue of B
+        issueC(0, 0, true);
+        load_res(I0{}, 0);
+        // ---- epilogue of B: into the t2 planes (same row layout, NBO * 32 rows per plane)
 #pragma unroll
         for (int i = 0; i < TCB; i++)
 #pragma unroll
             for (int j = 0; j < TPB; j++) {
                 const int row = (wpB * TPB + j) * 32 + lr;
 #pragma unroll
-                for (int g = 0; g < 4; g++) {
-                    const int ch = (wcB * TCB + i) * 32 + 8 * g + 4 * lh;
-                    float v0 = acc[i][j][4 * g] * scB[i][g].x + shB[i][g].x, v1 = acc[i][j][4 * g + 1] * scB[i][g].y + shB[i][g].y;
-                    float v2 = acc[i][j][4 * g + 2] * scB[i][g].z + shB[i][g].z, v3 = acc[i][j][4 * g + 3] * scB[i][g].w + shB[i][g].w;
-                    v0 = v0 > 0.f ? v0 : 0.f; v1 = v1 > 0.f ? v1 : 0.f; v2 = v2 > 0.f ? v2 : 0.f; v3 = v3 > 0.f ? v3 : 0.f;
-                    uint2 pk;
-                    pk.x = pack_bf16x2(v0, v1);
-                    pk.y = pack_bf16x2(v2, v3);
-                    unsigned char *dst = t1 + (ch >> 6) * PLANE2 + row * 128 + ((((ch & 63) >> 3) ^ swz<128>(row)) << 4) + (ch & 7) * 2;
-                    *reinterpret_cast<uint2 *>(dst) = pk;
-                }
+                for (int g = 0; g < 4; g++) park(acc[i][j], g, scB[i][g], shB[i][g], PLANE2, row, (wcB * TCB + i) * 32 + 8 * g + 4 * lh);
             }
+        wait_lgkmcnt<0>();
     }
-    __syncthreads();                                      // t2 is complete
 
     // ================================================================ phase C: y = relu(bn3(t2 . W3) + x), PC channels per pass
-    // The W3 rows of a pass (PC x WM, 16 KB) sit in one of two buffers; the next pass's rows are fetched while the
-    // current pass is contracted.  A wave waits for its own share of them (and for the shortcut rows) right before
-    // its epilogue, when they were issued a whole contraction ago, and the barrier behind the epilogue publishes
-    // them: no wait ever has to count the epilogue's stores.
-    const int wpC = wave % WPC, wcC = wave / WPC;
-    unsigned woC[LC];
-    {
-        const int lslot = lane & 7, lrow = lane >> 3;
-#pragma unroll
-        for (int i = 0; i < LC; i++) {
-            const int idx = wave * LC + i, c = idx / (PC / 8), row = (idx % (PC / 8)) * 8 + lrow;   // plane c, row of the pass
-            woC[i] = (unsigned)row * (unsigned)(WM * 2) + (unsigned)(c * 128) + (unsigned)((lslot ^ swz<128>(row)) << 4);
-        }
-    }
-    const int npass = C4 / PC;
-    auto issueC = [&](int buf, int q, bool real) {
-        const unsigned soff = (unsigned)(q * PC * WM * 2);
-        static_for<LC>([&](auto I) {
-            constexpr int i = decltype(I)::value;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w3r : nullr,
-                                                     (__attribute__((address_space(3))) void *)(ring + buf * PCBUF + (wave * LC + i) * 1024), 16,
-                                                     woC[i], soff, 0, 0);
-        });
-    };
+    // The W3 rows of a pass (PC x WM, 16 KB) sit in one of two buffers; the next pass's rows and shortcut rows are
+    // fetched while the current pass is contracted.  Right before its epilogue a wave waits until only the shortcut
+    // loads of the NEXT pass may be outstanding: its share of the next W3 rows and its own shortcut rows are then
+    // here, and the barrier behind the epilogue publishes the W3 rows.  No wait ever has to count the epilogue's stores.
     float *const strips = reinterpret_cast<float *>(ring + 2 * PCBUF);
     ConvArgs ca;                                          // what the shared epilogue reads
     ca.y = a.y; ca.res = a.x; ca.scale = a.s3; ca.shift = a.h3; ca.prepool = nullptr; ca.argmax = nullptr;
     ca.Cout = C4; ca.ldy = C4; ca.P = pend; ca.act = SOL_ACT_RELU; ca.pool = 0;
-    const int mwC = p0 + wpC * TPC * 32;
-    const bf16_t *__restrict__ xres = static_cast<const bf16_t *>(a.x);
-    issueC(0, 0, true);
-    wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
+    wait_vmcnt<NRES>();                                   // the first W3 rows (this wave's share) are here
+    __builtin_amdgcn_s_barrier();                         // ... everyone's, and t2 is complete
     {
         f32x16_t acc[1][TPC];
         const unsigned fw0 = lds_addr(ring) + (unsigned)((wcC * 32 + lr) * 128) + ((lh ^ (unsigned)swz<128>(lr)) << 4);
@@ -392,48 +411,44 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
             static_for<TPC>([&](auto J) { landed(fb[set][decltype(J)::value]); });
             static_for<TPC>([&](auto J) { Mma<bf16_t>::run(acc[0][decltype(J)::value], fa[set], fb[set][decltype(J)::value]); });
         };
-        ResidualRegs<bf16_t, TPC, 1> res;
-        res.on = true;
-        for (int q = 0; q < npass; q++) {
-            const int cw = q * PC + wcC * 32;
-            issueC((q + 1) & 1, q + 1, q + 1 < npass);
-            {   // shortcut rows of this pass, from clamped rows (rows beyond the tile are never stored)
-                const int erow = lane >> 2, cb = cw + (lane & 3) * 8;
+        for (int q0 = 0; q0 < npass; q0 += 2) {
+            static_for<2>([&](auto PARITY) {
+                constexpr int par = decltype(PARITY)::value;
+                const int q = q0 + par;
+                if (q < npass) {
+                    const int cw = q * PC + wcC * 32;
+                    issueC(par ^ 1, q + 1, q + 1 < npass);
+                    load_res(std::integral_constant<int, par ^ 1>{}, q + 1);
 #pragma unroll
-                for (int j = 0; j < TPC; j++)
+                    for (int j = 0; j < TPC; j++)
 #pragma unroll
-                    for (int ps = 0; ps < 2; ps++) {
-                        const int m = min(mwC + j * 32 + erow + ps * 16, pend - 1);
-                        res.r[j][ps].load(xres + (size_t)m * C4 + cb);
-                    }
-            }
-#pragma unroll
-            for (int j = 0; j < TPC; j++)
-#pragma unroll
-                for (int e = 0; e < 16; e++) acc[0][j][e] = 0.f;
-            const unsigned bufo = (unsigned)((q & 1) * PCBUF);
-            static_for<CH>([&](auto CI) {
-                constexpr int c = decltype(CI)::value;
-                const unsigned sb = bufo + (unsigned)(c * PC * 128), pb = (unsigned)(c * PLANE2);
-                readC(I0{}, 0u, sb, pb);
-                readC(I1{}, 32u, sb, pb);
-                wait_lgkmcnt<1 + TPC>();
-                mmaC(I0{});
-                readC(I0{}, 64u, sb, pb);
-                wait_lgkmcnt<1 + TPC>();
-                mmaC(I1{});
-                readC(I1{}, 96u, sb, pb);
-                wait_lgkmcnt<1 + TPC>();
-                mmaC(I0{});
-                wait_lgkmcnt<0>();
-                mmaC(I1{});
+                        for (int e = 0; e < 16; e++) acc[0][j][e] = 0.f;
+                    const unsigned bufo = (unsigned)(par * PCBUF);
+                    static_for<CH>([&](auto CI) {
+                        constexpr int c = decltype(CI)::value;
+                        const unsigned sb = bufo + (unsigned)(c * PC * 128), pb = (unsigned)(c * PLANE2);
+                        readC(I0{}, 0u, sb, pb);
+                        readC(I1{}, 32u, sb, pb);
+                        wait_lgkmcnt<1 + TPC>();
+                        mmaC(I0{});
+                        readC(I0{}, 64u, sb, pb);
+                        wait_lgkmcnt<1 + TPC>();
+                        mmaC(I1{});
+                        readC(I1{}, 96u, sb, pb);
+                        wait_lgkmcnt<1 + TPC>();
+                        mmaC(I0{});
+                        wait_lgkmcnt<0>();
+                        mmaC(I1{});
+                    });
+                    wait_vmcnt<NRES>();                   // all but the next pass's shortcut loads: the next W3 rows, this pass's shortcut rows
+                    const Affine8 aff = load_affine_unconditional<1>(ca, lane, cw);
+                    conv_epilogue_auto<bf16_t, TPC, 1>(ca, acc, strips, wave, lane, mwC, cw, aff, LinearRows{pend}, res[par]);
+                    __builtin_amdgcn_s_barrier();         // everyone's share has landed; everyone is done with this pass's buffer
+                }
             });
-            wait_vmcnt<0>();                              // the next pass's W3 rows (this wave's share) and the shortcut rows are here
-            const Affine8 aff = load_affine_unconditional<1>(ca, lane, cw);
-            conv_epilogue_auto<bf16_t, TPC, 1>(ca, acc, strips, wave, lane, mwC, cw, aff, LinearRows{pend}, res);
-            __builtin_amdgcn_s_barrier();                 // everyone's share has landed; everyone is done with this pass's buffer
         }
     }
+    wait_vmcnt<0>();
 #endif
 }
 
@@ -468,9 +483,9 @@ sol_status launch_conv_block(const BlockLaunch &b, hipStream_t st) {
     const int grid = ((a.ntiles + 7) / 8) * 8;
     if (b.WM == 64)
         //                              WM  PRA  NBO WPA TPA WPB TPB TCB NSA NSB
-        hipLaunchKernelGGL((conv_block_kernel<64, 384, 8, 4, 3, 4, 2, 1, 3, 4>), dim3(grid), dim3(512), 0, st, a);
+        hipLaunchKernelGGL((conv_block_kernel<64, 384, 8, 4, 3, 4, 2, 1, 5, 4>), dim3(grid), dim3(512), 0, st, a);
     else
-        hipLaunchKernelGGL((conv_block_kernel<128, 288, 8, 2, 5, 4, 2, 2, 3, 4>), dim3(grid), dim3(512), 0, st, a);
+        hipLaunchKernelGGL((conv_block_kernel<128, 288, 8, 2, 5, 4, 2, 2, 5, 4>), dim3(grid), dim3(512), 0, st, a);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }
