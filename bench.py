@@ -47,6 +47,9 @@ def layer_shapes(layers, in_shape, out_size):
         x = in_shape if (i == 0 and s == -1) else shapes[i - 1 if s == -1 else s]
         if l["kind"] == "conv":
             o = (x[0], l["cout"], out_size(x[2], l["kh"], l["sh"], l["ph"]), out_size(x[3], l["kw"], l["sw"], l["pw"]))
+            if l.get("pool"):      # a pool fused behind the convolution: the stored tensor is the pooled one
+                p = l["pool"]
+                o = (o[0], o[1], out_size(o[2], p["kh"], p["sh"], p["ph"]), out_size(o[3], p["kw"], p["sw"], p["pw"]))
         elif l["kind"] == "pool":
             p = l["pool"]
             o = (x[0], x[1], out_size(x[2], p["kh"], p["sh"], p["ph"]), out_size(x[3], p["kw"], p["sw"], p["pw"]))
@@ -69,7 +72,8 @@ def algorithmic_work(l, x, y, esize):
         return 2.0 * numel(y) * taps, esize * (numel(x) + taps * y[1] + numel(y) * (2 if l["res"] >= 0 else 1)) + 8 * y[1]
     if l["kind"] == "conv":
         k = l["kh"] * l["kw"] * x[1]
-        flops = 2.0 * y[0] * y[2] * y[3] * y[1] * k
+        ho, wo = (x[2] + 2 * l["ph"] - l["kh"]) // l["sh"] + 1, (x[3] + 2 * l["pw"] - l["kw"]) // l["sw"] + 1    # before any fused pool
+        flops = 2.0 * y[0] * ho * wo * y[1] * k
         byts = esize * (numel(x) + k * y[1] + numel(y) * (2 if l["res"] >= 0 else 1)) + 8 * y[1]
         return flops, byts
     if l["kind"] == "linear":
@@ -82,7 +86,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=3, help="workload: 3 = ResNet-50-shaped bs64 (default), 2 = ResNet-18-shaped bs32, 5 = 3-layer MLP with 8192 features bs64, 6 = depthwise-separable chain bs64, 7 = SqueezeNet-shaped bs64 (channel concatenations)")
+    ap.add_argument("--config", type=int, default=3, help="workload: 3 = ResNet-50-shaped bs64 (default), 2 = ResNet-18-shaped bs32, 5 = 3-layer MLP with 8192 features bs64, 6 = depthwise-separable chain bs64, 7 = SqueezeNet-shaped bs64 (channel concatenations), 8 = DenseNet-121-shaped bs64 (pre-activation convolutions on dense chains)")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--layer-reps", type=int, default=20, help="event-timed repetitions per layer for the roofline")
     ap.add_argument("--pass-reps", type=int, default=20, help="whole passes with an event in front of every launch (in-pass durations for the roofline)")

@@ -70,6 +70,10 @@ typedef struct {
     sol_pool_desc pool;     /* CONV: pool fused behind the activation (kind NONE = none); POOL: the pool */
     int out_features;       /* LINEAR */
     int src, res;
+    int pre_bn;             /* CONV: a batch-norm + ReLU of the layer's INPUT runs in front of the convolution (pre-activation
+                               order, as in the DenseNet-shaped networks of the paper's evaluation, Sec. VI); its parameters
+                               come through sol_network_set_pre_bn; the zero padding applies to the activated tensor;
+                               inference networks only */
 } sol_layer;
 
 typedef struct sol_network sol_network;
@@ -125,6 +129,20 @@ sol_status sol_conv2d_fused(const sol_tensor_desc *xd, const void *x, const sol_
                             const void *w_packed, const float *scale, const float *shift,
                             const void *residual, int act, const sol_pool_desc *pool, void *y,
                             int32_t *pool_argmax, void *prepool, void *hip_stream);
+
+/* The fused block with a batch-norm + ReLU on the INPUT side as well (pre-activation order; the paper names the
+ * DenseNet-shaped networks, built from such layers on concatenated features, among its largest gains, Sec. VI):
+ *   y = pool( act( scale[k] * conv( relu(pre_scale[c] * x + pre_shift[c]), w )[.,k] + shift[k] + residual ) )
+ * Taps in the padding contribute 0 (the padding surrounds the activated tensor).  For bf16 the activated input is
+ * rounded to bf16 before it is multiplied.  Arguments as sol_conv2d_fused, plus
+ *   ldx        elements between consecutive input pixels: 0 or xd->c for a dense tensor, more when x is a channel
+ *              prefix of a wider NHWC tensor (ldx * element size a multiple of 16)
+ *   pre_scale, pre_shift  device fp32 [xd->c] (sol_fold_bn of the input-side BN), or both NULL: no input-side map
+ * Runs on the register-staged kernel, which transforms the data on its way to on-chip memory; the 2x2 pools can be
+ * fused as usual, winners and the pre-pool tensor are not offered. */
+sol_status sol_conv2d_preact_fused(const sol_tensor_desc *xd, const void *x, int ldx, const float *pre_scale, const float *pre_shift,
+                                   const sol_conv_desc *cd, const void *w_packed, const float *scale, const float *shift,
+                                   const void *residual, int act, const sol_pool_desc *pool, void *y, void *hip_stream);
 
 /* A whole residual bottleneck as one depth-first kernel (the paper's layer-chain fusion, Sec. III-A: a chain of layers
  * is run over a block of data while it sits in registers and on-chip memory, here across three contractions):
@@ -205,6 +223,10 @@ sol_status sol_network_bind_params(sol_network *net, void *param_buf, size_t byt
 sol_status sol_network_set_params(sol_network *net, int layer, const float *w, const float *gamma,
                                   const float *beta, const float *mean, const float *var,
                                   const float *bias, float eps, void *hip_stream);
+
+/* Folds the input-side batch-norm of a CONV layer created with pre_bn (device fp32 [cin] each) into the bound buffer. */
+sol_status sol_network_set_pre_bn(sol_network *net, int layer, const float *gamma, const float *beta, const float *mean,
+                                  const float *var, float eps, void *hip_stream);
 
 /* Runs the layer list: one launch per fused layer on the stream, activations ping-ponged inside
  * `workspace`.  x: network input (NHWC), y: output of the last layer. */
@@ -298,8 +320,11 @@ sol_status sol_network_layer_fused_into(const sol_network *net, int layer, int *
 /* Concatenation in place: when a network keeps no activations, a convolution (no fused pool, channel count a
  * multiple of 8) whose output is read by one CONCAT layer only writes its channels straight into that layer's
  * buffer, provided its slice starts on a multiple of 8 channels and the joined count is one too; the other
- * inputs are copied into place when the CONCAT layer runs.  *parts = how many of the two inputs of CONCAT layer
- * `layer` are written in place (2: the layer launches nothing).  SOL_ERR_SHAPE if `layer` is not a CONCAT. */
+ * inputs are copied into place when the CONCAT layer runs.  A chain of CONCAT layers each of which extends the one
+ * before it by new channels (a dense block: src = the previous CONCAT) shares ONE buffer of the final width when the
+ * intermediate joins are read only by 1x1 convolutions, which then read a channel prefix of that buffer: the
+ * features of a dense block are written once and never copied.  *parts = how many of the two inputs of CONCAT layer
+ * `layer` are in place (2: the layer launches nothing).  SOL_ERR_SHAPE if `layer` is not a CONCAT. */
 sol_status sol_network_concat_in_place(const sol_network *net, int layer, int *parts);
 
 /* Runs one layer only, on whatever its producers left in the workspace (profiling aid: lets a caller

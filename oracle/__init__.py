@@ -323,9 +323,21 @@ def _src_of(i, l, outs, x):
     return outs[s]
 
 
+def pre_activation(x, p, bf16=False):
+    """BN + ReLU on the INPUT side of a convolution (the pre-activation order of the DenseNet-shaped networks of the
+    paper's evaluation, Sec. VI): relu(pre_gamma (x - pre_mean) / sqrt(pre_var + eps) + pre_beta), per input channel.
+    In bf16 mode the activated tensor is a rounding point, exactly as if a stand-alone BN-ReLU layer had stored it:
+    the HIP path feeds it to the matrix cores in bf16.  Zero padding of the convolution applies to this tensor."""
+    y = relu(bn_infer(x, p["pre_gamma"], p["pre_beta"], p["pre_mean"], p["pre_var"], p.get("eps", 1e-5)))
+    return round_bf16(y) if bf16 else y
+
+
 def fused_conv(x, p, l, residual=None, bf16=False, want_prepool=False):
-    """conv -> explicit BN -> (+residual) -> act -> pool -> (bf16 store).  Returns (y, argmax, prepool)."""
+    """[BN -> ReLU on the input ->] conv -> explicit BN -> (+residual) -> act -> pool -> (bf16 store).
+    Returns (y, argmax, prepool)."""
     cv = dwconv2d if l.get("dw") else conv2d
+    if l.get("pre_bn"):
+        x = pre_activation(x, p, bf16)
     y = cv(x, p["w"], p.get("bias"), (l["sh"], l["sw"]), (l["ph"], l["pw"]))
     if l["bn"]:
         y = bn_infer(y, p["gamma"], p["beta"], p["mean"], p["var"], p.get("eps", 1e-5))

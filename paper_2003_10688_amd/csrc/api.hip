@@ -62,13 +62,15 @@ static bool pool_is_fusable(const sol_pool_desc &p) {
 
 // second operand set of a fused projection pair: y = act(scale * conv(x, w) + shift + scale2 * conv(x2, w2) + shift2)
 struct PairOperand { const void *x2, *w2; const float *scale2, *shift2; int H2, W2, K2, Kp2, stride; };
+// input side of a pre-activation convolution / of a convolution that reads a channel prefix of a wider tensor
+struct InputSide { const float *pre_scale, *pre_shift; int ldx, cvalid; };   // NULL / NULL: no BN + ReLU; ldx 0: dense; cvalid 0: all channels real
 
 // Shared by sol_conv2d_fused and the network executor.
 static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, const sol_conv_desc &cd, const void *w,
                                   const float *scale, const float *shift, const void *res, int act,
                                   const sol_pool_desc *pool, void *y, int32_t *argmax, void *prepool, int tile,
                                   hipStream_t st, int ldy = 0,     // ldy: elements between output pixels in y, 0 = cout (dense)
-                                  const PairOperand *pair = nullptr) {
+                                  const PairOperand *pair = nullptr, const InputSide *ins = nullptr) {
     SOL_REQUIRE(cd.cin == xd.c, SOL_ERR_SHAPE, "conv cin %d != input channels %d", cd.cin, xd.c);
     SOL_REQUIRE(act == SOL_ACT_NONE || act == SOL_ACT_RELU, SOL_ERR_SHAPE, "bad activation %d", act);
     const int Ho = out_size(xd.h, cd.kh, cd.sh, cd.ph), Wo = out_size(xd.w, cd.kw, cd.sw, cd.pw);
@@ -108,6 +110,24 @@ static sol_status conv_fused_impl(const sol_tensor_desc &xd, const void *x, cons
         a.ldy = ldy;
     }
     SOL_REQUIRE((double)xd.n * Ho * Wo * a.ldy < 2147483648.0, SOL_ERR_UNSUPPORTED, "output spans 2^31 elements or more");
+    a.ldx = xd.c;
+    a.Cvalid = xd.c;
+    if (ins) {
+        SOL_REQUIRE((ins->pre_scale == nullptr) == (ins->pre_shift == nullptr), SOL_ERR_NULL, "input-side scale and shift come together");
+        SOL_REQUIRE(aligned16(ins->pre_scale) && aligned16(ins->pre_shift), SOL_ERR_ALIGN, "device pointers must be 16-byte aligned");
+        if (ins->ldx != 0 && ins->ldx != xd.c) {
+            SOL_REQUIRE(ins->ldx > xd.c && (ins->ldx * dtype_size(xd.dtype)) % 16 == 0, SOL_ERR_SHAPE,
+                        "input pitch %d: above the channel count %d, pixels 16-byte aligned", ins->ldx, xd.c);
+            SOL_REQUIRE((double)xd.n * xd.h * xd.w * ins->ldx < 2147483648.0, SOL_ERR_UNSUPPORTED, "input spans 2^31 elements or more");
+            a.ldx = ins->ldx;
+        }
+        if (ins->cvalid != 0) {
+            SOL_REQUIRE(ins->cvalid > 0 && ins->cvalid <= xd.c, SOL_ERR_SHAPE, "%d valid input channels of %d", ins->cvalid, xd.c);
+            a.Cvalid = ins->cvalid;
+        }
+        a.pre_scale = ins->pre_scale; a.pre_shift = ins->pre_shift;
+        SOL_REQUIRE(!(pool && a.pool == 3) && !pair, SOL_ERR_UNSUPPORTED, "the fused stem pair and the projection pair take a plain dense input");
+    }
     if (xd.n == 0) return SOL_OK;
     SOL_REQUIRE(x && w && y, SOL_ERR_NULL, "x, w_packed and y must not be NULL");
     SOL_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(scale) && aligned16(shift) && aligned16(res) &&
@@ -188,6 +208,11 @@ struct LayerPlan {
     int block_c1, block_c2;         // CONV (last 1x1 of a bottleneck): the reduce and 3x3 convolutions that one depth-first launch can compute with it (-1: none)
     int block_c3;                   // CONV (reduce / 3x3 of such a bottleneck): that last convolution (-1: none)
     bool use_block;                 // on the last convolution: the plan runs the bottleneck as one launch (heuristic or sol_network_autotune)
+    bool pre_bn, pre_set;           // CONV: BN + ReLU on the input side; its folded constants have been set
+    size_t pre_scale_off, pre_shift_off;
+    int ldx;                        // CONV: input pixel pitch when the input is a channel prefix of a dense-block buffer (0: dense)
+    int chain_owner;                // CONCAT: last CONCAT of the dense chain whose buffer this layer is a prefix of (-1: none; itself for the last)
+    bool part_inplace[2];           // CONCAT: src / res part already sits in the output buffer when the layer runs
     int fused_into;                 // index of the layer whose launch produces this layer's output (itself unless elided)
     bool no_buffer;                 // elided, and nobody allocates an output for it either
     size_t w_off, scale_off, shift_off;
@@ -363,6 +388,7 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
         lp.concat_into = -1;
         lp.pair = -1;
         lp.block_c1 = lp.block_c2 = lp.block_c3 = -1;
+        lp.chain_owner = -1;
         lp.fused_into = i;
         lp.in = lp.src < 0 ? net->input : net->layers[lp.src].out;
         lp.out = lp.in;
@@ -371,6 +397,8 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             case SOL_LAYER_CONV: {
                 lp.cd = L.conv;
                 lp.cd.cin = lp.in.c;
+                lp.pre_bn = L.pre_bn != 0;
+                SOL_REQUIRE(!(lp.pre_bn && net->training), SOL_ERR_UNSUPPORTED, "layer %d: input-side batch-norm is inference-only", i);
                 if (lp.src >= 0 && net->layers[lp.src].cout_real) lp.cin_real = net->layers[lp.src].cout_real;
                 if (pad_to[i]) { lp.cout_real = lp.cd.cout; lp.cd.cout = pad_to[i]; }
                 SOL_TRY(check_conv(&lp.cd));
@@ -470,6 +498,10 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             lp.w_off = poff; poff += round_up(sol_packed_weight_bytes(&lp.cd, (sol_dtype)dt), 256);
             lp.scale_off = poff; poff += round_up((size_t)lp.cd.cout * 4, 256);
             lp.shift_off = poff; poff += round_up((size_t)lp.cd.cout * 4, 256);
+            if (lp.pre_bn) {        // room for the channel count rounded up to one reduction chunk (a prefix of a dense-block buffer)
+                lp.pre_scale_off = poff; poff += round_up((size_t)(lp.cd.cin + 64) * 4, 256);
+                lp.pre_shift_off = poff; poff += round_up((size_t)(lp.cd.cin + 64) * 4, 256);
+            }
             if (net->training) {
                 const size_t wb = round_up((size_t)lp.cd.cout * lp.cd.cin * lp.cd.kh * lp.cd.kw * 4, 256);
                 lp.master_off = poff; poff += wb;
@@ -496,6 +528,49 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
     }
     net->param_bytes = poff;
 
+    // Dense chains.  A CONCAT whose src is the CONCAT in front of it extends that tensor by new channels (the dense
+    // blocks of a DenseNet-shaped list).  When every intermediate join is read only by unpadded 1x1 convolutions and by
+    // its extension, the whole chain shares ONE buffer of the final width: producers write their slices into it, the
+    // 1x1 convolutions read a channel prefix of it (pixel pitch = final width, reduction rounded up to whole chunks with
+    // the extra channels masked to zero), and nothing is ever copied but the block input.
+    if (!net->training && !net->keep) {
+        const int chunk = dt == SOL_BF16 ? 64 : 32;
+        std::vector<int> ext(n_layers, -1), is_ext(n_layers, 0);
+        for (int j = 0; j < n_layers; j++) {
+            if (net->layers[j].L.kind != SOL_LAYER_CONCAT) continue;
+            int e = -1;
+            bool ok = true;
+            for (int t = j + 1; t < n_layers; t++) {
+                const LayerPlan &r = net->layers[t];
+                if (r.src != j && r.res != j) continue;
+                if (r.L.kind == SOL_LAYER_CONCAT && r.src == j && r.res != j && e < 0) e = t;
+                else if (r.L.kind == SOL_LAYER_CONV && r.src == j && r.res != j && r.cd.kh == 1 && r.cd.kw == 1 && r.cd.ph == 0 && r.cd.pw == 0) {}
+                else ok = false;
+            }
+            if (ok && e >= 0) { ext[j] = e; is_ext[e] = 1; }
+        }
+        for (int j = 0; j < n_layers; j++) {
+            if (ext[j] < 0 || is_ext[j]) continue;                       // heads only
+            std::vector<int> mem;
+            for (int k = j; k >= 0; k = ext[k]) mem.push_back(k);
+            const int last = mem.back(), ctot = net->layers[last].out.c;
+            bool ok = last + 1 < n_layers && ctot % 8 == 0 && (ctot * dtype_size(dt)) % 16 == 0;
+            for (int k : mem) ok = ok && net->layers[k].out.c % 8 == 0 && net->layers[k].in.c % 8 == 0;
+            if (!ok) continue;
+            for (int k : mem) {
+                net->layers[k].chain_owner = last;
+                if (k == last) continue;
+                for (int t = k + 1; t < n_layers; t++) {                  // its readers fetch a prefix of the shared buffer
+                    LayerPlan &r = net->layers[t];
+                    if (r.L.kind != SOL_LAYER_CONV || r.src != k) continue;
+                    r.ldx = ctot;
+                    const int cpad = std::min((int)round_up((size_t)r.cd.cin, chunk), ctot);
+                    if (cpad != r.cd.cin) { r.cin_real = r.cd.cin; r.cd.cin = cpad; }
+                }
+            }
+        }
+    }
+
     // Depth-first pair (the paper's layer-chain fusion, Sec. III-A / IV): a stem convolution whose output feeds
     // nothing but the max-pool layer behind it runs in one kernel with that pool; the convolution's output, the
     // largest tensor of the list, never exists.  Not when every activation is kept for the caller or for training.
@@ -516,13 +591,13 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
     if (!net->training && !net->keep && dt == SOL_BF16)
         for (int i = 0; i < n_layers; i++) {
             LayerPlan &c = net->layers[i];
-            if (c.L.kind != SOL_LAYER_CONV || c.res < 0 || c.L.pool.kind != SOL_POOL_NONE || c.cout_real || c.cin_real) continue;
+            if (c.L.kind != SOL_LAYER_CONV || c.res < 0 || c.L.pool.kind != SOL_POOL_NONE || c.cout_real || c.cin_real || c.pre_bn || c.ldx) continue;
             LayerPlan &p = net->layers[c.res];
             const auto pointwise = [](const LayerPlan &l) {      // unpadded 1x1 over a multiple of 64 channels
                 return l.cd.kh == 1 && l.cd.kw == 1 && l.cd.ph == 0 && l.cd.pw == 0 && l.cd.cin % 64 == 0 && l.cd.sh == l.cd.sw;
             };
             if (p.L.kind == SOL_LAYER_CONV && p.L.act == SOL_ACT_NONE && p.res < 0 && p.L.pool.kind == SOL_POOL_NONE && p.nuse == 1 &&
-                !p.elided && !p.absorbs_next && !p.cout_real && !p.cin_real && pointwise(p) && pointwise(c) && c.cd.sh == 1 &&
+                !p.elided && !p.absorbs_next && !p.cout_real && !p.cin_real && !p.pre_bn && !p.ldx && pointwise(p) && pointwise(c) && c.cd.sh == 1 &&
                 c.cd.cout % 8 == 0 && c.src != c.res && tensor_bytes(p.in) < (1u << 31) && tensor_bytes(c.in) < (1u << 31)) {
                 c.pair = c.res;
                 p.elided = true;
@@ -540,15 +615,20 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
         for (int i = 0; i < n_layers; i++) {
             LayerPlan &cc = net->layers[i];
             if (cc.L.kind != SOL_LAYER_CONCAT || cc.out.c % 8 != 0) continue;
-            int off = 0;
+            const int owner = cc.chain_owner >= 0 ? cc.chain_owner : i;       // the layer whose buffer the parts are written into
+            int off = 0, k = 0;
             for (int part : {cc.src, cc.res}) {
                 LayerPlan &p = net->layers[part];
-                if (p.L.kind == SOL_LAYER_CONV && p.L.pool.kind == SOL_POOL_NONE && !p.absorbs_next && !p.elided && p.pair < 0 &&
-                    p.nuse == 1 && p.out.c % 8 == 0 && off % 8 == 0) {
-                    p.concat_into = i;
+                if (k == 0 && p.L.kind == SOL_LAYER_CONCAT && p.chain_owner >= 0 && p.chain_owner == cc.chain_owner) {
+                    cc.part_inplace[0] = true;                              // the chain's prefix: already there
+                } else if (p.L.kind == SOL_LAYER_CONV && p.L.pool.kind == SOL_POOL_NONE && !p.absorbs_next && !p.elided && p.pair < 0 &&
+                           p.nuse == 1 && p.out.c % 8 == 0 && off % 8 == 0) {
+                    p.concat_into = owner;
                     p.concat_off = off;
+                    cc.part_inplace[k] = true;
                 }
                 off += p.out.c;
+                k++;
             }
         }
 
@@ -560,7 +640,7 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
         for (int i = 0; i < n_layers; i++) {
             LayerPlan &c3 = net->layers[i];
             const auto plain = [](const LayerPlan &l) {
-                return l.L.kind == SOL_LAYER_CONV && l.L.pool.kind == SOL_POOL_NONE && l.L.act == SOL_ACT_RELU && !l.cout_real && !l.cin_real &&
+                return l.L.kind == SOL_LAYER_CONV && l.L.pool.kind == SOL_POOL_NONE && l.L.act == SOL_ACT_RELU && !l.cout_real && !l.cin_real && !l.pre_bn && !l.ldx &&
                        l.concat_into < 0 && l.pair < 0 && !l.elided && !l.absorbs_next && l.cd.sh == 1 && l.cd.sw == 1;
             };
             const auto pointwise = [](const LayerPlan &l) { return l.cd.kh == 1 && l.cd.kw == 1 && l.cd.ph == 0 && l.cd.pw == 0; };
@@ -582,7 +662,11 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
     for (int i = 0; i < n_layers; i++) {
         LayerPlan &lp = net->layers[i];
         if (lp.split_pool) lp.tmp_off = ar.alloc(tensor_bytes(lp.conv_out));
-        if (lp.absorbs_next) {          // writes the pool layer's output: that buffer has to exist while this layer runs
+        if (lp.chain_owner >= 0) {       // a join of a dense chain: a prefix of the chain's one buffer, laid out at the first touch
+            LayerPlan &ow = net->layers[lp.chain_owner];
+            if (!ow.prealloc) { ow.out_off = ar.alloc(tensor_bytes(ow.out)); ow.prealloc = true; }
+            lp.out_off = ow.out_off;
+        } else if (lp.absorbs_next) {   // writes the pool layer's output: that buffer has to exist while this layer runs
             if (i + 2 < n_layers) net->layers[i + 1].out_off = ar.alloc(tensor_bytes(net->layers[i + 1].out));
         } else if (lp.concat_into >= 0) {   // ... and so does the concatenation's, from its first in-place producer on
             LayerPlan &cc = net->layers[lp.concat_into];
@@ -594,7 +678,9 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
         if (!net->keep)
             for (int j = 0; j < i; j++) {
                 const LayerPlan &lj = net->layers[j];
-                if (lj.last_use == i && j + 1 < n_layers && !lj.absorbs_next && lj.concat_into < 0 && !lj.no_buffer) ar.release(lj.out_off);
+                if (lj.last_use == i && j + 1 < n_layers && !lj.absorbs_next && lj.concat_into < 0 && !lj.no_buffer &&
+                    !(lj.chain_owner >= 0 && lj.chain_owner != j))
+                    ar.release(lj.out_off);
             }
     }
     if (net->training) SOL_TRY(plan_training(net, ar));
@@ -653,6 +739,17 @@ sol_status sol_conv2d_fused(const sol_tensor_desc *xd, const void *x, const sol_
     SOL_TRY(check_conv(cd));
     return conv_fused_impl(*xd, x, *cd, w_packed, scale, shift, residual, act, pool, y, pool_argmax, prepool,
                            g_tile_override, (hipStream_t)stream);
+}
+
+sol_status sol_conv2d_preact_fused(const sol_tensor_desc *xd, const void *x, int ldx, const float *pre_scale, const float *pre_shift,
+                                   const sol_conv_desc *cd, const void *w_packed, const float *scale, const float *shift,
+                                   const void *residual, int act, const sol_pool_desc *pool, void *y, void *stream) {
+    SOL_TRY(check_tensor(xd, "x"));
+    SOL_TRY(check_conv(cd));
+    SOL_REQUIRE(ldx >= 0, SOL_ERR_SHAPE, "negative input pitch");
+    const InputSide ins{pre_scale, pre_shift, ldx, 0};
+    return conv_fused_impl(*xd, x, *cd, w_packed, scale, shift, residual, act, pool, y, nullptr, nullptr, g_tile_override,
+                           (hipStream_t)stream, 0, nullptr, &ins);
 }
 
 sol_status sol_bottleneck_fused(const sol_tensor_desc *xd, const void *x, int mid, const void *w1_packed, const float *scale1,
@@ -762,7 +859,7 @@ sol_status sol_network_bind_params(sol_network *net, void *param_buf, size_t byt
     SOL_REQUIRE(aligned16(param_buf), SOL_ERR_ALIGN, "parameter buffer must be 16-byte aligned");
     net->params = static_cast<unsigned char *>(param_buf);
     net->params_size = bytes;
-    for (auto &lp : net->layers) lp.params_set = false;
+    for (auto &lp : net->layers) lp.params_set = lp.pre_set = false;
     return SOL_OK;
 }
 
@@ -808,6 +905,27 @@ sol_status sol_network_set_params(sol_network *net, int layer, const float *w, c
     SOL_TRY(launch_fold(lp.cout_real ? lp.cout_real : lp.cd.cout, gamma, beta, mean, var, bias, eps,
                         reinterpret_cast<float *>(net->params + lp.scale_off), reinterpret_cast<float *>(net->params + lp.shift_off), st));
     lp.params_set = true;
+    return SOL_OK;
+}
+
+sol_status sol_network_set_pre_bn(sol_network *net, int layer, const float *gamma, const float *beta, const float *mean, const float *var,
+                                  float eps, void *stream) {
+    SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    LayerPlan &lp = net->layers[layer];
+    SOL_REQUIRE(lp.L.kind == SOL_LAYER_CONV && lp.pre_bn, SOL_ERR_SHAPE, "layer %d has no input-side batch-norm", layer);
+    SOL_REQUIRE(net->params, SOL_ERR_WORKSPACE, "no parameter buffer bound (sol_network_bind_params)");
+    SOL_REQUIRE(gamma && beta && mean && var, SOL_ERR_NULL, "gamma, beta, mean, var required");
+    SOL_REQUIRE(aligned16(gamma) && aligned16(beta) && aligned16(mean) && aligned16(var), SOL_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    const int creal = lp.cin_real ? lp.cin_real : lp.cd.cin;
+    float *ps = reinterpret_cast<float *>(net->params + lp.pre_scale_off), *ph = reinterpret_cast<float *>(net->params + lp.pre_shift_off);
+    if (creal != lp.cd.cin) {      // channels beyond the real ones (reduction rounded up to whole chunks): constants 0, masked in the kernel anyway
+        SOL_HIP(hipMemsetAsync(ps, 0, (size_t)lp.cd.cin * 4, st));
+        SOL_HIP(hipMemsetAsync(ph, 0, (size_t)lp.cd.cin * 4, st));
+    }
+    SOL_TRY(launch_fold(creal, gamma, beta, mean, var, nullptr, eps, ps, ph, st));
+    lp.pre_set = true;
     return SOL_OK;
 }
 
@@ -1025,7 +1143,7 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
     for (int i = first; i <= last; i++) {
         const LayerPlan &lp = net->layers[i];
         if (lp.L.kind == SOL_LAYER_CONV || lp.L.kind == SOL_LAYER_LINEAR || lp.L.kind == SOL_LAYER_DWCONV)
-            SOL_REQUIRE(lp.params_set, SOL_ERR_WORKSPACE, "layer %d: parameters not set", i);
+            SOL_REQUIRE(lp.params_set && (!lp.pre_bn || lp.pre_set), SOL_ERR_WORKSPACE, "layer %d: parameters not set", i);
     }
     unsigned char *ws = static_cast<unsigned char *>(workspace);
     if (net->training) {
@@ -1037,7 +1155,7 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
         if (lp.elided) continue;                            // computed by the convolution in front of it
         if (lp.block_c3 >= 0 && net->layers[lp.block_c3].use_block && !g_tile_override) continue;   // ... by the bottleneck launch behind it
         const void *in = layer_in(net, lp.src, x, ws);
-        const int oi = lp.absorbs_next ? i + 1 : lp.concat_into >= 0 ? lp.concat_into : i;   // the layer whose buffer this launch writes
+        const int oi = lp.absorbs_next ? i + 1 : lp.concat_into >= 0 ? lp.concat_into : lp.chain_owner >= 0 ? lp.chain_owner : i;   // the layer whose buffer this launch writes
         void *out = oi + 1 == nl ? y : static_cast<void *>(ws + net->layers[oi].out_off);
         const size_t es = dtype_size(lp.in.dtype);
         int ldy = 0;
@@ -1071,6 +1189,17 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
                                             nullptr, nullptr, T_AUTO, st, ldy, &po));
                     break;
                 }
+                if (lp.pre_bn || lp.ldx) {   // BN + ReLU on the input side and / or a channel prefix of a dense-block buffer
+                    sol_tensor_desc xin = lp.in;
+                    xin.c = lp.cd.cin;
+                    const InputSide ins{lp.pre_bn ? reinterpret_cast<const float *>(net->params + lp.pre_scale_off) : nullptr,
+                                        lp.pre_bn ? reinterpret_cast<const float *>(net->params + lp.pre_shift_off) : nullptr, lp.ldx,
+                                        lp.ldx ? lp.cin_real : 0};
+                    SOL_TRY(conv_fused_impl(xin, in, lp.cd, net->params + lp.w_off, scale, shift, res, lp.L.act, fused, conv_dst, nullptr,
+                                            nullptr, g_tile_override ? g_tile_override : lp.tile, st, ldy, nullptr, &ins));
+                    if (lp.split_pool) SOL_TRY(pool_impl(lp.conv_out, conv_dst, lp.L.pool, out, nullptr, st));
+                    break;
+                }
                 SOL_TRY(conv_fused_impl(lp.in, in, lp.cd, net->params + lp.w_off, scale, shift, res, lp.L.act,
                                         fused, conv_dst, nullptr, nullptr,
                                         g_tile_override ? g_tile_override : lp.tile, st, ldy));
@@ -1095,13 +1224,14 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
                 if (lp.in.n > 0) SOL_TRY(launch_gap(in, out, lp.in.n, lp.in.h * lp.in.w, lp.in.c, lp.in.dtype, st));
                 break;
             case SOL_LAYER_CONCAT: {    // only the parts their producers did not write in place
-                int off = 0;
+                int off = 0, k = 0;
                 for (int part : {lp.src, lp.res}) {
                     const LayerPlan &p = net->layers[part];
-                    if (p.concat_into != i)
+                    if (!lp.part_inplace[k])
                         SOL_TRY(launch_concat_copy(layer_in(net, part, x, ws), out, (long)lp.out.n * lp.out.h * lp.out.w, p.out.c,
-                                                   lp.out.c, off, lp.out.dtype, st));
+                                                   net->layers[oi].out.c, off, lp.out.dtype, st));
                     off += p.out.c;
+                    k++;
                 }
                 break;
             }
@@ -1153,6 +1283,7 @@ sol_status sol_network_forward_static(sol_network *net, const void *x, void *y, 
 // ---- plan-time micro auto-tune ------------------------------------------------------------------------------
 // Every kernel / tile id a convolution layer may be launched with (the launchers reject what does not fit a layer).
 static const int kTuneCandidates[] = {
+    T_256x128, T_128x128, T_128x64, T_256x64, T_64x64, T_128x32, T_128x256, T_64x128,
     D_128x128_64x4, D_128x128_64x3, D_256x128_64x3, D_128x64_64x4, D_64x64_64x4, D_128x256_64x3, D_256x64_64x3, D_64x128_64x4,
     D_128x128_128x2, D_128x128_128x3, D_128x64_128x3, D_64x64_128x3, D_128x128_64x5, D_64x64_128x4, D_256x128_128x3,
     D_256x128_64x4, D_128x256_64x4, D_64x64_64x8,
@@ -1389,7 +1520,7 @@ sol_status sol_network_concat_in_place(const sol_network *net, int layer, int *p
     SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
     const LayerPlan &lp = net->layers[layer];
     SOL_REQUIRE(lp.L.kind == SOL_LAYER_CONCAT, SOL_ERR_SHAPE, "layer %d is not a concatenation", layer);
-    *parts = (net->layers[lp.src].concat_into == layer) + (net->layers[lp.res].concat_into == layer);
+    *parts = (int)lp.part_inplace[0] + (int)lp.part_inplace[1];
     return SOL_OK;
 }
 

@@ -104,6 +104,10 @@ struct ConvArgs {
     int Kp;                  // padded reduction length of a packed weight row
     int Ktot;                // R*S*C
     int act, pool;           // pool: 0 none, 1 max 2x2/2, 2 avg 2x2/2 (in the epilogue of any kernel), 3 max 3x3/2 pad 1 (stem-pool kernel only)
+    const float *pre_scale, *pre_shift;   // not NULL: relu(pre_scale[c] * x + pre_shift[c]) is applied to every in-range input element before
+                             // the contraction (BN + ReLU on the input side; taps in the padding stay 0); conv_igemm kernel only
+    int ldx;                 // elements between consecutive input pixels in x: C, or more when x is a channel prefix of a wider tensor
+    int Cvalid;              // input channels >= Cvalid read as 0 whatever the memory holds (C rounded up over a channel prefix); C when unused
     int ntc;                 // number of channel tiles (set by the launcher)
     int ntiles;
     int cpx;                 // > 0: each XCD owns cpx channel tiles (all pixel tiles); 0: a contiguous run of tiles

@@ -38,6 +38,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
     constexpr int XG = VEC ? 1 : BP / RG;
     static_assert(BP % RPP == 0 && BC % RPP == 0 && BP % (WP * 32) == 0 && BC % (WC * 32) == 0, "tile");
     static_assert(NT % BK == 0 && BP % RG == 0, "gather tile");
+    static_assert(XA <= 32 && XG <= 32, "one validity bit per staged row");
 
     __shared__ __align__(16) unsigned char lds[2 * (BP + BC) * 128];
     __shared__ int row_base[BP], row_ih0[BP], row_iw0[BP];
@@ -64,7 +65,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
             decode_pixel(a, m, n, op, oq);
             ih0 = op * a.sh - a.ph;
             iw0 = oq * a.sw - a.pw;
-            base = ((n * a.H + ih0) * a.W + iw0) * a.C;
+            base = ((n * a.H + ih0) * a.W + iw0) * a.ldx;
         }
         row_base[r] = base; row_ih0[r] = ih0; row_iw0[r] = iw0;
     }
@@ -90,17 +91,35 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
 
     uint4 ra[XA], rwt[XB];
     T rg[XG];
+    // input-side BN + ReLU: the per-channel constants of the chunk being fetched, and which of its rows are real data
+    const bool pre = a.pre_scale != nullptr;
+    const bool partial = a.Cvalid < a.C;                  // channels >= Cvalid are whatever memory holds: they must read as 0
+    float psc[EPC], psh[EPC];
+    unsigned okm = 0, cfirst = 0;                        // VEC: bit i = row i of ra[] is in range; first channel of this lane's 16 bytes
+    float gsc = 0.f, gsh = 0.f;                          // gather path: constants of this lane's reduction element
+    bool gvalid = true;
     const int cpt = VEC ? a.C / BK : 1;         // chunks per filter tap
     const int nk = VEC ? a.R * a.S * cpt : a.Kp / BK;
     int tr = 0, ts = 0, tcc = 0;                // tap row / tap column / chunk inside tap of the NEXT load
 
     auto load_tiles = [&](int kc) {
         if (VEC) {
-            const int tapoff = (tr * a.W + ts) * a.C + tcc * BK;
+            const int tapoff = (tr * a.W + ts) * a.ldx + tcc * BK;
+            okm = 0;
 #pragma unroll
             for (int i = 0; i < XA; i++) {
                 const bool ok = (unsigned)(rh[i] + tr) < (unsigned)a.H && (unsigned)(rw[i] + ts) < (unsigned)a.W;
                 ra[i] = ok ? *reinterpret_cast<const uint4 *>(xg + (rb[i] + tapoff)) : make_uint4(0, 0, 0, 0);
+                okm |= ok ? 1u << i : 0u;
+            }
+            cfirst = (unsigned)(tcc * BK + lchunk * EPC);
+            if (pre) {
+#pragma unroll
+                for (int e = 0; e < EPC; e += 4) {
+                    const float4 s4 = *reinterpret_cast<const float4 *>(a.pre_scale + cfirst + e), h4 = *reinterpret_cast<const float4 *>(a.pre_shift + cfirst + e);
+                    psc[e] = s4.x; psc[e + 1] = s4.y; psc[e + 2] = s4.z; psc[e + 3] = s4.w;
+                    psh[e] = h4.x; psh[e + 1] = h4.y; psh[e + 2] = h4.z; psh[e + 3] = h4.w;
+                }
             }
             if (++tcc == cpt) { tcc = 0; if (++ts == a.S) { ts = 0; ++tr; } }
         } else {
@@ -108,13 +127,17 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
             const int c = k % a.C, tap = k / a.C;
             const int s = tap % a.S, r = tap / a.S;
             const bool kok = k < a.Ktot;
-            const int tapoff = (r * a.W + s) * a.C + c;
+            const int tapoff = (r * a.W + s) * a.ldx + c;
+            gvalid = c < a.Cvalid;
+            okm = 0;
+            if (pre) { gsc = kok ? a.pre_scale[c] : 0.f; gsh = kok ? a.pre_shift[c] : 0.f; }
 #pragma unroll
             for (int i = 0; i < XG; i++) {
                 const int row = grow + i * RG;
                 const bool ok = kok && (unsigned)(row_ih0[row] + r) < (unsigned)a.H &&
                                 (unsigned)(row_iw0[row] + s) < (unsigned)a.W;
                 rg[i] = ok ? xg[row_base[row] + tapoff] : (T)0;
+                okm |= ok ? 1u << i : 0u;
             }
         }
 #pragma unroll
@@ -128,14 +151,33 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
 #pragma unroll
             for (int i = 0; i < XA; i++) {
                 const int row = lrow + i * RPP;
-                *reinterpret_cast<uint4 *>(lx + row * 128 + ((lchunk ^ ((row >> 1) & 7)) << 4)) = ra[i];
+                uint4 v = ra[i];
+                if (pre || partial) {                     // wave-uniform
+                    T *el = reinterpret_cast<T *>(&v);
+                    const bool ok = (okm >> i) & 1u;
+#pragma unroll
+                    for (int e = 0; e < EPC; e++) {
+                        float f = Elem<T>::load(el + e);
+                        if (pre) { f = f * psc[e] + psh[e]; f = f > 0.f ? f : 0.f; }
+                        f = (ok && (int)(cfirst + e) < a.Cvalid) ? f : 0.f;       // padding taps and padding channels are zeros, not relu(shift)
+                        Elem<T>::store(el + e, f);
+                    }
+                }
+                *reinterpret_cast<uint4 *>(lx + row * 128 + ((lchunk ^ ((row >> 1) & 7)) << 4)) = v;
             }
         } else {
             const int gchunk = gk / EPC, gin = (gk % EPC) * (int)sizeof(T);
 #pragma unroll
             for (int i = 0; i < XG; i++) {
                 const int row = grow + i * RG;
-                *reinterpret_cast<T *>(lx + row * 128 + ((gchunk ^ ((row >> 1) & 7)) << 4) + gin) = rg[i];
+                T v = rg[i];
+                if (pre || partial) {
+                    float f = Elem<T>::load(&v);
+                    if (pre) { f = f * gsc + gsh; f = f > 0.f ? f : 0.f; }
+                    f = (((okm >> i) & 1u) && gvalid) ? f : 0.f;
+                    Elem<T>::store(&v, f);
+                }
+                *reinterpret_cast<T *>(lx + row * 128 + ((gchunk ^ ((row >> 1) & 7)) << 4) + gin) = v;
             }
         }
 #pragma unroll
@@ -248,8 +290,23 @@ template <typename T> static sol_status launch_typed(const ConvArgs &a, int tile
     }
 }
 
+// Input-side BN + ReLU, a strided input (channel prefix of a wider tensor) or masked padding channels: the
+// register-staged kernel is the one that can transform what it fetches on its way to LDS.
+static sol_status launch_conv_staged(const ConvArgs &a, int dt, int tile, hipStream_t st) {
+    if (!(tile >= T_256x128 && tile <= T_64x128)) {
+        SOL_REQUIRE(tile == T_AUTO || tile == T_NO_HALO, SOL_ERR_UNSUPPORTED,
+                    "conv tile %d cannot apply an input-side BN + ReLU or read a channel prefix; the register-staged tiles 1..8 can", tile);
+        const long np128 = ceil_div(a.P, 128);
+        tile = a.Cout <= 32 ? T_128x32 : a.Cout <= 64 ? T_128x64 : (a.Cout % 256 == 0 && np128 * (a.Cout / 256) >= 512) ? T_128x256 : T_128x128;
+    }
+    if (dt == SOL_BF16) return launch_typed<bf16_t>(a, tile, st);
+    if (dt == SOL_F32) return launch_typed<float>(a, tile, st);
+    SOL_FAIL(SOL_ERR_DTYPE, "unknown dtype %d", dt);
+}
+
 sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t st) {
     if (a.P <= 0) return SOL_OK;   // empty batch: nothing to do
+    if (a.pre_scale || a.ldx != a.C || a.Cvalid != a.C) return launch_conv_staged(a, dt, tile_override, st);
     if (tile_override == T_AUTO && stem_kernel_applies(a, dt)) return launch_conv_stem(a, st);
     if (tile_override == T_AUTO && linear_kernel_applies(a, dt)) {
         // few rows, but a weight matrix of many megabytes (the MLP workload): the job is streaming the weights, which the

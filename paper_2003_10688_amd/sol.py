@@ -40,7 +40,7 @@ class ConvDesc(C.Structure):
 
 class Layer(C.Structure):
     _fields_ = [("kind", C.c_int), ("conv", ConvDesc), ("has_bn", C.c_int), ("act", C.c_int),
-                ("pool", PoolDesc), ("out_features", C.c_int), ("src", C.c_int), ("res", C.c_int)]
+                ("pool", PoolDesc), ("out_features", C.c_int), ("src", C.c_int), ("res", C.c_int), ("pre_bn", C.c_int)]
 
 
 class SolError(RuntimeError):
@@ -192,6 +192,24 @@ def sol_conv2d_fused(x, cd, w_packed, scale=None, shift=None, residual=None, act
     return y, arg, pre
 
 
+def sol_conv2d_preact_fused(x, cd, w_packed, pre_scale=None, pre_shift=None, scale=None, shift=None, residual=None, act=ACT_NONE,
+                            pool=None, channels=None, stream=None):
+    """x: NHWC device tensor; channels: read only the first `channels` channels of every pixel of x (a channel prefix of
+    a wider tensor; default: all).  Returns y."""
+    n, h, w, ctot = x.shape
+    c = channels or ctot
+    ho, wo = sol_out_size(h, cd.kh, cd.sh, cd.ph), sol_out_size(w, cd.kw, cd.sw, cd.pw)
+    pd = pool if isinstance(pool, PoolDesc) or pool is None else pool_desc(pool)
+    if pd is not None and pd.kind != POOL_NONE:
+        ho, wo = sol_out_size(ho, pd.kh, pd.sh, pd.ph), sol_out_size(wo, pd.kw, pd.sw, pd.pw)
+    y = torch.empty((n, max(ho, 0), max(wo, 0), cd.cout), dtype=x.dtype, device=x.device)
+    xd = TensorDesc(n, h, w, c, dtype_of(x))
+    _check(lib().sol_conv2d_preact_fused(C.byref(xd), _ptr(x), C.c_int(ctot if c != ctot else 0), _ptr(pre_scale), _ptr(pre_shift),
+                                         C.byref(cd), _ptr(w_packed), _ptr(scale), _ptr(shift), _ptr(residual), C.c_int(act),
+                                         C.byref(pd) if pd is not None else None, _ptr(y), _stream(stream)))
+    return y
+
+
 def sol_bottleneck_fused(x, mid, w1, s1, h1, w2, s2, h2, w3, s3, h3, stream=None):
     """x: NHWC bf16 device tensor; w*: packed weights; s*/h*: folded scale / shift.  Returns y (same shape as x)."""
     y = torch.empty_like(x)
@@ -276,6 +294,7 @@ def make_layer_array(layers):
             a.kind = LAYER_DWCONV if l.get("dw") else LAYER_CONV
             a.conv = ConvDesc(l["cout"], 0, l["kh"], l["kw"], l["sh"], l["sw"], l["ph"], l["pw"])
             a.has_bn = int(l["bn"])
+            a.pre_bn = int(bool(l.get("pre_bn")))
             if l.get("pool"):
                 a.pool = pool_desc(l["pool"])
         elif l["kind"] == "pool":
@@ -327,6 +346,10 @@ class Network:
             bias = dev_f32(p.get("bias"), self.device)
             _check(lib().sol_network_set_params(self._h, C.c_int(i), _ptr(w), _ptr(g), _ptr(b), _ptr(m), _ptr(v),
                                                 _ptr(bias), C.c_float(p.get("eps", 1e-5)), _stream(stream)))
+            if l["kind"] == "conv" and l.get("pre_bn"):
+                pg, pb, pm, pv = (dev_f32(p[k], self.device) for k in ("pre_gamma", "pre_beta", "pre_mean", "pre_var"))
+                _check(lib().sol_network_set_pre_bn(self._h, C.c_int(i), _ptr(pg), _ptr(pb), _ptr(pm), _ptr(pv),
+                                                    C.c_float(p.get("eps", 1e-5)), _stream(stream)))
         torch.cuda.synchronize()
 
     def forward(self, x, stream=None):

@@ -37,6 +37,7 @@ BASE_SEED = 20031068
 
 # tensor-kind ids used to derive an independent random stream per tensor
 _T_INPUT, _T_W, _T_GAMMA, _T_BETA, _T_MEAN, _T_VAR, _T_LABEL, _T_BIAS = range(8)
+_T_PRE = 8     # added to _T_GAMMA .. _T_VAR for the input-side BN of a pre-activation convolution
 
 
 def _rng(seed: int, layer: int, kind: int) -> np.random.Generator:
@@ -59,12 +60,13 @@ def pool_desc(kind="max", k=2, s=2, p=0, count_pad=1):
             "count_pad": int(count_pad)}
 
 
-def conv(cout, k, s=1, p=None, bn=True, act="relu", pool=None, src=-1, res=-1, dw=False):
-    """dw: depthwise (groups == channels, cout must equal the input channel count; weights [C,1,k,k])."""
+def conv(cout, k, s=1, p=None, bn=True, act="relu", pool=None, src=-1, res=-1, dw=False, pre_bn=False):
+    """dw: depthwise (groups == channels, cout must equal the input channel count; weights [C,1,k,k]).
+    pre_bn: a BN + ReLU of the layer's INPUT runs in front of the convolution (pre-activation order)."""
     if p is None:
         p = (k - 1) // 2
     return {"kind": "conv", "cout": cout, "kh": k, "kw": k, "sh": s, "sw": s, "ph": p, "pw": p,
-            "bn": bool(bn), "act": act, "pool": pool, "src": src, "res": res, "dw": bool(dw)}
+            "bn": bool(bn), "act": act, "pool": pool, "src": src, "res": res, "dw": bool(dw), "pre_bn": bool(pre_bn)}
 
 
 def pool(kind="max", k=2, s=2, p=0, count_pad=1, src=-1):
@@ -148,6 +150,33 @@ def squeezenet_layers(num_classes=1000):
             L.append(pool("max", 3, 2, 0))
     L.append(conv(num_classes, 1, p=0, bn=False))
     L.append(gap())
+    return L
+
+
+def densenet_layers(num_classes=1000, growth=32, blocks=(6, 12, 24, 16), stem=64, bottleneck=4):
+    """Config 8: a DenseNet-121-shaped list (one of the evaluation networks of the paper, Sec. VI).  Stem as in the
+    ResNet-shaped lists; dense blocks of `blocks[i]` layers, each  BN-ReLU-conv1x1 (bottleneck * growth filters) -
+    BN-ReLU-conv3x3 (growth filters)  on the concatenation of the block input and all earlier layers' outputs;
+    transitions  BN-ReLU-conv1x1 (half the channels) - 2x2 average pool;  final BN-ReLU, global average pool, linear.
+    In list form: the first BN-ReLU of a dense layer is the input-side activation of its 1x1 convolution (pre_bn),
+    the second one that convolution's own BN + ReLU; the 3x3 convolution stores its raw output, which the
+    concatenation appends; the final BN-ReLU is a 1x1 depthwise convolution with BN + ReLU."""
+    L = [conv(stem, 7, s=2, p=3), pool("max", 3, 2, 1)]
+    c = stem
+    for bi, n in enumerate(blocks):
+        feat = len(L) - 1                                      # layer holding the concatenated features so far
+        for _ in range(n):
+            L.append(conv(bottleneck * growth, 1, p=0, src=feat, pre_bn=True))
+            L.append(conv(growth, 3, bn=False, act="none"))
+            L.append(concat(feat, len(L) - 1))
+            feat = len(L) - 1
+            c += growth
+        if bi + 1 < len(blocks):
+            c //= 2
+            L.append(conv(c, 1, p=0, bn=False, act="none", pre_bn=True, pool=pool_desc("avg", 2, 2, 0), src=feat))
+    L.append(conv(c, 1, p=0, dw=True))                         # final BN + ReLU
+    L.append(gap())
+    L.append(linear(num_classes))
     return L
 
 
@@ -245,6 +274,12 @@ def make_params(layers, cin, seed, bf16=False, bias_std=0.0):
                 p["mean"] = (_rng(seed, i, _T_MEAN).standard_normal(l["cout"]) * 0.1).astype(np.float32)
                 p["var"] = _rng(seed, i, _T_VAR).uniform(0.5, 1.5, l["cout"]).astype(np.float32)
                 p["eps"] = 1e-5
+            if l.get("pre_bn"):
+                p["pre_gamma"] = _rng(seed, i, _T_PRE + _T_GAMMA).uniform(0.5, 1.5, c_in).astype(np.float32)
+                p["pre_beta"] = _rng(seed, i, _T_PRE + _T_BETA).uniform(-0.1, 0.1, c_in).astype(np.float32)
+                p["pre_mean"] = (_rng(seed, i, _T_PRE + _T_MEAN).standard_normal(c_in) * 0.1).astype(np.float32)
+                p["pre_var"] = _rng(seed, i, _T_PRE + _T_VAR).uniform(0.5, 1.5, c_in).astype(np.float32)
+                p["eps"] = 1e-5
         elif l["kind"] == "linear":
             w = _rng(seed, i, _T_W).standard_normal((l["out"], c_in))
             w = (w * np.sqrt(2.0 / c_in)).astype(np.float32)
@@ -302,7 +337,7 @@ class Workload:
 
 
 def config(idx: int, batch: int | None = None, hw: int | None = None, dtype: str | None = None) -> Workload:
-    """The five configurations of the benchmark plus the paper's MLP workload (5), a depthwise-separable chain (6) and a SqueezeNet-shaped list with channel concatenations (7); ``batch`` / ``hw`` shrink a config for parity tests and ``dtype``
+    """The five configurations of the benchmark plus the paper's MLP workload (5), a depthwise-separable chain (6), a SqueezeNet-shaped list with channel concatenations (7) and a DenseNet-121-shaped list with pre-activation convolutions (8); ``batch`` / ``hw`` shrink a config for parity tests and ``dtype``
     overrides its storage type (same seed, same layer list)."""
     wk = _config(idx, batch, hw)
     if dtype is not None:
@@ -333,4 +368,6 @@ def _config(idx, batch, hw):
         return Workload("separable_bf16", separable_layers(), (batch or 64, 3, hw or 224, hw or 224), "bf16", seed, "normal")
     if idx == 7:
         return Workload("squeezenet_bf16", squeezenet_layers(), (batch or 64, 3, hw or 224, hw or 224), "bf16", seed, "normal")
+    if idx == 8:
+        return Workload("densenet121_bf16", densenet_layers(), (batch or 64, 3, hw or 224, hw or 224), "bf16", seed, "normal")
     raise ValueError(idx)

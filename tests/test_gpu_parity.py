@@ -919,7 +919,7 @@ def _concat_nets():
                             (2, 3, 12, 12), "bf16", [1]),
         "pool_and_conv": ([c(16, 3), pool("max", 2, 2, 0), c(16, 3, s=2, src=0), cat(1, 2), c(8, 1, p=0)], (2, 3, 16, 16), "bf16", [1]),
         "concat_is_output": ([c(16, 3)] + fire(8, 16), (2, 3, 9, 11), "bf16", [2]),
-        "nested": ([c(16, 3)] + fire(8, 16) + [c(32, 1, p=0, src=0), cat(4, 5), c(8, 1, p=0)], (2, 3, 12, 12), "bf16", [2, 1]),
+        "nested": ([c(16, 3)] + fire(8, 16) + [c(32, 1, p=0, src=0), cat(4, 5), c(8, 1, p=0)], (2, 3, 12, 12), "bf16", [2, 2]),   # the second join extends the first: one shared buffer
     }
 
 

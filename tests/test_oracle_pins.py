@@ -373,6 +373,48 @@ def test_bn_points_and_fused_block_points_agree_with_the_full_tensors():
         assert np.allclose(got, t.numpy()[tuple(cs.T)], rtol=tol, atol=tol * 1e-3 if bf else tol)
 
 
+def test_pre_activation_block_and_densenet_shaped_list():
+    """Input-side BN + ReLU of a convolution (pre-activation order): equals the tensor library's composition; the zero
+    padding applies to the ACTIVATED tensor (a positive BN shift must not leak into the border taps); points version
+    agrees; in bf16 mode the activated tensor is a rounding point.  The DenseNet-shaped list is wired like the
+    published network (channel counts per block, 120 convolutions + the final BN-ReLU)."""
+    l = wl.conv(5, 3, pre_bn=True)
+    x = R.standard_normal((2, 4, 7, 6))
+    p = {"w": R.standard_normal((5, 4, 3, 3)), "bias": R.standard_normal(5), "gamma": R.uniform(0.5, 1.5, 5), "beta": R.uniform(-0.1, 0.1, 5),
+         "mean": R.standard_normal(5) * 0.1, "var": R.uniform(0.5, 1.5, 5), "pre_gamma": R.uniform(0.5, 1.5, 4),
+         "pre_beta": R.uniform(0.5, 1.0, 4), "pre_mean": R.standard_normal(4) * 0.1, "pre_var": R.uniform(0.5, 1.5, 4)}
+    y, _, _ = orc.fused_conv(x, p, l)
+    a = F.relu(F.batch_norm(T(x), T(p["pre_mean"]), T(p["pre_var"]), T(p["pre_gamma"]), T(p["pre_beta"]), False, 0.0, 1e-5))
+    t = F.conv2d(a, T(p["w"]), T(p["bias"]), padding=1)
+    t = F.relu(F.batch_norm(t, T(p["mean"]), T(p["var"]), T(p["gamma"]), T(p["beta"]), False, 0.0, 1e-5))
+    assert np.allclose(y, t.numpy(), rtol=1e-12, atol=1e-12)
+    # activating a zero-padded input instead gives relu(pre_beta - ...) > 0 in the border taps: visibly different
+    xp = np.pad(x, ((0, 0), (0, 0), (1, 1), (1, 1)))
+    wrong, _, _ = orc.fused_conv(xp, p, dict(l, ph=0, pw=0))
+    assert wrong.shape == y.shape and not np.allclose(wrong[:, :, 0, :], y[:, :, 0, :], rtol=1e-3, atol=1e-3)
+    assert np.allclose(wrong[:, :, 2:-2, 2:-2], y[:, :, 2:-2, 2:-2], rtol=1e-12, atol=1e-12)          # interior: same
+    # bf16 mode: the activated tensor is rounded, then the output
+    xb = orc.round_bf16(x)
+    yb, _, _ = orc.fused_conv(xb, p, l, bf16=True)
+    ab = orc.round_bf16(a.numpy() if False else F.relu(F.batch_norm(T(xb), T(p["pre_mean"]), T(p["pre_var"]), T(p["pre_gamma"]), T(p["pre_beta"]),
+                                                                False, 0.0, 1e-5)).numpy())
+    tb = F.conv2d(T(ab), T(p["w"]), T(p["bias"]), padding=1)
+    tb = F.relu(F.batch_norm(tb, T(p["mean"]), T(p["var"]), T(p["gamma"]), T(p["beta"]), False, 0.0, 1e-5)).numpy()
+    assert np.allclose(yb, orc.round_bf16(tb), rtol=2.0 ** -7, atol=1e-6) and np.array_equal(yb, orc.round_bf16(yb))
+
+    L = wl.densenet_layers()
+    ch = wl.layer_channels(L, 3)
+    convs = [l for l in L if l["kind"] == "conv" and not l.get("dw")]
+    assert len(convs) == 120 and sum(1 for l in L if l["kind"] == "concat") == 58
+    ends = [ch[i - 1] for i, l in enumerate(L) if l["kind"] == "conv" and l.get("pool")]            # features entering a transition
+    assert ends == [256, 512, 1024] and ch[-3] == 1024 and ch[-1] == 1000
+    wk = wl.config(8, batch=2, hw=32)
+    outs, _ = orc.network_forward(wk.layers, wk.params, wk.x, return_all=True)
+    assert outs[-1].shape == (2, 1000) and outs[1].shape == (2, 64, 8, 8)
+    i = next(i for i, l in enumerate(wk.layers) if l["kind"] == "concat")
+    assert np.array_equal(outs[i][:, :64], outs[1]) and np.array_equal(outs[i][:, 64:], outs[i - 1])   # concat appends the new features
+
+
 def test_network_is_composition_and_batch_permutes():
     from paper_2003_10688_amd import workloads as wl
 
