@@ -246,3 +246,22 @@ def test_depthwise_planning_and_validation(sol):
     assert call(sol.ConvDesc(16, 16, 3, 3, 1, 1, 1, 1), w=null) == 1                  # NULL weights
     assert call(sol.ConvDesc(16, 16, 3, 3, 1, 1, 1, 1), x=C.c_void_p(0x1008)) == 4    # misaligned x
     assert call(sol.ConvDesc(16, 16, 11, 11, 1, 1, 0, 0)) == 2                        # filter larger than the input
+
+
+def test_no_kernel_spills_registers():
+    """The compiler's per-kernel resource report of the last build (written by paper_2003_10688_amd/build.py): no kernel
+    of the library may use scratch memory (spilled registers travel through HBM: the stage-3 3x3 kernels once wrote
+    5.7x their output that way), and none may exceed the 160 KB of LDS of a compute unit."""
+    import json
+
+    from paper_2003_10688_amd import build as b
+
+    path = b.RESOURCES
+    if not os.path.exists(path):
+        pytest.skip("no build report (run __graft_entry__.build())")
+    with open(path) as f:
+        res = json.load(f)
+    assert len(res) > 100
+    spills = {k: v["scratch_bytes_per_lane"] for k, v in res.items() if v.get("scratch_bytes_per_lane", 0) != 0}
+    assert not spills, spills
+    assert all(v.get("lds_bytes", 0) <= 160 * 1024 for v in res.values())
