@@ -39,17 +39,19 @@ struct BlockArgs {
     FastDiv dw, dh;                                  // by W, by H
 };
 
-// WM: mid channels (64 or 128); PRA: patch rows held in LDS (>= bp + 2W + 2, a multiple of 16); NBO: 32-pixel blocks
+// NW: waves per workgroup (8: one workgroup per CU.  A four-wave configuration with 128-pixel tiles and two workgroups
+// per CU -- <4, 64, 256, 4, 2, 4, 2, 2, 1, 3, 4>, 68 KB of LDS -- gives the same results and the same time on the 56x56
+// blocks, 80.9 against 81.2 us: the kernel is bound by the bytes that cross the fabric, not by latency); WM: mid channels (64 or 128); PRA: patch rows held in LDS (>= bp + 2W + 2, a multiple of 16); NBO: 32-pixel blocks
 // of a tile (bp <= 32 NBO); wave grids (pixels x channels, product 8) and 32x32 accumulator blocks per wave for the
 // phases A and B (C follows from WM: passes of 128 channels on 2 x 4 waves for WM = 64, of 64 channels on 4 x 2 waves
 // for WM = 128, one 32-channel block per wave); ring depths of A and B.
-template <int WM, int PRA, int NBO, int WPA, int TPA, int WPB, int TPB, int TCB, int NSA, int NSB>
-__global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
+template <int NW, int WM, int PRA, int NBO, int WPA, int TPA, int WPB, int TPB, int TCB, int NSA, int NSB>
+__global__ void __launch_bounds__(NW * 64, 512 / (NW * 64)) conv_block_kernel(const BlockArgs a) {
 #if defined(__HIP_DEVICE_COMPILE__)
     using namespace lds_pipe;
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
-    constexpr int NW = 8, CH = WM / 64;                               // waves; 64-channel planes of t1 / t2
+    constexpr int CH = WM / 64;                                       // 64-channel planes of t1 / t2
     constexpr int WCA = NW / WPA, TCA = WM / 32 / WCA;
     constexpr int WCB = NW / WPB;
     constexpr int PC = WM == 64 ? 128 : 64;                          // output channels per pass of phase C: PC * WM * 2 = 16 KB of W3
@@ -60,25 +62,26 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
     // LDS map (overlaid: the phases never need everything at once)
     //   phase A:  [ring of NSA slots ...........................................]            (t1 is written after the loop)
     //   phase B:  [t1 planes: rows, zero block          ][ring of NSB weight slots]
-    //   phase C:  [t2 planes                            ][two W3 buffers][epilogue strips]
+    //   phase C:  [t2 planes            ][two W3 buffers][epilogue strips]
     constexpr int PLANE1 = PRA * 128 + 256, PLANE2 = NBO * 32 * 128;
     constexpr int R0 = (CH * PLANE1 > CH * PLANE2 ? CH * PLANE1 : CH * PLANE2);
     constexpr int XROWB = 64;                                         // phase A: bytes of reduction per row and stage
     constexpr int SLOTA = (PRA + WM) * XROWB, SLOTB = WM * 128, PCBUF = PC * WM * 2;
     constexpr int STRIPS = NW * 32 * (32 + 4) * 4;
-    constexpr int R1B = NSB * SLOTB, R1C = 2 * PCBUF + STRIPS;
-    constexpr int LBC = R0 + (R1B > R1C ? R1B : R1C);
+    constexpr int LB_ = R0 + NSB * SLOTB, LC_ = CH * PLANE2 + 2 * PCBUF + STRIPS;
+    constexpr int LBC = LB_ > LC_ ? LB_ : LC_;
     constexpr int LMAIN = NSA * SLOTA > LBC ? NSA * SLOTA : LBC;
     constexpr int LDSB = LMAIN + 1024;
     static_assert(LDSB <= 160 * 1024, "LDS");
     static_assert(R0 % 256 == 0 && PCBUF == 16384, "alignment of the ring area; one pass of W3 is sixteen 1 KB DMA segments");
+    static_assert(NW == 8 || NW == 4, "one or two workgroups per CU");
     // DMA instructions per wave and stage
     constexpr int NXI = PRA / 16, XLA = (NXI + NW - 1) / NW, NWIA = WM / 16, WLA = (NWIA + NW - 1) / NW, LA = XLA + WLA;
     constexpr int LB = WM / 8 / NW, LC = PCBUF / 1024 / NW;
     static_assert(LB >= 1 && LC >= 1 && (NSA - 1) * LA < 64 && (NSB - 1) * LB < 64, "vmcnt");
 
     __shared__ __align__(1024) unsigned char lds[LDSB];
-    unsigned char *const t1 = lds, *const ringA = lds, *const ring = lds + R0, *const dump = lds + LMAIN;
+    unsigned char *const t1 = lds, *const ringA = lds, *const ring = lds + R0, *const ringC = lds + CH * PLANE2, *const dump = lds + LMAIN;
 
     asm volatile("" ::"s"(a.x), "s"(a.y), "s"(a.w1), "s"(a.w2), "s"(a.w3), "s"(a.s1), "s"(a.h1), "s"(a.s2), "s"(a.h2), "s"(a.s3),
                  "s"(a.h3), "s"(a.P), "s"(a.H), "s"(a.W), "s"(a.C4), "s"(a.bp), "s"(a.ntiles), "s"(a.dw.mul), "s"(a.dh.mul));
@@ -170,7 +173,7 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
         static_for<LC>([&](auto I) {
             constexpr int i = decltype(I)::value;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w3r : nullr,
-                                                     (__attribute__((address_space(3))) void *)(ring + buf * PCBUF + (wave * LC + i) * 1024), 16,
+                                                     (__attribute__((address_space(3))) void *)(ringC + buf * PCBUF + (wave * LC + i) * 1024), 16,
                                                      woC[i], soff, 0, 0);
         });
     };
@@ -388,7 +391,7 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
     // fetched while the current pass is contracted.  Right before its epilogue a wave waits until only the shortcut
     // loads of the NEXT pass may be outstanding: its share of the next W3 rows and its own shortcut rows are then
     // here, and the barrier behind the epilogue publishes the W3 rows.  No wait ever has to count the epilogue's stores.
-    float *const strips = reinterpret_cast<float *>(ring + 2 * PCBUF);
+    float *const strips = reinterpret_cast<float *>(ringC + 2 * PCBUF);
     ConvArgs ca;                                          // what the shared epilogue reads
     ca.y = a.y; ca.res = a.x; ca.scale = a.s3; ca.shift = a.h3; ca.prepool = nullptr; ca.argmax = nullptr;
     ca.Cout = C4; ca.ldy = C4; ca.P = pend; ca.act = SOL_ACT_RELU; ca.pool = 0;
@@ -396,7 +399,7 @@ __global__ void __launch_bounds__(512) conv_block_kernel(const BlockArgs a) {
     __builtin_amdgcn_s_barrier();                         // ... everyone's, and t2 is complete
     {
         f32x16_t acc[1][TPC];
-        const unsigned fw0 = lds_addr(ring) + (unsigned)((wcC * 32 + lr) * 128) + ((lh ^ (unsigned)swz<128>(lr)) << 4);
+        const unsigned fw0 = lds_addr(ringC) + (unsigned)((wcC * 32 + lr) * 128) + ((lh ^ (unsigned)swz<128>(lr)) << 4);
         const unsigned fx0 = lds_addr(t1) + (unsigned)((wpC * TPC * 32 + lr) * 128) + ((lh ^ (unsigned)swz<128>(lr)) << 4);
         u32x4_t fa[2], fb[2][TPC];
         auto readC = [&](auto SET, unsigned kx, unsigned sb, unsigned pb) {
@@ -481,11 +484,11 @@ sol_status launch_conv_block(const BlockLaunch &b, hipStream_t st) {
     a.dw = FastDiv((uint32_t)b.W);
     a.dh = FastDiv((uint32_t)b.H);
     const int grid = ((a.ntiles + 7) / 8) * 8;
+    //                                     NW  WM  PRA  NBO WPA TPA WPB TPB TCB NSA NSB
     if (b.WM == 64)
-        //                              WM  PRA  NBO WPA TPA WPB TPB TCB NSA NSB
-        hipLaunchKernelGGL((conv_block_kernel<64, 384, 8, 4, 3, 4, 2, 1, 5, 4>), dim3(grid), dim3(512), 0, st, a);
+        hipLaunchKernelGGL((conv_block_kernel<8, 64, 384, 8, 4, 3, 4, 2, 1, 5, 4>), dim3(grid), dim3(512), 0, st, a);
     else
-        hipLaunchKernelGGL((conv_block_kernel<128, 288, 8, 2, 5, 4, 2, 2, 5, 4>), dim3(grid), dim3(512), 0, st, a);
+        hipLaunchKernelGGL((conv_block_kernel<8, 128, 288, 8, 2, 5, 4, 2, 2, 5, 4>), dim3(grid), dim3(512), 0, st, a);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }
