@@ -126,7 +126,7 @@ def main():
     t0 = time.perf_counter()
     if a.load_plan:
         with open(a.load_plan) as f:
-            tuned = {(k if k.endswith("b") else int(k)): v for k, v in json.load(f).items()}
+            tuned = {(k if k[-1] in "bx" else int(k)): v for k, v in json.load(f).items()}
         net.set_tiles(tuned)
     else:
         tuned = net.autotune(x, reps=a.tune_reps, stream=stream) if a.tune_reps > 0 else {}
@@ -177,11 +177,15 @@ def main():
         e1.record(stream)
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) * 1e3 / a.layer_reps
-        absorbs = i + 1 < len(into) and into[i + 1] == i
+        absorbs = i + 1 < len(into) and into[i + 1] == i and wk.layers[i + 1]["kind"] == "pool"
         fl, by = algorithmic_work(l, ins[i], outs[i], esize)
         numel = lambda t: t[0] * t[1] * t[2] * t[3]  # noqa: E731
         if absorbs:   # a fused stem pair stores only the pooled tensor
             by += esize * (numel(outs[i + 1]) - numel(outs[i]))
+        if i + 1 < len(into) and into[i + 1] == i and wk.layers[i + 1]["kind"] == "conv":   # an expand-reduce pair: the second
+            fj, bj = algorithmic_work(wk.layers[i + 1], ins[i + 1], outs[i + 1], esize)         # convolution's work, minus the read of its input
+            fl += fj
+            by += bj - esize * numel(ins[i + 1])
         for j in range(i):   # layers computed inside this launch (a projection shortcut, the first two convolutions of a
             if into[j] == i:  # bottleneck): their work, minus the write and the re-read of their outputs
                 fj, bj = algorithmic_work(wk.layers[j], ins[j], outs[j], esize)
@@ -262,7 +266,7 @@ def main():
                                             "frac": round(sum(r["flops" if key == "tflops" else "bytes"] for r in rs) / max(sum(r["us_pass"] for r in rs), 1e-9) / scale / peak, 4)}
         traffic_mb = measured_traffic() if a.config == 3 and wk.in_shape[0] == 64 else None
         roofline = {
-            "bound": "mfma", "kernel": "fused convolution kernels (conv_dma / conv_halo / conv_gemm8 / conv_stem_pool / conv_pair / conv_block)", "launches_per_step": len(conv),
+            "bound": "mfma", "kernel": "fused convolution kernels (conv_dma / conv_halo / conv_gemm8 / conv_stem_pool / conv_pair / conv_block / conv_xr)", "launches_per_step": len(conv),
             "achieved": round(tfl, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl / PEAK_BF16_TFLOPS, 4),
             "avg_launch_us": round(conv_us / len(conv), 2), "algorithmic_gflop_per_launch": round(conv_fl / len(conv) / 1e9, 3),
             "timing": f"HIP events around every launch inside {a.pass_reps} whole passes, scaled by {marker_scale:.3f} so that the launches add up to the timed pass (the events between launches cost time the timed passes do not pay)",
@@ -372,7 +376,8 @@ def main():
         "submission": "HIP graph replay" if a.graph else "eager launches", "eager_ms_per_step": round(eager_ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if wk.bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"{wk.name} batch {batch} input {wk.in_shape[1]}x{wk.in_shape[2]}x{wk.in_shape[3]} (seeded synthetic, He-normal weights)",
-                   "launches_per_step": sum(1 for r in rows if r["kind"] != "fused"), "autotuned_layers": sum(1 for k in tuned if not str(k).endswith("b")), "fused_bottlenecks": sum(1 for k, v in tuned.items() if str(k).endswith("b") and v), "autotune_seconds": round(tune_s, 2)},
+                   "launches_per_step": sum(1 for r in rows if r["kind"] != "fused"), "autotuned_layers": sum(1 for k in tuned if str(k)[-1] not in "bx"), "fused_bottlenecks": sum(1 for k, v in tuned.items() if str(k).endswith("b") and v),
+                   "fused_expand_reduce_pairs": sum(1 for k, v in tuned.items() if str(k).endswith("x") and v), "autotune_seconds": round(tune_s, 2)},
         "roofline": roofline, "cpu_baseline": cpu, "parity": parity, "training_step": training,
     }
     print(json.dumps(out))

@@ -161,6 +161,22 @@ sol_status sol_bottleneck_fused(const sol_tensor_desc *xd, const void *x, int mi
                                 const float *shift1, const void *w2_packed, const float *scale2, const float *shift2,
                                 const void *w3_packed, const float *scale3, const float *shift3, void *y, void *hip_stream);
 
+/* The last 1x1 convolution of one bottleneck and the first 1x1 convolution of the next as one depth-first kernel (the
+ * paper's layer-chain fusion, Sec. III-A, across the border of two blocks):
+ *   y = relu(scale3 * conv1x1(t, w3) + shift3 + shortcut)      c  -> c4 channels   (stored: later layers read it)
+ *   z = relu(scale1 * conv1x1(y, w1) + shift1)                 c4 -> cz channels
+ * z is contracted from y while y sits in on-chip memory, rounded to bf16 as stored; y is written once and not read back.
+ *   td, t       input of the first convolution, NHWC, SOL_BF16, td->c = 256; n*h*w a multiple of 64
+ *   c4          a multiple of 128, at most 1024;  cz = 256; anything else -> SOL_ERR_UNSUPPORTED (run the two layers
+ *               through sol_conv2d_fused)
+ *   w3_packed   sol_pack_conv_weights of cd = {c4, 256, 1,1, 1,1, 0,0};  w1_packed: {cz, c4, 1,1, 1,1, 0,0}
+ *   scale*, shift*  device fp32 per output channel of each convolution (sol_fold_bn), all required
+ *   shortcut    NHWC [n][h][w][c4], added before the first ReLU, required
+ *   y, z        NHWC [n][h][w][c4] / [n][h][w][cz], written by the call; must not alias the inputs or each other */
+sol_status sol_expand_reduce_fused(const sol_tensor_desc *td, const void *t, int c4, const void *w3_packed, const float *scale3,
+                                   const float *shift3, const void *shortcut, void *y, int cz, const void *w1_packed,
+                                   const float *scale1, const float *shift1, void *z, void *hip_stream);
+
 /* Depthwise convolution: a grouped convolution with one group -- one kh x kw filter -- per channel, which the
  * paper assigns to the fusion engine as a pooling layer with learned window weights (Sec. III-A) instead of
  * to the contraction path:
@@ -292,6 +308,15 @@ sol_status sol_network_set_layer_block(sol_network *net, int layer, int fused);
 /* *state = -1: `layer` ends no such block; 0: the block runs layer by layer; 1: as one launch */
 sol_status sol_network_layer_block(const sol_network *net, int layer, int *state);
 
+/* Expand -> reduce pairs in one launch.  When a network keeps no activations (flags 0), bf16: the last 1x1 convolution of
+ * a bottleneck (+ shortcut, ReLU) followed directly by a 1x1 convolution + ReLU that reads only its output, with shapes
+ * sol_expand_reduce_fused accepts, can run as that one kernel; both outputs are stored.  The plan takes the pair where the
+ * kernel applies, sol_network_autotune times both ways.  sol_network_layer_fused_into reports the first layer's index
+ * for the second while the pair runs fused.  *state = -1: `layer` starts no such pair; 0: the two run layer by layer;
+ * 1: as one launch.  sol_network_set_layer_xr restores / forces the choice (SOL_ERR_UNSUPPORTED if `layer` starts no pair). */
+sol_status sol_network_layer_xr(const sol_network *net, int layer, int *state);
+sol_status sol_network_set_layer_xr(sol_network *net, int layer, int fused);
+
 /* One forward pass recorded as a HIP graph (launch-bound inner loops: the about fifty launches of a ResNet-50-shaped
  * pass replay as one submission).  sol_network_graph_create runs the pass once eagerly, then records the same
  * launches with the given pointers baked in: x, y, workspace, the bound parameter buffer and the network must
@@ -314,7 +339,8 @@ void sol_graph_destroy(sol_graph *graph);
  *     the two-launch result by at most one rounding of the shortcut term).
  * *into = index of the layer whose launch produces `layer`'s output: `layer` itself, the layer in front for such a
  * pool layer, the later convolution for such a shortcut, the last convolution of a bottleneck that runs as one launch
- * (see sol_network_set_layer_block) for its first two (sol_network_run_layer on a fused layer launches nothing). */
+ * (see sol_network_set_layer_block) for its first two, the first layer of an expand -> reduce pair (see
+ * sol_network_set_layer_xr) for its second (sol_network_run_layer on a fused layer launches nothing). */
 sol_status sol_network_layer_fused_into(const sol_network *net, int layer, int *into);
 
 /* Concatenation in place: when a network keeps no activations, a convolution (no fused pool, channel count a

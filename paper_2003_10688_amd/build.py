@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsol_mi355.so")
-SOURCES = ["conv_igemm.hip", "conv_dma.hip", "conv_halo.hip", "conv_gemm8.hip", "conv_stem.hip", "conv_pair.hip", "conv_block.hip", "fusion.hip", "dwconv.hip", "linear.hip", "train.hip", "probe.hip", "api.hip"]
+SOURCES = ["conv_igemm.hip", "conv_dma.hip", "conv_halo.hip", "conv_gemm8.hip", "conv_stem.hip", "conv_pair.hip", "conv_block.hip", "conv_xr.hip", "fusion.hip", "dwconv.hip", "linear.hip", "train.hip", "probe.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Rpass-analysis=kernel-resource-usage"]
 RESOURCES = os.path.join(HERE, "kernel_resources.json")     # per kernel: VGPRs, scratch bytes per lane, LDS bytes (written by build())

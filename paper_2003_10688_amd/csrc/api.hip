@@ -208,6 +208,8 @@ struct LayerPlan {
     int block_c1, block_c2;         // CONV (last 1x1 of a bottleneck): the reduce and 3x3 convolutions that one depth-first launch can compute with it (-1: none)
     int block_c3;                   // CONV (reduce / 3x3 of such a bottleneck): that last convolution (-1: none)
     bool use_block;                 // on the last convolution: the plan runs the bottleneck as one launch (heuristic or sol_network_autotune)
+    int xr_next, xr_from;           // CONV (last 1x1 of a bottleneck): the next bottleneck's first 1x1, which the same launch can compute (conv_xr.hip); on that layer: the former (-1: none)
+    bool use_xr;                    // on the former: the plan runs the two as one launch
     bool pre_bn, pre_set;           // CONV: BN + ReLU on the input side; its folded constants have been set
     size_t pre_scale_off, pre_shift_off;
     int ldx;                        // CONV: input pixel pitch when the input is a channel prefix of a dense-block buffer (0: dense)
@@ -388,6 +390,7 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
         lp.concat_into = -1;
         lp.pair = -1;
         lp.block_c1 = lp.block_c2 = lp.block_c3 = -1;
+        lp.xr_next = lp.xr_from = -1;
         lp.chain_owner = -1;
         lp.fused_into = i;
         lp.in = lp.src < 0 ? net->input : net->layers[lp.src].out;
@@ -657,6 +660,25 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             c3.use_block = (long)c1.in.n * c1.in.h * c1.in.w >= 40000;
         }
 
+    // Expand -> reduce pair (the same depth-first fusion across the border of two bottlenecks): the last 1x1 convolution of
+    // a block (+ shortcut, ReLU) and the first 1x1 convolution of the next block, which reads nothing else, can run as
+    // one launch that stores the block output once and never reads it back (conv_xr.hip).  Both layers keep their
+    // buffers; the heuristic takes the pair wherever the kernel applies, sol_network_autotune measures.
+    if (!net->training && !net->keep && dt == SOL_BF16)
+        for (int i = 0; i + 1 < n_layers; i++) {
+            LayerPlan &c3 = net->layers[i], &c1 = net->layers[i + 1];
+            const auto plain1x1 = [](const LayerPlan &l) {
+                return l.L.kind == SOL_LAYER_CONV && l.L.pool.kind == SOL_POOL_NONE && l.L.act == SOL_ACT_RELU && !l.cout_real && !l.cin_real && !l.pre_bn &&
+                       !l.ldx && l.concat_into < 0 && l.pair < 0 && !l.elided && !l.absorbs_next && l.cd.sh == 1 && l.cd.sw == 1 && l.cd.kh == 1 &&
+                       l.cd.kw == 1 && l.cd.ph == 0 && l.cd.pw == 0 && l.block_c1 < 0 && l.block_c3 < 0;
+            };
+            if (!plain1x1(c3) || !plain1x1(c1) || c3.res < 0 || c3.src < 0 || c1.src != i || c1.res >= 0 || c3.xr_from >= 0) continue;
+            if (!xr_kernel_applies(dt, (long)c3.in.n * c3.in.h * c3.in.w, c3.cd.cin, c3.cd.cout, c1.cd.cout)) continue;
+            c3.xr_next = i + 1;
+            c1.xr_from = i;
+            c3.use_xr = true;
+        }
+
     // activation layout: inference reuses buffers once their last consumer has run, training keeps all
     Arena ar;
     for (int i = 0; i < n_layers; i++) {
@@ -673,6 +695,11 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             if (!cc.prealloc && lp.concat_into + 1 < n_layers) { cc.out_off = ar.alloc(tensor_bytes(cc.out)); cc.prealloc = true; }
         } else if (!lp.elided && !lp.prealloc && (i + 1 < n_layers || net->training)) {
             lp.out_off = ar.alloc(tensor_bytes(lp.out));
+        }
+        if (lp.xr_next >= 0 && lp.xr_next + 1 < n_layers) {   // this launch may also write the next layer's output: that buffer exists from here on
+            LayerPlan &nx = net->layers[lp.xr_next];
+            nx.out_off = ar.alloc(tensor_bytes(nx.out));
+            nx.prealloc = true;
         }
         if (lp.split_pool && !net->keep) ar.release(lp.tmp_off);
         if (!net->keep)
@@ -770,6 +797,26 @@ sol_status sol_bottleneck_fused(const sol_tensor_desc *xd, const void *x, int mi
     SOL_REQUIRE(x != y, SOL_ERR_SHAPE, "the block cannot run in place: neighbouring tiles read x rows that others have already overwritten");
     const BlockLaunch b{x, y, w1_packed, w2_packed, w3_packed, scale1, shift1, scale2, shift2, scale3, shift3, xd->n, xd->h, xd->w, xd->c, mid};
     return launch_conv_block(b, (hipStream_t)stream);
+}
+
+sol_status sol_expand_reduce_fused(const sol_tensor_desc *td, const void *t, int c4, const void *w3_packed, const float *scale3, const float *shift3,
+                                   const void *shortcut, void *y, int cz, const void *w1_packed, const float *scale1, const float *shift1, void *z,
+                                   void *stream) {
+    SOL_TRY(check_tensor(td, "t"));
+    SOL_REQUIRE(td->dtype == SOL_BF16, SOL_ERR_DTYPE, "fused expand-reduce pair: bf16 only");
+    SOL_REQUIRE(c4 > 0 && cz > 0, SOL_ERR_SHAPE, "bad channel counts %d, %d", c4, cz);
+    const long P = (long)td->n * td->h * td->w;
+    if (P == 0) return SOL_OK;
+    SOL_REQUIRE(t && w3_packed && scale3 && shift3 && shortcut && y && w1_packed && scale1 && shift1 && z, SOL_ERR_NULL,
+                "fused expand-reduce pair: every pointer is required");
+    SOL_REQUIRE(aligned16(t) && aligned16(w3_packed) && aligned16(shortcut) && aligned16(y) && aligned16(w1_packed) && aligned16(z) &&
+                    aligned16(scale3) && aligned16(shift3) && aligned16(scale1) && aligned16(shift1),
+                SOL_ERR_ALIGN, "device pointers must be 16-byte aligned");
+    SOL_REQUIRE(y != t && y != shortcut && z != t && z != y, SOL_ERR_UNSUPPORTED, "fused expand-reduce pair: outputs must not alias inputs");
+    SOL_REQUIRE(xr_kernel_applies(td->dtype, P, td->c, c4, cz), SOL_ERR_UNSUPPORTED,
+                "fused expand-reduce pair: needs 256 -> c4 -> 256 channels, c4 a multiple of 128 up to 1024, n*h*w a multiple of 64");
+    const XrLaunch xl{t, shortcut, y, z, w3_packed, w1_packed, scale3, shift3, scale1, shift1, P, td->c, c4, cz};
+    return launch_conv_xr(xl, (hipStream_t)stream);
 }
 
 size_t sol_packed_dw_weight_bytes(int c, int kh, int kw, sol_dtype dt) {
@@ -1154,6 +1201,7 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
         const LayerPlan &lp = net->layers[i];
         if (lp.elided) continue;                            // computed by the convolution in front of it
         if (lp.block_c3 >= 0 && net->layers[lp.block_c3].use_block && !g_tile_override) continue;   // ... by the bottleneck launch behind it
+        if (lp.xr_from >= 0 && net->layers[lp.xr_from].use_xr && !g_tile_override) continue;        // ... by the expand-reduce launch in front of it
         const void *in = layer_in(net, lp.src, x, ws);
         const int oi = lp.absorbs_next ? i + 1 : lp.concat_into >= 0 ? lp.concat_into : lp.chain_owner >= 0 ? lp.chain_owner : i;   // the layer whose buffer this launch writes
         void *out = oi + 1 == nl ? y : static_cast<void *>(ws + net->layers[oi].out_off);
@@ -1177,6 +1225,15 @@ static sol_status run_layers(sol_network *net, const void *x, void *y, void *wor
                                          fp(b1.scale_off), fp(b1.shift_off), fp(b2.scale_off), fp(b2.shift_off), scale, shift,
                                          b1.in.n, b1.in.h, b1.in.w, b1.in.c, b1.cd.cout};
                     SOL_TRY(launch_conv_block(bl, st));
+                    break;
+                }
+                if (lp.xr_next >= 0 && lp.use_xr && !g_tile_override) {        // this launch also computes the next bottleneck's first convolution
+                    const LayerPlan &nx = net->layers[lp.xr_next];
+                    const auto fp = [&](size_t off) { return reinterpret_cast<const float *>(net->params + off); };
+                    void *z = lp.xr_next + 1 == nl ? y : static_cast<void *>(ws + nx.out_off);
+                    const XrLaunch xl{in, res, conv_dst, z, net->params + lp.w_off, net->params + nx.w_off, scale, shift, fp(nx.scale_off), fp(nx.shift_off),
+                                      (long)lp.in.n * lp.in.h * lp.in.w, lp.cd.cin, lp.cd.cout, nx.cd.cout};
+                    SOL_TRY(launch_conv_xr(xl, st));
                     break;
                 }
                 if (lp.pair >= 0) {     // this launch also computes the projection shortcut it adds
@@ -1358,7 +1415,7 @@ sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *
     if (net->training) return autotune_training(net, x, y, workspace, workspace_bytes, reps, (hipStream_t)stream);
     hipStream_t st = (hipStream_t)stream;
     const int nl = (int)net->layers.size();
-    for (auto &lp : net->layers) { lp.tile = T_AUTO; lp.use_block = false; }   // every layer is tuned on its own first
+    for (auto &lp : net->layers) { lp.tile = T_AUTO; lp.use_block = false; lp.use_xr = false; }   // every layer is tuned on its own first
     // one whole pass: validates the arguments and leaves finite activations of the right shape in every buffer
     SOL_TRY(run_layers(net, x, y, workspace, workspace_bytes, 0, nl - 1, st));
     hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -1425,10 +1482,50 @@ sol_status sol_network_autotune(sol_network *net, const void *x, void *y, void *
         }
         lp.use_block = t[1] < t[0];
     }
+    // expand -> reduce pairs: one launch against the two tuned launches, both right behind the producer of the pair's input
+    for (int i = 0; i < nl && rs == SOL_OK; i++) {
+        LayerPlan &lp = net->layers[i];
+        if (lp.xr_next < 0 || lp.in.n == 0) continue;
+        const int prod = lp.src;
+        float t[2] = {0.f, 0.f};
+        for (int fused = 0; fused < 2 && rs == SOL_OK; fused++) {
+            lp.use_xr = fused != 0;
+            for (int r = 0; r < reps + 1 && rs == SOL_OK; r++) {
+                if (prod >= 0) rs = run_layers(net, x, y, workspace, workspace_bytes, prod, prod, st);
+                if (rs != SOL_OK) break;
+                SOL_HIP(hipEventRecord(e0, st));
+                for (int j : {i, lp.xr_next})
+                    if (rs == SOL_OK) rs = run_layers(net, x, y, workspace, workspace_bytes, j, j, st);
+                SOL_HIP(hipEventRecord(e1, st));
+                SOL_HIP(hipEventSynchronize(e1));
+                float ms = 0.f;
+                SOL_HIP(hipEventElapsedTime(&ms, e0, e1));
+                if (r > 0) t[fused] += ms;
+            }
+        }
+        lp.use_xr = t[1] < t[0];
+    }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (rs != SOL_OK) for (auto &lp : net->layers) lp.tile = T_AUTO;
     return rs;
+}
+
+sol_status sol_network_layer_xr(const sol_network *net, int layer, int *state) {
+    SOL_REQUIRE(net && state, SOL_ERR_NULL, "net and state must not be NULL");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    const LayerPlan &lp = net->layers[layer];
+    *state = lp.xr_next < 0 ? -1 : (lp.use_xr ? 1 : 0);
+    return SOL_OK;
+}
+
+sol_status sol_network_set_layer_xr(sol_network *net, int layer, int fused) {
+    SOL_REQUIRE(net, SOL_ERR_NULL, "net is NULL");
+    SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
+    LayerPlan &lp = net->layers[layer];
+    SOL_REQUIRE(lp.xr_next >= 0 || !fused, SOL_ERR_UNSUPPORTED, "layer %d is not the first layer of an expand-reduce pair the depth-first kernel can run", layer);
+    lp.use_xr = fused != 0;
+    return SOL_OK;
 }
 
 sol_status sol_network_layer_block(const sol_network *net, int layer, int *state) {
@@ -1511,7 +1608,9 @@ sol_status sol_network_layer_fused_into(const sol_network *net, int layer, int *
     SOL_REQUIRE(net && into, SOL_ERR_NULL, "net / into is NULL");
     SOL_REQUIRE(layer >= 0 && layer < (int)net->layers.size(), SOL_ERR_SHAPE, "no layer %d", layer);
     const LayerPlan &lp = net->layers[layer];
-    *into = (lp.block_c3 >= 0 && net->layers[lp.block_c3].use_block) ? lp.block_c3 : lp.fused_into;
+    *into = (lp.block_c3 >= 0 && net->layers[lp.block_c3].use_block) ? lp.block_c3
+            : (lp.xr_from >= 0 && net->layers[lp.xr_from].use_xr)        ? lp.xr_from
+                                                                         : lp.fused_into;
     return SOL_OK;
 }
 

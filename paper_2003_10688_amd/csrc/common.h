@@ -173,6 +173,14 @@ struct BlockLaunch {
 };
 bool block_kernel_applies(int dt, int N, int H, int W, int C4, int WM);
 sol_status launch_conv_block(const BlockLaunch &b, hipStream_t st);
+struct XrLaunch {
+    const void *t, *r; void *y, *z;                  // expand input [P][WM], its shortcut [P][C4]; outputs y [P][C4], z [P][WZ]
+    const void *w3, *w1;                             // packed weights [C4][WM], [WZ][C4]
+    const float *s3, *h3, *s1, *h1;                  // folded scale / shift of the two layers
+    long P; int WM, C4, WZ;
+};
+bool xr_kernel_applies(int dt, long P, int WM, int C4, int WZ);
+sol_status launch_conv_xr(const XrLaunch &b, hipStream_t st);
 bool linear_kernel_applies(const ConvArgs &a, int dt);
 sol_status launch_linear(const ConvArgs &a, int dt, hipStream_t st);
 sol_status launch_conv(const ConvArgs &a, int dt, int tile_override, hipStream_t st);

@@ -219,6 +219,18 @@ def sol_bottleneck_fused(x, mid, w1, s1, h1, w2, s2, h2, w3, s3, h3, stream=None
     return y
 
 
+def sol_expand_reduce_fused(t, c4, w3, s3, h3, shortcut, cz, w1, s1, h1, stream=None):
+    """t: NHWC bf16 device tensor [n,h,w,256]; shortcut: [n,h,w,c4]; w*: packed weights; s*/h*: folded scale / shift.
+    Returns (y [n,h,w,c4], z [n,h,w,cz])."""
+    n, h, w, _ = t.shape
+    y = torch.empty((n, h, w, c4), dtype=t.dtype, device=t.device)
+    z = torch.empty((n, h, w, cz), dtype=t.dtype, device=t.device)
+    td = tensor_desc(t)
+    _check(lib().sol_expand_reduce_fused(C.byref(td), _ptr(t), C.c_int(c4), _ptr(w3), _ptr(s3), _ptr(h3), _ptr(shortcut), _ptr(y),
+                                         C.c_int(cz), _ptr(w1), _ptr(s1), _ptr(h1), _ptr(z), _stream(stream)))
+    return y, z
+
+
 def sol_pack_dwconv_weights(c, kh, kw, dt, w_c1hw, stream=None):
     """w_c1hw: device fp32 [c][1][kh][kw] -> packed device buffer (uint8 tensor)."""
     packed = torch.empty(lib().sol_packed_dw_weight_bytes(c, kh, kw, dt), dtype=torch.uint8, device=w_c1hw.device)
@@ -376,6 +388,9 @@ class Network:
             b = self.block_state(i)
             if b >= 0:
                 out[f"{i}b"] = b          # bottleneck ending in layer i: 1 = one depth-first launch, 0 = layer by layer
+            b = self.xr_state(i)
+            if b >= 0:
+                out[f"{i}x"] = b          # expand-reduce pair starting in layer i: 1 = one launch, 0 = two
         return out
 
     def set_tiles(self, tiles):
@@ -384,6 +399,8 @@ class Network:
             _check(lib().sol_network_set_layer_tile(self._h, C.c_int(i), C.c_int(int(tiles.get(i, tiles.get(str(i), 0))))))
             if f"{i}b" in tiles:
                 self.set_block(i, tiles[f"{i}b"])
+            if f"{i}x" in tiles:
+                self.set_xr(i, tiles[f"{i}x"])
 
     def graph(self, x, stream):
         """Records one forward pass on `stream` (a torch.cuda.Stream other than the default one) as a HIP graph;
@@ -408,6 +425,16 @@ class Network:
     def set_block(self, layer, fused):
         """Runs the bottleneck that ends in convolution `layer` as one depth-first launch (fused) or layer by layer."""
         _check(lib().sol_network_set_layer_block(self._h, C.c_int(layer), C.c_int(int(bool(fused)))))
+
+    def xr_state(self, layer):
+        """-1: `layer` starts no expand-reduce pair the depth-first kernel can run; 0: the two layers run one by one; 1: as one launch."""
+        t = C.c_int(0)
+        _check(lib().sol_network_layer_xr(self._h, C.c_int(layer), C.byref(t)))
+        return t.value
+
+    def set_xr(self, layer, fused):
+        """Runs convolution `layer` and the 1x1 convolution behind it as one depth-first launch (fused) or one by one."""
+        _check(lib().sol_network_set_layer_xr(self._h, C.c_int(layer), C.c_int(int(bool(fused)))))
 
     def fused_into(self, layer):
         """Index of the layer whose launch produces `layer`'s output (itself unless the plan fused it into
