@@ -317,7 +317,7 @@ sol_status sol_network_layer_block(const sol_network *net, int layer, int *state
 sol_status sol_network_layer_xr(const sol_network *net, int layer, int *state);
 sol_status sol_network_set_layer_xr(sol_network *net, int layer, int fused);
 
-/* One forward pass recorded as a HIP graph (launch-bound inner loops: the about fifty launches of a ResNet-50-shaped
+/* One forward pass recorded as a HIP graph (launch-bound inner loops: the about forty launches of a ResNet-50-shaped
  * pass replay as one submission).  sol_network_graph_create runs the pass once eagerly, then records the same
  * launches with the given pointers baked in: x, y, workspace, the bound parameter buffer and the network must
  * stay alive and unmoved while the graph is used (their CONTENTS may change between launches).  `hip_stream`
