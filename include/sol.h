@@ -166,7 +166,7 @@ sol_status sol_bottleneck_fused(const sol_tensor_desc *xd, const void *x, int mi
  *   y = relu(scale3 * conv1x1(t, w3) + shift3 + shortcut)      c  -> c4 channels   (stored: later layers read it)
  *   z = relu(scale1 * conv1x1(y, w1) + shift1)                 c4 -> cz channels
  * z is contracted from y while y sits in on-chip memory, rounded to bf16 as stored; y is written once and not read back.
- *   td, t       input of the first convolution, NHWC, SOL_BF16, td->c = 256; n*h*w a multiple of 64
+ *   td, t       input of the first convolution, NHWC, SOL_BF16, td->c = 256
  *   c4          a multiple of 128, at most 1024;  cz = 256; anything else -> SOL_ERR_UNSUPPORTED (run the two layers
  *               through sol_conv2d_fused)
  *   w3_packed   sol_pack_conv_weights of cd = {c4, 256, 1,1, 1,1, 0,0};  w1_packed: {cz, c4, 1,1, 1,1, 0,0}
@@ -310,8 +310,8 @@ sol_status sol_network_layer_block(const sol_network *net, int layer, int *state
 
 /* Expand -> reduce pairs in one launch.  When a network keeps no activations (flags 0), bf16: the last 1x1 convolution of
  * a bottleneck (+ shortcut, ReLU) followed directly by a 1x1 convolution + ReLU that reads only its output, with shapes
- * sol_expand_reduce_fused accepts, can run as that one kernel; both outputs are stored.  The plan takes the pair where the
- * kernel applies, sol_network_autotune times both ways.  sol_network_layer_fused_into reports the first layer's index
+ * sol_expand_reduce_fused accepts, can run as that one kernel; both outputs are stored.  The plan decides by a shape
+ * heuristic, sol_network_autotune by timing both ways.  sol_network_layer_fused_into reports the first layer's index
  * for the second while the pair runs fused.  *state = -1: `layer` starts no such pair; 0: the two run layer by layer;
  * 1: as one launch.  sol_network_set_layer_xr restores / forces the choice (SOL_ERR_UNSUPPORTED if `layer` starts no pair). */
 sol_status sol_network_layer_xr(const sol_network *net, int layer, int *state);

@@ -663,7 +663,7 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
     // Expand -> reduce pair (the same depth-first fusion across the border of two bottlenecks): the last 1x1 convolution of
     // a block (+ shortcut, ReLU) and the first 1x1 convolution of the next block, which reads nothing else, can run as
     // one launch that stores the block output once and never reads it back (conv_xr.hip).  Both layers keep their
-    // buffers; the heuristic takes the pair wherever the kernel applies, sol_network_autotune measures.
+    // buffers; a shape heuristic decides, sol_network_autotune measures.
     if (!net->training && !net->keep && dt == SOL_BF16)
         for (int i = 0; i + 1 < n_layers; i++) {
             LayerPlan &c3 = net->layers[i], &c1 = net->layers[i + 1];
@@ -676,7 +676,7 @@ static sol_status plan_network(sol_network *net, const sol_layer *layers, int n_
             if (!xr_kernel_applies(dt, (long)c3.in.n * c3.in.h * c3.in.w, c3.cd.cin, c3.cd.cout, c1.cd.cout)) continue;
             c3.xr_next = i + 1;
             c1.xr_from = i;
-            c3.use_xr = true;
+            c3.use_xr = (long)c3.in.n * c3.in.h * c3.in.w >= 128 * 64;   // heuristic: a workgroup per 64 pixels; worth it once those fill half the chip
         }
 
     // activation layout: inference reuses buffers once their last consumer has run, training keeps all
@@ -814,7 +814,7 @@ sol_status sol_expand_reduce_fused(const sol_tensor_desc *td, const void *t, int
                 SOL_ERR_ALIGN, "device pointers must be 16-byte aligned");
     SOL_REQUIRE(y != t && y != shortcut && z != t && z != y, SOL_ERR_UNSUPPORTED, "fused expand-reduce pair: outputs must not alias inputs");
     SOL_REQUIRE(xr_kernel_applies(td->dtype, P, td->c, c4, cz), SOL_ERR_UNSUPPORTED,
-                "fused expand-reduce pair: needs 256 -> c4 -> 256 channels, c4 a multiple of 128 up to 1024, n*h*w a multiple of 64");
+                "fused expand-reduce pair: needs 256 -> c4 -> 256 channels, c4 a multiple of 128 up to 1024");
     const XrLaunch xl{t, shortcut, y, z, w3_packed, w1_packed, scale3, shift3, scale1, shift1, P, td->c, c4, cz};
     return launch_conv_xr(xl, (hipStream_t)stream);
 }

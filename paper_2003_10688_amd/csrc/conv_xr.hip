@@ -99,12 +99,13 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
         const int rowz = idx * 16 + lrow16;                           // W1 row
         woZ[i] = (unsigned)rowz * (unsigned)(C4 * 2) + (unsigned)((ls4 ^ swz<64>(rowz)) << 4);
         const int rowr = (idx & 7) * 8 + lrow8;                       // shortcut: plane idx / 8 of the pass, pixel rowr
-        roR[i] = (unsigned)(p0 + rowr) * (unsigned)(C4 * 2) + (unsigned)((idx >> 3) * 128) + (unsigned)((ls8 ^ swz<128>(rowr)) << 4);
+        roR[i] = p0 + rowr < a.P ? (unsigned)(p0 + rowr) * (unsigned)(C4 * 2) + (unsigned)((idx >> 3) * 128) + (unsigned)((ls8 ^ swz<128>(rowr)) << 4)
+                                 : 0xffffffffu;   // pixels beyond the tensor (ragged last tile): the range check returns zeros
     }
 #pragma unroll
     for (int i = 0; i < UY; i++) {
         const int idx = wave * UY + i, row = (idx & 7) * 8 + lrow8;   // t: plane idx / 8, pixel row
-        toT[i] = (unsigned)(p0 + row) * (unsigned)(WM * 2) + (unsigned)((idx >> 3) * 128) + (unsigned)((ls8 ^ swz<128>(row)) << 4);
+        toT[i] = p0 + row < a.P ? (unsigned)(p0 + row) * (unsigned)(WM * 2) + (unsigned)((idx >> 3) * 128) + (unsigned)((ls8 ^ swz<128>(row)) << 4) : 0xffffffffu;
     }
     // slot POS of pass q: W3 rows (POS < UY) or W1 rows
     auto issue_unit = [&](auto POS, int slot, int q, bool real) {
@@ -161,7 +162,9 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
         eoff[g] = (unsigned)((ch >> 6) * PLANE + erow * 128) + (unsigned)((((ch & 63) >> 3) ^ swz<128>(erow)) << 4) + (unsigned)((ch & 7) * 2);
     }
     // store of a y pass from LDS: 16 bytes of plane 0 and of plane 1 per lane
-    const int srow = tid >> 3, sls = tid & 7;
+    // (a lane whose pixel lies beyond the tensor -- ragged last tile -- repeats the store of the last pixel, same bytes to the
+    // same place: every wave issues its two stores, as the static counts assume)
+    const int srow = min(tid >> 3, a.P - 1 - p0), sls = tid & 7;
     const unsigned ysrc = lds_addr(lds + YCH_OFF) + (unsigned)(srow * 128) + (unsigned)((sls ^ swz<128>(srow)) << 4);
     unsigned char *const ydst = static_cast<unsigned char *>(a.y) + ((size_t)(p0 + srow) * C4 + sls * 8) * 2;
 
@@ -310,10 +313,10 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
 }
 
 // bf16; 256 -> C4 -> 256 channels, C4 a multiple of 128 up to 1024 (the affine constants of y sit in 8 KB of LDS);
-// whole 64-pixel tiles; tensors below 2 GB (32-bit byte offsets)
+// any pixel count (tiles of 64, the last one ragged); tensors below 2 GB (32-bit byte offsets)
 bool xr_kernel_applies(int dt, long P, int WM, int C4, int WZ) {
     if (dt != SOL_BF16 || WM != 256 || WZ != 256 || C4 % 128 != 0 || C4 < 128 || C4 > 1024) return false;
-    if (P <= 0 || P % 64 != 0) return false;
+    if (P <= 0) return false;
     return (double)P * C4 * 2.0 < 2147483648.0;
 }
 
@@ -323,7 +326,7 @@ sol_status launch_conv_xr(const XrLaunch &b, hipStream_t st) {
     a.t = b.t; a.r = b.r; a.y = b.y; a.z = b.z; a.w3 = b.w3; a.w1 = b.w1;
     a.s3 = b.s3; a.h3 = b.h3; a.s1 = b.s1; a.h1 = b.h1;
     a.P = (int)b.P; a.C4 = b.C4;
-    a.ntiles = a.P / 64;
+    a.ntiles = (a.P + 63) / 64;
     const int grid = ((a.ntiles + 7) / 8) * 8;
     hipLaunchKernelGGL((conv_xr_kernel<256, 256, 6>), dim3(grid), dim3(512), 0, st, a);
     SOL_HIP(hipGetLastError());

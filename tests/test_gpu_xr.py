@@ -74,6 +74,8 @@ def _ref(t, r, ls, prm):
 XR_CASES = [
     # N, H, W, C4      one tile; several tiles over several XCDs with idle workgroups at the end of the grid; every pass count
     (1, 8, 8, 1024), (5, 16, 16, 1024), (2, 8, 16, 512), (3, 8, 8, 128), (7, 4, 16, 640), (16, 14, 14, 1024),
+    # ragged last tile: 196 = 3 * 64 + 4 pixels, 49 pixels (less than a tile), 5 * 81 = 405 = 6 * 64 + 21
+    (1, 14, 14, 1024), (1, 7, 7, 512), (5, 9, 9, 256),
 ]
 
 
@@ -124,7 +126,6 @@ def test_expand_reduce_fused_rejects_what_it_cannot_do(sol):
     for t, c4, r, cz in [(torch.zeros((1, 8, 8, 128), **bf), 512, torch.zeros((1, 8, 8, 512), **bf), 256),      # 128 input channels
                          (torch.zeros((1, 8, 8, 256), **bf), 2048, torch.zeros((1, 8, 8, 2048), **bf), 256),    # too wide
                          (torch.zeros((1, 8, 8, 256), **bf), 1024, torch.zeros((1, 8, 8, 1024), **bf), 512),    # 512 output channels
-                         (torch.zeros((1, 7, 7, 256), **bf), 1024, torch.zeros((1, 7, 7, 1024), **bf), 256),    # 49 pixels
                          (torch.zeros((1, 8, 8, 256), device="cuda:0"), 1024, torch.zeros((1, 8, 8, 1024), device="cuda:0"), 256)]:   # fp32
         with pytest.raises(sol.SolError) as e:
             call(t, c4, r, cz)
@@ -135,7 +136,7 @@ def test_expand_reduce_fused_rejects_what_it_cannot_do(sol):
 
 # ---- the plan runs expand -> reduce pairs as one launch -----------------------------------------------------------------
 def test_network_runs_expand_reduce_pairs(sol):
-    """ResNet-50-shaped list at 128x128 input (the 14x14 stage becomes 8x8: whole 64-pixel tiles), lean plan: (a) each
+    """ResNet-50-shaped list at 128x128 input (the 14x14 stage becomes 8x8), lean plan: (a) each
     pair, fed the checker's inputs, gives the checker's two outputs element-wise (2e-2); (b) the whole pass agrees with the
     layer-by-layer plan and with the checker norm-wise; (c) the plan reports what it fused; (d) a recorded graph of the
     fused plan replays bit-identically."""
@@ -147,7 +148,7 @@ def test_network_runs_expand_reduce_pairs(sol):
     net.set_params(wk.params)
     starts = [i for i in range(len(L)) if net.xr_state(i) >= 0]
     assert len(starts) == 4, starts                # bottlenecks 2-5 of the 1024-channel stage, each with the reduce layer behind it
-    assert all(net.xr_state(i) == 1 for i in starts)
+    assert all(net.xr_state(i) == 0 for i in starts)     # three tiles of 64 pixels: the plan's heuristic leaves such pairs alone
     for i in starts:
         net.set_xr(i, 0)
         assert net.fused_into(i + 1) == i + 1
