@@ -18,7 +18,7 @@
 //   Z-stage u (u < 4):   W1[rows 0..255][128 pass + 32 u .. + 31]     256 rows x  64 B;  z += y-pass[:, 32 u ..] . that
 // Between them the pass's accumulators get affine + shortcut + ReLU, are rounded and parked in LDS (the shortcut rows
 // and the affine constants also come from LDS: the rows by DMA one pass ahead, the constants once); the store of the
-// pass to y is issued from LDS under the first Z-stage.  A wave keeps its pixels of t as fragments in registers.
+// pass to y is issued from LDS behind the MFMAs of the first Z-stage.  A wave keeps its pixels of t as fragments in registers.
 #include <algorithm>
 
 #include "conv_common.h"
@@ -107,23 +107,20 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
         const int idx = wave * UY + i, row = (idx & 7) * 8 + lrow8;   // t: plane idx / 8, pixel row
         toT[i] = p0 + row < a.P ? (unsigned)(p0 + row) * (unsigned)(WM * 2) + (unsigned)((idx >> 3) * 128) + (unsigned)((ls8 ^ swz<128>(row)) << 4) : 0xffffffffu;
     }
-    // slot POS of pass q: W3 rows (POS < UY) or W1 rows
-    auto issue_unit = [&](auto POS, int slot, int q, bool real) {
-        constexpr int pos = decltype(POS)::value;
-        unsigned char *dst = ring + slot * SLOT + wave * L * 1024;
+    // I-th DMA instruction of this wave for slot POS of pass q: W3 rows (POS < UY) or W1 rows
+    auto issue_one = [&](auto POS, auto I, int slot, int q, bool real) {
+        constexpr int pos = decltype(POS)::value, i = decltype(I)::value;
+        unsigned char *dst = ring + slot * SLOT + (wave * L + i) * 1024;
         if constexpr (pos < UY) {
             const unsigned soff = (unsigned)(pe(q) * PC) * (unsigned)(WM * 2) + (unsigned)(pos * 128);
-            static_for<L>([&](auto I) {
-                constexpr int i = decltype(I)::value;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w3r : nullr, (__attribute__((address_space(3))) void *)(dst + i * 1024), 16, woY[i], soff, 0, 0);
-            });
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w3r : nullr, (__attribute__((address_space(3))) void *)dst, 16, woY[i], soff, 0, 0);
         } else {
             const unsigned soff = (unsigned)((pe(q) * PC + (pos - UY) * 32) * 2);
-            static_for<L>([&](auto I) {
-                constexpr int i = decltype(I)::value;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w1r : nullr, (__attribute__((address_space(3))) void *)(dst + i * 1024), 16, woZ[i], soff, 0, 0);
-            });
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w1r : nullr, (__attribute__((address_space(3))) void *)dst, 16, woZ[i], soff, 0, 0);
         }
+    };
+    auto issue_unit = [&](auto POS, int slot, int q, bool real) {
+        static_for<L>([&](auto I) { issue_one(POS, I, slot, q, real); });
     };
     auto issue_shortcut = [&](int q, bool real) {
         static_for<L>([&](auto I) {
@@ -187,36 +184,42 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
     for (int e = 0; e < 16; e++) { zacc[0][0][e] = 0.f; zacc[1][0][e] = 0.f; }
 
     // A wave has one (Y) or two (Z) MFMAs per k-step: too little to hide an LDS round trip behind.  All fragments of a
-    // slot are therefore requested at once and the MFMAs follow back to back.
-    u32x4_t fw[4], fz[2][2], fyy[2];
-    auto stageY = [&](auto C, unsigned sb) {
-        constexpr int c = decltype(C)::value;
-        static_for<4>([&](auto K) { lds_read16<0>(fw[decltype(K)::value], xor_add(fwy0, (unsigned)(decltype(K)::value * 32), sb)); });
-        static_for<4>([&](auto K) {
+    // stage (two slots) are therefore requested at once and the MFMAs follow back to back, each waiting only for its own.
+    u32x4_t fw[8], fz[4][2], fyy[4];
+    auto stageY = [&](auto C0, unsigned sb, auto &&between) {          // slots of planes C0 and C0 + 1; between(j) after MFMA pair j
+        constexpr int c0 = decltype(C0)::value;
+        static_for<8>([&](auto K) {
             constexpr int k = decltype(K)::value;
-            wait_lgkmcnt<3 - k>();
+            lds_read16<(k >> 2) * SLOT>(fw[k], xor_add(fwy0, (unsigned)((k & 3) * 32), sb));
+        });
+        static_for<8>([&](auto K) {
+            constexpr int k = decltype(K)::value;
+            wait_lgkmcnt<7 - k>();
             landed(fw[k]);
-            Mma<bf16_t>::run(yacc[k & 1], fw[k], ft[c][k]);
+            Mma<bf16_t>::run(yacc[k & 1], fw[k], ft[c0 + (k >> 2)][k & 3]);
+            if constexpr (k & 1) between(std::integral_constant<int, k / 2>{});
         });
     };
-    auto stageZ = [&](auto U, unsigned sb) {
-        constexpr int uz = decltype(U)::value;
-        constexpr unsigned ky = (unsigned)((uz & 1) * 64), pb = (unsigned)((uz >> 1) * PLANE);
-        static_for<2>([&](auto K) {
-            constexpr int k = decltype(K)::value;
-            const unsigned aw = xor_add(fwz0, (unsigned)(k * 32), sb);
-            lds_read16<0>(fz[k][0], aw);
-            lds_read16<32 * 64>(fz[k][1], aw);
-            lds_read16<0>(fyy[k], xor_add(fy0, ky + (unsigned)(k * 32), pb));
+    auto stageZ = [&](auto U0, unsigned sb, auto &&between) {          // slots of the 32-channel groups U0 and U0 + 1 of the pass
+        constexpr int u0 = decltype(U0)::value;
+        static_assert(u0 % 2 == 0, "both groups lie in one plane of the parked pass");
+        constexpr unsigned pb = (unsigned)((u0 >> 1) * PLANE);
+        static_for<4>([&](auto K) {
+            constexpr int k = decltype(K)::value;                      // k-step k & 1 of slot k >> 1
+            const unsigned aw = xor_add(fwz0, (unsigned)((k & 1) * 32), sb);
+            lds_read16<(k >> 1) * SLOT>(fz[k][0], aw);
+            lds_read16<(k >> 1) * SLOT + 32 * 64>(fz[k][1], aw);
+            lds_read16<0>(fyy[k], xor_add(fy0, (unsigned)(k * 32), pb));
         });
-        static_for<2>([&](auto K) {
+        static_for<4>([&](auto K) {
             constexpr int k = decltype(K)::value;
-            wait_lgkmcnt<3 - 3 * k>();
+            wait_lgkmcnt<9 - 3 * k>();
             landed(fz[k][0]);
             landed(fz[k][1]);
             landed(fyy[k]);
             Mma<bf16_t>::run(zacc[0][0], fz[k][0], fyy[k]);
             Mma<bf16_t>::run(zacc[1][0], fz[k][1], fyy[k]);
+            between(K);
         });
     };
 
@@ -227,37 +230,30 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
     for (int q = 0; q < npass; q++) {
         static_for<4>([&](auto POS) {
             constexpr int pos = decltype(POS)::value;
-            // in flight behind this stage's slots: the two slots issued one stage ago and, if that was the first Z stage,
-            // its two stores and the shortcut rows in front of them
-            constexpr int N = 2 * L + (pos == 3 ? 2 + L : 0);
-            wait_vmcnt<N>();                                           // this wave's share of both slots has landed
+            // in flight behind this stage's slots: the two slots issued one stage ago, and what the first Z stage issues at
+            // its END (the two stores of the y pass and the next shortcut rows), which is behind that stage's own slots and
+            // in front of the next stage's: it counts for the two stages that follow a first Z stage
+            constexpr int N0 = 2 * L, N = N0 + ((pos == 3 || pos == 0) ? 2 + L : 0);
+            if constexpr (pos == 0) {                                  // no first Z stage in front of the first pass
+                if (q == 0) wait_vmcnt<N0>(); else wait_vmcnt<N>();
+            } else {
+                wait_vmcnt<N>();                                       // this wave's share of both slots has landed
+            }
             __builtin_amdgcn_s_barrier();                              // ... everyone's; and nobody still reads the slots refilled now
-            if constexpr (pos == 2) {
-                // the parked y pass is complete: store it (two 16-byte pieces per lane), then fetch the next shortcut rows
-                u32x4_t v0, v1;
-                lds_read16<0>(v0, ysrc);
-                lds_read16<PLANE>(v1, ysrc);
-                wait_lgkmcnt<0>();
-                landed(v0);
-                landed(v1);
-                // opaque stores with a memory clobber: they stay in front of the DMAs issued below, as the static counts assume
-                unsigned char *const yq = ydst + (size_t)pe(q) * (PC * 2);
-                asm volatile("global_store_dwordx4 %0, %1, off\n\tglobal_store_dwordx4 %0, %2, off offset:128" ::"v"(yq), "v"(v0), "v"(v1) : "memory");
-                issue_shortcut(q + 1, q + 1 < npass);
-            }
-            {
-                constexpr int ipos = ((pos + 2) % 4) * 2, carry = (pos + 2) / 4;
-                issue_unit(std::integral_constant<int, ipos>{}, islot, q + carry, q + carry < npass);
-                issue_unit(std::integral_constant<int, ipos + 1>{}, islot + 1, q + carry, q + carry < npass);
-            }
+            // the four DMA instructions of the stage two ahead go out between this stage's MFMAs, one per MFMA pair: a wave
+            // issues in order, and a DMA instruction waits its turn at the CU's address unit (about 18 cycles per KB, all
+            // eight waves queue there right behind the barrier) -- time in which the matrix pipe would otherwise idle
+            auto dma = [&](auto J) {
+                constexpr int j = decltype(J)::value, ipos = ((pos + 2) % 4) * 2 + j / L, carry = (pos + 2) / 4;
+                issue_one(std::integral_constant<int, ipos>{}, std::integral_constant<int, j % L>{}, islot + j / L, q + carry, q + carry < npass);
+            };
             const unsigned sb = (unsigned)(slot * SLOT);
             if constexpr (pos < 2) {
                 if constexpr (pos == 0) {
 #pragma unroll
                     for (int e = 0; e < 16; e++) { yacc[0][e] = 0.f; yacc[1][e] = 0.f; }
                 }
-                stageY(std::integral_constant<int, 2 * pos>{}, sb);
-                stageY(std::integral_constant<int, 2 * pos + 1>{}, sb + SLOT);
+                stageY(std::integral_constant<int, 2 * pos>{}, sb, dma);
                 if constexpr (pos == 1) {
                     // ---- the pass is contracted: affine + shortcut + ReLU, rounded, parked as the operand of the Z-stages
                     // (constants, shortcut rows: in LDS since the barrier above at the latest)
@@ -290,8 +286,21 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
                     wait_lgkmcnt<0>();
                 }
             } else {
-                stageZ(std::integral_constant<int, 2 * (pos - 2)>{}, sb);
-                stageZ(std::integral_constant<int, 2 * (pos - 2) + 1>{}, sb + SLOT);
+                stageZ(std::integral_constant<int, 2 * (pos - 2)>{}, sb, dma);
+                if constexpr (pos == 2) {
+                    // under this stage's MFMAs: the parked y pass goes to memory (two 16-byte pieces per lane, from LDS), and
+                    // the next shortcut rows are fetched (every wave is past the epilogue that read the current ones)
+                    u32x4_t v0, v1;
+                    lds_read16<0>(v0, ysrc);
+                    lds_read16<PLANE>(v1, ysrc);
+                    wait_lgkmcnt<0>();
+                    landed(v0);
+                    landed(v1);
+                    // opaque stores with a memory clobber: they keep their place among the DMAs, as the static counts assume
+                    unsigned char *const yq = ydst + (size_t)pe(q) * (PC * 2);
+                    asm volatile("global_store_dwordx4 %0, %1, off\n\tglobal_store_dwordx4 %0, %2, off offset:128" ::"v"(yq), "v"(v0), "v"(v1) : "memory");
+                    issue_shortcut(q + 1, q + 1 < npass);
+                }
             }
             slot = slot + 2 == NS ? 0 : slot + 2;
             islot = islot + 2 == NS ? 0 : islot + 2;
