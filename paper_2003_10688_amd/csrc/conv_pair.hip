@@ -195,19 +195,22 @@ __global__ void __launch_bounds__(256, 2) conv_pair_kernel(const ConvArgs a, con
             od[i] = (unsigned)co * (unsigned)g.Kp2 * 2u + sl;
         }
     }
-    auto issue = [&](int c, int buf) {          // chunk c of the concatenated reduction into stage buf: 8 DMA instructions per wave
+    // IDX-th of the 8 DMA instructions of this wave for chunk c of the concatenated reduction into stage buf (even: pixel rows,
+    // odd: weight rows)
+    auto issue_one = [&](auto IDX, int c, int buf) {
+        constexpr int idx = decltype(IDX)::value, i = idx >> 1;
         const bool main = c < n3;
         const unsigned col = (unsigned)(main ? c : c - n3) * 128u;
         unsigned char *st = lds + buf * STG;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            const int seg = i * 4 + wave;
+        const int seg = i * 4 + wave;
+        if constexpr ((idx & 1) == 0)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(main ? r_y : r_x, (__attribute__((address_space(3))) void *)(st + seg * 1024), 16,
                                                      (main ? oy[i] : ox[i]) + col, 0, 0, 0);
+        else
             __builtin_amdgcn_raw_ptr_buffer_load_lds(main ? r_w3 : r_wd, (__attribute__((address_space(3))) void *)(st + PR_OPB + seg * 1024),
                                                      16, (main ? o3[i] : od[i]) + col, 0, 0, 0);
-        }
     };
+    auto issue = [&](int c, int buf) { static_for<8>([&](auto I) { issue_one(I, c, buf); }); };
     issue(0, 0);
     const int cc = min(c0 + (tid & (PR_BC - 1)), a.Cout - 1);
     const float k_s3 = a.scale ? a.scale[cc] : 1.f, k_sd = g.scale2 ? g.scale2[cc] : 1.f;
@@ -223,12 +226,15 @@ __global__ void __launch_bounds__(256, 2) conv_pair_kernel(const ConvArgs a, con
 
     const int lr = lane & 31, lh = lane >> 5;
     const int fsw = swz(lr);
-    auto contract = [&](f32x16_t (&acc)[TC][TP], unsigned stage) {
+    // between(k): called behind the MFMAs of k-step k.  The DMA instructions of the next chunk go out there, two per k-step:
+    // a wave issues in order, and issued up front they would queue at the CU's address unit (about 18 cycles per
+    // instruction, both workgroups' waves at once) with every wave's MFMAs waiting behind them
+    auto contract = [&](f32x16_t (&acc)[TC][TP], unsigned stage, auto &&between) {
         const unsigned ax = stage + (wp * TP * 32 + lr) * PR_ROWB, aw = stage + PR_OPB + (wc * TC * 32 + lr) * PR_ROWB;
         // one fragment set here: a second set (reads of the next k-step under these MFMAs) pays in the 64-channel
         // kernel above, but with this kernel's per-lane gather offsets live it spills registers and runs slower
-#pragma unroll
-        for (int ks = 0; ks < KS; ks++) {
+        static_for<KS>([&](auto KSI) {
+            constexpr int ks = decltype(KSI)::value;
             const unsigned so = (unsigned)(((2 * ks + lh) ^ fsw) << 4);
             u32x4_t fa[TC], fb[TP];
             static_for<TC>([&](auto I) { lds_read16<decltype(I)::value * 32 * PR_ROWB>(fa[decltype(I)::value], aw + so); });
@@ -240,14 +246,23 @@ __global__ void __launch_bounds__(256, 2) conv_pair_kernel(const ConvArgs a, con
             for (int i = 0; i < TC; i++)
 #pragma unroll
                 for (int j = 0; j < TP; j++) Mma<bf16_t>::run(acc[i][j], fa[i], fb[j]);
-        }
+            between(KSI);
+        });
     };
     const unsigned lbase = lds_addr(lds);
     for (int c = 0; c < nchunk; c++) {
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();                           // chunk c has landed for every wave, and every wave has contracted chunk c - 1
-        if (c + 1 < nchunk) issue(c + 1, (c + 1) & 1);
-        if (c < n3) contract(acc3, lbase + (c & 1) * STG); else contract(accd, lbase + (c & 1) * STG);
+        const bool more = c + 1 < nchunk;          // workgroup-uniform
+        auto dma = [&](auto K) {
+            constexpr int k = decltype(K)::value;
+            static_assert(KS == 4, "8 DMA instructions over 4 k-steps");
+            if (more) {
+                issue_one(std::integral_constant<int, 2 * k>{}, c + 1, (c + 1) & 1);
+                issue_one(std::integral_constant<int, 2 * k + 1>{}, c + 1, (c + 1) & 1);
+            }
+        };
+        if (c < n3) contract(acc3, lbase + (c & 1) * STG, dma); else contract(accd, lbase + (c & 1) * STG, dma);
     }
     if (tid < PR_BC) { chan[0][tid] = k_s3; chan[1][tid] = k_sd; chan[2][tid] = k_h3 + k_hd; }
     __syncthreads();
