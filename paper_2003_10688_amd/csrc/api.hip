@@ -1344,7 +1344,7 @@ static const int kTuneCandidates[] = {
     D_128x128_64x4, D_128x128_64x3, D_256x128_64x3, D_128x64_64x4, D_64x64_64x4, D_128x256_64x3, D_256x64_64x3, D_64x128_64x4,
     D_128x128_128x2, D_128x128_128x3, D_128x64_128x3, D_64x64_128x3, D_128x128_64x5, D_64x64_128x4, D_256x128_128x3,
     D_256x128_64x4, D_128x256_64x4, D_64x64_64x8,
-    H_256x128_x5, H_128x128_x3, H_256x64_x5, H_256x64_x6s, H_256x64_x6s2, H_128x128_k2, H_64x128_k4, H_128x64_k4, H_64x64_k4,
+    H_256x128_x5, H_128x128_x3, H_256x64_x5, H_256x64_x6s, H_256x64_x6s2, H_256x64_x6, H_128x128_k2, H_64x128_k4, H_128x64_k4, H_64x64_k4,
     G_128x128_k2, G_256x128, G_128x256, G_64x128_k4, G_128x64_k4, G_256x256_r64, G_256x128_r64, G_64x64_k4, G_64x64_k4_deep};
 
 // Training networks: the forward convolution of every layer and its data-gradient convolution get a tile each.

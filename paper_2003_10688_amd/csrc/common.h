@@ -143,7 +143,7 @@ enum {
     D_128x128_128x2 = 21, D_128x128_128x3 = 22, D_128x64_128x3 = 23, D_64x64_128x3 = 24,
     D_128x128_64x5 = 25, D_64x64_128x4 = 26, D_256x128_128x3 = 27, D_256x128_64x4 = 31, D_128x256_64x4 = 32, D_64x64_64x8 = 33,
     // H_*: 3x3 halo-in-LDS kernel (conv_halo.hip), suffix = patch DMA instructions per wave (s: single input chunk)
-    H_256x128_x5 = 41, H_128x128_x3 = 42, H_256x64_x5 = 43, H_256x64_x6s = 44, H_256x64_x6s2 = 45, H_128x128_k2 = 46, H_64x128_k4 = 47, H_128x64_k4 = 48, H_64x64_k4 = 49, H_FIRST = 41, H_LAST = 59,
+    H_256x128_x5 = 41, H_128x128_x3 = 42, H_256x64_x5 = 43, H_256x64_x6s = 44, H_256x64_x6s2 = 45, H_128x128_k2 = 46, H_64x128_k4 = 47, H_128x64_k4 = 48, H_64x64_k4 = 49, H_256x64_x6 = 50, H_FIRST = 41, H_LAST = 59,
     // G_*: eight-wave 1x1 GEMM kernel (conv_gemm8.hip); kN: reduction split N ways inside the workgroup, r64: 64-byte rows
     G_128x128_k2 = 61, G_256x128 = 62, G_128x256 = 63, G_64x128_k4 = 64, G_128x64_k4 = 65, G_256x256_r64 = 66, G_256x128_r64 = 67,
     G_64x64_k4 = 68, G_64x64_k4_deep = 69, G_64x32_k4_r256 = 70, G_FIRST = 61, G_LAST = 79,

@@ -328,7 +328,7 @@ bool halo_kernel_applies(const ConvArgs &a, int dt) {
 // several rounds of them.
 int halo_choose_tile(const ConvArgs &a) {
     const bool single = a.C == 64;
-    if (a.Cout <= 64) return a.W <= 30 ? H_256x64_x5 : (single ? H_256x64_x6s2 : 0);
+    if (a.Cout <= 64) return a.W <= 30 ? H_256x64_x5 : (single ? H_256x64_x6s2 : H_256x64_x6);
     if (a.W > 30) return 0;
     const long nt256 = (long)ceil_div(a.P, 256) * ceil_div(a.Cout, 128);
     if (nt256 >= 160) return H_256x128_x5;
@@ -344,6 +344,7 @@ sol_status launch_conv_halo(const ConvArgs &a, int tile, hipStream_t st) {
         case H_256x64_x5: return launch_halo_cfg<bf16_t, 4, 2, 1, 2, 1, 5, 4, 2>(a, st);
         case H_256x64_x6s: return launch_halo_cfg<bf16_t, 4, 2, 1, 2, 1, 6, 4, 1>(a, st);
         case H_256x64_x6s2: return launch_halo_cfg<bf16_t, 4, 2, 1, 2, 1, 6, 3, 1, 4>(a, st);   // 74 KB, <= 128 VGPRs: two workgroups per CU
+        case H_256x64_x6: return launch_halo_cfg<bf16_t, 4, 2, 1, 2, 1, 6, 4, 2>(a, st);          // wide images (up to 62 columns), several chunks of input channels
         case H_128x128_k2: return launch_halo_cfg<bf16_t, 2, 2, 2, 2, 2, 3, 4, 2>(a, st);
         case H_64x128_k4: return launch_halo_cfg<bf16_t, 1, 2, 4, 2, 2, 2, 5, 2>(a, st);
         case H_128x64_k4: return launch_halo_cfg<bf16_t, 2, 1, 4, 2, 2, 3, 8, 2>(a, st);

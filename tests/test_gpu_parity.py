@@ -185,6 +185,32 @@ def test_halo_conv_wide_single_chunk(sol, case, tile):
     assert rel_err(got, want) <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("case", [(1, 128, 56, 56, 32, False), (2, 192, 33, 50, 72, True), (3, 128, 9, 61, 64, False), (2, 64, 21, 20, 40, True),
+                                  (1, 256, 40, 62, 32, False)])
+def test_halo_conv_wide_several_chunks(sol, case):
+    """Wide images (up to 62 columns) with several 64-channel input chunks and at most 64 output channels per tile -- the
+    3x3 convolutions of a DenseNet-shaped first block -- on the tile with two patch buffers of 384 rows; plus an
+    exact-integer run on it (bit for bit)."""
+    N, C, H, W, K, res = case
+    rng = np.random.default_rng(hash(case) % (2 ** 31))
+    l, x, prm, r = make_block(sol, rng, "bf16", N, C, H, W, K, 3, 1, 1, res=res)
+    want, _, _ = orc.fused_conv(x, prm, l, r, bf16=True)
+    sol.sol_debug_set_conv_tile(50)
+    try:
+        got, _, _ = run_block(sol, "bf16", l, x, prm, r)
+        assert rel_err(got, want) <= TOL["bf16"]
+        xi = rng.integers(-2, 3, (N, C, H, W)).astype(np.float32)
+        wi = (rng.integers(-1, 2, (K, C, 3, 3)) * (rng.random((K, C, 3, 3)) < 0.03)).astype(np.float32)
+        li = wl.conv(K, 3, 1, 1, bn=False, act="none")
+        pi = {"w": wi, "bias": np.zeros(K, np.float32)}
+        wanti, _, _ = orc.fused_conv(xi, pi, li, None, bf16=True)
+        assert np.abs(wanti).max() <= 256
+        goti, _, _ = run_block(sol, "bf16", li, xi, pi, None)
+        assert np.array_equal(goti, wanti)
+    finally:
+        sol.sol_debug_set_conv_tile(0)
+
+
 def test_halo_conv_exact_integers(sol):
     """Small-integer inputs and weights: every product and partial sum is exact in fp32 and the outputs are exact
     in bf16, so the halo kernel must agree with the checker bit for bit (a wrong tap, border mask or patch row
