@@ -149,7 +149,13 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
 
     const int cpt = a.C / BK;                      // chunks per filter tap
     const int nk = a.R * a.S * cpt;
-    int tr = 0, ts = 0, tcc = 0, tap = 0;          // filter tap / chunk of the NEXT stage to issue
+    // Workgroups run in step, and chunk k of every pixel row and every weight row lies at the same offset inside rows whose
+    // pitch is a large power of two: all requests of the moment fall on the same few offsets.  Each pixel tile therefore
+    // starts the walk over the reduction at a chunk of its own (inside the first filter tap; the channel tiles of a pixel
+    // tile share it) and wraps around: the same terms, summed in an order that depends on the tile index alone.  (The same
+    // walk in the K-split, halo and whole-bottleneck kernels measured slower and is not used there.)
+    const int rot = (tile / a.ntc) % cpt;
+    int tr = 0, ts = 0, tcc = rot, tap = 0, tk = rot;   // filter tap / chunk of the NEXT stage to issue; tk: its index in the packed rows
 
     // the IDX-th DMA instruction of this wave for a stage; xsoff / wsoff: the stage's scalar offsets
     auto issue_one = [&](auto IDX, int buf, unsigned xsoff, unsigned wsoff, int tapbit) {
@@ -167,9 +173,12 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
         }
     };
     auto x_soff = [&]() { return (unsigned)((tr * a.W + ts) * a.C + tcc * BK) * ES; };
-    auto next_tap = [&]() { if (++tcc == cpt) { tcc = 0; ++tap; if (++ts == a.S) { ts = 0; ++tr; } } };
-    auto issue = [&](int kc, int buf) {
-        const unsigned xs = x_soff(), ws = (unsigned)(kc * BK) * ES;
+    auto next_tap = [&]() {
+        if (++tk == nk) { tk = 0; tcc = 0; tap = 0; ts = 0; tr = 0; return; }
+        if (++tcc == cpt) { tcc = 0; ++tap; if (++ts == a.S) { ts = 0; ++tr; } }
+    };
+    auto issue = [&](int buf) {
+        const unsigned xs = x_soff(), ws = (unsigned)(tk * BK) * ES;
         static_for<L>([&](auto IDX) { issue_one(IDX, buf, xs, ws, tap); });
         next_tap();
     };
@@ -194,7 +203,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
 
 #pragma unroll
     for (int s = 0; s < NS - 1; s++)
-        if (s < nk) issue(s, s);
+        if (s < nk) issue(s);
 
     // Epilogue operands behind the first DMAs: the compiler waits for the scale / shift loads where their two code
     // paths merge, and ahead of the DMAs that wait would put a whole memory round trip in front of the first tile
@@ -218,7 +227,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_dma_kernel(const ConvArgs a)
         __syncthreads();                           // ... for every wave; and stage kc-1 is no longer read
         const bool more = kc + NS - 1 < nk;        // a stage to prefetch during this iteration?
         const int nbuf = (kc + NS - 1) % NS, ntap = tap;
-        const unsigned nxs = x_soff(), nws = (unsigned)((kc + NS - 1) * BK) * ES;
+        const unsigned nxs = x_soff(), nws = (unsigned)(tk * BK) * ES;
         const unsigned sb = (kc % NS) * STAGE;
         read_frags(std::integral_constant<int, 0>{}, fx[0] + sb, fw[0] + sb);
         static_for<KS>([&](auto KSI) {
