@@ -167,8 +167,8 @@ sol_status sol_bottleneck_fused(const sol_tensor_desc *xd, const void *x, int mi
  *   z = relu(scale1 * conv1x1(y, w1) + shift1)                 c4 -> cz channels
  * z is contracted from y while y sits in on-chip memory, rounded to bf16 as stored; y is written once and not read back.
  *   td, t       input of the first convolution, NHWC, SOL_BF16, td->c = 256
- *   c4          a multiple of 128, at most 1024;  cz = 256; anything else -> SOL_ERR_UNSUPPORTED (run the two layers
- *               through sol_conv2d_fused)
+ *   c4          a multiple of 128, at most 1024;  cz = 256 or 512; anything else -> SOL_ERR_UNSUPPORTED (run the two
+ *               layers through sol_conv2d_fused)
  *   w3_packed   sol_pack_conv_weights of cd = {c4, 256, 1,1, 1,1, 0,0};  w1_packed: {cz, c4, 1,1, 1,1, 0,0}
  *   scale*, shift*  device fp32 per output channel of each convolution (sol_fold_bn), all required
  *   shortcut    NHWC [n][h][w][c4], added before the first ReLU, required

@@ -13,9 +13,10 @@
 // One pipeline for everything: operands reach LDS by DMA (buffer_load ... lds) into a ring of 16 KB slots, one
 // workgroup barrier per two slots, fragment reads as opaque statements ordered by hand, every DMA issued unconditionally
 // (beyond the end through a size-0 resource) so that the in-order vmcnt bookkeeping is static.  A pass is eight slots
-// (two per barrier):
+// (two per barrier) for WZ = 256:
 //   Y-stage k (k < 4):   W3[pass rows 0..127][64 k .. 64 k + 63]      128 rows x 128 B;  y-pass += t[:, plane k] . that
 //   Z-stage u (u < 4):   W1[rows 0..255][128 pass + 32 u .. + 31]     256 rows x  64 B;  z += y-pass[:, 32 u ..] . that
+// and twelve for WZ = 512: the W1 rows of a 32-channel group are then two adjacent slots (rows 0..255, 256..511).
 // Between them the pass's accumulators get affine + shortcut + ReLU, are rounded and parked in LDS (the shortcut rows
 // and the affine constants also come from LDS: the rows by DMA one pass ahead, the constants once); the store of the
 // pass to y is issued from LDS behind the MFMAs of the first Z-stage.  A wave keeps its pixels of t as fragments in registers.
@@ -44,7 +45,10 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
     constexpr int NW = 8, BP = 64, PC = 128;
-    constexpr int UY = WM / 64, UZ = PC / 32, UPP = UY + UZ;          // slots of a pass
+    constexpr int ZH = WZ / 256;                                      // 256-row halves of a 32-channel group of W1 rows
+    constexpr int UY = WM / 64, UZ = PC / 32 * ZH, UPP = UY + UZ;     // slots of a pass
+    constexpr int SP = UPP / 2;                                       // stages (two slots, one barrier) of a pass
+    constexpr int NB = WZ / 128;                                      // 32-channel blocks of z per wave
     constexpr int SLOT = 16384, L = SLOT / 1024 / NW;                 // DMA instructions per wave and slot
     constexpr int PLANE = BP * 128;                                   // 64 pixels x 64 channels
     // LDS: the parked y pass, the shortcut rows of a pass, the affine constants of y, the ring.  The pixel tile t is needed
@@ -52,7 +56,7 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
     // half of the LDS traffic of the Y-stages); it lands in the last two ring slots, which join the ring afterwards.
     constexpr int YCH_OFF = 0, RB_OFF = YCH_OFF + 2 * PLANE, CST_OFF = RB_OFF + 2 * PLANE, RING_OFF = CST_OFF + 8192,
                   T_OFF = RING_OFF + (NS - 2) * SLOT, LDSB = RING_OFF + NS * SLOT + 1024;
-    static_assert(WM == 256 && WZ == 256 && UPP == 8, "slots of 16 KB: 128 rows of W3 x 128 B, 256 rows of W1 x 64 B");
+    static_assert(WM == 256 && (WZ == 256 || WZ == 512), "slots of 16 KB: 128 rows of W3 x 128 B, 256 rows of W1 x 64 B");
     static_assert(NS == 6 && LDSB <= 160 * 1024 && UY * PLANE == 2 * SLOT, "ring: three stages of two slots");
     static_assert(NW * 32 * (64 + 4) * 4 <= NS * SLOT, "the epilogue strips of z go over the dead ring");
 
@@ -115,7 +119,8 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
             const unsigned soff = (unsigned)(pe(q) * PC) * (unsigned)(WM * 2) + (unsigned)(pos * 128);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w3r : nullr, (__attribute__((address_space(3))) void *)dst, 16, woY[i], soff, 0, 0);
         } else {
-            const unsigned soff = (unsigned)((pe(q) * PC + (pos - UY) * 32) * 2);
+            constexpr int zi = pos - UY, u = zi / ZH, h = zi % ZH;   // 32-channel group of the pass, half of the W1 rows
+            const unsigned soff = (unsigned)((pe(q) * PC + u * 32) * 2) + (unsigned)h * (unsigned)(256 * 2) * (unsigned)C4;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(real ? w1r : nullr, (__attribute__((address_space(3))) void *)dst, 16, woZ[i], soff, 0, 0);
         }
     };
@@ -147,7 +152,7 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
     // fragment addresses (k-step / slot / plane are added at the point of use)
     const unsigned sw128 = (unsigned)swz<128>(lr), sw64 = (unsigned)swz<64>(lr);
     const unsigned fwy0 = lds_addr(ring) + (unsigned)((wc * 32 + lr) * 128) + ((lh ^ sw128) << 4);       // W3 rows of this wave's 32 channels
-    const unsigned fwz0 = lds_addr(ring) + (unsigned)((wc * 64 + lr) * 64) + ((lh ^ sw64) << 4);         // W1 rows of its 64 channels of z
+    const unsigned fwz0 = lds_addr(ring) + (unsigned)((wc * (WZ / 4) + lr) * 64) + ((lh ^ sw64) << 4);   // W1 rows of its WZ / 4 channels of z
     const unsigned fpx0 = (unsigned)((wp * 32 + lr) * 128) + ((lh ^ sw128) << 4);                        // its pixel rows inside a plane
     const unsigned ft0 = lds_addr(lds + T_OFF) + fpx0, fy0 = lds_addr(lds + YCH_OFF) + fpx0;
     // epilogue of a y pass: this lane's pixel row, channel group g -> 4 channels 8 g + 4 lh of the wave's 32
@@ -179,9 +184,11 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
     static_for<UY>([&](auto C) { static_for<4>([&](auto K) { landed(ft[decltype(C)::value][decltype(K)::value]); }); });
     __builtin_amdgcn_s_barrier();                                      // every wave has its fragments: the tile's space joins the ring
 
-    f32x16_t zacc[2][1], yacc[2];      // y: two accumulators taking alternate k-steps (a wave's MFMAs of a Y-stage would otherwise form one dependent chain)
+    f32x16_t zacc[NB / 2][2][1], yacc[2];   // z: block b of the wave = zacc[b / 2][b % 2]; y: two accumulators taking alternate k-steps (a wave's MFMAs of a Y-stage would otherwise form one dependent chain)
 #pragma unroll
-    for (int e = 0; e < 16; e++) { zacc[0][0][e] = 0.f; zacc[1][0][e] = 0.f; }
+    for (int b = 0; b < NB; b++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) zacc[b / 2][b % 2][0][e] = 0.f;
 
     // A wave has one (Y) or two (Z) MFMAs per k-step: too little to hide an LDS round trip behind.  All fragments of a
     // stage (two slots) are therefore requested at once and the MFMAs follow back to back, each waiting only for its own.
@@ -217,23 +224,47 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
             landed(fz[k][0]);
             landed(fz[k][1]);
             landed(fyy[k]);
-            Mma<bf16_t>::run(zacc[0][0], fz[k][0], fyy[k]);
-            Mma<bf16_t>::run(zacc[1][0], fz[k][1], fyy[k]);
+            Mma<bf16_t>::run(zacc[0][0][0], fz[k][0], fyy[k]);
+            Mma<bf16_t>::run(zacc[0][1][0], fz[k][1], fyy[k]);
             between(K);
+        });
+    };
+    // WZ = 512: a stage is ONE 32-channel group of the pass, all 512 rows of W1 (two adjacent slots): two k-steps, four blocks
+    auto stageZ2 = [&](auto U, unsigned sb, auto &&between) {
+        constexpr int u = decltype(U)::value;
+        constexpr unsigned pb = (unsigned)((u >> 1) * PLANE);
+        u32x4_t gz[2][4];
+        static_for<2>([&](auto K) {
+            constexpr int k = decltype(K)::value;
+            const unsigned aw = xor_add(fwz0, (unsigned)(k * 32), sb);
+            static_for<4>([&](auto B) { lds_read16<decltype(B)::value * 32 * 64>(gz[k][decltype(B)::value], aw); });
+            lds_read16<0>(fyy[k], xor_add(fy0, (unsigned)(((u & 1) * 2 + k) * 32), pb));
+        });
+        static_for<2>([&](auto K) {
+            constexpr int k = decltype(K)::value;
+            wait_lgkmcnt<5 - 5 * k>();
+            static_for<4>([&](auto B) { landed(gz[k][decltype(B)::value]); });
+            landed(fyy[k]);
+            static_for<4>([&](auto B) {
+                constexpr int b = decltype(B)::value;
+                Mma<bf16_t>::run(zacc[b / 2][b % 2][0], gz[k][b], fyy[k]);
+                if constexpr (b & 1) between(std::integral_constant<int, 2 * k + b / 2>{});
+            });
         });
     };
 
     // A stage = two slots = one barrier (with one slot per barrier the waits, the barrier and the DMA issue cost as much as
-    // the four MFMAs of a slot).  A pass is four stages: Y 0-1, Y 2-3 + the epilogue of y, Z 0-1 (behind the store of the
-    // pass and the fetch of the next shortcut rows), Z 2-3.  Stage s issues the slots of stage s + 2.
+    // the four MFMAs of a slot).  A pass is SP stages: Y 0-1, Y 2-3 + the epilogue of y, then the Z stages (two for
+    // WZ = 256: groups 0-1, 2-3; four for WZ = 512: one group each), the first of them behind the store of the pass and the
+    // fetch of the next shortcut rows.  Stage s issues the slots of stage s + 2.
     int slot = 0, islot = NS - 2;
     for (int q = 0; q < npass; q++) {
-        static_for<4>([&](auto POS) {
+        static_for<SP>([&](auto POS) {
             constexpr int pos = decltype(POS)::value;
             // in flight behind this stage's slots: the two slots issued one stage ago, and what the first Z stage issues at
             // its END (the two stores of the y pass and the next shortcut rows), which is behind that stage's own slots and
             // in front of the next stage's: it counts for the two stages that follow a first Z stage
-            constexpr int N0 = 2 * L, N = N0 + ((pos == 3 || pos == 0) ? 2 + L : 0);
+            constexpr int N0 = 2 * L, N = N0 + ((pos == 3 || pos == 4 % SP) ? 2 + L : 0);
             if constexpr (pos == 0) {                                  // no first Z stage in front of the first pass
                 if (q == 0) wait_vmcnt<N0>(); else wait_vmcnt<N>();
             } else {
@@ -244,7 +275,7 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
             // issues in order, and a DMA instruction waits its turn at the CU's address unit (about 18 cycles per KB, all
             // eight waves queue there right behind the barrier) -- time in which the matrix pipe would otherwise idle
             auto dma = [&](auto J) {
-                constexpr int j = decltype(J)::value, ipos = ((pos + 2) % 4) * 2 + j / L, carry = (pos + 2) / 4;
+                constexpr int j = decltype(J)::value, ipos = ((pos + 2) % SP) * 2 + j / L, carry = (pos + 2) / SP;
                 issue_one(std::integral_constant<int, ipos>{}, std::integral_constant<int, j % L>{}, islot + j / L, q + carry, q + carry < npass);
             };
             const unsigned sb = (unsigned)(slot * SLOT);
@@ -286,7 +317,8 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
                     wait_lgkmcnt<0>();
                 }
             } else {
-                stageZ(std::integral_constant<int, 2 * (pos - 2)>{}, sb, dma);
+                if constexpr (WZ == 256) stageZ(std::integral_constant<int, 2 * (pos - 2)>{}, sb, dma);
+                else stageZ2(std::integral_constant<int, pos - 2>{}, sb, dma);
                 if constexpr (pos == 2) {
                     // under this stage's MFMAs: the parked y pass goes to memory (two 16-byte pieces per lane, from LDS), and
                     // the next shortcut rows are fetched (every wave is past the epilogue that read the current ones)
@@ -310,21 +342,25 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
     ConvArgs ca;
     ca.y = a.z; ca.res = nullptr; ca.scale = a.s1; ca.shift = a.h1; ca.prepool = nullptr; ca.argmax = nullptr;
     ca.Cout = WZ; ca.ldy = WZ; ca.P = a.P; ca.act = SOL_ACT_RELU; ca.pool = 0;
-    const int cw = wc * 64, mw = p0 + wp * 32;
-    const Affine8 aff = load_affine_unconditional<2>(ca, lane, cw);
+    const int mw = p0 + wp * 32;
     ResidualRegs<bf16_t, 1, 2> none;
     none.on = false;
     wait_vmcnt<0>();
     wait_lgkmcnt<0>();
     __builtin_amdgcn_s_barrier();                                      // every wave is done with the ring
-    conv_epilogue_auto<bf16_t, 1, 2>(ca, zacc, reinterpret_cast<float *>(ring), wave, lane, mw, cw, aff, LinearRows{a.P}, none);
+    static_for<NB / 2>([&](auto H) {                                   // 64 channels at a time through this wave's strip
+        constexpr int h = decltype(H)::value;
+        const int cw = wc * (WZ / 4) + h * 64;
+        const Affine8 aff = load_affine_unconditional<2>(ca, lane, cw);
+        conv_epilogue_auto<bf16_t, 1, 2>(ca, zacc[h], reinterpret_cast<float *>(ring), wave, lane, mw, cw, aff, LinearRows{a.P}, none);
+    });
 #endif
 }
 
-// bf16; 256 -> C4 -> 256 channels, C4 a multiple of 128 up to 1024 (the affine constants of y sit in 8 KB of LDS);
+// bf16; 256 -> C4 -> 256 or 512 channels, C4 a multiple of 128 up to 1024 (the affine constants of y sit in 8 KB of LDS);
 // any pixel count (tiles of 64, the last one ragged); tensors below 2 GB (32-bit byte offsets)
 bool xr_kernel_applies(int dt, long P, int WM, int C4, int WZ) {
-    if (dt != SOL_BF16 || WM != 256 || WZ != 256 || C4 % 128 != 0 || C4 < 128 || C4 > 1024) return false;
+    if (dt != SOL_BF16 || WM != 256 || (WZ != 256 && WZ != 512) || C4 % 128 != 0 || C4 < 128 || C4 > 1024) return false;
     if (P <= 0) return false;
     return (double)P * C4 * 2.0 < 2147483648.0;
 }
@@ -337,7 +373,8 @@ sol_status launch_conv_xr(const XrLaunch &b, hipStream_t st) {
     a.P = (int)b.P; a.C4 = b.C4;
     a.ntiles = (a.P + 63) / 64;
     const int grid = ((a.ntiles + 7) / 8) * 8;
-    hipLaunchKernelGGL((conv_xr_kernel<256, 256, 6>), dim3(grid), dim3(512), 0, st, a);
+    if (b.WZ == 256) hipLaunchKernelGGL((conv_xr_kernel<256, 256, 6>), dim3(grid), dim3(512), 0, st, a);
+    else hipLaunchKernelGGL((conv_xr_kernel<256, 512, 6>), dim3(grid), dim3(512), 0, st, a);
     SOL_HIP(hipGetLastError());
     return SOL_OK;
 }

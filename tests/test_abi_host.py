@@ -167,17 +167,18 @@ def test_plan_fuses_stem_and_pool_only_when_it_may(sol):
     for i in ends:
         want[i - 2] = want[i - 1] = i
     # the last 1x1 convolution of an identity bottleneck of stage 2 (256 -> 1024 channels at 14x14) and the first 1x1
-    # convolution of the next bottleneck (1024 -> 256) run as one expand-reduce launch: four pairs
+    # convolution of the next bottleneck (1024 -> 256, and 1024 -> 512 into the last stage) run as one expand-reduce launch:
+    # five pairs
     starts = [i for i, l in enumerate(wk.layers[:-1]) if l["kind"] == "conv" and l["cout"] == 1024 and l.get("res", -1) >= 0
-              and wk.layers[l["res"]]["act"] != "none" and wk.layers[i + 1]["kind"] == "conv" and wk.layers[i + 1]["cout"] == 256
+              and wk.layers[l["res"]]["act"] != "none" and wk.layers[i + 1]["kind"] == "conv" and wk.layers[i + 1]["cout"] in (256, 512)
               and wk.layers[i + 1]["kh"] == 1]
-    assert len(starts) == 4
+    assert len(starts) == 5
     for i in starts:
         want[i + 1] = i
     assert r == want
     st_, h_ = _create(sol, wk.layers, wk.in_shape, sol.BF16, 0)
     bs = C.c_int(-2)
-    assert [L.sol_network_layer_xr(h_, i, C.byref(bs)) or bs.value for i in starts] == [1] * 4
+    assert [L.sol_network_layer_xr(h_, i, C.byref(bs)) or bs.value for i in starts] == [1] * 5
     assert L.sol_network_layer_xr(h_, 0, C.byref(bs)) == 0 and bs.value == -1
     assert L.sol_network_set_layer_xr(h_, starts[0], 0) == 0 and L.sol_network_layer_xr(h_, starts[0], C.byref(bs)) == 0 and bs.value == 0
     assert L.sol_network_layer_fused_into(h_, starts[0] + 1, C.byref(t)) == 0 and t.value == starts[0] + 1

@@ -11,7 +11,7 @@ from paper_2003_10688_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
-WM = WZ = 256
+WM = 256
 
 
 @pytest.fixture(scope="module")
@@ -36,7 +36,7 @@ def _norm_err(g, r):
     return float(np.linalg.norm(np.asarray(g, np.float64) - r) / max(np.linalg.norm(r), 1e-30))
 
 
-def _case(rng, N, H, W, C4, bias_std=0.3):
+def _case(rng, N, H, W, C4, bias_std=0.3, WZ=256):
     t = wl.to_bf16_grid(rng.standard_normal((N, WM, H, W)))
     r = wl.to_bf16_grid(rng.standard_normal((N, C4, H, W)))
     ls = [wl.conv(C4, 1, p=0), wl.conv(WZ, 1, p=0)]
@@ -60,7 +60,7 @@ def _gpu(sol, t, r, ls, prm, fold=True):
             sc, sh = torch.ones(l["cout"], device="cuda:0"), sol.dev_f32(p["bias"])
         args.append((wp, sc, sh))
     (w3, s3, h3), (w1, s1, h1) = args
-    y, z = sol.sol_expand_reduce_fused(sol.to_device_nhwc(t, sol.BF16), ls[0]["cout"], w3, s3, h3, sol.to_device_nhwc(r, sol.BF16), WZ, w1, s1, h1)
+    y, z = sol.sol_expand_reduce_fused(sol.to_device_nhwc(t, sol.BF16), ls[0]["cout"], w3, s3, h3, sol.to_device_nhwc(r, sol.BF16), ls[1]["cout"], w1, s1, h1)
     torch.cuda.synchronize()
     return sol.to_host_nchw(y), sol.to_host_nchw(z)
 
@@ -76,6 +76,8 @@ XR_CASES = [
     (1, 8, 8, 1024), (5, 16, 16, 1024), (2, 8, 16, 512), (3, 8, 8, 128), (7, 4, 16, 640), (16, 14, 14, 1024),
     # ragged last tile: 196 = 3 * 64 + 4 pixels, 49 pixels (less than a tile), 5 * 81 = 405 = 6 * 64 + 21
     (1, 14, 14, 1024), (1, 7, 7, 512), (5, 9, 9, 256),
+    # 512 output channels (the pair across a stage border): the second contraction runs one 32-channel group per stage
+    (1, 8, 8, 1024, 512), (5, 16, 16, 1024, 512), (3, 8, 8, 128, 512), (7, 4, 16, 640, 512), (1, 14, 14, 1024, 512), (5, 9, 9, 256, 512),
 ]
 
 
@@ -83,9 +85,10 @@ XR_CASES = [
 def test_expand_reduce_fused_matches_oracle(sol, case):
     """Both outputs of the pair kernel against the checker's two fused layers (the first rounding its stored output to
     bf16, as the kernel rounds y where it parks it for the second contraction), element-wise."""
-    N, H, W, C4 = case
-    rng = np.random.default_rng(300 + H * W + C4)
-    t, r, ls, prm = _case(rng, N, H, W, C4)
+    N, H, W, C4 = case[:4]
+    WZ = case[4] if len(case) > 4 else 256
+    rng = np.random.default_rng(300 + H * W + C4 + WZ - 256)
+    t, r, ls, prm = _case(rng, N, H, W, C4, WZ=WZ)
     print(f"expand-reduce {case}", flush=True)
     gy, gz = _gpu(sol, t, r, ls, prm)
     wy, wz = _ref(t, r, ls, prm)
@@ -98,7 +101,7 @@ def test_expand_reduce_fused_exact_integers(sol):
     """Small-integer inputs and sparse +-1 weights, unit scales: every intermediate is exact in bf16 and in fp32, so the
     kernel must reproduce the checker bit for bit (channel order of both contractions, pass order, shortcut, stores)."""
     rng = np.random.default_rng(6)
-    for (N, H, W, C4) in [(2, 8, 8, 1024), (1, 8, 24, 384)]:
+    for (N, H, W, C4, WZ) in [(2, 8, 8, 1024, 256), (1, 8, 24, 384, 256), (2, 8, 8, 1024, 512), (1, 9, 9, 256, 512)]:
         t = rng.integers(-2, 3, (N, WM, H, W)).astype(np.float32)
         r = rng.integers(-3, 4, (N, C4, H, W)).astype(np.float32)
         ls = [wl.conv(C4, 1, p=0, bn=False), wl.conv(WZ, 1, p=0, bn=False)]
@@ -125,7 +128,7 @@ def test_expand_reduce_fused_rejects_what_it_cannot_do(sol):
 
     for t, c4, r, cz in [(torch.zeros((1, 8, 8, 128), **bf), 512, torch.zeros((1, 8, 8, 512), **bf), 256),      # 128 input channels
                          (torch.zeros((1, 8, 8, 256), **bf), 2048, torch.zeros((1, 8, 8, 2048), **bf), 256),    # too wide
-                         (torch.zeros((1, 8, 8, 256), **bf), 1024, torch.zeros((1, 8, 8, 1024), **bf), 512),    # 512 output channels
+                         (torch.zeros((1, 8, 8, 256), **bf), 1024, torch.zeros((1, 8, 8, 1024), **bf), 384),    # 384 output channels
                          (torch.zeros((1, 8, 8, 256), device="cuda:0"), 1024, torch.zeros((1, 8, 8, 1024), device="cuda:0"), 256)]:   # fp32
         with pytest.raises(sol.SolError) as e:
             call(t, c4, r, cz)
@@ -147,7 +150,7 @@ def test_network_runs_expand_reduce_pairs(sol):
     net = sol.Network(L, wk.in_shape, sol.BF16)
     net.set_params(wk.params)
     starts = [i for i in range(len(L)) if net.xr_state(i) >= 0]
-    assert len(starts) == 4, starts                # bottlenecks 2-5 of the 1024-channel stage, each with the reduce layer behind it
+    assert len(starts) == 5, starts                # bottlenecks 2-6 of the 1024-channel stage, each with the reduce layer behind it (the last one's has 512 channels)
     assert all(net.xr_state(i) == 0 for i in starts)     # three tiles of 64 pixels: the plan's heuristic leaves such pairs alone
     for i in starts:
         net.set_xr(i, 0)
@@ -195,7 +198,7 @@ def test_autotune_chooses_between_pair_and_layers(sol):
     x = sol.to_device_nhwc(wk.x, sol.BF16)
     tuned = net.autotune(x, reps=2)
     pairs = {k: v for k, v in tuned.items() if str(k).endswith("x")}
-    assert len(pairs) == 4 and all(v in (0, 1) for v in pairs.values()), tuned
+    assert len(pairs) == 5 and all(v in (0, 1) for v in pairs.values()), tuned
     y = sol.to_host_nchw(net.forward(x))
     assert _norm_err(y.reshape(outs[-1].shape), outs[-1]) <= TOL["bf16"]
     net2 = sol.Network(wk.layers, wk.in_shape, sol.BF16)      # the saved plan restores the same launches
@@ -205,7 +208,7 @@ def test_autotune_chooses_between_pair_and_layers(sol):
 
 
 def test_full_size_expand_reduce_pairs_sampled(sol):
-    """The pair launches of the benchmark's pass (batch 64, 14x14, 256 -> 1024 -> 256 channels), in the network object
+    """The pair launches of the benchmark's pass (batch 64, 14x14, 256 -> 1024 -> 256 or 512 channels), in the network object
     with its lean plan: random stored inputs, both outputs checked at sampled pixels -- y at sampled (pixel, channel)
     points; z from the checker's y at ALL channels of the sampled pixels."""
     wk = wl.config(3)
@@ -214,7 +217,7 @@ def test_full_size_expand_reduce_pairs_sampled(sol):
     net.set_params(P)
     x = sol.to_device_nhwc(wk.x[:1].repeat(wk.in_shape[0], 0), sol.BF16)
     starts = [i for i in range(len(L)) if net.xr_state(i) == 1]
-    assert len(starts) == 4
+    assert len(starts) == 5 and [L[i + 1]["cout"] for i in starts] == [256] * 4 + [512]
     rng = np.random.default_rng(77)
     N, H, W = wk.in_shape[0], 14, 14
     for i in starts:
@@ -226,7 +229,7 @@ def test_full_size_expand_reduce_pairs_sampled(sol):
         net.run_layer(i, x)
         torch.cuda.synchronize()
         gy, gz = sol.to_host_nchw(net.layer_output(i)), sol.to_host_nchw(net.layer_output(i + 1))
-        assert gy.shape == (N, 1024, H, W) and gz.shape == (N, 256, H, W)
+        assert gy.shape == (N, 1024, H, W) and gz.shape == (N, L[i + 1]["cout"], H, W)
         pix = np.stack([rng.integers(0, s, 48) for s in (N, H, W)], 1)
         pix[:3] = [[0, 0, 0], [N - 1, H - 1, W - 1], [N // 2, 0, W - 1]]
         coords = np.array([[n, k, h, w] for (n, h, w) in pix for k in range(1024)], np.int32)
