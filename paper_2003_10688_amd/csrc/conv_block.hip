@@ -182,7 +182,7 @@ __global__ void __launch_bounds__(NW * 64, 512 / (NW * 64)) conv_block_kernel(co
     // A bare ds_write: a store the compiler knows of would wait for the next phase's DMAs, which are already in flight.
     auto park = [&](const f32x16_t &acc, int g, const float4 &sc, const float4 &sh, unsigned plane_bytes, int row, int ch) {
         float v0 = acc[4 * g] * sc.x + sh.x, v1 = acc[4 * g + 1] * sc.y + sh.y, v2 = acc[4 * g + 2] * sc.z + sh.z, v3 = acc[4 * g + 3] * sc.w + sh.w;
-        v0 = v0 > 0.f ? v0 : 0.f; v1 = v1 > 0.f ? v1 : 0.f; v2 = v2 > 0.f ? v2 : 0.f; v3 = v3 > 0.f ? v3 : 0.f;
+        v0 = __builtin_fmaxf(v0, 0.f); v1 = __builtin_fmaxf(v1, 0.f); v2 = __builtin_fmaxf(v2, 0.f); v3 = __builtin_fmaxf(v3, 0.f);   // one v_max each; a NaN becomes 0
         const unsigned long long pk = (unsigned long long)pack_bf16x2(v0, v1) | ((unsigned long long)pack_bf16x2(v2, v3) << 32);
         const unsigned dst = lds_addr(t1) + (unsigned)(ch >> 6) * plane_bytes + (unsigned)(row * 128) +
                              (unsigned)((((ch & 63) >> 3) ^ swz<128>(row)) << 4) + (unsigned)((ch & 7) * 2);

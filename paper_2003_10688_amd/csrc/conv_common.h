@@ -283,7 +283,7 @@ __device__ __forceinline__ void conv_epilogue(const ConvArgs &a, f32x16_t (&acc)
         }
         if (a.act == SOL_ACT_RELU) {
 #pragma unroll
-            for (int e = 0; e < 8; e++) v[e] = v[e] > 0.f ? v[e] : 0.f;
+            for (int e = 0; e < 8; e++) v[e] = __builtin_fmaxf(v[e], 0.f);     // one v_max: a NaN becomes 0, as with a compare and a select
         }
     };
     // compile-time loop over the pixel blocks: the accumulator index must be a constant
@@ -370,7 +370,7 @@ __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16
     float *strip = lds_f + wave * (32 * ERS);
     T *__restrict__ yg = static_cast<T *>(a.y);
     const int ecg = lane % LPR, erow = lane / LPR;
-    const bool relu = a.act == SOL_ACT_RELU;     // wave-uniform
+    const float lim = a.act == SOL_ACT_RELU ? 0.f : __builtin_nanf("");     // wave-uniform lower bound of the outputs (none: NaN)
     const unsigned coff = (unsigned)(cw + ecg * 8);
     static_for<TP>([&](auto J) {
         constexpr int j = decltype(J)::value;
@@ -396,7 +396,7 @@ __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16
                 for (int e = 0; e < 8; e++) v[e] += rv[e];
             }
 #pragma unroll
-            for (int e = 0; e < 8; e++) v[e] = (relu && !(v[e] > 0.f)) ? 0.f : v[e];   // as the general epilogue: NaN stays NaN without ReLU, ReLU maps it to 0
+            for (int e = 0; e < 8; e++) v[e] = __builtin_fmaxf(v[e], lim);   // one v_max; as the general epilogue: NaN stays NaN without ReLU (the maximum with a NaN is the other operand), ReLU maps it to 0
             if (rowoff.valid(j * 32 + erow + ps * RPS)) store_vec8<T>(yg + rowoff(j * 32 + erow + ps * RPS) + coff, v);
         }
         wave_lds_fence();

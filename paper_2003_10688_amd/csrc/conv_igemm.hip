@@ -158,7 +158,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
 #pragma unroll
                     for (int e = 0; e < EPC; e++) {
                         float f = Elem<T>::load(el + e);
-                        if (pre) { f = f * psc[e] + psh[e]; f = f > 0.f ? f : 0.f; }
+                        if (pre) { f = f * psc[e] + psh[e]; f = __builtin_fmaxf(f, 0.f); }
                         f = (ok && (int)(cfirst + e) < a.Cvalid) ? f : 0.f;       // padding taps and padding channels are zeros, not relu(shift)
                         Elem<T>::store(el + e, f);
                     }
@@ -173,7 +173,7 @@ __global__ void __launch_bounds__(WP *WC * 64) conv_igemm_kernel(const ConvArgs 
                 T v = rg[i];
                 if (pre || partial) {
                     float f = Elem<T>::load(&v);
-                    if (pre) { f = f * gsc + gsh; f = f > 0.f ? f : 0.f; }
+                    if (pre) { f = f * gsc + gsh; f = __builtin_fmaxf(f, 0.f); }
                     f = (((okm >> i) & 1u) && gvalid) ? f : 0.f;
                     Elem<T>::store(&v, f);
                 }

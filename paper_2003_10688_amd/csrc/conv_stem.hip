@@ -369,7 +369,7 @@ __global__ void __launch_bounds__(256) conv_stem_pool_kernel(const ConvArgs a, i
                     const float4 sc = *reinterpret_cast<const float4 *>(&aff[0][c]), sf = *reinterpret_cast<const float4 *>(&aff[1][c]);
                     float v0 = acc[i][jb][4 * g + 0] * sc.x + sf.x, v1 = acc[i][jb][4 * g + 1] * sc.y + sf.y;
                     float v2 = acc[i][jb][4 * g + 2] * sc.z + sf.z, v3 = acc[i][jb][4 * g + 3] * sc.w + sf.w;
-                    v0 = v0 > 0.f ? v0 : 0.f; v1 = v1 > 0.f ? v1 : 0.f; v2 = v2 > 0.f ? v2 : 0.f; v3 = v3 > 0.f ? v3 : 0.f;
+                    v0 = __builtin_fmaxf(v0, 0.f); v1 = __builtin_fmaxf(v1, 0.f); v2 = __builtin_fmaxf(v2, 0.f); v3 = __builtin_fmaxf(v3, 0.f);   // one v_max each; a NaN becomes 0
                     uint2 pk = make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
                     if (!real) pk = make_uint2(0, 0);
                     *reinterpret_cast<uint2 *>(&ct[ctoff[jb] + 32 * i + 8 * g]) = pk;

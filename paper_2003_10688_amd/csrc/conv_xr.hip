@@ -309,7 +309,7 @@ __global__ void __launch_bounds__(512) conv_xr_kernel(const XrArgs a) {
                         float v1 = (yacc[0][4 * g + 1] + yacc[1][4 * g + 1]) * __uint_as_float(sc[g].y) + __uint_as_float(sh[g].y) + __uint_as_float(lo & 0xffff0000u);
                         float v2 = (yacc[0][4 * g + 2] + yacc[1][4 * g + 2]) * __uint_as_float(sc[g].z) + __uint_as_float(sh[g].z) + __uint_as_float(hi << 16);
                         float v3 = (yacc[0][4 * g + 3] + yacc[1][4 * g + 3]) * __uint_as_float(sc[g].w) + __uint_as_float(sh[g].w) + __uint_as_float(hi & 0xffff0000u);
-                        v0 = v0 > 0.f ? v0 : 0.f; v1 = v1 > 0.f ? v1 : 0.f; v2 = v2 > 0.f ? v2 : 0.f; v3 = v3 > 0.f ? v3 : 0.f;
+                        v0 = __builtin_fmaxf(v0, 0.f); v1 = __builtin_fmaxf(v1, 0.f); v2 = __builtin_fmaxf(v2, 0.f); v3 = __builtin_fmaxf(v3, 0.f);   // one v_max each; a NaN becomes 0
                         const unsigned long long pk = (unsigned long long)pack_bf16x2(v0, v1) | ((unsigned long long)pack_bf16x2(v2, v3) << 32);
                         const unsigned ydst_lds = ych_base + eoff[g];
                         asm volatile("ds_write_b64 %0, %1" ::"v"(ydst_lds), "v"(pk) : "memory");

@@ -73,7 +73,7 @@ __global__ void __launch_bounds__(512) linear_kernel(const ConvArgs a) {
         for (int w = 0; w < NWV; w++) t += red[w][row][f0 + e];
         t = t * (a.scale ? a.scale[o] : 1.f) + (a.shift ? a.shift[o] : 0.f);
         if (resg) t += Elem<T>::load(resg + (size_t)m * N + o);
-        if (a.act == SOL_ACT_RELU) t = t > 0.f ? t : 0.f;
+        if (a.act == SOL_ACT_RELU) t = __builtin_fmaxf(t, 0.f);
         Elem<T>::store(yg + (size_t)m * a.ldy + o, t);
     }
 }
