@@ -360,6 +360,9 @@ struct LinearRowOffset {
     unsigned first, cout;
     __device__ __forceinline__ unsigned operator()(int r) const { return first + (unsigned)r * cout; }
     __device__ __forceinline__ bool valid(int) const { return true; }     // every row of an interior tile is stored
+    // offset of row lane_row + r as a per-lane part, computed once, plus a wave-uniform part (no multiply per store)
+    __device__ __forceinline__ unsigned lane_base(int lane_row) const { return first + (unsigned)lane_row * cout; }
+    __device__ __forceinline__ unsigned at(unsigned lb, int r) const { return lb + (unsigned)r * cout; }
 };
 template <typename T, int TP, int TC, bool RES, typename RowOff>
 __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16_t (&acc)[TC][TP], float *lds_f, int wave, int lane,
@@ -372,6 +375,7 @@ __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16
     const int ecg = lane % LPR, erow = lane / LPR;
     const float lim = a.act == SOL_ACT_RELU ? 0.f : __builtin_nanf("");     // wave-uniform lower bound of the outputs (none: NaN)
     const unsigned coff = (unsigned)(cw + ecg * 8);
+    const unsigned lb = rowoff.lane_base(erow);
     static_for<TP>([&](auto J) {
         constexpr int j = decltype(J)::value;
 #pragma unroll
@@ -397,7 +401,7 @@ __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16
             }
 #pragma unroll
             for (int e = 0; e < 8; e++) v[e] = __builtin_fmaxf(v[e], lim);   // one v_max; as the general epilogue: NaN stays NaN without ReLU (the maximum with a NaN is the other operand), ReLU maps it to 0
-            if (rowoff.valid(j * 32 + erow + ps * RPS)) store_vec8<T>(yg + rowoff(j * 32 + erow + ps * RPS) + coff, v);
+            if (rowoff.valid(j * 32 + erow + ps * RPS)) store_vec8<T>(yg + rowoff.at(lb, j * 32 + ps * RPS) + coff, v);
         }
         wave_lds_fence();
     });

@@ -20,6 +20,8 @@ struct StemRowOffset {   // same map as StemRows as an element offset; rows past
     int hleft, wleft;            // output rows / columns from that pixel to the image border
     __device__ __forceinline__ unsigned operator()(int r) const { return base + ((unsigned)(r >> 4) * wo + (unsigned)(r & 15)) * cout; }
     __device__ __forceinline__ bool valid(int r) const { return (r >> 4) < hleft && (r & 15) < wleft; }
+    __device__ __forceinline__ unsigned lane_base(int lane_row) const { return (unsigned)lane_row; }      // the map is not linear in the row: kept as the row
+    __device__ __forceinline__ unsigned at(unsigned lb, int r) const { return (*this)((int)lb + r); }
 };
 
 struct StemRows {   // tile row (py*16+px) of the 8x16 output block -> output pixel index
