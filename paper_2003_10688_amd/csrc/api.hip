@@ -1579,14 +1579,14 @@ sol_status sol_network_graph_create(sol_network *net, const void *x, void *y, vo
     const sol_status rs = run_layers(net, x, y, workspace, workspace_bytes, 0, last, st);
     hipGraph_t graph = nullptr;
     const hipError_t ce = hipStreamEndCapture(st, &graph);
-    if (rs != SOL_OK) { if (graph) hipGraphDestroy(graph); return rs; }
+    if (rs != SOL_OK) { if (graph) (void)hipGraphDestroy(graph); return rs; }
     SOL_REQUIRE(ce == hipSuccess && graph, SOL_ERR_HIP, "hipStreamEndCapture: %s", hipGetErrorString(ce));
     hipGraphExec_t exec = nullptr;
     const hipError_t ie = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
-    hipGraphDestroy(graph);
+    (void)hipGraphDestroy(graph);       // the executable graph holds what it needs
     SOL_REQUIRE(ie == hipSuccess && exec, SOL_ERR_HIP, "hipGraphInstantiate: %s", hipGetErrorString(ie));
     sol_graph *g = new (std::nothrow) sol_graph();
-    if (!g) { hipGraphExecDestroy(exec); SOL_FAIL(SOL_ERR_HIP, "out of host memory"); }
+    if (!g) { (void)hipGraphExecDestroy(exec); SOL_FAIL(SOL_ERR_HIP, "out of host memory"); }
     g->exec = exec;
     *out = g;
     return SOL_OK;
@@ -1600,7 +1600,7 @@ sol_status sol_graph_launch(sol_graph *g, void *stream) {
 
 void sol_graph_destroy(sol_graph *g) {
     if (!g) return;
-    hipGraphExecDestroy(g->exec);
+    (void)hipGraphExecDestroy(g->exec);
     delete g;
 }
 
