@@ -376,7 +376,8 @@ __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16
     const float lim = a.act == SOL_ACT_RELU ? 0.f : __builtin_nanf("");     // wave-uniform lower bound of the outputs (none: NaN)
     const unsigned coff = (unsigned)(cw + ecg * 8);
     const unsigned lb = rowoff.lane_base(erow);
-    static_for<TP>([&](auto J) {
+    constexpr int NPS = 32 / RPS;
+    auto write_block = [&](auto J) {                       // accumulator blocks of pixel block j -> strip rows
         constexpr int j = decltype(J)::value;
 #pragma unroll
         for (int i = 0; i < TC; i++)
@@ -384,12 +385,25 @@ __device__ __forceinline__ void conv_epilogue_interior(const ConvArgs &a, f32x16
             for (int g = 0; g < 4; g++)
                 *reinterpret_cast<float4 *>(strip + lr * ERS + i * 32 + 8 * g + 4 * lh) =
                     make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
-        wave_lds_fence();
+    };
+    write_block(std::integral_constant<int, 0>{});
+    wave_lds_fence();
+    static_for<TP>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        // all rows of the block into registers first; the strip is then free for the next block, whose way to LDS overlaps
+        // this block's arithmetic and stores (a wave's epilogue is a chain of LDS round trips: one less per block)
+        float4 lo[NPS], hi[NPS];
 #pragma unroll
-        for (int ps = 0; ps < 32 / RPS; ps++) {
+        for (int ps = 0; ps < NPS; ps++) {
             const float *src = strip + (erow + ps * RPS) * ERS + ecg * 8;
-            const float4 lo = *reinterpret_cast<const float4 *>(src), hi = *reinterpret_cast<const float4 *>(src + 4);
-            const float r[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            lo[ps] = *reinterpret_cast<const float4 *>(src);
+            hi[ps] = *reinterpret_cast<const float4 *>(src + 4);
+        }
+        wave_lds_fence();
+        if constexpr (j + 1 < TP) write_block(std::integral_constant<int, j + 1>{});
+#pragma unroll
+        for (int ps = 0; ps < NPS; ps++) {
+            const float r[8] = {lo[ps].x, lo[ps].y, lo[ps].z, lo[ps].w, hi[ps].x, hi[ps].y, hi[ps].z, hi[ps].w};
             float v[8];
 #pragma unroll
             for (int e = 0; e < 8; e++) v[e] = r[e] * aff.sc[e] + aff.sf[e];
