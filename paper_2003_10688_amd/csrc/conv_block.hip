@@ -200,12 +200,22 @@ __global__ void __launch_bounds__(NW * 64, 512 / (NW * 64)) conv_block_kernel(co
         scA[g] = *reinterpret_cast<const float4 *>(a.s1 + wcA * 32 + 8 * g + 4 * lh);
         shA[g] = *reinterpret_cast<const float4 *>(a.h1 + wcA * 32 + 8 * g + 4 * lh);
     }
+    // ... and of phase B (behind the loop of A these sixteen loads per lane queued up at the address unit in front of the
+    // first weight stages of phase B)
+    const int wpB = wave % WPB, wcB = wave / WPB;
+    float4 scB[TCB][4], shB[TCB][4];
+#pragma unroll
+    for (int i = 0; i < TCB; i++)
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            scB[i][g] = *reinterpret_cast<const float4 *>(a.s2 + (wcB * TCB + i) * 32 + 8 * g + 4 * lh);
+            shB[i][g] = *reinterpret_cast<const float4 *>(a.h2 + (wcB * TCB + i) * 32 + 8 * g + 4 * lh);
+        }
 #pragma unroll
     for (int s = 0; s < NSA - 1; s++) issueA(s, (unsigned)(s * XROWB), s < nA);
 
     // tap addresses of phase B (computed under the first DMAs): ax[j][t] = LDS byte address, plane 0, k-step 0, of tap t
     // of this lane's pixel in pixel block j, or of the zero row when that tap lies outside the image / the tile
-    const int wpB = wave % WPB, wcB = wave / WPB;
     unsigned ax[TPB][9];
 #pragma unroll
     for (int j = 0; j < TPB; j++) {
@@ -230,8 +240,11 @@ __global__ void __launch_bounds__(NW * 64, 512 / (NW * 64)) conv_block_kernel(co
     // the compiler's own bookkeeping learns here that the BN constants have arrived (they are older than every DMA above)
 #pragma unroll
     for (int g = 0; g < 4; g++) asm volatile("" ::"v"(scA[g].x), "v"(scA[g].w), "v"(shA[g].x), "v"(shA[g].w));
+#pragma unroll
+    for (int i = 0; i < TCB; i++)
+#pragma unroll
+        for (int g = 0; g < 4; g++) asm volatile("" ::"v"(scB[i][g].x), "v"(scB[i][g].w), "v"(shB[i][g].x), "v"(shB[i][g].w));
 
-    float4 scB[TCB][4], shB[TCB][4];
     {
         f32x16_t acc[TPA];
 #pragma unroll
@@ -271,16 +284,9 @@ __global__ void __launch_bounds__(NW * 64, 512 / (NW * 64)) conv_block_kernel(co
         }
         wait_vmcnt<0>();
         __syncthreads();                                  // the ring is dead: its space becomes t1 and the ring of phase B
-        // zero rows of the t1 planes (no DMA of phase B writes them), BN constants and first weight stages of phase B,
-        // all under the epilogue of A
+        // zero rows of the t1 planes (no DMA of phase B writes them) and first weight stages of phase B, all under the
+        // epilogue of A
         if (tid < CH * 64) *reinterpret_cast<unsigned *>(t1 + (tid >> 6) * PLANE1 + PRA * 128 + (tid & 63) * 4) = 0u;
-#pragma unroll
-        for (int i = 0; i < TCB; i++)
-#pragma unroll
-            for (int g = 0; g < 4; g++) {
-                scB[i][g] = *reinterpret_cast<const float4 *>(a.s2 + (wcB * TCB + i) * 32 + 8 * g + 4 * lh);
-                shB[i][g] = *reinterpret_cast<const float4 *>(a.h2 + (wcB * TCB + i) * 32 + 8 * g + 4 * lh);
-            }
 #pragma unroll
         for (int s = 0; s < NSB - 1; s++) issueB(s, s, s < nB);
         // ---- epilogue of A
@@ -297,10 +303,6 @@ __global__ void __launch_bounds__(NW * 64, 512 / (NW * 64)) conv_block_kernel(co
     __builtin_amdgcn_s_barrier();                         // t1 is complete (every wave's stores have been executed)
 
     // ================================================================ phase B: t2 = relu(bn2(conv3x3(t1)))
-#pragma unroll
-    for (int i = 0; i < TCB; i++)
-#pragma unroll
-        for (int g = 0; g < 4; g++) asm volatile("" ::"v"(scB[i][g].x), "v"(scB[i][g].w), "v"(shB[i][g].x), "v"(shB[i][g].w));
     // phase C state that is set up before the epilogue of B
     const int wpC = wave % WPC, wcC = wave / WPC;
     const int mwC = p0 + wpC * TPC * 32;
